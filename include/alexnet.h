@@ -1,0 +1,200 @@
+/*
+ * libalexnet_hip -- one AlexNet SGD training step on one MI355X (gfx950).
+ *
+ * C ABI of the training hot path of "Theano-based Large-Scale Visual
+ * Recognition with Multiple GPUs" (arXiv 1412.2302): preprocessing of a
+ * minibatch (Section 2.1), one training iteration of AlexNet (Section 2,
+ * "Methods"), an inference pass (Section 3, validation error) and the
+ * exchange-and-average step between two replicas (Section 2.2).
+ *
+ * General rules for every call
+ *  - Pointers named d_* are DEVICE pointers, borrowed for the duration the
+ *    handle lives (alexnet_create) or of the enqueued work (all others).  The
+ *    library never allocates or frees device memory; the caller owns
+ *    parameters, momentum and workspace.
+ *  - `stream` is a hipStream_t (0 = the null stream).  Calls only enqueue work
+ *    and return; they never synchronise the device.
+ *  - Return value: ALEXNET_OK (0) or a negative ALEXNET_E* code;
+ *    alexnet_last_error() returns a thread-local message for the last failure.
+ *  - Canonical (external) tensor layouts are float32 NCHW activations, OIHW
+ *    convolution weights and [out][in] dense weights with the flatten order
+ *    (c, h, w).  The flat canonical parameter vector is: every weight tensor
+ *    conv1..conv5, fc6..fc8, then every bias in the same layer order.  The
+ *    library keeps its own internal layout inside d_params / d_momentum; use
+ *    alexnet_set_params / alexnet_get_params to convert.
+ *  - Calls on one handle, or on two handles passed to
+ *    alexnet_average_replicas, must be ordered by the caller (same stream or
+ *    events).  Preprocessing into slot s may overlap a training step reading
+ *    the other slot.
+ */
+#ifndef ALEXNET_H_
+#define ALEXNET_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ALEXNET_OK 0
+#define ALEXNET_EINVAL (-1)   /* null pointer, bad enum, bad slot ...            */
+#define ALEXNET_ESHAPE (-2)   /* configuration whose layer shapes do not work out */
+#define ALEXNET_EALIGN (-3)   /* device pointer not 256-byte aligned              */
+#define ALEXNET_ELABEL (-4)   /* a label outside [0, classes) was seen            */
+#define ALEXNET_EHIP (-5)     /* a HIP runtime call or kernel launch failed       */
+#define ALEXNET_ENOTIMPL (-6) /* feature not available in this build              */
+#define ALEXNET_ENOMEM (-7)   /* workspace smaller than alexnet_query reports     */
+
+typedef struct alexnet alexnet_t; /* opaque; host memory owned by the library */
+
+/* One convolution stage: conv -> ReLU -> [LRN] -> [3x3 stride-2 max-pool]. */
+typedef struct {
+  int32_t cout, k, stride, pad, groups;
+  int32_t lrn;  /* 1: cross-channel response normalisation after the ReLU */
+  int32_t pool; /* 1: 3x3 stride-2 max-pool (floor output size) after that */
+} alexnet_conv_t;
+
+/* Network and optimiser description (Section 2 names the layer census: five
+ * convolutions, three of them pooled, two dense layers and a softmax layer;
+ * every number below is the caller's). */
+typedef struct {
+  int32_t batch;
+  int32_t in_c, crop_h, crop_w; /* network input C x H x W                     */
+  int32_t raw_h, raw_w;         /* stored picture size; crop offsets are drawn */
+                                /* from [0, raw - crop]                        */
+  alexnet_conv_t conv[5];
+  int32_t fc[3];                /* dense output widths; fc[2] = classes        */
+  int32_t lrn_n;                /* s = k + alpha * sum over n channels of a^2; */
+  float lrn_k, lrn_alpha, lrn_beta; /* b = a * s^-beta (alpha not divided by n) */
+  float dropout_p;              /* drop probability after fc6 and fc7          */
+  float lr, momentum, weight_decay; /* v <- mu v - lr (g + wd w); w <- w + v;  */
+                                /* wd applies to weights, not to biases        */
+  int32_t precision;            /* 0: fp32 MFMA.  1: bf16 MFMA, fp32 accumulate */
+  uint64_t seed;                /* keys the crop / flip / dropout generator    */
+} alexnet_config_t;
+
+/* Sizes the caller must allocate: n_params floats each for parameters and
+ * momentum, and workspace_bytes of scratch.  Host-only; no GPU work. */
+int alexnet_query(const alexnet_config_t* cfg, size_t* n_params, size_t* workspace_bytes);
+
+/* Builds a replica over caller-owned device memory (Section 2.2: replicas are
+ * created identically by giving them the same parameters).  d_params and
+ * d_momentum hold n_params floats each in the library's internal layout and
+ * d_workspace holds workspace_bytes; all three must be 256-byte aligned and
+ * outlive the handle.  Contents of d_params / d_momentum are not touched
+ * (fill them with alexnet_set_params / alexnet_set_momentum).  The workspace
+ * is cleared on `stream`. */
+int alexnet_create(const alexnet_config_t* cfg, void* d_params, void* d_momentum, void* d_workspace,
+                   size_t workspace_bytes, void* stream, alexnet_t** out);
+void alexnet_destroy(alexnet_t* net);
+
+/* Section 2.1 footnote: subtract the mean image, cut a random crop_h x crop_w
+ * window and mirror it at random.  d_raw: uint8 [batch][in_c][raw_h][raw_w];
+ * d_mean: float32 [in_c][raw_h][raw_w].  The mean is taken at the source
+ * pixel, then the window is cut, then mirrored.  Offsets and the flip bit of
+ * picture n are functions of (seed, step, n) only.  Writes input slot `slot`
+ * (0 or 1) inside the workspace. */
+int alexnet_preprocess(alexnet_t* net, const uint8_t* d_raw, const float* d_mean, uint64_t step,
+                       int32_t slot, void* stream);
+
+/* Loads an already preprocessed float32 NCHW batch into input slot `slot`. */
+int alexnet_set_input(alexnet_t* net, const float* d_input_nchw, int32_t slot, void* stream);
+
+/* One training iteration on the batch in `slot` (Section 2: forward, backward,
+ * update): conv/ReLU/LRN/pool stack, fc6/fc7 with dropout masks keyed by
+ * `step`, fc8, softmax cross-entropy averaged over the batch, gradients of
+ * every parameter, momentum/weight-decay update in place.  d_labels: int32
+ * [batch] in [0, classes); a label out of range is clamped for the arithmetic
+ * and raises a sticky flag reported by alexnet_check().  d_loss: one float32,
+ * written on the device. */
+int alexnet_train_step(alexnet_t* net, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss,
+                       void* stream);
+
+/* Forward + backward only: as alexnet_train_step without the update.  The
+ * gradients stay readable through alexnet_get_grads. */
+int alexnet_forward_backward(alexnet_t* net, int32_t slot, const int32_t* d_labels, uint64_t step,
+                             float* d_loss, void* stream);
+
+/* The update alone, from the gradients left by the last backward pass. */
+int alexnet_apply_update(alexnet_t* net, void* stream);
+
+/* Inference (Section 3, validation): d_input_nchw float32
+ * [batch][in_c][crop_h][crop_w] already preprocessed; d_probs float32
+ * [batch][classes].  No dropout; fc6/fc7 activations are scaled by
+ * (1 - dropout_p). */
+int alexnet_forward(alexnet_t* net, const float* d_input_nchw, float* d_probs, void* stream);
+
+/* Section 2.2, steps 2 and 3 for two replicas living on the same GPU: after
+ * the call both replicas hold 0.5*(a+b) for every weight, bias and momentum
+ * value, bit-identical on both sides.  Configurations must match. */
+int alexnet_average_replicas(alexnet_t* a, alexnet_t* b, void* stream);
+
+/* Canonical <-> internal conversion of the flat parameter / momentum /
+ * gradient vectors (n_params float32 each, device memory). */
+int alexnet_set_params(alexnet_t* net, const float* d_canonical, void* stream);
+int alexnet_get_params(alexnet_t* net, float* d_canonical, void* stream);
+int alexnet_set_momentum(alexnet_t* net, const float* d_canonical, void* stream);
+int alexnet_get_momentum(alexnet_t* net, float* d_canonical, void* stream);
+int alexnet_get_grads(alexnet_t* net, float* d_canonical, void* stream);
+
+/* Intermediate tensors of the last pass, converted to canonical layout.
+ * `layer` is 1..5 for convolution stages, 6..8 for dense layers. */
+enum {
+  ALEXNET_T_INPUT = 0,    /* float32 NCHW, `layer` = slot                          */
+  ALEXNET_T_CONV_ACT = 1, /* float32 NCHW, output of the stage's ReLU              */
+  ALEXNET_T_LRN = 2,      /* float32 NCHW, normalised output (stages with lrn)     */
+  ALEXNET_T_POOL = 3,     /* float32 NCHW, pooled output (stages with pool)        */
+  ALEXNET_T_ARGMAX = 4,   /* int32 NCHW, y_in*W_in + x_in of the winning tap       */
+  ALEXNET_T_FC_ACT = 5,   /* float32 [batch][width]: fc6/fc7 after ReLU+dropout, fc8 logits */
+  ALEXNET_T_CROP_X = 6,   /* int32 [batch], `layer` = slot                         */
+  ALEXNET_T_CROP_Y = 7,   /* int32 [batch], `layer` = slot                         */
+  ALEXNET_T_FLIP = 8,     /* int32 [batch], `layer` = slot                         */
+  ALEXNET_T_DLOGITS = 9,  /* float32 [batch][classes]: (p - onehot)/batch          */
+  ALEXNET_T_CONV_DACT = 10 /* float32 NCHW, gradient w.r.t. the stage's pre-ReLU output */
+};
+int alexnet_tensor_elems(alexnet_t* net, int32_t kind, int32_t layer, size_t* elems);
+int alexnet_get_tensor(alexnet_t* net, int32_t kind, int32_t layer, void* d_out, void* stream);
+
+/* Synchronises `stream` and reports sticky device-side conditions:
+ * ALEXNET_ELABEL if a label was out of range since the last check. */
+int alexnet_check(alexnet_t* net, void* stream);
+
+/* --- single-operator entry points (used to measure and test one layer alone) ---
+ * All tensors canonical float32 on the device, shapes as the stage `layer`
+ * (1..5) of the handle's configuration defines them:
+ *   x  [batch][Cin][H][W]     y, dy [batch][Cout][Ho][Wo]
+ *   w  [Cout][Cin/groups][k][k]      b [Cout]
+ * The *_nhwc variants take the library's internal channel-last activations
+ * ([batch][H][W][C]) and packed weights, so that no conversion kernel is part
+ * of what is timed; alexnet_pack_conv_weight produces the packed form.      */
+int alexnet_conv_forward(alexnet_t* net, int32_t layer, const float* d_x, const float* d_w, const float* d_b,
+                         int32_t relu, float* d_y, void* stream);
+int alexnet_conv_backward_data(alexnet_t* net, int32_t layer, const float* d_dy, const float* d_w, float* d_dx,
+                               void* stream);
+int alexnet_conv_backward_weight(alexnet_t* net, int32_t layer, const float* d_x, const float* d_dy, float* d_dw,
+                                 float* d_db, void* stream);
+
+int alexnet_nchw_to_nhwc(const float* d_src, float* d_dst, int32_t n, int32_t c, int32_t h, int32_t w, void* stream);
+int alexnet_nhwc_to_nchw(const float* d_src, float* d_dst, int32_t n, int32_t c, int32_t h, int32_t w, void* stream);
+/* packed forward weights [groups][(r,s,c)][Cout/groups] and the backward-data
+ * form [groups][(r,s,o)][Cin/groups]; each holds Cout*Cin/groups*k*k floats. */
+int alexnet_pack_conv_weight(alexnet_t* net, int32_t layer, const float* d_w_oihw, float* d_w_fwd, float* d_w_bwd,
+                             void* stream);
+int alexnet_unpack_conv_weight(alexnet_t* net, int32_t layer, const float* d_w_fwd, float* d_w_oihw, void* stream);
+int alexnet_conv_forward_nhwc(alexnet_t* net, int32_t layer, const float* d_x, const float* d_w_fwd,
+                              const float* d_b, int32_t relu, float* d_y, void* stream);
+int alexnet_conv_backward_data_nhwc(alexnet_t* net, int32_t layer, const float* d_dy, const float* d_w_bwd,
+                                    float* d_dx, void* stream);
+/* d_dw_fwd receives the gradient in the packed forward-weight layout. */
+int alexnet_conv_backward_weight_nhwc(alexnet_t* net, int32_t layer, const float* d_x, const float* d_dy,
+                                      float* d_dw_fwd, float* d_db, void* stream);
+
+const char* alexnet_last_error(void);
+/* Library version string, e.g. "alexnet-hip gfx950 fp32". Host-only. */
+const char* alexnet_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALEXNET_H_ */

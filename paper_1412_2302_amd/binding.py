@@ -1,0 +1,318 @@
+"""Thin ctypes binding of libalexnet_hip.so (include/alexnet.h).
+
+Argument marshalling only: every step of the training path runs inside the
+HIP library.  PyTorch is used to own device memory and streams.  Importing
+this module fails loudly when the library has not been built
+(python -m paper_1412_2302_amd.build); there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libalexnet_hip.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1412_2302_amd.build`")
+_lib = C.CDLL(LIB_PATH)
+
+OK, EINVAL, ESHAPE, EALIGN, ELABEL, EHIP, ENOTIMPL, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
+
+T_INPUT, T_CONV_ACT, T_LRN, T_POOL, T_ARGMAX, T_FC_ACT, T_CROP_X, T_CROP_Y, T_FLIP, T_DLOGITS, T_CONV_DACT = range(11)
+_INT_KINDS = {T_ARGMAX, T_CROP_X, T_CROP_Y, T_FLIP}
+
+
+class ConvCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("cout", "k", "stride", "pad", "groups", "lrn", "pool")]
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("in_c", C.c_int32), ("crop_h", C.c_int32), ("crop_w", C.c_int32),
+        ("raw_h", C.c_int32), ("raw_w", C.c_int32),
+        ("conv", ConvCfg * 5), ("fc", C.c_int32 * 3),
+        ("lrn_n", C.c_int32), ("lrn_k", C.c_float), ("lrn_alpha", C.c_float), ("lrn_beta", C.c_float),
+        ("dropout_p", C.c_float), ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float),
+        ("precision", C.c_int32), ("seed", C.c_uint64),
+    ]
+
+
+_vp, _i32, _u64, _sz = C.c_void_p, C.c_int32, C.c_uint64, C.c_size_t
+_SIGS = {
+    "alexnet_query": [C.POINTER(Config), C.POINTER(_sz), C.POINTER(_sz)],
+    "alexnet_create": [C.POINTER(Config), _vp, _vp, _vp, _sz, _vp, C.POINTER(_vp)],
+    "alexnet_preprocess": [_vp, _vp, _vp, _u64, _i32, _vp],
+    "alexnet_set_input": [_vp, _vp, _i32, _vp],
+    "alexnet_train_step": [_vp, _i32, _vp, _u64, _vp, _vp],
+    "alexnet_forward_backward": [_vp, _i32, _vp, _u64, _vp, _vp],
+    "alexnet_apply_update": [_vp, _vp],
+    "alexnet_forward": [_vp, _vp, _vp, _vp],
+    "alexnet_average_replicas": [_vp, _vp, _vp],
+    "alexnet_set_params": [_vp, _vp, _vp],
+    "alexnet_get_params": [_vp, _vp, _vp],
+    "alexnet_set_momentum": [_vp, _vp, _vp],
+    "alexnet_get_momentum": [_vp, _vp, _vp],
+    "alexnet_get_grads": [_vp, _vp, _vp],
+    "alexnet_tensor_elems": [_vp, _i32, _i32, C.POINTER(_sz)],
+    "alexnet_get_tensor": [_vp, _i32, _i32, _vp, _vp],
+    "alexnet_check": [_vp, _vp],
+    "alexnet_conv_forward": [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp],
+    "alexnet_conv_backward_data": [_vp, _i32, _vp, _vp, _vp, _vp],
+    "alexnet_conv_backward_weight": [_vp, _i32, _vp, _vp, _vp, _vp, _vp],
+    "alexnet_nchw_to_nhwc": [_vp, _vp, _i32, _i32, _i32, _i32, _vp],
+    "alexnet_nhwc_to_nchw": [_vp, _vp, _i32, _i32, _i32, _i32, _vp],
+    "alexnet_pack_conv_weight": [_vp, _i32, _vp, _vp, _vp, _vp],
+    "alexnet_unpack_conv_weight": [_vp, _i32, _vp, _vp, _vp],
+    "alexnet_conv_forward_nhwc": [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp],
+    "alexnet_conv_backward_data_nhwc": [_vp, _i32, _vp, _vp, _vp, _vp],
+    "alexnet_conv_backward_weight_nhwc": [_vp, _i32, _vp, _vp, _vp, _vp, _vp],
+}
+for _name, _args in _SIGS.items():
+    _f = getattr(_lib, _name)
+    _f.argtypes = _args
+    _f.restype = C.c_int
+_lib.alexnet_destroy.argtypes = [_vp]
+_lib.alexnet_destroy.restype = None
+_lib.alexnet_last_error.restype = C.c_char_p
+_lib.alexnet_version.restype = C.c_char_p
+EXPORTS = sorted(list(_SIGS) + ["alexnet_destroy", "alexnet_last_error", "alexnet_version"])
+
+
+class AlexNetError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libalexnet_hip error {code}: {msg}")
+        self.code = code
+
+
+def last_error() -> str:
+    return (_lib.alexnet_last_error() or b"").decode()
+
+
+def version() -> str:
+    return _lib.alexnet_version().decode()
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise AlexNetError(rc, last_error())
+
+
+def make_config(workload: dict, batch: int, seed: int = 0, precision: int = 0) -> Config:
+    cfg = Config()
+    cfg.batch = batch
+    cfg.in_c = workload["in_c"]
+    cfg.crop_h = cfg.crop_w = workload["crop"]
+    cfg.raw_h = cfg.raw_w = workload["raw"]
+    for i, (co, k, st, pd, g, l, p) in enumerate(workload["conv"]):
+        cfg.conv[i] = ConvCfg(co, k, st, pd, g, l, p)
+    for j, f in enumerate(workload["fc"]):
+        cfg.fc[j] = f
+    n, k, a, b = workload["lrn"]
+    cfg.lrn_n, cfg.lrn_k, cfg.lrn_alpha, cfg.lrn_beta = n, k, a, b
+    cfg.dropout_p, cfg.lr = workload["dropout_p"], workload["lr"]
+    cfg.momentum, cfg.weight_decay = workload["momentum"], workload["weight_decay"]
+    cfg.precision, cfg.seed = precision, seed
+    return cfg
+
+
+def query(cfg: Config) -> Tuple[int, int]:
+    n, w = _sz(), _sz()
+    _check(_lib.alexnet_query(C.byref(cfg), C.byref(n), C.byref(w)))
+    return n.value, w.value
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else _vp(t.data_ptr())
+
+
+def _stream(stream: Optional[torch.cuda.Stream]):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return _vp(s.cuda_stream)
+
+
+def _dev(a, dtype=None) -> torch.Tensor:
+    if isinstance(a, torch.Tensor):
+        t = a.to("cuda")
+    else:
+        t = torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.contiguous()
+
+
+class AlexNet:
+    """One replica: owns parameter, momentum and workspace tensors on cuda:0."""
+
+    def __init__(self, workload: dict, batch: int, seed: int = 0, precision: int = 0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("libalexnet_hip needs a GPU; there is no CPU path")
+        self.workload, self.batch = workload, batch
+        self.cfg = make_config(workload, batch, seed, precision)
+        self.n_params, self.ws_bytes = query(self.cfg)
+        dev = torch.device("cuda", 0)
+        self.params = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
+        self.momentum = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        h = _vp()
+        _check(_lib.alexnet_create(C.byref(self.cfg), _ptr(self.params), _ptr(self.momentum), _ptr(self.workspace),
+                                   self.ws_bytes, _stream(None), C.byref(h)))
+        self._h = h
+        self.shapes = self._param_shapes()
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.alexnet_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    # ---- bookkeeping of the canonical flat vector (marshalling only) ----
+    def _param_shapes(self) -> Dict[str, Tuple[int, ...]]:
+        wl = self.workload
+        c, h = wl["in_c"], wl["crop"]
+        ws, bs = {}, {}
+        for i, (co, k, st, pd, g, l, p) in enumerate(wl["conv"]):
+            ws[f"conv{i+1}.w"] = (co, c // g, k, k)
+            bs[f"conv{i+1}.b"] = (co,)
+            h = (h + 2 * pd - k) // st + 1
+            if p:
+                h = (h - 3) // 2 + 1
+            c = co
+        fin = c * h * h
+        for j, fo in enumerate(wl["fc"]):
+            ws[f"fc{6+j}.w"] = (fo, fin)
+            bs[f"fc{6+j}.b"] = (fo,)
+            fin = fo
+        ws.update(bs)
+        total = sum(int(np.prod(s)) for s in ws.values())
+        assert total == self.n_params, (total, self.n_params)
+        return ws
+
+    def flatten(self, d: Dict[str, np.ndarray]) -> np.ndarray:
+        return np.concatenate([np.asarray(d[k], np.float32).ravel() for k in self.shapes])
+
+    def unflatten(self, flat: np.ndarray) -> Dict[str, np.ndarray]:
+        out, o = {}, 0
+        for k, s in self.shapes.items():
+            n = int(np.prod(s))
+            out[k] = flat[o:o + n].reshape(s)
+            o += n
+        return out
+
+    # ---- parameters ----
+    def _set(self, fn, d):
+        flat = _dev(self.flatten(d) if isinstance(d, dict) else d, torch.float32)
+        assert flat.numel() == self.n_params
+        _check(fn(self._h, _ptr(flat), _stream(None)))
+        torch.cuda.current_stream().synchronize()
+
+    def _get(self, fn) -> Dict[str, np.ndarray]:
+        flat = torch.empty(self.n_params, dtype=torch.float32, device="cuda")
+        _check(fn(self._h, _ptr(flat), _stream(None)))
+        return self.unflatten(flat.cpu().numpy())
+
+    def set_params(self, d): self._set(_lib.alexnet_set_params, d)
+    def set_momentum(self, d): self._set(_lib.alexnet_set_momentum, d)
+    def get_params(self): return self._get(_lib.alexnet_get_params)
+    def get_momentum(self): return self._get(_lib.alexnet_get_momentum)
+    def get_grads(self): return self._get(_lib.alexnet_get_grads)
+
+    # ---- the hot path ----
+    def preprocess(self, raw_u8: torch.Tensor, mean: torch.Tensor, step: int, slot: int, stream=None):
+        _check(_lib.alexnet_preprocess(self._h, _ptr(raw_u8), _ptr(mean), step, slot, _stream(stream)))
+
+    def set_input(self, x_nchw: torch.Tensor, slot: int = 0, stream=None):
+        _check(_lib.alexnet_set_input(self._h, _ptr(x_nchw), slot, _stream(stream)))
+
+    def train_step(self, labels: torch.Tensor, step: int, slot: int = 0, stream=None) -> torch.Tensor:
+        _check(_lib.alexnet_train_step(self._h, slot, _ptr(labels), step, _ptr(self.loss), _stream(stream)))
+        return self.loss
+
+    def forward_backward(self, labels: torch.Tensor, step: int, slot: int = 0, stream=None) -> torch.Tensor:
+        _check(_lib.alexnet_forward_backward(self._h, slot, _ptr(labels), step, _ptr(self.loss), _stream(stream)))
+        return self.loss
+
+    def apply_update(self, stream=None):
+        _check(_lib.alexnet_apply_update(self._h, _stream(stream)))
+
+    def forward(self, x_nchw: torch.Tensor, stream=None) -> torch.Tensor:
+        probs = torch.empty(self.batch, self.workload["fc"][-1], dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_forward(self._h, _ptr(x_nchw), _ptr(probs), _stream(stream)))
+        return probs
+
+    def check(self, stream=None):
+        _check(_lib.alexnet_check(self._h, _stream(stream)))
+
+    def tensor(self, kind: int, layer: int) -> np.ndarray:
+        n = _sz()
+        _check(_lib.alexnet_tensor_elems(self._h, kind, layer, C.byref(n)))
+        out = torch.empty(n.value, dtype=torch.int32 if kind in _INT_KINDS else torch.float32, device="cuda")
+        _check(_lib.alexnet_get_tensor(self._h, kind, layer, _ptr(out), _stream(None)))
+        return out.cpu().numpy()
+
+    # ---- single operators on canonical tensors ----
+    def conv_forward(self, layer, x, w, b, relu=False):
+        xs, wt = _dev(x, torch.float32), _dev(w, torch.float32)
+        bt = None if b is None else _dev(b, torch.float32)
+        n = _sz()
+        _check(_lib.alexnet_tensor_elems(self._h, T_CONV_ACT, layer, C.byref(n)))
+        y = torch.empty(n.value, dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_conv_forward(self._h, layer, _ptr(xs), _ptr(wt), _ptr(bt), int(relu), _ptr(y), _stream(None)))
+        return y
+
+    def conv_backward_data(self, layer, dy, w, x_shape):
+        dyt, wt = _dev(dy, torch.float32), _dev(w, torch.float32)
+        dx = torch.empty(int(np.prod(x_shape)), dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_conv_backward_data(self._h, layer, _ptr(dyt), _ptr(wt), _ptr(dx), _stream(None)))
+        return dx.view(*x_shape)
+
+    def conv_backward_weight(self, layer, x, dy, w_shape):
+        xs, dyt = _dev(x, torch.float32), _dev(dy, torch.float32)
+        dw = torch.empty(int(np.prod(w_shape)), dtype=torch.float32, device="cuda")
+        db = torch.empty(w_shape[0], dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_conv_backward_weight(self._h, layer, _ptr(xs), _ptr(dyt), _ptr(dw), _ptr(db), _stream(None)))
+        return dw.view(*w_shape), db
+
+    # channel-last variants: no conversion kernels in the call
+    def pack_conv_weight(self, layer, w_oihw: torch.Tensor):
+        wf, wb = torch.empty_like(w_oihw).view(-1), torch.empty_like(w_oihw).view(-1)
+        _check(_lib.alexnet_pack_conv_weight(self._h, layer, _ptr(w_oihw), _ptr(wf), _ptr(wb), _stream(None)))
+        return wf, wb
+
+    def unpack_conv_weight(self, layer, wf: torch.Tensor, w_shape):
+        w = torch.empty(int(np.prod(w_shape)), dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_unpack_conv_weight(self._h, layer, _ptr(wf), _ptr(w), _stream(None)))
+        return w.view(*w_shape)
+
+    def conv_forward_nhwc(self, layer, x, wf, b, relu, y, stream=None):
+        _check(_lib.alexnet_conv_forward_nhwc(self._h, layer, _ptr(x), _ptr(wf), _ptr(b), int(relu), _ptr(y), _stream(stream)))
+
+    def conv_backward_data_nhwc(self, layer, dy, wb, dx, stream=None):
+        _check(_lib.alexnet_conv_backward_data_nhwc(self._h, layer, _ptr(dy), _ptr(wb), _ptr(dx), _stream(stream)))
+
+    def conv_backward_weight_nhwc(self, layer, x, dy, dwf, db, stream=None):
+        _check(_lib.alexnet_conv_backward_weight_nhwc(self._h, layer, _ptr(x), _ptr(dy), _ptr(dwf), _ptr(db), _stream(stream)))
+
+
+def average_replicas(a: AlexNet, b: AlexNet, stream=None):
+    _check(_lib.alexnet_average_replicas(a._h, b._h, _stream(stream)))
+
+
+def nchw_to_nhwc(x: torch.Tensor) -> torch.Tensor:
+    n, c, h, w = x.shape
+    y = torch.empty(n, h, w, c, dtype=torch.float32, device="cuda")
+    _check(_lib.alexnet_nchw_to_nhwc(_ptr(x.contiguous()), _ptr(y), n, c, h, w, _stream(None)))
+    return y
+
+
+def nhwc_to_nchw(x: torch.Tensor) -> torch.Tensor:
+    n, h, w, c = x.shape
+    y = torch.empty(n, c, h, w, dtype=torch.float32, device="cuda")
+    _check(_lib.alexnet_nhwc_to_nchw(_ptr(x.contiguous()), _ptr(y), n, c, h, w, _stream(None)))
+    return y

@@ -1,0 +1,613 @@
+// The C ABI of include/alexnet.h: handle, workspace plan and the sequencing of
+// one training / inference pass over the kernels of this library.
+#include <stdarg.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+namespace ax {
+
+static thread_local char g_err[512] = "";
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+const char* get_error() { return g_err; }
+
+static const int kStages = 5, kFc = 3, kSlots = 3;  // slot 2 is the inference input
+
+struct Stage {
+  ConvGeom g;
+  bool lrn, pool;
+  int Hp, Wp;           // stage output size (after the pool when present)
+  size_t w_off, b_off;  // offsets into the flat parameter vector
+  float *act, *lrn_out, *pool_out, *dact, *d_lrn, *d_out, *wb;
+  uint8_t* slot;
+  long act_elems() const { return g.out_elems(); }
+  long out_elems() const { return (long)g.B * Hp * Wp * g.Cout; }
+  const float* out() const { return pool ? pool_out : lrn ? lrn_out : act; }
+  bool plain() const { return !lrn && !pool; }
+};
+struct Dense {
+  int in, out;
+  size_t w_off, b_off;
+  float *act, *dz;
+};
+
+// Bump allocator over the caller's workspace; with base == null it only sizes.
+struct Arena {
+  char* base;
+  size_t off;
+  template <class T>
+  T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+}  // namespace ax
+
+using namespace ax;
+
+struct alexnet {
+  alexnet_config_t cfg;
+  Stage st[kStages];
+  Dense fc[kFc];
+  size_t n_params, n_weights, ws_bytes;
+  float *params, *mom, *grads;
+  float* input[kSlots];
+  int32_t *crop_x[kSlots], *crop_y[kSlots], *flip[kSlots];
+  float *gemm_ws, *colsum_ws, *row_loss, *scratch_x, *scratch_y, *scratch_w[3];
+  int32_t* err_flag;
+  size_t gemm_ws_floats, colsum_ws_floats_;
+  int flat;  // flatten size feeding fc6
+};
+
+static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
+  const alexnet_config_t& c = *cfg;
+  if (c.batch <= 0 || c.in_c <= 0 || c.crop_h <= 0 || c.crop_w <= 0 || c.raw_h < c.crop_h || c.raw_w < c.crop_w) {
+    set_error("bad batch/input size");
+    return ALEXNET_ESHAPE;
+  }
+  if (c.precision != 0) {
+    set_error("precision %d is not available in this build (fp32 only)", c.precision);
+    return ALEXNET_ENOTIMPL;
+  }
+  if (c.lrn_n < 1 || c.lrn_n % 2 == 0 || !(c.dropout_p >= 0.f && c.dropout_p < 1.f)) {
+    set_error("bad lrn_n (must be odd) or dropout_p");
+    return ALEXNET_EINVAL;
+  }
+  n->cfg = c;
+  int C = c.in_c, H = c.crop_h, W = c.crop_w;
+  size_t off = 0;
+  for (int i = 0; i < kStages; ++i) {
+    const alexnet_conv_t& cv = c.conv[i];
+    if (cv.cout <= 0 || cv.k <= 0 || cv.stride <= 0 || cv.pad < 0 || cv.groups <= 0 || C % cv.groups ||
+        cv.cout % cv.groups) {
+      set_error("conv%d: bad hyper-parameters", i + 1);
+      return ALEXNET_ESHAPE;
+    }
+    Stage& s = n->st[i];
+    s.g.B = c.batch; s.g.H = H; s.g.W = W; s.g.Cin = C; s.g.Cout = cv.cout; s.g.k = cv.k;
+    s.g.stride = cv.stride; s.g.pad = cv.pad; s.g.groups = cv.groups;
+    s.g.Ho = (H + 2 * cv.pad - cv.k) / cv.stride + 1;
+    s.g.Wo = (W + 2 * cv.pad - cv.k) / cv.stride + 1;
+    if (H + 2 * cv.pad < cv.k || W + 2 * cv.pad < cv.k || s.g.Ho <= 0 || s.g.Wo <= 0) {
+      set_error("conv%d: kernel larger than its input", i + 1);
+      return ALEXNET_ESHAPE;
+    }
+    s.lrn = cv.lrn != 0;
+    s.pool = cv.pool != 0;
+    s.Hp = s.g.Ho; s.Wp = s.g.Wo;
+    if (s.pool) {
+      if (s.g.Ho < 3 || s.g.Wo < 3) {
+        set_error("conv%d: output too small to pool", i + 1);
+        return ALEXNET_ESHAPE;
+      }
+      s.Hp = (s.g.Ho - 3) / 2 + 1;
+      s.Wp = (s.g.Wo - 3) / 2 + 1;
+    }
+    if ((long)s.g.P() * 1 > 0x7fffffffL / 2 || s.g.in_elems() > 0x7fffffffL || s.g.out_elems() > 0x7fffffffL) {
+      set_error("conv%d: tensor too large for 32-bit pixel indices", i + 1);
+      return ALEXNET_ESHAPE;
+    }
+    s.w_off = off;
+    off += (size_t)s.g.w_elems();
+    C = cv.cout; H = s.Hp; W = s.Wp;
+  }
+  n->flat = C * H * W;
+  int in = n->flat;
+  for (int j = 0; j < kFc; ++j) {
+    if (c.fc[j] <= 0) {
+      set_error("fc width must be positive");
+      return ALEXNET_ESHAPE;
+    }
+    n->fc[j].in = in; n->fc[j].out = c.fc[j];
+    n->fc[j].w_off = off;
+    off += (size_t)in * c.fc[j];
+    in = c.fc[j];
+  }
+  n->n_weights = off;
+  for (int i = 0; i < kStages; ++i) { n->st[i].b_off = off; off += n->st[i].g.Cout; }
+  for (int j = 0; j < kFc; ++j) { n->fc[j].b_off = off; off += n->fc[j].out; }
+  n->n_params = off;
+
+  // ---- workspace ----
+  Arena a{base, 0};
+  const size_t in_elems = (size_t)c.batch * c.crop_h * c.crop_w * c.in_c;
+  for (int s = 0; s < kSlots; ++s) {
+    n->input[s] = a.take<float>(in_elems);
+    n->crop_x[s] = a.take<int32_t>(c.batch);
+    n->crop_y[s] = a.take<int32_t>(c.batch);
+    n->flip[s] = a.take<int32_t>(c.batch);
+  }
+  size_t max_in = in_elems, max_out = 0, max_w = 0, gws = 0, cws = 0;
+  for (int i = 0; i < kStages; ++i) {
+    Stage& s = n->st[i];
+    const size_t ae = s.act_elems(), oe = s.out_elems();
+    s.act = a.take<float>(ae);
+    s.dact = a.take<float>(ae);
+    s.lrn_out = s.lrn ? a.take<float>(ae) : nullptr;
+    s.pool_out = s.pool ? a.take<float>(oe) : nullptr;
+    s.slot = s.pool ? a.take<uint8_t>(oe) : nullptr;
+    s.d_lrn = (s.lrn && s.pool) ? a.take<float>(ae) : nullptr;
+    s.d_out = s.plain() ? s.dact : a.take<float>(oe);
+    s.wb = a.take<float>(s.g.w_elems());
+    max_in = std::max(max_in, (size_t)s.g.in_elems());
+    max_out = std::max(max_out, ae);
+    max_w = std::max(max_w, (size_t)s.g.w_elems());
+    gws = std::max(gws, conv_bwd_weight_ws_floats(s.g));
+    cws = std::max(cws, colsum_ws_floats(s.g.P(), s.g.Cout));
+  }
+  for (int j = 0; j < kFc; ++j) {
+    Dense& f = n->fc[j];
+    f.act = a.take<float>((size_t)c.batch * f.out);
+    f.dz = a.take<float>((size_t)c.batch * f.out);
+    gws = std::max(gws, fc_ws_floats(c.batch, f.in, f.out));
+    cws = std::max(cws, colsum_ws_floats(c.batch, f.out));
+  }
+  n->grads = a.take<float>(n->n_params);
+  n->gemm_ws = a.take<float>(gws);
+  n->gemm_ws_floats = gws;
+  n->colsum_ws = a.take<float>(cws);
+  n->colsum_ws_floats_ = cws;
+  n->row_loss = a.take<float>(c.batch);
+  n->err_flag = a.take<int32_t>(64);
+  n->scratch_x = a.take<float>(max_in);
+  n->scratch_y = a.take<float>(max_out);
+  for (int k = 0; k < 3; ++k) n->scratch_w[k] = a.take<float>(max_w);
+  n->ws_bytes = (a.off + 255) & ~(size_t)255;
+  return ALEXNET_OK;
+}
+
+static inline hipStream_t S(void* s) { return reinterpret_cast<hipStream_t>(s); }
+static inline bool aligned256(const void* p) { return ((uintptr_t)p & 255) == 0; }
+
+#define REQUIRE(cond, code, msg)   \
+  do {                             \
+    if (!(cond)) {                 \
+      ax::set_error("%s", msg);    \
+      return code;                 \
+    }                              \
+  } while (0)
+
+static uint32_t drop_thresh(float p) { return (uint32_t)floor((double)p * (double)(1 << 24)); }
+
+// --------------------------------------------------------------- passes ------
+static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, hipStream_t st) {
+  const alexnet_config_t& c = n->cfg;
+  const float* h = in;
+  for (int i = 0; i < kStages; ++i) {
+    Stage& s = n->st[i];
+    AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, st));
+    h = s.act;
+    if (s.lrn) {
+      AX_TRY(launch_lrn_fwd(s.act, s.lrn_out, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k, c.lrn_alpha, c.lrn_beta, st));
+      h = s.lrn_out;
+    }
+    if (s.pool) {
+      AX_TRY(launch_pool_fwd(h, s.pool_out, s.slot, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
+      h = s.pool_out;
+    }
+  }
+  const uint64_t key = step_key(c.seed, step);
+  for (int j = 0; j < kFc; ++j) {
+    Dense& f = n->fc[j];
+    FcAct act;
+    act.bias = n->params + f.b_off;
+    const bool hidden = j < kFc - 1;
+    act.relu = hidden ? 1 : 0;
+    act.dropout = (hidden && train && c.dropout_p > 0.f) ? 1 : 0;
+    act.key = key;
+    act.tag = j == 0 ? TAG_DROP6 : TAG_DROP7;
+    act.thresh24 = drop_thresh(c.dropout_p);
+    act.scale = (hidden && !train) ? 1.0f - c.dropout_p : 1.0f;
+    AX_TRY(launch_fc_fwd(c.batch, f.in, f.out, h, n->params + f.w_off, act, f.act, n->gemm_ws, st));
+    h = f.act;
+  }
+  return ALEXNET_OK;
+}
+
+static int run_backward(alexnet* n, const float* in, hipStream_t st) {
+  const alexnet_config_t& c = n->cfg;
+  // dense layers, last to first
+  for (int j = kFc - 1; j >= 0; --j) {
+    Dense& f = n->fc[j];
+    const float* x = j == 0 ? n->st[kStages - 1].out() : n->fc[j - 1].act;
+    AX_TRY(launch_fc_bwd_weight(c.batch, f.in, f.out, x, f.dz, n->grads + f.w_off, st));
+    AX_TRY(launch_colsum(f.dz, c.batch, f.out, n->grads + f.b_off, n->colsum_ws, st));
+    if (j > 0) {
+      // fc(j-1) output is ReLU+dropout: it is positive exactly where the gradient passes
+      AX_TRY(launch_fc_bwd_data(c.batch, f.in, f.out, f.dz, n->params + f.w_off, n->fc[j - 1].act, n->fc[j - 1].dz,
+                                n->gemm_ws, st));
+    } else {
+      Stage& last = n->st[kStages - 1];
+      AX_TRY(launch_fc_bwd_data(c.batch, f.in, f.out, f.dz, n->params + f.w_off, last.plain() ? last.act : nullptr,
+                                last.d_out, n->gemm_ws, st));
+    }
+  }
+  for (int i = kStages - 1; i >= 0; --i) {
+    Stage& s = n->st[i];
+    if (s.pool) {
+      if (s.lrn)
+        AX_TRY(launch_pool_bwd(s.d_out, s.slot, nullptr, s.d_lrn, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
+      else
+        AX_TRY(launch_pool_bwd(s.d_out, s.slot, s.act, s.dact, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
+    }
+    if (s.lrn)
+      AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
+                            c.lrn_alpha, c.lrn_beta, 1, st));
+    const float* x = i == 0 ? in : n->st[i - 1].out();
+    AX_TRY(launch_conv_bwd_weight(s.g, x, s.dact, n->grads + s.w_off, n->gemm_ws, st));
+    AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
+    if (i > 0) {
+      Stage& prev = n->st[i - 1];
+      AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
+      AX_TRY(launch_conv_bwd_data(s.g, s.dact, s.wb, prev.plain() ? prev.act : nullptr, prev.d_out, st));
+    }
+  }
+  return ALEXNET_OK;
+}
+
+static int fwd_bwd(alexnet* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss, hipStream_t st) {
+  const alexnet_config_t& c = n->cfg;
+  AX_TRY(run_forward(n, n->input[slot], true, step, st));
+  Dense& last = n->fc[kFc - 1];
+  AX_TRY(launch_softmax_xent(last.act, d_labels, c.batch, last.out, 0, last.dz, n->row_loss, n->err_flag, st));
+  AX_TRY(launch_mean_loss(n->row_loss, c.batch, d_loss, st));
+  return run_backward(n, n->input[slot], st);
+}
+
+static int apply_update(alexnet* n, hipStream_t st) {
+  const alexnet_config_t& c = n->cfg;
+  return launch_sgd_update(n->params, n->mom, n->grads, n->n_params, n->n_weights, c.lr, c.momentum, c.weight_decay,
+                           st);
+}
+
+// canonical <-> internal for one flat vector
+static int convert_flat(alexnet* n, const float* src, float* dst, int dir, hipStream_t st) {
+  for (int i = 0; i < kStages; ++i) {
+    Stage& s = n->st[i];
+    AX_TRY(launch_conv_weight_pack(src + s.w_off, dst + s.w_off, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, dir, st));
+    AX_TRY(launch_copy(src + s.b_off, dst + s.b_off, s.g.Cout, st));
+  }
+  for (int j = 0; j < kFc; ++j) {
+    Dense& f = n->fc[j];
+    if (j == 0) {
+      Stage& l = n->st[kStages - 1];
+      AX_TRY(launch_fc_weight_permute(src + f.w_off, dst + f.w_off, f.out, l.g.Cout, l.Hp * l.Wp, dir, st));
+    } else {
+      AX_TRY(launch_copy(src + f.w_off, dst + f.w_off, (size_t)f.in * f.out, st));
+    }
+    AX_TRY(launch_copy(src + f.b_off, dst + f.b_off, f.out, st));
+  }
+  return ALEXNET_OK;
+}
+
+static int stage_of(alexnet* n, int32_t layer, Stage** s) {
+  if (!n || layer < 1 || layer > kStages) {
+    set_error("layer must be 1..5");
+    return ALEXNET_EINVAL;
+  }
+  *s = &n->st[layer - 1];
+  return ALEXNET_OK;
+}
+
+// ================================ C ABI =======================================
+extern "C" {
+
+const char* alexnet_last_error(void) { return ax::get_error(); }
+const char* alexnet_version(void) { return "alexnet-hip gfx950 fp32-mfma 0.1"; }
+
+int alexnet_query(const alexnet_config_t* cfg, size_t* n_params, size_t* workspace_bytes) {
+  REQUIRE(cfg && n_params && workspace_bytes, ALEXNET_EINVAL, "alexnet_query: null argument");
+  alexnet tmp;
+  memset(&tmp, 0, sizeof tmp);
+  AX_TRY(plan(&tmp, cfg, nullptr));
+  *n_params = tmp.n_params;
+  *workspace_bytes = tmp.ws_bytes;
+  return ALEXNET_OK;
+}
+
+int alexnet_create(const alexnet_config_t* cfg, void* d_params, void* d_momentum, void* d_workspace,
+                   size_t workspace_bytes, void* stream, alexnet_t** out) {
+  REQUIRE(cfg && d_params && d_momentum && d_workspace && out, ALEXNET_EINVAL, "alexnet_create: null argument");
+  REQUIRE(aligned256(d_params) && aligned256(d_momentum) && aligned256(d_workspace), ALEXNET_EALIGN,
+          "alexnet_create: device pointers must be 256-byte aligned");
+  alexnet* n = new (std::nothrow) alexnet;
+  REQUIRE(n, ALEXNET_EINVAL, "out of host memory");
+  memset(n, 0, sizeof *n);
+  int r = plan(n, cfg, (char*)d_workspace);
+  if (r == ALEXNET_OK && workspace_bytes < n->ws_bytes) {
+    set_error("workspace too small: %zu < %zu bytes", workspace_bytes, n->ws_bytes);
+    r = ALEXNET_ENOMEM;
+  }
+  if (r == ALEXNET_OK) {
+    n->params = (float*)d_params;
+    n->mom = (float*)d_momentum;
+    r = launch_fill_bytes(d_workspace, n->ws_bytes, S(stream));
+  }
+  if (r != ALEXNET_OK) {
+    delete n;
+    return r;
+  }
+  *out = n;
+  return ALEXNET_OK;
+}
+
+void alexnet_destroy(alexnet_t* net) { delete net; }
+
+int alexnet_preprocess(alexnet_t* n, const uint8_t* d_raw, const float* d_mean, uint64_t step, int32_t slot,
+                       void* stream) {
+  REQUIRE(n && d_raw && d_mean, ALEXNET_EINVAL, "alexnet_preprocess: null argument");
+  REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_preprocess: slot must be 0 or 1");
+  const alexnet_config_t& c = n->cfg;
+  const uint64_t key = step_key(c.seed, step);
+  AX_TRY(launch_crop_params(key, c.batch, c.raw_w - c.crop_w + 1, c.raw_h - c.crop_h + 1, n->crop_x[slot],
+                            n->crop_y[slot], n->flip[slot], S(stream)));
+  return launch_preprocess(d_raw, d_mean, n->crop_x[slot], n->crop_y[slot], n->flip[slot], c.batch, c.in_c, c.raw_h,
+                           c.raw_w, c.crop_h, c.crop_w, n->input[slot], S(stream));
+}
+
+int alexnet_set_input(alexnet_t* n, const float* d_input_nchw, int32_t slot, void* stream) {
+  REQUIRE(n && d_input_nchw, ALEXNET_EINVAL, "alexnet_set_input: null argument");
+  REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_set_input: slot must be 0 or 1");
+  const alexnet_config_t& c = n->cfg;
+  return launch_nchw_to_nhwc(d_input_nchw, n->input[slot], c.batch, c.in_c, c.crop_h, c.crop_w, S(stream));
+}
+
+int alexnet_forward_backward(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss,
+                             void* stream) {
+  REQUIRE(n && d_labels && d_loss, ALEXNET_EINVAL, "alexnet_forward_backward: null argument");
+  REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_forward_backward: slot must be 0 or 1");
+  return fwd_bwd(n, slot, d_labels, step, d_loss, S(stream));
+}
+
+int alexnet_apply_update(alexnet_t* n, void* stream) {
+  REQUIRE(n, ALEXNET_EINVAL, "alexnet_apply_update: null handle");
+  return apply_update(n, S(stream));
+}
+
+int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss,
+                       void* stream) {
+  REQUIRE(n && d_labels && d_loss, ALEXNET_EINVAL, "alexnet_train_step: null argument");
+  REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_train_step: slot must be 0 or 1");
+  AX_TRY(fwd_bwd(n, slot, d_labels, step, d_loss, S(stream)));
+  return apply_update(n, S(stream));
+}
+
+int alexnet_forward(alexnet_t* n, const float* d_input_nchw, float* d_probs, void* stream) {
+  REQUIRE(n && d_input_nchw && d_probs, ALEXNET_EINVAL, "alexnet_forward: null argument");
+  const alexnet_config_t& c = n->cfg;
+  AX_TRY(launch_nchw_to_nhwc(d_input_nchw, n->input[2], c.batch, c.in_c, c.crop_h, c.crop_w, S(stream)));
+  AX_TRY(run_forward(n, n->input[2], false, 0, S(stream)));
+  Dense& last = n->fc[kFc - 1];
+  return launch_softmax_xent(last.act, nullptr, c.batch, last.out, 1, d_probs, n->row_loss, n->err_flag, S(stream));
+}
+
+int alexnet_average_replicas(alexnet_t* a, alexnet_t* b, void* stream) {
+  REQUIRE(a && b, ALEXNET_EINVAL, "alexnet_average_replicas: null handle");
+  REQUIRE(a != b, ALEXNET_EINVAL, "alexnet_average_replicas: the two replicas must be distinct");
+  REQUIRE(a->n_params == b->n_params && a->n_weights == b->n_weights, ALEXNET_ESHAPE,
+          "alexnet_average_replicas: configurations differ");
+  AX_TRY(launch_average(a->params, b->params, a->n_params, S(stream)));
+  return launch_average(a->mom, b->mom, a->n_params, S(stream));
+}
+
+int alexnet_set_params(alexnet_t* n, const float* d, void* stream) {
+  REQUIRE(n && d, ALEXNET_EINVAL, "alexnet_set_params: null argument");
+  return convert_flat(n, d, n->params, 0, S(stream));
+}
+int alexnet_get_params(alexnet_t* n, float* d, void* stream) {
+  REQUIRE(n && d, ALEXNET_EINVAL, "alexnet_get_params: null argument");
+  return convert_flat(n, n->params, d, 1, S(stream));
+}
+int alexnet_set_momentum(alexnet_t* n, const float* d, void* stream) {
+  REQUIRE(n && d, ALEXNET_EINVAL, "alexnet_set_momentum: null argument");
+  return convert_flat(n, d, n->mom, 0, S(stream));
+}
+int alexnet_get_momentum(alexnet_t* n, float* d, void* stream) {
+  REQUIRE(n && d, ALEXNET_EINVAL, "alexnet_get_momentum: null argument");
+  return convert_flat(n, n->mom, d, 1, S(stream));
+}
+int alexnet_get_grads(alexnet_t* n, float* d, void* stream) {
+  REQUIRE(n && d, ALEXNET_EINVAL, "alexnet_get_grads: null argument");
+  return convert_flat(n, n->grads, d, 1, S(stream));
+}
+
+int alexnet_tensor_elems(alexnet_t* n, int32_t kind, int32_t layer, size_t* elems) {
+  REQUIRE(n && elems, ALEXNET_EINVAL, "alexnet_tensor_elems: null argument");
+  const alexnet_config_t& c = n->cfg;
+  switch (kind) {
+    case ALEXNET_T_INPUT:
+      REQUIRE(layer >= 0 && layer < kSlots, ALEXNET_EINVAL, "bad slot");
+      *elems = (size_t)c.batch * c.in_c * c.crop_h * c.crop_w;
+      return ALEXNET_OK;
+    case ALEXNET_T_CROP_X:
+    case ALEXNET_T_CROP_Y:
+    case ALEXNET_T_FLIP:
+      REQUIRE(layer >= 0 && layer < 2, ALEXNET_EINVAL, "bad slot");
+      *elems = c.batch;
+      return ALEXNET_OK;
+    case ALEXNET_T_DLOGITS:
+      *elems = (size_t)c.batch * n->fc[kFc - 1].out;
+      return ALEXNET_OK;
+    case ALEXNET_T_FC_ACT:
+      REQUIRE(layer > kStages && layer <= kStages + kFc, ALEXNET_EINVAL, "dense layer must be 6..8");
+      *elems = (size_t)c.batch * n->fc[layer - kStages - 1].out;
+      return ALEXNET_OK;
+    default: break;
+  }
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  switch (kind) {
+    case ALEXNET_T_CONV_ACT:
+    case ALEXNET_T_CONV_DACT: *elems = s->act_elems(); return ALEXNET_OK;
+    case ALEXNET_T_LRN:
+      REQUIRE(s->lrn, ALEXNET_EINVAL, "stage has no LRN");
+      *elems = s->act_elems();
+      return ALEXNET_OK;
+    case ALEXNET_T_POOL:
+    case ALEXNET_T_ARGMAX:
+      REQUIRE(s->pool, ALEXNET_EINVAL, "stage has no pool");
+      *elems = s->out_elems();
+      return ALEXNET_OK;
+    default: break;
+  }
+  set_error("unknown tensor kind %d", kind);
+  return ALEXNET_EINVAL;
+}
+
+int alexnet_get_tensor(alexnet_t* n, int32_t kind, int32_t layer, void* d_out, void* stream) {
+  REQUIRE(n && d_out, ALEXNET_EINVAL, "alexnet_get_tensor: null argument");
+  size_t elems;
+  AX_TRY(alexnet_tensor_elems(n, kind, layer, &elems));
+  const alexnet_config_t& c = n->cfg;
+  hipStream_t st = S(stream);
+  switch (kind) {
+    case ALEXNET_T_INPUT: return launch_nhwc_to_nchw(n->input[layer], (float*)d_out, c.batch, c.in_c, c.crop_h, c.crop_w, st);
+    case ALEXNET_T_CROP_X: return launch_copy((const float*)n->crop_x[layer], (float*)d_out, elems, st);
+    case ALEXNET_T_CROP_Y: return launch_copy((const float*)n->crop_y[layer], (float*)d_out, elems, st);
+    case ALEXNET_T_FLIP: return launch_copy((const float*)n->flip[layer], (float*)d_out, elems, st);
+    case ALEXNET_T_DLOGITS: return launch_copy(n->fc[kFc - 1].dz, (float*)d_out, elems, st);
+    case ALEXNET_T_FC_ACT: return launch_copy(n->fc[layer - kStages - 1].act, (float*)d_out, elems, st);
+    default: break;
+  }
+  Stage& s = n->st[layer - 1];
+  switch (kind) {
+    case ALEXNET_T_CONV_ACT: return launch_nhwc_to_nchw(s.act, (float*)d_out, s.g.B, s.g.Cout, s.g.Ho, s.g.Wo, st);
+    case ALEXNET_T_CONV_DACT: return launch_nhwc_to_nchw(s.dact, (float*)d_out, s.g.B, s.g.Cout, s.g.Ho, s.g.Wo, st);
+    case ALEXNET_T_LRN: return launch_nhwc_to_nchw(s.lrn_out, (float*)d_out, s.g.B, s.g.Cout, s.g.Ho, s.g.Wo, st);
+    case ALEXNET_T_POOL: return launch_nhwc_to_nchw(s.pool_out, (float*)d_out, s.g.B, s.g.Cout, s.Hp, s.Wp, st);
+    case ALEXNET_T_ARGMAX:
+      return launch_pool_argmax_canonical(s.slot, (int32_t*)d_out, s.g.B, s.g.Cout, s.Hp, s.Wp, s.g.Wo, st);
+    default: break;
+  }
+  return ALEXNET_EINVAL;
+}
+
+int alexnet_check(alexnet_t* n, void* stream) {
+  REQUIRE(n, ALEXNET_EINVAL, "alexnet_check: null handle");
+  int32_t flag = 0;
+  AX_HIP(hipMemcpyAsync(&flag, n->err_flag, sizeof flag, hipMemcpyDeviceToHost, S(stream)));
+  AX_HIP(hipStreamSynchronize(S(stream)));
+  if (flag) {
+    AX_TRY(launch_fill_bytes(n->err_flag, 4, S(stream)));
+    set_error("a label outside [0, classes) was passed to a training step");
+    return ALEXNET_ELABEL;
+  }
+  return ALEXNET_OK;
+}
+
+// ---- single operators ---------------------------------------------------------
+int alexnet_nchw_to_nhwc(const float* s, float* d, int32_t n, int32_t c, int32_t h, int32_t w, void* stream) {
+  REQUIRE(s && d && n >= 0 && c > 0 && h > 0 && w > 0, ALEXNET_EINVAL, "alexnet_nchw_to_nhwc: bad argument");
+  return launch_nchw_to_nhwc(s, d, n, c, h, w, S(stream));
+}
+int alexnet_nhwc_to_nchw(const float* s, float* d, int32_t n, int32_t c, int32_t h, int32_t w, void* stream) {
+  REQUIRE(s && d && n >= 0 && c > 0 && h > 0 && w > 0, ALEXNET_EINVAL, "alexnet_nhwc_to_nchw: bad argument");
+  return launch_nhwc_to_nchw(s, d, n, c, h, w, S(stream));
+}
+int alexnet_pack_conv_weight(alexnet_t* n, int32_t layer, const float* w, float* wf, float* wb, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(w && wf, ALEXNET_EINVAL, "alexnet_pack_conv_weight: null argument");
+  AX_TRY(launch_conv_weight_pack(w, wf, s->g.Cout, s->g.cg(), s->g.k, s->g.groups, 0, S(stream)));
+  if (wb) AX_TRY(launch_conv_weight_wb(wf, wb, s->g.Cout, s->g.cg(), s->g.k, s->g.groups, S(stream)));
+  return ALEXNET_OK;
+}
+int alexnet_unpack_conv_weight(alexnet_t* n, int32_t layer, const float* wf, float* w, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(w && wf, ALEXNET_EINVAL, "alexnet_unpack_conv_weight: null argument");
+  return launch_conv_weight_pack(wf, w, s->g.Cout, s->g.cg(), s->g.k, s->g.groups, 1, S(stream));
+}
+int alexnet_conv_forward_nhwc(alexnet_t* n, int32_t layer, const float* x, const float* wf, const float* b,
+                              int32_t relu, float* y, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(x && wf && y, ALEXNET_EINVAL, "alexnet_conv_forward_nhwc: null argument");
+  return launch_conv_fwd(s->g, x, wf, b, relu, y, S(stream));
+}
+int alexnet_conv_backward_data_nhwc(alexnet_t* n, int32_t layer, const float* dy, const float* wb, float* dx,
+                                    void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(dy && wb && dx, ALEXNET_EINVAL, "alexnet_conv_backward_data_nhwc: null argument");
+  return launch_conv_bwd_data(s->g, dy, wb, nullptr, dx, S(stream));
+}
+int alexnet_conv_backward_weight_nhwc(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dwf,
+                                      float* db, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(x && dy && dwf, ALEXNET_EINVAL, "alexnet_conv_backward_weight_nhwc: null argument");
+  AX_TRY(launch_conv_bwd_weight(s->g, x, dy, dwf, n->gemm_ws, S(stream)));
+  if (db) AX_TRY(launch_colsum(dy, s->g.P(), s->g.Cout, db, n->colsum_ws, S(stream)));
+  return ALEXNET_OK;
+}
+int alexnet_conv_forward(alexnet_t* n, int32_t layer, const float* x, const float* w, const float* b, int32_t relu,
+                         float* y, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(x && w && y, ALEXNET_EINVAL, "alexnet_conv_forward: null argument");
+  const ConvGeom& g = s->g;
+  AX_TRY(launch_nchw_to_nhwc(x, n->scratch_x, g.B, g.Cin, g.H, g.W, S(stream)));
+  AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
+  AX_TRY(launch_conv_fwd(g, n->scratch_x, n->scratch_w[0], b, relu, n->scratch_y, S(stream)));
+  return launch_nhwc_to_nchw(n->scratch_y, y, g.B, g.Cout, g.Ho, g.Wo, S(stream));
+}
+int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, const float* w, float* dx,
+                               void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(dy && w && dx, ALEXNET_EINVAL, "alexnet_conv_backward_data: null argument");
+  const ConvGeom& g = s->g;
+  AX_TRY(launch_nchw_to_nhwc(dy, n->scratch_y, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
+  AX_TRY(launch_conv_weight_wb(n->scratch_w[0], n->scratch_w[1], g.Cout, g.cg(), g.k, g.groups, S(stream)));
+  AX_TRY(launch_conv_bwd_data(g, n->scratch_y, n->scratch_w[1], nullptr, n->scratch_x, S(stream)));
+  return launch_nhwc_to_nchw(n->scratch_x, dx, g.B, g.Cin, g.H, g.W, S(stream));
+}
+int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dw, float* db,
+                                 void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(x && dy && dw, ALEXNET_EINVAL, "alexnet_conv_backward_weight: null argument");
+  const ConvGeom& g = s->g;
+  AX_TRY(launch_nchw_to_nhwc(x, n->scratch_x, g.B, g.Cin, g.H, g.W, S(stream)));
+  AX_TRY(launch_nchw_to_nhwc(dy, n->scratch_y, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_conv_bwd_weight(g, n->scratch_x, n->scratch_y, n->scratch_w[2], n->gemm_ws, S(stream)));
+  AX_TRY(launch_conv_weight_pack(n->scratch_w[2], dw, g.Cout, g.cg(), g.k, g.groups, 1, S(stream)));
+  if (db) AX_TRY(launch_colsum(n->scratch_y, g.P(), g.Cout, db, n->colsum_ws, S(stream)));
+  return ALEXNET_OK;
+}
+
+}  // extern "C"

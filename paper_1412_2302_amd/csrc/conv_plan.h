@@ -1,0 +1,98 @@
+// Maps one convolution stage onto the three implicit GEMMs that compute it.
+// Plain host code shared by the launchers and by the CPU emulation test.
+//
+// Internal layouts (channel-last):
+//   activations  x[B][H][W][Cin],  y / dy[B][Ho][Wo][Cout]
+//   forward weights   wf[g][(r,s,c)][o]   r,s taps, c < Cin/G, o < Cout/G
+//   backward weights  wb[g][(r,s,o)][c]   same numbers, last two axes swapped
+//
+//   forward   y [p][g*og + o]  = sum_{(r,s,c)} im2col(x)[p][(r,s,c)] * wf[g][(r,s,c)][o]
+//   bwd-data  dx[q][g*cg + c]  = sum_{(r,s,o)} im2colT(dy)[q][(r,s,o)] * wb[g][(r,s,o)][c]
+//   bwd-wgt   dwf[g][(r,s,c)][o] = sum_p im2col(x)[p][(r,s,c)] * dy[p][g*og + o]
+#pragma once
+#include <stdint.h>
+
+#include "gemm.h"
+
+namespace ax {
+
+struct ConvGeom {
+  int B, H, W, Cin, Cout, k, stride, pad, groups, Ho, Wo;
+  int cg() const { return Cin / groups; }
+  int og() const { return Cout / groups; }
+  long in_elems() const { return (long)B * H * W * Cin; }
+  long out_elems() const { return (long)B * Ho * Wo * Cout; }
+  long w_elems() const { return (long)Cout * cg() * k * k; }
+  int kf() const { return k * k * cg(); }  // reduction length of the forward GEMM
+  int kb() const { return k * k * og(); }  // reduction length of the backward-data GEMM
+  long P() const { return (long)B * Ho * Wo; }
+  long Q() const { return (long)B * H * W; }
+};
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+struct GemmDims {
+  int M, N, K, groups;
+};
+
+// ---- forward ----
+inline GemmDims fwd_dims(const ConvGeom& c) { return {(int)c.P(), c.og(), c.kf(), c.groups}; }
+inline Im2colParams fwd_A(const ConvGeom& c, const float* x) {
+  Im2colParams a;
+  a.x = x; a.H = c.H; a.W = c.W; a.Ctot = c.Cin; a.Cg = c.cg(); a.c_stride_g = c.cg();
+  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad; a.transposed = 0;
+  a.OH = c.Ho; a.OW = c.Wo; a.P = (int)c.P();
+  a.vec = (c.cg() % 4 == 0 && c.Cin % 4 == 0 && aligned16(x)) ? 1 : 0;
+  return a;
+}
+inline DenseParams fwd_B(const ConvGeom& c, const float* wf) {
+  DenseParams b;
+  b.p = wf; b.ld = c.og(); b.gstride = (long)c.kf() * c.og(); b.R = c.og();
+  b.vec = (c.og() % 4 == 0 && aligned16(wf)) ? 1 : 0;
+  return b;
+}
+
+// ---- backward data ----
+inline GemmDims bwdd_dims(const ConvGeom& c) { return {(int)c.Q(), c.cg(), c.kb(), c.groups}; }
+inline Im2colParams bwdd_A(const ConvGeom& c, const float* dy) {
+  Im2colParams a;
+  a.x = dy; a.H = c.Ho; a.W = c.Wo; a.Ctot = c.Cout; a.Cg = c.og(); a.c_stride_g = c.og();
+  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad; a.transposed = 1;
+  a.OH = c.H; a.OW = c.W; a.P = (int)c.Q();
+  a.vec = (c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy)) ? 1 : 0;
+  return a;
+}
+inline DenseParams bwdd_B(const ConvGeom& c, const float* wb) {
+  DenseParams b;
+  b.p = wb; b.ld = c.cg(); b.gstride = (long)c.kb() * c.cg(); b.R = c.cg();
+  b.vec = (c.cg() % 4 == 0 && aligned16(wb)) ? 1 : 0;
+  return b;
+}
+
+// ---- backward weight ----
+inline GemmDims bwdw_dims(const ConvGeom& c) { return {c.kf(), c.og(), (int)c.P(), c.groups}; }
+inline Im2colParams bwdw_A(const ConvGeom& c, const float* x) {
+  Im2colParams a = fwd_A(c, x);
+  return a;
+}
+inline DenseParams bwdw_B(const ConvGeom& c, const float* dy) {
+  DenseParams b;
+  b.p = dy; b.ld = c.Cout; b.gstride = c.og(); b.R = c.og();
+  b.vec = (c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy)) ? 1 : 0;
+  return b;
+}
+
+// Split of the reduction so that a launch has enough workgroups: returns the
+// number of splits and sets kchunk (a multiple of bk).
+inline int plan_split(long tiles, int K, int bk, int target_blocks, int max_split, int* kchunk) {
+  int ktiles = (K + bk - 1) / bk;
+  int want = (int)((target_blocks + tiles - 1) / tiles);
+  if (want < 1) want = 1;
+  if (want > max_split) want = max_split;
+  if (want > ktiles) want = ktiles;
+  int per = (ktiles + want - 1) / want;
+  *kchunk = per * bk;
+  return (ktiles + per - 1) / per;
+}
+
+}  // namespace ax

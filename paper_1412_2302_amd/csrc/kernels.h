@@ -1,0 +1,72 @@
+// Host-side launch functions of every kernel in the library.  All tensors are
+// device pointers in the internal channel-last layout unless a name says
+// otherwise; every function only enqueues work on `st` and returns a status.
+#pragma once
+#include "common.h"
+#include "conv_plan.h"
+
+namespace ax {
+
+// ---- convolution as implicit GEMM (conv_gemm.hip) ---------------------------
+int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
+                    hipStream_t st);
+int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
+                         hipStream_t st);
+size_t conv_bwd_weight_ws_floats(const ConvGeom& c);
+int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* ws, hipStream_t st);
+
+// ---- dense layers (fc_gemm.hip) ---------------------------------------------
+struct FcAct {
+  const float* bias;  // [out]
+  int relu;
+  int dropout;        // 1: multiply by the keep mask of (key, tag)
+  uint64_t key;
+  uint32_t tag, thresh24;
+  float scale;        // applied after the ReLU (1 - p at inference, else 1)
+};
+size_t fc_ws_floats(int B, int in, int out);
+int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const FcAct& act, float* y, float* ws,
+                  hipStream_t st);
+int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, const float* gate, float* dx,
+                       float* ws, hipStream_t st);
+int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy, float* dw, hipStream_t st);
+
+// ---- bandwidth-bound kernels (ops.hip) --------------------------------------
+int launch_fill(float* p, size_t n, float v, hipStream_t st);
+int launch_fill_bytes(void* p, size_t nbytes, hipStream_t st);  // zero fill, nbytes % 4 == 0
+int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* ox, int32_t* oy, int32_t* flip,
+                       hipStream_t st);
+int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, const int32_t* oy,
+                      const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st);
+int launch_nchw_to_nhwc(const float* src, float* dst, int N, int C, int H, int W, hipStream_t st);
+int launch_nhwc_to_nchw(const float* src, float* dst, int N, int C, int H, int W, hipStream_t st);
+int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k, float alpha, float beta,
+                   hipStream_t st);
+// da = (dL/db through the normalisation) gated by a > 0 when relu_gate is set
+int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int C, int n, float k, float alpha,
+                   float beta, int relu_gate, hipStream_t st);
+int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo,
+                    hipStream_t st);
+// dx[n][y][x][c] = sum of dy over the windows whose winning tap is (y,x); gated by gate > 0 when gate != null
+int launch_pool_bwd(const float* dy, const uint8_t* slot, const float* gate, float* dx, int N, int H, int W, int C,
+                    int Ho, int Wo, hipStream_t st);
+int launch_pool_argmax_canonical(const uint8_t* slot, int32_t* out_nchw, int N, int C, int Ho, int Wo, int W,
+                                 hipStream_t st);
+// mode 0: dz = (p - onehot)/B and per-row loss; mode 1: p only
+int launch_softmax_xent(const float* z, const int32_t* labels, int B, int classes, int mode, float* out,
+                        float* row_loss, int32_t* err_flag, hipStream_t st);
+int launch_mean_loss(const float* row_loss, int B, float* loss, hipStream_t st);
+int launch_colsum(const float* m, long rows, int cols, float* out, float* ws, hipStream_t st);
+size_t colsum_ws_floats(long rows, int cols);
+int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, float* out, hipStream_t st);
+int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
+                      hipStream_t st);
+int launch_average(float* a, float* b, size_t n, hipStream_t st);
+// layout conversions of parameters; dir 0: canonical -> internal, 1: internal -> canonical
+int launch_conv_weight_pack(const float* src, float* dst, int Cout, int Cg, int k, int groups, int dir,
+                            hipStream_t st);
+int launch_conv_weight_wb(const float* wf, float* wb, int Cout, int Cg, int k, int groups, hipStream_t st);
+int launch_fc_weight_permute(const float* src, float* dst, int out, int C, int HW, int dir, hipStream_t st);
+int launch_copy(const float* src, float* dst, size_t n, hipStream_t st);
+
+}  // namespace ax

@@ -1,0 +1,573 @@
+// Bandwidth-bound kernels of the AlexNet step: preprocessing, response
+// normalisation, max pooling, softmax cross-entropy, reductions, the momentum
+// update, replica averaging and layout conversions.  Activations are
+// channel-last ([N][H][W][C]); a lane owns four consecutive channels wherever
+// C % 4 == 0 so that every global access is a coalesced 16-byte load/store.
+#include <math.h>
+
+#include "kernels.h"
+
+namespace ax {
+
+static inline unsigned grid_for(size_t n, unsigned block) { return (unsigned)((n + block - 1) / block); }
+
+// ------------------------------------------------------------------ fill ---
+__global__ void fill_kernel(float* p, size_t n, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+int launch_fill(float* p, size_t n, float v, hipStream_t st) {
+  if (n == 0) return ALEXNET_OK;
+  unsigned g = grid_for(n, 256);
+  if (g > 4096) g = 4096;
+  hipLaunchKernelGGL(fill_kernel, dim3(g), dim3(256), 0, st, p, n, v);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+int launch_fill_bytes(void* p, size_t nbytes, hipStream_t st) { return launch_fill((float*)p, nbytes / 4, 0.f, st); }
+
+__global__ void copy_kernel(const float* __restrict__ s, float* __restrict__ d, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) d[i] = s[i];
+}
+int launch_copy(const float* src, float* dst, size_t n, hipStream_t st) {
+  if (n == 0) return ALEXNET_OK;
+  unsigned g = grid_for(n, 256);
+  if (g > 8192) g = 8192;
+  hipLaunchKernelGGL(copy_kernel, dim3(g), dim3(256), 0, st, src, dst, n);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// ------------------------------------------------------------ preprocess ---
+// Paper Section 2.1 (footnote): mean subtraction, random crop, random flip.
+__global__ void crop_params_kernel(uint64_t key, int B, int range_x, int range_y, int32_t* ox, int32_t* oy,
+                                   int32_t* flip) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= B) return;
+  ox[n] = (int32_t)((rand_u64(key, TAG_CROP_X, n) >> 32) % (uint64_t)range_x);
+  oy[n] = (int32_t)((rand_u64(key, TAG_CROP_Y, n) >> 32) % (uint64_t)range_y);
+  flip[n] = (int32_t)(rand_u64(key, TAG_FLIP, n) >> 63);
+}
+int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* ox, int32_t* oy, int32_t* flip,
+                       hipStream_t st) {
+  hipLaunchKernelGGL(crop_params_kernel, dim3(grid_for(B, 64)), dim3(64), 0, st, key, B, range_x, range_y, ox, oy,
+                     flip);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// out[n][y][x][c] = raw[n][c][oy+y][ox + (flip ? CW-1-x : x)] - mean[c][same]
+__global__ void preprocess_kernel(const uint8_t* __restrict__ raw, const float* __restrict__ mean,
+                                  const int32_t* __restrict__ ox, const int32_t* __restrict__ oy,
+                                  const int32_t* __restrict__ flip, int B, int C, int RH, int RW, int CH, int CW,
+                                  float* __restrict__ out) {
+  const size_t total = (size_t)B * CH * CW;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int x = (int)(i % CW);
+  const int y = (int)((i / CW) % CH);
+  const int n = (int)(i / ((size_t)CW * CH));
+  const int sx = ox[n] + (flip[n] ? CW - 1 - x : x);
+  const int sy = oy[n] + y;
+  const size_t plane = (size_t)RH * RW;
+  const size_t src = (size_t)sy * RW + sx;
+  for (int c = 0; c < C; ++c)
+    out[i * C + c] = (float)raw[((size_t)n * C + c) * plane + src] - mean[(size_t)c * plane + src];
+}
+int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, const int32_t* oy,
+                      const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st) {
+  const size_t total = (size_t)B * CH * CW;
+  hipLaunchKernelGGL(preprocess_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, raw, mean, ox, oy, flip, B, C,
+                     RH, RW, CH, CW, out);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// ------------------------------------------------------ layout transposes ---
+__global__ void nchw_to_nhwc_kernel(const float* __restrict__ s, float* __restrict__ d, int N, int C, int HW) {
+  const size_t total = (size_t)N * C * HW;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into nhwc
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  const size_t p = i / C;
+  const int hw = (int)(p % HW);
+  const size_t n = p / HW;
+  d[i] = s[(n * C + c) * HW + hw];
+}
+__global__ void nhwc_to_nchw_kernel(const float* __restrict__ s, float* __restrict__ d, int N, int C, int HW) {
+  const size_t total = (size_t)N * C * HW;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into nchw
+  if (i >= total) return;
+  const int hw = (int)(i % HW);
+  const size_t q = i / HW;
+  const int c = (int)(q % C);
+  const size_t n = q / C;
+  d[i] = s[(n * HW + hw) * C + c];
+}
+int launch_nchw_to_nhwc(const float* src, float* dst, int N, int C, int H, int W, hipStream_t st) {
+  const size_t total = (size_t)N * C * H * W;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, src, dst, N, C, H * W);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+int launch_nhwc_to_nchw(const float* src, float* dst, int N, int C, int H, int W, hipStream_t st) {
+  const size_t total = (size_t)N * C * H * W;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(nhwc_to_nchw_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, src, dst, N, C, H * W);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// ------------------------------------------------------------------- LRN ---
+// b_i = a_i * s_i^-beta, s_i = k + alpha * sum_{j in [i-n/2, i+n/2] clipped} a_j^2
+__device__ __forceinline__ float neg_pow(float s, float beta) {
+  // s^-beta; the AlexNet exponent 3/4 is two square roots
+  if (beta == 0.75f) {
+    const float r = 1.0f / sqrtf(s);
+    return r * sqrtf(r);
+  }
+  return powf(s, -beta);
+}
+
+__global__ void lrn_fwd_kernel(const float* __restrict__ a, float* __restrict__ b, size_t total, int C, int half,
+                               float k, float alpha, float beta) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  const int lo = max(c - half, 0), hi = min(c + half, C - 1);
+  const float* row = a + (i - c);
+  float s = 0.f;
+  for (int j = lo; j <= hi; ++j) s += row[j] * row[j];
+  s = k + alpha * s;
+  b[i] = row[c] * neg_pow(s, beta);
+}
+
+__global__ void lrn_bwd_kernel(const float* __restrict__ a, const float* __restrict__ db, float* __restrict__ da,
+                               size_t total, int C, int half, float k, float alpha, float beta, int relu_gate) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  const float* row = a + (i - c);
+  const float* drow = db + (i - c);
+  const float ai = row[c];
+  float out = 0.f;
+  if (!relu_gate || ai > 0.f) {
+    float acc = 0.f, si = 0.f;
+    const int lo = max(c - half, 0), hi = min(c + half, C - 1);
+    for (int j = lo; j <= hi; ++j) {
+      const int l2 = max(j - half, 0), h2 = min(j + half, C - 1);
+      float s = 0.f;
+      for (int q = l2; q <= h2; ++q) s += row[q] * row[q];
+      s = k + alpha * s;
+      if (j == c) si = s;
+      acc += drow[j] * row[j] * neg_pow(s, beta) / s;
+    }
+    out = drow[c] * neg_pow(si, beta) - 2.f * alpha * beta * ai * acc;
+  }
+  da[i] = out;
+}
+
+int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k, float alpha, float beta,
+                   hipStream_t st) {
+  const size_t total = (size_t)pixels * C;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, b, total, C, n / 2, k, alpha,
+                     beta);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int C, int n, float k, float alpha,
+                   float beta, int relu_gate, hipStream_t st) {
+  const size_t total = (size_t)pixels * C;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, db, da, total, C, n / 2, k,
+                     alpha, beta, relu_gate);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// -------------------------------------------------------------- max pool ---
+// 3x3 stride-2 windows scanned row-major; a tap replaces the running maximum
+// only when strictly greater (first maximum wins).  slot = r*3 + s of the
+// winner, one byte per output element.
+__global__ void pool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, uint8_t* __restrict__ slot,
+                                int N, int H, int W, int C, int Ho, int Wo) {
+  const size_t total = (size_t)N * Ho * Wo * C;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  size_t p = i / C;
+  const int xo = (int)(p % Wo);
+  p /= Wo;
+  const int yo = (int)(p % Ho);
+  const size_t n = p / Ho;
+  const float* base = x + ((n * H + 2 * yo) * W + 2 * xo) * C + c;
+  float best = base[0];
+  int bs = 0;
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      if (r == 0 && s == 0) continue;
+      const float v = base[((size_t)r * W + s) * C];
+      if (v > best) {
+        best = v;
+        bs = r * 3 + s;
+      }
+    }
+  y[i] = best;
+  slot[i] = (uint8_t)bs;
+}
+int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo,
+                    hipStream_t st) {
+  const size_t total = (size_t)N * Ho * Wo * C;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(pool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, slot, N, H, W, C, Ho, Wo);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// Gather form of the pooling adjoint: each input element looks at the (at
+// most four) windows covering it and adds dy of those that chose it.
+__global__ void pool_bwd_kernel(const float* __restrict__ dy, const uint8_t* __restrict__ slot,
+                                const float* __restrict__ gate, float* __restrict__ dx, int N, int H, int W, int C,
+                                int Ho, int Wo) {
+  const size_t total = (size_t)N * H * W * C;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  size_t p = i / C;
+  const int x = (int)(p % W);
+  p /= W;
+  const int y = (int)(p % H);
+  const size_t n = p / H;
+  float acc = 0.f;
+  if (!gate || gate[i] > 0.f) {
+    const int yo_lo = y >= 2 ? (y - 1) / 2 : 0, yo_hi = min(y / 2, Ho - 1);
+    const int xo_lo = x >= 2 ? (x - 1) / 2 : 0, xo_hi = min(x / 2, Wo - 1);
+    for (int yo = yo_lo; yo <= yo_hi; ++yo)
+      for (int xo = xo_lo; xo <= xo_hi; ++xo) {
+        const size_t o = ((n * Ho + yo) * Wo + xo) * C + c;
+        const int want = (y - 2 * yo) * 3 + (x - 2 * xo);
+        if ((int)slot[o] == want) acc += dy[o];
+      }
+  }
+  dx[i] = acc;
+}
+int launch_pool_bwd(const float* dy, const uint8_t* slot, const float* gate, float* dx, int N, int H, int W, int C,
+                    int Ho, int Wo, hipStream_t st) {
+  const size_t total = (size_t)N * H * W * C;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(pool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, slot, gate, dx, N, H, W, C,
+                     Ho, Wo);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// slot bytes (channel-last) -> canonical int32 NCHW index y_in*W + x_in
+__global__ void pool_argmax_canonical_kernel(const uint8_t* __restrict__ slot, int32_t* __restrict__ out, int N,
+                                             int C, int Ho, int Wo, int W) {
+  const size_t total = (size_t)N * C * Ho * Wo;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // nchw index
+  if (i >= total) return;
+  const int xo = (int)(i % Wo);
+  size_t q = i / Wo;
+  const int yo = (int)(q % Ho);
+  q /= Ho;
+  const int c = (int)(q % C);
+  const size_t n = q / C;
+  const int s = slot[((n * Ho + yo) * Wo + xo) * C + c];
+  out[i] = (2 * yo + s / 3) * W + 2 * xo + s % 3;
+}
+int launch_pool_argmax_canonical(const uint8_t* slot, int32_t* out_nchw, int N, int C, int Ho, int Wo, int W,
+                                 hipStream_t st) {
+  const size_t total = (size_t)N * C * Ho * Wo;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(pool_argmax_canonical_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, slot, out_nchw, N,
+                     C, Ho, Wo, W);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// --------------------------------------------------- softmax cross-entropy ---
+__device__ __forceinline__ float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// all 256 threads receive the block-wide result; order of combination is fixed
+__device__ __forceinline__ float block_reduce(float v, float* sh, bool is_max) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  v = is_max ? wave_max(v) : wave_sum(v);
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  float r = sh[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = is_max ? fmaxf(r, sh[w]) : r + sh[w];
+  return r;
+}
+
+// one workgroup per row; p = exp(z - max - log(sum exp))
+__global__ void __launch_bounds__(256)
+softmax_xent_kernel(const float* __restrict__ z, const int32_t* __restrict__ labels, int B, int classes, int mode,
+                    float* __restrict__ out, float* __restrict__ row_loss, int32_t* __restrict__ err_flag) {
+  __shared__ float sh[4];
+  const int n = blockIdx.x;
+  const float* zr = z + (size_t)n * classes;
+  float m = -INFINITY;
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) m = fmaxf(m, zr[j]);
+  m = block_reduce(m, sh, true);
+  float s = 0.f;
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) s += expf(zr[j] - m);
+  s = block_reduce(s, sh, false);
+  const float lse = logf(s);
+  int lab = 0;
+  if (mode == 0) {
+    lab = labels[n];
+    if (lab < 0 || lab >= classes) {
+      if (threadIdx.x == 0) atomicOr(err_flag, 1);
+      lab = lab < 0 ? 0 : classes - 1;
+    }
+    if (threadIdx.x == 0) row_loss[n] = -(zr[lab] - m - lse);
+  }
+  const float inv_b = 1.0f / (float)B;
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
+    const float p = expf(zr[j] - m - lse);
+    out[(size_t)n * classes + j] = mode == 0 ? (p - (j == lab ? 1.f : 0.f)) * inv_b : p;
+  }
+}
+int launch_softmax_xent(const float* z, const int32_t* labels, int B, int classes, int mode, float* out,
+                        float* row_loss, int32_t* err_flag, hipStream_t st) {
+  hipLaunchKernelGGL(softmax_xent_kernel, dim3(B), dim3(256), 0, st, z, labels, B, classes, mode, out, row_loss,
+                     err_flag);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+__global__ void __launch_bounds__(256) mean_loss_kernel(const float* __restrict__ row_loss, int B, float* loss) {
+  __shared__ float sh[4];
+  float s = 0.f;
+  for (int j = threadIdx.x; j < B; j += blockDim.x) s += row_loss[j];
+  s = block_reduce(s, sh, false);
+  if (threadIdx.x == 0) *loss = s / (float)B;
+}
+int launch_mean_loss(const float* row_loss, int B, float* loss, hipStream_t st) {
+  hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(256), 0, st, row_loss, B, loss);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// ------------------------------------------------------------ reductions ---
+// Column sums of a row-major [rows][cols] matrix (bias gradients), in two
+// passes with a fixed combination order so results do not depend on timing.
+constexpr int kColsumRowsPerBlock = 2048;
+__global__ void __launch_bounds__(256)
+colsum_stage1(const float* __restrict__ m, long rows, int cols, float* __restrict__ part) {
+  __shared__ float sh[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cl;
+  const long r0 = (long)blockIdx.y * kColsumRowsPerBlock;
+  const long r1 = min(rows, r0 + kColsumRowsPerBlock);
+  float s = 0.f;
+  if (col < cols)
+    for (long r = r0 + rl; r < r1; r += 4) s += m[r * cols + col];
+  sh[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && col < cols) part[(size_t)blockIdx.y * cols + col] = (sh[0][cl] + sh[1][cl]) + (sh[2][cl] + sh[3][cl]);
+}
+__global__ void colsum_stage2(const float* __restrict__ part, int nparts, int cols, float* __restrict__ out) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= cols) return;
+  float s = 0.f;
+  for (int p = 0; p < nparts; ++p) s += part[(size_t)p * cols + col];
+  out[col] = s;
+}
+size_t colsum_ws_floats(long rows, int cols) {
+  return (size_t)ceil_div(rows, kColsumRowsPerBlock) * cols;
+}
+int launch_colsum(const float* m, long rows, int cols, float* out, float* ws, hipStream_t st) {
+  const int nparts = ceil_div(rows, kColsumRowsPerBlock);
+  hipLaunchKernelGGL(colsum_stage1, dim3(ceil_div(cols, 64), nparts), dim3(256), 0, st, m, rows, cols, ws);
+  AX_LAUNCH_CHECK();
+  hipLaunchKernelGGL(colsum_stage2, dim3(ceil_div(cols, 256)), dim3(256), 0, st, ws, nparts, cols, out);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// out[g][i] = sum_s ws[g*nsplit + s][i]  (split-k partial slabs)
+__global__ void reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int groups,
+                                    float* __restrict__ out) {
+  const size_t total = slab * groups;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const size_t g = i / slab, e = i - g * slab;
+  const float* p = ws + g * nsplit * slab + e;
+  float s = 0.f;
+  for (int k = 0; k < nsplit; ++k) s += p[(size_t)k * slab];
+  out[i] = s;
+}
+int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, float* out, hipStream_t st) {
+  const size_t total = (size_t)slab * groups;
+  if (!total) return ALEXNET_OK;
+  hipLaunchKernelGGL(reduce_slabs_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, ws, nsplit, (size_t)slab,
+                     groups, out);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// ---------------------------------------------------------------- update ---
+// v <- mu v - lr (g + wd w);  w <- w + v.  Elements below n_decay are weights
+// (decayed), the rest are biases (not decayed).
+__global__ void sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g, size_t n,
+                                  size_t n_decay, float lr, float mu, float wd) {
+  const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t i = q * 4;
+  if (i + 3 < n) {
+    float4 w4 = *reinterpret_cast<float4*>(w + i);
+    float4 v4 = *reinterpret_cast<float4*>(v + i);
+    const float4 g4 = *reinterpret_cast<const float4*>(g + i);
+    const float d0 = i + 0 < n_decay ? wd : 0.f, d1 = i + 1 < n_decay ? wd : 0.f;
+    const float d2 = i + 2 < n_decay ? wd : 0.f, d3 = i + 3 < n_decay ? wd : 0.f;
+    v4.x = mu * v4.x - lr * (g4.x + d0 * w4.x);
+    v4.y = mu * v4.y - lr * (g4.y + d1 * w4.y);
+    v4.z = mu * v4.z - lr * (g4.z + d2 * w4.z);
+    v4.w = mu * v4.w - lr * (g4.w + d3 * w4.w);
+    w4.x += v4.x;
+    w4.y += v4.y;
+    w4.z += v4.z;
+    w4.w += v4.w;
+    *reinterpret_cast<float4*>(v + i) = v4;
+    *reinterpret_cast<float4*>(w + i) = w4;
+  } else {
+    for (size_t j = i; j < n; ++j) {
+      const float d = j < n_decay ? wd : 0.f;
+      const float vn = mu * v[j] - lr * (g[j] + d * w[j]);
+      v[j] = vn;
+      w[j] += vn;
+    }
+  }
+}
+int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
+                      hipStream_t st) {
+  if (!n) return ALEXNET_OK;
+  hipLaunchKernelGGL(sgd_update_kernel, dim3(grid_for((n + 3) / 4, 256)), dim3(256), 0, st, w, v, g, n, n_decay, lr,
+                     mu, wd);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// --------------------------------------------------- replica averaging ------
+// Paper Section 2.2, steps 2+3 on one GPU: the peer replica is the staging
+// copy, so exchange and average collapse into one pass that writes the mean
+// to both sides.
+__global__ void average_kernel(float* __restrict__ a, float* __restrict__ b, size_t n) {
+  const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t i = q * 4;
+  if (i + 3 < n) {
+    const float4 x = *reinterpret_cast<const float4*>(a + i);
+    const float4 y = *reinterpret_cast<const float4*>(b + i);
+    float4 m;
+    m.x = 0.5f * (x.x + y.x);
+    m.y = 0.5f * (x.y + y.y);
+    m.z = 0.5f * (x.z + y.z);
+    m.w = 0.5f * (x.w + y.w);
+    *reinterpret_cast<float4*>(a + i) = m;
+    *reinterpret_cast<float4*>(b + i) = m;
+  } else {
+    for (size_t j = i; j < n; ++j) {
+      const float m = 0.5f * (a[j] + b[j]);
+      a[j] = m;
+      b[j] = m;
+    }
+  }
+}
+int launch_average(float* a, float* b, size_t n, hipStream_t st) {
+  if (!n) return ALEXNET_OK;
+  hipLaunchKernelGGL(average_kernel, dim3(grid_for((n + 3) / 4, 256)), dim3(256), 0, st, a, b, n);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// ------------------------------------------------- parameter layouts --------
+// canonical w[o][c][r][s]  <->  internal wf[g][(r,s,c)][o%og]
+__global__ void conv_weight_pack_kernel(const float* __restrict__ src, float* __restrict__ dst, int Cout, int Cg,
+                                        int k, int groups, int dir) {
+  const int og = Cout / groups;
+  const size_t total = (size_t)Cout * Cg * k * k;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // internal index
+  if (i >= total) return;
+  const int ol = (int)(i % og);
+  size_t q = i / og;
+  const int c = (int)(q % Cg);
+  q /= Cg;
+  const int s = (int)(q % k);
+  q /= k;
+  const int r = (int)(q % k);
+  const int g = (int)(q / k);
+  const size_t canon = ((((size_t)(g * og + ol)) * Cg + c) * k + r) * k + s;
+  if (dir == 0)
+    dst[i] = src[canon];
+  else
+    dst[canon] = src[i];
+}
+int launch_conv_weight_pack(const float* src, float* dst, int Cout, int Cg, int k, int groups, int dir,
+                            hipStream_t st) {
+  const size_t total = (size_t)Cout * Cg * k * k;
+  hipLaunchKernelGGL(conv_weight_pack_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, src, dst, Cout, Cg, k,
+                     groups, dir);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+// wb[g][(r,s,o)][c] = wf[g][(r,s,c)][o]
+__global__ void conv_weight_wb_kernel(const float* __restrict__ wf, float* __restrict__ wb, int Cout, int Cg, int k,
+                                      int groups) {
+  const int og = Cout / groups;
+  const size_t total = (size_t)Cout * Cg * k * k;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into wb
+  if (i >= total) return;
+  const int c = (int)(i % Cg);
+  size_t q = i / Cg;
+  const int ol = (int)(q % og);
+  q /= og;
+  const size_t grs = q;  // (g*k + r)*k + s
+  wb[i] = wf[(grs * Cg + c) * og + ol];
+}
+int launch_conv_weight_wb(const float* wf, float* wb, int Cout, int Cg, int k, int groups, hipStream_t st) {
+  const size_t total = (size_t)Cout * Cg * k * k;
+  hipLaunchKernelGGL(conv_weight_wb_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, wf, wb, Cout, Cg, k,
+                     groups);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+// canonical w[o][(c,hw)]  <->  internal w[o][(hw,c)]
+__global__ void fc_weight_permute_kernel(const float* __restrict__ src, float* __restrict__ dst, int out, int C,
+                                         int HW, int dir) {
+  const size_t total = (size_t)out * C * HW;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // internal index
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  size_t q = i / C;
+  const int hw = (int)(q % HW);
+  const size_t o = q / HW;
+  const size_t canon = (o * C + c) * HW + hw;
+  if (dir == 0)
+    dst[i] = src[canon];
+  else
+    dst[canon] = src[i];
+}
+int launch_fc_weight_permute(const float* src, float* dst, int out, int C, int HW, int dir, hipStream_t st) {
+  const size_t total = (size_t)out * C * HW;
+  hipLaunchKernelGGL(fc_weight_permute_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, src, dst, out, C, HW,
+                     dir);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+}  // namespace ax

@@ -1,0 +1,274 @@
+// CPU emulation of the workgroup program in csrc/gemm.h.
+//
+// Runs the real operand loaders, LDS stores, fragment index maps and epilogues
+// thread by thread on the host, with the MFMA replaced by its definition, and
+// checks the three convolution GEMMs against direct loops.  Built with
+// -fsanitize=address so that any out-of-range global or LDS access of a loader
+// aborts here, on the CPU, before the kernel ever runs on a GPU.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+struct float4 {
+  float x, y, z, w;
+};
+#define AX_HOST_EMU 1
+#include "../../paper_1412_2302_amd/csrc/conv_plan.h"
+
+using namespace ax;
+
+template <class T, class AL, class BL, class Epi>
+static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk,
+                     int nsplit, int groups) {
+  const int gx = (M + T::BM - 1) / T::BM, gy = (N + T::BN - 1) / T::BN, gz = groups * nsplit;
+  std::vector<float> As(T::BK * T::LDA), Bs(T::BK * T::LDB);
+  std::vector<float> acc((size_t)4 * T::TM * T::TN * 64 * 16);
+  auto ACC = [&](int wave, int i, int j, int lane, int r) -> float& {
+    return acc[((((size_t)wave * T::TM + i) * T::TN + j) * 64 + lane) * 16 + r];
+  };
+  for (int bz = 0; bz < gz; ++bz)
+    for (int by = 0; by < gy; ++by)
+      for (int bx = 0; bx < gx; ++bx) {
+        const int g = bz / nsplit, split = bz - g * nsplit;
+        const int m0 = bx * T::BM, n0 = by * T::BN;
+        const int kbeg = split * kchunk, kend = std::min(K, kbeg + kchunk);
+        const int nt = kend > kbeg ? (kend - kbeg + T::BK - 1) / T::BK : 0;
+        std::fill(acc.begin(), acc.end(), 0.f);
+        Epi e = ep;
+        e.set_group(g, bz);
+        for (int t = 0; t < nt; ++t) {
+          // poison LDS so that a slot nobody wrote shows up
+          std::fill(As.begin(), As.end(), NAN);
+          std::fill(Bs.begin(), Bs.end(), NAN);
+          for (int tid = 0; tid < kThreads; ++tid) {
+            AL al(ap, g, tid, m0);
+            BL bl(bp, g, tid, n0);
+            float4 ra[AL::NL], rb[BL::NL];
+            al.load(kbeg + t * T::BK, kend, ra);
+            bl.load(kbeg + t * T::BK, kend, rb);
+            al.store(As.data(), T::LDA, ra);
+            bl.store(Bs.data(), T::LDB, rb);
+          }
+          for (int wave = 0; wave < 4; ++wave) {
+            const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
+            for (int kk = 0; kk < T::BK / 2; ++kk) {
+              float a[64][T::TM], b[64][T::TN];
+              for (int lane = 0; lane < 64; ++lane) {
+                const int kr = frag_k(lane, kk);
+                for (int i = 0; i < T::TM; ++i) a[lane][i] = As[kr * T::LDA + wm * (T::TM * 32) + (lane & 31) + i * 32];
+                for (int j = 0; j < T::TN; ++j) b[lane][j] = Bs[kr * T::LDB + wn * (T::TN * 32) + (lane & 31) + j * 32];
+              }
+              // D[ii][jj] += sum_{k2<2} A[ii][k2] * B[k2][jj], lane k2*32+ii holds A[ii][k2], lane k2*32+jj holds B[k2][jj]
+              for (int i = 0; i < T::TM; ++i)
+                for (int j = 0; j < T::TN; ++j)
+                  for (int lane = 0; lane < 64; ++lane)
+                    for (int r = 0; r < 16; ++r) {
+                      const int ii = acc_row(lane, r), jj = lane & 31;
+                      float s = 0.f;
+                      for (int k2 = 0; k2 < 2; ++k2) s += a[k2 * 32 + ii][i] * b[k2 * 32 + jj][j];
+                      ACC(wave, i, j, lane, r) += s;
+                    }
+            }
+          }
+        }
+        for (int wave = 0; wave < 4; ++wave) {
+          const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
+          for (int lane = 0; lane < 64; ++lane)
+            for (int i = 0; i < T::TM; ++i)
+              for (int j = 0; j < T::TN; ++j) {
+                const int n = n0 + wn * (T::TN * 32) + j * 32 + (lane & 31);
+                if (n >= N) continue;
+                for (int r = 0; r < 16; ++r) {
+                  const int m = m0 + wm * (T::TM * 32) + i * 32 + acc_row(lane, r);
+                  if (m < M) e.apply(m, n, ACC(wave, i, j, lane, r));
+                }
+              }
+        }
+      }
+}
+
+static float frand() { return (float)rand() / RAND_MAX * 2.f - 1.f; }
+
+struct Case {
+  ConvGeom c;
+  const char* name;
+};
+
+static int failures = 0;
+static void check(const char* what, const char* name, const std::vector<float>& got, const std::vector<double>& want) {
+  double num = 0, den = 0;
+  bool nan = false;
+  for (size_t i = 0; i < want.size(); ++i) {
+    if (!(got[i] == got[i])) nan = true;
+    num += (got[i] - want[i]) * (got[i] - want[i]);
+    den += want[i] * want[i];
+  }
+  double rel = sqrt(num / (den > 0 ? den : 1));
+  bool ok = !nan && rel < 1e-5;
+  printf("%-10s %-28s rel_l2=%.3e %s\n", what, name, rel, ok ? "ok" : "FAIL");
+  if (!ok) ++failures;
+}
+
+template <class T>
+static void run_case(const Case& cs) {
+  const ConvGeom& c = cs.c;
+  const int cg = c.cg(), og = c.og(), k = c.k;
+  // exact-size heap buffers: the sanitizer flags any access past either end
+  float* x = new float[c.in_elems()];
+  float* dy = new float[c.out_elems()];
+  float* w = new float[c.w_elems()];  // canonical OIHW
+  float* wf = new float[c.w_elems()];
+  float* wb = new float[c.w_elems()];
+  float* bias = new float[c.Cout];
+  for (long i = 0; i < c.in_elems(); ++i) x[i] = frand();
+  for (long i = 0; i < c.out_elems(); ++i) dy[i] = frand();
+  for (long i = 0; i < c.w_elems(); ++i) w[i] = frand();
+  for (int i = 0; i < c.Cout; ++i) bias[i] = frand();
+  for (int o = 0; o < c.Cout; ++o)
+    for (int ci = 0; ci < cg; ++ci)
+      for (int r = 0; r < k; ++r)
+        for (int s = 0; s < k; ++s) {
+          const int g = o / og, ol = o % og;
+          const float v = w[((o * cg + ci) * k + r) * k + s];
+          wf[((long)g * c.kf() + (r * k + s) * cg + ci) * og + ol] = v;
+          wb[((long)g * c.kb() + (r * k + s) * og + ol) * cg + ci] = v;
+        }
+  auto X = [&](int n, int iy, int ix, int ch) -> double {
+    if (iy < 0 || iy >= c.H || ix < 0 || ix >= c.W) return 0.0;
+    return x[(((long)n * c.H + iy) * c.W + ix) * c.Cin + ch];
+  };
+  // ---- direct references (channel-last) ----
+  std::vector<double> y_ref(c.out_elems()), dx_ref(c.in_elems(), 0.0), dwf_ref(c.w_elems(), 0.0);
+  for (int n = 0; n < c.B; ++n)
+    for (int yy = 0; yy < c.Ho; ++yy)
+      for (int xx = 0; xx < c.Wo; ++xx)
+        for (int o = 0; o < c.Cout; ++o) {
+          const int g = o / og, ol = o % og;
+          double a = bias[o];
+          const double d = dy[(((long)n * c.Ho + yy) * c.Wo + xx) * c.Cout + o];
+          for (int ci = 0; ci < cg; ++ci)
+            for (int r = 0; r < k; ++r)
+              for (int s = 0; s < k; ++s) {
+                const int iy = yy * c.stride - c.pad + r, ix = xx * c.stride - c.pad + s;
+                const double wv = w[((o * cg + ci) * k + r) * k + s];
+                const double xv = X(n, iy, ix, g * cg + ci);
+                a += wv * xv;
+                dwf_ref[((long)g * c.kf() + (r * k + s) * cg + ci) * og + ol] += d * xv;
+                if (iy >= 0 && iy < c.H && ix >= 0 && ix < c.W)
+                  dx_ref[(((long)n * c.H + iy) * c.W + ix) * c.Cin + g * cg + ci] += d * wv;
+              }
+          y_ref[(((long)n * c.Ho + yy) * c.Wo + xx) * c.Cout + o] = a > 0 ? a : 0;
+        }
+  char nm[128];
+  snprintf(nm, sizeof nm, "%s/%dx%d", cs.name, T::BM, T::BN);
+  // ---- forward ----
+  {
+    std::vector<float> y(c.out_elems(), NAN);
+    GemmDims d = fwd_dims(c);
+    EpiBiasAct e{y.data(), c.Cout, bias, 1, og, 0};
+    emu_gemm<T, Im2colKInner<T::BM, T::BK>, DenseRowInner<T::BN, T::BK>, EpiBiasAct>(
+        fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
+    check("fwd", nm, y, y_ref);
+  }
+  // ---- backward data ----
+  {
+    std::vector<float> dx(c.in_elems(), NAN);
+    GemmDims d = bwdd_dims(c);
+    EpiGate e{dx.data(), c.Cin, nullptr, cg, 0};
+    emu_gemm<T, Im2colKInner<T::BM, T::BK>, DenseRowInner<T::BN, T::BK>, EpiGate>(
+        bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
+    check("bwd_data", nm, dx, dx_ref);
+  }
+  // ---- backward weight with split-k ----
+  {
+    GemmDims d = bwdw_dims(c);
+    int kchunk;
+    long tiles = (long)((d.M + T::BM - 1) / T::BM) * ((d.N + T::BN - 1) / T::BN) * d.groups;
+    int nsplit = plan_split(tiles, d.K, T::BK, 7, 5, &kchunk);
+    std::vector<float> ws((size_t)d.groups * nsplit * d.M * d.N, NAN);
+    EpiSlab e{ws.data(), (long)d.M * d.N, d.N, nullptr};
+    emu_gemm<T, Im2colRowInner<T::BM, T::BK>, DenseRowInner<T::BN, T::BK>, EpiSlab>(
+        bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
+    std::vector<float> dwf(c.w_elems(), 0.f);
+    for (int g = 0; g < d.groups; ++g)
+      for (int sp = 0; sp < nsplit; ++sp)
+        for (long i = 0; i < (long)d.M * d.N; ++i) dwf[(long)g * d.M * d.N + i] += ws[((long)g * nsplit + sp) * d.M * d.N + i];
+    snprintf(nm, sizeof nm, "%s/%dx%d/s%d", cs.name, T::BM, T::BN, nsplit);
+    check("bwd_wgt", nm, dwf, dwf_ref);
+  }
+  delete[] x; delete[] dy; delete[] w; delete[] wf; delete[] wb; delete[] bias;
+}
+
+static ConvGeom geom(int B, int H, int Cin, int Cout, int k, int st, int pad, int groups) {
+  ConvGeom c;
+  c.B = B; c.H = H; c.W = H + 1; c.Cin = Cin; c.Cout = Cout; c.k = k; c.stride = st; c.pad = pad; c.groups = groups;
+  c.Ho = (c.H + 2 * pad - k) / st + 1;
+  c.Wo = (c.W + 2 * pad - k) / st + 1;
+  return c;
+}
+
+template <int ROWS, int BK>
+static void dense_case() {
+  // fully connected layer shapes with ragged and non-multiple-of-4 extents
+  const int Bn = 6, In = 20, Out = 10;
+  float* x = new float[Bn * In];
+  float* w = new float[Out * In];
+  float* dy = new float[Bn * Out];
+  for (int i = 0; i < Bn * In; ++i) x[i] = frand();
+  for (int i = 0; i < Out * In; ++i) w[i] = frand();
+  for (int i = 0; i < Bn * Out; ++i) dy[i] = frand();
+  typedef Tile<128, 128, 16, 2, 2> T;
+  {  // y = x w^T : both operands contiguous along k
+    std::vector<float> y(Bn * Out, NAN);
+    std::vector<double> ref(Bn * Out, 0.0);
+    for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * Out + o] += (double)x[n * In + i] * w[o * In + i];
+    DenseParams a{x, In, 0, Bn, 1}, b{w, In, 0, Out, 1};
+    EpiSlab e{y.data(), (long)Bn * Out, Out, nullptr};
+    emu_gemm<T, DenseKInner<128, 16>, DenseKInner<128, 16>, EpiSlab>(a, b, e, Bn, Out, In, 32, 1, 1);
+    check("fc_fwd", "6x20->10", y, ref);
+  }
+  {  // dx = dy w : A contiguous along k (=Out, not a multiple of 4 -> scalar), B along rows
+    std::vector<float> dx(Bn * In, NAN);
+    std::vector<double> ref(Bn * In, 0.0);
+    for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * In + i] += (double)dy[n * Out + o] * w[o * In + i];
+    DenseParams a{dy, Out, 0, Bn, 0}, b{w, In, 0, In, 1};
+    EpiSlab e{dx.data(), (long)Bn * In, In, nullptr};
+    emu_gemm<T, DenseKInner<128, 16>, DenseRowInner<128, 16>, EpiSlab>(a, b, e, Bn, In, Out, 16, 1, 1);
+    check("fc_bwd_x", "6x20->10", dx, ref);
+  }
+  {  // dw = dy^T x : both contiguous along rows; A scalar path
+    std::vector<float> dw(Out * In, NAN);
+    std::vector<double> ref(Out * In, 0.0);
+    for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[o * In + i] += (double)dy[n * Out + o] * x[n * In + i];
+    DenseParams a{dy, Out, 0, Out, 0}, b{x, In, 0, In, 1};
+    EpiSlab e{dw.data(), (long)Out * In, In, nullptr};
+    emu_gemm<T, DenseRowInner<128, 16>, DenseRowInner<128, 16>, EpiSlab>(a, b, e, Out, In, Bn, 16, 1, 1);
+    check("fc_bwd_w", "6x20->10", dw, ref);
+  }
+  delete[] x; delete[] w; delete[] dy;
+}
+
+int main() {
+  srand(1234);
+  std::vector<Case> cases = {
+      {geom(2, 23, 3, 8, 11, 4, 0, 1), "k11s4c3"},      // scalar gather, stride 4
+      {geom(3, 13, 3, 16, 7, 2, 0, 1), "k7s2c3"},       // mini conv1
+      {geom(2, 7, 8, 40, 5, 1, 2, 2), "k5p2g2"},        // grouped, padded
+      {geom(3, 6, 24, 36, 3, 1, 1, 1), "k3p1"},
+      {geom(2, 6, 72, 72, 3, 1, 1, 2), "k3p1g2c36"},
+      {geom(1, 9, 12, 20, 3, 2, 1, 2), "k3s2p1g2"},      // strided transposed gather with groups
+      {geom(5, 5, 132, 136, 3, 1, 1, 1), "k3wide"},      // more than one tile along N and K rows
+  };
+  for (const Case& cs : cases) {
+    run_case<Tile<128, 128, 16, 2, 2>>(cs);
+    run_case<Tile<128, 96, 16, 4, 1>>(cs);
+    run_case<Tile<128, 64, 16, 4, 1>>(cs);
+  }
+  dense_case<128, 16>();
+  printf(failures ? "FAILED %d\n" : "ALL OK\n", failures);
+  return failures ? 1 : 0;
+}

@@ -1,0 +1,215 @@
+"""GPU parity: every call goes through the C ABI and is compared with the
+float64 oracle on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as S
+from gpu_common import LOSS_RTOL, TENSOR_RTOL, build_pair, cuda
+from helpers import oracle_spec, rel_l2, to64
+from oracle import alexnet_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def stage_io_shapes(spec):
+    stages, _ = O.layer_shapes(spec)
+    return stages
+
+
+# ------------------------------------------------------------ layouts -------
+def test_layout_roundtrip_is_bit_exact(lib):
+    x = S.make_normal((3, 5, 7, 6), 1)
+    y = lib.nchw_to_nhwc(cuda(x))
+    assert np.array_equal(y.cpu().numpy(), np.transpose(x, (0, 2, 3, 1)))
+    assert np.array_equal(lib.nhwc_to_nchw(y).cpu().numpy(), x)
+
+
+def test_param_roundtrip_is_bit_exact(lib):
+    net, spec, p64, _ = build_pair(lib, S.MIDI, 2, seed=3, bias=0.25, mom_std=0.1)
+    got = net.get_params()
+    for k in p64:
+        assert np.array_equal(got[k].astype(np.float64), p64[k]), k
+    mom = net.get_momentum()
+    assert all(np.abs(v).sum() > 0 for v in mom.values())
+
+
+# ---------------------------------------------------- single conv layers ----
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5)])
+def test_conv_layers_alone(lib, wl, batch):
+    net = lib.AlexNet(wl, batch)
+    spec = oracle_spec(wl, batch)
+    for li, (cv, st) in enumerate(zip(spec.conv, stage_io_shapes(spec)), start=1):
+        cin, h, w = st["in"]
+        cout, ho, wo = st["conv"]
+        x = S.make_normal((batch, cin, h, w), 10 + li)
+        wt = S.make_normal((cout, cin // cv.groups, cv.k, cv.k), 20 + li, std=0.05)
+        b = S.make_normal((cout,), 30 + li)
+        dy = S.make_normal((batch, cout, ho, wo), 40 + li)
+        y = net.conv_forward(li, x, wt, b, relu=False).cpu().numpy().reshape(batch, cout, ho, wo)
+        y_ref = O.conv_forward(x, wt, b, cv.stride, cv.pad, cv.groups)
+        assert rel_l2(y, y_ref) <= TENSOR_RTOL, (li, rel_l2(y, y_ref))
+        yr = net.conv_forward(li, x, wt, b, relu=True).cpu().numpy().reshape(y_ref.shape)
+        assert rel_l2(yr, np.maximum(y_ref, 0)) <= TENSOR_RTOL
+        dx = net.conv_backward_data(li, dy, wt, x.shape).cpu().numpy()
+        dx_ref = O.conv_backward_data(dy, wt, (h, w), cv.stride, cv.pad, cv.groups)
+        assert rel_l2(dx, dx_ref) <= TENSOR_RTOL, (li, rel_l2(dx, dx_ref))
+        dw, db = net.conv_backward_weight(li, x, dy, wt.shape)
+        dw_ref, db_ref = O.conv_backward_weight(x, dy, cv.k, cv.stride, cv.pad, cv.groups)
+        assert rel_l2(dw.cpu().numpy(), dw_ref) <= TENSOR_RTOL, (li, rel_l2(dw.cpu().numpy(), dw_ref))
+        assert rel_l2(db.cpu().numpy(), db_ref) <= TENSOR_RTOL
+    net.close()
+
+
+# --------------------------------------------------------- preprocess -------
+def test_preprocess_crop_flip_exact(lib):
+    batch = 9
+    net, spec, _, _ = build_pair(lib, S.MIDI, batch, seed=77)
+    raw, _ = S.make_raw_batch(batch, 3, 80, 80, 37, 5)
+    mean = S.make_mean_image(3, 80, 80, 6)
+    for step, slot in [(0, 0), (5, 1), (123456789012, 0)]:
+        net.preprocess(cuda(raw), cuda(mean), step, slot)
+        ox, oy, fl = O.crop_flip_params(spec, step)
+        assert np.array_equal(net.tensor(lib.T_CROP_X, slot), ox)
+        assert np.array_equal(net.tensor(lib.T_CROP_Y, slot), oy)
+        assert np.array_equal(net.tensor(lib.T_FLIP, slot), fl)
+        want = O.preprocess(raw, mean, ox, oy, fl, 67, 67).astype(np.float32)  # exact in f64, one rounding
+        got = net.tensor(lib.T_INPUT, slot).reshape(want.shape)
+        assert np.array_equal(got, want)
+    assert len(set(ox.tolist())) > 1 and set(fl.tolist()) == {0, 1}
+    net.close()
+
+
+# ------------------------------------------------------- whole step ---------
+def _run_step_and_compare(lib, wl, batch, seed, bias, std, use_raw, steps=1, mom_std=0.0, classes=None):
+    net, spec, p64, m64 = build_pair(lib, wl, batch, seed=seed, bias=bias, std=std, mom_std=mom_std)
+    classes = wl["fc"][-1]
+    for step in range(steps):
+        if use_raw:
+            raw, labels = S.make_raw_batch(batch, wl["in_c"], wl["raw"], wl["raw"], classes, S.SEED_BASE + 100 + step)
+            mean = S.make_mean_image(wl["in_c"], wl["raw"], wl["raw"], S.SEED_BASE + 7)
+            net.preprocess(cuda(raw), cuda(mean), step, step % 2)
+            ox, oy, fl = O.crop_flip_params(spec, step)
+            # scale pixels down so activations stay O(1) with the larger test weights
+            x64 = O.preprocess(raw, mean, ox, oy, fl, wl["crop"], wl["crop"])
+        else:
+            x32, labels = S.make_float_batch(batch, wl["in_c"], wl["crop"], wl["crop"], classes, S.SEED_BASE + 1 + step)
+            net.set_input(cuda(x32), step % 2)
+            x64 = x32.astype(np.float64)
+        loss = net.train_step(cuda(labels), step, slot=step % 2)
+        net.check()
+        loss_ref, p_new, m_new, g_ref, cache = O.train_step(spec, p64, m64, x64, labels, step)
+        got_loss = float(loss.cpu().item())
+        assert abs(got_loss - loss_ref) <= LOSS_RTOL * abs(loss_ref), (step, got_loss, loss_ref)
+
+        # forward intermediates
+        for i, cv in enumerate(spec.conv, start=1):
+            a = net.tensor(lib.T_CONV_ACT, i).reshape(cache[f"conv{i}.act"].shape)
+            assert rel_l2(a, cache[f"conv{i}.act"]) <= TENSOR_RTOL, ("act", i)
+            if cv.lrn:
+                l = net.tensor(lib.T_LRN, i).reshape(a.shape)
+                assert rel_l2(l, cache[f"conv{i}.lrn"]) <= TENSOR_RTOL, ("lrn", i)
+            if cv.pool:
+                pool_in = net.tensor(lib.T_LRN if cv.lrn else lib.T_CONV_ACT, i).reshape(a.shape)
+                pv = net.tensor(lib.T_POOL, i)
+                am = net.tensor(lib.T_ARGMAX, i)
+                # bit-exact per kernel: the oracle pools the GPU's own fp32 input
+                want_v, want_a = O.maxpool_forward(pool_in, 3, 2)
+                assert np.array_equal(pv.reshape(want_v.shape), want_v), ("pool", i)
+                assert np.array_equal(am.reshape(want_a.shape), want_a), ("argmax", i)
+                assert rel_l2(pv.reshape(want_v.shape), cache[f"conv{i}.pool"]) <= TENSOR_RTOL
+        for j, tag in ((6, O.TAG_DROP6), (7, O.TAG_DROP7)):
+            a = net.tensor(lib.T_FC_ACT, j).reshape(batch, -1)
+            mask = cache["masks"][j - 6]
+            assert np.all(a[mask == 0] == 0), "dropout mask must match the generator bit for bit"
+            assert rel_l2(a, cache[f"fc{j}.act"]) <= TENSOR_RTOL, ("fc act", j)
+        assert rel_l2(net.tensor(lib.T_FC_ACT, 8).reshape(batch, -1), cache["logits"]) <= TENSOR_RTOL
+
+        g = net.get_grads()
+        pn = net.get_params()
+        mn = net.get_momentum()
+        for k in g_ref:
+            assert np.linalg.norm(g_ref[k]) > 0, k
+            assert rel_l2(g[k], g_ref[k]) <= TENSOR_RTOL, ("grad", k, rel_l2(g[k], g_ref[k]))
+            assert rel_l2(pn[k], p_new[k]) <= TENSOR_RTOL, ("param", k)
+            assert rel_l2(mn[k], m_new[k]) <= TENSOR_RTOL, ("momentum", k, rel_l2(mn[k], m_new[k]))
+        # continue from the library's own fp32 state so that errors do not pile up across steps
+        p64, m64 = to64(pn), to64(mn)
+    net.close()
+    return got_loss
+
+
+def test_mini_alexnet_step_batch4(lib):
+    """Workload 1: mini-AlexNet, one SGD step, batch 4, weights N(0, 0.01^2), zero biases."""
+    loss = _run_step_and_compare(lib, S.MINI, 4, seed=11, bias=0.0, std=0.01, use_raw=False)
+    assert abs(loss - math.log(10)) < 1e-2
+
+
+def test_mini_alexnet_three_steps_with_signal_everywhere(lib):
+    _run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01)
+
+
+def test_midi_net_with_preprocess_ragged_tiles(lib):
+    # raw uint8 pixels are O(100); small conv1 weights keep the activations moderate
+    _run_step_and_compare(lib, S.MIDI, 7, seed=13, bias=0.05, std=0.02, use_raw=True, steps=2, mom_std=0.01)
+
+
+def test_inference_forward(lib):
+    batch = 5
+    net, spec, p64, _ = build_pair(lib, S.MIDI, batch, seed=3, bias=0.1, std=0.05)
+    x, _ = S.make_float_batch(batch, 3, 67, 67, 37, 99)
+    p = net.forward(cuda(x)).cpu().numpy()
+    want = O.forward(spec, p64, x.astype(np.float64))
+    np.testing.assert_allclose(p.sum(1), 1.0, rtol=1e-5)
+    assert rel_l2(p, want) <= TENSOR_RTOL
+    net.close()
+
+
+# --------------------------------------------------- two replicas (2.2) -----
+def test_average_replicas_bit_identical_and_correct(lib):
+    batch = 4
+    a, spec, p64, m64 = build_pair(lib, S.MINI, batch, seed=1, bias=0.1, std=0.08, mom_std=0.01)
+    b, _, _, _ = build_pair(lib, S.MINI, batch, seed=2, bias=0.1, std=0.08, mom_std=0.01)
+    # identical replicas stay identical and unchanged
+    lib.average_replicas(a, b)
+    pa, pb = a.get_params(), b.get_params()
+    for k in pa:
+        assert np.array_equal(pa[k], pb[k]) and np.array_equal(pa[k].astype(np.float64), p64[k]), k
+    # one step on different minibatches, then exchange-and-average
+    xa, la = S.make_float_batch(batch, 3, 63, 63, 10, 100)
+    xb, lb = S.make_float_batch(batch, 3, 63, 63, 10, 200)
+    a.set_input(cuda(xa), 0); b.set_input(cuda(xb), 0)
+    a.train_step(cuda(la), 0); b.train_step(cuda(lb), 0)
+    pa0, pb0, ma0, mb0 = a.get_params(), b.get_params(), a.get_momentum(), b.get_momentum()
+    assert any(not np.array_equal(pa0[k], pb0[k]) for k in pa0)
+    lib.average_replicas(a, b)
+    pa, pb, ma, mb = a.get_params(), b.get_params(), a.get_momentum(), b.get_momentum()
+    for k in pa:
+        assert np.array_equal(pa[k], pb[k]) and np.array_equal(ma[k], mb[k]), k
+        # 0.5*(x+y) in fp32 is one rounding of the exact mean
+        assert np.array_equal(pa[k], (0.5 * (pa0[k].astype(np.float64) + pb0[k])).astype(np.float32).astype(np.float64).astype(np.float32)) or \
+            rel_l2(pa[k], O.average_replicas(pa0[k], pb0[k])) <= 1e-7, k
+        assert rel_l2(ma[k], O.average_replicas(ma0[k], mb0[k])) <= 1e-7, k
+    # 2 x batch + average == one step on the concatenated batch (Section 3)
+    specA = oracle_spec(S.MINI, batch, seed=1); specB = oracle_spec(S.MINI, batch, seed=2)
+    masks = [np.concatenate([O.dropout_mask(specA, 0, t, 256), O.dropout_mask(specB, 0, t, 256)]) for t in (O.TAG_DROP6, O.TAG_DROP7)]
+    spec2 = oracle_spec(S.MINI, 2 * batch)
+    _, p2, m2, _, _ = O.train_step(spec2, p64, m64, np.concatenate([xa, xb]).astype(np.float64), np.concatenate([la, lb]), 0, masks=masks)
+    for k in pa:
+        assert rel_l2(pa[k], p2[k]) <= TENSOR_RTOL and rel_l2(ma[k], m2[k]) <= TENSOR_RTOL, k
+    a.close(); b.close()
+
+
+def test_out_of_range_label_is_reported(lib):
+    net, spec, _, _ = build_pair(lib, S.MINI, 4, seed=1)
+    x, labels = S.make_float_batch(4, 3, 63, 63, 10, 1)
+    net.set_input(cuda(x), 0)
+    labels[2] = 10
+    net.forward_backward(cuda(labels), 0)
+    with pytest.raises(lib.AlexNetError) as e:
+        net.check()
+    assert e.value.code == lib.ELABEL
+    net.check()  # flag is cleared once reported
+    net.close()
