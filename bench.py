@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Throughput of one AlexNet SGD training step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 128] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path over one synthetic minibatch whose
+stored uint8 pictures are already resident in HBM: on-device preprocessing
+(mean subtract, random crop, flip) of minibatch k+1 on a side stream,
+overlapped with forward + backward + momentum update of minibatch k on the
+compute stream.  Prints ONE JSON line: images/s, the MFMA roofline of the
+dominant kernel (measured with HIP events on the stream the kernels run on) and
+the float64 oracle timed on the host cores of the same machine.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(sample_batch: int):
+    """The float64 oracle, as it stands, on the host cores: one full training
+    step (preprocess + forward + backward + update) on `sample_batch` pictures."""
+    import numpy as np
+    import synthetic_inputs as S
+    from helpers import oracle_spec, to64
+    from oracle import alexnet_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    spec = oracle_spec(S.ALEXNET, sample_batch, seed=S.SEED_BASE + 3)
+    params = to64(S.make_params(O.param_shapes(spec), S.SEED_BASE + 3))
+    mom = {k: np.zeros_like(v) for k, v in params.items()}
+    raw, labels = S.make_raw_batch(sample_batch, 3, 256, 256, 1000, S.SEED_BASE + 3)
+    mean = S.make_mean_image(3, 256, 256, S.SEED_BASE + 7)
+    t0 = time.perf_counter()
+    ox, oy, fl = O.crop_flip_params(spec, 0)
+    x = O.preprocess(raw, mean, ox, oy, fl, 227, 227)
+    O.train_step(spec, params, mom, x, labels, 0)
+    dt = time.perf_counter() - t0
+    return {"value": sample_batch / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
+            "sample": f"one float64 numpy training step (preprocess+fwd+bwd+update) on {sample_batch} images, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=128)
+    ap.add_argument("--cpu-sample", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="run preprocessing on the compute stream")
+    ap.add_argument("--kernel-table", action="store_true", help="also print the per-kernel table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (two replicas share one GPU in its "
+              "data-parallel test); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synthetic_inputs as S
+    from paper_1412_2302_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU path", file=sys.stderr)
+        sys.exit(1)
+
+    wl, batch = S.ALEXNET, args.batch
+    net = B.AlexNet(wl, batch, seed=S.SEED_BASE + 3)
+    net.set_params(S.make_params(net.shapes, S.SEED_BASE + 3))
+    # a small pool of distinct minibatches resident in HBM, cycled through
+    pool = 4
+    raws, labels = [], []
+    for i in range(pool):
+        r, l = S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 3 + i)
+        raws.append(torch.from_numpy(r).cuda())
+        labels.append(torch.from_numpy(l).cuda())
+    mean = torch.from_numpy(S.make_mean_image(3, 256, 256, S.SEED_BASE + 7)).cuda()
+
+    compute = torch.cuda.Stream()
+    side = compute if args.no_overlap else torch.cuda.Stream()
+    ready = [torch.cuda.Event(), torch.cuda.Event()]   # slot s holds a preprocessed batch
+    freed = [torch.cuda.Event(), torch.cuda.Event()]   # the step reading slot s has finished
+    torch.cuda.synchronize()
+
+    def run(nsteps: int, first_step: int):
+        """Enqueues nsteps pipelined steps; slot (k % 2) holds minibatch k."""
+        with torch.cuda.stream(side):
+            net.preprocess(raws[first_step % pool], mean, first_step, first_step % 2, stream=side)
+            ready[first_step % 2].record(side)
+        for k in range(first_step, first_step + nsteps):
+            s = k % 2
+            if k + 1 < first_step + nsteps:
+                if k > first_step:  # the step that read slot 1-s must be done before it is overwritten
+                    side.wait_event(freed[1 - s])
+                net.preprocess(raws[(k + 1) % pool], mean, k + 1, 1 - s, stream=side)
+                ready[1 - s].record(side)
+            compute.wait_event(ready[s])
+            net.train_step(labels[k % pool], k, slot=s, stream=compute)
+            freed[s].record(compute)
+
+    run(args.warmup, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    net.check(stream=compute)
+    loss = float(net.loss.cpu().item())
+    ms_per_step = dt / args.steps * 1e3
+    value = batch * args.steps / dt
+
+    # ---- per-kernel durations with HIP events on the launch streams (same work, second pass) ----
+    prof_steps = min(args.steps, 10)
+    B.profile_begin()
+    run(prof_steps, args.warmup + args.steps)
+    torch.cuda.synchronize()
+    entries = B.profile_end()
+    gemm = [e for e in entries if e["name"].endswith(":gemm")]
+    other = [e for e in entries if not e["name"].endswith(":gemm")]
+    gemm_ms = sum(e["total_ms"] for e in gemm)
+    gemm_calls = sum(e["calls"] for e in gemm)
+    gemm_flops = sum(e["flops"] for e in gemm)
+    all_ms = sum(e["total_ms"] for e in entries)
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    roofline = {
+        "kernel": "ax::gemm_kernel (fp32 MFMA implicit-GEMM: conv fwd/bwd-data/bwd-weight and dense layers)",
+        "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
+        "launches_per_step": gemm_calls // prof_steps,
+        "flops_per_launch": gemm_flops / max(gemm_calls, 1),
+        "avg_launch_ms": gemm_ms / max(gemm_calls, 1),
+        "share_of_kernel_time": round(gemm_ms / all_ms, 4) if all_ms > 0 else None,
+    }
+    table = []
+    for e in sorted(entries, key=lambda e: -e["total_ms"]):
+        ms = e["total_ms"] / e["calls"]
+        row = {"name": e["name"], "calls_per_step": e["calls"] / prof_steps, "avg_ms": round(ms, 4)}
+        if e["flops"] > 0:
+            row["tflops"] = round(e["flops"] / e["calls"] / (ms * 1e-3) / 1e12, 2)
+        if e["bytes"] > 0:
+            row["gbs"] = round(e["bytes"] / e["calls"] / (ms * 1e-3) / 1e9, 1)
+        table.append(row)
+    if args.kernel_table:
+        for row in table:
+            print(json.dumps(row), file=sys.stderr)
+    bw = [e for e in other if e["bytes"] > 0]
+    bw_ms = sum(e["total_ms"] for e in bw)
+    hbm = {"achieved": round(sum(e["bytes"] for e in bw) / (bw_ms * 1e-3) / 1e9, 1) if bw_ms > 0 else None,
+           "peak": PEAK_HBM_GBS, "unit": "GB/s", "ms_per_step": round(bw_ms / prof_steps, 4),
+           "note": "all bandwidth-bound kernels together (LRN, pool, update, reductions, preprocess)"}
+
+    out = {
+        "metric": "AlexNet train images/sec at batch 128 on 1 MI355X; conv MFMA utilisation %",
+        "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"full AlexNet training step, fp32, batch {batch}: uint8 3x256x256 pictures in HBM, "
+                               "on-device mean-subtract/crop/flip on a side stream, conv1-5 + LRN + pools + fc6-8 "
+                               "with dropout, softmax cross-entropy, momentum/weight-decay update",
+                   "batch": batch, "overlap_preprocess": not args.no_overlap, "final_loss": round(loss, 5)},
+        "mfma_utilisation_pct": round(100 * achieved / PEAK_FP32_MFMA_TFLOPS, 2),
+        "step_flops": 4.136e9 * batch,
+        "step_mfma_frac": round(4.136e9 * batch / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+        "roofline": roofline,
+        "hbm_kernels": hbm,
+        "kernels": table[:12],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -190,6 +190,24 @@ int alexnet_conv_backward_data_nhwc(alexnet_t* net, int32_t layer, const float* 
 int alexnet_conv_backward_weight_nhwc(alexnet_t* net, int32_t layer, const float* d_x, const float* d_dy,
                                       float* d_dw_fwd, float* d_db, void* stream);
 
+/* --- per-kernel timing (measurement aid; not part of the training path) ---
+ * Between alexnet_profile_begin and alexnet_profile_end every kernel the
+ * calling thread launches through this library is bracketed by two HIP events
+ * on the stream it is launched on.  alexnet_profile_end waits for those
+ * events, writes up to `cap` entries (one per distinct kernel and layer) to
+ * the HOST array `out` and the number of distinct entries to *n.  flops and
+ * bytes are the algorithmic work summed over the calls (2*M*N*K per GEMM;
+ * each tensor read or written once for the bandwidth-bound kernels). */
+typedef struct {
+  char name[48];     /* e.g. "conv2.fwd:gemm", "conv1:lrn_fwd", "sgd_update" */
+  int32_t calls;
+  float total_ms;
+  double flops;
+  double bytes;
+} alexnet_prof_entry_t;
+int alexnet_profile_begin(void);
+int alexnet_profile_end(alexnet_prof_entry_t* out, int32_t cap, int32_t* n);
+
 const char* alexnet_last_error(void);
 /* Library version string, e.g. "alexnet-hip gfx950 fp32". Host-only. */
 const char* alexnet_version(void);

@@ -71,6 +71,15 @@ _SIGS = {
     "alexnet_conv_backward_data_nhwc": [_vp, _i32, _vp, _vp, _vp, _vp],
     "alexnet_conv_backward_weight_nhwc": [_vp, _i32, _vp, _vp, _vp, _vp, _vp],
 }
+
+
+class ProfEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("calls", C.c_int32), ("total_ms", C.c_float),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+_SIGS["alexnet_profile_begin"] = []
+_SIGS["alexnet_profile_end"] = [C.POINTER(ProfEntry), _i32, C.POINTER(_i32)]
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
     _f.argtypes = _args
@@ -94,6 +103,19 @@ def last_error() -> str:
 
 def version() -> str:
     return _lib.alexnet_version().decode()
+
+
+def profile_begin():
+    _check(_lib.alexnet_profile_begin())
+
+
+def profile_end(cap: int = 256):
+    """Returns [{name, calls, total_ms, flops, bytes}] for the kernels launched since profile_begin."""
+    buf = (ProfEntry * cap)()
+    n = _i32()
+    _check(_lib.alexnet_profile_end(buf, cap, C.byref(n)))
+    return [dict(name=buf[i].name.decode(), calls=buf[i].calls, total_ms=buf[i].total_ms, flops=buf[i].flops,
+                 bytes=buf[i].bytes) for i in range(min(n.value, cap))]
 
 
 def _check(rc: int):

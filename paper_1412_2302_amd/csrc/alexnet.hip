@@ -5,6 +5,8 @@
 
 #include <algorithm>
 #include <new>
+#include <string>
+#include <utility>
 #include <vector>
 
 #include "kernels.h"
@@ -20,6 +22,53 @@ void set_error(const char* fmt, ...) {
 }
 const char* get_error() { return g_err; }
 
+thread_local ProfSink* g_prof = nullptr;
+thread_local const char* g_prof_ctx = "";
+
+// Accumulates (event pair, work) per kernel name; elapsed times are read in finish().
+struct Profiler : ProfSink {
+  struct Entry {
+    std::string name;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
+    double flops = 0, bytes = 0;
+  };
+  std::vector<Entry> entries;
+  Entry* cur = nullptr;
+  bool failed = false;
+  void begin(const char* kernel, double flops, double bytes, hipStream_t st) override {
+    std::string nm = std::string(g_prof_ctx) + (g_prof_ctx[0] ? ":" : "") + kernel;
+    cur = nullptr;
+    for (auto& e : entries)
+      if (e.name == nm) cur = &e;
+    if (!cur) {
+      entries.emplace_back();
+      cur = &entries.back();
+      cur->name = nm;
+    }
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess || hipEventRecord(a, st) != hipSuccess) {
+      failed = true;
+      cur = nullptr;
+      return;
+    }
+    cur->ev.emplace_back(a, b);
+    cur->flops += flops;
+    cur->bytes += bytes;
+  }
+  void end(hipStream_t st) override {
+    if (cur && hipEventRecord(cur->ev.back().second, st) != hipSuccess) failed = true;
+    cur = nullptr;
+  }
+  ~Profiler() override {
+    for (auto& e : entries)
+      for (auto& p : e.ev) {
+        (void)hipEventDestroy(p.first);
+        (void)hipEventDestroy(p.second);
+      }
+  }
+};
+static thread_local Profiler* g_profiler = nullptr;
+
 static const int kStages = 5, kFc = 3, kSlots = 3;  // slot 2 is the inference input
 
 struct Stage {
@@ -29,6 +78,7 @@ struct Stage {
   size_t w_off, b_off;  // offsets into the flat parameter vector
   float *act, *lrn_out, *pool_out, *dact, *d_lrn, *d_out, *wb;
   uint8_t* slot;
+  char lab[4][16];  // profiling labels: stage, .fwd, .bwd_w, .bwd_x
   long act_elems() const { return g.out_elems(); }
   long out_elems() const { return (long)g.B * Hp * Wp * g.Cout; }
   const float* out() const { return pool ? pool_out : lrn ? lrn_out : act; }
@@ -38,6 +88,7 @@ struct Dense {
   int in, out;
   size_t w_off, b_off;
   float *act, *dz;
+  char lab[4][16];
 };
 
 // Bump allocator over the caller's workspace; with base == null it only sizes.
@@ -119,6 +170,10 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
       set_error("conv%d: tensor too large for 32-bit pixel indices", i + 1);
       return ALEXNET_ESHAPE;
     }
+    snprintf(s.lab[0], 16, "conv%d", i + 1);
+    snprintf(s.lab[1], 16, "conv%d.fwd", i + 1);
+    snprintf(s.lab[2], 16, "conv%d.bwd_w", i + 1);
+    snprintf(s.lab[3], 16, "conv%d.bwd_x", i + 1);
     s.w_off = off;
     off += (size_t)s.g.w_elems();
     C = cv.cout; H = s.Hp; W = s.Wp;
@@ -131,6 +186,10 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
       return ALEXNET_ESHAPE;
     }
     n->fc[j].in = in; n->fc[j].out = c.fc[j];
+    snprintf(n->fc[j].lab[0], 16, "fc%d", kStages + 1 + j);
+    snprintf(n->fc[j].lab[1], 16, "fc%d.fwd", kStages + 1 + j);
+    snprintf(n->fc[j].lab[2], 16, "fc%d.bwd_w", kStages + 1 + j);
+    snprintf(n->fc[j].lab[3], 16, "fc%d.bwd_x", kStages + 1 + j);
     n->fc[j].w_off = off;
     off += (size_t)in * c.fc[j];
     in = c.fc[j];
@@ -207,7 +266,11 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
   const float* h = in;
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
-    AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, st));
+    {
+      ProfContext pc(s.lab[1]);
+      AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, st));
+    }
+    ProfContext pc(s.lab[0]);
     h = s.act;
     if (s.lrn) {
       AX_TRY(launch_lrn_fwd(s.act, s.lrn_out, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k, c.lrn_alpha, c.lrn_beta, st));
@@ -230,6 +293,7 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
     act.tag = j == 0 ? TAG_DROP6 : TAG_DROP7;
     act.thresh24 = drop_thresh(c.dropout_p);
     act.scale = (hidden && !train) ? 1.0f - c.dropout_p : 1.0f;
+    ProfContext pc(f.lab[1]);
     AX_TRY(launch_fc_fwd(c.batch, f.in, f.out, h, n->params + f.w_off, act, f.act, n->gemm_ws, st));
     h = f.act;
   }
@@ -242,8 +306,12 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
   for (int j = kFc - 1; j >= 0; --j) {
     Dense& f = n->fc[j];
     const float* x = j == 0 ? n->st[kStages - 1].out() : n->fc[j - 1].act;
-    AX_TRY(launch_fc_bwd_weight(c.batch, f.in, f.out, x, f.dz, n->grads + f.w_off, st));
-    AX_TRY(launch_colsum(f.dz, c.batch, f.out, n->grads + f.b_off, n->colsum_ws, st));
+    {
+      ProfContext pc(f.lab[2]);
+      AX_TRY(launch_fc_bwd_weight(c.batch, f.in, f.out, x, f.dz, n->grads + f.w_off, st));
+      AX_TRY(launch_colsum(f.dz, c.batch, f.out, n->grads + f.b_off, n->colsum_ws, st));
+    }
+    ProfContext pc(f.lab[3]);
     if (j > 0) {
       // fc(j-1) output is ReLU+dropout: it is positive exactly where the gradient passes
       AX_TRY(launch_fc_bwd_data(c.batch, f.in, f.out, f.dz, n->params + f.w_off, n->fc[j - 1].act, n->fc[j - 1].dz,
@@ -256,6 +324,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
   }
   for (int i = kStages - 1; i >= 0; --i) {
     Stage& s = n->st[i];
+    ProfContext pc0(s.lab[0]);
     if (s.pool) {
       if (s.lrn)
         AX_TRY(launch_pool_bwd(s.d_out, s.slot, nullptr, s.d_lrn, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
@@ -266,9 +335,13 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
       AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
                             c.lrn_alpha, c.lrn_beta, 1, st));
     const float* x = i == 0 ? in : n->st[i - 1].out();
-    AX_TRY(launch_conv_bwd_weight(s.g, x, s.dact, n->grads + s.w_off, n->gemm_ws, st));
-    AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
+    {
+      ProfContext pc(s.lab[2]);
+      AX_TRY(launch_conv_bwd_weight(s.g, x, s.dact, n->grads + s.w_off, n->gemm_ws, st));
+      AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
+    }
     if (i > 0) {
+      ProfContext pc(s.lab[3]);
       Stage& prev = n->st[i - 1];
       AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
       AX_TRY(launch_conv_bwd_data(s.g, s.dact, s.wb, prev.plain() ? prev.act : nullptr, prev.d_out, st));
@@ -326,6 +399,61 @@ extern "C" {
 
 const char* alexnet_last_error(void) { return ax::get_error(); }
 const char* alexnet_version(void) { return "alexnet-hip gfx950 fp32-mfma 0.1"; }
+
+int alexnet_profile_begin(void) {
+  if (g_profiler) {
+    set_error("alexnet_profile_begin: already profiling on this thread");
+    return ALEXNET_EINVAL;
+  }
+  g_profiler = new (std::nothrow) Profiler;
+  if (!g_profiler) {
+    set_error("out of host memory");
+    return ALEXNET_EINVAL;
+  }
+  g_prof = g_profiler;
+  return ALEXNET_OK;
+}
+
+int alexnet_profile_end(alexnet_prof_entry_t* out, int32_t cap, int32_t* n_out) {
+  if (!g_profiler) {
+    set_error("alexnet_profile_end: not profiling");
+    return ALEXNET_EINVAL;
+  }
+  Profiler* p = g_profiler;
+  g_profiler = nullptr;
+  g_prof = nullptr;
+  int rc = ALEXNET_OK;
+  int32_t k = 0;
+  if (p->failed) {
+    set_error("alexnet_profile_end: an event call failed while profiling");
+    rc = ALEXNET_EHIP;
+  }
+  for (auto& e : p->entries) {
+    if (rc != ALEXNET_OK) break;
+    float total = 0.f;
+    for (auto& pr : e.ev) {
+      float ms = 0.f;
+      if (hipEventSynchronize(pr.second) != hipSuccess || hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) {
+        set_error("alexnet_profile_end: reading an event failed");
+        rc = ALEXNET_EHIP;
+        break;
+      }
+      total += ms;
+    }
+    if (rc == ALEXNET_OK && out && k < cap) {
+      alexnet_prof_entry_t& o = out[k];
+      snprintf(o.name, sizeof o.name, "%s", e.name.c_str());
+      o.calls = (int32_t)e.ev.size();
+      o.total_ms = total;
+      o.flops = e.flops;
+      o.bytes = e.bytes;
+    }
+    ++k;
+  }
+  if (n_out) *n_out = k;
+  delete p;
+  return rc;
+}
 
 int alexnet_query(const alexnet_config_t* cfg, size_t* n_params, size_t* workspace_bytes) {
   REQUIRE(cfg && n_params && workspace_bytes, ALEXNET_EINVAL, "alexnet_query: null argument");

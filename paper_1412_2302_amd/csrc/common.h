@@ -59,4 +59,32 @@ __host__ __device__ inline bool dropout_keep(uint64_t key, uint32_t tag, uint64_
 
 inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
 
+// ---- optional per-kernel timing ---------------------------------------------
+// When a sink is installed for the calling thread, every kernel launch of the
+// library is bracketed by two HIP events on its own stream.  `flops` / `bytes`
+// are the algorithmic work of the launch (what the operation must do, not what
+// the kernel happens to move).
+struct ProfSink {
+  virtual void begin(const char* kernel, double flops, double bytes, hipStream_t st) = 0;
+  virtual void end(hipStream_t st) = 0;
+  virtual ~ProfSink() {}
+};
+extern thread_local ProfSink* g_prof;
+extern thread_local const char* g_prof_ctx;  // e.g. "conv2.bwd_w"; prefixed to kernel names
+struct KernelScope {
+  hipStream_t st;
+  bool on;
+  KernelScope(const char* kernel, double flops, double bytes, hipStream_t s) : st(s), on(g_prof != nullptr) {
+    if (on) g_prof->begin(kernel, flops, bytes, s);
+  }
+  ~KernelScope() {
+    if (on) g_prof->end(st);
+  }
+};
+struct ProfContext {
+  const char* prev;
+  explicit ProfContext(const char* c) : prev(g_prof_ctx) { g_prof_ctx = c; }
+  ~ProfContext() { g_prof_ctx = prev; }
+};
+
 }  // namespace ax

@@ -34,6 +34,7 @@ static int launch_tile(const typename ALT<T::BM, T::BK>::Params& ap, const typen
     set_error("GEMM grid too large (%u,%u,%u)", grid.x, grid.y, grid.z);
     return ALEXNET_ESHAPE;
   }
+  KernelScope ks("gemm", 2.0 * M * N * (double)K * groups, 0, st);
   hipLaunchKernelGGL((gemm_kernel<T, ALT<T::BM, T::BK>, BLT<T::BN, T::BK>, Epi>), grid, dim3(kThreads), 0, st, ap, bp,
                      ep, M, N, K, kchunk, nsplit);
   AX_LAUNCH_CHECK();
@@ -143,6 +144,7 @@ int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const 
   EpiSlab ep{ws, (long)B * out, out, nullptr};
   AX_TRY((launch_tile<T128, DenseKInner, DenseKInner, EpiSlab>(a, b, ep, B, out, in, kchunk, ns, 1, st)));
   const size_t total = (size_t)B * out;
+  KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1), st);
   hipLaunchKernelGGL(fc_fwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, B, out, act, y);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
@@ -157,6 +159,7 @@ int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, 
   EpiSlab ep{ws, (long)B * in, in, nullptr};
   AX_TRY((launch_tile<T128, DenseKInner, DenseRowInner, EpiSlab>(a, b, ep, B, in, out, kchunk, ns, 1, st)));
   const size_t total = (size_t)B * in;
+  KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1 + (gate ? 1 : 0)), st);
   hipLaunchKernelGGL(fc_bwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, total, gate, dx);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;

@@ -53,6 +53,7 @@ __global__ void crop_params_kernel(uint64_t key, int B, int range_x, int range_y
 }
 int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* ox, int32_t* oy, int32_t* flip,
                        hipStream_t st) {
+  KernelScope ks("crop_params", 0, (double)B * 12.0, st);
   hipLaunchKernelGGL(crop_params_kernel, dim3(grid_for(B, 64)), dim3(64), 0, st, key, B, range_x, range_y, ox, oy,
                      flip);
   AX_LAUNCH_CHECK();
@@ -80,6 +81,7 @@ __global__ void preprocess_kernel(const uint8_t* __restrict__ raw, const float* 
 int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, const int32_t* oy,
                       const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st) {
   const size_t total = (size_t)B * CH * CW;
+  KernelScope ks("preprocess", 0, (double)total * C * 5.0, st);
   hipLaunchKernelGGL(preprocess_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, raw, mean, ox, oy, flip, B, C,
                      RH, RW, CH, CW, out);
   AX_LAUNCH_CHECK();
@@ -175,6 +177,7 @@ int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k,
                    hipStream_t st) {
   const size_t total = (size_t)pixels * C;
   if (!total) return ALEXNET_OK;
+  KernelScope ks("lrn_fwd", 0, (double)total * 8.0, st);
   hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, b, total, C, n / 2, k, alpha,
                      beta);
   AX_LAUNCH_CHECK();
@@ -184,6 +187,7 @@ int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int 
                    float beta, int relu_gate, hipStream_t st) {
   const size_t total = (size_t)pixels * C;
   if (!total) return ALEXNET_OK;
+  KernelScope ks("lrn_bwd", 0, (double)total * 12.0, st);
   hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, db, da, total, C, n / 2, k,
                      alpha, beta, relu_gate);
   AX_LAUNCH_CHECK();
@@ -226,6 +230,7 @@ int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W
                     hipStream_t st) {
   const size_t total = (size_t)N * Ho * Wo * C;
   if (!total) return ALEXNET_OK;
+  KernelScope ks("pool_fwd", 0, (double)N * H * W * C * 4.0 + (double)total * 5.0, st);
   hipLaunchKernelGGL(pool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, slot, N, H, W, C, Ho, Wo);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
@@ -262,6 +267,7 @@ int launch_pool_bwd(const float* dy, const uint8_t* slot, const float* gate, flo
                     int Ho, int Wo, hipStream_t st) {
   const size_t total = (size_t)N * H * W * C;
   if (!total) return ALEXNET_OK;
+  KernelScope ks("pool_bwd", 0, (double)total * (gate ? 8.0 : 4.0) + (double)N * Ho * Wo * C * 5.0, st);
   hipLaunchKernelGGL(pool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, slot, gate, dx, N, H, W, C,
                      Ho, Wo);
   AX_LAUNCH_CHECK();
@@ -345,6 +351,7 @@ softmax_xent_kernel(const float* __restrict__ z, const int32_t* __restrict__ lab
 }
 int launch_softmax_xent(const float* z, const int32_t* labels, int B, int classes, int mode, float* out,
                         float* row_loss, int32_t* err_flag, hipStream_t st) {
+  KernelScope ks("softmax_xent", 0, (double)B * classes * 8.0, st);
   hipLaunchKernelGGL(softmax_xent_kernel, dim3(B), dim3(256), 0, st, z, labels, B, classes, mode, out, row_loss,
                      err_flag);
   AX_LAUNCH_CHECK();
@@ -359,6 +366,7 @@ __global__ void __launch_bounds__(256) mean_loss_kernel(const float* __restrict_
   if (threadIdx.x == 0) *loss = s / (float)B;
 }
 int launch_mean_loss(const float* row_loss, int B, float* loss, hipStream_t st) {
+  KernelScope ks("mean_loss", 0, (double)B * 4.0, st);
   hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(256), 0, st, row_loss, B, loss);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
@@ -394,6 +402,7 @@ size_t colsum_ws_floats(long rows, int cols) {
 }
 int launch_colsum(const float* m, long rows, int cols, float* out, float* ws, hipStream_t st) {
   const int nparts = ceil_div(rows, kColsumRowsPerBlock);
+  KernelScope ks("colsum", 0, (double)rows * cols * 4.0, st);
   hipLaunchKernelGGL(colsum_stage1, dim3(ceil_div(cols, 64), nparts), dim3(256), 0, st, m, rows, cols, ws);
   AX_LAUNCH_CHECK();
   hipLaunchKernelGGL(colsum_stage2, dim3(ceil_div(cols, 256)), dim3(256), 0, st, ws, nparts, cols, out);
@@ -416,6 +425,7 @@ __global__ void reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, si
 int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, float* out, hipStream_t st) {
   const size_t total = (size_t)slab * groups;
   if (!total) return ALEXNET_OK;
+  KernelScope ks("reduce_slabs", 0, (double)total * 4.0 * (nsplit + 1), st);
   hipLaunchKernelGGL(reduce_slabs_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, ws, nsplit, (size_t)slab,
                      groups, out);
   AX_LAUNCH_CHECK();
@@ -457,6 +467,7 @@ __global__ void sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, 
 int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
                       hipStream_t st) {
   if (!n) return ALEXNET_OK;
+  KernelScope ks("sgd_update", 0, (double)n * 20.0, st);
   hipLaunchKernelGGL(sgd_update_kernel, dim3(grid_for((n + 3) / 4, 256)), dim3(256), 0, st, w, v, g, n, n_decay, lr,
                      mu, wd);
   AX_LAUNCH_CHECK();
@@ -490,6 +501,7 @@ __global__ void average_kernel(float* __restrict__ a, float* __restrict__ b, siz
 }
 int launch_average(float* a, float* b, size_t n, hipStream_t st) {
   if (!n) return ALEXNET_OK;
+  KernelScope ks("average", 0, (double)n * 16.0, st);
   hipLaunchKernelGGL(average_kernel, dim3(grid_for((n + 3) / 4, 256)), dim3(256), 0, st, a, b, n);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
@@ -541,6 +553,7 @@ __global__ void conv_weight_wb_kernel(const float* __restrict__ wf, float* __res
 }
 int launch_conv_weight_wb(const float* wf, float* wb, int Cout, int Cg, int k, int groups, hipStream_t st) {
   const size_t total = (size_t)Cout * Cg * k * k;
+  KernelScope ks("weight_transpose", 0, (double)total * 8.0, st);
   hipLaunchKernelGGL(conv_weight_wb_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, wf, wb, Cout, Cg, k,
                      groups);
   AX_LAUNCH_CHECK();

@@ -1,0 +1,103 @@
+"""Parity at the benchmark's full sizes (batch 128, real AlexNet shapes), in the
+launch configuration bench.py times."""
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as S
+from gpu_common import LOSS_RTOL, TENSOR_RTOL, build_pair, cuda
+from helpers import oracle_spec, rel_l2, to64
+from oracle import alexnet_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.timeout(900)
+def test_full_alexnet_step_batch128(lib):
+    """Workload 3: uint8 pictures -> preprocess -> full fp32 step at batch 128."""
+    batch, wl = 128, S.ALEXNET
+    net, spec, p64, m64 = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3)
+    raw, labels = S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 3)
+    mean = S.make_mean_image(3, 256, 256, S.SEED_BASE + 7)
+    print("gpu step", flush=True)
+    net.preprocess(cuda(raw), cuda(mean), 0, 0)
+    loss = float(net.train_step(cuda(labels), 0, slot=0).cpu().item())
+    net.check()
+    ox, oy, fl = O.crop_flip_params(spec, 0)
+    assert np.array_equal(net.tensor(lib.T_CROP_X, 0), ox) and np.array_equal(net.tensor(lib.T_CROP_Y, 0), oy)
+    assert np.array_equal(net.tensor(lib.T_FLIP, 0), fl)
+    print("oracle step", flush=True)
+    x64 = O.preprocess(raw, mean, ox, oy, fl, 227, 227)
+    assert np.array_equal(net.tensor(lib.T_INPUT, 0).reshape(x64.shape), x64.astype(np.float32))
+    loss_ref, p_new, m_new, g_ref, cache = O.train_step(spec, p64, m64, x64, labels, 0)
+    print("compare", loss, loss_ref, flush=True)
+    assert abs(loss - loss_ref) <= LOSS_RTOL * abs(loss_ref)
+    assert abs(loss_ref - np.log(1000)) < 0.05
+    g, pn, mn = net.get_grads(), net.get_params(), net.get_momentum()
+    for k in g_ref:
+        e = rel_l2(g[k], g_ref[k])
+        print(k, "grad rel_l2 %.2e" % e, flush=True)
+        assert e <= TENSOR_RTOL, (k, e)
+        assert rel_l2(pn[k], p_new[k]) <= TENSOR_RTOL and rel_l2(mn[k], m_new[k]) <= TENSOR_RTOL, k
+    for i in (1, 2, 5):
+        pool_in = net.tensor(lib.T_LRN if i < 3 else lib.T_CONV_ACT, i).reshape(cache[f"conv{i}.act"].shape)
+        want_v, want_a = O.maxpool_forward(pool_in, 3, 2)
+        assert np.array_equal(net.tensor(lib.T_ARGMAX, i).reshape(want_a.shape), want_a), i
+    net.close()
+
+
+def _sample_idx(rng, shape, n):
+    return [tuple(int(rng.integers(0, s)) for s in shape) for _ in range(n)]
+
+
+@pytest.mark.timeout(600)
+def test_conv_stack_alone_batch128_sampled(lib):
+    """Workload 2: each convolution alone at batch 128 on N(0,1) inputs and
+    N(0,1) output gradients; outputs the oracle's definition gives one by one."""
+    batch = 128
+    net = lib.AlexNet(S.ALEXNET, batch)
+    spec = oracle_spec(S.ALEXNET, batch)
+    stages, _ = O.layer_shapes(spec)
+    rng = np.random.default_rng(S.SEED_BASE + 2)
+    for li, (cv, st) in enumerate(zip(spec.conv, stages), start=1):
+        cin, h, w = st["in"]; cout, ho, wo = st["conv"]
+        cg, og, k, s_, pd = cin // cv.groups, cout // cv.groups, cv.k, cv.stride, cv.pad
+        print("conv", li, flush=True)
+        x = S.make_normal((batch, cin, h, w), S.SEED_BASE + 20 + li)
+        wt = S.make_normal((cout, cg, k, k), S.SEED_BASE + 30 + li, std=0.01)
+        dy = S.make_normal((batch, cout, ho, wo), S.SEED_BASE + 40 + li)
+        xp = np.pad(x, ((0, 0), (0, 0), (pd, pd), (pd, pd))).astype(np.float64)
+        y = net.conv_forward(li, x, wt, None).cpu().numpy().reshape(batch, cout, ho, wo)
+        got, want = [], []
+        for (n, o, yy, xx) in _sample_idx(rng, y.shape, 300):
+            g = o // og
+            want.append(float((wt[o].astype(np.float64) * xp[n, g * cg:(g + 1) * cg, yy * s_:yy * s_ + k, xx * s_:xx * s_ + k]).sum()))
+            got.append(y[n, o, yy, xx])
+        assert rel_l2(got, want) <= TENSOR_RTOL, ("fwd", li, rel_l2(got, want))
+        dx = net.conv_backward_data(li, dy, wt, x.shape).cpu().numpy()
+        got, want = [], []
+        for (n, c, iy, ix) in _sample_idx(rng, x.shape, 200):
+            g, cl = c // cg, c % cg
+            acc = 0.0
+            for r in range(k):
+                ty = iy + pd - r
+                if ty < 0 or ty % s_ or ty // s_ >= ho:
+                    continue
+                for q in range(k):
+                    tx = ix + pd - q
+                    if tx < 0 or tx % s_ or tx // s_ >= wo:
+                        continue
+                    acc += float(dy[n, g * og:(g + 1) * og, ty // s_, tx // s_].astype(np.float64) @ wt[g * og:(g + 1) * og, cl, r, q].astype(np.float64))
+            want.append(acc); got.append(dx[n, c, iy, ix])
+        assert rel_l2(got, want) <= TENSOR_RTOL, ("bwd_data", li, rel_l2(got, want))
+        dw, db = net.conv_backward_weight(li, x, dy, wt.shape)
+        dw = dw.cpu().numpy()
+        got, want = [], []
+        for (o, c, r, q) in _sample_idx(rng, wt.shape, 40):
+            g = o // og
+            patch = xp[:, g * cg + c, r:r + s_ * ho:s_, q:q + s_ * wo:s_]
+            want.append(float((patch * dy[:, o].astype(np.float64)).sum())); got.append(dw[o, c, r, q])
+        assert rel_l2(got, want) <= TENSOR_RTOL, ("bwd_weight", li, rel_l2(got, want))
+        assert rel_l2(db.cpu().numpy(), dy.astype(np.float64).sum((0, 2, 3))) <= TENSOR_RTOL
+        del x, dy, xp, y, dx
+    net.close()
