@@ -190,6 +190,30 @@ int alexnet_conv_backward_data_nhwc(alexnet_t* net, int32_t layer, const float* 
 int alexnet_conv_backward_weight_nhwc(alexnet_t* net, int32_t layer, const float* d_x, const float* d_dy,
                                       float* d_dw_fwd, float* d_db, void* stream);
 
+/* The bandwidth-bound operators alone, canonical float32 tensors, shapes of
+ * stage `layer`'s convolution output [batch][Cout][Ho][Wo] (LRN, pool input)
+ * and pooled output.  They stage through the handle's training buffers, so
+ * they overwrite the intermediates of the last training pass.
+ * LRN: b = a * (k + alpha * sum_{window} a^2)^-beta across channels; the
+ * backward call returns dL/da given dL/db, multiplied by [a > 0] if relu_gate.
+ * Pool: 3x3 stride 2, first maximum wins; argmax = y_in*Wo + x_in (int32). */
+int alexnet_lrn_forward(alexnet_t* net, int32_t layer, const float* d_a, float* d_b, void* stream);
+int alexnet_lrn_backward(alexnet_t* net, int32_t layer, const float* d_a, const float* d_db, int32_t relu_gate,
+                         float* d_da, void* stream);
+int alexnet_pool_forward(alexnet_t* net, int32_t layer, const float* d_x, float* d_y, int32_t* d_argmax,
+                         void* stream);
+int alexnet_pool_backward(alexnet_t* net, int32_t layer, const float* d_x, const float* d_dy, int32_t relu_gate,
+                          float* d_dx, void* stream);
+/* Dense layer `layer` (6..8) as plain matrices: x [batch][in], w [out][in],
+ * y, dy [batch][out]; y = act(x w^T + b), dx = dy w, dw = dy^T x, db = sum dy. */
+int alexnet_fc_forward(alexnet_t* net, int32_t layer, const float* d_x, const float* d_w, const float* d_b,
+                       int32_t relu, float* d_y, void* stream);
+int alexnet_fc_backward(alexnet_t* net, int32_t layer, const float* d_x, const float* d_w, const float* d_dy,
+                        float* d_dx, float* d_dw, float* d_db, void* stream);
+/* logits [batch][classes] -> dz = (softmax - onehot)/batch and the mean loss. */
+int alexnet_softmax_xent(alexnet_t* net, const float* d_logits, const int32_t* d_labels, float* d_dz,
+                         float* d_loss, void* stream);
+
 /* --- per-kernel timing (measurement aid; not part of the training path) ---
  * Between alexnet_profile_begin and alexnet_profile_end every kernel the
  * calling thread launches through this library is bracketed by two HIP events

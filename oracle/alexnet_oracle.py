@@ -434,6 +434,7 @@ def _forward_stack(spec: NetSpec, params, x, masks, train: bool):
         name = f"conv{i+1}"
         z = conv_forward(h, params[name + ".w"], params[name + ".b"], cv.stride, cv.pad, cv.groups)
         a = relu(z)
+        cache[name + ".z"] = z
         cache[name + ".in"] = h
         cache[name + ".act"] = a
         h = a
@@ -455,6 +456,7 @@ def _forward_stack(spec: NetSpec, params, x, masks, train: bool):
         name = f"fc{len(spec.conv)+1+j}"
         cache[name + ".in"] = h
         z = fc_forward(h, params[name + ".w"], params[name + ".b"])
+        cache[name + ".z"] = z
         if j < nfc - 1:
             a = relu(z)
             if train:
@@ -477,10 +479,23 @@ def forward(spec: NetSpec, params, x) -> np.ndarray:
     return e / e.sum(axis=1, keepdims=True)
 
 
-def loss_and_grads(spec: NetSpec, params, x, labels, masks, want_dx: bool = False):
+def loss_and_grads(spec: NetSpec, params, x, labels, masks, want_dx: bool = False, decisions=None):
     """Mean cross-entropy of the minibatch and its gradient w.r.t. every
-    parameter, with the given dropout masks held fixed."""
+    parameter, with the given dropout masks held fixed.
+
+    The network is piecewise smooth: which side of a ReLU a unit is on and
+    which tap wins a pooling window are discrete choices of the forward pass.
+    `decisions` (optional) fixes them for the backward pass: keys
+    "<layer>.gate" (bool, unit passes gradient) and "conv<i>.argmax" (int32,
+    same convention as maxpool_forward).  Missing keys, or decisions=None, mean
+    the choices this forward pass made itself.  A caller that passes choices
+    made elsewhere is responsible for checking them against cache["<layer>.z"]
+    and the pooled inputs (they may differ only where those are tied to within
+    rounding)."""
     z, cache = _forward_stack(spec, params, x, masks, train=True)
+    if callable(decisions):  # lets a caller inspect this forward pass before fixing the choices
+        decisions = decisions(cache)
+    decisions = decisions or {}
     loss, p, dz = softmax_xent(z, labels)
     cache["probs"] = p
     grads = {}
@@ -489,7 +504,8 @@ def loss_and_grads(spec: NetSpec, params, x, labels, masks, want_dx: bool = Fals
     for j in reversed(range(nfc)):
         name = f"fc{len(spec.conv)+1+j}"
         if j < nfc - 1:
-            d = d * (cache[name + ".act"] > 0)  # ReLU and dropout: act>0 iff kept and positive
+            # ReLU and dropout: act>0 iff kept and positive
+            d = d * decisions.get(name + ".gate", cache[name + ".act"] > 0)
         dx, dw, db = fc_backward(cache[name + ".in"], params[name + ".w"], d)
         grads[name + ".w"], grads[name + ".b"] = dw, db
         d = dx
@@ -498,10 +514,10 @@ def loss_and_grads(spec: NetSpec, params, x, labels, masks, want_dx: bool = Fals
         cv = spec.conv[i]
         name = f"conv{i+1}"
         if cv.pool:
-            d = maxpool_backward(d, cache[name + ".argmax"], cache[name + ".pool_in_hw"])
+            d = maxpool_backward(d, decisions.get(name + ".argmax", cache[name + ".argmax"]), cache[name + ".pool_in_hw"])
         if cv.lrn:
             d = lrn_backward(d, cache[name + ".act"], cache[name + ".lrn_s"], spec.lrn_n, spec.lrn_alpha, spec.lrn_beta)
-        d = d * (cache[name + ".act"] > 0)
+        d = d * decisions.get(name + ".gate", cache[name + ".act"] > 0)
         cache[name + ".dact"] = d
         xin = cache[name + ".in"]
         dw, db = conv_backward_weight(xin, d, cv.k, cv.stride, cv.pad, cv.groups)
@@ -513,13 +529,14 @@ def loss_and_grads(spec: NetSpec, params, x, labels, masks, want_dx: bool = Fals
     return loss, grads, cache
 
 
-def train_step(spec: NetSpec, params, momentum, x, labels, step: int, masks=None):
+def train_step(spec: NetSpec, params, momentum, x, labels, step: int, masks=None, decisions=None):
     """One SGD iteration.  Returns (loss, new_params, new_momentum, grads, cache).
-    Weight decay applies to weight tensors only; biases decay with 0."""
+    Weight decay applies to weight tensors only; biases decay with 0.
+    `decisions`: see loss_and_grads."""
     if masks is None:
         widths = spec.fc[:-1]
         masks = [dropout_mask(spec, step, tag, wd_) for tag, wd_ in zip((TAG_DROP6, TAG_DROP7), widths)]
-    loss, grads, cache = loss_and_grads(spec, params, x, labels, masks)
+    loss, grads, cache = loss_and_grads(spec, params, x, labels, masks, decisions=decisions)
     new_p, new_v = {}, {}
     for kname in param_shapes(spec):
         wd = spec.weight_decay if kname.endswith(".w") else 0.0

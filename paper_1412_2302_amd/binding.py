@@ -78,6 +78,15 @@ class ProfEntry(C.Structure):
                 ("flops", C.c_double), ("bytes", C.c_double)]
 
 
+_SIGS.update({
+    "alexnet_lrn_forward": [_vp, _i32, _vp, _vp, _vp],
+    "alexnet_lrn_backward": [_vp, _i32, _vp, _vp, _i32, _vp, _vp],
+    "alexnet_pool_forward": [_vp, _i32, _vp, _vp, _vp, _vp],
+    "alexnet_pool_backward": [_vp, _i32, _vp, _vp, _i32, _vp, _vp],
+    "alexnet_fc_forward": [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp],
+    "alexnet_fc_backward": [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
+    "alexnet_softmax_xent": [_vp, _vp, _vp, _vp, _vp, _vp],
+})
 _SIGS["alexnet_profile_begin"] = []
 _SIGS["alexnet_profile_end"] = [C.POINTER(ProfEntry), _i32, C.POINTER(_i32)]
 for _name, _args in _SIGS.items():
@@ -320,6 +329,56 @@ class AlexNet:
 
     def conv_backward_weight_nhwc(self, layer, x, dy, dwf, db, stream=None):
         _check(_lib.alexnet_conv_backward_weight_nhwc(self._h, layer, _ptr(x), _ptr(dy), _ptr(dwf), _ptr(db), _stream(stream)))
+
+
+    # ---- bandwidth-bound operators and dense layers alone (canonical tensors) ----
+    def lrn_forward(self, layer, a):
+        at = _dev(a, torch.float32)
+        b = torch.empty_like(at)
+        _check(_lib.alexnet_lrn_forward(self._h, layer, _ptr(at), _ptr(b), _stream(None)))
+        return b
+
+    def lrn_backward(self, layer, a, db, relu_gate=False):
+        at, dbt = _dev(a, torch.float32), _dev(db, torch.float32)
+        da = torch.empty_like(at)
+        _check(_lib.alexnet_lrn_backward(self._h, layer, _ptr(at), _ptr(dbt), int(relu_gate), _ptr(da), _stream(None)))
+        return da
+
+    def pool_forward(self, layer, x):
+        xt = _dev(x, torch.float32)
+        n, c, h, w = xt.shape
+        ho, wo = (h - 3) // 2 + 1, (w - 3) // 2 + 1
+        y = torch.empty(n, c, ho, wo, dtype=torch.float32, device="cuda")
+        arg = torch.empty(n, c, ho, wo, dtype=torch.int32, device="cuda")
+        _check(_lib.alexnet_pool_forward(self._h, layer, _ptr(xt), _ptr(y), _ptr(arg), _stream(None)))
+        return y, arg
+
+    def pool_backward(self, layer, x, dy, relu_gate=False):
+        xt, dyt = _dev(x, torch.float32), _dev(dy, torch.float32)
+        dx = torch.empty_like(xt)
+        _check(_lib.alexnet_pool_backward(self._h, layer, _ptr(xt), _ptr(dyt), int(relu_gate), _ptr(dx), _stream(None)))
+        return dx
+
+    def fc_forward(self, layer, x, w, b, relu=False):
+        xt, wt, bt = _dev(x, torch.float32), _dev(w, torch.float32), _dev(b, torch.float32)
+        y = torch.empty(xt.shape[0], wt.shape[0], dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_fc_forward(self._h, layer, _ptr(xt), _ptr(wt), _ptr(bt), int(relu), _ptr(y), _stream(None)))
+        return y
+
+    def fc_backward(self, layer, x, w, dy):
+        xt, wt, dyt = _dev(x, torch.float32), _dev(w, torch.float32), _dev(dy, torch.float32)
+        dx, dw = torch.empty_like(xt), torch.empty_like(wt)
+        db = torch.empty(wt.shape[0], dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_fc_backward(self._h, layer, _ptr(xt), _ptr(wt), _ptr(dyt), _ptr(dx), _ptr(dw), _ptr(db),
+                                        _stream(None)))
+        return dx, dw, db
+
+    def softmax_xent(self, logits, labels):
+        zt, lt = _dev(logits, torch.float32), _dev(labels, torch.int32)
+        dz = torch.empty_like(zt)
+        loss = torch.empty(1, dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_softmax_xent(self._h, _ptr(zt), _ptr(lt), _ptr(dz), _ptr(loss), _stream(None)))
+        return dz, loss
 
 
 def average_replicas(a: AlexNet, b: AlexNet, stream=None):

@@ -738,4 +738,94 @@ int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, co
   return ALEXNET_OK;
 }
 
+// ---- single bandwidth-bound operators on canonical tensors --------------------
+// These reuse the stage's own training buffers as staging space.
+int alexnet_lrn_forward(alexnet_t* n, int32_t layer, const float* d_a, float* d_b, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(d_a && d_b, ALEXNET_EINVAL, "alexnet_lrn_forward: null argument");
+  REQUIRE(s->lrn, ALEXNET_EINVAL, "alexnet_lrn_forward: stage has no LRN");
+  const ConvGeom& g = s->g;
+  const alexnet_config_t& c = n->cfg;
+  AX_TRY(launch_nchw_to_nhwc(d_a, s->act, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_lrn_fwd(s->act, s->lrn_out, g.P(), g.Cout, c.lrn_n, c.lrn_k, c.lrn_alpha, c.lrn_beta, S(stream)));
+  return launch_nhwc_to_nchw(s->lrn_out, d_b, g.B, g.Cout, g.Ho, g.Wo, S(stream));
+}
+int alexnet_lrn_backward(alexnet_t* n, int32_t layer, const float* d_a, const float* d_db, int32_t relu_gate,
+                         float* d_da, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(d_a && d_db && d_da, ALEXNET_EINVAL, "alexnet_lrn_backward: null argument");
+  REQUIRE(s->lrn, ALEXNET_EINVAL, "alexnet_lrn_backward: stage has no LRN");
+  const ConvGeom& g = s->g;
+  const alexnet_config_t& c = n->cfg;
+  AX_TRY(launch_nchw_to_nhwc(d_a, s->act, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_nchw_to_nhwc(d_db, s->lrn_out, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_lrn_bwd(s->act, s->lrn_out, s->dact, g.P(), g.Cout, c.lrn_n, c.lrn_k, c.lrn_alpha, c.lrn_beta,
+                        relu_gate, S(stream)));
+  return launch_nhwc_to_nchw(s->dact, d_da, g.B, g.Cout, g.Ho, g.Wo, S(stream));
+}
+int alexnet_pool_forward(alexnet_t* n, int32_t layer, const float* d_x, float* d_y, int32_t* d_argmax,
+                         void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(d_x && d_y, ALEXNET_EINVAL, "alexnet_pool_forward: null argument");
+  REQUIRE(s->pool, ALEXNET_EINVAL, "alexnet_pool_forward: stage has no pool");
+  const ConvGeom& g = s->g;
+  AX_TRY(launch_nchw_to_nhwc(d_x, s->act, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_pool_fwd(s->act, s->pool_out, s->slot, g.B, g.Ho, g.Wo, g.Cout, s->Hp, s->Wp, S(stream)));
+  AX_TRY(launch_nhwc_to_nchw(s->pool_out, d_y, g.B, g.Cout, s->Hp, s->Wp, S(stream)));
+  if (d_argmax) AX_TRY(launch_pool_argmax_canonical(s->slot, d_argmax, g.B, g.Cout, s->Hp, s->Wp, g.Wo, S(stream)));
+  return ALEXNET_OK;
+}
+int alexnet_pool_backward(alexnet_t* n, int32_t layer, const float* d_x, const float* d_dy, int32_t relu_gate,
+                          float* d_dx, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(d_x && d_dy && d_dx, ALEXNET_EINVAL, "alexnet_pool_backward: null argument");
+  REQUIRE(s->pool, ALEXNET_EINVAL, "alexnet_pool_backward: stage has no pool");
+  const ConvGeom& g = s->g;
+  AX_TRY(launch_nchw_to_nhwc(d_x, s->act, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_pool_fwd(s->act, s->pool_out, s->slot, g.B, g.Ho, g.Wo, g.Cout, s->Hp, s->Wp, S(stream)));
+  AX_TRY(launch_nchw_to_nhwc(d_dy, s->d_out, g.B, g.Cout, s->Hp, s->Wp, S(stream)));
+  AX_TRY(launch_pool_bwd(s->d_out, s->slot, relu_gate ? s->act : nullptr, s->dact, g.B, g.Ho, g.Wo, g.Cout, s->Hp,
+                         s->Wp, S(stream)));
+  return launch_nhwc_to_nchw(s->dact, d_dx, g.B, g.Cout, g.Ho, g.Wo, S(stream));
+}
+
+static int dense_of(alexnet* n, int32_t layer, Dense** f) {
+  if (!n || layer <= kStages || layer > kStages + kFc) {
+    set_error("dense layer must be 6..8");
+    return ALEXNET_EINVAL;
+  }
+  *f = &n->fc[layer - kStages - 1];
+  return ALEXNET_OK;
+}
+int alexnet_fc_forward(alexnet_t* n, int32_t layer, const float* d_x, const float* d_w, const float* d_b,
+                       int32_t relu, float* d_y, void* stream) {
+  Dense* f;
+  AX_TRY(dense_of(n, layer, &f));
+  REQUIRE(d_x && d_w && d_y, ALEXNET_EINVAL, "alexnet_fc_forward: null argument");
+  FcAct act;
+  act.bias = d_b; act.relu = relu; act.dropout = 0; act.key = 0; act.tag = 0; act.thresh24 = 0; act.scale = 1.0f;
+  return launch_fc_fwd(n->cfg.batch, f->in, f->out, d_x, d_w, act, d_y, n->gemm_ws, S(stream));
+}
+int alexnet_fc_backward(alexnet_t* n, int32_t layer, const float* d_x, const float* d_w, const float* d_dy,
+                        float* d_dx, float* d_dw, float* d_db, void* stream) {
+  Dense* f;
+  AX_TRY(dense_of(n, layer, &f));
+  REQUIRE(d_x && d_w && d_dy && d_dx && d_dw && d_db, ALEXNET_EINVAL, "alexnet_fc_backward: null argument");
+  const int B = n->cfg.batch;
+  AX_TRY(launch_fc_bwd_weight(B, f->in, f->out, d_x, d_dy, d_dw, S(stream)));
+  AX_TRY(launch_colsum(d_dy, B, f->out, d_db, n->colsum_ws, S(stream)));
+  return launch_fc_bwd_data(B, f->in, f->out, d_dy, d_w, nullptr, d_dx, n->gemm_ws, S(stream));
+}
+int alexnet_softmax_xent(alexnet_t* n, const float* d_logits, const int32_t* d_labels, float* d_dz, float* d_loss,
+                         void* stream) {
+  REQUIRE(n && d_logits && d_labels && d_dz && d_loss, ALEXNET_EINVAL, "alexnet_softmax_xent: null argument");
+  const int B = n->cfg.batch, classes = n->fc[kFc - 1].out;
+  AX_TRY(launch_softmax_xent(d_logits, d_labels, B, classes, 0, d_dz, n->row_loss, n->err_flag, S(stream)));
+  return launch_mean_loss(n->row_loss, B, d_loss, S(stream));
+}
+
 }  // extern "C"
