@@ -15,7 +15,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libalexnet_hip.so")
+# ALEXNET_HIP_LIB points at another build of the same library (used when comparing kernel variants)
+LIB_PATH = os.environ.get("ALEXNET_HIP_LIB") or os.path.join(_HERE, "libalexnet_hip.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1412_2302_amd.build`")
 _lib = C.CDLL(LIB_PATH)
@@ -196,7 +197,7 @@ class AlexNet:
         self.shapes = self._param_shapes()
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:  # _lib is gone at interpreter shutdown
             _lib.alexnet_destroy(self._h)
             self._h = None
 

@@ -224,6 +224,8 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     max_out = std::max(max_out, ae);
     max_w = std::max(max_w, (size_t)s.g.w_elems());
     gws = std::max(gws, conv_bwd_weight_ws_floats(s.g));
+    gws = std::max(gws, conv_fwd_ws_floats(s.g));
+    gws = std::max(gws, conv_bwd_data_ws_floats(s.g));
     cws = std::max(cws, colsum_ws_floats(s.g.P(), s.g.Cout));
   }
   for (int j = 0; j < kFc; ++j) {
@@ -268,7 +270,7 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
     Stage& s = n->st[i];
     {
       ProfContext pc(s.lab[1]);
-      AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, st));
+      AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, n->gemm_ws, st));
     }
     ProfContext pc(s.lab[0]);
     h = s.act;
@@ -344,7 +346,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
       ProfContext pc(s.lab[3]);
       Stage& prev = n->st[i - 1];
       AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
-      AX_TRY(launch_conv_bwd_data(s.g, s.dact, s.wb, prev.plain() ? prev.act : nullptr, prev.d_out, st));
+      AX_TRY(launch_conv_bwd_data(s.g, s.dact, s.wb, prev.plain() ? prev.act : nullptr, prev.d_out, n->gemm_ws, st));
     }
   }
   return ALEXNET_OK;
@@ -683,14 +685,14 @@ int alexnet_conv_forward_nhwc(alexnet_t* n, int32_t layer, const float* x, const
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(x && wf && y, ALEXNET_EINVAL, "alexnet_conv_forward_nhwc: null argument");
-  return launch_conv_fwd(s->g, x, wf, b, relu, y, S(stream));
+  return launch_conv_fwd(s->g, x, wf, b, relu, y, n->gemm_ws, S(stream));
 }
 int alexnet_conv_backward_data_nhwc(alexnet_t* n, int32_t layer, const float* dy, const float* wb, float* dx,
                                     void* stream) {
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(dy && wb && dx, ALEXNET_EINVAL, "alexnet_conv_backward_data_nhwc: null argument");
-  return launch_conv_bwd_data(s->g, dy, wb, nullptr, dx, S(stream));
+  return launch_conv_bwd_data(s->g, dy, wb, nullptr, dx, n->gemm_ws, S(stream));
 }
 int alexnet_conv_backward_weight_nhwc(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dwf,
                                       float* db, void* stream) {
@@ -709,7 +711,7 @@ int alexnet_conv_forward(alexnet_t* n, int32_t layer, const float* x, const floa
   const ConvGeom& g = s->g;
   AX_TRY(launch_nchw_to_nhwc(x, n->scratch_x, g.B, g.Cin, g.H, g.W, S(stream)));
   AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
-  AX_TRY(launch_conv_fwd(g, n->scratch_x, n->scratch_w[0], b, relu, n->scratch_y, S(stream)));
+  AX_TRY(launch_conv_fwd(g, n->scratch_x, n->scratch_w[0], b, relu, n->scratch_y, n->gemm_ws, S(stream)));
   return launch_nhwc_to_nchw(n->scratch_y, y, g.B, g.Cout, g.Ho, g.Wo, S(stream));
 }
 int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, const float* w, float* dx,
@@ -721,7 +723,7 @@ int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, con
   AX_TRY(launch_nchw_to_nhwc(dy, n->scratch_y, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
   AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
   AX_TRY(launch_conv_weight_wb(n->scratch_w[0], n->scratch_w[1], g.Cout, g.cg(), g.k, g.groups, S(stream)));
-  AX_TRY(launch_conv_bwd_data(g, n->scratch_y, n->scratch_w[1], nullptr, n->scratch_x, S(stream)));
+  AX_TRY(launch_conv_bwd_data(g, n->scratch_y, n->scratch_w[1], nullptr, n->scratch_x, n->gemm_ws, S(stream)));
   return launch_nhwc_to_nchw(n->scratch_x, dx, g.B, g.Cin, g.H, g.W, S(stream));
 }
 int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dw, float* db,

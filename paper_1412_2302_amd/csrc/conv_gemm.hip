@@ -4,9 +4,13 @@
 
 namespace ax {
 
-typedef Tile<128, 128, 16, 2, 2> T128;
-typedef Tile<128, 96, 16, 4, 1> T96;
-typedef Tile<128, 64, 16, 4, 1> T64;
+#ifndef AX_BK
+#define AX_BK 16
+#endif
+constexpr int kBK = AX_BK;  // depth of a k-tile
+typedef Tile<128, 128, kBK, 2, 2> T128;
+typedef Tile<128, 96, kBK, 4, 1> T96;
+typedef Tile<128, 64, kBK, 4, 1> T64;
 
 // Width of the N tile that wastes the fewest padded columns (ties: wider).
 static int pick_bn(int N) {
@@ -23,11 +27,10 @@ static int pick_bn(int N) {
   return best;
 }
 
-static const int kTargetBlocks = 512;  // two workgroups per compute unit
 
-template <class T, template <int, int> class ALT, template <int, int> class BLT, class Epi>
-static int launch_tile(const typename ALT<T::BM, T::BK>::Params& ap, const typename BLT<T::BN, T::BK>::Params& bp,
-                       const Epi& ep, int M, int N, int K, int kchunk, int nsplit, int groups, hipStream_t st) {
+template <class T, class AL, class BL, class Epi>
+static int launch_tile(const typename AL::Params& ap, const typename BL::Params& bp, const Epi& ep, int M, int N, int K,
+                       int kchunk, int nsplit, int groups, hipStream_t st) {
   if (M <= 0 || N <= 0) return ALEXNET_OK;
   dim3 grid(ceil_div(M, T::BM), ceil_div(N, T::BN), groups * nsplit);
   if (grid.y > 65535 || grid.z > 65535) {
@@ -35,62 +38,191 @@ static int launch_tile(const typename ALT<T::BM, T::BK>::Params& ap, const typen
     return ALEXNET_ESHAPE;
   }
   KernelScope ks("gemm", 2.0 * M * N * (double)K * groups, 0, st);
-  hipLaunchKernelGGL((gemm_kernel<T, ALT<T::BM, T::BK>, BLT<T::BN, T::BK>, Epi>), grid, dim3(kThreads), 0, st, ap, bp,
-                     ep, M, N, K, kchunk, nsplit);
+  hipLaunchKernelGGL((gemm_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), 0, st, ap, bp, ep, M, N, K, kchunk, nsplit);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
 
-template <template <int, int> class ALT, template <int, int> class BLT, class AP, class BP, class Epi>
-static int launch_any(int bn, const AP& ap, const BP& bp, const Epi& ep, int M, int N, int K, int kchunk, int nsplit,
-                      int groups, hipStream_t st) {
+static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// One struct per GEMM flavour: names the loaders for a tile and a pair of
+// vector/scalar choices, so that the dispatch below stays a table.
+template <int MODE>
+struct ConvGather {  // rows = pixels (forward, backward-data)
+  template <class T, bool AV, bool BV, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile<T, Im2colKInner<T::BM, T::BK, AV, MODE>, DenseRowInner<T::BN, T::BK, BV>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+struct ConvWeightGrad {  // rows = taps (backward-weight)
+  template <class T, bool AV, bool BV, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile<T, Im2colRowInner<T::BM, T::BK, AV>, DenseRowInner<T::BN, T::BK, BV>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+
+// vector loads on both operands, on B only, or on neither
+template <class F, class T, class Epi>
+static int by_vec(bool av, bool bv, const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d,
+                  int kchunk, int ns, hipStream_t st) {
+  if (av && bv) return F::template go<T, true, true, Epi>(a, b, e, d, kchunk, ns, st);
+  if (bv) return F::template go<T, false, true, Epi>(a, b, e, d, kchunk, ns, st);
+  return F::template go<T, false, false, Epi>(a, b, e, d, kchunk, ns, st);
+}
+template <class F, class Epi>
+static int by_tile(int bn, bool av, bool bv, const Im2colParams& a, const DenseParams& b, const Epi& e,
+                   const GemmDims& d, int kchunk, int ns, hipStream_t st) {
   switch (bn) {
-    case 128: return launch_tile<T128, ALT, BLT, Epi>(ap, bp, ep, M, N, K, kchunk, nsplit, groups, st);
-    case 96: return launch_tile<T96, ALT, BLT, Epi>(ap, bp, ep, M, N, K, kchunk, nsplit, groups, st);
-    default: return launch_tile<T64, ALT, BLT, Epi>(ap, bp, ep, M, N, K, kchunk, nsplit, groups, st);
+    case 128: return by_vec<F, T128, Epi>(av, bv, a, b, e, d, kchunk, ns, st);
+    case 96: return by_vec<F, T96, Epi>(av, bv, a, b, e, d, kchunk, ns, st);
+    default: return by_vec<F, T64, Epi>(av, bv, a, b, e, d, kchunk, ns, st);
   }
 }
 
-static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+// ---------------------------------------------------------------- split-k ---
+// A launch is as slow as its busiest compute unit.  With few output tiles (338
+// for a 21632 x 256 output) a third of the chip idles while the rest runs a
+// second tile, so the reduction is cut into `ns` slices whose partial tiles go
+// to slabs and are added by a finishing kernel in a fixed order.  ns minimises
+// a small cost model: rounds of tiles over 256 CUs plus the slab traffic.
+struct SplitPlan {
+  int ns, kchunk;
+};
+static SplitPlan choose_split(long tiles, int K, int bn, double out_bytes, int max_s) {
+  const int ktiles = ceil_div(K, kBK);
+  const double t_tile = 2.0 * 128 * bn * (double)ktiles * kBK / 0.43e12;  // one CU at ~70 % of its fp32 MFMA rate
+  SplitPlan best{1, ktiles * kBK};
+  double best_t = 1e30;
+  for (int s = 1; s <= max_s && s <= ktiles; ++s) {
+    const int per = ceil_div(ktiles, s);
+    const int real = ceil_div(ktiles, per);
+    if (real != s) continue;
+    if (s > 1 && per < 6) break;
+    const double rounds = (double)ceil_div(tiles * s, 256);
+    double t = rounds * t_tile * per / ktiles;
+    if (s > 1) t += (s + 1) * out_bytes / 2.5e12 + 6e-6;
+    if (t < best_t * 0.97) {  // prefer fewer slices unless clearly better
+      best_t = t;
+      best = SplitPlan{s, per * kBK};
+    }
+  }
+  return best;
+}
+
+// out[m][g*N + n] = post(sum_s ws[(g*ns + s)][m][n]); post = +bias, ReLU, or gate by a forward activation
+__global__ void slab_finish_kernel(const float* __restrict__ ws, int ns, int groups, long M, int N,
+                                   const float* __restrict__ bias, int relu, const float* __restrict__ gate,
+                                   float* __restrict__ out) {
+  const size_t total = (size_t)M * groups * N;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into out
+  if (i >= total) return;
+  const int col = (int)(i % ((size_t)groups * N));
+  const size_t m = i / ((size_t)groups * N);
+  const int g = col / N, n = col - g * N;
+  const size_t slab = (size_t)M * N;
+  const float* p = ws + (size_t)g * ns * slab + m * N + n;
+  float v = 0.f;
+  for (int k = 0; k < ns; ++k) v += p[(size_t)k * slab];
+  if (bias) v += bias[col];
+  if (relu) v = v > 0.f ? v : 0.f;
+  if (gate && !(gate[i] > 0.f)) v = 0.f;
+  out[i] = v;
+}
+static int launch_slab_finish(const float* ws, int ns, int groups, long M, int N, const float* bias, int relu,
+                              const float* gate, float* out, hipStream_t st) {
+  const size_t total = (size_t)M * groups * N;
+  KernelScope ks("slab_finish", 0, (double)total * 4.0 * (ns + 1 + (gate ? 1 : 0)), st);
+  hipLaunchKernelGGL(slab_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, groups, M, N, bias,
+                     relu, gate, out);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
 
 // ------------------------------------------------------------- convolution ---
-int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
-                    hipStream_t st) {
+static SplitPlan fwd_plan(const ConvGeom& c, int* bn) {
   const GemmDims d = fwd_dims(c);
-  EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
-  return launch_any<Im2colKInner, DenseRowInner>(pick_bn(d.N), fwd_A(c, x), fwd_B(c, wf), ep, d.M, d.N, d.K,
-                                                 round_up(d.K, 16), 1, d.groups, st);
+  *bn = pick_bn(d.N);
+  const long tiles = (long)ceil_div(d.M, 128) * ceil_div(d.N, *bn) * d.groups;
+  return choose_split(tiles, d.K, *bn, (double)c.out_elems() * 4, 8);
+}
+static SplitPlan bwdd_plan(const ConvGeom& c, int* bn) {
+  const GemmDims d = bwdd_dims(c);
+  *bn = pick_bn(d.N);
+  const long tiles = (long)ceil_div(d.M, 128) * ceil_div(d.N, *bn) * d.groups;
+  return choose_split(tiles, d.K, *bn, (double)c.in_elems() * 4, 8);
+}
+size_t conv_fwd_ws_floats(const ConvGeom& c) {
+  int bn;
+  const SplitPlan p = fwd_plan(c, &bn);
+  return p.ns > 1 ? (size_t)p.ns * c.out_elems() : 0;
+}
+size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
+  int bn;
+  const SplitPlan p = bwdd_plan(c, &bn);
+  return p.ns > 1 ? (size_t)p.ns * c.in_elems() : 0;
+}
+
+int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
+                    float* ws, hipStream_t st) {
+  const GemmDims d = fwd_dims(c);
+  int bn;
+  const SplitPlan p = fwd_plan(c, &bn);
+  const bool av = fwd_A_vec(c, x), bv = fwd_B_vec(c, wf);
+  if (p.ns == 1) {
+    EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
+    return by_tile<ConvGather<IM2COL_FWD>>(bn, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, p.kchunk, 1, st);
+  }
+  EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
+  AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(bn, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, p.kchunk, p.ns, st)));
+  return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st);
 }
 
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
-                         hipStream_t st) {
+                         float* ws, hipStream_t st) {
   const GemmDims d = bwdd_dims(c);
-  EpiGate ep{dx, c.Cin, gate, c.cg(), 0};
-  return launch_any<Im2colKInner, DenseRowInner>(pick_bn(d.N), bwdd_A(c, dy), bwdd_B(c, wb), ep, d.M, d.N, d.K,
-                                                 round_up(d.K, 16), 1, d.groups, st);
+  int bn;
+  const SplitPlan p = bwdd_plan(c, &bn);
+  const bool av = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb), bv = bwdd_B_vec(c, wb);
+  const Im2colParams a = bwdd_A(c, dy);
+  const DenseParams b = bwdd_B(c, wb);
+  if (p.ns == 1) {
+    EpiGate ep{dx, c.Cin, gate, c.cg(), 0};
+    if (c.stride == 1) return by_tile<ConvGather<IM2COL_T1>>(bn, av, bv, a, b, ep, d, p.kchunk, 1, st);
+    return by_tile<ConvGather<IM2COL_TS>>(bn, av, bv, a, b, ep, d, p.kchunk, 1, st);
+  }
+  EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
+  if (c.stride == 1)
+    AX_TRY((by_tile<ConvGather<IM2COL_T1>>(bn, av, bv, a, b, ep, d, p.kchunk, p.ns, st)));
+  else
+    AX_TRY((by_tile<ConvGather<IM2COL_TS>>(bn, av, bv, a, b, ep, d, p.kchunk, p.ns, st)));
+  return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, nullptr, 0, gate, dx, st);
 }
 
-static int bwdw_split(const ConvGeom& c, int* kchunk, int* bn) {
+static SplitPlan bwdw_plan(const ConvGeom& c, int* bn) {
   const GemmDims d = bwdw_dims(c);
   *bn = pick_bn(d.N);
   const long tiles = (long)ceil_div(d.M, 128) * ceil_div(d.N, *bn) * d.groups;
-  return plan_split(tiles, d.K, 16, kTargetBlocks, 256, kchunk);
+  return choose_split(tiles, d.K, *bn, (double)c.w_elems() * 4, 256);
 }
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
-  int kchunk, bn;
-  const int ns = bwdw_split(c, &kchunk, &bn);
-  return ns > 1 ? (size_t)ns * c.w_elems() : 0;
+  int bn;
+  const SplitPlan p = bwdw_plan(c, &bn);
+  return p.ns > 1 ? (size_t)p.ns * c.w_elems() : 0;
 }
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* ws,
                            hipStream_t st) {
   const GemmDims d = bwdw_dims(c);
-  int kchunk, bn;
-  const int ns = bwdw_split(c, &kchunk, &bn);
+  int bn;
+  const SplitPlan p = bwdw_plan(c, &bn);
   const long slab = (long)d.M * d.N;
-  EpiSlab ep{ns > 1 ? ws : dwf, slab, d.N, nullptr};
-  AX_TRY((launch_any<Im2colRowInner, DenseRowInner>(bn, bwdw_A(c, x), bwdw_B(c, dy), ep, d.M, d.N, d.K, kchunk, ns,
-                                                    d.groups, st)));
-  if (ns > 1) AX_TRY(launch_reduce_slabs(ws, ns, slab, d.groups, dwf, st));
+  EpiSlab ep{p.ns > 1 ? ws : dwf, slab, d.N, nullptr};
+  AX_TRY((by_tile<ConvWeightGrad>(bn, bwdw_A_vec(c, x), bwdw_B_vec(c, dy), bwdw_A(c, x), bwdw_B(c, dy), ep, d,
+                                  p.kchunk, p.ns, st)));
+  if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, dwf, st));
   return ALEXNET_OK;
 }
 
@@ -101,7 +233,9 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
 
 static int fc_split(int B, int N, int K, int* kchunk) {
   const long tiles = (long)ceil_div(B, 128) * ceil_div(N, 128);
-  return plan_split(tiles, K, 16, kTargetBlocks / 2, 64, kchunk);
+  const SplitPlan p = choose_split(tiles, K, 128, (double)B * N * 4, 64);
+  *kchunk = p.kchunk;
+  return p.ns;
 }
 size_t fc_ws_floats(int B, int in, int out) {
   int kc;
@@ -135,14 +269,23 @@ __global__ void fc_bwd_finish_kernel(const float* __restrict__ ws, int nsplit, s
 
 static inline bool vec_ok(const float* p, long ld) { return aligned16(p) && ld % 4 == 0; }
 
+template <template <int, int, bool> class ALT, template <int, int, bool> class BLT>
+static int launch_dense(bool vec, const DenseParams& a, const DenseParams& b, const EpiSlab& ep, int M, int N, int K,
+                        int kchunk, int ns, hipStream_t st) {
+  if (vec)
+    return launch_tile<T128, ALT<128, kBK, true>, BLT<128, kBK, true>, EpiSlab>(a, b, ep, M, N, K, kchunk, ns, 1, st);
+  return launch_tile<T128, ALT<128, kBK, false>, BLT<128, kBK, false>, EpiSlab>(a, b, ep, M, N, K, kchunk, ns, 1, st);
+}
+
 int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const FcAct& act, float* y, float* ws,
                   hipStream_t st) {
   int kchunk;
   const int ns = fc_split(B, out, in, &kchunk);
-  DenseParams a{x, in, 0, B, vec_ok(x, in) ? 1 : 0};
-  DenseParams b{w, in, 0, out, vec_ok(w, in) ? 1 : 0};
+  DenseParams a{x, in, 0, B};
+  DenseParams b{w, in, 0, out};
   EpiSlab ep{ws, (long)B * out, out, nullptr};
-  AX_TRY((launch_tile<T128, DenseKInner, DenseKInner, EpiSlab>(a, b, ep, B, out, in, kchunk, ns, 1, st)));
+  // both operands run along k = in
+  AX_TRY((launch_dense<DenseKInner, DenseKInner>(vec_ok(x, in) && vec_ok(w, in), a, b, ep, B, out, in, kchunk, ns, st)));
   const size_t total = (size_t)B * out;
   KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1), st);
   hipLaunchKernelGGL(fc_fwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, B, out, act, y);
@@ -154,10 +297,12 @@ int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, 
                        float* ws, hipStream_t st) {
   int kchunk;
   const int ns = fc_split(B, in, out, &kchunk);
-  DenseParams a{dy, out, 0, B, vec_ok(dy, out) ? 1 : 0};
-  DenseParams b{w, in, 0, in, vec_ok(w, in) ? 1 : 0};
+  DenseParams a{dy, out, 0, B};
+  DenseParams b{w, in, 0, in};
   EpiSlab ep{ws, (long)B * in, in, nullptr};
-  AX_TRY((launch_tile<T128, DenseKInner, DenseRowInner, EpiSlab>(a, b, ep, B, in, out, kchunk, ns, 1, st)));
+  // A runs along k = out, B along its rows = in
+  AX_TRY((launch_dense<DenseKInner, DenseRowInner>(vec_ok(dy, out) && vec_ok(w, in), a, b, ep, B, in, out, kchunk, ns,
+                                                  st)));
   const size_t total = (size_t)B * in;
   KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1 + (gate ? 1 : 0)), st);
   hipLaunchKernelGGL(fc_bwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, total, gate, dx);
@@ -166,10 +311,11 @@ int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, 
 }
 
 int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy, float* dw, hipStream_t st) {
-  DenseParams a{dy, out, 0, out, vec_ok(dy, out) ? 1 : 0};
-  DenseParams b{x, in, 0, in, vec_ok(x, in) ? 1 : 0};
+  DenseParams a{dy, out, 0, out};
+  DenseParams b{x, in, 0, in};
   EpiSlab ep{dw, (long)out * in, in, nullptr};
-  return launch_tile<T128, DenseRowInner, DenseRowInner, EpiSlab>(a, b, ep, out, in, B, round_up(B, 16), 1, 1, st);
+  return launch_dense<DenseRowInner, DenseRowInner>(vec_ok(dy, out) && vec_ok(x, in), a, b, ep, out, in, B,
+                                                    round_up(B, kBK), 1, st);
 }
 
 }  // namespace ax

@@ -35,52 +35,60 @@ struct GemmDims {
   int M, N, K, groups;
 };
 
+inline void fill_divs(Im2colParams& a) {
+  a.d_cg = make_fastdiv((uint32_t)a.Cg);
+  a.d_kw = make_fastdiv((uint32_t)a.kw);
+  a.d_ohw = make_fastdiv((uint32_t)(a.OH * a.OW));
+  a.d_ow = make_fastdiv((uint32_t)a.OW);
+  a.d_stride = make_fastdiv((uint32_t)a.stride);
+}
+
 // ---- forward ----
 inline GemmDims fwd_dims(const ConvGeom& c) { return {(int)c.P(), c.og(), c.kf(), c.groups}; }
 inline Im2colParams fwd_A(const ConvGeom& c, const float* x) {
   Im2colParams a;
   a.x = x; a.H = c.H; a.W = c.W; a.Ctot = c.Cin; a.Cg = c.cg(); a.c_stride_g = c.cg();
-  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad; a.transposed = 0;
+  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad;
   a.OH = c.Ho; a.OW = c.Wo; a.P = (int)c.P();
-  a.vec = (c.cg() % 4 == 0 && c.Cin % 4 == 0 && aligned16(x)) ? 1 : 0;
+  fill_divs(a);
   return a;
 }
+inline bool fwd_A_vec(const ConvGeom& c, const float* x) { return c.cg() % 4 == 0 && c.Cin % 4 == 0 && aligned16(x); }
 inline DenseParams fwd_B(const ConvGeom& c, const float* wf) {
   DenseParams b;
   b.p = wf; b.ld = c.og(); b.gstride = (long)c.kf() * c.og(); b.R = c.og();
-  b.vec = (c.og() % 4 == 0 && aligned16(wf)) ? 1 : 0;
   return b;
 }
+inline bool fwd_B_vec(const ConvGeom& c, const float* wf) { return c.og() % 4 == 0 && aligned16(wf); }
 
 // ---- backward data ----
 inline GemmDims bwdd_dims(const ConvGeom& c) { return {(int)c.Q(), c.cg(), c.kb(), c.groups}; }
 inline Im2colParams bwdd_A(const ConvGeom& c, const float* dy) {
   Im2colParams a;
   a.x = dy; a.H = c.Ho; a.W = c.Wo; a.Ctot = c.Cout; a.Cg = c.og(); a.c_stride_g = c.og();
-  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad; a.transposed = 1;
+  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad;
   a.OH = c.H; a.OW = c.W; a.P = (int)c.Q();
-  a.vec = (c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy)) ? 1 : 0;
+  fill_divs(a);
   return a;
 }
+inline bool bwdd_A_vec(const ConvGeom& c, const float* dy) { return c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy); }
 inline DenseParams bwdd_B(const ConvGeom& c, const float* wb) {
   DenseParams b;
   b.p = wb; b.ld = c.cg(); b.gstride = (long)c.kb() * c.cg(); b.R = c.cg();
-  b.vec = (c.cg() % 4 == 0 && aligned16(wb)) ? 1 : 0;
   return b;
 }
+inline bool bwdd_B_vec(const ConvGeom& c, const float* wb) { return c.cg() % 4 == 0 && aligned16(wb); }
 
 // ---- backward weight ----
 inline GemmDims bwdw_dims(const ConvGeom& c) { return {c.kf(), c.og(), (int)c.P(), c.groups}; }
-inline Im2colParams bwdw_A(const ConvGeom& c, const float* x) {
-  Im2colParams a = fwd_A(c, x);
-  return a;
-}
+inline Im2colParams bwdw_A(const ConvGeom& c, const float* x) { return fwd_A(c, x); }
+inline bool bwdw_A_vec(const ConvGeom& c, const float* x) { return fwd_A_vec(c, x); }
 inline DenseParams bwdw_B(const ConvGeom& c, const float* dy) {
   DenseParams b;
   b.p = dy; b.ld = c.Cout; b.gstride = c.og(); b.R = c.og();
-  b.vec = (c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy)) ? 1 : 0;
   return b;
 }
+inline bool bwdw_B_vec(const ConvGeom& c, const float* dy) { return c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy); }
 
 // Split of the reduction so that a launch has enough workgroups: returns the
 // number of splits and sets kchunk (a multiple of bk).

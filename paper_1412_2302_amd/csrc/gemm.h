@@ -14,14 +14,27 @@
 //   DenseRowInner   elem(row,k) = p[k*ld + row]      (contiguous along rows)
 //   Im2colKInner    rows = output pixels, k = (r,s,c): the implicit im2col
 //                   matrix of a channel-last activation tensor (convolution
-//                   forward, and backward-data when `transposed` is set)
+//                   forward, and backward-data in its transposed modes)
 //   Im2colRowInner  rows = (r,s,c), k = output pixels: its transpose
 //                   (convolution backward-weight)
 // Every loader zero-fills outside the operand, so ragged tiles need no care
-// in the MFMA loop.  Everything here is also compiled for the host by the
-// CPU emulation test (AX_HOST_EMU), which is why loaders and epilogues are
-// plain structs with host+device members.
+// in the MFMA loop.  Loads are predicated, never branched around: an element
+// outside the operand reads the operand's first element and is then replaced
+// by zero, which keeps the k-loop one straight-line block that the compiler
+// can software-pipeline.  Index decoding uses multiply-shift division by
+// launch constants.  A loader works in steps that the kernel places one by one:
+// addr_step<S>() computes offsets and predicates of a later k-tile (pure VALU
+// work), fetch<SET>() issues its global loads into one of two register sets,
+// store_step<SET>(s) zeroes what was outside the operand and writes one load
+// to LDS.  VEC selects 16-byte loads (legal only when the launcher
+// has checked alignment and divisibility) or four 4-byte loads.
+//
+// Everything here is also compiled for the host by the CPU emulation test
+// (AX_HOST_EMU), which is why loaders and epilogues are plain structs with
+// host+device members.
 #pragma once
+
+#include <stdint.h>
 
 #ifndef AX_HOST_EMU
 #include <hip/hip_runtime.h>
@@ -51,7 +64,38 @@ AX_HD float4 zero4() {
   return v;
 }
 AX_HD float4 ld4(const float* q) { return *reinterpret_cast<const float4*>(q); }
-AX_HD float& at4(float4& v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
+// ---- division by a launch constant -------------------------------------------
+// q = n / d for 0 <= n < 2^31:  umulhi(n, mul) >> shift, mul = ceil(2^(31+l)/d),
+// l = ceil(log2 d), shift = l - 1; d == 1 is handled by mul == 0.
+struct FastDiv {
+  uint32_t mul, shift, d;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  if (d <= 1) {
+    f.mul = 0;
+    f.shift = 0;
+    return f;
+  }
+  uint32_t l = 0;
+  while ((1u << l) < d) ++l;
+  const uint64_t num = 1ull << (31 + l);
+  f.mul = (uint32_t)((num + d - 1) / d);
+  f.shift = l - 1;
+  return f;
+}
+AX_HD uint32_t umulhi32(uint32_t a, uint32_t b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __umulhi(a, b);
+#else
+  return (uint32_t)(((uint64_t)a * b) >> 32);
+#endif
+}
+AX_HD uint32_t fdiv(uint32_t n, const FastDiv& f) {
+  const uint32_t q = umulhi32(n, f.mul) >> f.shift;
+  return f.mul ? q : n;
+}
 
 // ---- fragment and accumulator index maps of v_mfma_f32_32x32x2_f32 ---------
 // A/B fragment for k-pair kk: lane reads tile[(2*kk + lane/32)][base + lane%32].
@@ -66,276 +110,309 @@ struct DenseParams {
   long ld;       // leading dimension in floats
   long gstride;  // added per group
   int R;         // number of valid rows
-  int vec;       // 1: 16-byte loads are legal (alignment and divisibility checked by the launcher)
 };
 
-template <int ROWS, int BK>
+// Per-thread bookkeeping shared by all loaders.  A thread makes NL loads per
+// k-tile (16 bytes each when VEC, else four 4-byte loads).  `off`/`okn` describe
+// the tile that will be fetched next; two register sets can be in flight, and
+// ok[set] remembers which of their elements were inside the operand.
+template <int NL_, bool VEC>
+struct PlanRegs {
+  static constexpr int NL = NL_, NE = VEC ? NL : 4 * NL;
+  uint32_t off[NE];
+  uint32_t okn;
+  uint32_t ok[2];
+  AX_HD void put(int e, uint32_t o, bool good) {
+    off[e] = good ? o : 0u;  // an element outside reads element 0 and is zeroed when stored
+    okn |= (uint32_t)good << e;
+  }
+  template <int SET>
+  AX_HD void fetch(const float* p, float4* r) {
+    ok[SET] = okn;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      if (VEC) {
+        r[i] = *reinterpret_cast<const float4*>(p + off[i]);
+      } else {
+        r[i].x = p[off[4 * i]];
+        r[i].y = p[off[4 * i + 1]];
+        r[i].z = p[off[4 * i + 2]];
+        r[i].w = p[off[4 * i + 3]];
+      }
+    }
+  }
+  template <int SET>
+  AX_HD float4 masked(const float4& v, int i) const {
+    const uint32_t m = ok[SET] >> (VEC ? i : 4 * i);
+    float4 o;
+    o.x = (m & 1u) ? v.x : 0.f;
+    o.y = (VEC ? (m & 1u) : (m & 2u)) ? v.y : 0.f;
+    o.z = (VEC ? (m & 1u) : (m & 4u)) ? v.z : 0.f;
+    o.w = (VEC ? (m & 1u) : (m & 8u)) ? v.w : 0.f;
+    return o;
+  }
+};
+// four floats that are consecutive in k go to four LDS rows
+AX_HD void lds_put_k4(float* d, int ldt, const float4& v) {
+  d[0] = v.x;
+  d[ldt] = v.y;
+  d[2 * ldt] = v.z;
+  d[3 * ldt] = v.w;
+}
+
+template <int ROWS, int BK, bool VEC>
 struct DenseKInner {
-  static constexpr int QK = BK / 4, NQ = ROWS * QK, NL = (NQ + kThreads - 1) / kThreads;
+  static constexpr int QK = BK / 4, NQ = ROWS * QK, NL = NQ / kThreads, NA = NL;
+  static_assert(NQ % kThreads == 0, "tile must be a whole number of loads per thread");
   typedef DenseParams Params;
   const float* p;
-  long ld;
-  int R, vec, tid, row0;
+  uint32_t ld;
+  int R, tid, row0;
+  PlanRegs<NL, VEC> pl;
   AX_HD DenseKInner(const Params& a, int g, int tid_, int row0_)
-      : p(a.p + (long)g * a.gstride), ld(a.ld), R(a.R), vec(a.vec), tid(tid_), row0(row0_) {}
-  AX_HD void load(int k0, int kend, float4* r) const {
+      : p(a.p + (long)g * a.gstride), ld((uint32_t)a.ld), R(a.R), tid(tid_), row0(row0_) {}
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    if (S == 0) pl.okn = 0;
+    const int idx = tid + S * kThreads;
+    const int row = row0 + idx / QK, k = k0 + 4 * (idx % QK);
+    const bool rok = row < R;
+    const uint32_t off = (uint32_t)row * ld + (uint32_t)k;
+    if (VEC) {
+      pl.put(S, off, rok && k < kend);
+    } else {
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      float4 v = zero4();
-      if (idx < NQ) {
-        const int row = row0 + idx / QK, k = k0 + 4 * (idx % QK);
-        if (row < R && k < kend) {
-          const float* q = p + (long)row * ld + k;
-          if (vec && k + 3 < kend) {
-            v = ld4(q);
-          } else {
-            v.x = q[0];
-            if (k + 1 < kend) v.y = q[1];
-            if (k + 2 < kend) v.z = q[2];
-            if (k + 3 < kend) v.w = q[3];
-          }
-        }
-      }
-      r[i] = v;
+      for (int j = 0; j < 4; ++j) pl.put(4 * S + j, off + j, rok && k + j < kend);
     }
   }
-  AX_HD void store(float* lds, int ldt, const float4* r) const {
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      if (idx < NQ) {
-        float* d = lds + (4 * (idx % QK)) * ldt + idx / QK;
-        d[0] = r[i].x;
-        d[ldt] = r[i].y;
-        d[2 * ldt] = r[i].z;
-        d[3 * ldt] = r[i].w;
-      }
-    }
+  template <int SET>
+  AX_HD void fetch(float4* r) { pl.template fetch<SET>(p, r); }
+  template <int SET>
+  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
+    const int idx = tid + s * kThreads;
+    lds_put_k4(lds + (4 * (idx % QK)) * ldt + idx / QK, ldt, pl.template masked<SET>(r[s], s));
   }
 };
 
-template <int ROWS, int BK>
+template <int ROWS, int BK, bool VEC>
 struct DenseRowInner {
-  static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = (NQ + kThreads - 1) / kThreads;
+  static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = (NQ + kThreads - 1) / kThreads, NA = NL;
+  static constexpr bool kWhole = NQ % kThreads == 0;  // else the last load of some threads is outside the tile
   typedef DenseParams Params;
   const float* p;
-  long ld;
-  int R, vec, tid, row0;
+  uint32_t ld;
+  int R, tid, row0;
+  PlanRegs<NL, VEC> pl;
   AX_HD DenseRowInner(const Params& a, int g, int tid_, int row0_)
-      : p(a.p + (long)g * a.gstride), ld(a.ld), R(a.R), vec(a.vec), tid(tid_), row0(row0_) {}
-  AX_HD void load(int k0, int kend, float4* r) const {
+      : p(a.p + (long)g * a.gstride), ld((uint32_t)a.ld), R(a.R), tid(tid_), row0(row0_) {}
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    if (S == 0) pl.okn = 0;
+    const int idx = tid + S * kThreads;
+    const int row = row0 + 4 * (idx % QR), k = k0 + idx / QR;
+    const bool kok = k < kend && (kWhole || idx < NQ);
+    const uint32_t off = (uint32_t)k * ld + (uint32_t)row;
+    if (VEC) {
+      pl.put(S, off, kok && row < R);
+    } else {
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      float4 v = zero4();
-      if (idx < NQ) {
-        const int row = row0 + 4 * (idx % QR), k = k0 + idx / QR;
-        if (k < kend && row < R) {
-          const float* q = p + (long)k * ld + row;
-          if (vec && row + 3 < R) {
-            v = ld4(q);
-          } else {
-            v.x = q[0];
-            if (row + 1 < R) v.y = q[1];
-            if (row + 2 < R) v.z = q[2];
-            if (row + 3 < R) v.w = q[3];
-          }
-        }
-      }
-      r[i] = v;
+      for (int j = 0; j < 4; ++j) pl.put(4 * S + j, off + j, kok && row + j < R);
     }
   }
-  AX_HD void store(float* lds, int ldt, const float4* r) const {
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      if (idx < NQ) *reinterpret_cast<float4*>(lds + (idx / QR) * ldt + 4 * (idx % QR)) = r[i];
-    }
+  template <int SET>
+  AX_HD void fetch(float4* r) { pl.template fetch<SET>(p, r); }
+  template <int SET>
+  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
+    const int idx = tid + s * kThreads;
+    if (kWhole || idx < NQ)
+      *reinterpret_cast<float4*>(lds + (idx / QR) * ldt + 4 * (idx % QR)) = pl.template masked<SET>(r[s], s);
   }
 };
 
 // Geometry of an implicit im2col operand over a channel-last tensor
 // x[N][H][W][Ctot].  Pixels (n, y, x) run over an OH x OW grid; tap (r, s)
 // of pixel (y, x) reads x[n][iy][ix][c_off + c] with
-//   forward:     iy = y*stride - pad + r
-//   transposed:  iy = (y + pad - r)/stride, only where that division is exact
-// (the gather form of the adjoint of a strided convolution).
+//   mode 0 (forward):            iy = y*stride - pad + r
+//   mode 1 (transposed, unit):   iy = y + pad - r                    (stride 1)
+//   mode 2 (transposed, strided) iy = (y + pad - r)/stride, only where exact
+// (modes 1 and 2 are the gather form of the adjoint of a convolution).
 struct Im2colParams {
   const float* x;
   int H, W, Ctot;   // tensor being gathered from
   int Cg;           // channels per group (extent of c)
   int c_stride_g;   // channel offset added per group
-  int kh, kw, stride, pad, transposed;
+  int kh, kw, stride, pad;
   int OH, OW;       // pixel grid
   int P;            // number of pixels = N*OH*OW
-  int vec;          // 1: Cg % 4 == 0, Ctot % 4 == 0, aligned base
+  FastDiv d_cg, d_kw, d_ohw, d_ow, d_stride;
 };
+enum { IM2COL_FWD = 0, IM2COL_T1 = 1, IM2COL_TS = 2 };
 
 struct TapCoord {
   int r, s, c;
 };
-AX_HD TapCoord decode_tap(int k, int Cg, int kw) {
+AX_HD TapCoord decode_tap(int k, const Im2colParams& g) {
   TapCoord t;
-  const int rs = k / Cg;
-  t.c = k - rs * Cg;
-  t.r = rs / kw;
-  t.s = rs - t.r * kw;
+  const int rs = (int)fdiv((uint32_t)k, g.d_cg);
+  t.c = k - rs * g.Cg;
+  t.r = (int)fdiv((uint32_t)rs, g.d_kw);
+  t.s = rs - t.r * g.kw;
   return t;
 }
-// returns the pixel offset iy*W + ix or -1 when the tap falls outside
-AX_HD int tap_offset(const Im2colParams& g, int y0, int x0, int r, int s) {
+struct PixCoord {
+  int n, y, x;
+};
+AX_HD PixCoord decode_pixel(int p, const Im2colParams& g) {
+  PixCoord c;
+  c.n = (int)fdiv((uint32_t)p, g.d_ohw);
+  const int rem = p - c.n * (g.OH * g.OW);
+  c.y = (int)fdiv((uint32_t)rem, g.d_ow);
+  c.x = rem - c.y * g.OW;
+  return c;
+}
+// pixel offset iy*W + ix of tap (r,s) seen from origin (y0,x0); ok = inside the tensor
+template <int MODE>
+AX_HD uint32_t tap_offset(const Im2colParams& g, int y0, int x0, int r, int s, bool& ok) {
   int iy, ix;
-  if (!g.transposed) {
+  if (MODE == IM2COL_FWD) {
     iy = y0 + r;
     ix = x0 + s;
+    ok = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
+  } else if (MODE == IM2COL_T1) {
+    iy = y0 - r;
+    ix = x0 - s;
+    ok = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
   } else {
     const int ty = y0 - r, tx = x0 - s;
-    if (ty < 0 || tx < 0) return -1;
-    if (g.stride == 1) {
-      iy = ty;
-      ix = tx;
-    } else {
-      iy = ty / g.stride;
-      ix = tx / g.stride;
-      if (iy * g.stride != ty || ix * g.stride != tx) return -1;
-    }
+    const bool pos = ty >= 0 && tx >= 0;
+    iy = (int)fdiv((uint32_t)(pos ? ty : 0), g.d_stride);
+    ix = (int)fdiv((uint32_t)(pos ? tx : 0), g.d_stride);
+    ok = pos && iy * g.stride == ty && ix * g.stride == tx && iy < g.H && ix < g.W;
   }
-  if (iy < 0 || iy >= g.H || ix < 0 || ix >= g.W) return -1;
-  return iy * g.W + ix;
+  return (uint32_t)iy * (uint32_t)g.W + (uint32_t)ix;  // unsigned: wraps harmlessly when the tap is outside
 }
 constexpr int kInvalidCoord = -(1 << 28);
 
-template <int ROWS, int BK>
+template <int ROWS, int BK, bool VEC, int MODE>
 struct Im2colKInner {
-  static constexpr int QK = BK / 4, NQ = ROWS * QK, NL = (NQ + kThreads - 1) / kThreads;
-  static_assert(kThreads % QK == 0, "every load of a thread must share its k quad");
+  static constexpr int QK = BK / 4, NQ = ROWS * QK, NL = NQ / kThreads, NA = NL + 1;
+  static_assert(kThreads % QK == 0 && NQ % kThreads == 0, "every load of a thread shares its k quad");
   typedef Im2colParams Params;
   Im2colParams g;
   int c_off, tid, kq;
-  long nb[NL];
+  uint32_t nb[NL];  // pixel index of (n, 0, 0)
   int y0[NL], x0[NL];
+  TapCoord tap[VEC ? 1 : 4];
+  uint32_t kok;
+  PlanRegs<NL, VEC> pl;
   AX_HD Im2colKInner(const Params& a, int grp, int tid_, int row0) : g(a), c_off(grp * a.c_stride_g), tid(tid_) {
     kq = tid % QK;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      const int p = row0 + idx / QK;
-      nb[i] = 0;
-      y0[i] = x0[i] = kInvalidCoord;
-      if (idx < NQ && p < g.P) {
-        const int n = p / (g.OH * g.OW), rem = p - n * (g.OH * g.OW);
-        const int y = rem / g.OW, x = rem - y * g.OW;
-        nb[i] = (long)n * g.H * g.W;
-        y0[i] = g.transposed ? y + g.pad : y * g.stride - g.pad;
-        x0[i] = g.transposed ? x + g.pad : x * g.stride - g.pad;
+      const int p = row0 + (tid + i * kThreads) / QK;
+      const bool in = p < g.P;
+      const PixCoord c = decode_pixel(in ? p : 0, g);
+      nb[i] = (uint32_t)c.n * (uint32_t)(g.H * g.W);
+      if (MODE == IM2COL_FWD) {
+        y0[i] = in ? c.y * g.stride - g.pad : kInvalidCoord;
+        x0[i] = c.x * g.stride - g.pad;
+      } else {
+        // rows past the end get an origin whose every tap is above the tensor
+        y0[i] = in ? c.y + g.pad : -1;
+        x0[i] = c.x + g.pad;
       }
     }
   }
-  AX_HD void load(int k0, int kend, float4* r) const {
+  // step 0 decodes the taps of the thread's k quad, step 1+i places load i
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
     const int k = k0 + 4 * kq;
-    if (g.vec) {
-      const TapCoord t = decode_tap(k, g.Cg, g.kw);
+    if (S == 0) {
+      pl.okn = 0;
+      kok = 0;
 #pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        float4 v = zero4();
-        if (k < kend && y0[i] != kInvalidCoord) {
-          const int off = tap_offset(g, y0[i], x0[i], t.r, t.s);
-          if (off >= 0) v = ld4(g.x + (nb[i] + off) * g.Ctot + c_off + t.c);
-        }
-        r[i] = v;
+      for (int j = 0; j < (VEC ? 1 : 4); ++j) {
+        tap[j] = decode_tap(k + j, g);
+        kok |= (uint32_t)(k + j < kend) << j;
       }
     } else {
+      constexpr int i = S - 1;
 #pragma unroll
-      for (int i = 0; i < NL; ++i) r[i] = zero4();
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (k + j >= kend) continue;
-        const TapCoord t = decode_tap(k + j, g.Cg, g.kw);
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-          if (y0[i] == kInvalidCoord) continue;
-          const int off = tap_offset(g, y0[i], x0[i], t.r, t.s);
-          if (off >= 0) at4(r[i], j) = g.x[(nb[i] + off) * g.Ctot + c_off + t.c];
-        }
+      for (int j = 0; j < (VEC ? 1 : 4); ++j) {
+        bool ok;
+        const uint32_t po = tap_offset<MODE>(g, y0[i], x0[i], tap[j].r, tap[j].s, ok);
+        const uint32_t off = (nb[i] + po) * (uint32_t)g.Ctot + (uint32_t)(c_off + tap[j].c);
+        pl.put(VEC ? i : 4 * i + j, off, ok && ((kok >> j) & 1u));
       }
     }
   }
-  AX_HD void store(float* lds, int ldt, const float4* r) const {
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      if (idx < NQ) {
-        float* d = lds + (4 * kq) * ldt + idx / QK;
-        d[0] = r[i].x;
-        d[ldt] = r[i].y;
-        d[2 * ldt] = r[i].z;
-        d[3 * ldt] = r[i].w;
-      }
-    }
+  template <int SET>
+  AX_HD void fetch(float4* r) { pl.template fetch<SET>(g.x, r); }
+  template <int SET>
+  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
+    lds_put_k4(lds + (4 * kq) * ldt + (tid + s * kThreads) / QK, ldt, pl.template masked<SET>(r[s], s));
   }
 };
 
-template <int ROWS, int BK>
+template <int ROWS, int BK, bool VEC>
 struct Im2colRowInner {
-  static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = (NQ + kThreads - 1) / kThreads;
-  static_assert(kThreads % QR == 0, "every load of a thread must share its row quad");
+  static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = NQ / kThreads, NA = NL;
+  static_assert(kThreads % QR == 0 && NQ % kThreads == 0, "every load of a thread shares its row quad");
   typedef Im2colParams Params;
   Im2colParams g;
   int c_off, tid, rq;
-  int rr[4], ss[4], cc[4];  // taps of the thread's four rows; cc < 0 marks a row past the end
+  int rr[VEC ? 1 : 4], ss[VEC ? 1 : 4], cc[VEC ? 1 : 4];  // taps of the thread's rows; rr = kInvalidCoord past the end
+  PlanRegs<NL, VEC> pl;
   AX_HD Im2colRowInner(const Params& a, int grp, int tid_, int row0) : g(a), c_off(grp * a.c_stride_g), tid(tid_) {
     rq = tid % QR;
     const int rtot = g.kh * g.kw * g.Cg;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < (VEC ? 1 : 4); ++j) {
       const int m = row0 + 4 * rq + j;
-      rr[j] = ss[j] = 0;
-      cc[j] = -1;
-      if (m < rtot) {
-        const TapCoord t = decode_tap(m, g.Cg, g.kw);
-        rr[j] = t.r;
-        ss[j] = t.s;
-        cc[j] = t.c;
-      }
+      const bool in = m < rtot;
+      const TapCoord t = decode_tap(in ? m : 0, g);
+      rr[j] = in ? t.r : kInvalidCoord;  // pushes every tap above the tensor
+      ss[j] = t.s;
+      cc[j] = t.c;
     }
   }
-  AX_HD void load(int k0, int kend, float4* r) const {
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    if (S == 0) pl.okn = 0;
+    const int p = k0 + (tid + S * kThreads) / QR;
+    const bool pok = p < kend;
+    const PixCoord c = decode_pixel(pok ? p : 0, g);
+    const uint32_t nbase = (uint32_t)c.n * (uint32_t)(g.H * g.W);
+    const int y0 = c.y * g.stride - g.pad, x0 = c.x * g.stride - g.pad;
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      float4 v = zero4();
-      const int p = k0 + idx / QR;
-      if (idx < NQ && p < kend) {
-        const int n = p / (g.OH * g.OW), rem = p - n * (g.OH * g.OW);
-        const int y = rem / g.OW, x = rem - y * g.OW;
-        const long nbase = (long)n * g.H * g.W;
-        const int y0 = y * g.stride - g.pad, x0 = x * g.stride - g.pad;
-        if (g.vec) {
-          if (cc[0] >= 0) {
-            const int off = tap_offset(g, y0, x0, rr[0], ss[0]);
-            if (off >= 0) v = ld4(g.x + (nbase + off) * g.Ctot + c_off + cc[0]);
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (cc[j] < 0) continue;
-            const int off = tap_offset(g, y0, x0, rr[j], ss[j]);
-            if (off >= 0) at4(v, j) = g.x[(nbase + off) * g.Ctot + c_off + cc[j]];
-          }
-        }
-      }
-      r[i] = v;
+    for (int j = 0; j < (VEC ? 1 : 4); ++j) {
+      bool ok;
+      const uint32_t po = tap_offset<IM2COL_FWD>(g, y0, x0, rr[j], ss[j], ok);
+      const uint32_t off = (nbase + po) * (uint32_t)g.Ctot + (uint32_t)(c_off + cc[j]);
+      pl.put(VEC ? S : 4 * S + j, off, ok && pok);
     }
   }
-  AX_HD void store(float* lds, int ldt, const float4* r) const {
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int idx = tid + i * kThreads;
-      if (idx < NQ) *reinterpret_cast<float4*>(lds + (idx / QR) * ldt + 4 * rq) = r[i];
-    }
+  template <int SET>
+  AX_HD void fetch(float4* r) { pl.template fetch<SET>(g.x, r); }
+  template <int SET>
+  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
+    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QR) * ldt + 4 * rq) = pl.template masked<SET>(r[s], s);
   }
 };
+
+// Whole-tile helpers (prologue of the kernel, CPU emulation).
+template <class L, int S = 0>
+AX_HD void plan_all(L& l, int k0, int kend) {
+  if constexpr (S < L::NA) {
+    l.template addr_step<S>(k0, kend);
+    plan_all<L, S + 1>(l, k0, kend);
+  }
+}
+template <int SET, class L>
+AX_HD void store_all(const L& l, float* lds, int ldt, const float4* r) {
+#pragma unroll
+  for (int s = 0; s < L::NL; ++s) l.template store_step<SET>(s, lds, ldt, r);
+}
 
 // ================================ epilogues ==================================
 // apply(m, n, v) is called once per valid element of the tile.
@@ -382,6 +459,83 @@ struct EpiSlab {
 #ifndef AX_HOST_EMU
 typedef float v16f __attribute__((ext_vector_type(16)));
 
+// ---- the k-tile: MFMAs with the rest of the pipeline in their shadow ----------
+// While the MFMAs of tile t run, the same wave (a) writes tile t+1, which was
+// fetched one iteration ago, to the other LDS buffer and (b) computes the
+// addresses of tile t+3.  That side work is cut into steps and dealt out over
+// the k-pairs of the tile; a scheduling fence after every k-pair keeps each
+// portion in the shadow of that pair's MFMAs instead of in one lump after them.
+template <class T, class AL, class BL, int SET, int IDX>
+__device__ __forceinline__ void side_step(AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
+                                          const float4* rb, int k_plan, int kend) {
+  constexpr int S0 = AL::NL, S1 = S0 + BL::NL, S2 = S1 + AL::NA, S3 = S2 + BL::NA;
+  if constexpr (IDX < S0) {
+    al.template store_step<SET>(IDX, as_next, T::LDA, ra);
+  } else if constexpr (IDX < S1) {
+    bl.template store_step<SET>(IDX - S0, bs_next, T::LDB, rb);
+  } else if constexpr (IDX < S2) {
+    al.template addr_step<IDX - S1>(k_plan, kend);
+  } else if constexpr (IDX < S3) {
+    bl.template addr_step<IDX - S2>(k_plan, kend);
+  }
+}
+template <class T, class AL, class BL, int SET, int Q, int U = 0>
+__device__ __forceinline__ void side_slot(AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
+                                          const float4* rb, int k_plan, int kend) {
+  constexpr int TOTAL = AL::NL + BL::NL + AL::NA + BL::NA, KP = T::BK / 2, PER = (TOTAL + KP - 1) / KP;
+  if constexpr (U < PER) {
+    side_step<T, AL, BL, SET, Q * PER + U>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    side_slot<T, AL, BL, SET, Q, U + 1>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+  }
+}
+
+template <class T, class AL, class BL, int SET, bool SIDE, int Q = 0>
+__device__ __forceinline__ void tile_stream(const float* __restrict__ as, const float* __restrict__ bs, int kh,
+                                            v16f (&acc)[T::TM][T::TN], float (&a)[2][T::TM], float (&b)[2][T::TN],
+                                            AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
+                                            const float4* rb, int k_plan, int kend) {
+  constexpr int KP = T::BK / 2;
+  if constexpr (Q < KP) {
+    constexpr int c = Q & 1, n = c ^ 1;
+    if constexpr (Q + 1 < KP) {  // fragments of the next k-pair, one pair ahead of their MFMAs
+      const int kr = 2 * (Q + 1) + kh;
+#pragma unroll
+      for (int i = 0; i < T::TM; ++i) a[n][i] = as[kr * T::LDA + i * 32];
+#pragma unroll
+      for (int j = 0; j < T::TN; ++j) b[n][j] = bs[kr * T::LDB + j * 32];
+    }
+#pragma unroll
+    for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < T::TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+    if constexpr (SIDE) side_slot<T, AL, BL, SET, Q>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    __builtin_amdgcn_sched_barrier(0);
+    tile_stream<T, AL, BL, SET, SIDE, Q + 1>(as, bs, kh, acc, a, b, al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+  }
+}
+
+// One iteration of the main loop for tile t, PAR = t & 1.  Register set PAR
+// receives tile t+2, register set PAR^1 (tile t+1) is written to LDS buffer PAR^1.
+template <class T, class AL, class BL, int PAR>
+__device__ __forceinline__ void main_iter(float (&As)[2][T::BK * T::LDA], float (&Bs)[2][T::BK * T::LDB], int a_off,
+                                          int b_off, int kh, v16f (&acc)[T::TM][T::TN], AL& al, BL& bl,
+                                          float4 (&ra)[2][AL::NL], float4 (&rb)[2][BL::NL], int k_plan, int kend) {
+  al.template fetch<PAR>(ra[PAR]);
+  bl.template fetch<PAR>(rb[PAR]);
+  float a[2][T::TM], b[2][T::TN];
+  const float* as = As[PAR] + a_off;
+  const float* bs = Bs[PAR] + b_off;
+#pragma unroll
+  for (int i = 0; i < T::TM; ++i) a[0][i] = as[kh * T::LDA + i * 32];
+#pragma unroll
+  for (int j = 0; j < T::TN; ++j) b[0][j] = bs[kh * T::LDB + j * 32];
+  __builtin_amdgcn_sched_barrier(0);
+  tile_stream<T, AL, BL, PAR ^ 1, true>(as, bs, kh, acc, a, b, al, bl, As[PAR ^ 1], Bs[PAR ^ 1], ra[PAR ^ 1],
+                                        rb[PAR ^ 1], k_plan, kend);
+  __syncthreads();
+}
+
 template <class T, class AL, class BL, class Epi>
 __global__ void __launch_bounds__(kThreads)
 gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk, int nsplit) {
@@ -407,42 +561,29 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  float4 ra[AL::NL], rb[BL::NL];
+  const int a_off = wm * (T::TM * 32) + (lane & 31), b_off = wn * (T::TN * 32) + (lane & 31), kh = lane >> 5;
   if (nt > 0) {
-    al.load(kbeg, kend, ra);
-    bl.load(kbeg, kend, rb);
-    al.store(As[0], T::LDA, ra);
-    bl.store(Bs[0], T::LDB, rb);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < nt; ++t) {
-    const int cur = t & 1;
-    const bool more = t + 1 < nt;
-    if (more) {
-      al.load(kbeg + (t + 1) * T::BK, kend, ra);
-      bl.load(kbeg + (t + 1) * T::BK, kend, rb);
-    }
-    const float* as = As[cur] + wm * (T::TM * 32) + (lane & 31);
-    const float* bs = Bs[cur] + wn * (T::TN * 32) + (lane & 31);
-#pragma unroll
-    for (int kk = 0; kk < T::BK / 2; ++kk) {
-      float a[T::TM], b[T::TN];
-      const int kr = frag_k(lane, kk);
-#pragma unroll
-      for (int i = 0; i < T::TM; ++i) a[i] = as[kr * T::LDA + i * 32];
-#pragma unroll
-      for (int j = 0; j < T::TN; ++j) b[j] = bs[kr * T::LDB + j * 32];
-#pragma unroll
-      for (int i = 0; i < T::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < T::TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-      al.store(As[cur ^ 1], T::LDA, ra);
-      bl.store(Bs[cur ^ 1], T::LDB, rb);
-    }
+    // prologue: tile 0 -> LDS buffer 0, tile 1 in flight in register set 1, addresses of tile 2 ready.
+    // Tiles past the end have every predicate off: they fetch element 0 and store zeros, harmlessly.
+    float4 ra[2][AL::NL], rb[2][BL::NL];
+    plan_all(al, kbeg, kend);
+    plan_all(bl, kbeg, kend);
+    al.template fetch<0>(ra[0]);
+    bl.template fetch<0>(rb[0]);
+    plan_all(al, kbeg + T::BK, kend);
+    plan_all(bl, kbeg + T::BK, kend);
+    al.template fetch<1>(ra[1]);
+    bl.template fetch<1>(rb[1]);
+    store_all<0>(al, As[0], T::LDA, ra[0]);
+    store_all<0>(bl, Bs[0], T::LDB, rb[0]);
+    plan_all(al, kbeg + 2 * T::BK, kend);
+    plan_all(bl, kbeg + 2 * T::BK, kend);
     __syncthreads();
+    for (int t = 0; t < nt; t += 2) {
+      main_iter<T, AL, BL, 0>(As, Bs, a_off, b_off, kh, acc, al, bl, ra, rb, kbeg + (t + 3) * T::BK, kend);
+      if (t + 1 < nt)
+        main_iter<T, AL, BL, 1>(As, Bs, a_off, b_off, kh, acc, al, bl, ra, rb, kbeg + (t + 4) * T::BK, kend);
+    }
   }
 
 #pragma unroll

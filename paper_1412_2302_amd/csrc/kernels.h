@@ -8,11 +8,14 @@
 namespace ax {
 
 // ---- convolution as implicit GEMM (conv_gemm.hip) ---------------------------
-int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
-                    hipStream_t st);
-int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
-                         hipStream_t st);
+// `ws` is split-k scratch of at least the matching *_ws_floats() floats (may be null when that is 0)
+size_t conv_fwd_ws_floats(const ConvGeom& c);
+size_t conv_bwd_data_ws_floats(const ConvGeom& c);
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c);
+int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
+                    float* ws, hipStream_t st);
+int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
+                         float* ws, hipStream_t st);
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* ws, hipStream_t st);
 
 // ---- dense layers (fc_gemm.hip) ---------------------------------------------

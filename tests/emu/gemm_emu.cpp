@@ -48,10 +48,19 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
             AL al(ap, g, tid, m0);
             BL bl(bp, g, tid, n0);
             float4 ra[AL::NL], rb[BL::NL];
-            al.load(kbeg + t * T::BK, kend, ra);
-            bl.load(kbeg + t * T::BK, kend, rb);
-            al.store(As.data(), T::LDA, ra);
-            bl.store(Bs.data(), T::LDB, rb);
+            plan_all(al, kbeg + t * T::BK, kend);
+            plan_all(bl, kbeg + t * T::BK, kend);
+            if (t & 1) {  // exercise both register sets
+              al.template fetch<1>(ra);
+              bl.template fetch<1>(rb);
+              store_all<1>(al, As.data(), T::LDA, ra);
+              store_all<1>(bl, Bs.data(), T::LDB, rb);
+            } else {
+              al.template fetch<0>(ra);
+              bl.template fetch<0>(rb);
+              store_all<0>(al, As.data(), T::LDA, ra);
+              store_all<0>(bl, Bs.data(), T::LDB, rb);
+            }
           }
           for (int wave = 0; wave < 4; ++wave) {
             const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
@@ -170,8 +179,16 @@ static void run_case(const Case& cs) {
     std::vector<float> y(c.out_elems(), NAN);
     GemmDims d = fwd_dims(c);
     EpiBiasAct e{y.data(), c.Cout, bias, 1, og, 0};
-    emu_gemm<T, Im2colKInner<T::BM, T::BK>, DenseRowInner<T::BN, T::BK>, EpiBiasAct>(
-        fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
+    const int kc = ((d.K + T::BK - 1) / T::BK) * T::BK;
+    if (fwd_A_vec(c, x) && fwd_B_vec(c, wf))
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, true, IM2COL_FWD>, DenseRowInner<T::BN, T::BK, true>, EpiBiasAct>(
+          fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, kc, 1, d.groups);
+    else if (fwd_B_vec(c, wf))
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, false, IM2COL_FWD>, DenseRowInner<T::BN, T::BK, true>, EpiBiasAct>(
+          fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, kc, 1, d.groups);
+    else
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, false, IM2COL_FWD>, DenseRowInner<T::BN, T::BK, false>, EpiBiasAct>(
+          fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, kc, 1, d.groups);
     check("fwd", nm, y, y_ref);
   }
   // ---- backward data ----
@@ -179,8 +196,20 @@ static void run_case(const Case& cs) {
     std::vector<float> dx(c.in_elems(), NAN);
     GemmDims d = bwdd_dims(c);
     EpiGate e{dx.data(), c.Cin, nullptr, cg, 0};
-    emu_gemm<T, Im2colKInner<T::BM, T::BK>, DenseRowInner<T::BN, T::BK>, EpiGate>(
-        bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
+    const int kc = ((d.K + T::BK - 1) / T::BK) * T::BK;
+    const bool vv = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb);
+    if (c.stride == 1 && vv)
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, true, IM2COL_T1>, DenseRowInner<T::BN, T::BK, true>, EpiGate>(
+          bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, kc, 1, d.groups);
+    else if (c.stride == 1)
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, false, IM2COL_T1>, DenseRowInner<T::BN, T::BK, false>, EpiGate>(
+          bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, kc, 1, d.groups);
+    else if (vv)
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, true, IM2COL_TS>, DenseRowInner<T::BN, T::BK, true>, EpiGate>(
+          bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, kc, 1, d.groups);
+    else
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, false, IM2COL_TS>, DenseRowInner<T::BN, T::BK, false>, EpiGate>(
+          bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, kc, 1, d.groups);
     check("bwd_data", nm, dx, dx_ref);
   }
   // ---- backward weight with split-k ----
@@ -191,8 +220,15 @@ static void run_case(const Case& cs) {
     int nsplit = plan_split(tiles, d.K, T::BK, 7, 5, &kchunk);
     std::vector<float> ws((size_t)d.groups * nsplit * d.M * d.N, NAN);
     EpiSlab e{ws.data(), (long)d.M * d.N, d.N, nullptr};
-    emu_gemm<T, Im2colRowInner<T::BM, T::BK>, DenseRowInner<T::BN, T::BK>, EpiSlab>(
-        bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
+    if (bwdw_A_vec(c, x) && bwdw_B_vec(c, dy))
+      emu_gemm<T, Im2colRowInner<T::BM, T::BK, true>, DenseRowInner<T::BN, T::BK, true>, EpiSlab>(
+          bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
+    else if (bwdw_B_vec(c, dy))
+      emu_gemm<T, Im2colRowInner<T::BM, T::BK, false>, DenseRowInner<T::BN, T::BK, true>, EpiSlab>(
+          bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
+    else
+      emu_gemm<T, Im2colRowInner<T::BM, T::BK, false>, DenseRowInner<T::BN, T::BK, false>, EpiSlab>(
+          bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
     std::vector<float> dwf(c.w_elems(), 0.f);
     for (int g = 0; g < d.groups; ++g)
       for (int sp = 0; sp < nsplit; ++sp)
@@ -226,34 +262,54 @@ static void dense_case() {
     std::vector<float> y(Bn * Out, NAN);
     std::vector<double> ref(Bn * Out, 0.0);
     for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * Out + o] += (double)x[n * In + i] * w[o * In + i];
-    DenseParams a{x, In, 0, Bn, 1}, b{w, In, 0, Out, 1};
+    DenseParams a{x, In, 0, Bn}, b{w, In, 0, Out};
     EpiSlab e{y.data(), (long)Bn * Out, Out, nullptr};
-    emu_gemm<T, DenseKInner<128, 16>, DenseKInner<128, 16>, EpiSlab>(a, b, e, Bn, Out, In, 32, 1, 1);
+    emu_gemm<T, DenseKInner<128, 16, true>, DenseKInner<128, 16, true>, EpiSlab>(a, b, e, Bn, Out, In, 32, 1, 1);
+    check("fc_fwd", "6x20->10 vec", y, ref);
+    std::fill(y.begin(), y.end(), NAN);
+    emu_gemm<T, DenseKInner<128, 16, false>, DenseKInner<128, 16, false>, EpiSlab>(a, b, e, Bn, Out, In, 32, 1, 1);
     check("fc_fwd", "6x20->10", y, ref);
   }
   {  // dx = dy w : A contiguous along k (=Out, not a multiple of 4 -> scalar), B along rows
     std::vector<float> dx(Bn * In, NAN);
     std::vector<double> ref(Bn * In, 0.0);
     for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * In + i] += (double)dy[n * Out + o] * w[o * In + i];
-    DenseParams a{dy, Out, 0, Bn, 0}, b{w, In, 0, In, 1};
+    DenseParams a{dy, Out, 0, Bn}, b{w, In, 0, In};
     EpiSlab e{dx.data(), (long)Bn * In, In, nullptr};
-    emu_gemm<T, DenseKInner<128, 16>, DenseRowInner<128, 16>, EpiSlab>(a, b, e, Bn, In, Out, 16, 1, 1);
+    emu_gemm<T, DenseKInner<128, 16, false>, DenseRowInner<128, 16, false>, EpiSlab>(a, b, e, Bn, In, Out, 16, 1, 1);
     check("fc_bwd_x", "6x20->10", dx, ref);
   }
   {  // dw = dy^T x : both contiguous along rows; A scalar path
     std::vector<float> dw(Out * In, NAN);
     std::vector<double> ref(Out * In, 0.0);
     for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[o * In + i] += (double)dy[n * Out + o] * x[n * In + i];
-    DenseParams a{dy, Out, 0, Out, 0}, b{x, In, 0, In, 1};
+    DenseParams a{dy, Out, 0, Out}, b{x, In, 0, In};
     EpiSlab e{dw.data(), (long)Out * In, In, nullptr};
-    emu_gemm<T, DenseRowInner<128, 16>, DenseRowInner<128, 16>, EpiSlab>(a, b, e, Out, In, Bn, 16, 1, 1);
+    emu_gemm<T, DenseRowInner<128, 16, false>, DenseRowInner<128, 16, false>, EpiSlab>(a, b, e, Out, In, Bn, 16, 1, 1);
     check("fc_bwd_w", "6x20->10", dw, ref);
   }
   delete[] x; delete[] w; delete[] dy;
 }
 
+static void check_fastdiv() {
+  const uint32_t ds[] = {1, 2, 3, 4, 5, 7, 8, 11, 12, 13, 16, 24, 27, 36, 48, 55, 96, 169, 192, 256, 729, 3025, 51529, 1000003};
+  long bad = 0;
+  for (uint32_t d : ds) {
+    FastDiv f = make_fastdiv(d);
+    for (uint32_t n = 0; n < 3000000u; ++n) bad += fdiv(n, f) != n / d;
+    for (uint64_t n = 0x7fffffffull - 100000; n <= 0x7fffffffull; ++n) bad += fdiv((uint32_t)n, f) != (uint32_t)n / d;
+    for (int i = 0; i < 2000000; ++i) {
+      uint32_t n = ((uint32_t)rand() << 16 ^ (uint32_t)rand()) & 0x7fffffffu;
+      bad += fdiv(n, f) != n / d;
+    }
+  }
+  printf("fastdiv %s\n", bad ? "FAIL" : "ok");
+  if (bad) ++failures;
+}
+
 int main() {
   srand(1234);
+  check_fastdiv();
   std::vector<Case> cases = {
       {geom(2, 23, 3, 8, 11, 4, 0, 1), "k11s4c3"},      // scalar gather, stride 4
       {geom(3, 13, 3, 16, 7, 2, 0, 1), "k7s2c3"},       // mini conv1
@@ -264,9 +320,10 @@ int main() {
       {geom(5, 5, 132, 136, 3, 1, 1, 1), "k3wide"},      // more than one tile along N and K rows
   };
   for (const Case& cs : cases) {
+    run_case<Tile<128, 128, 32, 2, 2>>(cs);
+    run_case<Tile<128, 96, 32, 4, 1>>(cs);
+    run_case<Tile<128, 64, 32, 4, 1>>(cs);
     run_case<Tile<128, 128, 16, 2, 2>>(cs);
-    run_case<Tile<128, 96, 16, 4, 1>>(cs);
-    run_case<Tile<128, 64, 16, 4, 1>>(cs);
   }
   dense_case<128, 16>();
   printf(failures ? "FAILED %d\n" : "ALL OK\n", failures);
