@@ -5,6 +5,8 @@
 // C % 4 == 0 so that every global access is a coalesced 16-byte load/store.
 #include <math.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace ax {
@@ -173,13 +175,105 @@ __global__ void lrn_bwd_kernel(const float* __restrict__ a, const float* __restr
   da[i] = out;
 }
 
+// Vector versions (C % 4 == 0, C <= 1024): a workgroup owns PB whole pixels, a
+// lane owns four consecutive channels of one pixel.  Squares (and, backward,
+// the per-channel terms dy*a*s^(-beta-1)) are staged in LDS rows that carry
+// `half` zeros on both sides, so the clipped window needs no branches and every
+// tensor is read from and written to HBM exactly once with 16-byte accesses.
+constexpr int kLrnMaxHalf = 4;
+constexpr int kLrnPad = 4;  // zeros on both sides of an LDS row; keeps 16-byte alignment
+__device__ __forceinline__ float4 lrn_window_sum(const float* row, int c, int half) {
+  // sums of row[c+j-half .. c+j+half] for j = 0..3, each added up directly
+  float v[12];
+  *reinterpret_cast<float4*>(v) = *reinterpret_cast<const float4*>(row + c - 4);
+  *reinterpret_cast<float4*>(v + 4) = *reinterpret_cast<const float4*>(row + c);
+  *reinterpret_cast<float4*>(v + 8) = *reinterpret_cast<const float4*>(row + c + 4);
+  float s[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float w = v[4 + j];
+#pragma unroll
+    for (int d = 1; d <= kLrnMaxHalf; ++d)
+      if (d <= half) w += v[4 + j - d] + v[4 + j + d];
+    s[j] = w;
+  }
+  return make_float4(s[0], s[1], s[2], s[3]);
+}
+
+template <bool BWD>
+__global__ void __launch_bounds__(256)
+lrn_vec_kernel(const float* __restrict__ a, const float* __restrict__ db, float* __restrict__ out, long pixels, int C,
+               int half, int PB, float k, float alpha, float beta, int relu_gate) {
+  extern __shared__ __attribute__((aligned(16))) float sh[];  // [2][PB][kLrnPad + C + kLrnPad]
+  const int q = C >> 2;                                        // lanes per pixel
+  const int ld = C + 2 * kLrnPad;
+  const int pl = threadIdx.x / q, cq = threadIdx.x - pl * q;
+  const long pix = (long)blockIdx.x * PB + pl;
+  const bool on = pl < PB && pix < pixels;
+  float* sq = sh + (size_t)pl * ld + kLrnPad;
+  float* tt = sh + (size_t)PB * ld + (size_t)pl * ld + kLrnPad;
+  if (pl < PB && cq < 2) {  // zero the pads of this pixel's two rows
+    const int o = cq == 0 ? -kLrnPad : C;
+    *reinterpret_cast<float4*>(sq + o) = make_float4(0.f, 0.f, 0.f, 0.f);
+    *reinterpret_cast<float4*>(tt + o) = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const int c = cq * 4;
+  float4 av = make_float4(0.f, 0.f, 0.f, 0.f), dv = av;
+  if (on) {
+    av = *reinterpret_cast<const float4*>(a + pix * C + c);
+    if (BWD) dv = *reinterpret_cast<const float4*>(db + pix * C + c);
+    *reinterpret_cast<float4*>(sq + c) = make_float4(av.x * av.x, av.y * av.y, av.z * av.z, av.w * av.w);
+  }
+  __syncthreads();
+  float4 p = av;  // s^-beta per channel
+  float4 sv = av;
+  if (on) {
+    const float4 w = lrn_window_sum(sq, c, half);
+    sv = make_float4(k + alpha * w.x, k + alpha * w.y, k + alpha * w.z, k + alpha * w.w);
+    p = make_float4(neg_pow(sv.x, beta), neg_pow(sv.y, beta), neg_pow(sv.z, beta), neg_pow(sv.w, beta));
+  }
+  if (!BWD) {
+    if (on) *reinterpret_cast<float4*>(out + pix * C + c) = make_float4(av.x * p.x, av.y * p.y, av.z * p.z, av.w * p.w);
+    return;
+  }
+  if (on)
+    *reinterpret_cast<float4*>(tt + c) = make_float4(dv.x * av.x * p.x / sv.x, dv.y * av.y * p.y / sv.y,
+                                                     dv.z * av.z * p.z / sv.z, dv.w * av.w * p.w / sv.w);
+  __syncthreads();
+  if (on) {
+    const float4 acc = lrn_window_sum(tt, c, half);
+    const float f = 2.f * alpha * beta;
+    float4 r = make_float4(dv.x * p.x - f * av.x * acc.x, dv.y * p.y - f * av.y * acc.y, dv.z * p.z - f * av.z * acc.z,
+                           dv.w * p.w - f * av.w * acc.w);
+    if (relu_gate) {
+      r.x = av.x > 0.f ? r.x : 0.f;
+      r.y = av.y > 0.f ? r.y : 0.f;
+      r.z = av.z > 0.f ? r.z : 0.f;
+      r.w = av.w > 0.f ? r.w : 0.f;
+    }
+    *reinterpret_cast<float4*>(out + pix * C + c) = r;
+  }
+}
+
+static bool lrn_vec_ok(const void* p0, const void* p1, const void* p2, int C, int half) {
+  return C % 4 == 0 && C <= 1024 && half <= kLrnMaxHalf && aligned16(p0) && aligned16(p1) && aligned16(p2);
+}
+
 int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k, float alpha, float beta,
                    hipStream_t st) {
   const size_t total = (size_t)pixels * C;
   if (!total) return ALEXNET_OK;
   KernelScope ks("lrn_fwd", 0, (double)total * 8.0, st);
-  hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, b, total, C, n / 2, k, alpha,
-                     beta);
+  const int half = n / 2;
+  if (lrn_vec_ok(a, b, b, C, half)) {
+    const int PB = 256 / (C / 4);
+    const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
+    hipLaunchKernelGGL((lrn_vec_kernel<false>), dim3(ceil_div(pixels, PB)), dim3(256), lds, st, a, nullptr, b, pixels, C,
+                       half, PB, k, alpha, beta, 0);
+  } else {
+    hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, b, total, C, half, k, alpha,
+                       beta);
+  }
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -188,8 +282,16 @@ int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int 
   const size_t total = (size_t)pixels * C;
   if (!total) return ALEXNET_OK;
   KernelScope ks("lrn_bwd", 0, (double)total * 12.0, st);
-  hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, db, da, total, C, n / 2, k,
-                     alpha, beta, relu_gate);
+  const int half = n / 2;
+  if (lrn_vec_ok(a, db, da, C, half)) {
+    const int PB = 256 / (C / 4);
+    const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
+    hipLaunchKernelGGL((lrn_vec_kernel<true>), dim3(ceil_div(pixels, PB)), dim3(256), lds, st, a, db, da, pixels, C,
+                       half, PB, k, alpha, beta, relu_gate);
+  } else {
+    hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, db, da, total, C, half, k,
+                       alpha, beta, relu_gate);
+  }
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -263,11 +365,53 @@ __global__ void pool_bwd_kernel(const float* __restrict__ dy, const uint8_t* __r
   }
   dx[i] = acc;
 }
+// Same gather with a lane owning four consecutive channels (C % 4 == 0).
+__global__ void pool_bwd_vec_kernel(const float* __restrict__ dy, const uint8_t* __restrict__ slot,
+                                    const float* __restrict__ gate, float* __restrict__ dx, int N, int H, int W, int C,
+                                    int Ho, int Wo) {
+  const int cq = C >> 2;
+  const size_t total = (size_t)N * H * W * cq;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cq) * 4;
+  size_t p = i / cq;
+  const int x = (int)(p % W);
+  p /= W;
+  const int y = (int)(p % H);
+  const size_t n = p / H;
+  const size_t e = i * 4;  // element index of (n, y, x, c)
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int yo_lo = y >= 2 ? (y - 1) / 2 : 0, yo_hi = min(y / 2, Ho - 1);
+  const int xo_lo = x >= 2 ? (x - 1) / 2 : 0, xo_hi = min(x / 2, Wo - 1);
+  for (int yo = yo_lo; yo <= yo_hi; ++yo)
+    for (int xo = xo_lo; xo <= xo_hi; ++xo) {
+      const size_t o = ((n * Ho + yo) * Wo + xo) * C + c;
+      const uint32_t want = (uint32_t)((y - 2 * yo) * 3 + (x - 2 * xo));
+      const uint32_t s4 = *reinterpret_cast<const uint32_t*>(slot + o);
+      const float4 d = *reinterpret_cast<const float4*>(dy + o);
+      acc.x += (s4 & 0xffu) == want ? d.x : 0.f;
+      acc.y += ((s4 >> 8) & 0xffu) == want ? d.y : 0.f;
+      acc.z += ((s4 >> 16) & 0xffu) == want ? d.z : 0.f;
+      acc.w += (s4 >> 24) == want ? d.w : 0.f;
+    }
+  if (gate) {
+    const float4 g = *reinterpret_cast<const float4*>(gate + e);
+    acc.x = g.x > 0.f ? acc.x : 0.f;
+    acc.y = g.y > 0.f ? acc.y : 0.f;
+    acc.z = g.z > 0.f ? acc.z : 0.f;
+    acc.w = g.w > 0.f ? acc.w : 0.f;
+  }
+  *reinterpret_cast<float4*>(dx + e) = acc;
+}
 int launch_pool_bwd(const float* dy, const uint8_t* slot, const float* gate, float* dx, int N, int H, int W, int C,
                     int Ho, int Wo, hipStream_t st) {
   const size_t total = (size_t)N * H * W * C;
   if (!total) return ALEXNET_OK;
   KernelScope ks("pool_bwd", 0, (double)total * (gate ? 8.0 : 4.0) + (double)N * Ho * Wo * C * 5.0, st);
+  if (C % 4 == 0 && aligned16(dy) && aligned16(dx) && (!gate || aligned16(gate)) && ((uintptr_t)slot & 3) == 0)
+    hipLaunchKernelGGL(pool_bwd_vec_kernel, dim3(grid_for(total / 4, 256)), dim3(256), 0, st, dy, slot, gate, dx, N, H,
+                       W, C, Ho, Wo);
+  else
   hipLaunchKernelGGL(pool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, slot, gate, dx, N, H, W, C,
                      Ho, Wo);
   AX_LAUNCH_CHECK();
@@ -375,37 +519,84 @@ int launch_mean_loss(const float* row_loss, int B, float* loss, hipStream_t st) 
 // ------------------------------------------------------------ reductions ---
 // Column sums of a row-major [rows][cols] matrix (bias gradients), in two
 // passes with a fixed combination order so results do not depend on timing.
-constexpr int kColsumRowsPerBlock = 2048;
+// Stage 1: a workgroup sums `rpb` rows of a 64-column stripe; 16 row lanes x
+// 16 column quads (16-byte loads when VEC), then a fixed-order LDS reduction.
+// rpb is chosen by the launcher so that the grid has about a thousand workgroups.
+template <bool VEC>
 __global__ void __launch_bounds__(256)
-colsum_stage1(const float* __restrict__ m, long rows, int cols, float* __restrict__ part) {
+colsum_stage1(const float* __restrict__ m, long rows, int cols, int rpb, float* __restrict__ part) {
+  __shared__ float sh[16][65];
+  const int cq = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const int col = blockIdx.x * 64 + cq * 4;
+  const long r0 = (long)blockIdx.y * rpb;
+  const long r1 = min(rows, r0 + rpb);
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (VEC) {
+    if (col < cols)
+      for (long r = r0 + rl; r < r1; r += 16) {
+        const float4 v = *reinterpret_cast<const float4*>(m + r * cols + col);
+        s.x += v.x;
+        s.y += v.y;
+        s.z += v.z;
+        s.w += v.w;
+      }
+  } else {
+    for (long r = r0 + rl; r < r1; r += 16) {
+      const float* p = m + r * cols + col;
+      if (col < cols) s.x += p[0];
+      if (col + 1 < cols) s.y += p[1];
+      if (col + 2 < cols) s.z += p[2];
+      if (col + 3 < cols) s.w += p[3];
+    }
+  }
+  sh[rl][cq * 4] = s.x;
+  sh[rl][cq * 4 + 1] = s.y;
+  sh[rl][cq * 4 + 2] = s.z;
+  sh[rl][cq * 4 + 3] = s.w;
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += sh[r][threadIdx.x];
+    if (c < cols) part[(size_t)blockIdx.y * cols + c] = t;
+  }
+}
+__global__ void __launch_bounds__(256)
+colsum_stage2(const float* __restrict__ part, int nparts, int cols, float* __restrict__ out) {
   __shared__ float sh[4][64];
-  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int cl = threadIdx.x & 63, pl = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + cl;
-  const long r0 = (long)blockIdx.y * kColsumRowsPerBlock;
-  const long r1 = min(rows, r0 + kColsumRowsPerBlock);
   float s = 0.f;
   if (col < cols)
-    for (long r = r0 + rl; r < r1; r += 4) s += m[r * cols + col];
-  sh[rl][cl] = s;
+    for (int p = pl; p < nparts; p += 4) s += part[(size_t)p * cols + col];
+  sh[pl][cl] = s;
   __syncthreads();
-  if (rl == 0 && col < cols) part[(size_t)blockIdx.y * cols + col] = (sh[0][cl] + sh[1][cl]) + (sh[2][cl] + sh[3][cl]);
+  if (pl == 0 && col < cols) out[col] = (sh[0][cl] + sh[1][cl]) + (sh[2][cl] + sh[3][cl]);
 }
-__global__ void colsum_stage2(const float* __restrict__ part, int nparts, int cols, float* __restrict__ out) {
-  const int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= cols) return;
-  float s = 0.f;
-  for (int p = 0; p < nparts; ++p) s += part[(size_t)p * cols + col];
-  out[col] = s;
+// rows per workgroup: enough row chunks for ~1024 workgroups, at least 64 rows each
+static int colsum_rows_per_block(long rows, int cols) {
+  const int stripes = ceil_div(cols, 64);
+  const int want_chunks = std::max(1, 1024 / stripes);
+  long rpb = (rows + want_chunks - 1) / want_chunks;
+  rpb = (rpb + 15) / 16 * 16;
+  return (int)std::max(64L, rpb);
 }
 size_t colsum_ws_floats(long rows, int cols) {
-  return (size_t)ceil_div(rows, kColsumRowsPerBlock) * cols;
+  return (size_t)ceil_div(rows, colsum_rows_per_block(rows, cols)) * cols;
 }
 int launch_colsum(const float* m, long rows, int cols, float* out, float* ws, hipStream_t st) {
-  const int nparts = ceil_div(rows, kColsumRowsPerBlock);
+  const int rpb = colsum_rows_per_block(rows, cols);
+  const int nparts = ceil_div(rows, rpb);
   KernelScope ks("colsum", 0, (double)rows * cols * 4.0, st);
-  hipLaunchKernelGGL(colsum_stage1, dim3(ceil_div(cols, 64), nparts), dim3(256), 0, st, m, rows, cols, ws);
+  if (cols % 4 == 0 && aligned16(m))
+    hipLaunchKernelGGL((colsum_stage1<true>), dim3(ceil_div(cols, 64), nparts), dim3(256), 0, st, m, rows, cols, rpb,
+                       ws);
+  else
+    hipLaunchKernelGGL((colsum_stage1<false>), dim3(ceil_div(cols, 64), nparts), dim3(256), 0, st, m, rows, cols, rpb,
+                       ws);
   AX_LAUNCH_CHECK();
-  hipLaunchKernelGGL(colsum_stage2, dim3(ceil_div(cols, 256)), dim3(256), 0, st, ws, nparts, cols, out);
+  hipLaunchKernelGGL(colsum_stage2, dim3(ceil_div(cols, 64)), dim3(256), 0, st, ws, nparts, cols, out);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
