@@ -166,8 +166,8 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
       s.Hp = (s.g.Ho - 3) / 2 + 1;
       s.Wp = (s.g.Wo - 3) / 2 + 1;
     }
-    if ((long)s.g.P() * 1 > 0x7fffffffL / 2 || s.g.in_elems() > 0x7fffffffL || s.g.out_elems() > 0x7fffffffL) {
-      set_error("conv%d: tensor too large for 32-bit pixel indices", i + 1);
+    if (s.g.in_elems() > 0x1fffffffL || s.g.out_elems() > 0x1fffffffL || s.g.w_elems() > 0x1fffffffL) {
+      set_error("conv%d: a tensor reaches 2 GiB; byte offsets in the kernels are 32-bit", i + 1);
       return ALEXNET_ESHAPE;
     }
     snprintf(s.lab[0], 16, "conv%d", i + 1);
@@ -183,6 +183,10 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
   for (int j = 0; j < kFc; ++j) {
     if (c.fc[j] <= 0) {
       set_error("fc width must be positive");
+      return ALEXNET_ESHAPE;
+    }
+    if ((long)in * c.fc[j] > 0x1fffffffL || (long)c.batch * in > 0x1fffffffL || (long)c.batch * c.fc[j] > 0x1fffffffL) {
+      set_error("fc%d: a tensor reaches 2 GiB; byte offsets in the kernels are 32-bit", kStages + 1 + j);
       return ALEXNET_ESHAPE;
     }
     n->fc[j].in = in; n->fc[j].out = c.fc[j];

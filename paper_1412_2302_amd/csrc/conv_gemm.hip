@@ -281,8 +281,8 @@ int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const 
                   hipStream_t st) {
   int kchunk;
   const int ns = fc_split(B, out, in, &kchunk);
-  DenseParams a{x, in, 0, B};
-  DenseParams b{w, in, 0, out};
+  DenseParams a{x, in, 0, B, (uint32_t)((size_t)B * in * 4)};
+  DenseParams b{w, in, 0, out, (uint32_t)((size_t)out * in * 4)};
   EpiSlab ep{ws, (long)B * out, out, nullptr};
   // both operands run along k = in
   AX_TRY((launch_dense<DenseKInner, DenseKInner>(vec_ok(x, in) && vec_ok(w, in), a, b, ep, B, out, in, kchunk, ns, st)));
@@ -297,8 +297,8 @@ int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, 
                        float* ws, hipStream_t st) {
   int kchunk;
   const int ns = fc_split(B, in, out, &kchunk);
-  DenseParams a{dy, out, 0, B};
-  DenseParams b{w, in, 0, in};
+  DenseParams a{dy, out, 0, B, (uint32_t)((size_t)B * out * 4)};
+  DenseParams b{w, in, 0, in, (uint32_t)((size_t)out * in * 4)};
   EpiSlab ep{ws, (long)B * in, in, nullptr};
   // A runs along k = out, B along its rows = in
   AX_TRY((launch_dense<DenseKInner, DenseRowInner>(vec_ok(dy, out) && vec_ok(w, in), a, b, ep, B, in, out, kchunk, ns,
@@ -311,8 +311,8 @@ int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, 
 }
 
 int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy, float* dw, hipStream_t st) {
-  DenseParams a{dy, out, 0, out};
-  DenseParams b{x, in, 0, in};
+  DenseParams a{dy, out, 0, out, (uint32_t)((size_t)B * out * 4)};
+  DenseParams b{x, in, 0, in, (uint32_t)((size_t)B * in * 4)};
   EpiSlab ep{dw, (long)out * in, in, nullptr};
   return launch_dense<DenseRowInner, DenseRowInner>(vec_ok(dy, out) && vec_ok(x, in), a, b, ep, out, in, B,
                                                     round_up(B, kBK), 1, st);

@@ -47,7 +47,8 @@ inline void fill_divs(Im2colParams& a) {
 inline GemmDims fwd_dims(const ConvGeom& c) { return {(int)c.P(), c.og(), c.kf(), c.groups}; }
 inline Im2colParams fwd_A(const ConvGeom& c, const float* x) {
   Im2colParams a;
-  a.x = x; a.H = c.H; a.W = c.W; a.Ctot = c.Cin; a.Cg = c.cg(); a.c_stride_g = c.cg();
+  a.x = x; a.bytes = (uint32_t)(c.in_elems() * 4);
+  a.H = c.H; a.W = c.W; a.Ctot = c.Cin; a.Cg = c.cg(); a.c_stride_g = c.cg();
   a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad;
   a.OH = c.Ho; a.OW = c.Wo; a.P = (int)c.P();
   fill_divs(a);
@@ -56,7 +57,7 @@ inline Im2colParams fwd_A(const ConvGeom& c, const float* x) {
 inline bool fwd_A_vec(const ConvGeom& c, const float* x) { return c.cg() % 4 == 0 && c.Cin % 4 == 0 && aligned16(x); }
 inline DenseParams fwd_B(const ConvGeom& c, const float* wf) {
   DenseParams b;
-  b.p = wf; b.ld = c.og(); b.gstride = (long)c.kf() * c.og(); b.R = c.og();
+  b.p = wf; b.ld = c.og(); b.gstride = (long)c.kf() * c.og(); b.R = c.og(); b.bytes = (uint32_t)(c.w_elems() * 4);
   return b;
 }
 inline bool fwd_B_vec(const ConvGeom& c, const float* wf) { return c.og() % 4 == 0 && aligned16(wf); }
@@ -65,7 +66,8 @@ inline bool fwd_B_vec(const ConvGeom& c, const float* wf) { return c.og() % 4 ==
 inline GemmDims bwdd_dims(const ConvGeom& c) { return {(int)c.Q(), c.cg(), c.kb(), c.groups}; }
 inline Im2colParams bwdd_A(const ConvGeom& c, const float* dy) {
   Im2colParams a;
-  a.x = dy; a.H = c.Ho; a.W = c.Wo; a.Ctot = c.Cout; a.Cg = c.og(); a.c_stride_g = c.og();
+  a.x = dy; a.bytes = (uint32_t)(c.out_elems() * 4);
+  a.H = c.Ho; a.W = c.Wo; a.Ctot = c.Cout; a.Cg = c.og(); a.c_stride_g = c.og();
   a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad;
   a.OH = c.H; a.OW = c.W; a.P = (int)c.Q();
   fill_divs(a);
@@ -74,7 +76,7 @@ inline Im2colParams bwdd_A(const ConvGeom& c, const float* dy) {
 inline bool bwdd_A_vec(const ConvGeom& c, const float* dy) { return c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy); }
 inline DenseParams bwdd_B(const ConvGeom& c, const float* wb) {
   DenseParams b;
-  b.p = wb; b.ld = c.cg(); b.gstride = (long)c.kb() * c.cg(); b.R = c.cg();
+  b.p = wb; b.ld = c.cg(); b.gstride = (long)c.kb() * c.cg(); b.R = c.cg(); b.bytes = (uint32_t)(c.w_elems() * 4);
   return b;
 }
 inline bool bwdd_B_vec(const ConvGeom& c, const float* wb) { return c.cg() % 4 == 0 && aligned16(wb); }
@@ -85,7 +87,7 @@ inline Im2colParams bwdw_A(const ConvGeom& c, const float* x) { return fwd_A(c, 
 inline bool bwdw_A_vec(const ConvGeom& c, const float* x) { return fwd_A_vec(c, x); }
 inline DenseParams bwdw_B(const ConvGeom& c, const float* dy) {
   DenseParams b;
-  b.p = dy; b.ld = c.Cout; b.gstride = c.og(); b.R = c.og();
+  b.p = dy; b.ld = c.Cout; b.gstride = c.og(); b.R = c.og(); b.bytes = (uint32_t)(c.out_elems() * 4);
   return b;
 }
 inline bool bwdw_B_vec(const ConvGeom& c, const float* dy) { return c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy); }

@@ -2,12 +2,25 @@
 //
 //   C[m][n] = sum_k A(m,k) * B(k,n)          (per group, per split of k)
 //
-// A workgroup of four 64-lane waves owns a BM x BN tile of C.  Both operands
-// are staged through LDS k-major (tile[k][row]) so that one ds_read_b32 per
-// lane feeds v_mfma_f32_32x32x2_f32 directly: lane l supplies A[l%32][l/32]
-// and B[l/32][l%32].  Global loads of tile t+1 are issued before the MFMA
-// loop of tile t and written to the other LDS buffer afterwards, so a single
-// barrier per k-tile is enough.
+// A workgroup of four 64-lane waves owns a BM x BN tile of C and walks the
+// reduction in k-tiles of BK.  On this hardware every VALU or LDS instruction
+// a wave issues takes issue time away from its MFMAs (measured: ~5 cycles
+// each against 64 per v_mfma_f32_32x32x2_f32), so the design goal is few
+// instructions per MFMA:
+//  * operands are fetched with raw buffer loads: an element outside the operand
+//    gets a byte offset past the buffer and the hardware returns zero, so there
+//    are no predicated selects and no 64-bit address arithmetic;
+//  * an operand that is contiguous along k in memory is kept [row][k] in LDS:
+//    one 16-byte store per load, and one 16-byte read gives a lane its values
+//    for four MFMAs (the MFMAs then take k in the order 8q+j, 8q+4+j, which is
+//    as good as any since both operands agree on it);
+//  * an operand that is contiguous along rows is kept [k][row]: one 16-byte
+//    store per load, 4-byte reads one k-pair ahead of their MFMAs;
+//  * index decoding uses multiply-shift division by launch constants, and
+//    everything that does not depend on the k-tile is computed once per thread.
+// Global loads run two k-tiles ahead (two register sets), LDS is double
+// buffered with one barrier per k-tile, and the LDS stores and address
+// arithmetic of later tiles are dealt out between the MFMAs of the current one.
 //
 // Loaders know how an operand lives in memory:
 //   DenseKInner     elem(row,k) = p[row*ld + k]      (contiguous along k)
@@ -17,17 +30,9 @@
 //                   forward, and backward-data in its transposed modes)
 //   Im2colRowInner  rows = (r,s,c), k = output pixels: its transpose
 //                   (convolution backward-weight)
-// Every loader zero-fills outside the operand, so ragged tiles need no care
-// in the MFMA loop.  Loads are predicated, never branched around: an element
-// outside the operand reads the operand's first element and is then replaced
-// by zero, which keeps the k-loop one straight-line block that the compiler
-// can software-pipeline.  Index decoding uses multiply-shift division by
-// launch constants.  A loader works in steps that the kernel places one by one:
-// addr_step<S>() computes offsets and predicates of a later k-tile (pure VALU
-// work), fetch<SET>() issues its global loads into one of two register sets,
-// store_step<SET>(s) zeroes what was outside the operand and writes one load
-// to LDS.  VEC selects 16-byte loads (legal only when the launcher
-// has checked alignment and divisibility) or four 4-byte loads.
+// VEC selects 16-byte loads (legal only when the launcher has checked alignment
+// and divisibility) or four 4-byte loads.  Every operand must be smaller than
+// 2 GiB (byte offsets are 32-bit and 0x80000000 marks "outside").
 //
 // Everything here is also compiled for the host by the CPU emulation test
 // (AX_HOST_EMU), which is why loaders and epilogues are plain structs with
@@ -46,24 +51,55 @@
 namespace ax {
 
 constexpr int kThreads = 256;
+constexpr uint32_t kOob = 0x80000000u;  // byte offset no operand reaches
 
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
 struct Tile {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int TM = BM / (32 * WAVES_M), TN = BN / (32 * WAVES_N);
-  static constexpr int PAD = 4;
-  static constexpr int LDA = BM + PAD, LDB = BN + PAD;
   static_assert(WAVES_M * WAVES_N * 64 == kThreads, "four waves per workgroup");
   static_assert(TM * 32 * WAVES_M == BM && TN * 32 * WAVES_N == BN, "tile must be whole 32x32 MFMA blocks");
-  static_assert(BK % 4 == 0, "k tile is loaded in quads");
+  static_assert(BK % 8 == 0, "MFMAs take k in blocks of eight");
 };
 
-AX_HD float4 zero4() {
-  float4 v;
-  v.x = v.y = v.z = v.w = 0.f;
-  return v;
+// ---- buffer views --------------------------------------------------------------
+#ifdef AX_HOST_EMU
+struct BufView {
+  const float* p;
+  uint32_t bytes;
+};
+inline BufView make_view(const float* p, uint32_t bytes) { return BufView{p, bytes}; }
+// The emulation treats a load that is only partly inside as an error: the
+// kernel never relies on per-dword clipping.
+inline void emu_fail(const char* what);
+inline float4 buf_ld4(const BufView& v, uint32_t off) {
+  float4 z;
+  z.x = z.y = z.z = z.w = 0.f;
+  if (off >= v.bytes) return z;
+  if (off + 16 > v.bytes || (off & 3)) emu_fail("16-byte load straddles the end of its operand");
+  return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(v.p) + off);
 }
-AX_HD float4 ld4(const float* q) { return *reinterpret_cast<const float4*>(q); }
+inline float buf_ld1(const BufView& v, uint32_t off) {
+  if (off >= v.bytes) return 0.f;
+  if (off & 3) emu_fail("unaligned 4-byte load");
+  return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(v.p) + off);
+}
+#else
+typedef __amdgpu_buffer_rsrc_t BufView;
+__device__ __forceinline__ BufView make_view(const float* p, uint32_t bytes) {
+  // raw buffer (stride 0): the range check is offset >= num_records -> 0
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float4 buf_ld4(const BufView& v, uint32_t off) {
+  typedef unsigned v4u __attribute__((ext_vector_type(4)));
+  const v4u r = __builtin_amdgcn_raw_buffer_load_b128(v, (int)off, 0, 0);
+  return __builtin_bit_cast(float4, r);
+}
+__device__ __forceinline__ float buf_ld1(const BufView& v, uint32_t off) {
+  return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(v, (int)off, 0, 0));
+}
+#endif
+
 // ---- division by a launch constant -------------------------------------------
 // q = n / d for 0 <= n < 2^31:  umulhi(n, mul) >> shift, mul = ceil(2^(31+l)/d),
 // l = ceil(log2 d), shift = l - 1; d == 1 is handled by mul == 0.
@@ -97,100 +133,80 @@ AX_HD uint32_t fdiv(uint32_t n, const FastDiv& f) {
   return f.mul ? q : n;
 }
 
-// ---- fragment and accumulator index maps of v_mfma_f32_32x32x2_f32 ---------
-// A/B fragment for k-pair kk: lane reads tile[(2*kk + lane/32)][base + lane%32].
-AX_HD int frag_k(int lane, int kk) { return 2 * kk + (lane >> 5); }
+// ---- index maps of v_mfma_f32_32x32x2_f32 ---------------------------------------
+// MFMA step u = 4q + j of a k-tile consumes k = 8q + j (lanes 0..31) and
+// k = 8q + 4 + j (lanes 32..63).
+AX_HD int step_k(int u, int kh) { return 8 * (u >> 2) + 4 * kh + (u & 3); }
 // accumulator register r of a lane holds C[acc_row(lane,r)][lane%32] of the 32x32 block
 AX_HD int acc_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
 // =========================== operand loaders ================================
+// Common interface (NL loads per thread and k-tile, NA address steps):
+//   addr_step<S>(k0, kend)   byte offsets of the tile starting at k0 (S = 0..NA-1)
+//   fetch(r)                 issue the NL loads of the last addressed tile
+//   store_step(s, lds, r)    write load s to the LDS tile
+//   kRowMajor, LD, LDS_FLOATS  layout of the LDS tile ([row][k] or [k][row])
 
 struct DenseParams {
   const float* p;
-  long ld;       // leading dimension in floats
-  long gstride;  // added per group
-  int R;         // number of valid rows
+  long ld;         // leading dimension in floats
+  long gstride;    // floats added per group
+  int R;           // number of valid rows
+  uint32_t bytes;  // extent of the operand from p, all groups
 };
 
-// Per-thread bookkeeping shared by all loaders.  A thread makes NL loads per
-// k-tile (16 bytes each when VEC, else four 4-byte loads).  `off`/`okn` describe
-// the tile that will be fetched next; two register sets can be in flight, and
-// ok[set] remembers which of their elements were inside the operand.
-template <int NL_, bool VEC>
-struct PlanRegs {
-  static constexpr int NL = NL_, NE = VEC ? NL : 4 * NL;
+template <int NL, bool VEC>
+struct Offsets {
+  static constexpr int NE = VEC ? NL : 4 * NL;
   uint32_t off[NE];
-  uint32_t okn;
-  uint32_t ok[2];
-  AX_HD void put(int e, uint32_t o, bool good) {
-    off[e] = good ? o : 0u;  // an element outside reads element 0 and is zeroed when stored
-    okn |= (uint32_t)good << e;
-  }
-  template <int SET>
-  AX_HD void fetch(const float* p, float4* r) {
-    ok[SET] = okn;
+  AX_HD void fetch(const BufView& v, float4* r) const {
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       if (VEC) {
-        r[i] = *reinterpret_cast<const float4*>(p + off[i]);
+        r[i] = buf_ld4(v, off[i]);
       } else {
-        r[i].x = p[off[4 * i]];
-        r[i].y = p[off[4 * i + 1]];
-        r[i].z = p[off[4 * i + 2]];
-        r[i].w = p[off[4 * i + 3]];
+        r[i].x = buf_ld1(v, off[4 * i]);
+        r[i].y = buf_ld1(v, off[4 * i + 1]);
+        r[i].z = buf_ld1(v, off[4 * i + 2]);
+        r[i].w = buf_ld1(v, off[4 * i + 3]);
       }
     }
   }
-  template <int SET>
-  AX_HD float4 masked(const float4& v, int i) const {
-    const uint32_t m = ok[SET] >> (VEC ? i : 4 * i);
-    float4 o;
-    o.x = (m & 1u) ? v.x : 0.f;
-    o.y = (VEC ? (m & 1u) : (m & 2u)) ? v.y : 0.f;
-    o.z = (VEC ? (m & 1u) : (m & 4u)) ? v.z : 0.f;
-    o.w = (VEC ? (m & 1u) : (m & 8u)) ? v.w : 0.f;
-    return o;
-  }
 };
-// four floats that are consecutive in k go to four LDS rows
-AX_HD void lds_put_k4(float* d, int ldt, const float4& v) {
-  d[0] = v.x;
-  d[ldt] = v.y;
-  d[2 * ldt] = v.z;
-  d[3 * ldt] = v.w;
-}
 
 template <int ROWS, int BK, bool VEC>
 struct DenseKInner {
   static constexpr int QK = BK / 4, NQ = ROWS * QK, NL = NQ / kThreads, NA = NL;
+  static constexpr bool kRowMajor = true;
+  static constexpr int LD = BK + 4, LDS_FLOATS = ROWS * LD;
   static_assert(NQ % kThreads == 0, "tile must be a whole number of loads per thread");
   typedef DenseParams Params;
-  const float* p;
-  uint32_t ld;
-  int R, tid, row0;
-  PlanRegs<NL, VEC> pl;
-  AX_HD DenseKInner(const Params& a, int g, int tid_, int row0_)
-      : p(a.p + (long)g * a.gstride), ld((uint32_t)a.ld), R(a.R), tid(tid_), row0(row0_) {}
-  template <int S>
-  AX_HD void addr_step(int k0, int kend) {
-    if (S == 0) pl.okn = 0;
-    const int idx = tid + S * kThreads;
-    const int row = row0 + idx / QK, k = k0 + 4 * (idx % QK);
-    const bool rok = row < R;
-    const uint32_t off = (uint32_t)row * ld + (uint32_t)k;
-    if (VEC) {
-      pl.put(S, off, rok && k < kend);
-    } else {
+  BufView v;
+  int tid, kq;
+  uint32_t base[NL];  // byte offset of (row, 4*kq), or kOob for a row past the end
+  Offsets<NL, VEC> pl;
+  AX_HD DenseKInner(const Params& a, int g, int tid_, int row0)
+      : v(make_view(a.p + (long)g * a.gstride, a.bytes - (uint32_t)(g * a.gstride * 4))), tid(tid_) {
+    kq = tid % QK;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) pl.put(4 * S + j, off + j, rok && k + j < kend);
+    for (int i = 0; i < NL; ++i) {
+      const int row = row0 + (tid + i * kThreads) / QK;
+      base[i] = row < a.R ? ((uint32_t)row * (uint32_t)a.ld + 4u * kq) * 4u : kOob;
     }
   }
-  template <int SET>
-  AX_HD void fetch(float4* r) { pl.template fetch<SET>(p, r); }
-  template <int SET>
-  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
-    const int idx = tid + s * kThreads;
-    lds_put_k4(lds + (4 * (idx % QK)) * ldt + idx / QK, ldt, pl.template masked<SET>(r[s], s));
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int k = k0 + 4 * kq;
+    if (VEC) {
+      pl.off[S] = k < kend ? base[S] + (uint32_t)k0 * 4u : kOob;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) pl.off[4 * S + j] = k + j < kend ? base[S] + (uint32_t)(k0 + j) * 4u : kOob;
+    }
+  }
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int s, float* lds, const float4* r) const {
+    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QK) * LD + 4 * kq) = r[s];
   }
 };
 
@@ -198,34 +214,41 @@ template <int ROWS, int BK, bool VEC>
 struct DenseRowInner {
   static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = (NQ + kThreads - 1) / kThreads, NA = NL;
   static constexpr bool kWhole = NQ % kThreads == 0;  // else the last load of some threads is outside the tile
+  static constexpr bool kRowMajor = false;
+  static constexpr int LD = ROWS + 4, LDS_FLOATS = BK * LD;
   typedef DenseParams Params;
-  const float* p;
-  uint32_t ld;
-  int R, tid, row0;
-  PlanRegs<NL, VEC> pl;
-  AX_HD DenseRowInner(const Params& a, int g, int tid_, int row0_)
-      : p(a.p + (long)g * a.gstride), ld((uint32_t)a.ld), R(a.R), tid(tid_), row0(row0_) {}
-  template <int S>
-  AX_HD void addr_step(int k0, int kend) {
-    if (S == 0) pl.okn = 0;
-    const int idx = tid + S * kThreads;
-    const int row = row0 + 4 * (idx % QR), k = k0 + idx / QR;
-    const bool kok = k < kend && (kWhole || idx < NQ);
-    const uint32_t off = (uint32_t)k * ld + (uint32_t)row;
-    if (VEC) {
-      pl.put(S, off, kok && row < R);
-    } else {
+  BufView v;
+  int tid;
+  uint32_t ld4;                          // leading dimension in bytes
+  uint32_t base[VEC ? NL : 4 * NL];      // byte offset of (kl, row), or kOob
+  Offsets<NL, VEC> pl;
+  AX_HD DenseRowInner(const Params& a, int g, int tid_, int row0)
+      : v(make_view(a.p + (long)g * a.gstride, a.bytes - (uint32_t)(g * a.gstride * 4))), tid(tid_) {
+    ld4 = (uint32_t)a.ld * 4u;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) pl.put(4 * S + j, off + j, kok && row + j < R);
+    for (int i = 0; i < NL; ++i) {
+      const int idx = tid + i * kThreads;
+      const int row = row0 + 4 * (idx % QR), kl = idx / QR;
+      const bool in = kWhole || idx < NQ;
+#pragma unroll
+      for (int j = 0; j < (VEC ? 1 : 4); ++j)
+        base[VEC ? i : 4 * i + j] = in && row + j < a.R ? (uint32_t)kl * ld4 + (uint32_t)(row + j) * 4u : kOob;
     }
   }
-  template <int SET>
-  AX_HD void fetch(float4* r) { pl.template fetch<SET>(p, r); }
-  template <int SET>
-  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int k = k0 + (tid + S * kThreads) / QR;
+    const uint32_t adv = (uint32_t)k0 * ld4;
+#pragma unroll
+    for (int j = 0; j < (VEC ? 1 : 4); ++j) {
+      const int e = VEC ? S : 4 * S + j;
+      pl.off[e] = k < kend ? base[e] + adv : kOob;
+    }
+  }
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int s, float* lds, const float4* r) const {
     const int idx = tid + s * kThreads;
-    if (kWhole || idx < NQ)
-      *reinterpret_cast<float4*>(lds + (idx / QR) * ldt + 4 * (idx % QR)) = pl.template masked<SET>(r[s], s);
+    if (kWhole || idx < NQ) *reinterpret_cast<float4*>(lds + (idx / QR) * LD + 4 * (idx % QR)) = r[s];
   }
 };
 
@@ -238,6 +261,7 @@ struct DenseRowInner {
 // (modes 1 and 2 are the gather form of the adjoint of a convolution).
 struct Im2colParams {
   const float* x;
+  uint32_t bytes;   // extent of the tensor
   int H, W, Ctot;   // tensor being gathered from
   int Cg;           // channels per group (extent of c)
   int c_stride_g;   // channel offset added per group
@@ -270,57 +294,65 @@ AX_HD PixCoord decode_pixel(int p, const Im2colParams& g) {
   c.x = rem - c.y * g.OW;
   return c;
 }
-// pixel offset iy*W + ix of tap (r,s) seen from origin (y0,x0); ok = inside the tensor
+constexpr int kFar = 1 << 28;  // coordinate that puts every tap outside the tensor
+
+// Byte offset of tap (r,s,c) seen from a pixel whose origin is (y0, x0) and
+// whose origin offset is rowbase = ((n*H*W + y0*W + x0)*Ctot + c_off)*4 (mod 2^32).
 template <int MODE>
-AX_HD uint32_t tap_offset(const Im2colParams& g, int y0, int x0, int r, int s, bool& ok) {
-  int iy, ix;
-  if (MODE == IM2COL_FWD) {
-    iy = y0 + r;
-    ix = x0 + s;
-    ok = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
-  } else if (MODE == IM2COL_T1) {
-    iy = y0 - r;
-    ix = x0 - s;
-    ok = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
-  } else {
-    const int ty = y0 - r, tx = x0 - s;
+AX_HD uint32_t tap_address(const Im2colParams& g, uint32_t rowbase, int y0, int x0, const TapCoord& t) {
+  if (MODE == IM2COL_TS) {
+    const int ty = y0 - t.r, tx = x0 - t.s;
     const bool pos = ty >= 0 && tx >= 0;
-    iy = (int)fdiv((uint32_t)(pos ? ty : 0), g.d_stride);
-    ix = (int)fdiv((uint32_t)(pos ? tx : 0), g.d_stride);
-    ok = pos && iy * g.stride == ty && ix * g.stride == tx && iy < g.H && ix < g.W;
+    const int iy = (int)fdiv((uint32_t)(pos ? ty : 0), g.d_stride);
+    const int ix = (int)fdiv((uint32_t)(pos ? tx : 0), g.d_stride);
+    const bool ok = pos && iy * g.stride == ty && ix * g.stride == tx && iy < g.H && ix < g.W;
+    // rowbase is the offset of (n, 0, 0, c_off) in this mode
+    return ok ? rowbase + ((uint32_t)(iy * g.W + ix) * (uint32_t)g.Ctot + (uint32_t)t.c) * 4u : kOob;
   }
-  return (uint32_t)iy * (uint32_t)g.W + (uint32_t)ix;  // unsigned: wraps harmlessly when the tap is outside
+  const int iy = MODE == IM2COL_FWD ? y0 + t.r : y0 - t.r;
+  const int ix = MODE == IM2COL_FWD ? x0 + t.s : x0 - t.s;
+  const bool ok = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
+  const uint32_t tap = (((uint32_t)t.r * (uint32_t)g.W + (uint32_t)t.s) * (uint32_t)g.Ctot) * 4u;
+  const uint32_t o = (MODE == IM2COL_FWD ? rowbase + tap : rowbase - tap) + (uint32_t)t.c * 4u;
+  return ok ? o : kOob;
 }
-constexpr int kInvalidCoord = -(1 << 28);
+template <int MODE>
+AX_HD uint32_t row_base(const Im2colParams& g, int n, int y0, int x0, int c_off) {
+  const uint32_t img = (uint32_t)n * (uint32_t)(g.H * g.W);
+  if (MODE == IM2COL_TS) return (img * (uint32_t)g.Ctot + (uint32_t)c_off) * 4u;
+  return ((img + (uint32_t)y0 * (uint32_t)g.W + (uint32_t)x0) * (uint32_t)g.Ctot + (uint32_t)c_off) * 4u;
+}
 
 template <int ROWS, int BK, bool VEC, int MODE>
 struct Im2colKInner {
   static constexpr int QK = BK / 4, NQ = ROWS * QK, NL = NQ / kThreads, NA = NL + 1;
+  static constexpr bool kRowMajor = true;
+  static constexpr int LD = BK + 4, LDS_FLOATS = ROWS * LD;
   static_assert(kThreads % QK == 0 && NQ % kThreads == 0, "every load of a thread shares its k quad");
   typedef Im2colParams Params;
   Im2colParams g;
-  int c_off, tid, kq;
-  uint32_t nb[NL];  // pixel index of (n, 0, 0)
+  BufView v;
+  int tid, kq;
+  uint32_t rowbase[NL];
   int y0[NL], x0[NL];
   TapCoord tap[VEC ? 1 : 4];
-  uint32_t kok;
-  PlanRegs<NL, VEC> pl;
-  AX_HD Im2colKInner(const Params& a, int grp, int tid_, int row0) : g(a), c_off(grp * a.c_stride_g), tid(tid_) {
+  Offsets<NL, VEC> pl;
+  AX_HD Im2colKInner(const Params& a, int grp, int tid_, int row0) : g(a), v(make_view(a.x, a.bytes)), tid(tid_) {
     kq = tid % QK;
+    const int c_off = grp * a.c_stride_g;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       const int p = row0 + (tid + i * kThreads) / QK;
       const bool in = p < g.P;
       const PixCoord c = decode_pixel(in ? p : 0, g);
-      nb[i] = (uint32_t)c.n * (uint32_t)(g.H * g.W);
       if (MODE == IM2COL_FWD) {
-        y0[i] = in ? c.y * g.stride - g.pad : kInvalidCoord;
+        y0[i] = in ? c.y * g.stride - g.pad : -kFar;
         x0[i] = c.x * g.stride - g.pad;
       } else {
-        // rows past the end get an origin whose every tap is above the tensor
-        y0[i] = in ? c.y + g.pad : -1;
+        y0[i] = in ? c.y + g.pad : -kFar;
         x0[i] = c.x + g.pad;
       }
+      rowbase[i] = row_base<MODE>(g, c.n, in ? y0[i] : 0, x0[i], c_off);
     }
   }
   // step 0 decodes the taps of the thread's k quad, step 1+i places load i
@@ -328,75 +360,63 @@ struct Im2colKInner {
   AX_HD void addr_step(int k0, int kend) {
     const int k = k0 + 4 * kq;
     if (S == 0) {
-      pl.okn = 0;
-      kok = 0;
 #pragma unroll
       for (int j = 0; j < (VEC ? 1 : 4); ++j) {
         tap[j] = decode_tap(k + j, g);
-        kok |= (uint32_t)(k + j < kend) << j;
+        // a k past the end turns into a tap far outside the picture
+        if (k + j >= kend) tap[j].r = MODE == IM2COL_FWD ? 2 * kFar : -2 * kFar;
       }
     } else {
       constexpr int i = S - 1;
 #pragma unroll
-      for (int j = 0; j < (VEC ? 1 : 4); ++j) {
-        bool ok;
-        const uint32_t po = tap_offset<MODE>(g, y0[i], x0[i], tap[j].r, tap[j].s, ok);
-        const uint32_t off = (nb[i] + po) * (uint32_t)g.Ctot + (uint32_t)(c_off + tap[j].c);
-        pl.put(VEC ? i : 4 * i + j, off, ok && ((kok >> j) & 1u));
-      }
+      for (int j = 0; j < (VEC ? 1 : 4); ++j)
+        pl.off[VEC ? i : 4 * i + j] = tap_address<MODE>(g, rowbase[i], y0[i], x0[i], tap[j]);
     }
   }
-  template <int SET>
-  AX_HD void fetch(float4* r) { pl.template fetch<SET>(g.x, r); }
-  template <int SET>
-  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
-    lds_put_k4(lds + (4 * kq) * ldt + (tid + s * kThreads) / QK, ldt, pl.template masked<SET>(r[s], s));
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int s, float* lds, const float4* r) const {
+    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QK) * LD + 4 * kq) = r[s];
   }
 };
 
 template <int ROWS, int BK, bool VEC>
 struct Im2colRowInner {
   static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = NQ / kThreads, NA = NL;
+  static constexpr bool kRowMajor = false;
+  static constexpr int LD = ROWS + 4, LDS_FLOATS = BK * LD;
   static_assert(kThreads % QR == 0 && NQ % kThreads == 0, "every load of a thread shares its row quad");
   typedef Im2colParams Params;
   Im2colParams g;
-  int c_off, tid, rq;
-  int rr[VEC ? 1 : 4], ss[VEC ? 1 : 4], cc[VEC ? 1 : 4];  // taps of the thread's rows; rr = kInvalidCoord past the end
-  PlanRegs<NL, VEC> pl;
-  AX_HD Im2colRowInner(const Params& a, int grp, int tid_, int row0) : g(a), c_off(grp * a.c_stride_g), tid(tid_) {
+  BufView v;
+  int tid, rq, c_off;
+  TapCoord tap[VEC ? 1 : 4];  // taps of the thread's rows; r = 2*kFar for a row past the end
+  Offsets<NL, VEC> pl;
+  AX_HD Im2colRowInner(const Params& a, int grp, int tid_, int row0)
+      : g(a), v(make_view(a.x, a.bytes)), tid(tid_), c_off(grp * a.c_stride_g) {
     rq = tid % QR;
     const int rtot = g.kh * g.kw * g.Cg;
 #pragma unroll
     for (int j = 0; j < (VEC ? 1 : 4); ++j) {
       const int m = row0 + 4 * rq + j;
       const bool in = m < rtot;
-      const TapCoord t = decode_tap(in ? m : 0, g);
-      rr[j] = in ? t.r : kInvalidCoord;  // pushes every tap above the tensor
-      ss[j] = t.s;
-      cc[j] = t.c;
+      tap[j] = decode_tap(in ? m : 0, g);
+      if (!in) tap[j].r = 2 * kFar;
     }
   }
   template <int S>
   AX_HD void addr_step(int k0, int kend) {
-    if (S == 0) pl.okn = 0;
     const int p = k0 + (tid + S * kThreads) / QR;
     const bool pok = p < kend;
     const PixCoord c = decode_pixel(pok ? p : 0, g);
-    const uint32_t nbase = (uint32_t)c.n * (uint32_t)(g.H * g.W);
-    const int y0 = c.y * g.stride - g.pad, x0 = c.x * g.stride - g.pad;
+    const int y0 = pok ? c.y * g.stride - g.pad : -kFar, x0 = c.x * g.stride - g.pad;
+    const uint32_t rb = row_base<IM2COL_FWD>(g, c.n, pok ? y0 : 0, x0, c_off);
 #pragma unroll
-    for (int j = 0; j < (VEC ? 1 : 4); ++j) {
-      bool ok;
-      const uint32_t po = tap_offset<IM2COL_FWD>(g, y0, x0, rr[j], ss[j], ok);
-      const uint32_t off = (nbase + po) * (uint32_t)g.Ctot + (uint32_t)(c_off + cc[j]);
-      pl.put(VEC ? S : 4 * S + j, off, ok && pok);
-    }
+    for (int j = 0; j < (VEC ? 1 : 4); ++j)
+      pl.off[VEC ? S : 4 * S + j] = tap_address<IM2COL_FWD>(g, rb, y0, x0, tap[j]);
   }
-  template <int SET>
-  AX_HD void fetch(float4* r) { pl.template fetch<SET>(g.x, r); }
-  template <int SET>
-  AX_HD void store_step(int s, float* lds, int ldt, const float4* r) const {
-    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QR) * ldt + 4 * rq) = pl.template masked<SET>(r[s], s);
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int s, float* lds, const float4* r) const {
+    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QR) * LD + 4 * rq) = r[s];
   }
 };
 
@@ -408,10 +428,15 @@ AX_HD void plan_all(L& l, int k0, int kend) {
     plan_all<L, S + 1>(l, k0, kend);
   }
 }
-template <int SET, class L>
-AX_HD void store_all(const L& l, float* lds, int ldt, const float4* r) {
+template <class L>
+AX_HD void store_all(const L& l, float* lds, const float4* r) {
 #pragma unroll
-  for (int s = 0; s < L::NL; ++s) l.template store_step<SET>(s, lds, ldt, r);
+  for (int s = 0; s < L::NL; ++s) l.store_step(s, lds, r);
+}
+// element (row, k) of an LDS tile written by loader L
+template <class L>
+AX_HD int lds_index(int row, int k) {
+  return L::kRowMajor ? row * L::LD + k : k * L::LD + row;
 }
 
 // ================================ epilogues ==================================
@@ -459,88 +484,98 @@ struct EpiSlab {
 #ifndef AX_HOST_EMU
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// ---- the k-tile: MFMAs with the rest of the pipeline in their shadow ----------
-// While the MFMAs of tile t run, the same wave (a) writes tile t+1, which was
-// fetched one iteration ago, to the other LDS buffer and (b) computes the
-// addresses of tile t+3.  That side work is cut into steps and dealt out over
-// the k-pairs of the tile; a scheduling fence after every k-pair keeps each
-// portion in the shadow of that pair's MFMAs instead of in one lump after them.
-template <class T, class AL, class BL, int SET, int IDX>
+// Fragments of one operand for a wave: TT 32-row blocks starting at LDS row `row`.
+// [row][k] tiles give a lane all its values of the k-tile in BK/8 16-byte reads;
+// [k][row] tiles are read 4 bytes at a time, one MFMA step ahead.
+template <class L, int TT, int BK>
+struct Frags {
+  float4 rk[L::kRowMajor ? TT : 1][L::kRowMajor ? BK / 8 : 1];
+  float kr[2][TT];
+  const float* base;
+  int kh;
+  __device__ __forceinline__ void begin(const float* lds, int row, int kh_) {
+    kh = kh_;
+    if (L::kRowMajor) {
+      base = lds + row * L::LD + 4 * kh;
+#pragma unroll
+      for (int t = 0; t < TT; ++t)
+#pragma unroll
+        for (int q = 0; q < BK / 8; ++q) rk[t][q] = *reinterpret_cast<const float4*>(base + t * 32 * L::LD + 8 * q);
+    } else {
+      base = lds + row;
+      read<0>();
+    }
+  }
+  template <int U>
+  __device__ __forceinline__ void read() {  // [k][row] values of MFMA step U
+    if (!L::kRowMajor) {
+      const int k = 8 * (U >> 2) + (U & 3) + 4 * kh;
+#pragma unroll
+      for (int t = 0; t < TT; ++t) kr[U & 1][t] = base[k * L::LD + t * 32];
+    }
+  }
+  template <int U>
+  __device__ __forceinline__ float get(int t) const {
+    if (L::kRowMajor) {
+      const float4& v = rk[t][U >> 2];
+      return (U & 3) == 0 ? v.x : (U & 3) == 1 ? v.y : (U & 3) == 2 ? v.z : v.w;
+    }
+    return kr[U & 1][t];
+  }
+};
+
+// Side work of one main-loop iteration: LDS stores of tile t+1, addresses of tile t+3.
+template <class T, class AL, class BL, int IDX>
 __device__ __forceinline__ void side_step(AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
                                           const float4* rb, int k_plan, int kend) {
   constexpr int S0 = AL::NL, S1 = S0 + BL::NL, S2 = S1 + AL::NA, S3 = S2 + BL::NA;
   if constexpr (IDX < S0) {
-    al.template store_step<SET>(IDX, as_next, T::LDA, ra);
+    al.store_step(IDX, as_next, ra);
   } else if constexpr (IDX < S1) {
-    bl.template store_step<SET>(IDX - S0, bs_next, T::LDB, rb);
+    bl.store_step(IDX - S0, bs_next, rb);
   } else if constexpr (IDX < S2) {
     al.template addr_step<IDX - S1>(k_plan, kend);
   } else if constexpr (IDX < S3) {
     bl.template addr_step<IDX - S2>(k_plan, kend);
   }
 }
-template <class T, class AL, class BL, int SET, int Q, int U = 0>
+template <class T, class AL, class BL, int U, int W = 0>
 __device__ __forceinline__ void side_slot(AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
                                           const float4* rb, int k_plan, int kend) {
   constexpr int TOTAL = AL::NL + BL::NL + AL::NA + BL::NA, KP = T::BK / 2, PER = (TOTAL + KP - 1) / KP;
-  if constexpr (U < PER) {
-    side_step<T, AL, BL, SET, Q * PER + U>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
-    side_slot<T, AL, BL, SET, Q, U + 1>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+  if constexpr (W < PER) {
+    side_step<T, AL, BL, U * PER + W>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    side_slot<T, AL, BL, U, W + 1>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
   }
 }
 
-template <class T, class AL, class BL, int SET, bool SIDE, int Q = 0>
-__device__ __forceinline__ void tile_stream(const float* __restrict__ as, const float* __restrict__ bs, int kh,
-                                            v16f (&acc)[T::TM][T::TN], float (&a)[2][T::TM], float (&b)[2][T::TN],
-                                            AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
-                                            const float4* rb, int k_plan, int kend) {
+template <class T, class AL, class BL, bool SIDE, int U = 0>
+__device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T::BK>& fa, Frags<BL, T::TN, T::BK>& fb,
+                                            v16f (&acc)[T::TM][T::TN], AL& al, BL& bl, float* as_next,
+                                            float* bs_next, const float4* ra, const float4* rb, int k_plan,
+                                            int kend) {
   constexpr int KP = T::BK / 2;
-  if constexpr (Q < KP) {
-    constexpr int c = Q & 1, n = c ^ 1;
-    if constexpr (Q + 1 < KP) {  // fragments of the next k-pair, one pair ahead of their MFMAs
-      const int kr = 2 * (Q + 1) + kh;
-#pragma unroll
-      for (int i = 0; i < T::TM; ++i) a[n][i] = as[kr * T::LDA + i * 32];
-#pragma unroll
-      for (int j = 0; j < T::TN; ++j) b[n][j] = bs[kr * T::LDB + j * 32];
+  if constexpr (U < KP) {
+    if constexpr (U + 1 < KP) {
+      fa.template read<U + 1>();
+      fb.template read<U + 1>();
     }
 #pragma unroll
     for (int i = 0; i < T::TM; ++i)
 #pragma unroll
       for (int j = 0; j < T::TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
-    if constexpr (SIDE) side_slot<T, AL, BL, SET, Q>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.template get<U>(i), fb.template get<U>(j), acc[i][j], 0, 0, 0);
+    if constexpr (SIDE) side_slot<T, AL, BL, U>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
     __builtin_amdgcn_sched_barrier(0);
-    tile_stream<T, AL, BL, SET, SIDE, Q + 1>(as, bs, kh, acc, a, b, al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    tile_stream<T, AL, BL, SIDE, U + 1>(fa, fb, acc, al, bl, as_next, bs_next, ra, rb, k_plan, kend);
   }
-}
-
-// One iteration of the main loop for tile t, PAR = t & 1.  Register set PAR
-// receives tile t+2, register set PAR^1 (tile t+1) is written to LDS buffer PAR^1.
-template <class T, class AL, class BL, int PAR>
-__device__ __forceinline__ void main_iter(float (&As)[2][T::BK * T::LDA], float (&Bs)[2][T::BK * T::LDB], int a_off,
-                                          int b_off, int kh, v16f (&acc)[T::TM][T::TN], AL& al, BL& bl,
-                                          float4 (&ra)[2][AL::NL], float4 (&rb)[2][BL::NL], int k_plan, int kend) {
-  al.template fetch<PAR>(ra[PAR]);
-  bl.template fetch<PAR>(rb[PAR]);
-  float a[2][T::TM], b[2][T::TN];
-  const float* as = As[PAR] + a_off;
-  const float* bs = Bs[PAR] + b_off;
-#pragma unroll
-  for (int i = 0; i < T::TM; ++i) a[0][i] = as[kh * T::LDA + i * 32];
-#pragma unroll
-  for (int j = 0; j < T::TN; ++j) b[0][j] = bs[kh * T::LDB + j * 32];
-  __builtin_amdgcn_sched_barrier(0);
-  tile_stream<T, AL, BL, PAR ^ 1, true>(as, bs, kh, acc, a, b, al, bl, As[PAR ^ 1], Bs[PAR ^ 1], ra[PAR ^ 1],
-                                        rb[PAR ^ 1], k_plan, kend);
-  __syncthreads();
 }
 
 template <class T, class AL, class BL, class Epi>
 __global__ void __launch_bounds__(kThreads)
 gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk, int nsplit) {
-  __shared__ __attribute__((aligned(16))) float As[2][T::BK * T::LDA];
-  __shared__ __attribute__((aligned(16))) float Bs[2][T::BK * T::LDB];
+  __shared__ __attribute__((aligned(16))) float As[2][AL::LDS_FLOATS];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BL::LDS_FLOATS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
   const int z = blockIdx.z, g = z / nsplit, split = z - g * nsplit;
@@ -561,28 +596,45 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int a_off = wm * (T::TM * 32) + (lane & 31), b_off = wn * (T::TN * 32) + (lane & 31), kh = lane >> 5;
+  const int a_row = wm * (T::TM * 32) + (lane & 31), b_row = wn * (T::TN * 32) + (lane & 31), kh = lane >> 5;
   if (nt > 0) {
     // prologue: tile 0 -> LDS buffer 0, tile 1 in flight in register set 1, addresses of tile 2 ready.
-    // Tiles past the end have every predicate off: they fetch element 0 and store zeros, harmlessly.
+    // Tiles past the end have every offset outside: they load zeros and store zeros, harmlessly.
     float4 ra[2][AL::NL], rb[2][BL::NL];
     plan_all(al, kbeg, kend);
     plan_all(bl, kbeg, kend);
-    al.template fetch<0>(ra[0]);
-    bl.template fetch<0>(rb[0]);
+    al.fetch(ra[0]);
+    bl.fetch(rb[0]);
     plan_all(al, kbeg + T::BK, kend);
     plan_all(bl, kbeg + T::BK, kend);
-    al.template fetch<1>(ra[1]);
-    bl.template fetch<1>(rb[1]);
-    store_all<0>(al, As[0], T::LDA, ra[0]);
-    store_all<0>(bl, Bs[0], T::LDB, rb[0]);
+    al.fetch(ra[1]);
+    bl.fetch(rb[1]);
+    store_all(al, As[0], ra[0]);
+    store_all(bl, Bs[0], rb[0]);
     plan_all(al, kbeg + 2 * T::BK, kend);
     plan_all(bl, kbeg + 2 * T::BK, kend);
     __syncthreads();
+    Frags<AL, T::TM, T::BK> fa;
+    Frags<BL, T::TN, T::BK> fb;
+    // iteration t (parity p): fetch tile t+2 into register set p, MFMAs of tile t from LDS buffer p,
+    // meanwhile store register set p^1 (tile t+1) to LDS buffer p^1 and address tile t+3.
     for (int t = 0; t < nt; t += 2) {
-      main_iter<T, AL, BL, 0>(As, Bs, a_off, b_off, kh, acc, al, bl, ra, rb, kbeg + (t + 3) * T::BK, kend);
-      if (t + 1 < nt)
-        main_iter<T, AL, BL, 1>(As, Bs, a_off, b_off, kh, acc, al, bl, ra, rb, kbeg + (t + 4) * T::BK, kend);
+      al.fetch(ra[0]);
+      bl.fetch(rb[0]);
+      fa.begin(As[0], a_row, kh);
+      fb.begin(Bs[0], b_row, kh);
+      __builtin_amdgcn_sched_barrier(0);
+      tile_stream<T, AL, BL, true>(fa, fb, acc, al, bl, As[1], Bs[1], ra[1], rb[1], kbeg + (t + 3) * T::BK, kend);
+      __syncthreads();
+      if (t + 1 < nt) {
+        al.fetch(ra[1]);
+        bl.fetch(rb[1]);
+        fa.begin(As[1], a_row, kh);
+        fb.begin(Bs[1], b_row, kh);
+        __builtin_amdgcn_sched_barrier(0);
+        tile_stream<T, AL, BL, true>(fa, fb, acc, al, bl, As[0], Bs[0], ra[0], rb[0], kbeg + (t + 4) * T::BK, kend);
+        __syncthreads();
+      }
     }
   }
 

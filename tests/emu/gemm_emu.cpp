@@ -18,6 +18,12 @@ struct float4 {
 };
 #define AX_HOST_EMU 1
 #include "../../paper_1412_2302_amd/csrc/conv_plan.h"
+namespace ax {
+inline void emu_fail(const char* what) {
+  fprintf(stderr, "EMULATION FAULT: %s\n", what);
+  abort();
+}
+}  // namespace ax
 
 using namespace ax;
 
@@ -25,7 +31,7 @@ template <class T, class AL, class BL, class Epi>
 static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk,
                      int nsplit, int groups) {
   const int gx = (M + T::BM - 1) / T::BM, gy = (N + T::BN - 1) / T::BN, gz = groups * nsplit;
-  std::vector<float> As(T::BK * T::LDA), Bs(T::BK * T::LDB);
+  std::vector<float> As(AL::LDS_FLOATS), Bs(BL::LDS_FLOATS);
   std::vector<float> acc((size_t)4 * T::TM * T::TN * 64 * 16);
   auto ACC = [&](int wave, int i, int j, int lane, int r) -> float& {
     return acc[((((size_t)wave * T::TM + i) * T::TN + j) * 64 + lane) * 16 + r];
@@ -50,26 +56,19 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
             float4 ra[AL::NL], rb[BL::NL];
             plan_all(al, kbeg + t * T::BK, kend);
             plan_all(bl, kbeg + t * T::BK, kend);
-            if (t & 1) {  // exercise both register sets
-              al.template fetch<1>(ra);
-              bl.template fetch<1>(rb);
-              store_all<1>(al, As.data(), T::LDA, ra);
-              store_all<1>(bl, Bs.data(), T::LDB, rb);
-            } else {
-              al.template fetch<0>(ra);
-              bl.template fetch<0>(rb);
-              store_all<0>(al, As.data(), T::LDA, ra);
-              store_all<0>(bl, Bs.data(), T::LDB, rb);
-            }
+            al.fetch(ra);
+            bl.fetch(rb);
+            store_all(al, As.data(), ra);
+            store_all(bl, Bs.data(), rb);
           }
           for (int wave = 0; wave < 4; ++wave) {
             const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
             for (int kk = 0; kk < T::BK / 2; ++kk) {
               float a[64][T::TM], b[64][T::TN];
               for (int lane = 0; lane < 64; ++lane) {
-                const int kr = frag_k(lane, kk);
-                for (int i = 0; i < T::TM; ++i) a[lane][i] = As[kr * T::LDA + wm * (T::TM * 32) + (lane & 31) + i * 32];
-                for (int j = 0; j < T::TN; ++j) b[lane][j] = Bs[kr * T::LDB + wn * (T::TN * 32) + (lane & 31) + j * 32];
+                const int kr = step_k(kk, lane >> 5);
+                for (int i = 0; i < T::TM; ++i) a[lane][i] = As[lds_index<AL>(wm * (T::TM * 32) + (lane & 31) + i * 32, kr)];
+                for (int j = 0; j < T::TN; ++j) b[lane][j] = Bs[lds_index<BL>(wn * (T::TN * 32) + (lane & 31) + j * 32, kr)];
               }
               // D[ii][jj] += sum_{k2<2} A[ii][k2] * B[k2][jj], lane k2*32+ii holds A[ii][k2], lane k2*32+jj holds B[k2][jj]
               for (int i = 0; i < T::TM; ++i)
@@ -262,7 +261,7 @@ static void dense_case() {
     std::vector<float> y(Bn * Out, NAN);
     std::vector<double> ref(Bn * Out, 0.0);
     for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * Out + o] += (double)x[n * In + i] * w[o * In + i];
-    DenseParams a{x, In, 0, Bn}, b{w, In, 0, Out};
+    DenseParams a{x, In, 0, Bn, Bn * In * 4}, b{w, In, 0, Out, Out * In * 4};
     EpiSlab e{y.data(), (long)Bn * Out, Out, nullptr};
     emu_gemm<T, DenseKInner<128, 16, true>, DenseKInner<128, 16, true>, EpiSlab>(a, b, e, Bn, Out, In, 32, 1, 1);
     check("fc_fwd", "6x20->10 vec", y, ref);
@@ -274,7 +273,7 @@ static void dense_case() {
     std::vector<float> dx(Bn * In, NAN);
     std::vector<double> ref(Bn * In, 0.0);
     for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * In + i] += (double)dy[n * Out + o] * w[o * In + i];
-    DenseParams a{dy, Out, 0, Bn}, b{w, In, 0, In};
+    DenseParams a{dy, Out, 0, Bn, Bn * Out * 4}, b{w, In, 0, In, Out * In * 4};
     EpiSlab e{dx.data(), (long)Bn * In, In, nullptr};
     emu_gemm<T, DenseKInner<128, 16, false>, DenseRowInner<128, 16, false>, EpiSlab>(a, b, e, Bn, In, Out, 16, 1, 1);
     check("fc_bwd_x", "6x20->10", dx, ref);
@@ -283,7 +282,7 @@ static void dense_case() {
     std::vector<float> dw(Out * In, NAN);
     std::vector<double> ref(Out * In, 0.0);
     for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[o * In + i] += (double)dy[n * Out + o] * x[n * In + i];
-    DenseParams a{dy, Out, 0, Out}, b{x, In, 0, In};
+    DenseParams a{dy, Out, 0, Out, Bn * Out * 4}, b{x, In, 0, In, Bn * In * 4};
     EpiSlab e{dw.data(), (long)Out * In, In, nullptr};
     emu_gemm<T, DenseRowInner<128, 16, false>, DenseRowInner<128, 16, false>, EpiSlab>(a, b, e, Out, In, Bn, 16, 1, 1);
     check("fc_bwd_w", "6x20->10", dw, ref);
