@@ -8,20 +8,50 @@ namespace ax {
 #define AX_BK 16
 #endif
 constexpr int kBK = AX_BK;  // depth of a k-tile
-typedef Tile<128, 128, kBK, 2, 2> T128;
-typedef Tile<128, 96, kBK, 4, 1> T96;
-typedef Tile<128, 64, kBK, 4, 1> T64;
+typedef Tile<128, 128, kBK, 2, 2> T128;  // wave tile 64 x 64
+typedef Tile<128, 96, kBK, 4, 1> T96;    // wave tile 32 x 96
+typedef Tile<128, 64, kBK, 4, 1> T64;    // wave tile 32 x 64
+// (256 x 128 and 256 x 96 tiles were measured too: their 128 accumulator
+// registers leave one wave per SIMD, and with nobody to cover barrier and LDS
+// latency they ran 8-12 % slower than 128 x 128 on every AlexNet layer.)
 
-// Width of the N tile that wastes the fewest padded columns (ties: wider).
-static int pick_bn(int N) {
-  const int opts[3] = {128, 96, 64};
-  int best = 128;
-  long best_cost = -1;
-  for (int i = 0; i < 3; ++i) {
-    const long cost = (long)ceil_div(N, opts[i]) * opts[i];
-    if (best_cost < 0 || cost < best_cost) {
-      best_cost = cost;
-      best = opts[i];
+// ------------------------------------------------------------ tile + split-k ---
+// A launch is as slow as its busiest compute unit.  With few output tiles (338
+// for a 21632 x 256 output at 128 x 128) a third of the chip idles while the
+// rest runs a second tile, so the reduction can be cut into `ns` slices whose
+// partial tiles go to slabs and are added by a finishing kernel in a fixed
+// order.  Larger tiles spend fewer non-MFMA instructions per MFMA but make
+// that quantisation worse.  plan_gemm() prices every (tile, ns) pair with a
+// small model -- rounds of tiles over 256 compute units at the tile's measured
+// MFMA efficiency, padded columns, slab traffic -- and takes the cheapest.
+struct GemmPlan {
+  int bm, bn, ns, kchunk;
+};
+struct TileOption {
+  int bm, bn;
+  double eff;  // fraction of the per-CU fp32 MFMA rate this tile reaches on a long reduction
+};
+static const TileOption kTileOptions[] = {{128, 128, 0.80}, {128, 96, 0.68}, {128, 64, 0.62}};
+
+static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int max_s) {
+  const int ktiles = ceil_div(K, kBK);
+  GemmPlan best{128, 128, 1, ktiles * kBK};
+  double best_t = 1e30;
+  for (int o = 0; o < 3; ++o) {
+    const TileOption& to = kTileOptions[o];
+    const long tiles = (long)ceil_div(M, to.bm) * ceil_div(N, to.bn) * groups;
+    const double t_tile = 2.0 * to.bm * to.bn * (double)ktiles * kBK / (0.614e12 * to.eff);
+    for (int s = 1; s <= max_s && s <= ktiles; ++s) {
+      const int per = ceil_div(ktiles, s);
+      if (ceil_div(ktiles, per) != s) continue;
+      if (s > 1 && per < 6) break;
+      const double rounds = (double)ceil_div(tiles * s, 256);
+      double t = rounds * t_tile * per / ktiles + 4e-6;
+      if (s > 1) t += (s + 1) * out_bytes / 2.5e12 + 6e-6;
+      if (t < best_t * 0.98) {  // prefer earlier (larger, unsplit) candidates unless clearly better
+        best_t = t;
+        best = GemmPlan{to.bm, to.bn, s, per * kBK};
+      }
     }
   }
   return best;
@@ -74,43 +104,11 @@ static int by_vec(bool av, bool bv, const Im2colParams& a, const DenseParams& b,
   return F::template go<T, false, false, Epi>(a, b, e, d, kchunk, ns, st);
 }
 template <class F, class Epi>
-static int by_tile(int bn, bool av, bool bv, const Im2colParams& a, const DenseParams& b, const Epi& e,
-                   const GemmDims& d, int kchunk, int ns, hipStream_t st) {
-  switch (bn) {
-    case 128: return by_vec<F, T128, Epi>(av, bv, a, b, e, d, kchunk, ns, st);
-    case 96: return by_vec<F, T96, Epi>(av, bv, a, b, e, d, kchunk, ns, st);
-    default: return by_vec<F, T64, Epi>(av, bv, a, b, e, d, kchunk, ns, st);
-  }
-}
-
-// ---------------------------------------------------------------- split-k ---
-// A launch is as slow as its busiest compute unit.  With few output tiles (338
-// for a 21632 x 256 output) a third of the chip idles while the rest runs a
-// second tile, so the reduction is cut into `ns` slices whose partial tiles go
-// to slabs and are added by a finishing kernel in a fixed order.  ns minimises
-// a small cost model: rounds of tiles over 256 CUs plus the slab traffic.
-struct SplitPlan {
-  int ns, kchunk;
-};
-static SplitPlan choose_split(long tiles, int K, int bn, double out_bytes, int max_s) {
-  const int ktiles = ceil_div(K, kBK);
-  const double t_tile = 2.0 * 128 * bn * (double)ktiles * kBK / 0.43e12;  // one CU at ~70 % of its fp32 MFMA rate
-  SplitPlan best{1, ktiles * kBK};
-  double best_t = 1e30;
-  for (int s = 1; s <= max_s && s <= ktiles; ++s) {
-    const int per = ceil_div(ktiles, s);
-    const int real = ceil_div(ktiles, per);
-    if (real != s) continue;
-    if (s > 1 && per < 6) break;
-    const double rounds = (double)ceil_div(tiles * s, 256);
-    double t = rounds * t_tile * per / ktiles;
-    if (s > 1) t += (s + 1) * out_bytes / 2.5e12 + 6e-6;
-    if (t < best_t * 0.97) {  // prefer fewer slices unless clearly better
-      best_t = t;
-      best = SplitPlan{s, per * kBK};
-    }
-  }
-  return best;
+static int by_tile(const GemmPlan& p, bool av, bool bv, const Im2colParams& a, const DenseParams& b, const Epi& e,
+                   const GemmDims& d, hipStream_t st) {
+  if (p.bn == 128) return by_vec<F, T128, Epi>(av, bv, a, b, e, d, p.kchunk, p.ns, st);
+  if (p.bn == 96) return by_vec<F, T96, Epi>(av, bv, a, b, e, d, p.kchunk, p.ns, st);
+  return by_vec<F, T64, Epi>(av, bv, a, b, e, d, p.kchunk, p.ns, st);
 }
 
 // out[m][g*N + n] = post(sum_s ws[(g*ns + s)][m][n]); post = +bias, ReLU, or gate by a forward activation
@@ -143,85 +141,72 @@ static int launch_slab_finish(const float* ws, int ns, int groups, long M, int N
 }
 
 // ------------------------------------------------------------- convolution ---
-static SplitPlan fwd_plan(const ConvGeom& c, int* bn) {
+static GemmPlan fwd_plan(const ConvGeom& c) {
   const GemmDims d = fwd_dims(c);
-  *bn = pick_bn(d.N);
-  const long tiles = (long)ceil_div(d.M, 128) * ceil_div(d.N, *bn) * d.groups;
-  return choose_split(tiles, d.K, *bn, (double)c.out_elems() * 4, 8);
+  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.out_elems() * 4, 8);
 }
-static SplitPlan bwdd_plan(const ConvGeom& c, int* bn) {
+static GemmPlan bwdd_plan(const ConvGeom& c) {
   const GemmDims d = bwdd_dims(c);
-  *bn = pick_bn(d.N);
-  const long tiles = (long)ceil_div(d.M, 128) * ceil_div(d.N, *bn) * d.groups;
-  return choose_split(tiles, d.K, *bn, (double)c.in_elems() * 4, 8);
+  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8);
+}
+static GemmPlan bwdw_plan(const ConvGeom& c) {
+  const GemmDims d = bwdw_dims(c);
+  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.w_elems() * 4, 256);
 }
 size_t conv_fwd_ws_floats(const ConvGeom& c) {
-  int bn;
-  const SplitPlan p = fwd_plan(c, &bn);
+  const GemmPlan p = fwd_plan(c);
   return p.ns > 1 ? (size_t)p.ns * c.out_elems() : 0;
 }
 size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
-  int bn;
-  const SplitPlan p = bwdd_plan(c, &bn);
+  const GemmPlan p = bwdd_plan(c);
   return p.ns > 1 ? (size_t)p.ns * c.in_elems() : 0;
+}
+size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
+  const GemmPlan p = bwdw_plan(c);
+  return p.ns > 1 ? (size_t)p.ns * c.w_elems() : 0;
 }
 
 int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
                     float* ws, hipStream_t st) {
   const GemmDims d = fwd_dims(c);
-  int bn;
-  const SplitPlan p = fwd_plan(c, &bn);
+  const GemmPlan p = fwd_plan(c);
   const bool av = fwd_A_vec(c, x), bv = fwd_B_vec(c, wf);
   if (p.ns == 1) {
     EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
-    return by_tile<ConvGather<IM2COL_FWD>>(bn, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, p.kchunk, 1, st);
+    return by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
-  AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(bn, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, p.kchunk, p.ns, st)));
+  AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, st)));
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st);
 }
 
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
                          float* ws, hipStream_t st) {
   const GemmDims d = bwdd_dims(c);
-  int bn;
-  const SplitPlan p = bwdd_plan(c, &bn);
+  const GemmPlan p = bwdd_plan(c);
   const bool av = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb), bv = bwdd_B_vec(c, wb);
   const Im2colParams a = bwdd_A(c, dy);
   const DenseParams b = bwdd_B(c, wb);
   if (p.ns == 1) {
     EpiGate ep{dx, c.Cin, gate, c.cg(), 0};
-    if (c.stride == 1) return by_tile<ConvGather<IM2COL_T1>>(bn, av, bv, a, b, ep, d, p.kchunk, 1, st);
-    return by_tile<ConvGather<IM2COL_TS>>(bn, av, bv, a, b, ep, d, p.kchunk, 1, st);
+    if (c.stride == 1) return by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st);
+    return by_tile<ConvGather<IM2COL_TS>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
   if (c.stride == 1)
-    AX_TRY((by_tile<ConvGather<IM2COL_T1>>(bn, av, bv, a, b, ep, d, p.kchunk, p.ns, st)));
+    AX_TRY((by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st)));
   else
-    AX_TRY((by_tile<ConvGather<IM2COL_TS>>(bn, av, bv, a, b, ep, d, p.kchunk, p.ns, st)));
+    AX_TRY((by_tile<ConvGather<IM2COL_TS>>(p, av, bv, a, b, ep, d, st)));
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, nullptr, 0, gate, dx, st);
 }
 
-static SplitPlan bwdw_plan(const ConvGeom& c, int* bn) {
-  const GemmDims d = bwdw_dims(c);
-  *bn = pick_bn(d.N);
-  const long tiles = (long)ceil_div(d.M, 128) * ceil_div(d.N, *bn) * d.groups;
-  return choose_split(tiles, d.K, *bn, (double)c.w_elems() * 4, 256);
-}
-size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
-  int bn;
-  const SplitPlan p = bwdw_plan(c, &bn);
-  return p.ns > 1 ? (size_t)p.ns * c.w_elems() : 0;
-}
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* ws,
                            hipStream_t st) {
   const GemmDims d = bwdw_dims(c);
-  int bn;
-  const SplitPlan p = bwdw_plan(c, &bn);
+  const GemmPlan p = bwdw_plan(c);
   const long slab = (long)d.M * d.N;
   EpiSlab ep{p.ns > 1 ? ws : dwf, slab, d.N, nullptr};
-  AX_TRY((by_tile<ConvWeightGrad>(bn, bwdw_A_vec(c, x), bwdw_B_vec(c, dy), bwdw_A(c, x), bwdw_B(c, dy), ep, d,
-                                  p.kchunk, p.ns, st)));
+  AX_TRY((by_tile<ConvWeightGrad>(p, bwdw_A_vec(c, x), bwdw_B_vec(c, dy), bwdw_A(c, x), bwdw_B(c, dy), ep, d, st)));
   if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, dwf, st));
   return ALEXNET_OK;
 }
@@ -230,12 +215,28 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
 // y = act(x w^T + b),  dx = gate(dy w),  dw = dy^T x.  The batch is the small
 // dimension, so forward and backward-data split the reduction over several
 // workgroups and finish in a second kernel that also applies the activation.
+// The dense layers always use the 128 x 128 tile.
 
 static int fc_split(int B, int N, int K, int* kchunk) {
+  const int ktiles = ceil_div(K, kBK);
   const long tiles = (long)ceil_div(B, 128) * ceil_div(N, 128);
-  const SplitPlan p = choose_split(tiles, K, 128, (double)B * N * 4, 64);
-  *kchunk = p.kchunk;
-  return p.ns;
+  const double t_tile = 2.0 * 128 * 128 * (double)ktiles * kBK / (0.614e12 * 0.8);
+  int best = 1, best_per = ktiles;
+  double best_t = 1e30;
+  for (int s = 1; s <= 64 && s <= ktiles; ++s) {
+    const int per = ceil_div(ktiles, s);
+    if (ceil_div(ktiles, per) != s) continue;
+    if (s > 1 && per < 6) break;
+    double t = (double)ceil_div(tiles * s, 256) * t_tile * per / ktiles;
+    if (s > 1) t += (s + 1) * (double)B * N * 4 / 2.5e12;
+    if (t < best_t * 0.98) {
+      best_t = t;
+      best = s;
+      best_per = per;
+    }
+  }
+  *kchunk = best_per * kBK;
+  return best;
 }
 size_t fc_ws_floats(int B, int in, int out) {
   int kc;
