@@ -77,6 +77,7 @@ struct Stage {
   int Hp, Wp;           // stage output size (after the pool when present)
   size_t w_off, b_off;  // offsets into the flat parameter vector
   float *act, *lrn_out, *pool_out, *dact, *d_lrn, *d_out, *wb;
+  float *wrun, *dwrun;  // run-mode copies of the weights and their gradient (null when not used)
   uint8_t* slot;
   char lab[4][16];  // profiling labels: stage, .fwd, .bwd_w, .bwd_x
   long act_elems() const { return g.out_elems(); }
@@ -224,6 +225,8 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.d_lrn = (s.lrn && s.pool) ? a.take<float>(ae) : nullptr;
     s.d_out = s.plain() ? s.dact : a.take<float>(oe);
     s.wb = a.take<float>(s.g.w_elems());
+    s.wrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
+    s.dwrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     max_in = std::max(max_in, (size_t)s.g.in_elems());
     max_out = std::max(max_out, ae);
     max_w = std::max(max_w, (size_t)s.g.w_elems());
@@ -274,7 +277,8 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
     Stage& s = n->st[i];
     {
       ProfContext pc(s.lab[1]);
-      AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, n->gemm_ws, st));
+      if (s.wrun) AX_TRY(launch_conv_run_pack(s.g, n->params + s.w_off, s.wrun, st));
+      AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, s.wrun, n->params + s.b_off, 1, s.act, n->gemm_ws, st));
     }
     ProfContext pc(s.lab[0]);
     h = s.act;
@@ -343,7 +347,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
-      AX_TRY(launch_conv_bwd_weight(s.g, x, s.dact, n->grads + s.w_off, n->gemm_ws, st));
+      AX_TRY(launch_conv_bwd_weight(s.g, x, s.dact, n->grads + s.w_off, s.dwrun, n->gemm_ws, st));
       AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
     }
     if (i > 0) {
@@ -689,7 +693,8 @@ int alexnet_conv_forward_nhwc(alexnet_t* n, int32_t layer, const float* x, const
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(x && wf && y, ALEXNET_EINVAL, "alexnet_conv_forward_nhwc: null argument");
-  return launch_conv_fwd(s->g, x, wf, b, relu, y, n->gemm_ws, S(stream));
+  if (s->wrun) AX_TRY(launch_conv_run_pack(s->g, wf, s->wrun, S(stream)));
+  return launch_conv_fwd(s->g, x, wf, s->wrun, b, relu, y, n->gemm_ws, S(stream));
 }
 int alexnet_conv_backward_data_nhwc(alexnet_t* n, int32_t layer, const float* dy, const float* wb, float* dx,
                                     void* stream) {
@@ -703,7 +708,7 @@ int alexnet_conv_backward_weight_nhwc(alexnet_t* n, int32_t layer, const float* 
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(x && dy && dwf, ALEXNET_EINVAL, "alexnet_conv_backward_weight_nhwc: null argument");
-  AX_TRY(launch_conv_bwd_weight(s->g, x, dy, dwf, n->gemm_ws, S(stream)));
+  AX_TRY(launch_conv_bwd_weight(s->g, x, dy, dwf, s->dwrun, n->gemm_ws, S(stream)));
   if (db) AX_TRY(launch_colsum(dy, s->g.P(), s->g.Cout, db, n->colsum_ws, S(stream)));
   return ALEXNET_OK;
 }
@@ -715,7 +720,8 @@ int alexnet_conv_forward(alexnet_t* n, int32_t layer, const float* x, const floa
   const ConvGeom& g = s->g;
   AX_TRY(launch_nchw_to_nhwc(x, n->scratch_x, g.B, g.Cin, g.H, g.W, S(stream)));
   AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
-  AX_TRY(launch_conv_fwd(g, n->scratch_x, n->scratch_w[0], b, relu, n->scratch_y, n->gemm_ws, S(stream)));
+  if (s->wrun) AX_TRY(launch_conv_run_pack(g, n->scratch_w[0], s->wrun, S(stream)));
+  AX_TRY(launch_conv_fwd(g, n->scratch_x, n->scratch_w[0], s->wrun, b, relu, n->scratch_y, n->gemm_ws, S(stream)));
   return launch_nhwc_to_nchw(n->scratch_y, y, g.B, g.Cout, g.Ho, g.Wo, S(stream));
 }
 int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, const float* w, float* dx,
@@ -738,7 +744,7 @@ int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, co
   const ConvGeom& g = s->g;
   AX_TRY(launch_nchw_to_nhwc(x, n->scratch_x, g.B, g.Cin, g.H, g.W, S(stream)));
   AX_TRY(launch_nchw_to_nhwc(dy, n->scratch_y, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
-  AX_TRY(launch_conv_bwd_weight(g, n->scratch_x, n->scratch_y, n->scratch_w[2], n->gemm_ws, S(stream)));
+  AX_TRY(launch_conv_bwd_weight(g, n->scratch_x, n->scratch_y, n->scratch_w[2], s->dwrun, n->gemm_ws, S(stream)));
   AX_TRY(launch_conv_weight_pack(n->scratch_w[2], dw, g.Cout, g.cg(), g.k, g.groups, 1, S(stream)));
   if (db) AX_TRY(launch_colsum(n->scratch_y, g.P(), g.Cout, db, n->colsum_ws, S(stream)));
   return ALEXNET_OK;

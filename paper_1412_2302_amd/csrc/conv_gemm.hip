@@ -1,5 +1,7 @@
 // Convolution forward, backward-data and backward-weight as implicit GEMMs on
 // the fp32 MFMA core (gemm.h), and the dense layers on the same core.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace ax {
@@ -141,21 +143,21 @@ static int launch_slab_finish(const float* ws, int ns, int groups, long M, int N
 }
 
 // ------------------------------------------------------------- convolution ---
-static GemmPlan fwd_plan(const ConvGeom& c) {
+static GemmPlan fwd_plan(const ConvGeom& c, bool run = false) {
   const GemmDims d = fwd_dims(c);
-  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.out_elems() * 4, 8);
+  return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8);
 }
 static GemmPlan bwdd_plan(const ConvGeom& c) {
   const GemmDims d = bwdd_dims(c);
   return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8);
 }
-static GemmPlan bwdw_plan(const ConvGeom& c) {
+static GemmPlan bwdw_plan(const ConvGeom& c, bool run = false) {
   const GemmDims d = bwdw_dims(c);
-  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.w_elems() * 4, 256);
+  return plan_gemm(run ? run_k(c) : d.M, d.N, d.K, d.groups, (double)(run ? run_w_elems(c) : c.w_elems()) * 4, 256);
 }
 size_t conv_fwd_ws_floats(const ConvGeom& c) {
-  const GemmPlan p = fwd_plan(c);
-  return p.ns > 1 ? (size_t)p.ns * c.out_elems() : 0;
+  const GemmPlan p = fwd_plan(c), q = fwd_plan(c, run_mode(c));
+  return (size_t)std::max(p.ns > 1 ? p.ns : 0, q.ns > 1 ? q.ns : 0) * c.out_elems();
 }
 size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
   const GemmPlan p = bwdd_plan(c);
@@ -163,20 +165,61 @@ size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
 }
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
   const GemmPlan p = bwdw_plan(c);
-  return p.ns > 1 ? (size_t)p.ns * c.w_elems() : 0;
+  size_t n = p.ns > 1 ? (size_t)p.ns * c.w_elems() : 0;
+  if (run_mode(c)) n = std::max(n, (size_t)bwdw_plan(c, true).ns * run_w_elems(c));
+  return n;
 }
 
-int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
-                    float* ws, hipStream_t st) {
-  const GemmDims d = fwd_dims(c);
-  const GemmPlan p = fwd_plan(c);
-  const bool av = fwd_A_vec(c, x), bv = fwd_B_vec(c, wf);
+// ---- run mode helpers: padded copies of the forward weights / of their gradient ----
+bool conv_run_mode(const ConvGeom& c) { return run_mode(c); }
+size_t conv_run_w_floats(const ConvGeom& c) { return run_mode(c) ? (size_t)run_w_elems(c) : 0; }
+// dir 0: wrun[(r,j)][o] = j < k*Cin ? wf[(r, j)][o] : 0;  dir 1: wf[(r,j)][o] = wrun[(r,j)][o] for j < k*Cin
+__global__ void run_repack_kernel(const float* __restrict__ src, float* __restrict__ dst, int k, int kc, int run,
+                                  int cout, int dir) {
+  const size_t total = (size_t)k * run * cout;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into the padded layout
+  if (i >= total) return;
+  const int o = (int)(i % cout);
+  const size_t q = i / cout;
+  const int j = (int)(q % run), r = (int)(q / run);
+  const size_t packed = ((size_t)r * kc + j) * cout + o;
+  if (dir == 0)
+    dst[i] = j < kc ? src[packed] : 0.f;
+  else if (j < kc)
+    dst[packed] = src[i];
+}
+int launch_conv_run_pack(const ConvGeom& c, const float* wf, float* wrun, hipStream_t st) {
+  const size_t total = (size_t)run_w_elems(c);
+  KernelScope ks("run_repack", 0, (double)total * 8.0, st);
+  hipLaunchKernelGGL(run_repack_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, wf, wrun, c.k, c.k * c.Cin,
+                     run_len(c), c.Cout, 0);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+static int launch_conv_run_unpack(const ConvGeom& c, const float* dwrun, float* dwf, hipStream_t st) {
+  const size_t total = (size_t)run_w_elems(c);
+  KernelScope ks("run_repack", 0, (double)total * 8.0, st);
+  hipLaunchKernelGGL(run_repack_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, dwrun, dwf, c.k, c.k * c.Cin,
+                     run_len(c), c.Cout, 1);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
+                    int relu, float* y, float* ws, hipStream_t st) {
+  const bool run = wrun && run_mode(c) && c.Cout % 4 == 0;
+  GemmDims d = fwd_dims(c);
+  if (run) d.K = run_k(c);
+  const GemmPlan p = fwd_plan(c, run);
+  const bool av = run || fwd_A_vec(c, x), bv = run || fwd_B_vec(c, wf);
+  const Im2colParams a = run ? run_A(c, x) : fwd_A(c, x);
+  const DenseParams b = run ? run_B(c, wrun) : fwd_B(c, wf);
   if (p.ns == 1) {
     EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
-    return by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, st);
+    return by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
-  AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, fwd_A(c, x), fwd_B(c, wf), ep, d, st)));
+  AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st)));
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st);
 }
 
@@ -200,14 +243,19 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, co
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, nullptr, 0, gate, dx, st);
 }
 
-int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* ws,
+int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
                            hipStream_t st) {
-  const GemmDims d = bwdw_dims(c);
-  const GemmPlan p = bwdw_plan(c);
+  const bool run = dwrun && run_mode(c) && bwdw_B_vec(c, dy);
+  GemmDims d = bwdw_dims(c);
+  if (run) d.M = run_k(c);
+  const GemmPlan p = bwdw_plan(c, run);
   const long slab = (long)d.M * d.N;
-  EpiSlab ep{p.ns > 1 ? ws : dwf, slab, d.N, nullptr};
-  AX_TRY((by_tile<ConvWeightGrad>(p, bwdw_A_vec(c, x), bwdw_B_vec(c, dy), bwdw_A(c, x), bwdw_B(c, dy), ep, d, st)));
-  if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, dwf, st));
+  float* out = run ? dwrun : dwf;
+  EpiSlab ep{p.ns > 1 ? ws : out, slab, d.N, nullptr};
+  const Im2colParams a = run ? run_A(c, x) : bwdw_A(c, x);
+  AX_TRY((by_tile<ConvWeightGrad>(p, run || bwdw_A_vec(c, x), bwdw_B_vec(c, dy), a, bwdw_B(c, dy), ep, d, st)));
+  if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, out, st));
+  if (run) AX_TRY(launch_conv_run_unpack(c, dwrun, dwf, st));
   return ALEXNET_OK;
 }
 

@@ -49,7 +49,7 @@ inline Im2colParams fwd_A(const ConvGeom& c, const float* x) {
   Im2colParams a;
   a.x = x; a.bytes = (uint32_t)(c.in_elems() * 4);
   a.H = c.H; a.W = c.W; a.Ctot = c.Cin; a.Cg = c.cg(); a.c_stride_g = c.cg();
-  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad;
+  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad; a.stride_x = c.stride; a.pad_x = c.pad;
   a.OH = c.Ho; a.OW = c.Wo; a.P = (int)c.P();
   fill_divs(a);
   return a;
@@ -62,13 +62,33 @@ inline DenseParams fwd_B(const ConvGeom& c, const float* wf) {
 }
 inline bool fwd_B_vec(const ConvGeom& c, const float* wf) { return c.og() % 4 == 0 && aligned16(wf); }
 
+// ---- run mode (see gemm.h): forward and backward-weight of an unpadded conv with Cin % 4 != 0 ----
+inline bool run_mode(const ConvGeom& c) { return c.pad == 0 && c.groups == 1 && c.Cin % 4 != 0; }
+inline int run_len(const ConvGeom& c) { return (c.k * c.Cin + 3) / 4 * 4; }  // padded run of one kernel row
+inline int run_k(const ConvGeom& c) { return c.k * run_len(c); }             // reduction length in run mode
+inline long run_w_elems(const ConvGeom& c) { return (long)run_k(c) * c.Cout; }
+inline Im2colParams run_A(const ConvGeom& c, const float* x) {
+  Im2colParams a;
+  a.x = x; a.bytes = (uint32_t)(c.in_elems() * 4);
+  a.H = c.H; a.W = c.W * c.Cin; a.Ctot = 1; a.Cg = run_len(c); a.c_stride_g = 0;
+  a.kh = c.k; a.kw = 1; a.stride = c.stride; a.pad = 0; a.stride_x = c.stride * c.Cin; a.pad_x = 0;
+  a.OH = c.Ho; a.OW = c.Wo; a.P = (int)c.P();
+  fill_divs(a);
+  return a;
+}
+inline DenseParams run_B(const ConvGeom& c, const float* wrun) {  // wrun[(r, j)][o], zero for j >= k*Cin
+  DenseParams b;
+  b.p = wrun; b.ld = c.Cout; b.gstride = 0; b.R = c.Cout; b.bytes = (uint32_t)(run_w_elems(c) * 4);
+  return b;
+}
+
 // ---- backward data ----
 inline GemmDims bwdd_dims(const ConvGeom& c) { return {(int)c.Q(), c.cg(), c.kb(), c.groups}; }
 inline Im2colParams bwdd_A(const ConvGeom& c, const float* dy) {
   Im2colParams a;
   a.x = dy; a.bytes = (uint32_t)(c.out_elems() * 4);
   a.H = c.Ho; a.W = c.Wo; a.Ctot = c.Cout; a.Cg = c.og(); a.c_stride_g = c.og();
-  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad;
+  a.kh = a.kw = c.k; a.stride = c.stride; a.pad = c.pad; a.stride_x = c.stride; a.pad_x = c.pad;
   a.OH = c.H; a.OW = c.W; a.P = (int)c.Q();
   fill_divs(a);
   return a;

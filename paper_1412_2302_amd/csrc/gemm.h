@@ -69,15 +69,19 @@ struct BufView {
   uint32_t bytes;
 };
 inline BufView make_view(const float* p, uint32_t bytes) { return BufView{p, bytes}; }
-// The emulation treats a load that is only partly inside as an error: the
-// kernel never relies on per-dword clipping.
+// Range checking is per dword, as measured on gfx950: the dwords of a 16-byte
+// load that lie past num_records come back as zero, the others are loaded.
 inline void emu_fail(const char* what);
 inline float4 buf_ld4(const BufView& v, uint32_t off) {
+  if (off & 3) emu_fail("unaligned buffer load");
+  float r[4];
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t o = off + 4u * j;
+    r[j] = (o >= off && o + 4 <= v.bytes) ? *reinterpret_cast<const float*>(reinterpret_cast<const char*>(v.p) + o) : 0.f;
+  }
   float4 z;
-  z.x = z.y = z.z = z.w = 0.f;
-  if (off >= v.bytes) return z;
-  if (off + 16 > v.bytes || (off & 3)) emu_fail("16-byte load straddles the end of its operand");
-  return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(v.p) + off);
+  z.x = r[0]; z.y = r[1]; z.z = r[2]; z.w = r[3];
+  return z;
 }
 inline float buf_ld1(const BufView& v, uint32_t off) {
   if (off >= v.bytes) return 0.f;
@@ -259,6 +263,14 @@ struct DenseRowInner {
 //   mode 1 (transposed, unit):   iy = y + pad - r                    (stride 1)
 //   mode 2 (transposed, strided) iy = (y + pad - r)/stride, only where exact
 // (modes 1 and 2 are the gather form of the adjoint of a convolution).
+//
+// Run mode (forward geometry only): an unpadded convolution whose channel count
+// is not a multiple of four (3-channel pictures) is viewed as a tensor
+// x'[N][H][W*C] with one channel: all taps (s, c) of one kernel row r are then
+// one contiguous run of kw*C floats starting at column x*stride*C, which is
+// read in 16-byte pieces (4-byte aligned) and padded to a multiple of four with
+// weights that are zero.  In the struct this is kw = 1, Cg = run length,
+// Ctot = 1, W = W*C, stride_x = stride*C.
 struct Im2colParams {
   const float* x;
   uint32_t bytes;   // extent of the tensor
@@ -266,6 +278,7 @@ struct Im2colParams {
   int Cg;           // channels per group (extent of c)
   int c_stride_g;   // channel offset added per group
   int kh, kw, stride, pad;
+  int stride_x, pad_x;  // forward mode only: step and padding along x (differ from stride/pad in run mode)
   int OH, OW;       // pixel grid
   int P;            // number of pixels = N*OH*OW
   FastDiv d_cg, d_kw, d_ohw, d_ow, d_stride;
@@ -347,7 +360,7 @@ struct Im2colKInner {
       const PixCoord c = decode_pixel(in ? p : 0, g);
       if (MODE == IM2COL_FWD) {
         y0[i] = in ? c.y * g.stride - g.pad : -kFar;
-        x0[i] = c.x * g.stride - g.pad;
+        x0[i] = c.x * g.stride_x - g.pad_x;
       } else {
         y0[i] = in ? c.y + g.pad : -kFar;
         x0[i] = c.x + g.pad;
@@ -408,7 +421,7 @@ struct Im2colRowInner {
     const int p = k0 + (tid + S * kThreads) / QR;
     const bool pok = p < kend;
     const PixCoord c = decode_pixel(pok ? p : 0, g);
-    const int y0 = pok ? c.y * g.stride - g.pad : -kFar, x0 = c.x * g.stride - g.pad;
+    const int y0 = pok ? c.y * g.stride - g.pad : -kFar, x0 = c.x * g.stride_x - g.pad_x;
     const uint32_t rb = row_base<IM2COL_FWD>(g, c.n, pok ? y0 : 0, x0, c_off);
 #pragma unroll
     for (int j = 0; j < (VEC ? 1 : 4); ++j)

@@ -12,11 +12,17 @@ namespace ax {
 size_t conv_fwd_ws_floats(const ConvGeom& c);
 size_t conv_bwd_data_ws_floats(const ConvGeom& c);
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c);
-int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* bias, int relu, float* y,
-                    float* ws, hipStream_t st);
+// Run mode (unpadded conv over 3-channel pictures, see gemm.h): `wrun` / `dwrun` are padded copies of the
+// forward weights and of their gradient, conv_run_w_floats() floats each; null selects the generic gather.
+bool conv_run_mode(const ConvGeom& c);
+size_t conv_run_w_floats(const ConvGeom& c);
+int launch_conv_run_pack(const ConvGeom& c, const float* wf, float* wrun, hipStream_t st);
+int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
+                    int relu, float* y, float* ws, hipStream_t st);
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
                          float* ws, hipStream_t st);
-int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* ws, hipStream_t st);
+int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
+                           hipStream_t st);
 
 // ---- dense layers (fc_gemm.hip) ---------------------------------------------
 struct FcAct {

@@ -190,6 +190,37 @@ static void run_case(const Case& cs) {
           fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, kc, 1, d.groups);
     check("fwd", nm, y, y_ref);
   }
+  // ---- run mode: forward and backward weight through the padded-row view ----
+  if (run_mode(c) && c.Cout % 4 == 0) {
+    const int run = run_len(c), kc = c.k * c.Cin;
+    float* wrun = new float[run_w_elems(c)];
+    for (int r = 0; r < c.k; ++r)
+      for (int j = 0; j < run; ++j)
+        for (int o = 0; o < c.Cout; ++o) wrun[((long)r * run + j) * c.Cout + o] = j < kc ? wf[((long)r * kc + j) * c.Cout + o] : 0.f;
+    {
+      std::vector<float> y(c.out_elems(), NAN);
+      GemmDims d = fwd_dims(c);
+      d.K = run_k(c);
+      EpiBiasAct e{y.data(), c.Cout, bias, 1, og, 0};
+      emu_gemm<T, Im2colKInner<T::BM, T::BK, true, IM2COL_FWD>, DenseRowInner<T::BN, T::BK, true>, EpiBiasAct>(
+          run_A(c, x), run_B(c, wrun), e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, 1);
+      check("fwd_run", nm, y, y_ref);
+    }
+    {
+      GemmDims d = bwdw_dims(c);
+      d.M = run_k(c);
+      std::vector<float> dwr((size_t)d.M * d.N, NAN);
+      EpiSlab e{dwr.data(), (long)d.M * d.N, d.N, nullptr};
+      emu_gemm<T, Im2colRowInner<T::BM, T::BK, true>, DenseRowInner<T::BN, T::BK, true>, EpiSlab>(
+          run_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, 1);
+      std::vector<float> dwf(c.w_elems(), 0.f);
+      for (int r = 0; r < c.k; ++r)
+        for (int j = 0; j < kc; ++j)
+          for (int o = 0; o < c.Cout; ++o) dwf[((long)r * kc + j) * c.Cout + o] = dwr[((long)r * run + j) * c.Cout + o];
+      check("bwdw_run", nm, dwf, dwf_ref);
+    }
+    delete[] wrun;
+  }
   // ---- backward data ----
   {
     std::vector<float> dx(c.in_elems(), NAN);
