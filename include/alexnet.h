@@ -184,8 +184,9 @@ int alexnet_pack_conv_weight(alexnet_t* net, int32_t layer, const float* d_w_oih
 int alexnet_unpack_conv_weight(alexnet_t* net, int32_t layer, const float* d_w_fwd, float* d_w_oihw, void* stream);
 int alexnet_conv_forward_nhwc(alexnet_t* net, int32_t layer, const float* d_x, const float* d_w_fwd,
                               const float* d_b, int32_t relu, float* d_y, void* stream);
-int alexnet_conv_backward_data_nhwc(alexnet_t* net, int32_t layer, const float* d_dy, const float* d_w_bwd,
-                                    float* d_dx, void* stream);
+/* d_w_fwd may be null; when given, a strided ungrouped stage is computed phase by phase from it. */
+int alexnet_conv_backward_data_nhwc(alexnet_t* net, int32_t layer, const float* d_dy, const float* d_w_fwd,
+                                    const float* d_w_bwd, float* d_dx, void* stream);
 /* d_dw_fwd receives the gradient in the packed forward-weight layout. */
 int alexnet_conv_backward_weight_nhwc(alexnet_t* net, int32_t layer, const float* d_x, const float* d_dy,
                                       float* d_dw_fwd, float* d_db, void* stream);

@@ -69,7 +69,7 @@ _SIGS = {
     "alexnet_pack_conv_weight": [_vp, _i32, _vp, _vp, _vp, _vp],
     "alexnet_unpack_conv_weight": [_vp, _i32, _vp, _vp, _vp],
     "alexnet_conv_forward_nhwc": [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp],
-    "alexnet_conv_backward_data_nhwc": [_vp, _i32, _vp, _vp, _vp, _vp],
+    "alexnet_conv_backward_data_nhwc": [_vp, _i32, _vp, _vp, _vp, _vp, _vp],
     "alexnet_conv_backward_weight_nhwc": [_vp, _i32, _vp, _vp, _vp, _vp, _vp],
 }
 
@@ -325,8 +325,8 @@ class AlexNet:
     def conv_forward_nhwc(self, layer, x, wf, b, relu, y, stream=None):
         _check(_lib.alexnet_conv_forward_nhwc(self._h, layer, _ptr(x), _ptr(wf), _ptr(b), int(relu), _ptr(y), _stream(stream)))
 
-    def conv_backward_data_nhwc(self, layer, dy, wb, dx, stream=None):
-        _check(_lib.alexnet_conv_backward_data_nhwc(self._h, layer, _ptr(dy), _ptr(wb), _ptr(dx), _stream(stream)))
+    def conv_backward_data_nhwc(self, layer, dy, wb, dx, wf=None, stream=None):
+        _check(_lib.alexnet_conv_backward_data_nhwc(self._h, layer, _ptr(dy), _ptr(wf), _ptr(wb), _ptr(dx), _stream(stream)))
 
     def conv_backward_weight_nhwc(self, layer, x, dy, dwf, db, stream=None):
         _check(_lib.alexnet_conv_backward_weight_nhwc(self._h, layer, _ptr(x), _ptr(dy), _ptr(dwf), _ptr(db), _stream(stream)))

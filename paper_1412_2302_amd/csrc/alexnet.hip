@@ -77,6 +77,7 @@ struct Stage {
   int Hp, Wp;           // stage output size (after the pool when present)
   size_t w_off, b_off;  // offsets into the flat parameter vector
   float *act, *lrn_out, *pool_out, *dact, *d_lrn, *d_out, *wb;
+  float* wphase;        // weights regrouped by phase for a strided backward-data pass (null when not used)
   float *wrun, *dwrun;  // run-mode copies of the weights and their gradient (null when not used)
   uint8_t* slot;
   char lab[4][16];  // profiling labels: stage, .fwd, .bwd_w, .bwd_x
@@ -225,6 +226,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.d_lrn = (s.lrn && s.pool) ? a.take<float>(ae) : nullptr;
     s.d_out = s.plain() ? s.dact : a.take<float>(oe);
     s.wb = a.take<float>(s.g.w_elems());
+    s.wphase = conv_phase_mode(s.g) ? a.take<float>(conv_phase_w_floats(s.g)) : nullptr;
     s.wrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     s.dwrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     max_in = std::max(max_in, (size_t)s.g.in_elems());
@@ -354,7 +356,8 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
       ProfContext pc(s.lab[3]);
       Stage& prev = n->st[i - 1];
       AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
-      AX_TRY(launch_conv_bwd_data(s.g, s.dact, s.wb, prev.plain() ? prev.act : nullptr, prev.d_out, n->gemm_ws, st));
+      AX_TRY(launch_conv_bwd_data(s.g, s.dact, n->params + s.w_off, s.wb, s.wphase, prev.plain() ? prev.act : nullptr,
+                                  prev.d_out, n->gemm_ws, st));
     }
   }
   return ALEXNET_OK;
@@ -696,12 +699,12 @@ int alexnet_conv_forward_nhwc(alexnet_t* n, int32_t layer, const float* x, const
   if (s->wrun) AX_TRY(launch_conv_run_pack(s->g, wf, s->wrun, S(stream)));
   return launch_conv_fwd(s->g, x, wf, s->wrun, b, relu, y, n->gemm_ws, S(stream));
 }
-int alexnet_conv_backward_data_nhwc(alexnet_t* n, int32_t layer, const float* dy, const float* wb, float* dx,
-                                    void* stream) {
+int alexnet_conv_backward_data_nhwc(alexnet_t* n, int32_t layer, const float* dy, const float* wf, const float* wb,
+                                    float* dx, void* stream) {
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(dy && wb && dx, ALEXNET_EINVAL, "alexnet_conv_backward_data_nhwc: null argument");
-  return launch_conv_bwd_data(s->g, dy, wb, nullptr, dx, n->gemm_ws, S(stream));
+  return launch_conv_bwd_data(s->g, dy, wf, wb, wf ? s->wphase : nullptr, nullptr, dx, n->gemm_ws, S(stream));
 }
 int alexnet_conv_backward_weight_nhwc(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dwf,
                                       float* db, void* stream) {
@@ -733,7 +736,8 @@ int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, con
   AX_TRY(launch_nchw_to_nhwc(dy, n->scratch_y, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
   AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
   AX_TRY(launch_conv_weight_wb(n->scratch_w[0], n->scratch_w[1], g.Cout, g.cg(), g.k, g.groups, S(stream)));
-  AX_TRY(launch_conv_bwd_data(g, n->scratch_y, n->scratch_w[1], nullptr, n->scratch_x, n->gemm_ws, S(stream)));
+  AX_TRY(launch_conv_bwd_data(g, n->scratch_y, n->scratch_w[0], n->scratch_w[1], s->wphase, nullptr, n->scratch_x,
+                              n->gemm_ws, S(stream)));
   return launch_nhwc_to_nchw(n->scratch_x, dx, g.B, g.Cin, g.H, g.W, S(stream));
 }
 int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dw, float* db,

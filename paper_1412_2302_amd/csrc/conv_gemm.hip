@@ -60,6 +60,15 @@ static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int
 }
 
 
+// Algorithmic flops of the launch being prepared (2 x multiply-adds of the
+// operation, not of the padded GEMM); 0 means "use 2*M*N*K".
+static thread_local double g_algo_flops = 0;
+struct AlgoFlops {
+  explicit AlgoFlops(double f) { g_algo_flops = f; }
+  ~AlgoFlops() { g_algo_flops = 0; }
+};
+static inline double conv_flops(const ConvGeom& c) { return 2.0 * c.P() * c.Cout * c.cg() * c.k * c.k; }
+
 template <class T, class AL, class BL, class Epi>
 static int launch_tile(const typename AL::Params& ap, const typename BL::Params& bp, const Epi& ep, int M, int N, int K,
                        int kchunk, int nsplit, int groups, hipStream_t st) {
@@ -69,7 +78,7 @@ static int launch_tile(const typename AL::Params& ap, const typename BL::Params&
     set_error("GEMM grid too large (%u,%u,%u)", grid.x, grid.y, grid.z);
     return ALEXNET_ESHAPE;
   }
-  KernelScope ks("gemm", 2.0 * M * N * (double)K * groups, 0, st);
+  KernelScope ks("gemm", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups, 0, st);
   hipLaunchKernelGGL((gemm_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), 0, st, ap, bp, ep, M, N, K, kchunk, nsplit);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
@@ -208,6 +217,7 @@ static int launch_conv_run_unpack(const ConvGeom& c, const float* dwrun, float* 
 int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
                     int relu, float* y, float* ws, hipStream_t st) {
   const bool run = wrun && run_mode(c) && c.Cout % 4 == 0;
+  AlgoFlops af(conv_flops(c));
   GemmDims d = fwd_dims(c);
   if (run) d.K = run_k(c);
   const GemmPlan p = fwd_plan(c, run);
@@ -223,9 +233,45 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st);
 }
 
-int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
-                         float* ws, hipStream_t st) {
+// ---- strided backward data by phases (conv_plan.h) ----
+bool conv_phase_mode(const ConvGeom& c) { return phase_mode(c) && c.Cout % 4 == 0 && phase_n(c) % 4 == 0; }
+size_t conv_phase_w_floats(const ConvGeom& c) { return conv_phase_mode(c) ? (size_t)phase_w_elems(c) : 0; }
+__global__ void phase_pack_kernel(const float* __restrict__ wf, float* __restrict__ wp, int k, int st, int ka, int cin,
+                                  int cout) {
+  const int pn = st * st * cin;
+  const size_t total = (size_t)ka * ka * cout * pn;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into wp[(a,b,o)][(py,px,c)]
+  if (i >= total) return;
+  const int col = (int)(i % pn);
+  size_t q = i / pn;
+  const int o = (int)(q % cout);
+  q /= cout;
+  const int b = (int)(q % ka), a = (int)(q / ka);
+  const int c = col % cin, pp = col / cin, px = pp % st, py = pp / st;
+  const int r = py + st * a, s = px + st * b;
+  wp[i] = (r < k && s < k) ? wf[((size_t)(r * k + s) * cin + c) * cout + o] : 0.f;
+}
+static int launch_conv_bwd_data_phases(const ConvGeom& c, const float* dy, const float* wf, float* wphase, float* dx,
+                                       hipStream_t st) {
+  const size_t total = (size_t)phase_w_elems(c);
+  {
+    KernelScope ks("phase_pack", 0, (double)total * 8.0, st);
+    hipLaunchKernelGGL(phase_pack_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, wf, wphase, c.k, c.stride,
+                       phase_taps(c), c.Cin, c.Cout);
+    AX_LAUNCH_CHECK();
+  }
+  const GemmDims d = phase_dims(c);
+  AlgoFlops af(conv_flops(c));
+  GemmPlan p = plan_gemm(d.M, d.N, d.K, 1, 0, 1);  // never split: the epilogue scatters
+  return by_tile<ConvGather<IM2COL_T1>>(p, true, true, phase_A(c, dy), phase_B(c, wphase), phase_epilogue(c, dx), d,
+                                        st);
+}
+
+int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, const float* wb, float* wphase,
+                         const float* gate, float* dx, float* ws, hipStream_t st) {
+  if (wphase && !gate && conv_phase_mode(c) && aligned16(dy)) return launch_conv_bwd_data_phases(c, dy, wf, wphase, dx, st);
   const GemmDims d = bwdd_dims(c);
+  AlgoFlops af(conv_flops(c));
   const GemmPlan p = bwdd_plan(c);
   const bool av = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb), bv = bwdd_B_vec(c, wb);
   const Im2colParams a = bwdd_A(c, dy);
@@ -246,6 +292,7 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, co
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
                            hipStream_t st) {
   const bool run = dwrun && run_mode(c) && bwdw_B_vec(c, dy);
+  AlgoFlops af(conv_flops(c));
   GemmDims d = bwdw_dims(c);
   if (run) d.M = run_k(c);
   const GemmPlan p = bwdw_plan(c, run);

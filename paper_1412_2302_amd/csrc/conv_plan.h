@@ -101,6 +101,43 @@ inline DenseParams bwdd_B(const ConvGeom& c, const float* wb) {
 }
 inline bool bwdd_B_vec(const ConvGeom& c, const float* wb) { return c.cg() % 4 == 0 && aligned16(wb); }
 
+// ---- backward data of a strided convolution, by phases ----
+// Input pixel iy = st*qy + py - pad only receives taps r = py + st*a, so all st*st phases (py, px) together
+// are one unit-stride transposed gather over dy with ceil(k/st)^2 taps and st*st*Cin output columns:
+//   dxall[(n,qy,qx)][(py,px,c)] = sum_{(a,b,o)} dy[n][qy-a][qx-b][o] * wp[(a,b,o)][(py,px,c)],
+//   wp[(a,b,o)][(py,px,c)] = w[o][c][py+st*a][px+st*b]  (0 where that tap does not exist).
+inline bool phase_mode(const ConvGeom& c) { return c.stride > 1 && c.groups == 1; }
+inline int phase_taps(const ConvGeom& c) { return (c.k + c.stride - 1) / c.stride; }
+inline int phase_qh(const ConvGeom& c) { return (c.H - 1 + c.pad) / c.stride + 1; }
+inline int phase_qw(const ConvGeom& c) { return (c.W - 1 + c.pad) / c.stride + 1; }
+inline int phase_n(const ConvGeom& c) { return c.stride * c.stride * c.Cin; }
+inline int phase_k(const ConvGeom& c) { return phase_taps(c) * phase_taps(c) * c.Cout; }
+inline long phase_w_elems(const ConvGeom& c) { return (long)phase_k(c) * phase_n(c); }
+inline GemmDims phase_dims(const ConvGeom& c) { return {c.B * phase_qh(c) * phase_qw(c), phase_n(c), phase_k(c), 1}; }
+inline Im2colParams phase_A(const ConvGeom& c, const float* dy) {
+  Im2colParams a;
+  a.x = dy; a.bytes = (uint32_t)(c.out_elems() * 4);
+  a.H = c.Ho; a.W = c.Wo; a.Ctot = c.Cout; a.Cg = c.Cout; a.c_stride_g = 0;
+  a.kh = a.kw = phase_taps(c); a.stride = 1; a.pad = 0; a.stride_x = 1; a.pad_x = 0;
+  a.OH = phase_qh(c); a.OW = phase_qw(c); a.P = c.B * phase_qh(c) * phase_qw(c);
+  fill_divs(a);
+  return a;
+}
+inline DenseParams phase_B(const ConvGeom& c, const float* wp) {
+  DenseParams b;
+  b.p = wp; b.ld = phase_n(c); b.gstride = 0; b.R = phase_n(c); b.bytes = (uint32_t)(phase_w_elems(c) * 4);
+  return b;
+}
+inline EpiPhases phase_epilogue(const ConvGeom& c, float* dx) {
+  EpiPhases e;
+  e.dx = dx; e.H = c.H; e.W = c.W; e.C = c.Cin; e.st = c.stride; e.pad = c.pad; e.QW = phase_qw(c);
+  e.d_qhw = make_fastdiv((uint32_t)(phase_qh(c) * phase_qw(c)));
+  e.d_qw = make_fastdiv((uint32_t)phase_qw(c));
+  e.d_stc = make_fastdiv((uint32_t)(c.stride * c.Cin));
+  e.d_c = make_fastdiv((uint32_t)c.Cin);
+  return e;
+}
+
 // ---- backward weight ----
 inline GemmDims bwdw_dims(const ConvGeom& c) { return {c.kf(), c.og(), (int)c.P(), c.groups}; }
 inline Im2colParams bwdw_A(const ConvGeom& c, const float* x) { return fwd_A(c, x); }

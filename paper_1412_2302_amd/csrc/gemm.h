@@ -483,6 +483,25 @@ struct EpiGate {
   }
 };
 
+// Depth-to-space store of a strided backward-data pass computed per phase:
+// row m = (n, qy, qx) on the coarse grid, column = (py, px, c);
+// dx[n][st*qy + py - pad][st*qx + px - pad][c] = v where that lies inside the picture.
+struct EpiPhases {
+  float* dx;
+  int H, W, C, st, pad, QW;
+  FastDiv d_qhw, d_qw, d_stc, d_c;  // divisors QH*QW, QW, st*C, C
+  AX_HD void set_group(int /*g*/, int /*z*/) {}
+  AX_HD void apply(int m, int n, float v) const {
+    const int img = (int)fdiv((uint32_t)m, d_qhw);
+    const int rem = m - img * (int)d_qhw.d;
+    const int qy = (int)fdiv((uint32_t)rem, d_qw), qx = rem - qy * QW;
+    const int py = (int)fdiv((uint32_t)n, d_stc), r2 = n - py * (int)d_stc.d;
+    const int px = (int)fdiv((uint32_t)r2, d_c), c = r2 - px * C;
+    const int iy = st * qy + py - pad, ix = st * qx + px - pad;
+    if ((uint32_t)iy < (uint32_t)H && (uint32_t)ix < (uint32_t)W) dx[(((long)img * H + iy) * W + ix) * C + c] = v;
+  }
+};
+
 // ws[z][m][n] = v   (z = group*nsplit + split); one M x N slab per launch slice
 struct EpiSlab {
   float* ws;

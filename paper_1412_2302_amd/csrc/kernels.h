@@ -19,8 +19,12 @@ size_t conv_run_w_floats(const ConvGeom& c);
 int launch_conv_run_pack(const ConvGeom& c, const float* wf, float* wrun, hipStream_t st);
 int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
                     int relu, float* y, float* ws, hipStream_t st);
-int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wb, const float* gate, float* dx,
-                         float* ws, hipStream_t st);
+// Strided, ungrouped, ungated backward-data runs by phases when `wphase` (conv_phase_w_floats() floats of
+// scratch) is given; it then reads the forward weights wf instead of wb.
+bool conv_phase_mode(const ConvGeom& c);
+size_t conv_phase_w_floats(const ConvGeom& c);
+int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, const float* wb, float* wphase,
+                         const float* gate, float* dx, float* ws, hipStream_t st);
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
                            hipStream_t st);
 

@@ -242,6 +242,28 @@ static void run_case(const Case& cs) {
           bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, kc, 1, d.groups);
     check("bwd_data", nm, dx, dx_ref);
   }
+  // ---- backward data by phases (strided, ungrouped) ----
+  if (phase_mode(c) && c.Cout % 4 == 0 && phase_n(c) % 4 == 0) {
+    const int ka = phase_taps(c), st = c.stride, pn = phase_n(c);
+    float* wp = new float[phase_w_elems(c)];
+    for (int a = 0; a < ka; ++a)
+      for (int b2 = 0; b2 < ka; ++b2)
+        for (int o = 0; o < c.Cout; ++o)
+          for (int py = 0; py < st; ++py)
+            for (int px = 0; px < st; ++px)
+              for (int ci = 0; ci < c.Cin; ++ci) {
+                const int r = py + st * a, s2 = px + st * b2;
+                wp[(((long)a * ka + b2) * c.Cout + o) * pn + (py * st + px) * c.Cin + ci] =
+                    (r < k && s2 < k) ? w[((o * cg + ci) * k + r) * k + s2] : 0.f;
+              }
+    std::vector<float> dx(c.in_elems(), NAN);
+    const GemmDims d = phase_dims(c);
+    emu_gemm<T, Im2colKInner<T::BM, T::BK, true, IM2COL_T1>, DenseRowInner<T::BN, T::BK, true>, EpiPhases>(
+        phase_A(c, dy), phase_B(c, wp), phase_epilogue(c, dx.data()), d.M, d.N, d.K,
+        ((d.K + T::BK - 1) / T::BK) * T::BK, 1, 1);
+    check("bwdd_phase", nm, dx, dx_ref);
+    delete[] wp;
+  }
   // ---- backward weight with split-k ----
   {
     GemmDims d = bwdw_dims(c);
