@@ -24,6 +24,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -59,6 +60,8 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=128)
+    ap.add_argument("--precision", choices=["fp32", "bf16"], default="fp32",
+                    help="arithmetic of the matrix products (bf16: operands rounded, fp32 accumulation)")
     ap.add_argument("--cpu-sample", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="run preprocessing on the compute stream")
@@ -79,7 +82,9 @@ def main():
         sys.exit(1)
 
     wl, batch = S.ALEXNET, args.batch
-    net = B.AlexNet(wl, batch, seed=S.SEED_BASE + 3)
+    bf16 = args.precision == "bf16"
+    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_MFMA_TFLOPS
+    net = B.AlexNet(wl, batch, seed=S.SEED_BASE + 3, precision=1 if bf16 else 0)
     net.set_params(S.make_params(net.shapes, S.SEED_BASE + 3))
     # a small pool of distinct minibatches resident in HBM, cycled through
     pool = 4
@@ -129,17 +134,18 @@ def main():
     run(prof_steps, args.warmup + args.steps)
     torch.cuda.synchronize()
     entries = B.profile_end()
-    gemm = [e for e in entries if e["name"].endswith(":gemm")]
-    other = [e for e in entries if not e["name"].endswith(":gemm")]
+    gemm = [e for e in entries if ":gemm" in e["name"]]
+    other = [e for e in entries if ":gemm" not in e["name"]]
     gemm_ms = sum(e["total_ms"] for e in gemm)
     gemm_calls = sum(e["calls"] for e in gemm)
     gemm_flops = sum(e["flops"] for e in gemm)
     all_ms = sum(e["total_ms"] for e in entries)
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     roofline = {
-        "kernel": "ax::gemm_kernel (fp32 MFMA implicit-GEMM: conv fwd/bwd-data/bwd-weight and dense layers)",
-        "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
+        "kernel": ("ax::gemm_bf16_kernel (bf16 MFMA" if bf16 else "ax::gemm_kernel (fp32 MFMA")
+                  + " implicit-GEMM: conv fwd/bwd-data/bwd-weight and dense layers)",
+        "bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+        "frac": round(achieved / peak, 4), "traffic": None,
         "launches_per_step": gemm_calls // prof_steps,
         "flops_per_launch": gemm_flops / max(gemm_calls, 1),
         "avg_launch_ms": gemm_ms / max(gemm_calls, 1),
@@ -167,14 +173,14 @@ def main():
         "metric": "AlexNet train images/sec at batch 128 on 1 MI355X; conv MFMA utilisation %",
         "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"full AlexNet training step, fp32, batch {batch}: uint8 3x256x256 pictures in HBM, "
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"full AlexNet training step, {args.precision}, batch {batch}: uint8 3x256x256 pictures in HBM, "
                                "on-device mean-subtract/crop/flip on a side stream, conv1-5 + LRN + pools + fc6-8 "
                                "with dropout, softmax cross-entropy, momentum/weight-decay update",
                    "batch": batch, "overlap_preprocess": not args.no_overlap, "final_loss": round(loss, 5)},
-        "mfma_utilisation_pct": round(100 * achieved / PEAK_FP32_MFMA_TFLOPS, 2),
+        "mfma_utilisation_pct": round(100 * achieved / peak, 2),
         "step_flops": 4.136e9 * batch,
-        "step_mfma_frac": round(4.136e9 * batch / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+        "step_mfma_frac": round(4.136e9 * batch / (ms_per_step * 1e-3) / 1e12 / peak, 4),
         "roofline": roofline,
         "hbm_kernels": hbm,
         "kernels": table[:12],

@@ -46,6 +46,14 @@ extern "C" {
 #define ALEXNET_ENOTIMPL (-6) /* feature not available in this build              */
 #define ALEXNET_ENOMEM (-7)   /* workspace smaller than alexnet_query reports     */
 
+/* alexnet_config_t.precision: arithmetic of the matrix products (convolutions and
+ * dense layers).  Everything else, and every tensor in memory, stays fp32.
+ * BF16 rounds both operands to bfloat16 (nearest even) as they enter the
+ * multiplier and accumulates in fp32; products whose operands cannot be read
+ * 16 bytes at a time (channel counts not a multiple of 4) keep fp32. */
+#define ALEXNET_PRECISION_FP32 0
+#define ALEXNET_PRECISION_BF16 1
+
 typedef struct alexnet alexnet_t; /* opaque; host memory owned by the library */
 
 /* One convolution stage: conv -> ReLU -> [LRN] -> [3x3 stride-2 max-pool]. */
@@ -70,7 +78,7 @@ typedef struct {
   float dropout_p;              /* drop probability after fc6 and fc7          */
   float lr, momentum, weight_decay; /* v <- mu v - lr (g + wd w); w <- w + v;  */
                                 /* wd applies to weights, not to biases        */
-  int32_t precision;            /* 0: fp32 MFMA.  1: bf16 MFMA, fp32 accumulate */
+  int32_t precision;            /* ALEXNET_PRECISION_*                         */
   uint64_t seed;                /* keys the crop / flip / dropout generator    */
 } alexnet_config_t;
 

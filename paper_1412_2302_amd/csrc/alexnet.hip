@@ -130,8 +130,8 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     set_error("bad batch/input size");
     return ALEXNET_ESHAPE;
   }
-  if (c.precision != 0) {
-    set_error("precision %d is not available in this build (fp32 only)", c.precision);
+  if (c.precision != ALEXNET_PRECISION_FP32 && c.precision != ALEXNET_PRECISION_BF16) {
+    set_error("precision %d is not available (0: fp32, 1: bf16 products with fp32 accumulation)", c.precision);
     return ALEXNET_ENOTIMPL;
   }
   if (c.lrn_n < 1 || c.lrn_n % 2 == 0 || !(c.dropout_p >= 0.f && c.dropout_p < 1.f)) {
@@ -274,6 +274,7 @@ static uint32_t drop_thresh(float p) { return (uint32_t)floor((double)p * (doubl
 // --------------------------------------------------------------- passes ------
 static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, hipStream_t st) {
   const alexnet_config_t& c = n->cfg;
+  set_gemm_precision(c.precision);
   const float* h = in;
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
@@ -314,6 +315,7 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
 
 static int run_backward(alexnet* n, const float* in, hipStream_t st) {
   const alexnet_config_t& c = n->cfg;
+  set_gemm_precision(c.precision);
   // dense layers, last to first
   for (int j = kFc - 1; j >= 0; --j) {
     Dense& f = n->fc[j];
@@ -404,6 +406,7 @@ static int stage_of(alexnet* n, int32_t layer, Stage** s) {
     return ALEXNET_EINVAL;
   }
   *s = &n->st[layer - 1];
+  set_gemm_precision(n->cfg.precision);
   return ALEXNET_OK;
 }
 
@@ -815,6 +818,7 @@ static int dense_of(alexnet* n, int32_t layer, Dense** f) {
     return ALEXNET_EINVAL;
   }
   *f = &n->fc[layer - kStages - 1];
+  set_gemm_precision(n->cfg.precision);
   return ALEXNET_OK;
 }
 int alexnet_fc_forward(alexnet_t* n, int32_t layer, const float* d_x, const float* d_w, const float* d_b,

@@ -2,6 +2,7 @@
 // the fp32 MFMA core (gemm.h), and the dense layers on the same core.
 #include <algorithm>
 
+#include "gemm_bf16.h"
 #include "kernels.h"
 
 namespace ax {
@@ -34,15 +35,25 @@ struct TileOption {
   double eff;  // fraction of the per-CU fp32 MFMA rate this tile reaches on a long reduction
 };
 static const TileOption kTileOptions[] = {{128, 128, 0.80}, {128, 96, 0.68}, {128, 64, 0.62}};
+// bf16 MFMA tiles: k-tile of 32; no longer MFMA-bound, priced at ~4x the fp32 rate
+constexpr int kBKbf = 32;
+typedef Tile<128, 128, kBKbf, 2, 2> B128;
+typedef Tile<128, 64, kBKbf, 4, 1> B64;
+static const TileOption kTileOptionsBf[] = {{128, 128, 3.2}, {128, 64, 2.2}};
 
-static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int max_s) {
-  const int ktiles = ceil_div(K, kBK);
-  GemmPlan best{128, 128, 1, ktiles * kBK};
+// precision of the GEMMs launched by the calling thread: 0 fp32 MFMA, 1 bf16 MFMA with fp32 accumulation
+static thread_local int g_bf16 = 0;
+void set_gemm_precision(int bf16) { g_bf16 = bf16 ? 1 : 0; }
+
+static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int max_s, bool bf = false) {
+  const int bk = bf ? kBKbf : kBK;
+  const int ktiles = ceil_div(K, bk);
+  GemmPlan best{128, 128, 1, ktiles * bk};
   double best_t = 1e30;
-  for (int o = 0; o < 3; ++o) {
-    const TileOption& to = kTileOptions[o];
+  for (int o = 0; o < (bf ? 2 : 3); ++o) {
+    const TileOption& to = bf ? kTileOptionsBf[o] : kTileOptions[o];
     const long tiles = (long)ceil_div(M, to.bm) * ceil_div(N, to.bn) * groups;
-    const double t_tile = 2.0 * to.bm * to.bn * (double)ktiles * kBK / (0.614e12 * to.eff);
+    const double t_tile = 2.0 * to.bm * to.bn * (double)ktiles * bk / (0.614e12 * to.eff);
     for (int s = 1; s <= max_s && s <= ktiles; ++s) {
       const int per = ceil_div(ktiles, s);
       if (ceil_div(ktiles, per) != s) continue;
@@ -52,7 +63,7 @@ static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int
       if (s > 1) t += (s + 1) * out_bytes / 2.5e12 + 6e-6;
       if (t < best_t * 0.98) {  // prefer earlier (larger, unsplit) candidates unless clearly better
         best_t = t;
-        best = GemmPlan{to.bm, to.bn, s, per * kBK};
+        best = GemmPlan{to.bm, to.bn, s, per * bk};
       }
     }
   }
@@ -84,6 +95,22 @@ static int launch_tile(const typename AL::Params& ap, const typename BL::Params&
   return ALEXNET_OK;
 }
 
+template <class T, class AL, class BL, class Epi>
+static int launch_tile_bf(const typename AL::Params& ap, const typename BL::Params& bp, const Epi& ep, int M, int N,
+                          int K, int kchunk, int nsplit, int groups, hipStream_t st) {
+  if (M <= 0 || N <= 0) return ALEXNET_OK;
+  dim3 grid(ceil_div(M, T::BM), ceil_div(N, T::BN), groups * nsplit);
+  if (grid.y > 65535 || grid.z > 65535) {
+    set_error("GEMM grid too large (%u,%u,%u)", grid.x, grid.y, grid.z);
+    return ALEXNET_ESHAPE;
+  }
+  KernelScope ks("gemm_bf16", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups, 0, st);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), 0, st, ap, bp, ep, M, N, K, kchunk,
+                     nsplit);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // One struct per GEMM flavour: names the loaders for a tile and a pair of
@@ -105,6 +132,31 @@ struct ConvWeightGrad {  // rows = taps (backward-weight)
         a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
   }
 };
+
+// bf16 flavours (vector loads only)
+template <int MODE>
+struct ConvGatherBf {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, BfRowMajor<Im2colKInner<T::BM, T::BK, true, MODE>, T::BM, T::BK>,
+                          BfDenseRowInner<T::BN, T::BK>, Epi>(a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+struct ConvWeightGradBf {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, BfIm2colRowInner<T::BM, T::BK>, BfDenseRowInner<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+template <class F, class Epi>
+static int by_tile_bf(const GemmPlan& p, const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d,
+                      hipStream_t st) {
+  if (p.bn == 128) return F::template go<B128, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+  return F::template go<B64, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+}
 
 // vector loads on both operands, on B only, or on neither
 template <class F, class T, class Epi>
@@ -152,30 +204,37 @@ static int launch_slab_finish(const float* ws, int ns, int groups, long M, int N
 }
 
 // ------------------------------------------------------------- convolution ---
-static GemmPlan fwd_plan(const ConvGeom& c, bool run = false) {
+static GemmPlan fwd_plan(const ConvGeom& c, bool run, bool bf) {
   const GemmDims d = fwd_dims(c);
-  return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8);
+  return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8, bf);
 }
-static GemmPlan bwdd_plan(const ConvGeom& c) {
+static GemmPlan bwdd_plan(const ConvGeom& c, bool bf) {
   const GemmDims d = bwdd_dims(c);
-  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8);
+  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8, bf);
 }
-static GemmPlan bwdw_plan(const ConvGeom& c, bool run = false) {
+static GemmPlan bwdw_plan(const ConvGeom& c, bool run, bool bf) {
   const GemmDims d = bwdw_dims(c);
-  return plan_gemm(run ? run_k(c) : d.M, d.N, d.K, d.groups, (double)(run ? run_w_elems(c) : c.w_elems()) * 4, 256);
+  return plan_gemm(run ? run_k(c) : d.M, d.N, d.K, d.groups, (double)(run ? run_w_elems(c) : c.w_elems()) * 4, 256,
+                   bf);
 }
+// scratch sizes cover every variant (generic / run mode, fp32 / bf16) of the op
 size_t conv_fwd_ws_floats(const ConvGeom& c) {
-  const GemmPlan p = fwd_plan(c), q = fwd_plan(c, run_mode(c));
-  return (size_t)std::max(p.ns > 1 ? p.ns : 0, q.ns > 1 ? q.ns : 0) * c.out_elems();
+  int ns = 0;
+  for (int run = 0; run < 2; ++run)
+    for (int bf = 0; bf < 2; ++bf) ns = std::max(ns, fwd_plan(c, run && run_mode(c), bf).ns);
+  return ns > 1 ? (size_t)ns * c.out_elems() : 0;
 }
 size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
-  const GemmPlan p = bwdd_plan(c);
-  return p.ns > 1 ? (size_t)p.ns * c.in_elems() : 0;
+  const int ns = std::max(bwdd_plan(c, false).ns, bwdd_plan(c, true).ns);
+  return ns > 1 ? (size_t)ns * c.in_elems() : 0;
 }
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
-  const GemmPlan p = bwdw_plan(c);
-  size_t n = p.ns > 1 ? (size_t)p.ns * c.w_elems() : 0;
-  if (run_mode(c)) n = std::max(n, (size_t)bwdw_plan(c, true).ns * run_w_elems(c));
+  size_t n = 0;
+  for (int bf = 0; bf < 2; ++bf) {
+    const GemmPlan p = bwdw_plan(c, false, bf);
+    if (p.ns > 1) n = std::max(n, (size_t)p.ns * c.w_elems());
+    if (run_mode(c)) n = std::max(n, (size_t)bwdw_plan(c, true, bf).ns * run_w_elems(c));
+  }
   return n;
 }
 
@@ -220,16 +279,21 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
   AlgoFlops af(conv_flops(c));
   GemmDims d = fwd_dims(c);
   if (run) d.K = run_k(c);
-  const GemmPlan p = fwd_plan(c, run);
   const bool av = run || fwd_A_vec(c, x), bv = run || fwd_B_vec(c, wf);
+  const bool bf = g_bf16 && av && bv;
+  const GemmPlan p = fwd_plan(c, run, bf);
   const Im2colParams a = run ? run_A(c, x) : fwd_A(c, x);
   const DenseParams b = run ? run_B(c, wrun) : fwd_B(c, wf);
   if (p.ns == 1) {
     EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
+    if (bf) return by_tile_bf<ConvGatherBf<IM2COL_FWD>>(p, a, b, ep, d, st);
     return by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
-  AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st)));
+  if (bf)
+    AX_TRY((by_tile_bf<ConvGatherBf<IM2COL_FWD>>(p, a, b, ep, d, st)));
+  else
+    AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st)));
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st);
 }
 
@@ -262,7 +326,7 @@ static int launch_conv_bwd_data_phases(const ConvGeom& c, const float* dy, const
   }
   const GemmDims d = phase_dims(c);
   AlgoFlops af(conv_flops(c));
-  GemmPlan p = plan_gemm(d.M, d.N, d.K, 1, 0, 1);  // never split: the epilogue scatters
+  GemmPlan p = plan_gemm(d.M, d.N, d.K, 1, 0, 1, false);  // never split: the epilogue scatters; fp32 only
   return by_tile<ConvGather<IM2COL_T1>>(p, true, true, phase_A(c, dy), phase_B(c, wphase), phase_epilogue(c, dx), d,
                                         st);
 }
@@ -272,17 +336,21 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
   if (wphase && !gate && conv_phase_mode(c) && aligned16(dy)) return launch_conv_bwd_data_phases(c, dy, wf, wphase, dx, st);
   const GemmDims d = bwdd_dims(c);
   AlgoFlops af(conv_flops(c));
-  const GemmPlan p = bwdd_plan(c);
   const bool av = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb), bv = bwdd_B_vec(c, wb);
+  const bool bf = g_bf16 && av && bv && c.stride == 1;
+  const GemmPlan p = bwdd_plan(c, bf);
   const Im2colParams a = bwdd_A(c, dy);
   const DenseParams b = bwdd_B(c, wb);
   if (p.ns == 1) {
     EpiGate ep{dx, c.Cin, gate, c.cg(), 0};
+    if (bf) return by_tile_bf<ConvGatherBf<IM2COL_T1>>(p, a, b, ep, d, st);
     if (c.stride == 1) return by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st);
     return by_tile<ConvGather<IM2COL_TS>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
-  if (c.stride == 1)
+  if (bf)
+    AX_TRY((by_tile_bf<ConvGatherBf<IM2COL_T1>>(p, a, b, ep, d, st)));
+  else if (c.stride == 1)
     AX_TRY((by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st)));
   else
     AX_TRY((by_tile<ConvGather<IM2COL_TS>>(p, av, bv, a, b, ep, d, st)));
@@ -295,12 +363,17 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
   AlgoFlops af(conv_flops(c));
   GemmDims d = bwdw_dims(c);
   if (run) d.M = run_k(c);
-  const GemmPlan p = bwdw_plan(c, run);
+  const bool av = run || bwdw_A_vec(c, x), bv = bwdw_B_vec(c, dy);
+  const bool bf = g_bf16 && av && bv;
+  const GemmPlan p = bwdw_plan(c, run, bf);
   const long slab = (long)d.M * d.N;
   float* out = run ? dwrun : dwf;
   EpiSlab ep{p.ns > 1 ? ws : out, slab, d.N, nullptr};
   const Im2colParams a = run ? run_A(c, x) : bwdw_A(c, x);
-  AX_TRY((by_tile<ConvWeightGrad>(p, run || bwdw_A_vec(c, x), bwdw_B_vec(c, dy), a, bwdw_B(c, dy), ep, d, st)));
+  if (bf)
+    AX_TRY((by_tile_bf<ConvWeightGradBf>(p, a, bwdw_B(c, dy), ep, d, st)));
+  else
+    AX_TRY((by_tile<ConvWeightGrad>(p, av, bv, a, bwdw_B(c, dy), ep, d, st)));
   if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, out, st));
   if (run) AX_TRY(launch_conv_run_unpack(c, dwrun, dwf, st));
   return ALEXNET_OK;
@@ -312,10 +385,11 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
 // workgroups and finish in a second kernel that also applies the activation.
 // The dense layers always use the 128 x 128 tile.
 
-static int fc_split(int B, int N, int K, int* kchunk) {
-  const int ktiles = ceil_div(K, kBK);
+static int fc_split(int B, int N, int K, int* kchunk, bool bf) {
+  const int bk = bf ? kBKbf : kBK;
+  const int ktiles = ceil_div(K, bk);
   const long tiles = (long)ceil_div(B, 128) * ceil_div(N, 128);
-  const double t_tile = 2.0 * 128 * 128 * (double)ktiles * kBK / (0.614e12 * 0.8);
+  const double t_tile = 2.0 * 128 * 128 * (double)ktiles * bk / (0.614e12 * (bf ? 3.2 : 0.8));
   int best = 1, best_per = ktiles;
   double best_t = 1e30;
   for (int s = 1; s <= 64 && s <= ktiles; ++s) {
@@ -330,14 +404,17 @@ static int fc_split(int B, int N, int K, int* kchunk) {
       best_per = per;
     }
   }
-  *kchunk = best_per * kBK;
+  *kchunk = best_per * bk;
   return best;
 }
 size_t fc_ws_floats(int B, int in, int out) {
   int kc;
-  const size_t f = (size_t)fc_split(B, out, in, &kc) * B * out;
-  const size_t b = (size_t)fc_split(B, in, out, &kc) * B * in;
-  return f > b ? f : b;
+  size_t n = 0;
+  for (int bf = 0; bf < 2; ++bf) {
+    n = std::max(n, (size_t)fc_split(B, out, in, &kc, bf) * B * out);
+    n = std::max(n, (size_t)fc_split(B, in, out, &kc, bf) * B * in);
+  }
+  return n;
 }
 
 __global__ void fc_fwd_finish_kernel(const float* __restrict__ ws, int nsplit, int B, int out, FcAct act,
@@ -373,15 +450,22 @@ static int launch_dense(bool vec, const DenseParams& a, const DenseParams& b, co
   return launch_tile<T128, ALT<128, kBK, false>, BLT<128, kBK, false>, EpiSlab>(a, b, ep, M, N, K, kchunk, ns, 1, st);
 }
 
+typedef BfRowMajor<DenseKInner<128, kBKbf, true>, 128, kBKbf> BfDenseK;
+typedef BfDenseRowInner<128, kBKbf> BfDenseR;
+
 int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const FcAct& act, float* y, float* ws,
                   hipStream_t st) {
+  const bool vec = vec_ok(x, in) && vec_ok(w, in), bf = g_bf16 && vec;
   int kchunk;
-  const int ns = fc_split(B, out, in, &kchunk);
+  const int ns = fc_split(B, out, in, &kchunk, bf);
   DenseParams a{x, in, 0, B, (uint32_t)((size_t)B * in * 4)};
   DenseParams b{w, in, 0, out, (uint32_t)((size_t)out * in * 4)};
   EpiSlab ep{ws, (long)B * out, out, nullptr};
   // both operands run along k = in
-  AX_TRY((launch_dense<DenseKInner, DenseKInner>(vec_ok(x, in) && vec_ok(w, in), a, b, ep, B, out, in, kchunk, ns, st)));
+  if (bf)
+    AX_TRY((launch_tile_bf<B128, BfDenseK, BfDenseK, EpiSlab>(a, b, ep, B, out, in, kchunk, ns, 1, st)));
+  else
+    AX_TRY((launch_dense<DenseKInner, DenseKInner>(vec, a, b, ep, B, out, in, kchunk, ns, st)));
   const size_t total = (size_t)B * out;
   KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1), st);
   hipLaunchKernelGGL(fc_fwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, B, out, act, y);
@@ -391,14 +475,17 @@ int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const 
 
 int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, const float* gate, float* dx,
                        float* ws, hipStream_t st) {
+  const bool vec = vec_ok(dy, out) && vec_ok(w, in), bf = g_bf16 && vec;
   int kchunk;
-  const int ns = fc_split(B, in, out, &kchunk);
+  const int ns = fc_split(B, in, out, &kchunk, bf);
   DenseParams a{dy, out, 0, B, (uint32_t)((size_t)B * out * 4)};
   DenseParams b{w, in, 0, in, (uint32_t)((size_t)out * in * 4)};
   EpiSlab ep{ws, (long)B * in, in, nullptr};
   // A runs along k = out, B along its rows = in
-  AX_TRY((launch_dense<DenseKInner, DenseRowInner>(vec_ok(dy, out) && vec_ok(w, in), a, b, ep, B, in, out, kchunk, ns,
-                                                  st)));
+  if (bf)
+    AX_TRY((launch_tile_bf<B128, BfDenseK, BfDenseR, EpiSlab>(a, b, ep, B, in, out, kchunk, ns, 1, st)));
+  else
+    AX_TRY((launch_dense<DenseKInner, DenseRowInner>(vec, a, b, ep, B, in, out, kchunk, ns, st)));
   const size_t total = (size_t)B * in;
   KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1 + (gate ? 1 : 0)), st);
   hipLaunchKernelGGL(fc_bwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, total, gate, dx);
@@ -410,8 +497,10 @@ int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy
   DenseParams a{dy, out, 0, out, (uint32_t)((size_t)B * out * 4)};
   DenseParams b{x, in, 0, in, (uint32_t)((size_t)B * in * 4)};
   EpiSlab ep{dw, (long)out * in, in, nullptr};
-  return launch_dense<DenseRowInner, DenseRowInner>(vec_ok(dy, out) && vec_ok(x, in), a, b, ep, out, in, B,
-                                                    round_up(B, kBK), 1, st);
+  const bool vec = vec_ok(dy, out) && vec_ok(x, in);
+  if (g_bf16 && vec)
+    return launch_tile_bf<B128, BfDenseR, BfDenseR, EpiSlab>(a, b, ep, out, in, B, round_up(B, kBKbf), 1, 1, st);
+  return launch_dense<DenseRowInner, DenseRowInner>(vec, a, b, ep, out, in, B, round_up(B, kBK), 1, st);
 }
 
 }  // namespace ax

@@ -1,0 +1,297 @@
+// bf16 MFMA variant of the GEMM core (gemm.h): operands are fetched as fp32,
+// rounded to bf16 (round to nearest even, v_cvt_pk_bf16_f32) on their way into
+// LDS, multiplied with v_mfma_f32_32x32x16_bf16 and accumulated in fp32.
+// Addressing, zero fill, split-k and epilogues are those of the fp32 core.
+//
+// LDS layouts (32-bit words holding two bf16, even k in the low half):
+//   k-contiguous operands   [row][k/2]   one 8-byte store per load; a lane reads
+//                                        its 8 values of a 16-deep MFMA step as 16 bytes
+//   row-contiguous operands [k/2][row]   a thread fetches k and k+1 of its four rows
+//                                        and stores one 16-byte row of (k,k+1) pairs;
+//                                        a lane reads its 8 values as four words
+// One MFMA step covers k = 16*ks + 8*kh + e (kh = lane/32, e = 0..7) on both operands.
+#pragma once
+
+#include <string.h>
+
+#include "gemm.h"
+
+namespace ax {
+
+// ---- bf16 packing ----------------------------------------------------------------
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  bf2 v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+#else
+inline uint32_t bf16_bits(float f) {  // round to nearest even (finite inputs)
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+inline uint32_t pack_bf16(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+#endif
+
+// LDS word that holds elements (k, k+1), k even, of `row` in a tile written by loader L
+template <class L>
+AX_HD int bf_word(int row, int k) {
+  return L::kRowMajor ? row * L::LDW + (k >> 1) : (k >> 1) * L::LDW + row;
+}
+
+// LDS word that holds values 2w and 2w+1 of the 8 that the lane of (row, kh) feeds to MFMA step ks
+template <class L>
+AX_HD int bf_frag_word(int row, int ks, int kh, int w) {
+  return L::kRowMajor ? row * L::LDW + 8 * ks + 4 * kh + w : (8 * ks + 4 * kh + w) * L::LDW + row;
+}
+
+// ---- k-contiguous operands: reuse the fp32 loader's addressing -------------------
+template <class L, int ROWS, int BK>
+struct BfRowMajor : L {
+  using L::L;
+  static constexpr bool kRowMajor = true;
+  static constexpr int LDW = BK / 2 + 4, LDS_WORDS = ROWS * LDW, NS = L::NL;
+  AX_HD void store_step(int s, uint32_t* lds, const float4* r) const {
+    uint32_t* d = lds + ((this->tid + s * kThreads) / L::QK) * LDW + 2 * this->kq;
+    d[0] = pack_bf16(r[s].x, r[s].y);
+    d[1] = pack_bf16(r[s].z, r[s].w);
+  }
+};
+
+// ---- row-contiguous operands: a unit = rows 4*rq..4*rq+3 at k = 2*kp and 2*kp+1 ----
+template <int ROWS, int BK>
+struct BfDenseRowInner {
+  static constexpr int QR = ROWS / 4, NU = QR * (BK / 2), NUT = NU / kThreads, NL = 2 * NUT, NA = NL, NS = NUT;
+  static_assert(NU % kThreads == 0, "tile must be a whole number of units per thread");
+  static constexpr bool kRowMajor = false;
+  static constexpr int LDW = ROWS + 4, LDS_WORDS = (BK / 2) * LDW;
+  typedef DenseParams Params;
+  BufView v;
+  int tid;
+  uint32_t ld4;
+  uint32_t base[NL];  // byte offset of (k local, row), or kOob
+  Offsets<NL, true> pl;
+  AX_HD BfDenseRowInner(const Params& a, int g, int tid_, int row0)
+      : v(make_view(a.p + (long)g * a.gstride, a.bytes - (uint32_t)(g * a.gstride * 4))), tid(tid_) {
+    ld4 = (uint32_t)a.ld * 4u;
+#pragma unroll
+    for (int u = 0; u < NUT; ++u) {
+      const int idx = tid + u * kThreads;
+      const int row = row0 + 4 * (idx % QR), kp = idx / QR;
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        base[2 * u + h] = row < a.R ? (uint32_t)(2 * kp + h) * ld4 + (uint32_t)row * 4u : kOob;
+    }
+  }
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int k = k0 + 2 * ((tid + (S / 2) * kThreads) / QR) + (S & 1);
+    pl.off[S] = k < kend ? base[S] + (uint32_t)k0 * ld4 : kOob;
+  }
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int u, uint32_t* lds, const float4* r) const {
+    const int idx = tid + u * kThreads;
+    uint32_t* d = lds + (idx / QR) * LDW + 4 * (idx % QR);
+    const float4 a = r[2 * u], b = r[2 * u + 1];
+    d[0] = pack_bf16(a.x, b.x);
+    d[1] = pack_bf16(a.y, b.y);
+    d[2] = pack_bf16(a.z, b.z);
+    d[3] = pack_bf16(a.w, b.w);
+  }
+};
+
+template <int ROWS, int BK>
+struct BfIm2colRowInner {
+  static constexpr int QR = ROWS / 4, NU = QR * (BK / 2), NUT = NU / kThreads, NL = 2 * NUT, NA = NL, NS = NUT;
+  static_assert(NU % kThreads == 0 && kThreads % QR == 0, "every unit of a thread shares its row quad");
+  static constexpr bool kRowMajor = false;
+  static constexpr int LDW = ROWS + 4, LDS_WORDS = (BK / 2) * LDW;
+  typedef Im2colParams Params;
+  Im2colParams g;
+  BufView v;
+  int tid, rq, c_off;
+  TapCoord tap;  // tap of the thread's four rows; r = 2*kFar for rows past the end
+  Offsets<NL, true> pl;
+  AX_HD BfIm2colRowInner(const Params& a, int grp, int tid_, int row0)
+      : g(a), v(make_view(a.x, a.bytes)), tid(tid_), c_off(grp * a.c_stride_g) {
+    rq = tid % QR;
+    const int m = row0 + 4 * rq;
+    const bool in = m < g.kh * g.kw * g.Cg;
+    tap = decode_tap(in ? m : 0, g);
+    if (!in) tap.r = 2 * kFar;
+  }
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int p = k0 + 2 * ((tid + (S / 2) * kThreads) / QR) + (S & 1);
+    const bool pok = p < kend;
+    const PixCoord c = decode_pixel(pok ? p : 0, g);
+    const int y0 = pok ? c.y * g.stride - g.pad : -kFar, x0 = c.x * g.stride_x - g.pad_x;
+    const uint32_t rb = row_base<IM2COL_FWD>(g, c.n, pok ? y0 : 0, x0, c_off);
+    pl.off[S] = tap_address<IM2COL_FWD>(g, rb, y0, x0, tap);
+  }
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int u, uint32_t* lds, const float4* r) const {
+    uint32_t* d = lds + ((tid + u * kThreads) / QR) * LDW + 4 * rq;
+    const float4 a = r[2 * u], b = r[2 * u + 1];
+    d[0] = pack_bf16(a.x, b.x);
+    d[1] = pack_bf16(a.y, b.y);
+    d[2] = pack_bf16(a.z, b.z);
+    d[3] = pack_bf16(a.w, b.w);
+  }
+};
+
+template <class L>
+AX_HD void bf_store_all(const L& l, uint32_t* lds, const float4* r) {
+#pragma unroll
+  for (int s = 0; s < L::NS; ++s) l.store_step(s, lds, r);
+}
+
+// ================================= kernel ====================================
+#ifndef AX_HOST_EMU
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+template <class L, int TT>
+struct BfFrags {
+  v8bf f[TT];
+  // the 8 values of MFMA step KS for each of the wave's TT row blocks
+  template <int KS>
+  __device__ __forceinline__ void read(const uint32_t* lds, int row, int kh) {
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+      typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+      v4u w;
+      if (L::kRowMajor) {
+        w = *reinterpret_cast<const v4u*>(lds + bf_frag_word<L>(row + 32 * t, KS, kh, 0));
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w[q] = lds[bf_frag_word<L>(row + 32 * t, KS, kh, q)];
+      }
+      f[t] = __builtin_bit_cast(v8bf, w);
+    }
+  }
+};
+
+template <class T, class AL, class BL, int IDX>
+__device__ __forceinline__ void bf_side_step(AL& al, BL& bl, uint32_t* as_next, uint32_t* bs_next, const float4* ra,
+                                             const float4* rb, int k_plan, int kend) {
+  constexpr int S0 = AL::NS, S1 = S0 + BL::NS, S2 = S1 + AL::NA, S3 = S2 + BL::NA;
+  if constexpr (IDX < S0) {
+    al.store_step(IDX, as_next, ra);
+  } else if constexpr (IDX < S1) {
+    bl.store_step(IDX - S0, bs_next, rb);
+  } else if constexpr (IDX < S2) {
+    al.template addr_step<IDX - S1>(k_plan, kend);
+  } else if constexpr (IDX < S3) {
+    bl.template addr_step<IDX - S2>(k_plan, kend);
+  }
+}
+template <class T, class AL, class BL, int SLOT, int W = 0>
+__device__ __forceinline__ void bf_side_slot(AL& al, BL& bl, uint32_t* as_next, uint32_t* bs_next, const float4* ra,
+                                             const float4* rb, int k_plan, int kend) {
+  constexpr int TOTAL = AL::NS + BL::NS + AL::NA + BL::NA, SLOTS = T::BK / 16, PER = (TOTAL + SLOTS - 1) / SLOTS;
+  if constexpr (W < PER) {
+    bf_side_step<T, AL, BL, SLOT * PER + W>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    bf_side_slot<T, AL, BL, SLOT, W + 1>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+  }
+}
+
+template <class T, class AL, class BL, int KS = 0>
+__device__ __forceinline__ void bf_tile_stream(const uint32_t* as, const uint32_t* bs, int a_row, int b_row, int kh,
+                                               v16f (&acc)[T::TM][T::TN], AL& al, BL& bl, uint32_t* as_next,
+                                               uint32_t* bs_next, const float4* ra, const float4* rb, int k_plan,
+                                               int kend) {
+  if constexpr (KS < T::BK / 16) {
+    BfFrags<AL, T::TM> fa;
+    BfFrags<BL, T::TN> fb;
+    fa.template read<KS>(as, a_row, kh);
+    fb.template read<KS>(bs, b_row, kh);
+#pragma unroll
+    for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < T::TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.f[i], fb.f[j], acc[i][j], 0, 0, 0);
+    bf_side_slot<T, AL, BL, KS>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    bf_tile_stream<T, AL, BL, KS + 1>(as, bs, a_row, b_row, kh, acc, al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+  }
+}
+
+template <class T, class AL, class BL, class Epi>
+__global__ void __launch_bounds__(kThreads)
+gemm_bf16_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk,
+                 int nsplit) {
+  __shared__ __attribute__((aligned(16))) uint32_t As[2][AL::LDS_WORDS];
+  __shared__ __attribute__((aligned(16))) uint32_t Bs[2][BL::LDS_WORDS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
+  const int z = blockIdx.z, g = z / nsplit, split = z - g * nsplit;
+  const int m0 = blockIdx.x * T::BM, n0 = blockIdx.y * T::BN;
+  const int kbeg = split * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  const int nt = kend > kbeg ? (kend - kbeg + T::BK - 1) / T::BK : 0;
+
+  AL al(ap, g, tid, m0);
+  BL bl(bp, g, tid, n0);
+  ep.set_group(g, z);
+
+  v16f acc[T::TM][T::TN];
+#pragma unroll
+  for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int a_row = wm * (T::TM * 32) + (lane & 31), b_row = wn * (T::TN * 32) + (lane & 31), kh = lane >> 5;
+  if (nt > 0) {
+    // same schedule as the fp32 kernel: tile t from LDS buffer t&1, tile t+1 on its way
+    // from registers to the other buffer, tile t+2 being fetched, tile t+3 being addressed
+    float4 ra[2][AL::NL], rb[2][BL::NL];
+    plan_all(al, kbeg, kend);
+    plan_all(bl, kbeg, kend);
+    al.fetch(ra[0]);
+    bl.fetch(rb[0]);
+    plan_all(al, kbeg + T::BK, kend);
+    plan_all(bl, kbeg + T::BK, kend);
+    al.fetch(ra[1]);
+    bl.fetch(rb[1]);
+    bf_store_all(al, As[0], ra[0]);
+    bf_store_all(bl, Bs[0], rb[0]);
+    plan_all(al, kbeg + 2 * T::BK, kend);
+    plan_all(bl, kbeg + 2 * T::BK, kend);
+    __syncthreads();
+    for (int t = 0; t < nt; t += 2) {
+      al.fetch(ra[0]);
+      bl.fetch(rb[0]);
+      bf_tile_stream<T, AL, BL>(As[0], Bs[0], a_row, b_row, kh, acc, al, bl, As[1], Bs[1], ra[1], rb[1],
+                                kbeg + (t + 3) * T::BK, kend);
+      __syncthreads();
+      if (t + 1 < nt) {
+        al.fetch(ra[1]);
+        bl.fetch(rb[1]);
+        bf_tile_stream<T, AL, BL>(As[1], Bs[1], a_row, b_row, kh, acc, al, bl, As[0], Bs[0], ra[0], rb[0],
+                                  kbeg + (t + 4) * T::BK, kend);
+        __syncthreads();
+      }
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < T::TN; ++j) {
+      const int n = n0 + wn * (T::TN * 32) + j * 32 + (lane & 31);
+      if (n >= N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * (T::TM * 32) + i * 32 + acc_row(lane, r);
+        if (m < M) ep.apply(m, n, acc[i][j][r]);
+      }
+    }
+}
+#endif  // AX_HOST_EMU
+
+}  // namespace ax

@@ -8,6 +8,10 @@
 namespace ax {
 
 // ---- convolution as implicit GEMM (conv_gemm.hip) ---------------------------
+// Arithmetic of the GEMMs the calling thread launches from now on: 0 = fp32 MFMA, 1 = operands rounded to
+// bf16 (nearest even) on their way into LDS, products accumulated in fp32.  Operands that cannot be read
+// 16 bytes at a time keep the fp32 kernels.
+void set_gemm_precision(int bf16);
 // `ws` is split-k scratch of at least the matching *_ws_floats() floats (may be null when that is 0)
 size_t conv_fwd_ws_floats(const ConvGeom& c);
 size_t conv_bwd_data_ws_floats(const ConvGeom& c);

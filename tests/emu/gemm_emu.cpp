@@ -1,4 +1,4 @@
-// CPU emulation of the workgroup program in csrc/gemm.h.
+// CPU emulation of the workgroup programs in csrc/gemm.h and csrc/gemm_bf16.h.
 //
 // Runs the real operand loaders, LDS stores, fragment index maps and epilogues
 // thread by thread on the host, with the MFMA replaced by its definition, and
@@ -24,6 +24,8 @@ inline void emu_fail(const char* what) {
   abort();
 }
 }  // namespace ax
+
+#include "../../paper_1412_2302_amd/csrc/gemm_bf16.h"
 
 using namespace ax;
 
@@ -99,7 +101,85 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
       }
 }
 
-static float frand() { return (float)rand() / RAND_MAX * 2.f - 1.f; }
+static float bf_value(uint32_t word, int half) {
+  const uint32_t u = (half ? word >> 16 : word & 0xffffu) << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+// The bf16 workgroup program: same loaders' addressing, packed LDS words, and the
+// 32x32x16 MFMA by its definition: the lane of (row, kh) supplies 8 values of k-block kh,
+// D[i][j] += sum over kh < 2, e < 8 of A[i][kh][e] * B[j][kh][e].
+template <class T, class AL, class BL, class Epi>
+static void emu_gemm_bf(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk,
+                        int nsplit, int groups) {
+  const int gx = (M + T::BM - 1) / T::BM, gy = (N + T::BN - 1) / T::BN, gz = groups * nsplit;
+  std::vector<uint32_t> As(AL::LDS_WORDS), Bs(BL::LDS_WORDS);
+  std::vector<float> acc((size_t)T::BM * T::BN);
+  for (int bz = 0; bz < gz; ++bz)
+    for (int by = 0; by < gy; ++by)
+      for (int bx = 0; bx < gx; ++bx) {
+        const int g = bz / nsplit, split = bz - g * nsplit;
+        const int m0 = bx * T::BM, n0 = by * T::BN;
+        const int kbeg = split * kchunk, kend = std::min(K, kbeg + kchunk);
+        const int nt = kend > kbeg ? (kend - kbeg + T::BK - 1) / T::BK : 0;
+        std::fill(acc.begin(), acc.end(), 0.f);
+        Epi e = ep;
+        e.set_group(g, bz);
+        for (int t = 0; t < nt; ++t) {
+          std::fill(As.begin(), As.end(), 0x7fc07fc0u);  // two bf16 NaNs: an unwritten slot shows up
+          std::fill(Bs.begin(), Bs.end(), 0x7fc07fc0u);
+          for (int tid = 0; tid < kThreads; ++tid) {
+            AL al(ap, g, tid, m0);
+            BL bl(bp, g, tid, n0);
+            float4 ra[AL::NL], rb[BL::NL];
+            plan_all(al, kbeg + t * T::BK, kend);
+            plan_all(bl, kbeg + t * T::BK, kend);
+            al.fetch(ra);
+            bl.fetch(rb);
+            bf_store_all(al, As.data(), ra);
+            bf_store_all(bl, Bs.data(), rb);
+          }
+          for (int ks = 0; ks < T::BK / 16; ++ks)
+            for (int i = 0; i < T::BM; ++i)
+              for (int j = 0; j < T::BN; ++j) {
+                float s = 0.f;
+                for (int kh = 0; kh < 2; ++kh)
+                  for (int w = 0; w < 4; ++w) {
+                    const int ia = bf_frag_word<AL>(i, ks, kh, w), ib = bf_frag_word<BL>(j, ks, kh, w);
+                    if (ia < 0 || ia >= AL::LDS_WORDS || ib < 0 || ib >= BL::LDS_WORDS) emu_fail("LDS read out of range");
+                    for (int h = 0; h < 2; ++h) s += bf_value(As[ia], h) * bf_value(Bs[ib], h);
+                  }
+                acc[(size_t)i * T::BN + j] += s;
+              }
+        }
+        // every accumulator element belongs to exactly one (wave, block, lane, register)
+        for (int wave = 0; wave < 4; ++wave) {
+          const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
+          for (int lane = 0; lane < 64; ++lane)
+            for (int i = 0; i < T::TM; ++i)
+              for (int j = 0; j < T::TN; ++j) {
+                const int nl = wn * (T::TN * 32) + j * 32 + (lane & 31);
+                if (n0 + nl >= N) continue;
+                for (int r = 0; r < 16; ++r) {
+                  const int ml = wm * (T::TM * 32) + i * 32 + acc_row(lane, r);
+                  if (m0 + ml < M) e.apply(m0 + ml, n0 + nl, acc[(size_t)ml * T::BN + nl]);
+                }
+              }
+        }
+      }
+}
+
+static bool g_round_bf = false;  // draw values that bf16 holds exactly, so both arithmetic kinds share the references
+static float frand() {
+  float f = (float)rand() / RAND_MAX * 2.f - 1.f;
+  if (g_round_bf) {
+    const uint32_t u = bf16_bits(f) << 16;
+    memcpy(&f, &u, 4);
+  }
+  return f;
+}
 
 struct Case {
   ConvGeom c;
@@ -121,8 +201,9 @@ static void check(const char* what, const char* name, const std::vector<float>& 
   if (!ok) ++failures;
 }
 
-template <class T>
+template <class T, bool BF = false>
 static void run_case(const Case& cs) {
+  g_round_bf = BF;
   const ConvGeom& c = cs.c;
   const int cg = c.cg(), og = c.og(), k = c.k;
   // exact-size heap buffers: the sanitizer flags any access past either end
@@ -172,7 +253,78 @@ static void run_case(const Case& cs) {
           y_ref[(((long)n * c.Ho + yy) * c.Wo + xx) * c.Cout + o] = a > 0 ? a : 0;
         }
   char nm[128];
-  snprintf(nm, sizeof nm, "%s/%dx%d", cs.name, T::BM, T::BN);
+  snprintf(nm, sizeof nm, "%s/%dx%d%s", cs.name, T::BM, T::BN, BF ? "/bf16" : "");
+  typedef BfRowMajor<Im2colKInner<T::BM, T::BK, true, IM2COL_FWD>, T::BM, T::BK> BfGatherF;
+  typedef BfRowMajor<Im2colKInner<T::BM, T::BK, true, IM2COL_T1>, T::BM, T::BK> BfGatherT;
+  typedef BfDenseRowInner<T::BN, T::BK> BfRows;
+  if constexpr (BF) {
+    // the bf16 kernels exist for 16-byte loads only; other shapes keep the fp32 kernels
+    const int kcf = ((fwd_dims(c).K + T::BK - 1) / T::BK) * T::BK;
+    if (fwd_A_vec(c, x) && fwd_B_vec(c, wf)) {
+      std::vector<float> y(c.out_elems(), NAN);
+      const GemmDims d = fwd_dims(c);
+      EpiBiasAct e{y.data(), c.Cout, bias, 1, og, 0};
+      emu_gemm_bf<T, BfGatherF, BfRows, EpiBiasAct>(fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, kcf, 1, d.groups);
+      check("fwd", nm, y, y_ref);
+    }
+    if (run_mode(c) && c.Cout % 4 == 0) {
+      const int run = run_len(c), kc = c.k * c.Cin;
+      float* wrun = new float[run_w_elems(c)];
+      for (int r = 0; r < c.k; ++r)
+        for (int j = 0; j < run; ++j)
+          for (int o = 0; o < c.Cout; ++o) wrun[((long)r * run + j) * c.Cout + o] = j < kc ? wf[((long)r * kc + j) * c.Cout + o] : 0.f;
+      {
+        std::vector<float> y(c.out_elems(), NAN);
+        GemmDims d = fwd_dims(c);
+        d.K = run_k(c);
+        EpiBiasAct e{y.data(), c.Cout, bias, 1, og, 0};
+        emu_gemm_bf<T, BfGatherF, BfRows, EpiBiasAct>(run_A(c, x), run_B(c, wrun), e, d.M, d.N, d.K,
+                                                       ((d.K + T::BK - 1) / T::BK) * T::BK, 1, 1);
+        check("fwd_run", nm, y, y_ref);
+      }
+      {
+        GemmDims d = bwdw_dims(c);
+        d.M = run_k(c);
+        std::vector<float> dwr((size_t)d.M * d.N, NAN);
+        EpiSlab e{dwr.data(), (long)d.M * d.N, d.N, nullptr};
+        emu_gemm_bf<T, BfIm2colRowInner<T::BM, T::BK>, BfRows, EpiSlab>(run_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K,
+                                                                         ((d.K + T::BK - 1) / T::BK) * T::BK, 1, 1);
+        std::vector<float> dwf(c.w_elems(), 0.f);
+        for (int r = 0; r < c.k; ++r)
+          for (int j = 0; j < kc; ++j)
+            for (int o = 0; o < c.Cout; ++o) dwf[((long)r * kc + j) * c.Cout + o] = dwr[((long)r * run + j) * c.Cout + o];
+        check("bwdw_run", nm, dwf, dwf_ref);
+      }
+      delete[] wrun;
+    }
+    if (c.stride == 1 && bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb)) {
+      std::vector<float> dx(c.in_elems(), NAN);
+      const GemmDims d = bwdd_dims(c);
+      EpiGate e{dx.data(), c.Cin, nullptr, cg, 0};
+      emu_gemm_bf<T, BfGatherT, BfRows, EpiGate>(bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K,
+                                                 ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
+      check("bwd_data", nm, dx, dx_ref);
+    }
+    if (bwdw_A_vec(c, x) && bwdw_B_vec(c, dy)) {
+      const GemmDims d = bwdw_dims(c);
+      int kchunk;
+      long tiles = (long)((d.M + T::BM - 1) / T::BM) * ((d.N + T::BN - 1) / T::BN) * d.groups;
+      int nsplit = plan_split(tiles, d.K, T::BK, 7, 5, &kchunk);
+      std::vector<float> ws((size_t)d.groups * nsplit * d.M * d.N, NAN);
+      EpiSlab e{ws.data(), (long)d.M * d.N, d.N, nullptr};
+      emu_gemm_bf<T, BfIm2colRowInner<T::BM, T::BK>, BfRows, EpiSlab>(bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K,
+                                                                       kchunk, nsplit, d.groups);
+      std::vector<float> dwf(c.w_elems(), 0.f);
+      for (int g = 0; g < d.groups; ++g)
+        for (int sp = 0; sp < nsplit; ++sp)
+          for (long i = 0; i < (long)d.M * d.N; ++i) dwf[(long)g * d.M * d.N + i] += ws[((long)g * nsplit + sp) * d.M * d.N + i];
+      snprintf(nm, sizeof nm, "%s/%dx%d/s%d/bf16", cs.name, T::BM, T::BN, nsplit);
+      check("bwd_wgt", nm, dwf, dwf_ref);
+    }
+    delete[] x; delete[] dy; delete[] w; delete[] wf; delete[] wb; delete[] bias;
+    g_round_bf = false;
+    return;
+  }
   // ---- forward ----
   {
     std::vector<float> y(c.out_elems(), NAN);
@@ -343,6 +495,52 @@ static void dense_case() {
   delete[] x; delete[] w; delete[] dy;
 }
 
+static void dense_case_bf() {
+  // vector-aligned dense shapes: ragged rows, k that ends inside a k-tile, split-k
+  g_round_bf = true;
+  const int Bn = 6, In = 72, Out = 36;
+  float* x = new float[Bn * In];
+  float* w = new float[Out * In];
+  float* dy = new float[Bn * Out];
+  for (int i = 0; i < Bn * In; ++i) x[i] = frand();
+  for (int i = 0; i < Out * In; ++i) w[i] = frand();
+  for (int i = 0; i < Bn * Out; ++i) dy[i] = frand();
+  typedef Tile<128, 128, 32, 2, 2> T;
+  typedef BfRowMajor<DenseKInner<128, 32, true>, 128, 32> KIn;
+  typedef BfDenseRowInner<128, 32> RIn;
+  {
+    const int ns = 2, kc = 64;
+    std::vector<float> ws(ns * Bn * Out, NAN), y(Bn * Out, 0.f);
+    std::vector<double> ref(Bn * Out, 0.0);
+    for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * Out + o] += (double)x[n * In + i] * w[o * In + i];
+    DenseParams a{x, In, 0, Bn, Bn * In * 4}, b{w, In, 0, Out, Out * In * 4};
+    EpiSlab e{ws.data(), (long)Bn * Out, Out, nullptr};
+    emu_gemm_bf<T, KIn, KIn, EpiSlab>(a, b, e, Bn, Out, In, kc, ns, 1);
+    for (int sp = 0; sp < ns; ++sp) for (int i = 0; i < Bn * Out; ++i) y[i] += ws[sp * Bn * Out + i];
+    check("fc_fwd", "6x72->36 bf16 s2", y, ref);
+  }
+  {
+    std::vector<float> dx(Bn * In, NAN);
+    std::vector<double> ref(Bn * In, 0.0);
+    for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[n * In + i] += (double)dy[n * Out + o] * w[o * In + i];
+    DenseParams a{dy, Out, 0, Bn, Bn * Out * 4}, b{w, In, 0, In, Out * In * 4};
+    EpiSlab e{dx.data(), (long)Bn * In, In, nullptr};
+    emu_gemm_bf<T, KIn, RIn, EpiSlab>(a, b, e, Bn, In, Out, 64, 1, 1);
+    check("fc_bwd_x", "6x72->36 bf16", dx, ref);
+  }
+  {
+    std::vector<float> dw(Out * In, NAN);
+    std::vector<double> ref(Out * In, 0.0);
+    for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out; ++o) for (int i = 0; i < In; ++i) ref[o * In + i] += (double)dy[n * Out + o] * x[n * In + i];
+    DenseParams a{dy, Out, 0, Out, Bn * Out * 4}, b{x, In, 0, In, Bn * In * 4};
+    EpiSlab e{dw.data(), (long)Out * In, In, nullptr};
+    emu_gemm_bf<T, RIn, RIn, EpiSlab>(a, b, e, Out, In, Bn, 32, 1, 1);
+    check("fc_bwd_w", "6x72->36 bf16", dw, ref);
+  }
+  delete[] x; delete[] w; delete[] dy;
+  g_round_bf = false;
+}
+
 static void check_fastdiv() {
   const uint32_t ds[] = {1, 2, 3, 4, 5, 7, 8, 11, 12, 13, 16, 24, 27, 36, 48, 55, 96, 169, 192, 256, 729, 3025, 51529, 1000003};
   long bad = 0;
@@ -376,8 +574,11 @@ int main() {
     run_case<Tile<128, 96, 32, 4, 1>>(cs);
     run_case<Tile<128, 64, 32, 4, 1>>(cs);
     run_case<Tile<128, 128, 16, 2, 2>>(cs);
+    run_case<Tile<128, 128, 32, 2, 2>, true>(cs);
+    run_case<Tile<128, 64, 32, 4, 1>, true>(cs);
   }
   dense_case<128, 16>();
+  dense_case_bf();
   printf(failures ? "FAILED %d\n" : "ALL OK\n", failures);
   return failures ? 1 : 0;
 }

@@ -4,7 +4,7 @@ import numpy as np
 import torch
 
 import synthetic_inputs as S
-from helpers import oracle_spec, to64
+from helpers import oracle_spec, rel_l2, to64
 from oracle import alexnet_oracle as O
 
 # Tolerances of the fp32 path: loss relative error and per-tensor relative L2.
@@ -12,10 +12,10 @@ LOSS_RTOL = 1e-4
 TENSOR_RTOL = 1e-3
 
 
-def build_pair(binding, wl, batch, seed, bias=0.0, std=0.01, pseed=1, mom_std=0.0):
+def build_pair(binding, wl, batch, seed, bias=0.0, std=0.01, pseed=1, mom_std=0.0, precision=0):
     """Returns (net, spec, params64, mom64): a HIP replica and the oracle's
     view of the same float32 parameters."""
-    net = binding.AlexNet(wl, batch, seed=seed)
+    net = binding.AlexNet(wl, batch, seed=seed, precision=precision)
     spec = oracle_spec(wl, batch, seed=seed)
     shapes = O.param_shapes(spec)
     assert {k: tuple(v) for k, v in shapes.items()} == {k: tuple(v) for k, v in net.shapes.items()}
@@ -91,3 +91,72 @@ def validated_decisions(binding, net, spec, tau=1e-4, max_frac=1e-4, report=None
                 report[name] = int(diff.sum())
         return dec
     return hook
+
+
+# ------------------------------------------------------- whole step ---------
+def check_forward(lib, net, spec, cache, batch, tol=TENSOR_RTOL):
+    """Forward tensors are continuous in the inputs: compared directly."""
+    for i, cv in enumerate(spec.conv, start=1):
+        a = net.tensor(lib.T_CONV_ACT, i).reshape(cache[f"conv{i}.act"].shape)
+        assert rel_l2(a, cache[f"conv{i}.act"]) <= tol, ("act", i)
+        if cv.lrn:
+            assert rel_l2(net.tensor(lib.T_LRN, i).reshape(a.shape), cache[f"conv{i}.lrn"]) <= tol, ("lrn", i)
+        if cv.pool:
+            pv = net.tensor(lib.T_POOL, i).reshape(cache[f"conv{i}.pool"].shape)
+            assert rel_l2(pv, cache[f"conv{i}.pool"]) <= tol, ("pool", i)
+    for j in (6, 7):
+        a = net.tensor(lib.T_FC_ACT, j).reshape(batch, -1)
+        mask = cache["masks"][j - 6]
+        assert np.all(a[mask == 0] == 0), "dropout mask must match the generator bit for bit"
+        assert rel_l2(a, cache[f"fc{j}.act"]) <= tol, ("fc act", j)
+    assert rel_l2(net.tensor(lib.T_FC_ACT, 8).reshape(batch, -1), cache["logits"]) <= tol
+
+
+def run_step_and_compare(lib, wl, batch, seed, bias, std, use_raw, steps=1, mom_std=0.0, direct=True, precision=0,
+                         loss_rtol=LOSS_RTOL, tol=TENSOR_RTOL, direct_tol=None, tau=1e-4, max_frac=1e-4, report=None):
+    """Runs `steps` SGD steps in the library and in the oracle and compares loss,
+    forward tensors, gradients, updated weights and momentum.
+
+    direct=True additionally compares against the oracle's own forward
+    decisions (no information from the library enters the oracle at all)."""
+    net, spec, p64, m64 = build_pair(lib, wl, batch, seed=seed, bias=bias, std=std, mom_std=mom_std,
+                                     precision=precision)
+    direct_tol = tol if direct_tol is None else direct_tol
+    classes = wl["fc"][-1]
+    for step in range(steps):
+        if use_raw:
+            raw, labels = S.make_raw_batch(batch, wl["in_c"], wl["raw"], wl["raw"], classes, S.SEED_BASE + 100 + step)
+            mean = S.make_mean_image(wl["in_c"], wl["raw"], wl["raw"], S.SEED_BASE + 7)
+            net.preprocess(cuda(raw), cuda(mean), step, step % 2)
+            ox, oy, fl = O.crop_flip_params(spec, step)
+            x64 = O.preprocess(raw, mean, ox, oy, fl, wl["crop"], wl["crop"])
+        else:
+            x32, labels = S.make_float_batch(batch, wl["in_c"], wl["crop"], wl["crop"], classes, S.SEED_BASE + 1 + step)
+            net.set_input(cuda(x32), step % 2)
+            x64 = x32.astype(np.float64)
+        loss = net.forward_backward(cuda(labels), step, slot=step % 2)
+        net.check()
+        got_loss = float(loss.cpu().item())
+        g = net.get_grads()
+        flips = {}
+        loss_ref, p_new, m_new, g_ref, cache = O.train_step(
+            spec, p64, m64, x64, labels, step, decisions=validated_decisions(lib, net, spec, tau=tau, max_frac=max_frac, report=flips))
+        assert abs(got_loss - loss_ref) <= loss_rtol * abs(loss_ref), (step, got_loss, loss_ref)
+        check_forward(lib, net, spec, cache, batch, tol)
+        net.apply_update()
+        pn, mn = net.get_params(), net.get_momentum()
+        for k in g_ref:
+            assert np.linalg.norm(g_ref[k]) > 0, k
+            assert rel_l2(g[k], g_ref[k]) <= tol, ("grad", k, rel_l2(g[k], g_ref[k]))
+            if report is not None:
+                report[k] = max(report.get(k, 0.0), rel_l2(g[k], g_ref[k]))
+            assert rel_l2(pn[k], p_new[k]) <= tol, ("param", k)
+            assert rel_l2(mn[k], m_new[k]) <= tol, ("momentum", k, rel_l2(mn[k], m_new[k]))
+        if direct:
+            _, _, _, g_own, _ = O.train_step(spec, p64, m64, x64, labels, step)
+            for k in g_own:
+                assert rel_l2(g[k], g_own[k]) <= direct_tol, ("grad vs oracle's own decisions", k, flips)
+        # continue from the library's own fp32 state so that errors do not pile up across steps
+        p64, m64 = to64(pn), to64(mn)
+    net.close()
+    return got_loss

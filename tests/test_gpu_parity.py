@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import synthetic_inputs as S
-from gpu_common import LOSS_RTOL, TENSOR_RTOL, build_pair, cuda, validated_decisions
+from gpu_common import LOSS_RTOL, TENSOR_RTOL, build_pair, cuda, run_step_and_compare
 from helpers import oracle_spec, rel_l2, to64
 from oracle import alexnet_oracle as O
 
@@ -83,79 +83,19 @@ def test_preprocess_crop_flip_exact(lib):
 
 
 # ------------------------------------------------------- whole step ---------
-def _check_forward(lib, net, spec, cache, batch):
-    """Forward tensors are continuous in the inputs: compared directly."""
-    for i, cv in enumerate(spec.conv, start=1):
-        a = net.tensor(lib.T_CONV_ACT, i).reshape(cache[f"conv{i}.act"].shape)
-        assert rel_l2(a, cache[f"conv{i}.act"]) <= TENSOR_RTOL, ("act", i)
-        if cv.lrn:
-            assert rel_l2(net.tensor(lib.T_LRN, i).reshape(a.shape), cache[f"conv{i}.lrn"]) <= TENSOR_RTOL, ("lrn", i)
-        if cv.pool:
-            pv = net.tensor(lib.T_POOL, i).reshape(cache[f"conv{i}.pool"].shape)
-            assert rel_l2(pv, cache[f"conv{i}.pool"]) <= TENSOR_RTOL, ("pool", i)
-    for j in (6, 7):
-        a = net.tensor(lib.T_FC_ACT, j).reshape(batch, -1)
-        mask = cache["masks"][j - 6]
-        assert np.all(a[mask == 0] == 0), "dropout mask must match the generator bit for bit"
-        assert rel_l2(a, cache[f"fc{j}.act"]) <= TENSOR_RTOL, ("fc act", j)
-    assert rel_l2(net.tensor(lib.T_FC_ACT, 8).reshape(batch, -1), cache["logits"]) <= TENSOR_RTOL
-
-
-def _run_step_and_compare(lib, wl, batch, seed, bias, std, use_raw, steps=1, mom_std=0.0, direct=True):
-    """direct=True additionally compares against the oracle's own forward
-    decisions (no information from the library enters the oracle at all)."""
-    net, spec, p64, m64 = build_pair(lib, wl, batch, seed=seed, bias=bias, std=std, mom_std=mom_std)
-    classes = wl["fc"][-1]
-    for step in range(steps):
-        if use_raw:
-            raw, labels = S.make_raw_batch(batch, wl["in_c"], wl["raw"], wl["raw"], classes, S.SEED_BASE + 100 + step)
-            mean = S.make_mean_image(wl["in_c"], wl["raw"], wl["raw"], S.SEED_BASE + 7)
-            net.preprocess(cuda(raw), cuda(mean), step, step % 2)
-            ox, oy, fl = O.crop_flip_params(spec, step)
-            x64 = O.preprocess(raw, mean, ox, oy, fl, wl["crop"], wl["crop"])
-        else:
-            x32, labels = S.make_float_batch(batch, wl["in_c"], wl["crop"], wl["crop"], classes, S.SEED_BASE + 1 + step)
-            net.set_input(cuda(x32), step % 2)
-            x64 = x32.astype(np.float64)
-        loss = net.forward_backward(cuda(labels), step, slot=step % 2)
-        net.check()
-        got_loss = float(loss.cpu().item())
-        g = net.get_grads()
-        flips = {}
-        loss_ref, p_new, m_new, g_ref, cache = O.train_step(
-            spec, p64, m64, x64, labels, step, decisions=validated_decisions(lib, net, spec, report=flips))
-        assert abs(got_loss - loss_ref) <= LOSS_RTOL * abs(loss_ref), (step, got_loss, loss_ref)
-        _check_forward(lib, net, spec, cache, batch)
-        net.apply_update()
-        pn, mn = net.get_params(), net.get_momentum()
-        for k in g_ref:
-            assert np.linalg.norm(g_ref[k]) > 0, k
-            assert rel_l2(g[k], g_ref[k]) <= TENSOR_RTOL, ("grad", k, rel_l2(g[k], g_ref[k]))
-            assert rel_l2(pn[k], p_new[k]) <= TENSOR_RTOL, ("param", k)
-            assert rel_l2(mn[k], m_new[k]) <= TENSOR_RTOL, ("momentum", k, rel_l2(mn[k], m_new[k]))
-        if direct:
-            _, _, _, g_own, _ = O.train_step(spec, p64, m64, x64, labels, step)
-            for k in g_own:
-                assert rel_l2(g[k], g_own[k]) <= TENSOR_RTOL, ("grad vs oracle's own decisions", k, flips)
-        # continue from the library's own fp32 state so that errors do not pile up across steps
-        p64, m64 = to64(pn), to64(mn)
-    net.close()
-    return got_loss
-
-
 def test_mini_alexnet_step_batch4(lib):
     """Workload 1: mini-AlexNet, one SGD step, batch 4, weights N(0, 0.01^2), zero biases."""
-    loss = _run_step_and_compare(lib, S.MINI, 4, seed=11, bias=0.0, std=0.01, use_raw=False)
+    loss = run_step_and_compare(lib, S.MINI, 4, seed=11, bias=0.0, std=0.01, use_raw=False)
     assert abs(loss - math.log(10)) < 1e-2
 
 
 def test_mini_alexnet_three_steps_with_signal_everywhere(lib):
-    _run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01)
+    run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01)
 
 
 def test_midi_net_with_preprocess_ragged_tiles(lib):
     # raw uint8 pixels are O(100); small conv1 weights keep the activations moderate
-    _run_step_and_compare(lib, S.MIDI, 7, seed=13, bias=0.05, std=0.02, use_raw=True, steps=2, mom_std=0.01)
+    run_step_and_compare(lib, S.MIDI, 7, seed=13, bias=0.05, std=0.02, use_raw=True, steps=2, mom_std=0.01)
 
 
 def test_inference_forward(lib):

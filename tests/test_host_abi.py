@@ -57,7 +57,8 @@ def test_bad_arguments_are_reported_not_crashed(B):
     cfg = B.make_config(S.MINI, 0)
     with pytest.raises(B.AlexNetError):
         B.query(cfg)
-    cfg = B.make_config(S.MINI, 4, precision=1)
+    B.query(B.make_config(S.MINI, 4, precision=1))  # bf16 products are a valid configuration
+    cfg = B.make_config(S.MINI, 4, precision=2)
     with pytest.raises(B.AlexNetError) as e:
         B.query(cfg)
     assert e.value.code == B.ENOTIMPL
