@@ -168,7 +168,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
       s.Hp = (s.g.Ho - 3) / 2 + 1;
       s.Wp = (s.g.Wo - 3) / 2 + 1;
     }
-    if (s.g.in_elems() > 0x1fffffffL || s.g.out_elems() > 0x1fffffffL || s.g.w_elems() > 0x1fffffffL) {
+    if (s.g.in_elems() > 0x1ffffff0L || s.g.out_elems() > 0x1ffffff0L || s.g.w_elems() > 0x1ffffff0L) {
       set_error("conv%d: a tensor reaches 2 GiB; byte offsets in the kernels are 32-bit", i + 1);
       return ALEXNET_ESHAPE;
     }
@@ -187,7 +187,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
       set_error("fc width must be positive");
       return ALEXNET_ESHAPE;
     }
-    if ((long)in * c.fc[j] > 0x1fffffffL || (long)c.batch * in > 0x1fffffffL || (long)c.batch * c.fc[j] > 0x1fffffffL) {
+    if ((long)in * c.fc[j] > 0x1ffffff0L || (long)c.batch * in > 0x1ffffff0L || (long)c.batch * c.fc[j] > 0x1ffffff0L) {
       set_error("fc%d: a tensor reaches 2 GiB; byte offsets in the kernels are 32-bit", kStages + 1 + j);
       return ALEXNET_ESHAPE;
     }

@@ -133,6 +133,20 @@ struct ConvWeightGrad {  // rows = taps (backward-weight)
   }
 };
 
+// a k-tile inside one tap (see Im2colKTap): 16-byte loads, whole k-tiles
+template <int MODE>
+struct ConvGatherTap {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile<T, Im2colKTap<T::BM, T::BK, MODE>, DenseRowWhole<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+static inline bool tap_ok(const Im2colParams& a, const GemmDims& d) {
+  return a.Cg % kBK == 0 && a.kh * a.kw <= 32 && d.K % kBK == 0;
+}
+
 // bf16 flavours (vector loads only)
 template <int MODE>
 struct ConvGatherBf {
@@ -204,6 +218,14 @@ static int launch_slab_finish(const float* ws, int ns, int groups, long M, int N
 }
 
 // ------------------------------------------------------------- convolution ---
+template <class F, class Epi>
+static int by_tile_tap(const GemmPlan& p, const Im2colParams& a, const DenseParams& b, const Epi& e,
+                       const GemmDims& d, hipStream_t st) {
+  if (p.bn == 128) return F::template go<T128, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+  if (p.bn == 96) return F::template go<T96, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+  return F::template go<T64, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+}
+
 static GemmPlan fwd_plan(const ConvGeom& c, bool run, bool bf) {
   const GemmDims d = fwd_dims(c);
   return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8, bf);
@@ -284,14 +306,18 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
   const GemmPlan p = fwd_plan(c, run, bf);
   const Im2colParams a = run ? run_A(c, x) : fwd_A(c, x);
   const DenseParams b = run ? run_B(c, wrun) : fwd_B(c, wf);
+  const bool tap = !run && !bf && av && bv && tap_ok(a, d);
   if (p.ns == 1) {
     EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
     if (bf) return by_tile_bf<ConvGatherBf<IM2COL_FWD>>(p, a, b, ep, d, st);
+    if (tap) return by_tile_tap<ConvGatherTap<IM2COL_FWD>>(p, a, b, ep, d, st);
     return by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
   if (bf)
     AX_TRY((by_tile_bf<ConvGatherBf<IM2COL_FWD>>(p, a, b, ep, d, st)));
+  else if (tap)
+    AX_TRY((by_tile_tap<ConvGatherTap<IM2COL_FWD>>(p, a, b, ep, d, st)));
   else
     AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st)));
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st);
@@ -341,15 +367,19 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
   const GemmPlan p = bwdd_plan(c, bf);
   const Im2colParams a = bwdd_A(c, dy);
   const DenseParams b = bwdd_B(c, wb);
+  const bool tap = !bf && c.stride == 1 && av && bv && tap_ok(a, d);
   if (p.ns == 1) {
     EpiGate ep{dx, c.Cin, gate, c.cg(), 0};
     if (bf) return by_tile_bf<ConvGatherBf<IM2COL_T1>>(p, a, b, ep, d, st);
+    if (tap) return by_tile_tap<ConvGatherTap<IM2COL_T1>>(p, a, b, ep, d, st);
     if (c.stride == 1) return by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st);
     return by_tile<ConvGather<IM2COL_TS>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
   if (bf)
     AX_TRY((by_tile_bf<ConvGatherBf<IM2COL_T1>>(p, a, b, ep, d, st)));
+  else if (tap)
+    AX_TRY((by_tile_tap<ConvGatherTap<IM2COL_T1>>(p, a, b, ep, d, st)));
   else if (c.stride == 1)
     AX_TRY((by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st)));
   else

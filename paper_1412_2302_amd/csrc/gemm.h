@@ -77,7 +77,7 @@ inline float4 buf_ld4(const BufView& v, uint32_t off) {
   float r[4];
   for (int j = 0; j < 4; ++j) {
     const uint32_t o = off + 4u * j;
-    r[j] = (o >= off && o + 4 <= v.bytes) ? *reinterpret_cast<const float*>(reinterpret_cast<const char*>(v.p) + o) : 0.f;
+    r[j] = (o >= off && (uint64_t)o + 4 <= v.bytes) ? *reinterpret_cast<const float*>(reinterpret_cast<const char*>(v.p) + o) : 0.f;
   }
   float4 z;
   z.x = r[0]; z.y = r[1]; z.z = r[2]; z.w = r[3];
@@ -256,6 +256,20 @@ struct DenseRowInner {
   }
 };
 
+// DenseRowInner for GEMMs whose K and split chunk are multiples of BK: every k-tile is whole, the k test
+// is the same for all threads, and an address is one add.  A k-tile past the end is only ever prefetched,
+// never multiplied, so it may read real data: k0 is clamped to the last tile instead of being zero-filled.
+template <int ROWS, int BK>
+struct DenseRowWhole : DenseRowInner<ROWS, BK, true> {
+  typedef DenseRowInner<ROWS, BK, true> Base;
+  using Base::Base;
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int kc = k0 < kend ? k0 : kend - BK;  // uniform
+    this->pl.off[S] = this->base[S] + (uint32_t)kc * this->ld4;
+  }
+};
+
 // Geometry of an implicit im2col operand over a channel-last tensor
 // x[N][H][W][Ctot].  Pixels (n, y, x) run over an OH x OW grid; tap (r, s)
 // of pixel (y, x) reads x[n][iy][ix][c_off + c] with
@@ -392,6 +406,71 @@ struct Im2colKInner {
   }
 };
 
+// Im2colKInner for the common case that a k-tile lies inside one tap: channels per group a multiple of
+// BK (so K is too), at most 32 taps, 16-byte loads, modes 0 and 1.  The tap (r, s) and first channel of a
+// k-tile are then the same for the whole workgroup (scalar registers), and whether tap (r, s) of a pixel
+// lies inside the tensor is looked up in a per-pixel bit mask built once per tile: an address costs an
+// add, a bit-field extract and a bit-field insert.  K-tiles past the end are clamped as in DenseRowWhole.
+template <int ROWS, int BK, int MODE>
+struct Im2colKTap {
+  static constexpr int QK = BK / 4, NQ = ROWS * QK, NL = NQ / kThreads, NA = NL + 1;
+  static constexpr bool kRowMajor = true;
+  static constexpr int LD = BK + 4, LDS_FLOATS = ROWS * LD;
+  static_assert(kThreads % QK == 0 && NQ % kThreads == 0, "every load of a thread shares its k quad");
+  static_assert(MODE == IM2COL_FWD || MODE == IM2COL_T1, "unit-step gathers only");
+  typedef Im2colParams Params;
+  Im2colParams g;
+  BufView v;
+  int tid, kq;
+  uint32_t rowbase[NL];  // byte offset of the pixel's origin, its group's first channel and the thread's k quad
+  uint32_t outside[NL];  // bit r*kw + s set: that tap of the pixel lies outside the tensor
+  uint32_t tapoff;       // byte offset of the k-tile's tap and first channel from a pixel's origin (mod 2^32)
+  int tapbit;
+  Offsets<NL, true> pl;
+  AX_HD Im2colKTap(const Params& a, int grp, int tid_, int row0) : g(a), v(make_view(a.x, a.bytes)), tid(tid_) {
+    kq = tid % QK;
+    const int c_off = grp * a.c_stride_g + 4 * kq;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int p = row0 + (tid + i * kThreads) / QK;
+      const bool in = p < g.P;
+      const PixCoord c = decode_pixel(in ? p : 0, g);
+      const int y0 = MODE == IM2COL_FWD ? c.y * g.stride - g.pad : c.y + g.pad;
+      const int x0 = MODE == IM2COL_FWD ? c.x * g.stride_x - g.pad_x : c.x + g.pad;
+      rowbase[i] = row_base<MODE>(g, c.n, y0, x0, c_off);
+      uint32_t inside = 0;
+      int bit = 0;
+      for (int r = 0; r < g.kh; ++r)
+        for (int s2 = 0; s2 < g.kw; ++s2, ++bit) {
+          const int iy = MODE == IM2COL_FWD ? y0 + r : y0 - r, ix = MODE == IM2COL_FWD ? x0 + s2 : x0 - s2;
+          const bool ok = in && (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
+          inside |= (ok ? 1u : 0u) << bit;
+        }
+      outside[i] = ~inside;
+    }
+  }
+  // step 0 decodes the k-tile's tap (uniform), step 1+i places load i
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    if (S == 0) {
+      const TapCoord t = decode_tap(k0 < kend ? k0 : kend - BK, g);
+      const uint32_t tap = (((uint32_t)t.r * (uint32_t)g.W + (uint32_t)t.s) * (uint32_t)g.Ctot) * 4u;
+      tapoff = (MODE == IM2COL_FWD ? tap : 0u - tap) + (uint32_t)t.c * 4u;
+      tapbit = t.r * g.kw + t.s;
+    } else {
+      constexpr int i = S - 1;
+      // all ones where the tap is outside: the offset then becomes exactly kOob (the sum itself may be
+      // anything there, also close to 2^32, where a range check could wrap)
+      const uint32_t out = 0u - ((outside[i] >> tapbit) & 1u);
+      pl.off[i] = (out & kOob) | (~out & (rowbase[i] + tapoff));
+    }
+  }
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int s, float* lds, const float4* r) const {
+    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QK) * LD + 4 * kq) = r[s];
+  }
+};
+
 template <int ROWS, int BK, bool VEC>
 struct Im2colRowInner {
   static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = NQ / kThreads, NA = NL;
@@ -517,33 +596,43 @@ struct EpiSlab {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 // Fragments of one operand for a wave: TT 32-row blocks starting at LDS row `row`.
-// [row][k] tiles give a lane all its values of the k-tile in BK/8 16-byte reads;
-// [k][row] tiles are read 4 bytes at a time, one MFMA step ahead.
+// [row][k] tiles give a lane its values of four MFMA steps in one 16-byte read;
+// [k][row] tiles are read 4 bytes at a time.  Everything is fetched one MFMA step ahead of its use,
+// and the first values of a tile (start) during the last step of the tile before.
 template <class L, int TT, int BK>
 struct Frags {
+  static_assert(BK >= 16, "the last step of a tile must not use the registers that start() refills");
   float4 rk[L::kRowMajor ? TT : 1][L::kRowMajor ? BK / 8 : 1];
   float kr[2][TT];
   const float* base;
   int kh;
-  __device__ __forceinline__ void begin(const float* lds, int row, int kh_) {
+  __device__ __forceinline__ void start(const float* lds, int row, int kh_) {
     kh = kh_;
     if (L::kRowMajor) {
       base = lds + row * L::LD + 4 * kh;
-#pragma unroll
-      for (int t = 0; t < TT; ++t)
-#pragma unroll
-        for (int q = 0; q < BK / 8; ++q) rk[t][q] = *reinterpret_cast<const float4*>(base + t * 32 * L::LD + 8 * q);
+      quad<0>();
     } else {
       base = lds + row;
-      read<0>();
+      column<0>();
     }
   }
-  template <int U>
-  __device__ __forceinline__ void read() {  // [k][row] values of MFMA step U
-    if (!L::kRowMajor) {
-      const int k = 8 * (U >> 2) + (U & 3) + 4 * kh;
+  template <int Q>
+  __device__ __forceinline__ void quad() {
 #pragma unroll
-      for (int t = 0; t < TT; ++t) kr[U & 1][t] = base[k * L::LD + t * 32];
+    for (int t = 0; t < TT; ++t) rk[t][Q] = *reinterpret_cast<const float4*>(base + t * 32 * L::LD + 8 * Q);
+  }
+  template <int U>
+  __device__ __forceinline__ void column() {
+    const int k = 8 * (U >> 2) + (U & 3) + 4 * kh;
+#pragma unroll
+    for (int t = 0; t < TT; ++t) kr[U & 1][t] = base[k * L::LD + t * 32];
+  }
+  template <int U>
+  __device__ __forceinline__ void read() {  // values of MFMA step U >= 1
+    if (!L::kRowMajor) {
+      column<U>();
+    } else if (U % 4 == 0) {
+      quad<U / 4>();
     }
   }
   template <int U>
@@ -556,50 +645,61 @@ struct Frags {
   }
 };
 
-// Side work of one main-loop iteration: LDS stores of tile t+1, addresses of tile t+3.
+// Side work of one main-loop iteration, in this order: addresses of tile t+3, then the LDS stores of
+// tile t+1 (as late as possible: its loads were issued almost two iterations earlier).
 template <class T, class AL, class BL, int IDX>
 __device__ __forceinline__ void side_step(AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
                                           const float4* rb, int k_plan, int kend) {
-  constexpr int S0 = AL::NL, S1 = S0 + BL::NL, S2 = S1 + AL::NA, S3 = S2 + BL::NA;
-  if constexpr (IDX < S0) {
-    al.store_step(IDX, as_next, ra);
+  constexpr int S0 = AL::NA, S1 = S0 + BL::NA, S2 = S1 + AL::NL, S3 = S2 + BL::NL;
+  if constexpr (IDX < 0) {
+  } else if constexpr (IDX < S0) {
+    al.template addr_step<IDX>(k_plan, kend);
   } else if constexpr (IDX < S1) {
-    bl.store_step(IDX - S0, bs_next, rb);
+    bl.template addr_step<IDX - S0>(k_plan, kend);
   } else if constexpr (IDX < S2) {
-    al.template addr_step<IDX - S1>(k_plan, kend);
+    al.store_step(IDX - S1, as_next, ra);
   } else if constexpr (IDX < S3) {
-    bl.template addr_step<IDX - S2>(k_plan, kend);
+    bl.store_step(IDX - S2, bs_next, rb);
   }
 }
+// The side steps are dealt over the MFMA steps 0 .. KP-2, ending in step KP-2 (step KP-1 follows the barrier).
 template <class T, class AL, class BL, int U, int W = 0>
 __device__ __forceinline__ void side_slot(AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
                                           const float4* rb, int k_plan, int kend) {
-  constexpr int TOTAL = AL::NL + BL::NL + AL::NA + BL::NA, KP = T::BK / 2, PER = (TOTAL + KP - 1) / KP;
+  constexpr int TOTAL = AL::NL + BL::NL + AL::NA + BL::NA, SLOTS = T::BK / 2 - 1, PER = (TOTAL + SLOTS - 1) / SLOTS,
+                PAD = SLOTS * PER - TOTAL;
   if constexpr (W < PER) {
-    side_step<T, AL, BL, U * PER + W>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    side_step<T, AL, BL, U * PER + W - PAD>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
     side_slot<T, AL, BL, U, W + 1>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
   }
 }
 
-template <class T, class AL, class BL, bool SIDE, int U = 0>
+// The MFMA steps of one k-tile.  Before the last step all waves meet: by then every wave has read the
+// last values of this tile and stored its share of the next one, so the barrier also frees this tile's
+// buffer; the first reads of the next tile run under the last step's MFMAs.
+template <class T, class AL, class BL, int U = 0>
 __device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T::BK>& fa, Frags<BL, T::TN, T::BK>& fb,
                                             v16f (&acc)[T::TM][T::TN], AL& al, BL& bl, float* as_next,
                                             float* bs_next, const float4* ra, const float4* rb, int k_plan,
-                                            int kend) {
+                                            int kend, int a_row, int b_row, int kh) {
   constexpr int KP = T::BK / 2;
   if constexpr (U < KP) {
     if constexpr (U + 1 < KP) {
       fa.template read<U + 1>();
       fb.template read<U + 1>();
+    } else {
+      __syncthreads();
+      fa.start(as_next, a_row, kh);
+      fb.start(bs_next, b_row, kh);
     }
 #pragma unroll
     for (int i = 0; i < T::TM; ++i)
 #pragma unroll
       for (int j = 0; j < T::TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.template get<U>(i), fb.template get<U>(j), acc[i][j], 0, 0, 0);
-    if constexpr (SIDE) side_slot<T, AL, BL, U>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    if constexpr (U + 1 < KP) side_slot<T, AL, BL, U>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
     __builtin_amdgcn_sched_barrier(0);
-    tile_stream<T, AL, BL, SIDE, U + 1>(fa, fb, acc, al, bl, as_next, bs_next, ra, rb, k_plan, kend);
+    tile_stream<T, AL, BL, U + 1>(fa, fb, acc, al, bl, as_next, bs_next, ra, rb, k_plan, kend, a_row, b_row, kh);
   }
 }
 
@@ -631,7 +731,8 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
   const int a_row = wm * (T::TM * 32) + (lane & 31), b_row = wn * (T::TN * 32) + (lane & 31), kh = lane >> 5;
   if (nt > 0) {
     // prologue: tile 0 -> LDS buffer 0, tile 1 in flight in register set 1, addresses of tile 2 ready.
-    // Tiles past the end have every offset outside: they load zeros and store zeros, harmlessly.
+    // Tiles past the end are fetched and stored like any other but never multiplied: their loads return
+    // zeros (every offset outside) or, with the whole-tile loaders, repeat the last tile.
     float4 ra[2][AL::NL], rb[2][BL::NL];
     plan_all(al, kbeg, kend);
     plan_all(bl, kbeg, kend);
@@ -648,24 +749,22 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
     __syncthreads();
     Frags<AL, T::TM, T::BK> fa;
     Frags<BL, T::TN, T::BK> fb;
+    fa.start(As[0], a_row, kh);
+    fb.start(Bs[0], b_row, kh);
     // iteration t (parity p): fetch tile t+2 into register set p, MFMAs of tile t from LDS buffer p,
-    // meanwhile store register set p^1 (tile t+1) to LDS buffer p^1 and address tile t+3.
+    // meanwhile address tile t+3 and store register set p^1 (tile t+1) to LDS buffer p^1.
     for (int t = 0; t < nt; t += 2) {
       al.fetch(ra[0]);
       bl.fetch(rb[0]);
-      fa.begin(As[0], a_row, kh);
-      fb.begin(Bs[0], b_row, kh);
       __builtin_amdgcn_sched_barrier(0);
-      tile_stream<T, AL, BL, true>(fa, fb, acc, al, bl, As[1], Bs[1], ra[1], rb[1], kbeg + (t + 3) * T::BK, kend);
-      __syncthreads();
+      tile_stream<T, AL, BL>(fa, fb, acc, al, bl, As[1], Bs[1], ra[1], rb[1], kbeg + (t + 3) * T::BK, kend, a_row,
+                             b_row, kh);
       if (t + 1 < nt) {
         al.fetch(ra[1]);
         bl.fetch(rb[1]);
-        fa.begin(As[1], a_row, kh);
-        fb.begin(Bs[1], b_row, kh);
         __builtin_amdgcn_sched_barrier(0);
-        tile_stream<T, AL, BL, true>(fa, fb, acc, al, bl, As[0], Bs[0], ra[0], rb[0], kbeg + (t + 4) * T::BK, kend);
-        __syncthreads();
+        tile_stream<T, AL, BL>(fa, fb, acc, al, bl, As[0], Bs[0], ra[0], rb[0], kbeg + (t + 4) * T::BK, kend, a_row,
+                               b_row, kh);
       }
     }
   }

@@ -341,6 +341,34 @@ static void run_case(const Case& cs) {
       emu_gemm<T, Im2colKInner<T::BM, T::BK, false, IM2COL_FWD>, DenseRowInner<T::BN, T::BK, false>, EpiBiasAct>(
           fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, kc, 1, d.groups);
     check("fwd", nm, y, y_ref);
+    // a k-tile inside one tap: uniform tap decode, per-pixel tap masks, whole k-tiles
+    const Im2colParams fa = fwd_A(c, x);
+    if (fwd_A_vec(c, x) && fwd_B_vec(c, wf) && fa.Cg % T::BK == 0 && c.k * c.k <= 32) {
+      std::fill(y.begin(), y.end(), NAN);
+      emu_gemm<T, Im2colKTap<T::BM, T::BK, IM2COL_FWD>, DenseRowWhole<T::BN, T::BK>, EpiBiasAct>(
+          fa, fwd_B(c, wf), e, d.M, d.N, d.K, kc, 1, d.groups);
+      check("fwd_tap", nm, y, y_ref);
+      // split-k with whole-tile chunks
+      if (d.K / T::BK >= 3) {
+        const int ns = 3, chunk = ((d.K / T::BK + ns - 1) / ns) * T::BK;
+        std::vector<float> ws((size_t)d.groups * ns * d.M * d.N, NAN), ysum(c.out_elems(), 0.f);
+        EpiSlab es{ws.data(), (long)d.M * d.N, d.N, nullptr};
+        emu_gemm<T, Im2colKTap<T::BM, T::BK, IM2COL_FWD>, DenseRowWhole<T::BN, T::BK>, EpiSlab>(
+            fa, fwd_B(c, wf), es, d.M, d.N, d.K, chunk, ns, d.groups);
+        for (int g = 0; g < d.groups; ++g)
+          for (int sp = 0; sp < ns; ++sp)
+            for (int m = 0; m < d.M; ++m)
+              for (int n = 0; n < d.N; ++n) {
+                const float v = ws[(((size_t)g * ns + sp) * d.M + m) * d.N + n];
+                if (v == v) ysum[(size_t)m * c.Cout + g * og + n] += v;  // a chunk past K leaves its slab unwritten
+              }
+        for (long i = 0; i < c.out_elems(); ++i) {
+          const float v = ysum[i] + bias[i % c.Cout];
+          ysum[i] = v > 0 ? v : 0;
+        }
+        check("fwd_tap_s3", nm, ysum, y_ref);
+      }
+    }
   }
   // ---- run mode: forward and backward weight through the padded-row view ----
   if (run_mode(c) && c.Cout % 4 == 0) {
@@ -393,6 +421,13 @@ static void run_case(const Case& cs) {
       emu_gemm<T, Im2colKInner<T::BM, T::BK, false, IM2COL_TS>, DenseRowInner<T::BN, T::BK, false>, EpiGate>(
           bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K, kc, 1, d.groups);
     check("bwd_data", nm, dx, dx_ref);
+    const Im2colParams ba = bwdd_A(c, dy);
+    if (c.stride == 1 && vv && ba.Cg % T::BK == 0 && c.k * c.k <= 32) {
+      std::fill(dx.begin(), dx.end(), NAN);
+      emu_gemm<T, Im2colKTap<T::BM, T::BK, IM2COL_T1>, DenseRowWhole<T::BN, T::BK>, EpiGate>(
+          ba, bwdd_B(c, wb), e, d.M, d.N, d.K, kc, 1, d.groups);
+      check("bwdd_tap", nm, dx, dx_ref);
+    }
   }
   // ---- backward data by phases (strided, ungrouped) ----
   if (phase_mode(c) && c.Cout % 4 == 0 && phase_n(c) % 4 == 0) {
@@ -568,6 +603,8 @@ int main() {
       {geom(2, 6, 72, 72, 3, 1, 1, 2), "k3p1g2c36"},
       {geom(1, 9, 12, 20, 3, 2, 1, 2), "k3s2p1g2"},      // strided transposed gather with groups
       {geom(5, 5, 132, 136, 3, 1, 1, 1), "k3wide"},      // more than one tile along N and K rows
+      {geom(2, 7, 64, 64, 3, 1, 1, 2), "k3p1g2c32"},     // a k-tile inside one tap (32 channels per group)
+      {geom(3, 6, 32, 96, 5, 1, 2, 1), "k5p2c32"},       // 25 taps, ragged rows and columns
   };
   for (const Case& cs : cases) {
     run_case<Tile<128, 128, 32, 2, 2>>(cs);
