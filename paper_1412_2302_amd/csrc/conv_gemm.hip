@@ -14,6 +14,9 @@ constexpr int kBK = AX_BK;  // depth of a k-tile
 typedef Tile<128, 128, kBK, 2, 2> T128;  // wave tile 64 x 64
 typedef Tile<128, 96, kBK, 4, 1> T96;    // wave tile 32 x 96
 typedef Tile<128, 64, kBK, 4, 1> T64;    // wave tile 32 x 64
+// 48 columns out of 16x16x4 blocks (wave tile 32 x 48), k-tile 32; only with the whole-tile loaders
+constexpr int kBK48 = 32;
+typedef Tile<128, 48, kBK48, 4, 1, 16> T48;
 // (256 x 128 and 256 x 96 tiles were measured too: their 128 accumulator
 // registers leave one wave per SIMD, and with nobody to cover barrier and LDS
 // latency they ran 8-12 % slower than 128 x 128 on every AlexNet layer.)
@@ -31,33 +34,36 @@ struct GemmPlan {
   int bm, bn, ns, kchunk;
 };
 struct TileOption {
-  int bm, bn;
+  int bm, bn, bk;
   double eff;  // fraction of the per-CU fp32 MFMA rate this tile reaches on a long reduction
 };
-static const TileOption kTileOptions[] = {{128, 128, 0.80}, {128, 96, 0.68}, {128, 64, 0.62}};
+static const TileOption kTileOptions[] = {{128, 128, kBK, 0.80}, {128, 96, kBK, 0.68}, {128, 64, kBK, 0.62},
+                                          {128, 48, kBK48, 0.60}};
 // bf16 MFMA tiles: k-tile of 32; no longer MFMA-bound, priced at ~4x the fp32 rate
 constexpr int kBKbf = 32;
 typedef Tile<128, 128, kBKbf, 2, 2> B128;
 typedef Tile<128, 64, kBKbf, 4, 1> B64;
-static const TileOption kTileOptionsBf[] = {{128, 128, 3.2}, {128, 64, 2.2}};
+static const TileOption kTileOptionsBf[] = {{128, 128, kBKbf, 3.2}, {128, 64, kBKbf, 2.2}};
 
 // precision of the GEMMs launched by the calling thread: 0 fp32 MFMA, 1 bf16 MFMA with fp32 accumulation
 static thread_local int g_bf16 = 0;
 void set_gemm_precision(int bf16) { g_bf16 = bf16 ? 1 : 0; }
 
-static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int max_s, bool bf = false) {
-  const int bk = bf ? kBKbf : kBK;
-  const int ktiles = ceil_div(K, bk);
-  GemmPlan best{128, 128, 1, ktiles * bk};
+static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int max_s, bool bf = false,
+                          bool allow48 = false) {
+  const TileOption* opts = bf ? kTileOptionsBf : kTileOptions;
+  const int nopts = bf ? 2 : (allow48 ? 4 : 3);
+  GemmPlan best{128, 128, 1, ceil_div(K, opts[0].bk) * opts[0].bk};
   double best_t = 1e30;
-  for (int o = 0; o < (bf ? 2 : 3); ++o) {
-    const TileOption& to = bf ? kTileOptionsBf[o] : kTileOptions[o];
+  for (int o = 0; o < nopts; ++o) {
+    const TileOption& to = opts[o];
+    const int bk = to.bk, ktiles = ceil_div(K, bk);
     const long tiles = (long)ceil_div(M, to.bm) * ceil_div(N, to.bn) * groups;
     const double t_tile = 2.0 * to.bm * to.bn * (double)ktiles * bk / (0.614e12 * to.eff);
     for (int s = 1; s <= max_s && s <= ktiles; ++s) {
       const int per = ceil_div(ktiles, s);
       if (ceil_div(ktiles, per) != s) continue;
-      if (s > 1 && per < 6) break;
+      if (s > 1 && per * bk < 96) break;
       const double rounds = (double)ceil_div(tiles * s, 256);
       double t = rounds * t_tile * per / ktiles + 4e-6;
       if (s > 1) t += (s + 1) * out_bytes / 2.5e12 + 6e-6;
@@ -143,8 +149,8 @@ struct ConvGatherTap {
         a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
   }
 };
-static inline bool tap_ok(const Im2colParams& a, const GemmDims& d) {
-  return a.Cg % kBK == 0 && a.kh * a.kw <= 32 && d.K % kBK == 0;
+static inline bool tap_ok(const Im2colParams& a, const GemmDims& d, int bk = kBK) {
+  return a.Cg % bk == 0 && a.kh * a.kw <= 32 && d.K % bk == 0;
 }
 
 // bf16 flavours (vector loads only)
@@ -223,16 +229,18 @@ static int by_tile_tap(const GemmPlan& p, const Im2colParams& a, const DensePara
                        const GemmDims& d, hipStream_t st) {
   if (p.bn == 128) return F::template go<T128, Epi>(a, b, e, d, p.kchunk, p.ns, st);
   if (p.bn == 96) return F::template go<T96, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+  if (p.bn == 48) return F::template go<T48, Epi>(a, b, e, d, p.kchunk, p.ns, st);
   return F::template go<T64, Epi>(a, b, e, d, p.kchunk, p.ns, st);
 }
 
-static GemmPlan fwd_plan(const ConvGeom& c, bool run, bool bf) {
+// t48: the 48-column tile may be used (its loaders need a k-tile of 32 inside one tap)
+static GemmPlan fwd_plan(const ConvGeom& c, bool run, bool bf, bool t48 = false) {
   const GemmDims d = fwd_dims(c);
-  return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8, bf);
+  return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8, bf, t48);
 }
-static GemmPlan bwdd_plan(const ConvGeom& c, bool bf) {
+static GemmPlan bwdd_plan(const ConvGeom& c, bool bf, bool t48 = false) {
   const GemmDims d = bwdd_dims(c);
-  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8, bf);
+  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8, bf, t48);
 }
 static GemmPlan bwdw_plan(const ConvGeom& c, bool run, bool bf) {
   const GemmDims d = bwdw_dims(c);
@@ -244,10 +252,11 @@ size_t conv_fwd_ws_floats(const ConvGeom& c) {
   int ns = 0;
   for (int run = 0; run < 2; ++run)
     for (int bf = 0; bf < 2; ++bf) ns = std::max(ns, fwd_plan(c, run && run_mode(c), bf).ns);
+  ns = std::max(ns, fwd_plan(c, false, false, true).ns);
   return ns > 1 ? (size_t)ns * c.out_elems() : 0;
 }
 size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
-  const int ns = std::max(bwdd_plan(c, false).ns, bwdd_plan(c, true).ns);
+  const int ns = std::max(std::max(bwdd_plan(c, false).ns, bwdd_plan(c, true).ns), bwdd_plan(c, false, true).ns);
   return ns > 1 ? (size_t)ns * c.in_elems() : 0;
 }
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
@@ -303,9 +312,10 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
   if (run) d.K = run_k(c);
   const bool av = run || fwd_A_vec(c, x), bv = run || fwd_B_vec(c, wf);
   const bool bf = g_bf16 && av && bv;
-  const GemmPlan p = fwd_plan(c, run, bf);
   const Im2colParams a = run ? run_A(c, x) : fwd_A(c, x);
   const DenseParams b = run ? run_B(c, wrun) : fwd_B(c, wf);
+  const bool t48 = !run && !bf && av && bv && tap_ok(a, d, kBK48);
+  const GemmPlan p = fwd_plan(c, run, bf, t48);
   const bool tap = !run && !bf && av && bv && tap_ok(a, d);
   if (p.ns == 1) {
     EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
@@ -364,9 +374,10 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
   AlgoFlops af(conv_flops(c));
   const bool av = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb), bv = bwdd_B_vec(c, wb);
   const bool bf = g_bf16 && av && bv && c.stride == 1;
-  const GemmPlan p = bwdd_plan(c, bf);
   const Im2colParams a = bwdd_A(c, dy);
   const DenseParams b = bwdd_B(c, wb);
+  const bool t48 = !bf && c.stride == 1 && av && bv && tap_ok(a, d, kBK48);
+  const GemmPlan p = bwdd_plan(c, bf, t48);
   const bool tap = !bf && c.stride == 1 && av && bv && tap_ok(a, d);
   if (p.ns == 1) {
     EpiGate ep{dx, c.Cin, gate, c.cg(), 0};

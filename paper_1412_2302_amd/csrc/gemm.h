@@ -53,13 +53,28 @@ namespace ax {
 constexpr int kThreads = 256;
 constexpr uint32_t kOob = 0x80000000u;  // byte offset no operand reaches
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
+// Workgroup tile BM x BN x BK computed by WAVES_M x WAVES_N waves out of RB x RB MFMA blocks:
+// RB = 32 is v_mfma_f32_32x32x2_f32 (lane l supplies A[l%32][l/32] and B[l/32][l%32]; accumulator register
+// r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32]), RB = 16 is v_mfma_f32_16x16x4_f32 (A[l%16][l/16],
+// B[l/16][l%16], C[4*(l/16) + r][l%16]).  Both run at the same rate; the small block exists for operands
+// whose extent is a multiple of 16 but not of 32.
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int RB_ = 32>
 struct Tile {
-  static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-  static constexpr int TM = BM / (32 * WAVES_M), TN = BN / (32 * WAVES_N);
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, RB = RB_;
+  static constexpr int G = 64 / RB;          // k depth of one MFMA = lane groups along k
+  static constexpr int KP = BK / G;          // MFMA steps per k-tile
+  static constexpr int NACC = RB * RB / 64;  // accumulator registers per block
+  static constexpr int TM = BM / (RB * WAVES_M), TN = BN / (RB * WAVES_N);
+  static_assert(RB == 32 || RB == 16, "MFMA block is 32x32x2 or 16x16x4");
   static_assert(WAVES_M * WAVES_N * 64 == kThreads, "four waves per workgroup");
-  static_assert(TM * 32 * WAVES_M == BM && TN * 32 * WAVES_N == BN, "tile must be whole 32x32 MFMA blocks");
-  static_assert(BK % 8 == 0, "MFMAs take k in blocks of eight");
+  static_assert(TM * RB * WAVES_M == BM && TN * RB * WAVES_N == BN, "tile must be whole MFMA blocks");
+  static_assert(BK % (4 * G) == 0, "a lane's four consecutive k feed four MFMA steps");
+  // k consumed by MFMA step u from lane group g (the same on both operands, so any order is a valid contraction)
+  AX_HD static int step_k(int u, int g) { return 4 * G * (u >> 2) + 4 * g + (u & 3); }
+  // row of accumulator register r of a lane inside its block; the column is lane % RB
+  AX_HD static int acc_row(int lane, int r) {
+    return RB == 32 ? 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) : 4 * (lane >> 4) + r;
+  }
 };
 
 // ---- buffer views --------------------------------------------------------------
@@ -595,21 +610,22 @@ struct EpiSlab {
 #ifndef AX_HOST_EMU
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// Fragments of one operand for a wave: TT 32-row blocks starting at LDS row `row`.
+// Fragments of one operand for a wave: TT blocks of T::RB rows starting at LDS row `row`.
 // [row][k] tiles give a lane its values of four MFMA steps in one 16-byte read;
 // [k][row] tiles are read 4 bytes at a time.  Everything is fetched one MFMA step ahead of its use,
 // and the first values of a tile (start) during the last step of the tile before.
-template <class L, int TT, int BK>
+template <class L, int TT, class T>
 struct Frags {
-  static_assert(BK >= 16, "the last step of a tile must not use the registers that start() refills");
-  float4 rk[L::kRowMajor ? TT : 1][L::kRowMajor ? BK / 8 : 1];
+  static constexpr int NQ = T::BK / (4 * T::G);
+  static_assert(((T::KP - 1) >> 2) >= 1, "the last step of a tile must not use the registers that start() refills");
+  float4 rk[L::kRowMajor ? TT : 1][L::kRowMajor ? NQ : 1];
   float kr[2][TT];
   const float* base;
-  int kh;
-  __device__ __forceinline__ void start(const float* lds, int row, int kh_) {
-    kh = kh_;
+  int g;
+  __device__ __forceinline__ void start(const float* lds, int row, int g_) {
+    g = g_;
     if (L::kRowMajor) {
-      base = lds + row * L::LD + 4 * kh;
+      base = lds + row * L::LD + 4 * g;
       quad<0>();
     } else {
       base = lds + row;
@@ -619,13 +635,14 @@ struct Frags {
   template <int Q>
   __device__ __forceinline__ void quad() {
 #pragma unroll
-    for (int t = 0; t < TT; ++t) rk[t][Q] = *reinterpret_cast<const float4*>(base + t * 32 * L::LD + 8 * Q);
+    for (int t = 0; t < TT; ++t)
+      rk[t][Q] = *reinterpret_cast<const float4*>(base + t * T::RB * L::LD + 4 * T::G * Q);
   }
   template <int U>
   __device__ __forceinline__ void column() {
-    const int k = 8 * (U >> 2) + (U & 3) + 4 * kh;
+    const int k = T::step_k(U, g);
 #pragma unroll
-    for (int t = 0; t < TT; ++t) kr[U & 1][t] = base[k * L::LD + t * 32];
+    for (int t = 0; t < TT; ++t) kr[U & 1][t] = base[k * L::LD + t * T::RB];
   }
   template <int U>
   __device__ __forceinline__ void read() {  // values of MFMA step U >= 1
@@ -642,6 +659,24 @@ struct Frags {
       return (U & 3) == 0 ? v.x : (U & 3) == 1 ? v.y : (U & 3) == 2 ? v.z : v.w;
     }
     return kr[U & 1][t];
+  }
+};
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+template <int RB>
+struct MfmaBlock;
+template <>
+struct MfmaBlock<32> {
+  typedef v16f Acc;
+  static __device__ __forceinline__ Acc mma(float a, float b, Acc c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+  }
+};
+template <>
+struct MfmaBlock<16> {
+  typedef v4f Acc;
+  static __device__ __forceinline__ Acc mma(float a, float b, Acc c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
   }
 };
 
@@ -666,7 +701,7 @@ __device__ __forceinline__ void side_step(AL& al, BL& bl, float* as_next, float*
 template <class T, class AL, class BL, int U, int W = 0>
 __device__ __forceinline__ void side_slot(AL& al, BL& bl, float* as_next, float* bs_next, const float4* ra,
                                           const float4* rb, int k_plan, int kend) {
-  constexpr int TOTAL = AL::NL + BL::NL + AL::NA + BL::NA, SLOTS = T::BK / 2 - 1, PER = (TOTAL + SLOTS - 1) / SLOTS,
+  constexpr int TOTAL = AL::NL + BL::NL + AL::NA + BL::NA, SLOTS = T::KP - 1, PER = (TOTAL + SLOTS - 1) / SLOTS,
                 PAD = SLOTS * PER - TOTAL;
   if constexpr (W < PER) {
     side_step<T, AL, BL, U * PER + W - PAD>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
@@ -678,11 +713,11 @@ __device__ __forceinline__ void side_slot(AL& al, BL& bl, float* as_next, float*
 // last values of this tile and stored its share of the next one, so the barrier also frees this tile's
 // buffer; the first reads of the next tile run under the last step's MFMAs.
 template <class T, class AL, class BL, int U = 0>
-__device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T::BK>& fa, Frags<BL, T::TN, T::BK>& fb,
-                                            v16f (&acc)[T::TM][T::TN], AL& al, BL& bl, float* as_next,
-                                            float* bs_next, const float4* ra, const float4* rb, int k_plan,
-                                            int kend, int a_row, int b_row, int kh) {
-  constexpr int KP = T::BK / 2;
+__device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T>& fa, Frags<BL, T::TN, T>& fb,
+                                            typename MfmaBlock<T::RB>::Acc (&acc)[T::TM][T::TN], AL& al, BL& bl,
+                                            float* as_next, float* bs_next, const float4* ra, const float4* rb,
+                                            int k_plan, int kend, int a_row, int b_row, int kh) {
+  constexpr int KP = T::KP;
   if constexpr (U < KP) {
     if constexpr (U + 1 < KP) {
       fa.template read<U + 1>();
@@ -696,7 +731,7 @@ __device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T::BK>& fa, Frags<B
     for (int i = 0; i < T::TM; ++i)
 #pragma unroll
       for (int j = 0; j < T::TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.template get<U>(i), fb.template get<U>(j), acc[i][j], 0, 0, 0);
+        acc[i][j] = MfmaBlock<T::RB>::mma(fa.template get<U>(i), fb.template get<U>(j), acc[i][j]);
     if constexpr (U + 1 < KP) side_slot<T, AL, BL, U>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
     __builtin_amdgcn_sched_barrier(0);
     tile_stream<T, AL, BL, U + 1>(fa, fb, acc, al, bl, as_next, bs_next, ra, rb, k_plan, kend, a_row, b_row, kh);
@@ -720,15 +755,16 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
   BL bl(bp, g, tid, n0);
   ep.set_group(g, z);
 
-  v16f acc[T::TM][T::TN];
+  typename MfmaBlock<T::RB>::Acc acc[T::TM][T::TN];
 #pragma unroll
   for (int i = 0; i < T::TM; ++i)
 #pragma unroll
     for (int j = 0; j < T::TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < T::NACC; ++r) acc[i][j][r] = 0.f;
 
-  const int a_row = wm * (T::TM * 32) + (lane & 31), b_row = wn * (T::TN * 32) + (lane & 31), kh = lane >> 5;
+  constexpr int RB = T::RB;
+  const int a_row = wm * (T::TM * RB) + lane % RB, b_row = wn * (T::TN * RB) + lane % RB, kh = lane / RB;
   if (nt > 0) {
     // prologue: tile 0 -> LDS buffer 0, tile 1 in flight in register set 1, addresses of tile 2 ready.
     // Tiles past the end are fetched and stored like any other but never multiplied: their loads return
@@ -747,8 +783,8 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
     plan_all(al, kbeg + 2 * T::BK, kend);
     plan_all(bl, kbeg + 2 * T::BK, kend);
     __syncthreads();
-    Frags<AL, T::TM, T::BK> fa;
-    Frags<BL, T::TN, T::BK> fb;
+    Frags<AL, T::TM, T> fa;
+    Frags<BL, T::TN, T> fb;
     fa.start(As[0], a_row, kh);
     fb.start(Bs[0], b_row, kh);
     // iteration t (parity p): fetch tile t+2 into register set p, MFMAs of tile t from LDS buffer p,
@@ -773,11 +809,11 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
   for (int i = 0; i < T::TM; ++i)
 #pragma unroll
     for (int j = 0; j < T::TN; ++j) {
-      const int n = n0 + wn * (T::TN * 32) + j * 32 + (lane & 31);
+      const int n = n0 + wn * (T::TN * RB) + j * RB + lane % RB;
       if (n >= N) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * (T::TM * 32) + i * 32 + acc_row(lane, r);
+      for (int r = 0; r < T::NACC; ++r) {
+        const int m = m0 + wm * (T::TM * RB) + i * RB + T::acc_row(lane, r);
         if (m < M) ep.apply(m, n, acc[i][j][r]);
       }
     }

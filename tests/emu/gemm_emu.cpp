@@ -65,21 +65,23 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
           }
           for (int wave = 0; wave < 4; ++wave) {
             const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
-            for (int kk = 0; kk < T::BK / 2; ++kk) {
+            constexpr int RB = T::RB, G = T::G;
+            for (int kk = 0; kk < T::KP; ++kk) {
               float a[64][T::TM], b[64][T::TN];
               for (int lane = 0; lane < 64; ++lane) {
-                const int kr = step_k(kk, lane >> 5);
-                for (int i = 0; i < T::TM; ++i) a[lane][i] = As[lds_index<AL>(wm * (T::TM * 32) + (lane & 31) + i * 32, kr)];
-                for (int j = 0; j < T::TN; ++j) b[lane][j] = Bs[lds_index<BL>(wn * (T::TN * 32) + (lane & 31) + j * 32, kr)];
+                const int kr = T::step_k(kk, lane / RB);
+                for (int i = 0; i < T::TM; ++i) a[lane][i] = As[lds_index<AL>(wm * (T::TM * RB) + lane % RB + i * RB, kr)];
+                for (int j = 0; j < T::TN; ++j) b[lane][j] = Bs[lds_index<BL>(wn * (T::TN * RB) + lane % RB + j * RB, kr)];
               }
-              // D[ii][jj] += sum_{k2<2} A[ii][k2] * B[k2][jj], lane k2*32+ii holds A[ii][k2], lane k2*32+jj holds B[k2][jj]
+              // one MFMA: D[ii][jj] += sum over g < G of A[ii][g] * B[g][jj]; lane g*RB+ii holds A[ii][g],
+              // lane g*RB+jj holds B[g][jj]; register r of lane l is D[acc_row(l, r)][l % RB]
               for (int i = 0; i < T::TM; ++i)
                 for (int j = 0; j < T::TN; ++j)
                   for (int lane = 0; lane < 64; ++lane)
-                    for (int r = 0; r < 16; ++r) {
-                      const int ii = acc_row(lane, r), jj = lane & 31;
+                    for (int r = 0; r < T::NACC; ++r) {
+                      const int ii = T::acc_row(lane, r), jj = lane % RB;
                       float s = 0.f;
-                      for (int k2 = 0; k2 < 2; ++k2) s += a[k2 * 32 + ii][i] * b[k2 * 32 + jj][j];
+                      for (int k2 = 0; k2 < G; ++k2) s += a[k2 * RB + ii][i] * b[k2 * RB + jj][j];
                       ACC(wave, i, j, lane, r) += s;
                     }
             }
@@ -87,13 +89,14 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
         }
         for (int wave = 0; wave < 4; ++wave) {
           const int wm = wave % T::WAVES_M, wn = wave / T::WAVES_M;
+          constexpr int RB = T::RB;
           for (int lane = 0; lane < 64; ++lane)
             for (int i = 0; i < T::TM; ++i)
               for (int j = 0; j < T::TN; ++j) {
-                const int n = n0 + wn * (T::TN * 32) + j * 32 + (lane & 31);
+                const int n = n0 + wn * (T::TN * RB) + j * RB + lane % RB;
                 if (n >= N) continue;
-                for (int r = 0; r < 16; ++r) {
-                  const int m = m0 + wm * (T::TM * 32) + i * 32 + acc_row(lane, r);
+                for (int r = 0; r < T::NACC; ++r) {
+                  const int m = m0 + wm * (T::TM * RB) + i * RB + T::acc_row(lane, r);
                   if (m < M) e.apply(m, n, ACC(wave, i, j, lane, r));
                 }
               }
@@ -592,9 +595,28 @@ static void check_fastdiv() {
   if (bad) ++failures;
 }
 
+template <class T>
+static void check_acc_map() {
+  // registers x lanes of one MFMA block cover its RB x RB outputs exactly once
+  std::vector<int> seen(T::RB * T::RB, 0);
+  for (int lane = 0; lane < 64; ++lane)
+    for (int r = 0; r < T::NACC; ++r) ++seen[T::acc_row(lane, r) * T::RB + lane % T::RB];
+  bool ok = true;
+  for (int v : seen) ok = ok && v == 1;
+  // the k of the steps and lane groups of one k-tile cover 0..BK-1 exactly once
+  std::vector<int> ks(T::BK, 0);
+  for (int u = 0; u < T::KP; ++u)
+    for (int g = 0; g < T::G; ++g) ++ks[T::step_k(u, g)];
+  for (int v : ks) ok = ok && v == 1;
+  printf("acc/k map RB=%d BK=%d %s\n", T::RB, T::BK, ok ? "ok" : "FAIL");
+  if (!ok) ++failures;
+}
+
 int main() {
   srand(1234);
   check_fastdiv();
+  check_acc_map<Tile<128, 128, 16, 2, 2>>();
+  check_acc_map<Tile<128, 48, 32, 4, 1, 16>>();
   std::vector<Case> cases = {
       {geom(2, 23, 3, 8, 11, 4, 0, 1), "k11s4c3"},      // scalar gather, stride 4
       {geom(3, 13, 3, 16, 7, 2, 0, 1), "k7s2c3"},       // mini conv1
@@ -611,6 +633,7 @@ int main() {
     run_case<Tile<128, 96, 32, 4, 1>>(cs);
     run_case<Tile<128, 64, 32, 4, 1>>(cs);
     run_case<Tile<128, 128, 16, 2, 2>>(cs);
+    run_case<Tile<128, 48, 32, 4, 1, 16>>(cs);
     run_case<Tile<128, 128, 32, 2, 2>, true>(cs);
     run_case<Tile<128, 64, 32, 4, 1>, true>(cs);
   }
