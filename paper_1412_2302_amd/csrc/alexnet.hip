@@ -74,6 +74,7 @@ static const int kStages = 5, kFc = 3, kSlots = 3;  // slot 2 is the inference i
 struct Stage {
   ConvGeom g;
   bool lrn, pool;
+  bool fused_ok;        // normalisation and pool run as one kernel, forward and backward
   int Hp, Wp;           // stage output size (after the pool when present)
   size_t w_off, b_off;  // offsets into the flat parameter vector
   float *act, *lrn_out, *pool_out, *dact, *d_lrn, *d_out, *wb;
@@ -85,6 +86,7 @@ struct Stage {
   long out_elems() const { return (long)g.B * Hp * Wp * g.Cout; }
   const float* out() const { return pool ? pool_out : lrn ? lrn_out : act; }
   bool plain() const { return !lrn && !pool; }
+  bool fused() const { return fused_ok; }
 };
 struct Dense {
   int in, out;
@@ -225,6 +227,8 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.slot = s.pool ? a.take<uint8_t>(oe) : nullptr;
     s.d_lrn = (s.lrn && s.pool) ? a.take<float>(ae) : nullptr;
     s.d_out = s.plain() ? s.dact : a.take<float>(oe);
+    s.fused_ok = s.lrn && s.pool && base &&
+                 lrn_pool_fused_ok(s.act, s.pool_out, s.d_out, s.dact, s.slot, s.g.Cout, c.lrn_n);
     s.wb = a.take<float>(s.g.w_elems());
     s.wphase = conv_phase_mode(s.g) ? a.take<float>(conv_phase_w_floats(s.g)) : nullptr;
     s.wrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
@@ -236,6 +240,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     gws = std::max(gws, conv_fwd_ws_floats(s.g));
     gws = std::max(gws, conv_bwd_data_ws_floats(s.g));
     cws = std::max(cws, colsum_ws_floats(s.g.P(), s.g.Cout));
+    if (s.lrn && s.pool) cws = std::max(cws, lrn_part_floats(s.g.Cout));
   }
   for (int j = 0; j < kFc; ++j) {
     Dense& f = n->fc[j];
@@ -285,6 +290,12 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
     }
     ProfContext pc(s.lab[0]);
     h = s.act;
+    if (s.fused()) {  // normalise and pool in one pass; the normalised tensor is only made on request
+      AX_TRY(launch_lrn_pool_fwd(s.act, s.pool_out, s.slot, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, c.lrn_n,
+                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, st));
+      h = s.pool_out;
+      continue;
+    }
     if (s.lrn) {
       AX_TRY(launch_lrn_fwd(s.act, s.lrn_out, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k, c.lrn_alpha, c.lrn_beta, st));
       h = s.lrn_out;
@@ -339,20 +350,25 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
   for (int i = kStages - 1; i >= 0; --i) {
     Stage& s = n->st[i];
     ProfContext pc0(s.lab[0]);
-    if (s.pool) {
+    bool bias_done = false;
+    if (s.fused()) {  // pool adjoint, normalisation adjoint, ReLU gate and bias gradient in one pass
+      AX_TRY(launch_pool_lrn_bwd(s.act, s.d_out, s.slot, s.dact, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, c.lrn_n,
+                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, 1, n->grads + s.b_off, n->colsum_ws, st));
+      bias_done = true;
+    } else if (s.pool) {
       if (s.lrn)
         AX_TRY(launch_pool_bwd(s.d_out, s.slot, nullptr, s.d_lrn, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
       else
         AX_TRY(launch_pool_bwd(s.d_out, s.slot, s.act, s.dact, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
     }
-    if (s.lrn)
+    if (s.lrn && !s.fused())
       AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
                             c.lrn_alpha, c.lrn_beta, 1, st));
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
       AX_TRY(launch_conv_bwd_weight(s.g, x, s.dact, n->grads + s.w_off, s.dwrun, n->gemm_ws, st));
-      AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
+      if (!bias_done) AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
     }
     if (i > 0) {
       ProfContext pc(s.lab[3]);
@@ -649,7 +665,11 @@ int alexnet_get_tensor(alexnet_t* n, int32_t kind, int32_t layer, void* d_out, v
   switch (kind) {
     case ALEXNET_T_CONV_ACT: return launch_nhwc_to_nchw(s.act, (float*)d_out, s.g.B, s.g.Cout, s.g.Ho, s.g.Wo, st);
     case ALEXNET_T_CONV_DACT: return launch_nhwc_to_nchw(s.dact, (float*)d_out, s.g.B, s.g.Cout, s.g.Ho, s.g.Wo, st);
-    case ALEXNET_T_LRN: return launch_nhwc_to_nchw(s.lrn_out, (float*)d_out, s.g.B, s.g.Cout, s.g.Ho, s.g.Wo, st);
+    case ALEXNET_T_LRN:
+      if (s.fused())  // the training path does not store it: normalise the stored activations now
+        AX_TRY(launch_lrn_fwd(s.act, s.lrn_out, s.g.P(), s.g.Cout, n->cfg.lrn_n, n->cfg.lrn_k, n->cfg.lrn_alpha,
+                              n->cfg.lrn_beta, st));
+      return launch_nhwc_to_nchw(s.lrn_out, (float*)d_out, s.g.B, s.g.Cout, s.g.Ho, s.g.Wo, st);
     case ALEXNET_T_POOL: return launch_nhwc_to_nchw(s.pool_out, (float*)d_out, s.g.B, s.g.Cout, s.Hp, s.Wp, st);
     case ALEXNET_T_ARGMAX:
       return launch_pool_argmax_canonical(s.slot, (int32_t*)d_out, s.g.B, s.g.Cout, s.Hp, s.Wp, s.g.Wo, st);

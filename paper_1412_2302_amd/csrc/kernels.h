@@ -62,6 +62,18 @@ int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k,
 // da = (dL/db through the normalisation) gated by a > 0 when relu_gate is set
 int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int C, int n, float k, float alpha,
                    float beta, int relu_gate, hipStream_t st);
+// Normalisation fused with the 3x3 stride-2 max-pool after it (forward: the normalised tensor is never
+// stored) and with that pool's adjoint before it (backward: dy is the pooled gradient).  Usable when
+// lrn_pool_fused_ok(); colsum_out (may be null) receives the per-channel sums of da, `part` is scratch of
+// lrn_part_floats(C) floats.
+bool lrn_pool_fused_ok(const float* a, const float* y, const float* dy, const float* da, const uint8_t* slot, int C,
+                       int n);
+size_t lrn_part_floats(int C);
+int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo, int n,
+                        float k, float alpha, float beta, hipStream_t st);
+int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, float* da, int N, int H, int W, int C,
+                        int Ho, int Wo, int n, float k, float alpha, float beta, int relu_gate, float* colsum_out,
+                        float* part, hipStream_t st);
 int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo,
                     hipStream_t st);
 // dx[n][y][x][c] = sum of dy over the windows whose winning tap is (y,x); gated by gate > 0 when gate != null

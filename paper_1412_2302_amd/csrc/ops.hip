@@ -128,13 +128,23 @@ int launch_nhwc_to_nchw(const float* src, float* dst, int N, int C, int H, int W
 
 // ------------------------------------------------------------------- LRN ---
 // b_i = a_i * s_i^-beta, s_i = k + alpha * sum_{j in [i-n/2, i+n/2] clipped} a_j^2
+// s^-beta.  The AlexNet exponent 3/4 is two square roots, taken with the hardware's one-instruction
+// v_rsq_f32 / v_sqrt_f32 (about 1 ulp each; s >= k is a normal number): the correctly rounded library
+// routines cost some forty instructions per call, which made these kernels ALU-bound.
 __device__ __forceinline__ float neg_pow(float s, float beta) {
-  // s^-beta; the AlexNet exponent 3/4 is two square roots
   if (beta == 0.75f) {
-    const float r = 1.0f / sqrtf(s);
-    return r * sqrtf(r);
+    const float r = __builtin_amdgcn_rsqf(s);
+    return r * __builtin_amdgcn_sqrtf(r);
   }
   return powf(s, -beta);
+}
+// s^-beta / s
+__device__ __forceinline__ float neg_pow_over_s(float s, float p, float beta) {
+  if (beta == 0.75f) {
+    const float r = __builtin_amdgcn_rsqf(s);
+    return p * (r * r);
+  }
+  return p / s;
 }
 
 __global__ void lrn_fwd_kernel(const float* __restrict__ a, float* __restrict__ b, size_t total, int C, int half,
@@ -182,12 +192,8 @@ __global__ void lrn_bwd_kernel(const float* __restrict__ a, const float* __restr
 // tensor is read from and written to HBM exactly once with 16-byte accesses.
 constexpr int kLrnMaxHalf = 4;
 constexpr int kLrnPad = 4;  // zeros on both sides of an LDS row; keeps 16-byte alignment
-__device__ __forceinline__ float4 lrn_window_sum(const float* row, int c, int half) {
-  // sums of row[c+j-half .. c+j+half] for j = 0..3, each added up directly
-  float v[12];
-  *reinterpret_cast<float4*>(v) = *reinterpret_cast<const float4*>(row + c - 4);
-  *reinterpret_cast<float4*>(v + 4) = *reinterpret_cast<const float4*>(row + c);
-  *reinterpret_cast<float4*>(v + 8) = *reinterpret_cast<const float4*>(row + c + 4);
+// sums of v[4+j-half .. 4+j+half] for j = 0..3, each added up directly (v = values of channels c-4 .. c+7)
+__device__ __forceinline__ float4 lrn_window_sum_regs(const float* v, int half) {
   float s[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -199,17 +205,53 @@ __device__ __forceinline__ float4 lrn_window_sum(const float* row, int c, int ha
   }
   return make_float4(s[0], s[1], s[2], s[3]);
 }
+__device__ __forceinline__ float4 lrn_window_sum(const float* row, int c, int half) {
+  float v[12];
+  *reinterpret_cast<float4*>(v) = *reinterpret_cast<const float4*>(row + c - 4);
+  *reinterpret_cast<float4*>(v + 4) = *reinterpret_cast<const float4*>(row + c);
+  *reinterpret_cast<float4*>(v + 8) = *reinterpret_cast<const float4*>(row + c + 4);
+  return lrn_window_sum_regs(v, half);
+}
 
-template <bool BWD>
+// Where the gradient of the normalised activations comes from: a tensor, or (dy != null) the adjoint of the
+// 3x3 stride-2 max-pool that follows, gathered on the fly from the pooled gradient and the winning taps.
+struct PoolGather {
+  const float* dy;       // [N][Ho][Wo][C]
+  const uint8_t* slot;   // winning tap 0..8 of each pooled element
+  int H, W, Ho, Wo;
+  FastDiv d_w, d_h;
+};
+__device__ __forceinline__ float4 pool_gather4(const PoolGather& pg, long pix, int c, int C) {
+  const uint32_t q = fdiv((uint32_t)pix, pg.d_w);  // pix < 2^31: a tensor is smaller than 2 GiB
+  const int x = (int)((uint32_t)pix - q * (uint32_t)pg.W);
+  const uint32_t n = fdiv(q, pg.d_h);
+  const int y = (int)(q - n * (uint32_t)pg.H);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int yo_lo = y >= 2 ? (y - 1) / 2 : 0, yo_hi = min(y / 2, pg.Ho - 1);
+  const int xo_lo = x >= 2 ? (x - 1) / 2 : 0, xo_hi = min(x / 2, pg.Wo - 1);
+  for (int yo = yo_lo; yo <= yo_hi; ++yo)
+    for (int xo = xo_lo; xo <= xo_hi; ++xo) {
+      const uint32_t o = ((n * (uint32_t)pg.Ho + (uint32_t)yo) * (uint32_t)pg.Wo + (uint32_t)xo) * (uint32_t)C + c;
+      const uint32_t want = (uint32_t)((y - 2 * yo) * 3 + (x - 2 * xo));
+      const uint32_t s4 = *reinterpret_cast<const uint32_t*>(pg.slot + o);
+      const float4 d = *reinterpret_cast<const float4*>(pg.dy + o);
+      acc.x += (s4 & 0xffu) == want ? d.x : 0.f;
+      acc.y += ((s4 >> 8) & 0xffu) == want ? d.y : 0.f;
+      acc.z += ((s4 >> 16) & 0xffu) == want ? d.z : 0.f;
+      acc.w += (s4 >> 24) == want ? d.w : 0.f;
+    }
+  return acc;
+}
+
+template <bool BWD, bool GATHER>
 __global__ void __launch_bounds__(256)
 lrn_vec_kernel(const float* __restrict__ a, const float* __restrict__ db, float* __restrict__ out, long pixels, int C,
-               int half, int PB, float k, float alpha, float beta, int relu_gate) {
+               int half, int PB, float k, float alpha, float beta, int relu_gate, PoolGather pg,
+               float* __restrict__ part) {
   extern __shared__ __attribute__((aligned(16))) float sh[];  // [2][PB][kLrnPad + C + kLrnPad]
   const int q = C >> 2;                                        // lanes per pixel
   const int ld = C + 2 * kLrnPad;
   const int pl = threadIdx.x / q, cq = threadIdx.x - pl * q;
-  const long pix = (long)blockIdx.x * PB + pl;
-  const bool on = pl < PB && pix < pixels;
   float* sq = sh + (size_t)pl * ld + kLrnPad;
   float* tt = sh + (size_t)PB * ld + (size_t)pl * ld + kLrnPad;
   if (pl < PB && cq < 2) {  // zero the pads of this pixel's two rows
@@ -218,43 +260,136 @@ lrn_vec_kernel(const float* __restrict__ a, const float* __restrict__ db, float*
     *reinterpret_cast<float4*>(tt + o) = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   const int c = cq * 4;
-  float4 av = make_float4(0.f, 0.f, 0.f, 0.f), dv = av;
-  if (on) {
-    av = *reinterpret_cast<const float4*>(a + pix * C + c);
-    if (BWD) dv = *reinterpret_cast<const float4*>(db + pix * C + c);
-    *reinterpret_cast<float4*>(sq + c) = make_float4(av.x * av.x, av.y * av.y, av.z * av.z, av.w * av.w);
-  }
-  __syncthreads();
-  float4 p = av;  // s^-beta per channel
-  float4 sv = av;
-  if (on) {
-    const float4 w = lrn_window_sum(sq, c, half);
-    sv = make_float4(k + alpha * w.x, k + alpha * w.y, k + alpha * w.z, k + alpha * w.w);
-    p = make_float4(neg_pow(sv.x, beta), neg_pow(sv.y, beta), neg_pow(sv.z, beta), neg_pow(sv.w, beta));
-  }
-  if (!BWD) {
-    if (on) *reinterpret_cast<float4*>(out + pix * C + c) = make_float4(av.x * p.x, av.y * p.y, av.z * p.z, av.w * p.w);
-    return;
-  }
-  if (on)
-    *reinterpret_cast<float4*>(tt + c) = make_float4(dv.x * av.x * p.x / sv.x, dv.y * av.y * p.y / sv.y,
-                                                     dv.z * av.z * p.z / sv.z, dv.w * av.w * p.w / sv.w);
-  __syncthreads();
-  if (on) {
-    const float4 acc = lrn_window_sum(tt, c, half);
-    const float f = 2.f * alpha * beta;
-    float4 r = make_float4(dv.x * p.x - f * av.x * acc.x, dv.y * p.y - f * av.y * acc.y, dv.z * p.z - f * av.z * acc.z,
-                           dv.w * p.w - f * av.w * acc.w);
-    if (relu_gate) {
-      r.x = av.x > 0.f ? r.x : 0.f;
-      r.y = av.y > 0.f ? r.y : 0.f;
-      r.z = av.z > 0.f ? r.z : 0.f;
-      r.w = av.w > 0.f ? r.w : 0.f;
+  float4 colsum = make_float4(0.f, 0.f, 0.f, 0.f);  // of this lane's outputs over all its pixels
+  // every workgroup makes the same number of trips, so the barriers inside are uniform
+  for (long first = (long)blockIdx.x * PB; first < pixels; first += (long)gridDim.x * PB) {
+    const long pix = first + pl;
+    const bool on = pl < PB && pix < pixels;
+    float4 av = make_float4(0.f, 0.f, 0.f, 0.f), dv = av;
+    if (on) {
+      av = *reinterpret_cast<const float4*>(a + pix * C + c);
+      if (BWD) dv = GATHER ? pool_gather4(pg, pix, c, C) : *reinterpret_cast<const float4*>(db + pix * C + c);
+      *reinterpret_cast<float4*>(sq + c) = make_float4(av.x * av.x, av.y * av.y, av.z * av.z, av.w * av.w);
     }
-    *reinterpret_cast<float4*>(out + pix * C + c) = r;
+    __syncthreads();
+    float4 p = av;  // s^-beta per channel
+    float4 sv = av;
+    if (on) {
+      const float4 w = lrn_window_sum(sq, c, half);
+      sv = make_float4(k + alpha * w.x, k + alpha * w.y, k + alpha * w.z, k + alpha * w.w);
+      p = make_float4(neg_pow(sv.x, beta), neg_pow(sv.y, beta), neg_pow(sv.z, beta), neg_pow(sv.w, beta));
+    }
+    if (!BWD) {
+      if (on)
+        *reinterpret_cast<float4*>(out + pix * C + c) = make_float4(av.x * p.x, av.y * p.y, av.z * p.z, av.w * p.w);
+      __syncthreads();  // the next trip overwrites the squares
+      continue;
+    }
+    if (on)
+      *reinterpret_cast<float4*>(tt + c) =
+          make_float4(dv.x * av.x * neg_pow_over_s(sv.x, p.x, beta), dv.y * av.y * neg_pow_over_s(sv.y, p.y, beta),
+                      dv.z * av.z * neg_pow_over_s(sv.z, p.z, beta), dv.w * av.w * neg_pow_over_s(sv.w, p.w, beta));
+    __syncthreads();
+    if (on) {
+      const float4 acc = lrn_window_sum(tt, c, half);
+      const float f = 2.f * alpha * beta;
+      float4 r = make_float4(dv.x * p.x - f * av.x * acc.x, dv.y * p.y - f * av.y * acc.y,
+                             dv.z * p.z - f * av.z * acc.z, dv.w * p.w - f * av.w * acc.w);
+      if (relu_gate) {
+        r.x = av.x > 0.f ? r.x : 0.f;
+        r.y = av.y > 0.f ? r.y : 0.f;
+        r.z = av.z > 0.f ? r.z : 0.f;
+        r.w = av.w > 0.f ? r.w : 0.f;
+      }
+      *reinterpret_cast<float4*>(out + pix * C + c) = r;
+      colsum.x += r.x;
+      colsum.y += r.y;
+      colsum.z += r.z;
+      colsum.w += r.w;
+    }
+    // the next trip writes the squares, which were last read before the barrier above, and writes the
+    // products only after its own first barrier, when every lane is done with this trip's
+  }
+  if (BWD && part) {  // part[workgroup][channel] = sum of this workgroup's outputs, in a fixed order
+    __syncthreads();
+    if (pl < PB) *reinterpret_cast<float4*>(sh + (size_t)pl * C + c) = colsum;
+    __syncthreads();
+    if (pl == 0) {
+      float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int r = 0; r < PB; ++r) {
+        const float4 v = *reinterpret_cast<const float4*>(sh + (size_t)r * C + c);
+        t.x += v.x;
+        t.y += v.y;
+        t.z += v.z;
+        t.w += v.w;
+      }
+      *reinterpret_cast<float4*>(part + (size_t)blockIdx.x * C + c) = t;
+    }
   }
 }
 
+// Normalisation and the max-pool that follows it in one pass (C % 4 == 0).  A workgroup owns PH x PW pooled
+// pixels of one picture: it normalises the (2PH+1) x (2PW+1) input pixels under them into LDS (a lane takes
+// four channels of a pixel and reads that pixel's channels c-4 .. c+7 itself), then pools out of LDS.  The
+// normalised tensor never goes to memory.  Same arithmetic and tie-break (first maximum in row-major tap
+// order) as the separate kernels.
+__global__ void __launch_bounds__(256)
+lrn_pool_fwd_kernel(const float* __restrict__ a, float* __restrict__ y, uint8_t* __restrict__ slot, int H, int W,
+                    int C, int Ho, int Wo, int PH, int PW, int tiles_y, int tiles_x, int half, float k, float alpha,
+                    float beta) {
+  extern __shared__ __attribute__((aligned(16))) float bbuf[];  // [(2PH+1)*(2PW+1)][C]
+  const int q = C >> 2;
+  int t = blockIdx.x;
+  const int tx = t % tiles_x;
+  t /= tiles_x;
+  const int ty = t % tiles_y;
+  const int n = t / tiles_y;
+  const int py0 = ty * PH, px0 = tx * PW;
+  const int ph = min(PH, Ho - py0), pw = min(PW, Wo - px0);
+  const int ih = 2 * ph + 1, iw = 2 * pw + 1;  // always inside the picture: 2*Ho <= H-1
+  const float* src = a + (((size_t)n * H + 2 * py0) * W + 2 * px0) * C;
+  for (int item = threadIdx.x; item < ih * iw * q; item += 256) {
+    const int pxl = item / q, c = (item - pxl * q) * 4;
+    const int ly = pxl / iw, lx = pxl - ly * iw;
+    const float* px = src + ((size_t)ly * W + lx) * C + c;
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 m = *reinterpret_cast<const float4*>(px);
+    const float4 l = c >= 4 ? *reinterpret_cast<const float4*>(px - 4) : z;
+    const float4 h = c + 4 < C ? *reinterpret_cast<const float4*>(px + 4) : z;
+    float v[12] = {l.x * l.x, l.y * l.y, l.z * l.z, l.w * l.w, m.x * m.x, m.y * m.y,
+                   m.z * m.z, m.w * m.w, h.x * h.x, h.y * h.y, h.z * h.z, h.w * h.w};
+    const float4 w = lrn_window_sum_regs(v, half);
+    *reinterpret_cast<float4*>(bbuf + (size_t)pxl * C + c) =
+        make_float4(m.x * neg_pow(k + alpha * w.x, beta), m.y * neg_pow(k + alpha * w.y, beta),
+                    m.z * neg_pow(k + alpha * w.z, beta), m.w * neg_pow(k + alpha * w.w, beta));
+  }
+  __syncthreads();
+  for (int item = threadIdx.x; item < ph * pw * q; item += 256) {
+    const int o = item / q, c = (item - o * q) * 4;
+    const int oy = o / pw, ox = o - oy * pw;
+    const float* win = bbuf + ((size_t)(2 * oy) * iw + 2 * ox) * C + c;
+    float4 best = *reinterpret_cast<const float4*>(win);
+    uint32_t bs = 0;
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+      for (int s2 = 0; s2 < 3; ++s2) {
+        if (r == 0 && s2 == 0) continue;
+        const float4 b = *reinterpret_cast<const float4*>(win + ((size_t)r * iw + s2) * C);
+        const uint32_t tap = (uint32_t)(r * 3 + s2);
+        if (b.x > best.x) { best.x = b.x; bs = (bs & 0xffffff00u) | tap; }
+        if (b.y > best.y) { best.y = b.y; bs = (bs & 0xffff00ffu) | (tap << 8); }
+        if (b.z > best.z) { best.z = b.z; bs = (bs & 0xff00ffffu) | (tap << 16); }
+        if (b.w > best.w) { best.w = b.w; bs = (bs & 0x00ffffffu) | (tap << 24); }
+      }
+    const size_t e = (((size_t)n * Ho + py0 + oy) * Wo + px0 + ox) * C + c;
+    *reinterpret_cast<float4*>(y + e) = best;
+    *reinterpret_cast<uint32_t*>(slot + e) = bs;
+  }
+}
+
+constexpr int kLrnMaxBlocks = 2048;  // workgroups of the vector kernels (= rows of their column-sum partials)
+static int lrn_grid(long pixels, int PB) { return (int)std::min<long>(ceil_div(pixels, PB), kLrnMaxBlocks); }
 static bool lrn_vec_ok(const void* p0, const void* p1, const void* p2, int C, int half) {
   return C % 4 == 0 && C <= 1024 && half <= kLrnMaxHalf && aligned16(p0) && aligned16(p1) && aligned16(p2);
 }
@@ -268,8 +403,8 @@ int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k,
   if (lrn_vec_ok(a, b, b, C, half)) {
     const int PB = 256 / (C / 4);
     const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
-    hipLaunchKernelGGL((lrn_vec_kernel<false>), dim3(ceil_div(pixels, PB)), dim3(256), lds, st, a, nullptr, b, pixels, C,
-                       half, PB, k, alpha, beta, 0);
+    hipLaunchKernelGGL((lrn_vec_kernel<false, false>), dim3(lrn_grid(pixels, PB)), dim3(256), lds, st, a, nullptr, b,
+                       pixels, C, half, PB, k, alpha, beta, 0, PoolGather{}, nullptr);
   } else {
     hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, b, total, C, half, k, alpha,
                        beta);
@@ -286,13 +421,90 @@ int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int 
   if (lrn_vec_ok(a, db, da, C, half)) {
     const int PB = 256 / (C / 4);
     const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
-    hipLaunchKernelGGL((lrn_vec_kernel<true>), dim3(ceil_div(pixels, PB)), dim3(256), lds, st, a, db, da, pixels, C,
-                       half, PB, k, alpha, beta, relu_gate);
+    hipLaunchKernelGGL((lrn_vec_kernel<true, false>), dim3(lrn_grid(pixels, PB)), dim3(256), lds, st, a, db, da,
+                       pixels, C, half, PB, k, alpha, beta, relu_gate, PoolGather{}, nullptr);
   } else {
     hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, db, da, total, C, half, k,
                        alpha, beta, relu_gate);
   }
   AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// out[c..c+3] = sum over the rows of part[nparts][cols] (cols % 4 == 0): one workgroup per four columns,
+// 256 interleaved row sets added up by a fixed tree
+__global__ void __launch_bounds__(256)
+colsum_finish_kernel(const float* __restrict__ part, int nparts, int cols, float* __restrict__ out) {
+  __shared__ float4 sh[256];
+  const int c = blockIdx.x * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p = threadIdx.x; p < nparts; p += 256) {
+    const float4 v = *reinterpret_cast<const float4*>(part + (size_t)p * cols + c);
+    s.x += v.x;
+    s.y += v.y;
+    s.z += v.z;
+    s.w += v.w;
+  }
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      const float4 o = sh[threadIdx.x + w];
+      float4& m = sh[threadIdx.x];
+      m.x += o.x;
+      m.y += o.y;
+      m.z += o.z;
+      m.w += o.w;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *reinterpret_cast<float4*>(out + c) = sh[0];
+}
+
+bool lrn_pool_fused_ok(const float* a, const float* y, const float* dy, const float* da, const uint8_t* slot, int C,
+                       int n) {
+  // the smallest pooled tile (2 x 2) needs 25 normalised pixels in LDS
+  return lrn_vec_ok(a, y, dy ? dy : a, C, n / 2) && C <= 512 && aligned16(da ? da : a) && ((uintptr_t)slot & 3) == 0;
+}
+size_t lrn_part_floats(int C) { return (size_t)kLrnMaxBlocks * C; }
+
+int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo, int n,
+                        float k, float alpha, float beta, hipStream_t st) {
+  const size_t total = (size_t)N * Ho * Wo * C;
+  if (!total) return ALEXNET_OK;
+  // pooled tile edge: the normalised input pixels under a tile fill about 32 KiB of LDS
+  int pt = 2;
+  while ((size_t)(2 * pt + 3) * (2 * pt + 3) * C * 4 <= 32768 && pt < 8) ++pt;
+  const int PH = std::min(pt, Ho), PW = std::min(pt, Wo);
+  const int tiles_y = ceil_div(Ho, PH), tiles_x = ceil_div(Wo, PW);
+  const size_t lds = (size_t)(2 * PH + 1) * (2 * PW + 1) * C * sizeof(float);
+  KernelScope ks("lrn_pool_fwd", 0, (double)N * H * W * C * 4.0 + (double)total * 5.0, st);
+  hipLaunchKernelGGL(lrn_pool_fwd_kernel, dim3((unsigned)(N * tiles_y * tiles_x)), dim3(256), lds, st, a, y, slot, H, W,
+                     C, Ho, Wo, PH, PW, tiles_y, tiles_x, n / 2, k, alpha, beta);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, float* da, int N, int H, int W, int C,
+                        int Ho, int Wo, int n, float k, float alpha, float beta, int relu_gate, float* colsum_out,
+                        float* part, hipStream_t st) {
+  const long pixels = (long)N * H * W;
+  if (!pixels) return ALEXNET_OK;
+  const int PB = 256 / (C / 4);
+  const int blocks = lrn_grid(pixels, PB);
+  {
+    KernelScope ks("pool_lrn_bwd", 0, (double)pixels * C * 8.0 + (double)N * Ho * Wo * C * 5.0, st);
+    const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
+    const PoolGather pg{dy, slot, H, W, Ho, Wo, make_fastdiv((uint32_t)W), make_fastdiv((uint32_t)H)};
+    hipLaunchKernelGGL((lrn_vec_kernel<true, true>), dim3(blocks), dim3(256), lds, st, a, nullptr, da, pixels, C, n / 2,
+                       PB, k, alpha, beta, relu_gate, pg, colsum_out ? part : nullptr);
+    AX_LAUNCH_CHECK();
+  }
+  if (colsum_out) {
+    KernelScope ks("colsum_finish", 0, (double)blocks * C * 4.0, st);
+    hipLaunchKernelGGL(colsum_finish_kernel, dim3(C / 4), dim3(256), 0, st, part, blocks, C, colsum_out);
+    AX_LAUNCH_CHECK();
+  }
   return ALEXNET_OK;
 }
 
