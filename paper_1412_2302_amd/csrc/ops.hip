@@ -221,25 +221,43 @@ struct PoolGather {
   int H, W, Ho, Wo;
   FastDiv d_w, d_h;
 };
-__device__ __forceinline__ float4 pool_gather4(const PoolGather& pg, long pix, int c, int C) {
+// The (at most four) pooled windows over an input pixel, as loaded: the reduction is a separate step so
+// that the loads can be issued a trip ahead of their use.
+struct PoolTaps {
+  uint32_t s4[4];    // winning taps of four channels
+  float4 d[4];       // pooled gradient of four channels
+  uint32_t want[4];  // this pixel's tap number in that window; 9 (never a winner) for a window that does not exist
+};
+__device__ __forceinline__ void pool_taps_fetch(const PoolGather& pg, long pix, int c, int C, PoolTaps& t) {
   const uint32_t q = fdiv((uint32_t)pix, pg.d_w);  // pix < 2^31: a tensor is smaller than 2 GiB
   const int x = (int)((uint32_t)pix - q * (uint32_t)pg.W);
   const uint32_t n = fdiv(q, pg.d_h);
   const int y = (int)(q - n * (uint32_t)pg.H);
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   const int yo_lo = y >= 2 ? (y - 1) / 2 : 0, yo_hi = min(y / 2, pg.Ho - 1);
   const int xo_lo = x >= 2 ? (x - 1) / 2 : 0, xo_hi = min(x / 2, pg.Wo - 1);
-  for (int yo = yo_lo; yo <= yo_hi; ++yo)
-    for (int xo = xo_lo; xo <= xo_hi; ++xo) {
+#pragma unroll
+  for (int wy = 0; wy < 2; ++wy)
+#pragma unroll
+    for (int wx = 0; wx < 2; ++wx) {
+      const int yo = min(yo_lo + wy, yo_hi), xo = min(xo_lo + wx, xo_hi);
+      // a pixel in a last row or column that no window covers has lo > hi: the clamped address is still inside
+      const bool valid = yo_lo + wy <= yo_hi && xo_lo + wx <= xo_hi;
       const uint32_t o = ((n * (uint32_t)pg.Ho + (uint32_t)yo) * (uint32_t)pg.Wo + (uint32_t)xo) * (uint32_t)C + c;
-      const uint32_t want = (uint32_t)((y - 2 * yo) * 3 + (x - 2 * xo));
-      const uint32_t s4 = *reinterpret_cast<const uint32_t*>(pg.slot + o);
-      const float4 d = *reinterpret_cast<const float4*>(pg.dy + o);
-      acc.x += (s4 & 0xffu) == want ? d.x : 0.f;
-      acc.y += ((s4 >> 8) & 0xffu) == want ? d.y : 0.f;
-      acc.z += ((s4 >> 16) & 0xffu) == want ? d.z : 0.f;
-      acc.w += (s4 >> 24) == want ? d.w : 0.f;
+      t.want[wy * 2 + wx] = valid ? (uint32_t)((y - 2 * yo) * 3 + (x - 2 * xo)) : 9u;
+      t.s4[wy * 2 + wx] = *reinterpret_cast<const uint32_t*>(pg.slot + o);
+      t.d[wy * 2 + wx] = *reinterpret_cast<const float4*>(pg.dy + o);
     }
+}
+__device__ __forceinline__ float4 pool_taps_reduce(const PoolTaps& t) {
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const uint32_t s4 = t.s4[w], want = t.want[w];
+    acc.x += (s4 & 0xffu) == want ? t.d[w].x : 0.f;
+    acc.y += ((s4 >> 8) & 0xffu) == want ? t.d[w].y : 0.f;
+    acc.z += ((s4 >> 16) & 0xffu) == want ? t.d[w].z : 0.f;
+    acc.w += (s4 >> 24) == want ? t.d[w].w : 0.f;
+  }
   return acc;
 }
 
@@ -261,15 +279,33 @@ lrn_vec_kernel(const float* __restrict__ a, const float* __restrict__ db, float*
   }
   const int c = cq * 4;
   float4 colsum = make_float4(0.f, 0.f, 0.f, 0.f);  // of this lane's outputs over all its pixels
-  // every workgroup makes the same number of trips, so the barriers inside are uniform
-  for (long first = (long)blockIdx.x * PB; first < pixels; first += (long)gridDim.x * PB) {
+  // every workgroup makes the same number of trips, so the barriers inside are uniform; the loads of a
+  // trip are issued during the trip before
+  const long stride = (long)gridDim.x * PB;
+  float4 nav = make_float4(0.f, 0.f, 0.f, 0.f), ndv = nav;
+  PoolTaps taps;
+  {
+    const long pix = (long)blockIdx.x * PB + pl;
+    if (pl < PB && pix < pixels) {
+      nav = *reinterpret_cast<const float4*>(a + pix * C + c);
+      if (BWD && GATHER) pool_taps_fetch(pg, pix, c, C, taps);
+      if (BWD && !GATHER) ndv = *reinterpret_cast<const float4*>(db + pix * C + c);
+    }
+  }
+  for (long first = (long)blockIdx.x * PB; first < pixels; first += stride) {
     const long pix = first + pl;
     const bool on = pl < PB && pix < pixels;
-    float4 av = make_float4(0.f, 0.f, 0.f, 0.f), dv = av;
-    if (on) {
-      av = *reinterpret_cast<const float4*>(a + pix * C + c);
-      if (BWD) dv = GATHER ? pool_gather4(pg, pix, c, C) : *reinterpret_cast<const float4*>(db + pix * C + c);
-      *reinterpret_cast<float4*>(sq + c) = make_float4(av.x * av.x, av.y * av.y, av.z * av.z, av.w * av.w);
+    const float4 av = nav;
+    float4 dv = ndv;
+    if (BWD && GATHER && on) dv = pool_taps_reduce(taps);
+    if (on) *reinterpret_cast<float4*>(sq + c) = make_float4(av.x * av.x, av.y * av.y, av.z * av.z, av.w * av.w);
+    {
+      const long npix = pix + stride;
+      if (pl < PB && npix < pixels) {
+        nav = *reinterpret_cast<const float4*>(a + npix * C + c);
+        if (BWD && GATHER) pool_taps_fetch(pg, npix, c, C, taps);
+        if (BWD && !GATHER) ndv = *reinterpret_cast<const float4*>(db + npix * C + c);
+      }
     }
     __syncthreads();
     float4 p = av;  // s^-beta per channel
@@ -348,25 +384,54 @@ lrn_pool_fwd_kernel(const float* __restrict__ a, float* __restrict__ y, uint8_t*
   const int ph = min(PH, Ho - py0), pw = min(PW, Wo - px0);
   const int ih = 2 * ph + 1, iw = 2 * pw + 1;  // always inside the picture: 2*Ho <= H-1
   const float* src = a + (((size_t)n * H + 2 * py0) * W + 2 * px0) * C;
-  for (int item = threadIdx.x; item < ih * iw * q; item += 256) {
-    const int pxl = item / q, c = (item - pxl * q) * 4;
-    const int ly = pxl / iw, lx = pxl - ly * iw;
-    const float* px = src + ((size_t)ly * W + lx) * C + c;
-    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-    const float4 m = *reinterpret_cast<const float4*>(px);
-    const float4 l = c >= 4 ? *reinterpret_cast<const float4*>(px - 4) : z;
-    const float4 h = c + 4 < C ? *reinterpret_cast<const float4*>(px + 4) : z;
-    float v[12] = {l.x * l.x, l.y * l.y, l.z * l.z, l.w * l.w, m.x * m.x, m.y * m.y,
-                   m.z * m.z, m.w * m.w, h.x * h.x, h.y * h.y, h.z * h.z, h.w * h.w};
-    const float4 w = lrn_window_sum_regs(v, half);
-    *reinterpret_cast<float4*>(bbuf + (size_t)pxl * C + c) =
-        make_float4(m.x * neg_pow(k + alpha * w.x, beta), m.y * neg_pow(k + alpha * w.y, beta),
-                    m.z * neg_pow(k + alpha * w.z, beta), m.w * neg_pow(k + alpha * w.w, beta));
+  // a lane keeps its four channels and walks over every PB-th pixel; coordinates advance without divisions
+  const int PB = 256 / q, pl = threadIdx.x / q, c = (threadIdx.x - pl * q) * 4;
+  const bool lane_on = pl < PB;
+  {
+    // four pixels per trip with all twelve loads issued before the first use: one memory latency per
+    // four pixels instead of one per pixel (a pixel past the end re-reads the tile's first pixel)
+    constexpr int U = 2;
+    const int dq = PB / iw, dr = PB - dq * iw, np = ih * iw;
+    int ly = pl / iw, lx = pl - ly * iw;
+    for (int pxl0 = pl; lane_on && pxl0 < np; pxl0 += U * PB) {
+      float4 m[U], l[U], h[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const bool valid = pxl0 + u * PB < np;
+        const float* px = src + (valid ? ((size_t)ly * W + lx) * C : 0) + c;
+        m[u] = *reinterpret_cast<const float4*>(px);
+        l[u] = h[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c >= 4) l[u] = *reinterpret_cast<const float4*>(px - 4);
+        if (c + 4 < C) h[u] = *reinterpret_cast<const float4*>(px + 4);
+        ly += dq;
+        lx += dr;
+        if (lx >= iw) {
+          lx -= iw;
+          ++ly;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int pxl = pxl0 + u * PB;
+        const float v[12] = {l[u].x * l[u].x, l[u].y * l[u].y, l[u].z * l[u].z, l[u].w * l[u].w,
+                             m[u].x * m[u].x, m[u].y * m[u].y, m[u].z * m[u].z, m[u].w * m[u].w,
+                             h[u].x * h[u].x, h[u].y * h[u].y, h[u].z * h[u].z, h[u].w * h[u].w};
+        const float4 w = lrn_window_sum_regs(v, half);
+        if (pxl < np)
+          *reinterpret_cast<float4*>(bbuf + (size_t)pxl * C + c) = make_float4(
+              m[u].x * neg_pow(k + alpha * w.x, beta), m[u].y * neg_pow(k + alpha * w.y, beta),
+              m[u].z * neg_pow(k + alpha * w.z, beta), m[u].w * neg_pow(k + alpha * w.w, beta));
+      }
+    }
   }
   __syncthreads();
-  for (int item = threadIdx.x; item < ph * pw * q; item += 256) {
-    const int o = item / q, c = (item - o * q) * 4;
-    const int oy = o / pw, ox = o - oy * pw;
+  const int dq = PB / pw, dr = PB - dq * pw;
+  int oy = pl / pw, ox = pl - oy * pw;
+  for (int o = pl; lane_on && o < ph * pw; o += PB, oy += dq, ox += dr) {
+    if (ox >= pw) {
+      ox -= pw;
+      ++oy;
+    }
     const float* win = bbuf + ((size_t)(2 * oy) * iw + 2 * ox) * C + c;
     float4 best = *reinterpret_cast<const float4*>(win);
     uint32_t bs = 0;
@@ -472,9 +537,9 @@ int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, i
                         float k, float alpha, float beta, hipStream_t st) {
   const size_t total = (size_t)N * Ho * Wo * C;
   if (!total) return ALEXNET_OK;
-  // pooled tile edge: the normalised input pixels under a tile fill about 32 KiB of LDS
+  // pooled tile edge: the normalised input pixels under a tile fill at most 20 KiB of LDS (25 pixels at least)
   int pt = 2;
-  while ((size_t)(2 * pt + 3) * (2 * pt + 3) * C * 4 <= 32768 && pt < 8) ++pt;
+  while ((size_t)(2 * pt + 3) * (2 * pt + 3) * C * 4 <= 20480 && pt < 8) ++pt;
   const int PH = std::min(pt, Ho), PW = std::min(pt, Wo);
   const int tiles_y = ceil_div(Ho, PH), tiles_x = ceil_div(Wo, PW);
   const size_t lds = (size_t)(2 * PH + 1) * (2 * PW + 1) * C * sizeof(float);
