@@ -738,8 +738,20 @@ __device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T>& fa, Frags<BL, T
   }
 }
 
+// Workgroups the compiler must fit on a CU.  A forward pass over a short reduction (the first layer: 25
+// k-tiles per output tile) spends a good part of a tile's life in its prologue and epilogue, and co-resident
+// workgroups that started together stay in step; a third workgroup per CU fills those gaps.
+template <class T, class Epi>
+struct MinBlocks {
+  static constexpr int value = 1;
+};
+template <int BK, int WM, int WN>
+struct MinBlocks<Tile<128, 96, BK, WM, WN, 32>, EpiBiasAct> {
+  static constexpr int value = 3;
+};
+
 template <class T, class AL, class BL, class Epi>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, (MinBlocks<T, Epi>::value))
 gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk, int nsplit) {
   __shared__ __attribute__((aligned(16))) float As[2][AL::LDS_FLOATS];
   __shared__ __attribute__((aligned(16))) float Bs[2][BL::LDS_FLOATS];

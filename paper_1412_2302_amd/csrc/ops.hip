@@ -63,29 +63,48 @@ int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* o
 }
 
 // out[n][y][x][c] = raw[n][c][oy+y][ox + (flip ? CW-1-x : x)] - mean[c][same]
-__global__ void preprocess_kernel(const uint8_t* __restrict__ raw, const float* __restrict__ mean,
-                                  const int32_t* __restrict__ ox, const int32_t* __restrict__ oy,
-                                  const int32_t* __restrict__ flip, int B, int C, int RH, int RW, int CH, int CW,
-                                  float* __restrict__ out) {
-  const size_t total = (size_t)B * CH * CW;
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= total) return;
-  const int x = (int)(i % CW);
-  const int y = (int)((i / CW) % CH);
-  const int n = (int)(i / ((size_t)CW * CH));
-  const int sx = ox[n] + (flip[n] ? CW - 1 - x : x);
-  const int sy = oy[n] + y;
-  const size_t plane = (size_t)RH * RW;
-  const size_t src = (size_t)sy * RW + sx;
-  for (int c = 0; c < C; ++c)
-    out[i * C + c] = (float)raw[((size_t)n * C + c) * plane + src] - mean[(size_t)c * plane + src];
+// out[n][y][x][c] = raw[n][c][oy+y][ox + (flip ? CW-1-x : x)] - mean[c][same place]; a lane makes four
+// consecutive floats of the flat output (16-byte stores), each from its own source byte.
+struct PreprocessDivs {
+  FastDiv c, chw, cw;  // channels, crop_h*crop_w, crop_w
+};
+__global__ void __launch_bounds__(256)
+preprocess_kernel(const uint8_t* __restrict__ raw, const float* __restrict__ mean, const int32_t* __restrict__ ox,
+                  const int32_t* __restrict__ oy, const int32_t* __restrict__ flip, uint32_t total, int C, int RH,
+                  int RW, int CH, int CW, PreprocessDivs d, float* __restrict__ out) {
+  const uint32_t e0 = (blockIdx.x * blockDim.x + threadIdx.x) * 4u;
+  if (e0 >= total) return;
+  const uint32_t plane = (uint32_t)(RH * RW);
+  float v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t e = min(e0 + j, total - 1);  // a lane past the end repeats the last element and drops it below
+    const uint32_t p = fdiv(e, d.c), c = e - p * (uint32_t)C;
+    const uint32_t n = fdiv(p, d.chw), rem = p - n * (uint32_t)(CH * CW);
+    const uint32_t y = fdiv(rem, d.cw), x = rem - y * (uint32_t)CW;
+    const uint32_t sx = (uint32_t)ox[n] + (flip[n] ? (uint32_t)CW - 1u - x : x);
+    const uint32_t sy = (uint32_t)oy[n] + y;
+    const uint32_t src = sy * (uint32_t)RW + sx;
+    v[j] = (float)raw[((size_t)n * C + c) * plane + src] - mean[(size_t)c * plane + src];
+  }
+  if (e0 + 4 <= total) {
+    *reinterpret_cast<float4*>(out + e0) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+    for (uint32_t j = 0; e0 + j < total; ++j) out[e0 + j] = v[j];
+  }
 }
 int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, const int32_t* oy,
                       const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st) {
-  const size_t total = (size_t)B * CH * CW;
-  KernelScope ks("preprocess", 0, (double)total * C * 5.0, st);
-  hipLaunchKernelGGL(preprocess_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, raw, mean, ox, oy, flip, B, C,
-                     RH, RW, CH, CW, out);
+  const size_t total = (size_t)B * CH * CW * C;
+  if (!total) return ALEXNET_OK;
+  if (total >= 0x7fffffffu) {
+    set_error("preprocess: more than 2^31 output elements");
+    return ALEXNET_ESHAPE;
+  }
+  KernelScope ks("preprocess", 0, (double)total * 5.0, st);
+  const PreprocessDivs d{make_fastdiv((uint32_t)C), make_fastdiv((uint32_t)(CH * CW)), make_fastdiv((uint32_t)CW)};
+  hipLaunchKernelGGL(preprocess_kernel, dim3(grid_for(ceil_div(total, 4), 256)), dim3(256), 0, st, raw, mean, ox, oy,
+                     flip, (uint32_t)total, C, RH, RW, CH, CW, d, out);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -810,6 +829,7 @@ colsum_stage1(const float* __restrict__ m, long rows, int cols, int rpb, float* 
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (VEC) {
     if (col < cols)
+#pragma unroll 8
       for (long r = r0 + rl; r < r1; r += 16) {
         const float4 v = *reinterpret_cast<const float4*>(m + r * cols + col);
         s.x += v.x;
