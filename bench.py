@@ -25,6 +25,10 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+# Memory-side traffic of the GEMM launches of one fp32 batch-128 step, bytes per launch (23 launches):
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB elementwise copy, from
+# profiles/train_step_alexnet_b128_fp32_counters.txt.  Not measured for other configurations.
+GEMM_TRAFFIC_FP32_B128 = 420073655
 PEAK_HBM_GBS = 8000.0
 
 
@@ -66,6 +70,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="run preprocessing on the compute stream")
     ap.add_argument("--kernel-table", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run three plain 1 GiB elementwise copies (under rocprofv3 --pmc they calibrate FETCH_SIZE / "
+                         "WRITE_SIZE: each reads and writes exactly 2^30 bytes)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (two replicas share one GPU in its "
@@ -117,6 +124,14 @@ def main():
             net.train_step(labels[k % pool], k, slot=s, stream=compute)
             freed[s].record(compute)
 
+    if args.traffic_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)  # an elementwise kernel (copy_ would go through the DMA engines)
+        torch.cuda.synchronize()
+        del src, dst
+
     run(args.warmup, 0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -145,7 +160,8 @@ def main():
         "kernel": ("ax::gemm_bf16_kernel (bf16 MFMA" if bf16 else "ax::gemm_kernel (fp32 MFMA")
                   + " implicit-GEMM: conv fwd/bwd-data/bwd-weight and dense layers)",
         "bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-        "frac": round(achieved / peak, 4), "traffic": None,
+        "frac": round(achieved / peak, 4),
+        "traffic": GEMM_TRAFFIC_FP32_B128 if (not bf16 and batch == 128) else None,
         "launches_per_step": gemm_calls // prof_steps,
         "flops_per_launch": gemm_flops / max(gemm_calls, 1),
         "avg_launch_ms": gemm_ms / max(gemm_calls, 1),
