@@ -421,6 +421,34 @@ def average_replicas(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return (np.asarray(a, F64) + np.asarray(b, F64)) / 2.0
 
 
+def averaged_gradient_update(w_a, v_a, g_a, w_b, v_b, g_b, lr: float, mu: float, wd: float):
+    """Exchange gradients instead of parameters (a variant of Section 2.2's exchange): both replicas
+    apply the update rule to the mean of their two gradients.  The rule is affine in g, so for
+    replicas that hold the same w and v this gives what updating separately and then averaging
+    weights and momentum gives; replicas that differ keep their own w and v.
+    Returns ((w_a', v_a'), (w_b', v_b'))."""
+    g = (np.asarray(g_a, F64) + np.asarray(g_b, F64)) / 2.0
+    return sgd_update(w_a, v_a, g, lr, mu, wd), sgd_update(w_b, v_b, g, lr, mu, wd)
+
+
+def topk_correct(scores, labels, k: int) -> int:
+    """Section 3's validation count: the number of rows whose label is among the k highest scores.
+    A row counts when fewer than k classes score strictly higher than its label (so ties go to the
+    label)."""
+    scores = np.asarray(scores, F64)
+    labels = np.asarray(labels)
+    own = scores[np.arange(scores.shape[0]), labels][:, None]
+    return int(np.sum(np.sum(scores > own, axis=1) < k))
+
+
+def center_crop_params(spec: "NetSpec"):
+    """Validation preprocessing: the central crop, no mirroring (offsets floor((raw - crop) / 2))."""
+    n = spec.batch
+    ox = np.full(n, (spec.raw_w - spec.crop_w) // 2, dtype=np.int32)
+    oy = np.full(n, (spec.raw_h - spec.crop_h) // 2, dtype=np.int32)
+    return ox, oy, np.zeros(n, dtype=np.int32)
+
+
 # --------------------------------------------------------------------------
 # Whole network
 # --------------------------------------------------------------------------

@@ -464,6 +464,62 @@ def test_two_half_batches_plus_average_equal_one_full_batch():
         np.testing.assert_allclose(O.average_replicas(va[k], vb[k]), vab[k], rtol=1e-10, atol=1e-15, err_msg=k)
 
 
+def test_gradient_exchange_equals_parameter_exchange_for_identical_replicas():
+    """Update-then-average (Section 2.2) and average-the-gradients-then-update agree when both
+    replicas start from the same weights and momentum, and agree with one step on the joint batch."""
+    b = 2
+    specA = oracle_spec(S.MINI, b, seed=1); specB = oracle_spec(S.MINI, b, seed=2); specAB = oracle_spec(S.MINI, 2 * b)
+    params = to64(S.make_params(O.param_shapes(specA), 3, bias_value=0.1, std=0.08))
+    mom = to64(S.make_random_like(O.param_shapes(specA), 4, std=0.01))
+    xa, la = S.make_float_batch(b, 3, 63, 63, 10, 100); xb, lb = S.make_float_batch(b, 3, 63, 63, 10, 200)
+    _, pa, va, ga, ca = O.train_step(specA, params, mom, xa, la, 0)
+    _, pb, vb, gb, cb = O.train_step(specB, params, mom, xb, lb, 0)
+    masks = [np.concatenate([ca["masks"][j], cb["masks"][j]]) for j in range(2)]
+    _, pab, vab, _, _ = O.train_step(specAB, params, mom, np.concatenate([xa, xb]), np.concatenate([la, lb]), 0, masks=masks)
+    for k in params:
+        wd = specA.weight_decay if k.endswith(".w") else 0.0
+        (wa2, va2), (wb2, vb2) = O.averaged_gradient_update(params[k], mom[k], ga[k], params[k], mom[k], gb[k],
+                                                            specA.lr, specA.momentum, wd)
+        assert np.array_equal(wa2, wb2) and np.array_equal(va2, vb2)
+        np.testing.assert_allclose(wa2, O.average_replicas(pa[k], pb[k]), rtol=1e-12, atol=1e-15, err_msg=k)
+        np.testing.assert_allclose(va2, O.average_replicas(va[k], vb[k]), rtol=1e-12, atol=1e-15, err_msg=k)
+        np.testing.assert_allclose(wa2, pab[k], rtol=1e-10, atol=1e-15, err_msg=k)
+
+
+def test_gradient_exchange_by_hand_for_replicas_that_differ():
+    # lr 0.5, mu 0.5, wd 0.25; replica a: w 2, v 4, g 1; replica b: w -1, v 0, g 3 -> mean gradient 2
+    (wa, va), (wb, vb) = O.averaged_gradient_update(np.array([2.0]), np.array([4.0]), np.array([1.0]),
+                                                    np.array([-1.0]), np.array([0.0]), np.array([3.0]), 0.5, 0.5, 0.25)
+    assert va[0] == 0.5 * 4.0 - 0.5 * (2.0 + 0.25 * 2.0) and wa[0] == 2.0 + va[0]      # 0.75, 2.75
+    assert vb[0] == 0.0 - 0.5 * (2.0 + 0.25 * -1.0) and wb[0] == -1.0 + vb[0]          # -0.875, -1.875
+    assert (va[0], wa[0], vb[0], wb[0]) == (0.75, 2.75, -0.875, -1.875)
+
+
+def test_topk_count_against_sorting_and_ties():
+    scores = rng.standard_normal((50, 17))
+    labels = rng.integers(0, 17, size=50)
+    order = np.argsort(-scores, axis=1, kind="stable")  # continuous draws: no ties
+    for k in (1, 3, 5, 17):
+        want = sum(int(labels[i] in order[i, :k]) for i in range(50))
+        assert O.topk_correct(scores, labels, k) == want
+    assert O.topk_correct(scores, labels, 17) == 50
+    tied = np.array([[1.0, 1.0, 1.0, 0.0], [2.0, 1.0, 1.0, 1.0], [0.0, 3.0, 2.0, 1.0]])
+    # row 0: nothing beats the label (tie goes to the label); row 1: label 3 is beaten by one class;
+    # row 2: label 0 is beaten by three
+    assert O.topk_correct(tied, np.array([2, 3, 0]), 1) == 1
+    assert O.topk_correct(tied, np.array([2, 3, 0]), 2) == 2
+    assert O.topk_correct(tied, np.array([2, 3, 0]), 4) == 3
+
+
+def test_center_crop_offsets():
+    spec = oracle_spec(S.ALEXNET, 3)
+    ox, oy, fl = O.center_crop_params(spec)
+    assert ox.tolist() == [14, 14, 14] and oy.tolist() == [14, 14, 14] and fl.tolist() == [0, 0, 0]  # (256-227)//2
+    raw = np.arange(3 * 3 * 256 * 256, dtype=np.int64).reshape(3, 3, 256, 256) % 251
+    out = O.preprocess(raw.astype(np.uint8), np.zeros((3, 256, 256)), ox, oy, fl, 227, 227)
+    assert np.array_equal(out, raw[:, :, 14:241, 14:241].astype(np.float64))
+
+
 def test_flatten_roundtrip_and_order():
     spec = oracle_spec(S.MINI, 2)
     shapes = O.param_shapes(spec)
