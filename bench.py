@@ -66,9 +66,10 @@ def main():
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--precision", choices=["fp32", "bf16"], default="fp32",
                     help="arithmetic of the matrix products (bf16: operands rounded, fp32 accumulation)")
-    ap.add_argument("--cpu-sample", type=int, default=32)
+    ap.add_argument("--cpu-sample", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="run preprocessing on the compute stream")
+    ap.add_argument("--no-exchange", action="store_true", help="skip timing the two-replica exchange kernels")
     ap.add_argument("--kernel-table", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run three plain 1 GiB elementwise copies (under rocprofv3 --pmc they calibrate FETCH_SIZE / "
@@ -185,6 +186,29 @@ def main():
            "peak": PEAK_HBM_GBS, "unit": "GB/s", "ms_per_step": round(bw_ms / prof_steps, 4),
            "note": "all bandwidth-bound kernels together (LRN, pool, update, reductions, preprocess)"}
 
+    # ---- the two-replica exchange kernels alone (bandwidth-bound; not part of `value`) ----
+    exchange = None
+    if not args.no_exchange:
+        peer = B.AlexNet(wl, batch, seed=S.SEED_BASE + 4, precision=1 if bf16 else 0)
+        peer.set_params(S.make_params(peer.shapes, S.SEED_BASE + 3))
+        torch.cuda.synchronize()
+        B.profile_begin()
+        for _ in range(10):
+            B.average_replicas(net, peer, stream=compute)
+        for _ in range(10):
+            B.average_gradients_update(net, peer, stream=compute)
+        torch.cuda.synchronize()
+        ex = {e["name"]: e for e in B.profile_end()}
+        def _rate(name):
+            e = ex[name]
+            ms = e["total_ms"] / e["calls"]
+            return {"avg_ms": round(ms, 4), "gbs": round(e["bytes"] / e["calls"] / (ms * 1e-3) / 1e9, 1)}
+        exchange = {"average_replicas": _rate("average"), "average_gradients_update": _rate("avg_grad_update"),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "note": "average_replicas = two launches (parameters, momentum), 16 B/param each; the "
+                            "gradient-exchange update is one launch of 40 B/param and replaces two updates + the average"}
+        peer.close()
+
     out = {
         "metric": "AlexNet train images/sec at batch 128 on 1 MI355X; conv MFMA utilisation %",
         "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -199,6 +223,7 @@ def main():
         "step_mfma_frac": round(4.136e9 * batch / (ms_per_step * 1e-3) / 1e12 / peak, 4),
         "roofline": roofline,
         "hbm_kernels": hbm,
+        "exchange": exchange,
         "kernels": table[:12],
     }
     if not args.no_cpu_baseline:

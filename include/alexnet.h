@@ -138,6 +138,27 @@ int alexnet_forward(alexnet_t* net, const float* d_input_nchw, float* d_probs, v
  * value, bit-identical on both sides.  Configurations must match. */
 int alexnet_average_replicas(alexnet_t* a, alexnet_t* b, void* stream);
 
+/* A variant of the Section 2.2 exchange that sends gradients instead of
+ * parameters: from the gradients left by alexnet_forward_backward on each
+ * replica, g = 0.5*(g_a + g_b), then each replica applies
+ * v <- mu v - lr (g + wd w), w <- w + v to its own weights and momentum (one
+ * pass over both).  The rule is affine in g, so replicas that hold the same w
+ * and v end up bit-identical and equal, up to rounding, to updating separately
+ * and then calling alexnet_average_replicas.  Configurations must match. */
+int alexnet_average_gradients_update(alexnet_t* a, alexnet_t* b, void* stream);
+
+/* Validation (Section 3).  alexnet_preprocess_center writes the mean-subtracted
+ * central crop (offsets floor((raw - crop) / 2), not mirrored) of d_raw into
+ * input slot `slot`.  alexnet_validate runs the inference pass (as
+ * alexnet_forward) on that slot and adds, for each of the nk <= 8 host values
+ * ks[j] >= 1, the number of pictures whose label is among the ks[j] highest
+ * scores to d_counts[j] (device int32; the caller zeroes them; a label counts
+ * when fewer than k classes score strictly higher).  Labels as in
+ * alexnet_train_step. */
+int alexnet_preprocess_center(alexnet_t* net, const uint8_t* d_raw, const float* d_mean, int32_t slot, void* stream);
+int alexnet_validate(alexnet_t* net, int32_t slot, const int32_t* d_labels, const int32_t* ks, int32_t nk,
+                     int32_t* d_counts, void* stream);
+
 /* Canonical <-> internal conversion of the flat parameter / momentum /
  * gradient vectors (n_params float32 each, device memory). */
 int alexnet_set_params(alexnet_t* net, const float* d_canonical, void* stream);

@@ -53,6 +53,9 @@ _SIGS = {
     "alexnet_apply_update": [_vp, _vp],
     "alexnet_forward": [_vp, _vp, _vp, _vp],
     "alexnet_average_replicas": [_vp, _vp, _vp],
+    "alexnet_average_gradients_update": [_vp, _vp, _vp],
+    "alexnet_preprocess_center": [_vp, _vp, _vp, _i32, _vp],
+    "alexnet_validate": [_vp, _i32, _vp, C.POINTER(_i32), _i32, _vp, _vp],
     "alexnet_set_params": [_vp, _vp, _vp],
     "alexnet_get_params": [_vp, _vp, _vp],
     "alexnet_set_momentum": [_vp, _vp, _vp],
@@ -259,6 +262,14 @@ class AlexNet:
     def preprocess(self, raw_u8: torch.Tensor, mean: torch.Tensor, step: int, slot: int, stream=None):
         _check(_lib.alexnet_preprocess(self._h, _ptr(raw_u8), _ptr(mean), step, slot, _stream(stream)))
 
+    def preprocess_center(self, raw_u8: torch.Tensor, mean: torch.Tensor, slot: int, stream=None):
+        _check(_lib.alexnet_preprocess_center(self._h, _ptr(raw_u8), _ptr(mean), slot, _stream(stream)))
+
+    def validate(self, labels: torch.Tensor, ks, counts: torch.Tensor, slot: int = 0, stream=None):
+        """counts (int32, device, one per k) += pictures of input slot `slot` whose label is in the top k."""
+        arr = (_i32 * len(ks))(*ks)
+        _check(_lib.alexnet_validate(self._h, slot, _ptr(labels), arr, len(ks), _ptr(counts), _stream(stream)))
+
     def set_input(self, x_nchw: torch.Tensor, slot: int = 0, stream=None):
         _check(_lib.alexnet_set_input(self._h, _ptr(x_nchw), slot, _stream(stream)))
 
@@ -384,6 +395,10 @@ class AlexNet:
 
 def average_replicas(a: AlexNet, b: AlexNet, stream=None):
     _check(_lib.alexnet_average_replicas(a._h, b._h, _stream(stream)))
+
+
+def average_gradients_update(a: AlexNet, b: AlexNet, stream=None):
+    _check(_lib.alexnet_average_gradients_update(a._h, b._h, _stream(stream)))
 
 
 def nchw_to_nhwc(x: torch.Tensor) -> torch.Tensor:

@@ -537,6 +537,16 @@ int alexnet_preprocess(alexnet_t* n, const uint8_t* d_raw, const float* d_mean, 
                            c.raw_w, c.crop_h, c.crop_w, n->input[slot], S(stream));
 }
 
+int alexnet_preprocess_center(alexnet_t* n, const uint8_t* d_raw, const float* d_mean, int32_t slot, void* stream) {
+  REQUIRE(n && d_raw && d_mean, ALEXNET_EINVAL, "alexnet_preprocess_center: null argument");
+  REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_preprocess_center: slot must be 0 or 1");
+  const alexnet_config_t& c = n->cfg;
+  AX_TRY(launch_crop_center(c.batch, (c.raw_w - c.crop_w) / 2, (c.raw_h - c.crop_h) / 2, n->crop_x[slot],
+                            n->crop_y[slot], n->flip[slot], S(stream)));
+  return launch_preprocess(d_raw, d_mean, n->crop_x[slot], n->crop_y[slot], n->flip[slot], c.batch, c.in_c, c.raw_h,
+                           c.raw_w, c.crop_h, c.crop_w, n->input[slot], S(stream));
+}
+
 int alexnet_set_input(alexnet_t* n, const float* d_input_nchw, int32_t slot, void* stream) {
   REQUIRE(n && d_input_nchw, ALEXNET_EINVAL, "alexnet_set_input: null argument");
   REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_set_input: slot must be 0 or 1");
@@ -571,6 +581,30 @@ int alexnet_forward(alexnet_t* n, const float* d_input_nchw, float* d_probs, voi
   AX_TRY(run_forward(n, n->input[2], false, 0, S(stream)));
   Dense& last = n->fc[kFc - 1];
   return launch_softmax_xent(last.act, nullptr, c.batch, last.out, 1, d_probs, n->row_loss, n->err_flag, S(stream));
+}
+
+int alexnet_validate(alexnet_t* n, int32_t slot, const int32_t* d_labels, const int32_t* ks, int32_t nk,
+                     int32_t* d_counts, void* stream) {
+  REQUIRE(n && d_labels && ks && d_counts, ALEXNET_EINVAL, "alexnet_validate: null argument");
+  REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_validate: slot must be 0 or 1");
+  REQUIRE(nk >= 1 && nk <= 8, ALEXNET_EINVAL, "alexnet_validate: between 1 and 8 values of k");
+  for (int j = 0; j < nk; ++j) REQUIRE(ks[j] >= 1, ALEXNET_EINVAL, "alexnet_validate: k must be positive");
+  AX_TRY(run_forward(n, n->input[slot], false, 0, S(stream)));
+  Dense& last = n->fc[kFc - 1];
+  // the order of the scores is the order of the probabilities, so the logits are counted directly
+  return launch_topk_count(last.act, d_labels, n->cfg.batch, last.out, ks, nk, d_counts, n->err_flag, S(stream));
+}
+
+int alexnet_average_gradients_update(alexnet_t* a, alexnet_t* b, void* stream) {
+  REQUIRE(a && b, ALEXNET_EINVAL, "alexnet_average_gradients_update: null handle");
+  REQUIRE(a != b, ALEXNET_EINVAL, "alexnet_average_gradients_update: the two replicas must be distinct");
+  REQUIRE(a->n_params == b->n_params && a->n_weights == b->n_weights, ALEXNET_ESHAPE,
+          "alexnet_average_gradients_update: configurations differ");
+  const alexnet_config_t& c = a->cfg;
+  REQUIRE(c.lr == b->cfg.lr && c.momentum == b->cfg.momentum && c.weight_decay == b->cfg.weight_decay, ALEXNET_ESHAPE,
+          "alexnet_average_gradients_update: optimiser constants differ");
+  return launch_avg_grad_update(a->params, a->mom, a->grads, b->params, b->mom, b->grads, a->n_params, a->n_weights,
+                                c.lr, c.momentum, c.weight_decay, S(stream));
 }
 
 int alexnet_average_replicas(alexnet_t* a, alexnet_t* b, void* stream) {

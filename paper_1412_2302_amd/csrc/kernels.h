@@ -91,6 +91,12 @@ int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, floa
 int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
                       hipStream_t st);
 int launch_average(float* a, float* b, size_t n, hipStream_t st);
+int launch_avg_grad_update(float* wa, float* va, const float* ga, float* wb, float* vb, const float* gb, size_t n,
+                           size_t n_decay, float lr, float mu, float wd, hipStream_t st);
+// counts[j] += rows whose label is among the ks[j] highest scores (ties go to the label); nk <= 8, ks on the host
+int launch_topk_count(const float* z, const int32_t* labels, int B, int classes, const int32_t* ks, int nk,
+                      int32_t* counts, int32_t* err_flag, hipStream_t st);
+int launch_crop_center(int B, int off_x, int off_y, int32_t* ox, int32_t* oy, int32_t* flip, hipStream_t st);
 // layout conversions of parameters; dir 0: canonical -> internal, 1: internal -> canonical
 int launch_conv_weight_pack(const float* src, float* dst, int Cout, int Cg, int k, int groups, int dir,
                             hipStream_t st);

@@ -53,6 +53,20 @@ __global__ void crop_params_kernel(uint64_t key, int B, int range_x, int range_y
   oy[n] = (int32_t)((rand_u64(key, TAG_CROP_Y, n) >> 32) % (uint64_t)range_y);
   flip[n] = (int32_t)(rand_u64(key, TAG_FLIP, n) >> 63);
 }
+// the central crop, not mirrored (validation)
+__global__ void crop_center_kernel(int B, int off_x, int off_y, int32_t* ox, int32_t* oy, int32_t* flip) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= B) return;
+  ox[n] = off_x;
+  oy[n] = off_y;
+  flip[n] = 0;
+}
+int launch_crop_center(int B, int off_x, int off_y, int32_t* ox, int32_t* oy, int32_t* flip, hipStream_t st) {
+  KernelScope ks("crop_params", 0, (double)B * 12.0, st);
+  hipLaunchKernelGGL(crop_center_kernel, dim3(grid_for(B, 64)), dim3(64), 0, st, B, off_x, off_y, ox, oy, flip);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
 int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* ox, int32_t* oy, int32_t* flip,
                        hipStream_t st) {
   KernelScope ks("crop_params", 0, (double)B * 12.0, st);
@@ -62,7 +76,6 @@ int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* o
   return ALEXNET_OK;
 }
 
-// out[n][y][x][c] = raw[n][c][oy+y][ox + (flip ? CW-1-x : x)] - mean[c][same]
 // out[n][y][x][c] = raw[n][c][oy+y][ox + (flip ? CW-1-x : x)] - mean[c][same place]; a lane makes four
 // consecutive floats of the flat output (16-byte stores), each from its own source byte.
 struct PreprocessDivs {
@@ -991,6 +1004,98 @@ int launch_average(float* a, float* b, size_t n, hipStream_t st) {
   if (!n) return ALEXNET_OK;
   KernelScope ks("average", 0, (double)n * 16.0, st);
   hipLaunchKernelGGL(average_kernel, dim3(grid_for((n + 3) / 4, 256)), dim3(256), 0, st, a, b, n);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// Gradient exchange: g = 0.5 (ga + gb), then each replica's own  v <- mu v - lr (g + wd w);  w <- w + v.
+// Replicas that hold the same w and v end up bit-identical (same arithmetic on the same values).
+__device__ __forceinline__ void sgd_one(float& w, float& v, float g, float d, float lr, float mu) {
+  v = mu * v - lr * (g + d * w);
+  w += v;
+}
+__global__ void avg_grad_update_kernel(float* __restrict__ wa, float* __restrict__ va, const float* __restrict__ ga,
+                                       float* __restrict__ wb, float* __restrict__ vb, const float* __restrict__ gb,
+                                       size_t n, size_t n_decay, float lr, float mu, float wd) {
+  const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t i = q * 4;
+  if (i + 3 < n) {
+    float4 w1 = *reinterpret_cast<float4*>(wa + i), v1 = *reinterpret_cast<float4*>(va + i);
+    float4 w2 = *reinterpret_cast<float4*>(wb + i), v2 = *reinterpret_cast<float4*>(vb + i);
+    const float4 g1 = *reinterpret_cast<const float4*>(ga + i), g2 = *reinterpret_cast<const float4*>(gb + i);
+    const float4 g = make_float4(0.5f * (g1.x + g2.x), 0.5f * (g1.y + g2.y), 0.5f * (g1.z + g2.z), 0.5f * (g1.w + g2.w));
+    const float d0 = i + 0 < n_decay ? wd : 0.f, d1 = i + 1 < n_decay ? wd : 0.f;
+    const float d2 = i + 2 < n_decay ? wd : 0.f, d3 = i + 3 < n_decay ? wd : 0.f;
+    sgd_one(w1.x, v1.x, g.x, d0, lr, mu);
+    sgd_one(w1.y, v1.y, g.y, d1, lr, mu);
+    sgd_one(w1.z, v1.z, g.z, d2, lr, mu);
+    sgd_one(w1.w, v1.w, g.w, d3, lr, mu);
+    sgd_one(w2.x, v2.x, g.x, d0, lr, mu);
+    sgd_one(w2.y, v2.y, g.y, d1, lr, mu);
+    sgd_one(w2.z, v2.z, g.z, d2, lr, mu);
+    sgd_one(w2.w, v2.w, g.w, d3, lr, mu);
+    *reinterpret_cast<float4*>(va + i) = v1;
+    *reinterpret_cast<float4*>(wa + i) = w1;
+    *reinterpret_cast<float4*>(vb + i) = v2;
+    *reinterpret_cast<float4*>(wb + i) = w2;
+  } else {
+    for (size_t j = i; j < n; ++j) {
+      const float d = j < n_decay ? wd : 0.f, g = 0.5f * (ga[j] + gb[j]);
+      sgd_one(wa[j], va[j], g, d, lr, mu);
+      sgd_one(wb[j], vb[j], g, d, lr, mu);
+    }
+  }
+}
+int launch_avg_grad_update(float* wa, float* va, const float* ga, float* wb, float* vb, const float* gb, size_t n,
+                           size_t n_decay, float lr, float mu, float wd, hipStream_t st) {
+  if (!n) return ALEXNET_OK;
+  KernelScope ks("avg_grad_update", 0, (double)n * 40.0, st);
+  hipLaunchKernelGGL(avg_grad_update_kernel, dim3(grid_for((n + 3) / 4, 256)), dim3(256), 0, st, wa, va, ga, wb, vb, gb,
+                     n, n_decay, lr, mu, wd);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// counts[j] += number of rows whose label has fewer than ks[j] classes scoring strictly higher (one
+// workgroup per row; integer atomics, so the result does not depend on the order)
+struct TopK {
+  int n;
+  int k[8];
+};
+__global__ void __launch_bounds__(256)
+topk_count_kernel(const float* __restrict__ z, const int32_t* __restrict__ labels, int classes, TopK tk,
+                  int32_t* __restrict__ counts, int32_t* __restrict__ err_flag) {
+  __shared__ int sh[4];
+  const int row = blockIdx.x;
+  int lab = labels[row];
+  if (lab < 0 || lab >= classes) {
+    if (threadIdx.x == 0) *err_flag = 1;
+    lab = min(max(lab, 0), classes - 1);
+  }
+  const float* zr = z + (size_t)row * classes;
+  const float own = zr[lab];
+  int higher = 0;
+  for (int c = threadIdx.x; c < classes; c += 256) higher += zr[c] > own ? 1 : 0;
+  for (int o = 32; o > 0; o >>= 1) higher += __shfl_down(higher, o, 64);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = higher;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int total = sh[0] + sh[1] + sh[2] + sh[3];
+    for (int j = 0; j < tk.n; ++j)
+      if (total < tk.k[j]) atomicAdd(counts + j, 1);
+  }
+}
+int launch_topk_count(const float* z, const int32_t* labels, int B, int classes, const int32_t* ks, int nk,
+                      int32_t* counts, int32_t* err_flag, hipStream_t st) {
+  if (nk < 1 || nk > 8) {
+    set_error("top-k count: between 1 and 8 values of k");
+    return ALEXNET_EINVAL;
+  }
+  TopK tk;
+  tk.n = nk;
+  for (int j = 0; j < 8; ++j) tk.k[j] = j < nk ? ks[j] : 0;
+  KernelScope ks_("topk_count", 0, (double)B * classes * 4.0, st);
+  hipLaunchKernelGGL(topk_count_kernel, dim3(B), dim3(256), 0, st, z, labels, classes, tk, counts, err_flag);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
