@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="run preprocessing on the compute stream")
     ap.add_argument("--no-exchange", action="store_true", help="skip timing the two-replica exchange kernels")
+    ap.add_argument("--no-host-loader", action="store_true",
+                    help="skip the run fed from host memory through the loading thread (reported beside `value`)")
     ap.add_argument("--kernel-table", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run three plain 1 GiB elementwise copies (under rocprofv3 --pmc they calibrate FETCH_SIZE / "
@@ -209,6 +211,37 @@ def main():
                             "gradient-exchange update is one launch of 40 B/param and replaces two updates + the average"}
         peer.close()
 
+    # ---- the same steps fed from host memory by the loading thread (PCIe inclusive; never `value`) ----
+    host_loader = None
+    if not args.no_host_loader:
+        count = 4 * batch
+        himg = torch.from_numpy(np.concatenate([S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 3 + i)[0]
+                                                for i in range(4)]))
+        hlab = torch.from_numpy(np.concatenate([S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 3 + i)[1]
+                                                for i in range(4)]))
+        loader = B.Loader(net, himg, hlab, depth=3)
+        torch.cuda.synchronize()
+
+        lab = loader.stage(0, mean, side, compute)
+        t1 = 0.0
+        for k in range(args.warmup + args.steps):
+            if k == args.warmup:
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+            nxt = loader.stage(k + 1, mean, side, compute)  # one more is staged than trained: harmless
+            net.train_step(lab, k, slot=k % 2, stream=compute)
+            loader.done(k, compute)
+            lab = nxt
+        torch.cuda.synchronize()
+        dt_l = time.perf_counter() - t1
+        net.check(stream=compute)
+        host_loader = {"value": round(batch * args.steps / dt_l, 1), "unit": "images/s",
+                       "ms_per_step": round(dt_l / args.steps * 1e3, 4),
+                       "note": f"{count} stored pictures in pageable host memory -> pinned staging (3 sets) -> "
+                               "host-to-device copies on the loader's stream -> on-device preprocessing; "
+                               "PCIe inclusive"}
+        loader.close()
+
     out = {
         "metric": "AlexNet train images/sec at batch 128 on 1 MI355X; conv MFMA utilisation %",
         "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -224,6 +257,7 @@ def main():
         "roofline": roofline,
         "hbm_kernels": hbm,
         "exchange": exchange,
+        "host_loader": host_loader,
         "kernels": table[:12],
     }
     if not args.no_cpu_baseline:

@@ -159,6 +159,39 @@ int alexnet_preprocess_center(alexnet_t* net, const uint8_t* d_raw, const float*
 int alexnet_validate(alexnet_t* net, int32_t slot, const int32_t* d_labels, const int32_t* ks, int32_t nk,
                      int32_t* d_counts, void* stream);
 
+/* Loading thread of Section 2.1 (Figure 1): while the GPU trains on minibatch
+ * k, a host thread brings minibatch k+1 from the stored pictures to the GPU.
+ *
+ * host_images (uint8 [count][in_c][raw_h][raw_w]) and host_labels (int32
+ * [count]) are ordinary host memory and stand for the disk; minibatch k is
+ * pictures (k*batch + i) mod count.  The caller owns, for `depth` (2..16)
+ * staging sets, pinned host memory pinned_raw (depth*batch*in_c*raw_h*raw_w
+ * bytes) and pinned_labels (depth*batch int32), and device memory d_raw /
+ * d_labels of the same sizes; all must outlive the loader.  The thread copies
+ * minibatch k into staging set k % depth and issues its host-to-device copies
+ * on a stream of the loader's own, at most `depth` minibatches ahead of
+ * alexnet_loader_done.
+ *
+ * alexnet_loader_stage(k): k must be the next minibatch in order and at most
+ * two ahead of alexnet_loader_done (there are two input slots).  Blocks the
+ * calling host thread until the copies of minibatch k have been issued, then
+ * enqueues on side_stream: wait for them, alexnet_preprocess(step k, slot k%2);
+ * makes compute_stream wait for that, and returns the device address of the
+ * minibatch's labels.  The caller then enqueues the training step of slot k%2
+ * on compute_stream and calls alexnet_loader_done(k, compute_stream), which
+ * lets the thread reuse that staging set once the step has run.
+ * alexnet_loader_destroy stops the thread and waits for copies in flight.
+ * Errors: ALEXNET_EINVAL for calls out of order, ALEXNET_EHIP if a HIP call
+ * fails (also one made by the thread). */
+typedef struct alexnet_loader alexnet_loader_t;
+int alexnet_loader_create(alexnet_t* net, const alexnet_config_t* cfg, const uint8_t* host_images,
+                          const int32_t* host_labels, int64_t count, int32_t depth, void* pinned_raw,
+                          void* pinned_labels, void* d_raw, void* d_labels, alexnet_loader_t** out);
+int alexnet_loader_stage(alexnet_loader_t* loader, uint64_t k, const float* d_mean, void* side_stream,
+                         void* compute_stream, const int32_t** d_labels_k);
+int alexnet_loader_done(alexnet_loader_t* loader, uint64_t k, void* compute_stream);
+int alexnet_loader_destroy(alexnet_loader_t* loader);
+
 /* Canonical <-> internal conversion of the flat parameter / momentum /
  * gradient vectors (n_params float32 each, device memory). */
 int alexnet_set_params(alexnet_t* net, const float* d_canonical, void* stream);

@@ -55,6 +55,10 @@ _SIGS = {
     "alexnet_average_replicas": [_vp, _vp, _vp],
     "alexnet_average_gradients_update": [_vp, _vp, _vp],
     "alexnet_preprocess_center": [_vp, _vp, _vp, _i32, _vp],
+    "alexnet_loader_create": [_vp, _vp, _vp, _vp, C.c_int64, _i32, _vp, _vp, _vp, _vp, C.POINTER(_vp)],
+    "alexnet_loader_stage": [_vp, _u64, _vp, _vp, _vp, C.POINTER(_vp)],
+    "alexnet_loader_done": [_vp, _u64, _vp],
+    "alexnet_loader_destroy": [_vp],
     "alexnet_validate": [_vp, _i32, _vp, C.POINTER(_i32), _i32, _vp, _vp],
     "alexnet_set_params": [_vp, _vp, _vp],
     "alexnet_get_params": [_vp, _vp, _vp],
@@ -395,6 +399,45 @@ class AlexNet:
 
 def average_replicas(a: AlexNet, b: AlexNet, stream=None):
     _check(_lib.alexnet_average_replicas(a._h, b._h, _stream(stream)))
+
+
+class Loader:
+    """Section 2.1's loading thread: `images` (uint8 [count][C][RH][RW]) and `labels` (int32 [count]) are CPU
+    tensors standing for the disk; staging memory (pinned host + device) is allocated here with torch."""
+
+    def __init__(self, net: AlexNet, images: torch.Tensor, labels: torch.Tensor, depth: int = 2):
+        assert images.dtype == torch.uint8 and labels.dtype == torch.int32 and not images.is_cuda
+        self.net, self.images, self.labels = net, images.contiguous(), labels.contiguous()
+        per = net.batch * int(np.prod(images.shape[1:]))
+        self.pinned_raw = torch.empty(depth * per, dtype=torch.uint8, pin_memory=True)
+        self.pinned_labels = torch.empty(depth * net.batch, dtype=torch.int32, pin_memory=True)
+        self.d_raw = torch.empty(depth * per, dtype=torch.uint8, device="cuda")
+        self.d_labels = torch.empty(depth * net.batch, dtype=torch.int32, device="cuda")
+        h = _vp()
+        _check(_lib.alexnet_loader_create(net._h, C.byref(net.cfg), self.images.data_ptr(), self.labels.data_ptr(),
+                                          self.images.shape[0], depth, self.pinned_raw.data_ptr(),
+                                          self.pinned_labels.data_ptr(), self.d_raw.data_ptr(),
+                                          self.d_labels.data_ptr(), C.byref(h)))
+        self._h = h
+
+    def stage(self, k: int, mean: torch.Tensor, side_stream, compute_stream) -> torch.Tensor:
+        """Returns the labels of minibatch k (a view of the loader's device buffer)."""
+        p = _vp()
+        _check(_lib.alexnet_loader_stage(self._h, k, _ptr(mean), _stream(side_stream), _stream(compute_stream),
+                                         C.byref(p)))
+        off = (p.value - self.d_labels.data_ptr()) // 4
+        return self.d_labels[off:off + self.net.batch]
+
+    def done(self, k: int, compute_stream):
+        _check(_lib.alexnet_loader_done(self._h, k, _stream(compute_stream)))
+
+    def close(self):
+        if self._h is not None and _lib is not None:
+            _lib.alexnet_loader_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
 
 
 def average_gradients_update(a: AlexNet, b: AlexNet, stream=None):
