@@ -50,7 +50,7 @@ static thread_local int g_bf16 = 0;
 void set_gemm_precision(int bf16) { g_bf16 = bf16 ? 1 : 0; }
 
 static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int max_s, bool bf = false,
-                          bool allow48 = false) {
+                          bool allow48 = false, int max_chunk = 0) {
   const TileOption* opts = bf ? kTileOptionsBf : kTileOptions;
   const int nopts = bf ? 2 : (allow48 ? 4 : 3);
   GemmPlan best{128, 128, 1, ceil_div(K, opts[0].bk) * opts[0].bk};
@@ -64,6 +64,7 @@ static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int
       const int per = ceil_div(ktiles, s);
       if (ceil_div(ktiles, per) != s) continue;
       if (s > 1 && per * bk < 96) break;
+      if (max_chunk && per * bk > max_chunk) continue;  // the workgroup's k range must fit its pixel table
       const double rounds = (double)ceil_div(tiles * s, 256);
       double t = rounds * t_tile * per / ktiles + 4e-6;
       if (s > 1) t += (s + 1) * out_bytes / 2.5e12 + 6e-6;
@@ -88,7 +89,7 @@ static inline double conv_flops(const ConvGeom& c) { return 2.0 * c.P() * c.Cout
 
 template <class T, class AL, class BL, class Epi>
 static int launch_tile(const typename AL::Params& ap, const typename BL::Params& bp, const Epi& ep, int M, int N, int K,
-                       int kchunk, int nsplit, int groups, hipStream_t st) {
+                       int kchunk, int nsplit, int groups, hipStream_t st, size_t dyn_lds = 0) {
   if (M <= 0 || N <= 0) return ALEXNET_OK;
   dim3 grid(ceil_div(M, T::BM), ceil_div(N, T::BN), groups * nsplit);
   if (grid.y > 65535 || grid.z > 65535) {
@@ -96,7 +97,8 @@ static int launch_tile(const typename AL::Params& ap, const typename BL::Params&
     return ALEXNET_ESHAPE;
   }
   KernelScope ks("gemm", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups, 0, st);
-  hipLaunchKernelGGL((gemm_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), 0, st, ap, bp, ep, M, N, K, kchunk, nsplit);
+  hipLaunchKernelGGL((gemm_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), dyn_lds, st, ap, bp, ep, M, N, K, kchunk,
+                     nsplit);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -138,6 +140,19 @@ struct ConvWeightGrad {  // rows = taps (backward-weight)
         a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
   }
 };
+
+// backward-weight with the pixel table in LDS (see Im2colRowTable): 16-byte loads, whole k-tiles
+struct ConvWeightGradTable {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile<T, Im2colRowTable<T::BM, T::BK>, DenseRowWhole<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st, (size_t)std::min(kchunk, d.K) * sizeof(PixelEntry));
+  }
+};
+static inline bool table_ok(const Im2colParams& a, const GemmDims& d) {
+  return a.kh * a.kw <= 31 && d.K % kBK == 0;
+}
 
 // a k-tile inside one tap (see Im2colKTap): 16-byte loads, whole k-tiles
 template <int MODE>
@@ -242,10 +257,10 @@ static GemmPlan bwdd_plan(const ConvGeom& c, bool bf, bool t48 = false) {
   const GemmDims d = bwdd_dims(c);
   return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8, bf, t48);
 }
-static GemmPlan bwdw_plan(const ConvGeom& c, bool run, bool bf) {
+static GemmPlan bwdw_plan(const ConvGeom& c, bool run, bool bf, bool table = false) {
   const GemmDims d = bwdw_dims(c);
   return plan_gemm(run ? run_k(c) : d.M, d.N, d.K, d.groups, (double)(run ? run_w_elems(c) : c.w_elems()) * 4, 256,
-                   bf);
+                   bf, false, table ? kMaxTableK : 0);
 }
 // scratch sizes cover every variant (generic / run mode, fp32 / bf16) of the op
 size_t conv_fwd_ws_floats(const ConvGeom& c) {
@@ -261,11 +276,12 @@ size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
 }
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
   size_t n = 0;
-  for (int bf = 0; bf < 2; ++bf) {
-    const GemmPlan p = bwdw_plan(c, false, bf);
-    if (p.ns > 1) n = std::max(n, (size_t)p.ns * c.w_elems());
-    if (run_mode(c)) n = std::max(n, (size_t)bwdw_plan(c, true, bf).ns * run_w_elems(c));
-  }
+  for (int bf = 0; bf < 2; ++bf)
+    for (int table = 0; table < 2 - bf; ++table) {
+      const GemmPlan p = bwdw_plan(c, false, bf, table);
+      if (p.ns > 1) n = std::max(n, (size_t)p.ns * c.w_elems());
+      if (run_mode(c)) n = std::max(n, (size_t)bwdw_plan(c, true, bf, table).ns * run_w_elems(c));
+    }
   return n;
 }
 
@@ -406,13 +422,20 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
   if (run) d.M = run_k(c);
   const bool av = run || bwdw_A_vec(c, x), bv = bwdw_B_vec(c, dy);
   const bool bf = g_bf16 && av && bv;
-  const GemmPlan p = bwdw_plan(c, run, bf);
+  const Im2colParams a = run ? run_A(c, x) : bwdw_A(c, x);
+  bool table = !bf && av && bv && table_ok(a, d);
+  GemmPlan p = bwdw_plan(c, run, bf, table);
+  if (table && p.kchunk > kMaxTableK) {  // no split count within reach keeps the k range inside the table
+    table = false;
+    p = bwdw_plan(c, run, bf, false);
+  }
   const long slab = (long)d.M * d.N;
   float* out = run ? dwrun : dwf;
   EpiSlab ep{p.ns > 1 ? ws : out, slab, d.N, nullptr};
-  const Im2colParams a = run ? run_A(c, x) : bwdw_A(c, x);
   if (bf)
     AX_TRY((by_tile_bf<ConvWeightGradBf>(p, a, bwdw_B(c, dy), ep, d, st)));
+  else if (table)
+    AX_TRY((by_tile_tap<ConvWeightGradTable>(p, a, bwdw_B(c, dy), ep, d, st)));
   else
     AX_TRY((by_tile<ConvWeightGrad>(p, av, bv, a, bwdw_B(c, dy), ep, d, st)));
   if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, out, st));

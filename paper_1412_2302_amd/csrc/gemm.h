@@ -41,6 +41,8 @@
 
 #include <stdint.h>
 
+#include <type_traits>
+
 #ifndef AX_HOST_EMU
 #include <hip/hip_runtime.h>
 #define AX_HD __host__ __device__ __forceinline__
@@ -527,6 +529,78 @@ struct Im2colRowInner {
   }
 };
 
+// Im2colRowInner for the common case of whole k-tiles, at most 31 taps and 16-byte loads.  The pixels of
+// the workgroup's k range are decoded once, by all threads together, into a table in LDS: the byte offset
+// of the pixel's origin and a bit mask of the taps that fall outside the tensor there.  A thread's tap never
+// changes, so an address is a table read, an add, a mask test and a select.  K-tiles past the end are
+// clamped as in DenseRowWhole.
+struct PixelEntry {
+  uint32_t base;     // byte offset of (n, y*stride - pad, x*stride_x - pad_x, channel 0), mod 2^32
+  uint32_t outside;  // bit r*kw + s: that tap is outside the tensor; bit 31 always set
+};
+constexpr int kMaxTableK = 3072;  // longest k range of one workgroup with a table (24 KiB of LDS)
+template <int ROWS, int BK>
+struct Im2colRowTable {
+  static constexpr int QR = ROWS / 4, NQ = QR * BK, NL = NQ / kThreads, NA = NL;
+  static constexpr bool kRowMajor = false;
+  static constexpr bool kUsesTable = true;
+  static constexpr int LD = ROWS + 4, LDS_FLOATS = BK * LD;
+  static_assert(kThreads % QR == 0 && NQ % kThreads == 0, "every load of a thread shares its row quad");
+  typedef Im2colParams Params;
+  BufView v;
+  int tid, rq;
+  uint32_t tapoff;   // byte offset of the thread's tap, first channel and group from a pixel's origin
+  uint32_t tapmask;  // that tap's bit in PixelEntry::outside; bit 31 for a row past the end
+  const PixelEntry* tbl;
+  int kbase, klast;
+  Offsets<NL, true> pl;
+  AX_HD Im2colRowTable(const Params& a, int grp, int tid_, int row0)
+      : v(make_view(a.x, a.bytes)), tid(tid_), tbl(nullptr), kbase(0), klast(0) {
+    rq = tid % QR;
+    const int m = row0 + 4 * rq;
+    const bool in = m < a.kh * a.kw * a.Cg;
+    const TapCoord t = decode_tap(in ? m : 0, a);
+    tapoff = (((uint32_t)t.r * (uint32_t)a.W + (uint32_t)t.s) * (uint32_t)a.Ctot + (uint32_t)t.c +
+              (uint32_t)(grp * a.c_stride_g)) * 4u;
+    tapmask = in ? 1u << (t.r * a.kw + t.s) : 0x80000000u;
+  }
+  // all threads of the workgroup: entries of pixels kbeg .. kend-1; a barrier must follow
+  static AX_HD void build_table(const Params& g, PixelEntry* table, int kbeg, int kend, int tid) {
+    for (int e = tid; e < kend - kbeg; e += kThreads) {
+      const PixCoord c = decode_pixel(kbeg + e, g);
+      const int y0 = c.y * g.stride - g.pad, x0 = c.x * g.stride_x - g.pad_x;
+      uint32_t inside = 0;
+      int bit = 0;
+      for (int r = 0; r < g.kh; ++r)
+        for (int s2 = 0; s2 < g.kw; ++s2, ++bit)
+          inside |= ((uint32_t)(y0 + r) < (uint32_t)g.H && (uint32_t)(x0 + s2) < (uint32_t)g.W ? 1u : 0u) << bit;
+      PixelEntry pe;
+      pe.base = row_base<IM2COL_FWD>(g, c.n, y0, x0, 0);
+      pe.outside = ~inside | 0x80000000u;
+      table[e] = pe;
+    }
+  }
+  AX_HD void set_table(const PixelEntry* table, int kbeg, int kend) {
+    tbl = table;
+    kbase = kbeg;
+    klast = kend - BK;
+  }
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int kc = k0 < kend ? k0 : klast;  // uniform
+    const PixelEntry pe = tbl[kc - kbase + (tid + S * kThreads) / QR];
+    pl.off[S] = (pe.outside & tapmask) ? kOob : pe.base + tapoff;
+  }
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int s, float* lds, const float4* r) const {
+    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QR) * LD + 4 * rq) = r[s];
+  }
+};
+template <class L, class = void>
+struct uses_table : std::false_type {};
+template <class L>
+struct uses_table<L, std::void_t<decltype(L::kUsesTable)>> : std::true_type {};
+
 // Whole-tile helpers (prologue of the kernel, CPU emulation).
 template <class L, int S = 0>
 AX_HD void plan_all(L& l, int k0, int kend) {
@@ -766,6 +840,12 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
   AL al(ap, g, tid, m0);
   BL bl(bp, g, tid, n0);
   ep.set_group(g, z);
+  if constexpr (uses_table<AL>::value) {  // launched with (kend - kbeg) * sizeof(PixelEntry) bytes of dynamic LDS
+    extern __shared__ __attribute__((aligned(16))) PixelEntry pixel_table[];
+    AL::build_table(ap, pixel_table, kbeg, kend, tid);
+    al.set_table(pixel_table, kbeg, kend);
+    __syncthreads();
+  }
 
   typename MfmaBlock<T::RB>::Acc acc[T::TM][T::TN];
 #pragma unroll

@@ -52,9 +52,16 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
           // poison LDS so that a slot nobody wrote shows up
           std::fill(As.begin(), As.end(), NAN);
           std::fill(Bs.begin(), Bs.end(), NAN);
+          // the workgroup's pixel table (loaders that use one): exactly as many entries as the kernel gets
+          std::vector<PixelEntry> table;
+          if constexpr (uses_table<AL>::value) {
+            table.assign(kend - kbeg, PixelEntry{0xdeadbeefu, 0u});
+            for (int tid = 0; tid < kThreads; ++tid) AL::build_table(ap, table.data(), kbeg, kend, tid);
+          }
           for (int tid = 0; tid < kThreads; ++tid) {
             AL al(ap, g, tid, m0);
             BL bl(bp, g, tid, n0);
+            if constexpr (uses_table<AL>::value) al.set_table(table.data(), kbeg, kend);
             float4 ra[AL::NL], rb[BL::NL];
             plan_all(al, kbeg + t * T::BK, kend);
             plan_all(bl, kbeg + t * T::BK, kend);
@@ -401,6 +408,22 @@ static void run_case(const Case& cs) {
         for (int j = 0; j < kc; ++j)
           for (int o = 0; o < c.Cout; ++o) dwf[((long)r * kc + j) * c.Cout + o] = dwr[((long)r * run + j) * c.Cout + o];
       check("bwdw_run", nm, dwf, dwf_ref);
+      if (d.K % T::BK == 0) {  // pixel table in LDS, whole k-tiles, two splits
+        const int ns = 2, chunk = ((d.K / T::BK + ns - 1) / ns) * T::BK;
+        std::vector<float> ws((size_t)ns * d.M * d.N, NAN);
+        EpiSlab es{ws.data(), (long)d.M * d.N, d.N, nullptr};
+        emu_gemm<T, Im2colRowTable<T::BM, T::BK>, DenseRowWhole<T::BN, T::BK>, EpiSlab>(run_A(c, x), bwdw_B(c, dy), es,
+                                                                                       d.M, d.N, d.K, chunk, ns, 1);
+        std::fill(dwf.begin(), dwf.end(), 0.f);
+        for (int sp = 0; sp < ns; ++sp)
+          for (int r = 0; r < c.k; ++r)
+            for (int j = 0; j < kc; ++j)
+              for (int o = 0; o < c.Cout; ++o) {
+                const float v = ws[((size_t)sp * d.M + (size_t)r * run + j) * d.N + o];
+                if (v == v) dwf[((long)r * kc + j) * c.Cout + o] += v;
+              }
+        check("bwdw_run_tbl", nm, dwf, dwf_ref);
+      }
     }
     delete[] wrun;
   }
@@ -477,6 +500,19 @@ static void run_case(const Case& cs) {
         for (long i = 0; i < (long)d.M * d.N; ++i) dwf[(long)g * d.M * d.N + i] += ws[((long)g * nsplit + sp) * d.M * d.N + i];
     snprintf(nm, sizeof nm, "%s/%dx%d/s%d", cs.name, T::BM, T::BN, nsplit);
     check("bwd_wgt", nm, dwf, dwf_ref);
+    if (bwdw_A_vec(c, x) && bwdw_B_vec(c, dy) && d.K % T::BK == 0 && c.k * c.k <= 31 && kchunk % T::BK == 0) {
+      std::fill(ws.begin(), ws.end(), NAN);
+      emu_gemm<T, Im2colRowTable<T::BM, T::BK>, DenseRowWhole<T::BN, T::BK>, EpiSlab>(
+          bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
+      std::fill(dwf.begin(), dwf.end(), 0.f);
+      for (int g = 0; g < d.groups; ++g)
+        for (int sp = 0; sp < nsplit; ++sp)
+          for (long i = 0; i < (long)d.M * d.N; ++i) {
+            const float v = ws[((long)g * nsplit + sp) * d.M * d.N + i];
+            if (v == v) dwf[(long)g * d.M * d.N + i] += v;  // a chunk past K leaves its slab unwritten
+          }
+      check("bwd_wgt_tbl", nm, dwf, dwf_ref);
+    }
   }
   delete[] x; delete[] dy; delete[] w; delete[] wf; delete[] wb; delete[] bias;
 }
@@ -627,6 +663,8 @@ int main() {
       {geom(5, 5, 132, 136, 3, 1, 1, 1), "k3wide"},      // more than one tile along N and K rows
       {geom(2, 7, 64, 64, 3, 1, 1, 2), "k3p1g2c32"},     // a k-tile inside one tap (32 channels per group)
       {geom(3, 6, 32, 96, 5, 1, 2, 1), "k5p2c32"},       // 25 taps, ragged rows and columns
+      {geom(4, 7, 8, 24, 3, 1, 1, 2), "k3p1g2px224"},    // 4*7*8 = 224 pixels: whole k-tiles for backward-weight
+      {geom(4, 15, 3, 8, 5, 2, 0, 1), "k5s2c3px192"},    // run mode with 4*6*8 = 192 output pixels
   };
   for (const Case& cs : cases) {
     run_case<Tile<128, 128, 32, 2, 2>>(cs);
