@@ -105,7 +105,7 @@ static int launch_tile(const typename AL::Params& ap, const typename BL::Params&
 
 template <class T, class AL, class BL, class Epi>
 static int launch_tile_bf(const typename AL::Params& ap, const typename BL::Params& bp, const Epi& ep, int M, int N,
-                          int K, int kchunk, int nsplit, int groups, hipStream_t st) {
+                          int K, int kchunk, int nsplit, int groups, hipStream_t st, size_t dyn_lds = 0) {
   if (M <= 0 || N <= 0) return ALEXNET_OK;
   dim3 grid(ceil_div(M, T::BM), ceil_div(N, T::BN), groups * nsplit);
   if (grid.y > 65535 || grid.z > 65535) {
@@ -113,8 +113,8 @@ static int launch_tile_bf(const typename AL::Params& ap, const typename BL::Para
     return ALEXNET_ESHAPE;
   }
   KernelScope ks("gemm_bf16", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups, 0, st);
-  hipLaunchKernelGGL((gemm_bf16_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), 0, st, ap, bp, ep, M, N, K, kchunk,
-                     nsplit);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), dyn_lds, st, ap, bp, ep, M, N, K,
+                     kchunk, nsplit);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -184,6 +184,24 @@ struct ConvWeightGradBf {
                 hipStream_t st) {
     return launch_tile_bf<T, BfIm2colRowInner<T::BM, T::BK>, BfDenseRowInner<T::BN, T::BK>, Epi>(
         a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+// bf16 with the uniform-tap / whole-tile / pixel-table loaders
+template <int MODE>
+struct ConvGatherTapBf {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, BfRowMajor<Im2colKTap<T::BM, T::BK, MODE>, T::BM, T::BK>, BfDenseRowWhole<T::BN, T::BK>,
+                          Epi>(a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+struct ConvWeightGradTableBf {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, BfIm2colRowTable<T::BM, T::BK>, BfDenseRowWhole<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st, (size_t)std::min(kchunk, d.K) * sizeof(PixelEntry));
   }
 };
 template <class F, class Epi>
@@ -277,7 +295,7 @@ size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
   size_t n = 0;
   for (int bf = 0; bf < 2; ++bf)
-    for (int table = 0; table < 2 - bf; ++table) {
+    for (int table = 0; table < 2; ++table) {
       const GemmPlan p = bwdw_plan(c, false, bf, table);
       if (p.ns > 1) n = std::max(n, (size_t)p.ns * c.w_elems());
       if (run_mode(c)) n = std::max(n, (size_t)bwdw_plan(c, true, bf, table).ns * run_w_elems(c));
@@ -333,14 +351,18 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
   const bool t48 = !run && !bf && av && bv && tap_ok(a, d, kBK48);
   const GemmPlan p = fwd_plan(c, run, bf, t48);
   const bool tap = !run && !bf && av && bv && tap_ok(a, d);
+  const bool tapbf = bf && !run && tap_ok(a, d, kBKbf);
   if (p.ns == 1) {
     EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
+    if (tapbf) return by_tile_bf<ConvGatherTapBf<IM2COL_FWD>>(p, a, b, ep, d, st);
     if (bf) return by_tile_bf<ConvGatherBf<IM2COL_FWD>>(p, a, b, ep, d, st);
     if (tap) return by_tile_tap<ConvGatherTap<IM2COL_FWD>>(p, a, b, ep, d, st);
     return by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
-  if (bf)
+  if (tapbf)
+    AX_TRY((by_tile_bf<ConvGatherTapBf<IM2COL_FWD>>(p, a, b, ep, d, st)));
+  else if (bf)
     AX_TRY((by_tile_bf<ConvGatherBf<IM2COL_FWD>>(p, a, b, ep, d, st)));
   else if (tap)
     AX_TRY((by_tile_tap<ConvGatherTap<IM2COL_FWD>>(p, a, b, ep, d, st)));
@@ -395,15 +417,19 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
   const bool t48 = !bf && c.stride == 1 && av && bv && tap_ok(a, d, kBK48);
   const GemmPlan p = bwdd_plan(c, bf, t48);
   const bool tap = !bf && c.stride == 1 && av && bv && tap_ok(a, d);
+  const bool tapbf = bf && tap_ok(a, d, kBKbf);
   if (p.ns == 1) {
     EpiGate ep{dx, c.Cin, gate, c.cg(), 0};
+    if (tapbf) return by_tile_bf<ConvGatherTapBf<IM2COL_T1>>(p, a, b, ep, d, st);
     if (bf) return by_tile_bf<ConvGatherBf<IM2COL_T1>>(p, a, b, ep, d, st);
     if (tap) return by_tile_tap<ConvGatherTap<IM2COL_T1>>(p, a, b, ep, d, st);
     if (c.stride == 1) return by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st);
     return by_tile<ConvGather<IM2COL_TS>>(p, av, bv, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
-  if (bf)
+  if (tapbf)
+    AX_TRY((by_tile_bf<ConvGatherTapBf<IM2COL_T1>>(p, a, b, ep, d, st)));
+  else if (bf)
     AX_TRY((by_tile_bf<ConvGatherBf<IM2COL_T1>>(p, a, b, ep, d, st)));
   else if (tap)
     AX_TRY((by_tile_tap<ConvGatherTap<IM2COL_T1>>(p, a, b, ep, d, st)));
@@ -423,7 +449,7 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
   const bool av = run || bwdw_A_vec(c, x), bv = bwdw_B_vec(c, dy);
   const bool bf = g_bf16 && av && bv;
   const Im2colParams a = run ? run_A(c, x) : bwdw_A(c, x);
-  bool table = !bf && av && bv && table_ok(a, d);
+  bool table = av && bv && table_ok(a, d) && (!bf || d.K % kBKbf == 0);
   GemmPlan p = bwdw_plan(c, run, bf, table);
   if (table && p.kchunk > kMaxTableK) {  // no split count within reach keeps the k range inside the table
     table = false;
@@ -432,7 +458,9 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
   const long slab = (long)d.M * d.N;
   float* out = run ? dwrun : dwf;
   EpiSlab ep{p.ns > 1 ? ws : out, slab, d.N, nullptr};
-  if (bf)
+  if (bf && table)
+    AX_TRY((by_tile_bf<ConvWeightGradTableBf>(p, a, bwdw_B(c, dy), ep, d, st)));
+  else if (bf)
     AX_TRY((by_tile_bf<ConvWeightGradBf>(p, a, bwdw_B(c, dy), ep, d, st)));
   else if (table)
     AX_TRY((by_tile_tap<ConvWeightGradTable>(p, a, bwdw_B(c, dy), ep, d, st)));

@@ -144,6 +144,68 @@ struct BfIm2colRowInner {
   }
 };
 
+// BfDenseRowInner for whole k-tiles (see DenseRowWhole): one add per address, k-tiles past the end clamped.
+template <int ROWS, int BK>
+struct BfDenseRowWhole : BfDenseRowInner<ROWS, BK> {
+  typedef BfDenseRowInner<ROWS, BK> Base;
+  using Base::Base;
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int kc = k0 < kend ? k0 : kend - BK;  // uniform
+    this->pl.off[S] = this->base[S] + (uint32_t)kc * this->ld4;
+  }
+};
+
+// BfIm2colRowInner through the workgroup's pixel table (see Im2colRowTable): whole k-tiles, at most 31 taps.
+template <int ROWS, int BK>
+struct BfIm2colRowTable {
+  static constexpr int QR = ROWS / 4, NU = QR * (BK / 2), NUT = NU / kThreads, NL = 2 * NUT, NA = NL, NS = NUT;
+  static_assert(NU % kThreads == 0 && kThreads % QR == 0, "every unit of a thread shares its row quad");
+  static constexpr bool kRowMajor = false;
+  static constexpr bool kUsesTable = true;
+  static constexpr int LDW = ROWS + 4, LDS_WORDS = (BK / 2) * LDW;
+  typedef Im2colParams Params;
+  BufView v;
+  int tid, rq;
+  uint32_t tapoff, tapmask;
+  const PixelEntry* tbl;
+  int kbase, klast;
+  Offsets<NL, true> pl;
+  AX_HD BfIm2colRowTable(const Params& a, int grp, int tid_, int row0)
+      : v(make_view(a.x, a.bytes)), tid(tid_), tbl(nullptr), kbase(0), klast(0) {
+    rq = tid % QR;
+    const int m = row0 + 4 * rq;
+    const bool in = m < a.kh * a.kw * a.Cg;
+    const TapCoord t = decode_tap(in ? m : 0, a);
+    tapoff = (((uint32_t)t.r * (uint32_t)a.W + (uint32_t)t.s) * (uint32_t)a.Ctot + (uint32_t)t.c +
+              (uint32_t)(grp * a.c_stride_g)) * 4u;
+    tapmask = in ? 1u << (t.r * a.kw + t.s) : 0x80000000u;
+  }
+  static AX_HD void build_table(const Params& g, PixelEntry* table, int kbeg, int kend, int tid) {
+    Im2colRowTable<ROWS, 16>::build_table(g, table, kbeg, kend, tid);
+  }
+  AX_HD void set_table(const PixelEntry* table, int kbeg, int kend) {
+    tbl = table;
+    kbase = kbeg;
+    klast = kend - BK;
+  }
+  template <int S>
+  AX_HD void addr_step(int k0, int kend) {
+    const int kc = k0 < kend ? k0 : klast;  // uniform
+    const PixelEntry pe = tbl[kc - kbase + 2 * ((tid + (S / 2) * kThreads) / QR) + (S & 1)];
+    pl.off[S] = (pe.outside & tapmask) ? kOob : pe.base + tapoff;
+  }
+  AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
+  AX_HD void store_step(int u, uint32_t* lds, const float4* r) const {
+    uint32_t* d = lds + ((tid + u * kThreads) / QR) * LDW + 4 * rq;
+    const float4 a = r[2 * u], b = r[2 * u + 1];
+    d[0] = pack_bf16(a.x, b.x);
+    d[1] = pack_bf16(a.y, b.y);
+    d[2] = pack_bf16(a.z, b.z);
+    d[3] = pack_bf16(a.w, b.w);
+  }
+};
+
 template <class L>
 AX_HD void bf_store_all(const L& l, uint32_t* lds, const float4* r) {
 #pragma unroll
@@ -236,6 +298,12 @@ gemm_bf16_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, 
   AL al(ap, g, tid, m0);
   BL bl(bp, g, tid, n0);
   ep.set_group(g, z);
+  if constexpr (uses_table<AL>::value) {  // launched with (kend - kbeg) * sizeof(PixelEntry) bytes of dynamic LDS
+    extern __shared__ __attribute__((aligned(16))) PixelEntry pixel_table[];
+    AL::build_table(ap, pixel_table, kbeg, kend, tid);
+    al.set_table(pixel_table, kbeg, kend);
+    __syncthreads();
+  }
 
   v16f acc[T::TM][T::TN];
 #pragma unroll

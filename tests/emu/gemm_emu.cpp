@@ -140,9 +140,15 @@ static void emu_gemm_bf(typename AL::Params ap, typename BL::Params bp, Epi ep, 
         for (int t = 0; t < nt; ++t) {
           std::fill(As.begin(), As.end(), 0x7fc07fc0u);  // two bf16 NaNs: an unwritten slot shows up
           std::fill(Bs.begin(), Bs.end(), 0x7fc07fc0u);
+          std::vector<PixelEntry> table;
+          if constexpr (uses_table<AL>::value) {
+            table.assign(kend - kbeg, PixelEntry{0xdeadbeefu, 0u});
+            for (int tid = 0; tid < kThreads; ++tid) AL::build_table(ap, table.data(), kbeg, kend, tid);
+          }
           for (int tid = 0; tid < kThreads; ++tid) {
             AL al(ap, g, tid, m0);
             BL bl(bp, g, tid, n0);
+            if constexpr (uses_table<AL>::value) al.set_table(table.data(), kbeg, kend);
             float4 ra[AL::NL], rb[BL::NL];
             plan_all(al, kbeg + t * T::BK, kend);
             plan_all(bl, kbeg + t * T::BK, kend);
@@ -276,6 +282,13 @@ static void run_case(const Case& cs) {
       EpiBiasAct e{y.data(), c.Cout, bias, 1, og, 0};
       emu_gemm_bf<T, BfGatherF, BfRows, EpiBiasAct>(fwd_A(c, x), fwd_B(c, wf), e, d.M, d.N, d.K, kcf, 1, d.groups);
       check("fwd", nm, y, y_ref);
+      const Im2colParams fa = fwd_A(c, x);
+      if (fa.Cg % T::BK == 0 && c.k * c.k <= 32) {
+        std::fill(y.begin(), y.end(), NAN);
+        emu_gemm_bf<T, BfRowMajor<Im2colKTap<T::BM, T::BK, IM2COL_FWD>, T::BM, T::BK>, BfDenseRowWhole<T::BN, T::BK>,
+                    EpiBiasAct>(fa, fwd_B(c, wf), e, d.M, d.N, d.K, kcf, 1, d.groups);
+        check("fwd_tap", nm, y, y_ref);
+      }
     }
     if (run_mode(c) && c.Cout % 4 == 0) {
       const int run = run_len(c), kc = c.k * c.Cin;
@@ -314,6 +327,13 @@ static void run_case(const Case& cs) {
       emu_gemm_bf<T, BfGatherT, BfRows, EpiGate>(bwdd_A(c, dy), bwdd_B(c, wb), e, d.M, d.N, d.K,
                                                  ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
       check("bwd_data", nm, dx, dx_ref);
+      const Im2colParams ba = bwdd_A(c, dy);
+      if (ba.Cg % T::BK == 0 && c.k * c.k <= 32) {
+        std::fill(dx.begin(), dx.end(), NAN);
+        emu_gemm_bf<T, BfRowMajor<Im2colKTap<T::BM, T::BK, IM2COL_T1>, T::BM, T::BK>, BfDenseRowWhole<T::BN, T::BK>,
+                    EpiGate>(ba, bwdd_B(c, wb), e, d.M, d.N, d.K, d.K, 1, d.groups);
+        check("bwdd_tap", nm, dx, dx_ref);
+      }
     }
     if (bwdw_A_vec(c, x) && bwdw_B_vec(c, dy)) {
       const GemmDims d = bwdw_dims(c);
@@ -330,6 +350,19 @@ static void run_case(const Case& cs) {
           for (long i = 0; i < (long)d.M * d.N; ++i) dwf[(long)g * d.M * d.N + i] += ws[((long)g * nsplit + sp) * d.M * d.N + i];
       snprintf(nm, sizeof nm, "%s/%dx%d/s%d/bf16", cs.name, T::BM, T::BN, nsplit);
       check("bwd_wgt", nm, dwf, dwf_ref);
+      if (d.K % T::BK == 0 && c.k * c.k <= 31 && kchunk % T::BK == 0) {
+        std::fill(ws.begin(), ws.end(), NAN);
+        emu_gemm_bf<T, BfIm2colRowTable<T::BM, T::BK>, BfDenseRowWhole<T::BN, T::BK>, EpiSlab>(
+            bwdw_A(c, x), bwdw_B(c, dy), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
+        std::fill(dwf.begin(), dwf.end(), 0.f);
+        for (int g = 0; g < d.groups; ++g)
+          for (int sp = 0; sp < nsplit; ++sp)
+            for (long i = 0; i < (long)d.M * d.N; ++i) {
+              const float v = ws[((long)g * nsplit + sp) * d.M * d.N + i];
+              if (v == v) dwf[(long)g * d.M * d.N + i] += v;
+            }
+        check("bwd_wgt_tbl", nm, dwf, dwf_ref);
+      }
     }
     delete[] x; delete[] dy; delete[] w; delete[] wf; delete[] wb; delete[] bias;
     g_round_bf = false;
