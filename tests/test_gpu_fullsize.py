@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import synthetic_inputs as S
-from gpu_common import LOSS_RTOL, TENSOR_RTOL, build_pair, cuda, validated_decisions
+from gpu_common import LOSS_RTOL, TENSOR_RTOL, build_pair, cuda, run_step_and_compare, validated_decisions
 from helpers import oracle_spec, rel_l2, to64
 from oracle import alexnet_oracle as O
 
@@ -121,3 +121,17 @@ def test_conv_stack_alone_batch128_sampled(lib):
         assert rel_l2(db.cpu().numpy(), dy.astype(np.float64).sum((0, 2, 3))) <= TENSOR_RTOL
         del x, dy, xp, y, dx
     net.close()
+
+
+@pytest.mark.timeout(900)
+def test_full_alexnet_bf16_step_batch256(lib):
+    """Workload 4: the full step at batch 256 with bf16 products (fp32 accumulation, fp32 state), in the
+    launch configuration `bench.py --precision bf16 --batch 256` times, against the float64 oracle at the
+    2e-2 bar of that configuration; gates and pooling winners validated as in the fp32 test, with the
+    margin a bf16 forward pass needs (3e-2 of the tensor's rms)."""
+    errs = {}
+    loss = run_step_and_compare(lib, S.ALEXNET, 256, seed=S.SEED_BASE + 4, bias=0.0, std=0.01, use_raw=True,
+                                precision=1, direct=False, loss_rtol=1e-2, tol=2e-2, tau=3e-2, max_frac=3e-2,
+                                report=errs)
+    print("bf16 batch 256: loss", loss, "worst gradient rel-L2", max(errs.values()), flush=True)
+    assert abs(loss - np.log(1000)) < 0.05

@@ -58,6 +58,11 @@ def test_bad_arguments_are_reported_not_crashed(B):
     with pytest.raises(B.AlexNetError):
         B.query(cfg)
     B.query(B.make_config(S.MINI, 4, precision=1))  # bf16 products are a valid configuration
+    # maximum sizes: every tensor must stay below 2 GiB (32-bit byte offsets in the kernels)
+    B.query(B.make_config(S.ALEXNET, 1024))          # conv1 activations: 1.19 GB
+    with pytest.raises(B.AlexNetError) as e:
+        B.query(B.make_config(S.ALEXNET, 2048))      # 2.38 GB
+    assert e.value.code == B.ESHAPE and "2 GiB" in str(e.value)
     cfg = B.make_config(S.MINI, 4, precision=2)
     with pytest.raises(B.AlexNetError) as e:
         B.query(cfg)
