@@ -906,29 +906,40 @@ int launch_colsum(const float* m, long rows, int cols, float* out, float* ws, hi
     hipLaunchKernelGGL((colsum_stage1<false>), dim3(ceil_div(cols, 64), nparts), dim3(256), 0, st, m, rows, cols, rpb,
                        ws);
   AX_LAUNCH_CHECK();
-  hipLaunchKernelGGL(colsum_stage2, dim3(ceil_div(cols, 64)), dim3(256), 0, st, ws, nparts, cols, out);
+  if (cols % 4 == 0)
+    hipLaunchKernelGGL(colsum_finish_kernel, dim3(cols / 4), dim3(256), 0, st, ws, nparts, cols, out);
+  else
+    hipLaunchKernelGGL(colsum_stage2, dim3(ceil_div(cols, 64)), dim3(256), 0, st, ws, nparts, cols, out);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
 
 // out[g][i] = sum_s ws[g*nsplit + s][i]  (split-k partial slabs)
-__global__ void reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int groups,
-                                    float* __restrict__ out) {
+__global__ void __launch_bounds__(256)
+reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int groups, float* __restrict__ out) {
+  // 64 consecutive elements per workgroup; four lanes per element take every fourth slab, then add up in a
+  // fixed order
+  __shared__ float sh[4][64];
   const size_t total = slab * groups;
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= total) return;
-  const size_t g = i / slab, e = i - g * slab;
-  const float* p = ws + g * nsplit * slab + e;
+  const int el = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const size_t i = (size_t)blockIdx.x * 64 + el;
   float s = 0.f;
-  for (int k = 0; k < nsplit; ++k) s += p[(size_t)k * slab];
-  out[i] = s;
+  if (i < total) {
+    const size_t g = i / slab, e = i - g * slab;
+    const float* p = ws + g * nsplit * slab + e;
+#pragma unroll 8
+    for (int k = part; k < nsplit; k += 4) s += p[(size_t)k * slab];
+  }
+  sh[part][el] = s;
+  __syncthreads();
+  if (part == 0 && i < total) out[i] = (sh[0][el] + sh[1][el]) + (sh[2][el] + sh[3][el]);
 }
 int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, float* out, hipStream_t st) {
   const size_t total = (size_t)slab * groups;
   if (!total) return ALEXNET_OK;
   KernelScope ks("reduce_slabs", 0, (double)total * 4.0 * (nsplit + 1), st);
-  hipLaunchKernelGGL(reduce_slabs_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, ws, nsplit, (size_t)slab,
-                     groups, out);
+  hipLaunchKernelGGL(reduce_slabs_kernel, dim3(grid_for(total, 64)), dim3(256), 0, st, ws, nsplit, (size_t)slab, groups,
+                     out);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
