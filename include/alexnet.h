@@ -22,6 +22,9 @@
  *    conv1..conv5, fc6..fc8, then every bias in the same layer order.  The
  *    library keeps its own internal layout inside d_params / d_momentum; use
  *    alexnet_set_params / alexnet_get_params to convert.
+ *  - alexnet_train_step runs part of the update on a stream of the handle's
+ *    own, forked from and joined back into `stream` by events inside the
+ *    call: for the caller everything is ordered on `stream` as usual.
  *  - Calls on one handle, or on two handles passed to
  *    alexnet_average_replicas, must be ordered by the caller (same stream or
  *    events).  Preprocessing into slot s may overlap a training step reading

@@ -124,6 +124,10 @@ struct alexnet {
   int32_t* err_flag;
   size_t gemm_ws_floats, colsum_ws_floats_;
   int flat;  // flatten size feeding fc6
+  // The dense layers hold 96 % of the parameters and finish their backward pass first: their update, which is
+  // bound by memory bandwidth, runs on this stream under the convolution backward pass, which is not.
+  hipStream_t upd_stream;
+  hipEvent_t ev_fc_done, ev_upd_done;
 };
 
 static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
@@ -324,7 +328,17 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
   return ALEXNET_OK;
 }
 
-static int run_backward(alexnet* n, const float* in, hipStream_t st) {
+static int update_range(alexnet* n, size_t begin, size_t end, hipStream_t st) {
+  const alexnet_config_t& c = n->cfg;
+  if (end <= begin) return ALEXNET_OK;
+  const size_t decayed = n->n_weights > begin ? std::min(n->n_weights, end) - begin : 0;
+  return launch_sgd_update(n->params + begin, n->mom + begin, n->grads + begin, end - begin, decayed, c.lr, c.momentum,
+                           c.weight_decay, st);
+}
+
+// early_update: also start the update of the dense-layer weights on the side stream as soon as the dense
+// layers' backward pass is done (the caller updates the rest and joins, see alexnet_train_step)
+static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_update = false) {
   const alexnet_config_t& c = n->cfg;
   set_gemm_precision(c.precision);
   // dense layers, last to first
@@ -364,6 +378,14 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
     if (s.lrn && !s.fused())
       AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
                             c.lrn_alpha, c.lrn_beta, 1, st));
+    if (early_update && i == kStages - 1) {
+      // fork here, behind the last stage's pooling adjoint: that kernel is bound by bandwidth like the update
+      // and would be starved by it, while the GEMMs that follow are not
+      AX_HIP(hipEventRecord(n->ev_fc_done, st));
+      AX_HIP(hipStreamWaitEvent(n->upd_stream, n->ev_fc_done, 0));
+      AX_TRY(update_range(n, n->fc[0].w_off, n->n_weights, n->upd_stream));
+      AX_HIP(hipEventRecord(n->ev_upd_done, n->upd_stream));
+    }
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
@@ -381,13 +403,14 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st) {
   return ALEXNET_OK;
 }
 
-static int fwd_bwd(alexnet* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss, hipStream_t st) {
+static int fwd_bwd(alexnet* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss, hipStream_t st,
+                   bool early_update = false) {
   const alexnet_config_t& c = n->cfg;
   AX_TRY(run_forward(n, n->input[slot], true, step, st));
   Dense& last = n->fc[kFc - 1];
   AX_TRY(launch_softmax_xent(last.act, d_labels, c.batch, last.out, 0, last.dz, n->row_loss, n->err_flag, st));
   AX_TRY(launch_mean_loss(n->row_loss, c.batch, d_loss, st));
-  return run_backward(n, n->input[slot], st);
+  return run_backward(n, n->input[slot], st, early_update);
 }
 
 static int apply_update(alexnet* n, hipStream_t st) {
@@ -515,15 +538,33 @@ int alexnet_create(const alexnet_config_t* cfg, void* d_params, void* d_momentum
     n->mom = (float*)d_momentum;
     r = launch_fill_bytes(d_workspace, n->ws_bytes, S(stream));
   }
+  if (r == ALEXNET_OK) {
+    hipError_t e = hipStreamCreateWithFlags(&n->upd_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_fc_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_upd_done, hipEventDisableTiming);
+    if (e != hipSuccess) {
+      set_error("alexnet_create: %s", hipGetErrorString(e));
+      r = ALEXNET_EHIP;
+    }
+  }
   if (r != ALEXNET_OK) {
-    delete n;
+    alexnet_destroy(n);
     return r;
   }
   *out = n;
   return ALEXNET_OK;
 }
 
-void alexnet_destroy(alexnet_t* net) { delete net; }
+void alexnet_destroy(alexnet_t* net) {
+  if (!net) return;
+  if (net->upd_stream) {
+    (void)hipStreamSynchronize(net->upd_stream);
+    (void)hipStreamDestroy(net->upd_stream);
+  }
+  if (net->ev_fc_done) (void)hipEventDestroy(net->ev_fc_done);
+  if (net->ev_upd_done) (void)hipEventDestroy(net->ev_upd_done);
+  delete net;
+}
 
 int alexnet_preprocess(alexnet_t* n, const uint8_t* d_raw, const float* d_mean, uint64_t step, int32_t slot,
                        void* stream) {
@@ -570,8 +611,16 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
                        void* stream) {
   REQUIRE(n && d_labels && d_loss, ALEXNET_EINVAL, "alexnet_train_step: null argument");
   REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_train_step: slot must be 0 or 1");
-  AX_TRY(fwd_bwd(n, slot, d_labels, step, d_loss, S(stream)));
-  return apply_update(n, S(stream));
+  // the dense-layer weights start at a 16-byte boundary of the flat vector in every AlexNet-like shape; if not,
+  // one update at the end
+  const size_t fc_begin = n->fc[0].w_off;
+  const bool early = fc_begin % 4 == 0 && n->n_weights % 4 == 0;
+  AX_TRY(fwd_bwd(n, slot, d_labels, step, d_loss, S(stream), early));
+  if (!early) return apply_update(n, S(stream));
+  AX_TRY(update_range(n, 0, fc_begin, S(stream)));              // convolution weights
+  AX_TRY(update_range(n, n->n_weights, n->n_params, S(stream)));  // all biases
+  AX_HIP(hipStreamWaitEvent(S(stream), n->ev_upd_done, 0));      // join the dense-layer update
+  return ALEXNET_OK;
 }
 
 int alexnet_forward(alexnet_t* n, const float* d_input_nchw, float* d_probs, void* stream) {

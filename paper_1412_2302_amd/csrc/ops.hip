@@ -947,41 +947,46 @@ int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, floa
 // ---------------------------------------------------------------- update ---
 // v <- mu v - lr (g + wd w);  w <- w + v.  Elements below n_decay are weights
 // (decayed), the rest are biases (not decayed).
-__global__ void sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g, size_t n,
-                                  size_t n_decay, float lr, float mu, float wd) {
-  const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t i = q * 4;
-  if (i + 3 < n) {
-    float4 w4 = *reinterpret_cast<float4*>(w + i);
-    float4 v4 = *reinterpret_cast<float4*>(v + i);
-    const float4 g4 = *reinterpret_cast<const float4*>(g + i);
-    const float d0 = i + 0 < n_decay ? wd : 0.f, d1 = i + 1 < n_decay ? wd : 0.f;
-    const float d2 = i + 2 < n_decay ? wd : 0.f, d3 = i + 3 < n_decay ? wd : 0.f;
-    v4.x = mu * v4.x - lr * (g4.x + d0 * w4.x);
-    v4.y = mu * v4.y - lr * (g4.y + d1 * w4.y);
-    v4.z = mu * v4.z - lr * (g4.z + d2 * w4.z);
-    v4.w = mu * v4.w - lr * (g4.w + d3 * w4.w);
-    w4.x += v4.x;
-    w4.y += v4.y;
-    w4.z += v4.z;
-    w4.w += v4.w;
-    *reinterpret_cast<float4*>(v + i) = v4;
-    *reinterpret_cast<float4*>(w + i) = w4;
-  } else {
-    for (size_t j = i; j < n; ++j) {
-      const float d = j < n_decay ? wd : 0.f;
-      const float vn = mu * v[j] - lr * (g[j] + d * w[j]);
-      v[j] = vn;
-      w[j] += vn;
+__global__ void __launch_bounds__(256)
+sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g, size_t n, size_t n_decay,
+                  float lr, float mu, float wd) {
+  // grid-stride over groups of four: a bounded number of workgroups, so that a GEMM running beside this
+  // kernel on another stream still finds room on every CU
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q * 4 < n; q += stride) {
+    const size_t i = q * 4;
+    if (i + 3 < n) {
+      float4 w4 = *reinterpret_cast<float4*>(w + i);
+      float4 v4 = *reinterpret_cast<float4*>(v + i);
+      const float4 g4 = *reinterpret_cast<const float4*>(g + i);
+      const float d0 = i + 0 < n_decay ? wd : 0.f, d1 = i + 1 < n_decay ? wd : 0.f;
+      const float d2 = i + 2 < n_decay ? wd : 0.f, d3 = i + 3 < n_decay ? wd : 0.f;
+      v4.x = mu * v4.x - lr * (g4.x + d0 * w4.x);
+      v4.y = mu * v4.y - lr * (g4.y + d1 * w4.y);
+      v4.z = mu * v4.z - lr * (g4.z + d2 * w4.z);
+      v4.w = mu * v4.w - lr * (g4.w + d3 * w4.w);
+      w4.x += v4.x;
+      w4.y += v4.y;
+      w4.z += v4.z;
+      w4.w += v4.w;
+      *reinterpret_cast<float4*>(v + i) = v4;
+      *reinterpret_cast<float4*>(w + i) = w4;
+    } else {
+      for (size_t j = i; j < n; ++j) {
+        const float d = j < n_decay ? wd : 0.f;
+        v[j] = mu * v[j] - lr * (g[j] + d * w[j]);
+        w[j] += v[j];
+      }
     }
   }
 }
+constexpr unsigned kUpdateMaxBlocks = 1024;  // 4 per CU
 int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
                       hipStream_t st) {
   if (!n) return ALEXNET_OK;
   KernelScope ks("sgd_update", 0, (double)n * 20.0, st);
-  hipLaunchKernelGGL(sgd_update_kernel, dim3(grid_for((n + 3) / 4, 256)), dim3(256), 0, st, w, v, g, n, n_decay, lr,
-                     mu, wd);
+  const unsigned blocks = std::min<unsigned>(grid_for((n + 3) / 4, 256), kUpdateMaxBlocks);
+  hipLaunchKernelGGL(sgd_update_kernel, dim3(blocks), dim3(256), 0, st, w, v, g, n, n_decay, lr, mu, wd);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
