@@ -127,7 +127,7 @@ struct alexnet {
   // The dense layers hold 96 % of the parameters and finish their backward pass first: their update, which is
   // bound by memory bandwidth, runs on this stream under the convolution backward pass, which is not.
   hipStream_t upd_stream;
-  hipEvent_t ev_fc_done, ev_upd_done;
+  hipEvent_t ev_fc_done, ev_upd_done, ev_step_begin, ev_wb_done;
 };
 
 static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
@@ -395,7 +395,11 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     if (i > 0) {
       ProfContext pc(s.lab[3]);
       Stage& prev = n->st[i - 1];
-      AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
+      if (early_update) {  // the side stream re-packed the weights during the forward pass
+        if (i == kStages - 1) AX_HIP(hipStreamWaitEvent(st, n->ev_wb_done, 0));
+      } else {
+        AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
+      }
       AX_TRY(launch_conv_bwd_data(s.g, s.dact, n->params + s.w_off, s.wb, s.wphase, prev.plain() ? prev.act : nullptr,
                                   prev.d_out, n->gemm_ws, st));
     }
@@ -542,6 +546,8 @@ int alexnet_create(const alexnet_config_t* cfg, void* d_params, void* d_momentum
     hipError_t e = hipStreamCreateWithFlags(&n->upd_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_fc_done, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_upd_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_step_begin, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_wb_done, hipEventDisableTiming);
     if (e != hipSuccess) {
       set_error("alexnet_create: %s", hipGetErrorString(e));
       r = ALEXNET_EHIP;
@@ -563,6 +569,8 @@ void alexnet_destroy(alexnet_t* net) {
   }
   if (net->ev_fc_done) (void)hipEventDestroy(net->ev_fc_done);
   if (net->ev_upd_done) (void)hipEventDestroy(net->ev_upd_done);
+  if (net->ev_step_begin) (void)hipEventDestroy(net->ev_step_begin);
+  if (net->ev_wb_done) (void)hipEventDestroy(net->ev_wb_done);
   delete net;
 }
 
@@ -615,6 +623,18 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
   // one update at the end
   const size_t fc_begin = n->fc[0].w_off;
   const bool early = fc_begin % 4 == 0 && n->n_weights % 4 == 0;
+  if (early) {
+    // the backward-data packing of the convolution weights depends on the weights only: it runs on the side
+    // stream under the forward pass
+    AX_HIP(hipEventRecord(n->ev_step_begin, S(stream)));
+    AX_HIP(hipStreamWaitEvent(n->upd_stream, n->ev_step_begin, 0));
+    for (int i = 1; i < kStages; ++i) {
+      Stage& s = n->st[i];
+      ProfContext pc(s.lab[3]);
+      AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, n->upd_stream));
+    }
+    AX_HIP(hipEventRecord(n->ev_wb_done, n->upd_stream));
+  }
   AX_TRY(fwd_bwd(n, slot, d_labels, step, d_loss, S(stream), early));
   if (!early) return apply_update(n, S(stream));
   AX_TRY(update_range(n, 0, fc_begin, S(stream)));              // convolution weights
