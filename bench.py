@@ -28,7 +28,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # Memory-side traffic of the GEMM launches of one fp32 batch-128 step, bytes per launch (23 launches):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB elementwise copy, from
 # profiles/train_step_alexnet_b128_fp32_counters.txt.  Not measured for other configurations.
-GEMM_TRAFFIC_FP32_B128 = 420073655
+GEMM_TRAFFIC_FP32_B128 = 422544344
 PEAK_HBM_GBS = 8000.0
 
 
