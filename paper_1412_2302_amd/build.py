@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libalexnet_hip.so")
-SOURCES = ["alexnet.hip", "conv_gemm.hip", "ops.hip", "loader.hip"]
+SOURCES = ["alexnet.hip", "conv_gemm.hip", "ops.hip", "winograd.hip", "loader.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
     # packed fp32 VALU ops are kept off on the test machines

@@ -79,6 +79,10 @@ struct Stage {
   size_t w_off, b_off;  // offsets into the flat parameter vector
   float *act, *lrn_out, *pool_out, *dact, *d_lrn, *d_out, *wb;
   float* wphase;        // weights regrouped by phase for a strided backward-data pass (null when not used)
+  // 3x3 unit-stride stages run through the F(4x4, 3x3) transforms: the transformed input of the forward pass
+  // (kept for the weight gradient) and the transformed taps of the forward and backward-data passes
+  bool wino;
+  float *wino_v, *wino_u, *wino_ub;
   float *wrun, *dwrun;  // run-mode copies of the weights and their gradient (null when not used)
   uint8_t* slot;
   char lab[4][16];  // profiling labels: stage, .fwd, .bwd_w, .bwd_x
@@ -121,14 +125,26 @@ struct alexnet {
   float* input[kSlots];
   int32_t *crop_x[kSlots], *crop_y[kSlots], *flip[kSlots];
   float *gemm_ws, *colsum_ws, *row_loss, *scratch_x, *scratch_y, *scratch_w[3];
+  float *wino_a, *wino_m, *wino_du;  // transformed operand / product / tap-gradient scratch shared by the stages
   int32_t* err_flag;
   size_t gemm_ws_floats, colsum_ws_floats_;
   int flat;  // flatten size feeding fc6
+  int upd_fork_stage;  // the dense-layer update starts on the side stream behind this stage's pooling adjoint
   // The dense layers hold 96 % of the parameters and finish their backward pass first: their update, which is
   // bound by memory bandwidth, runs on this stream under the convolution backward pass, which is not.
   hipStream_t upd_stream;
-  hipEvent_t ev_fc_done, ev_upd_done, ev_step_begin, ev_wb_done;
+  hipEvent_t ev_fc_done, ev_upd_done, ev_step_begin, ev_wb_done, ev_u_done;
 };
+
+// F(4x4, 3x3) pays when the 4x4 tiles cover the output without much waste (2.6x fewer multiplies at 13 x 13);
+// the environment variable ALEXNET_DIRECT_CONV=1 keeps every stage on the direct implicit GEMM.
+static bool use_winograd(const alexnet_config_t& c, const ConvGeom& g) {
+  if (c.precision != ALEXNET_PRECISION_FP32 || !wino_ok(g)) return false;
+  const char* e = getenv("ALEXNET_DIRECT_CONV");
+  if (e && e[0] == '1') return false;
+  const double covered = (double)g.Ho * g.Wo / (16.0 * ((g.Ho + 3) / 4) * ((g.Wo + 3) / 4));
+  return 4.0 * covered >= 1.5;
+}
 
 static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
   const alexnet_config_t& c = *cfg;
@@ -188,6 +204,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
   }
   n->flat = C * H * W;
   int in = n->flat;
+  n->upd_fork_stage = kStages - 1;
   for (int j = 0; j < kFc; ++j) {
     if (c.fc[j] <= 0) {
       set_error("fc width must be positive");
@@ -220,7 +237,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     n->crop_y[s] = a.take<int32_t>(c.batch);
     n->flip[s] = a.take<int32_t>(c.batch);
   }
-  size_t max_in = in_elems, max_out = 0, max_w = 0, gws = 0, cws = 0;
+  size_t max_in = in_elems, max_out = 0, max_w = 0, gws = 0, cws = 0, wscr = 0, wdu = 0;
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
     const size_t ae = s.act_elems(), oe = s.out_elems();
@@ -237,6 +254,15 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.wphase = conv_phase_mode(s.g) ? a.take<float>(conv_phase_w_floats(s.g)) : nullptr;
     s.wrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     s.dwrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
+    s.wino = use_winograd(c, s.g) && s.w_off % 4 == 0 && s.b_off % 4 == 0;
+    s.wino_v = s.wino ? a.take<float>(wino_v_floats(s.g)) : nullptr;
+    s.wino_u = s.wino ? a.take<float>(wino_u_floats(s.g)) : nullptr;
+    s.wino_ub = s.wino ? a.take<float>(wino_u_floats(s.g)) : nullptr;
+    if (s.wino) {
+      wscr = std::max(wscr, wino_scratch_floats(s.g));
+      wdu = std::max(wdu, wino_u_floats(s.g));
+      gws = std::max(gws, wino_gemm_ws_floats(s.g));
+    }
     max_in = std::max(max_in, (size_t)s.g.in_elems());
     max_out = std::max(max_out, ae);
     max_w = std::max(max_w, (size_t)s.g.w_elems());
@@ -246,6 +272,19 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     cws = std::max(cws, colsum_ws_floats(s.g.P(), s.g.Cout));
     if (s.lrn && s.pool) cws = std::max(cws, lrn_part_floats(s.g.Cout));
   }
+  {
+    // the dense-layer update shares the chip best with the largest direct convolution of the backward pass:
+    // the transformed 3x3 stages move several times their activations and compete with it for bandwidth
+    double best = -1;
+    for (int i = 1; i < kStages; ++i) {
+      const Stage& s = n->st[i];
+      const double fl = (double)s.g.P() * s.g.Cout * s.g.cg() * s.g.k * s.g.k;
+      if (!s.wino && fl > best) {
+        best = fl;
+        n->upd_fork_stage = i;
+      }
+    }
+  }
   for (int j = 0; j < kFc; ++j) {
     Dense& f = n->fc[j];
     f.act = a.take<float>((size_t)c.batch * f.out);
@@ -254,6 +293,9 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     cws = std::max(cws, colsum_ws_floats(c.batch, f.out));
   }
   n->grads = a.take<float>(n->n_params);
+  n->wino_a = wscr ? a.take<float>(wscr) : nullptr;
+  n->wino_m = wscr ? a.take<float>(wscr) : nullptr;
+  n->wino_du = wdu ? a.take<float>(wdu) : nullptr;
   n->gemm_ws = a.take<float>(gws);
   n->gemm_ws_floats = gws;
   n->colsum_ws = a.take<float>(cws);
@@ -280,17 +322,57 @@ static inline bool aligned256(const void* p) { return ((uintptr_t)p & 255) == 0;
 
 static uint32_t drop_thresh(float p) { return (uint32_t)floor((double)p * (double)(1 << 24)); }
 
+// ---- one convolution stage, by the F(4x4, 3x3) path when the stage has one and the tensors allow 16-byte access ----
+static bool wino_usable(const Stage& s, const void* a, const void* b, const void* c, const void* d = nullptr) {
+  return s.wino && aligned16(a) && aligned16(b) && aligned16(c) && aligned16(d);
+}
+// taps_ready: s.wino_u already holds the transform of wf
+static int stage_fwd(alexnet* n, Stage& s, const float* x, const float* wf, const float* bias, int relu, float* y,
+                     bool taps_ready, hipStream_t st) {
+  if (wino_usable(s, x, wf, y, bias)) {
+    if (!taps_ready) AX_TRY(launch_wino_filter(s.g, wf, s.wino_u, st));
+    return launch_wino_fwd(s.g, x, s.wino_u, bias, relu, y, s.wino_v, n->wino_m, n->gemm_ws, st);
+  }
+  if (s.wrun) AX_TRY(launch_conv_run_pack(s.g, wf, s.wrun, st));
+  return launch_conv_fwd(s.g, x, wf, s.wrun, bias, relu, y, n->gemm_ws, st);
+}
+// have_v: s.wino_v already holds the transform of x (the forward pass of the same minibatch left it there)
+static int stage_bwd_weight(alexnet* n, Stage& s, const float* x, const float* dy, float* dwf, bool have_v,
+                            hipStream_t st) {
+  if (wino_usable(s, x, dy, dwf)) {
+    if (!have_v) AX_TRY(launch_wino_input(s.g, x, s.wino_v, st));
+    return launch_wino_bwd_weight(s.g, s.wino_v, dy, dwf, n->wino_a, n->wino_du, n->gemm_ws, st);
+  }
+  return launch_conv_bwd_weight(s.g, x, dy, dwf, s.dwrun, n->gemm_ws, st);
+}
+// taps_ready: s.wino_ub already holds the transform of wb
+static int stage_bwd_data(alexnet* n, Stage& s, const float* dy, const float* wf, const float* wb, float* wphase,
+                          const float* gate, float* dx, bool taps_ready, hipStream_t st) {
+  if (wino_usable(s, dy, wb, dx, gate)) {
+    if (!taps_ready) AX_TRY(launch_wino_filter_bwd(s.g, wb, s.wino_ub, st));
+    return launch_wino_bwd_data(s.g, dy, s.wino_ub, gate, dx, n->wino_a, n->wino_m, n->gemm_ws, st);
+  }
+  return launch_conv_bwd_data(s.g, dy, wf, wb, wphase, gate, dx, n->gemm_ws, st);
+}
+
 // --------------------------------------------------------------- passes ------
-static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, hipStream_t st) {
+// taps_ready: recorded on another stream once every stage's transformed forward taps are in place (null: they
+// are made here)
+static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, hipStream_t st,
+                       hipEvent_t taps_ready = nullptr) {
   const alexnet_config_t& c = n->cfg;
   set_gemm_precision(c.precision);
   const float* h = in;
+  bool waited = false;
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
     {
       ProfContext pc(s.lab[1]);
-      if (s.wrun) AX_TRY(launch_conv_run_pack(s.g, n->params + s.w_off, s.wrun, st));
-      AX_TRY(launch_conv_fwd(s.g, h, n->params + s.w_off, s.wrun, n->params + s.b_off, 1, s.act, n->gemm_ws, st));
+      if (s.wino && taps_ready && !waited) {
+        AX_HIP(hipStreamWaitEvent(st, taps_ready, 0));
+        waited = true;
+      }
+      AX_TRY(stage_fwd(n, s, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, taps_ready != nullptr, st));
     }
     ProfContext pc(s.lab[0]);
     h = s.act;
@@ -378,9 +460,9 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     if (s.lrn && !s.fused())
       AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
                             c.lrn_alpha, c.lrn_beta, 1, st));
-    if (early_update && i == kStages - 1) {
-      // fork here, behind the last stage's pooling adjoint: that kernel is bound by bandwidth like the update
-      // and would be starved by it, while the GEMMs that follow are not
+    if (early_update && i == n->upd_fork_stage) {
+      // fork here, behind this stage's pooling adjoint: that kernel is bound by bandwidth like the update
+      // and would be starved by it, while the direct-convolution GEMMs that follow are not
       AX_HIP(hipEventRecord(n->ev_fc_done, st));
       AX_HIP(hipStreamWaitEvent(n->upd_stream, n->ev_fc_done, 0));
       AX_TRY(update_range(n, n->fc[0].w_off, n->n_weights, n->upd_stream));
@@ -389,7 +471,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
-      AX_TRY(launch_conv_bwd_weight(s.g, x, s.dact, n->grads + s.w_off, s.dwrun, n->gemm_ws, st));
+      AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st));
       if (!bias_done) AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
     }
     if (i > 0) {
@@ -400,8 +482,8 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
       } else {
         AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
       }
-      AX_TRY(launch_conv_bwd_data(s.g, s.dact, n->params + s.w_off, s.wb, s.wphase, prev.plain() ? prev.act : nullptr,
-                                  prev.d_out, n->gemm_ws, st));
+      AX_TRY(stage_bwd_data(n, s, s.dact, n->params + s.w_off, s.wb, s.wphase, prev.plain() ? prev.act : nullptr,
+                            prev.d_out, early_update, st));
     }
   }
   return ALEXNET_OK;
@@ -410,7 +492,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
 static int fwd_bwd(alexnet* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss, hipStream_t st,
                    bool early_update = false) {
   const alexnet_config_t& c = n->cfg;
-  AX_TRY(run_forward(n, n->input[slot], true, step, st));
+  AX_TRY(run_forward(n, n->input[slot], true, step, st, early_update ? n->ev_u_done : nullptr));
   Dense& last = n->fc[kFc - 1];
   AX_TRY(launch_softmax_xent(last.act, d_labels, c.batch, last.out, 0, last.dz, n->row_loss, n->err_flag, st));
   AX_TRY(launch_mean_loss(n->row_loss, c.batch, d_loss, st));
@@ -548,6 +630,7 @@ int alexnet_create(const alexnet_config_t* cfg, void* d_params, void* d_momentum
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_upd_done, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_step_begin, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_wb_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_u_done, hipEventDisableTiming);
     if (e != hipSuccess) {
       set_error("alexnet_create: %s", hipGetErrorString(e));
       r = ALEXNET_EHIP;
@@ -571,6 +654,7 @@ void alexnet_destroy(alexnet_t* net) {
   if (net->ev_upd_done) (void)hipEventDestroy(net->ev_upd_done);
   if (net->ev_step_begin) (void)hipEventDestroy(net->ev_step_begin);
   if (net->ev_wb_done) (void)hipEventDestroy(net->ev_wb_done);
+  if (net->ev_u_done) (void)hipEventDestroy(net->ev_u_done);
   delete net;
 }
 
@@ -628,10 +712,17 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
     // stream under the forward pass
     AX_HIP(hipEventRecord(n->ev_step_begin, S(stream)));
     AX_HIP(hipStreamWaitEvent(n->upd_stream, n->ev_step_begin, 0));
+    for (int i = 0; i < kStages; ++i) {  // transformed taps of the forward pass first: it needs them soonest
+      Stage& s = n->st[i];
+      ProfContext pc(s.lab[1]);
+      if (s.wino) AX_TRY(launch_wino_filter(s.g, n->params + s.w_off, s.wino_u, n->upd_stream));
+    }
+    AX_HIP(hipEventRecord(n->ev_u_done, n->upd_stream));
     for (int i = 1; i < kStages; ++i) {
       Stage& s = n->st[i];
       ProfContext pc(s.lab[3]);
       AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, n->upd_stream));
+      if (s.wino) AX_TRY(launch_wino_filter_bwd(s.g, s.wb, s.wino_ub, n->upd_stream));
     }
     AX_HIP(hipEventRecord(n->ev_wb_done, n->upd_stream));
   }
@@ -822,22 +913,21 @@ int alexnet_conv_forward_nhwc(alexnet_t* n, int32_t layer, const float* x, const
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(x && wf && y, ALEXNET_EINVAL, "alexnet_conv_forward_nhwc: null argument");
-  if (s->wrun) AX_TRY(launch_conv_run_pack(s->g, wf, s->wrun, S(stream)));
-  return launch_conv_fwd(s->g, x, wf, s->wrun, b, relu, y, n->gemm_ws, S(stream));
+  return stage_fwd(n, *s, x, wf, b, relu, y, false, S(stream));
 }
 int alexnet_conv_backward_data_nhwc(alexnet_t* n, int32_t layer, const float* dy, const float* wf, const float* wb,
                                     float* dx, void* stream) {
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(dy && wb && dx, ALEXNET_EINVAL, "alexnet_conv_backward_data_nhwc: null argument");
-  return launch_conv_bwd_data(s->g, dy, wf, wb, wf ? s->wphase : nullptr, nullptr, dx, n->gemm_ws, S(stream));
+  return stage_bwd_data(n, *s, dy, wf, wb, wf ? s->wphase : nullptr, nullptr, dx, false, S(stream));
 }
 int alexnet_conv_backward_weight_nhwc(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dwf,
                                       float* db, void* stream) {
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(x && dy && dwf, ALEXNET_EINVAL, "alexnet_conv_backward_weight_nhwc: null argument");
-  AX_TRY(launch_conv_bwd_weight(s->g, x, dy, dwf, s->dwrun, n->gemm_ws, S(stream)));
+  AX_TRY(stage_bwd_weight(n, *s, x, dy, dwf, false, S(stream)));
   if (db) AX_TRY(launch_colsum(dy, s->g.P(), s->g.Cout, db, n->colsum_ws, S(stream)));
   return ALEXNET_OK;
 }
@@ -849,8 +939,7 @@ int alexnet_conv_forward(alexnet_t* n, int32_t layer, const float* x, const floa
   const ConvGeom& g = s->g;
   AX_TRY(launch_nchw_to_nhwc(x, n->scratch_x, g.B, g.Cin, g.H, g.W, S(stream)));
   AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
-  if (s->wrun) AX_TRY(launch_conv_run_pack(g, n->scratch_w[0], s->wrun, S(stream)));
-  AX_TRY(launch_conv_fwd(g, n->scratch_x, n->scratch_w[0], s->wrun, b, relu, n->scratch_y, n->gemm_ws, S(stream)));
+  AX_TRY(stage_fwd(n, *s, n->scratch_x, n->scratch_w[0], b, relu, n->scratch_y, false, S(stream)));
   return launch_nhwc_to_nchw(n->scratch_y, y, g.B, g.Cout, g.Ho, g.Wo, S(stream));
 }
 int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, const float* w, float* dx,
@@ -862,8 +951,8 @@ int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, con
   AX_TRY(launch_nchw_to_nhwc(dy, n->scratch_y, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
   AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
   AX_TRY(launch_conv_weight_wb(n->scratch_w[0], n->scratch_w[1], g.Cout, g.cg(), g.k, g.groups, S(stream)));
-  AX_TRY(launch_conv_bwd_data(g, n->scratch_y, n->scratch_w[0], n->scratch_w[1], s->wphase, nullptr, n->scratch_x,
-                              n->gemm_ws, S(stream)));
+  AX_TRY(stage_bwd_data(n, *s, n->scratch_y, n->scratch_w[0], n->scratch_w[1], s->wphase, nullptr, n->scratch_x, false,
+                        S(stream)));
   return launch_nhwc_to_nchw(n->scratch_x, dx, g.B, g.Cin, g.H, g.W, S(stream));
 }
 int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dw, float* db,
@@ -874,7 +963,7 @@ int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, co
   const ConvGeom& g = s->g;
   AX_TRY(launch_nchw_to_nhwc(x, n->scratch_x, g.B, g.Cin, g.H, g.W, S(stream)));
   AX_TRY(launch_nchw_to_nhwc(dy, n->scratch_y, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
-  AX_TRY(launch_conv_bwd_weight(g, n->scratch_x, n->scratch_y, n->scratch_w[2], s->dwrun, n->gemm_ws, S(stream)));
+  AX_TRY(stage_bwd_weight(n, *s, n->scratch_x, n->scratch_y, n->scratch_w[2], false, S(stream)));
   AX_TRY(launch_conv_weight_pack(n->scratch_w[2], dw, g.Cout, g.cg(), g.k, g.groups, 1, S(stream)));
   if (db) AX_TRY(launch_colsum(n->scratch_y, g.P(), g.Cout, db, n->colsum_ws, S(stream)));
   return ALEXNET_OK;

@@ -29,8 +29,28 @@ bool conv_phase_mode(const ConvGeom& c);
 size_t conv_phase_w_floats(const ConvGeom& c);
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, const float* wb, float* wphase,
                          const float* gate, float* dx, float* ws, hipStream_t st);
+// slices: when given and the reduction was split, the partial results stay in ws as [(group*n + slice)][rows][og]
+// and *slices = n (the caller adds them); otherwise they are added into dwf and *slices = 1
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
-                           hipStream_t st);
+                           hipStream_t st, int* slices = nullptr);
+
+// ---- 3x3 unit-stride convolutions through F(4x4, 3x3) (winograd.hip) ------------
+// All tensors 16-byte aligned, channels per group multiples of 4.  V: wino_v_floats(), U / Ub / dU:
+// wino_u_floats(), every other transformed tensor (v, m, yt): wino_scratch_floats(); ws: wino_gemm_ws_floats().
+bool wino_ok(const ConvGeom& c);
+size_t wino_v_floats(const ConvGeom& c);
+size_t wino_u_floats(const ConvGeom& c);
+size_t wino_scratch_floats(const ConvGeom& c);
+size_t wino_gemm_ws_floats(const ConvGeom& c);
+int launch_wino_filter(const ConvGeom& c, const float* wf, float* U, hipStream_t st);
+int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStream_t st);
+int launch_wino_input(const ConvGeom& c, const float* x, float* V, hipStream_t st);
+int launch_wino_fwd(const ConvGeom& c, const float* x, const float* U, const float* bias, int relu, float* y, float* V,
+                    float* m, float* ws, hipStream_t st);
+int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, const float* gate, float* dx, float* v,
+                         float* m, float* ws, hipStream_t st);
+int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
+                           float* ws, hipStream_t st);
 
 // ---- dense layers (fc_gemm.hip) ---------------------------------------------
 struct FcAct {

@@ -1,0 +1,283 @@
+// 3x3 unit-stride convolutions through the minimal-filtering identity F(4x4, 3x3).
+//
+// A 1-D correlation y_i = sum_j g_j d_{i+j} (4 outputs, 3 taps, 6 inputs) is the bilinear form
+//     y = At [ (G g) .* (Bt d) ]
+// with the Cook-Toom matrices for the points 0, +-1, +-2 and infinity: 6 products instead of 12.
+// Nesting it in both image directions turns a 3x3 convolution over 4x4 output tiles into 36
+// independent matrix products over the channels (one per position of the transformed 6x6 tile),
+// 36 multiplies per tile and channel pair instead of 144.  Writing the same trilinear form
+// T[i][j][k] = sum_p At[i][p] G[p][j] Bt[p][k] for the other two arguments gives the adjoints:
+//     dg = Gt [ (A dy) .* (Bt d) ]         (gradient of the taps: A = At^T applied to the 4 output gradients)
+// and the gradient of the input is again a 3x3 correlation (of dy, with the taps reversed and the channel
+// roles swapped), so it runs through the forward form.
+//
+// Data layout of the transformed tensors: one row per tile t = (picture, tile row, tile column) and
+// 36 * groups * Cg columns, column (p*groups + g)*Cg + c for tile position p = 6*row + column.  That is
+// exactly a channel-last activation tensor of a 1x1 convolution with 36*groups groups, so the 36 products
+// run as one launch of the grouped implicit-GEMM kernels (conv_gemm.hip) and need no kernel of their own.
+//
+// Everything here is per-thread code shared by the kernels (winograd.hip) and by the CPU emulation test,
+// which runs it thread by thread under an address sanitizer.
+#pragma once
+
+#include <stdint.h>
+
+#include "gemm.h"
+
+namespace ax {
+
+struct Vec4 {
+  float x, y, z, w;
+};
+AX_HD Vec4 operator+(Vec4 a, Vec4 b) { return {a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w}; }
+AX_HD Vec4 operator-(Vec4 a, Vec4 b) { return {a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w}; }
+AX_HD Vec4 operator*(float s, Vec4 a) { return {s * a.x, s * a.y, s * a.z, s * a.w}; }
+AX_HD Vec4 vzero() { return {0.f, 0.f, 0.f, 0.f}; }
+AX_HD Vec4 vload(const float* p) {
+  const float4 v = *reinterpret_cast<const float4*>(p);
+  return {v.x, v.y, v.z, v.w};
+}
+AX_HD void vstore(float* p, Vec4 v) {
+  float4 o;
+  o.x = v.x; o.y = v.y; o.z = v.z; o.w = v.w;
+  *reinterpret_cast<float4*>(p) = o;
+}
+
+// ---- the five 1-D maps (strided in / out so that they serve rows and columns of a register tile) ----
+// Bt (6x6): data transform
+template <int SI, int SO>
+AX_HD void wino_bt(const Vec4* d, Vec4* o) {
+  const Vec4 d0 = d[0], d1 = d[SI], d2 = d[2 * SI], d3 = d[3 * SI], d4 = d[4 * SI], d5 = d[5 * SI];
+  o[0] = 4.f * d0 - 5.f * d2 + d4;
+  o[SO] = d3 + d4 - 4.f * (d1 + d2);
+  o[2 * SO] = 4.f * (d1 - d2) - d3 + d4;
+  o[3 * SO] = 2.f * (d3 - d1) - d2 + d4;
+  o[4 * SO] = 2.f * (d1 - d3) - d2 + d4;
+  o[5 * SO] = 4.f * d1 - 5.f * d3 + d5;
+}
+// At (4x6): output transform
+template <int SI, int SO>
+AX_HD void wino_at(const Vec4* m, Vec4* o) {
+  const Vec4 m0 = m[0], m1 = m[SI], m2 = m[2 * SI], m3 = m[3 * SI], m4 = m[4 * SI], m5 = m[5 * SI];
+  const Vec4 s12 = m1 + m2, d12 = m1 - m2, s34 = m3 + m4, d34 = m3 - m4;
+  o[0] = m0 + s12 + s34;
+  o[SO] = d12 + 2.f * d34;
+  o[2 * SO] = s12 + 4.f * s34;
+  o[3 * SO] = d12 + 8.f * d34 + m5;
+}
+// A (6x4): transform of the four output gradients
+template <int SI, int SO>
+AX_HD void wino_a(const Vec4* e, Vec4* o) {
+  const Vec4 e0 = e[0], e1 = e[SI], e2 = e[2 * SI], e3 = e[3 * SI];
+  const Vec4 ev = e0 + e2, od = e1 + e3, ev4 = e0 + 4.f * e2, od4 = e1 + 4.f * e3;
+  o[0] = e0;
+  o[SO] = ev + od;
+  o[2 * SO] = ev - od;
+  o[3 * SO] = ev4 + 2.f * od4;
+  o[4 * SO] = ev4 - 2.f * od4;
+  o[5 * SO] = e3;
+}
+// G (6x3): tap transform
+template <int SI, int SO>
+AX_HD void wino_g(const Vec4* g, Vec4* o) {
+  const Vec4 g0 = g[0], g1 = g[SI], g2 = g[2 * SI];
+  const Vec4 a = (1.f / 6.f) * (g0 + g2), b = (1.f / 6.f) * g1;
+  const Vec4 c = (1.f / 24.f) * g0 + (1.f / 6.f) * g2, d = (1.f / 12.f) * g1;
+  o[0] = 0.25f * g0;
+  o[SO] = vzero() - a - b;
+  o[2 * SO] = b - a;
+  o[3 * SO] = c + d;
+  o[4 * SO] = c - d;
+  o[5 * SO] = g2;
+}
+// Gt (3x6): back from the 6 transformed positions to the gradient of the 3 taps
+template <int SI, int SO>
+AX_HD void wino_gt(const Vec4* m, Vec4* o) {
+  const Vec4 m0 = m[0], m1 = m[SI], m2 = m[2 * SI], m3 = m[3 * SI], m4 = m[4 * SI], m5 = m[5 * SI];
+  const Vec4 s12 = m1 + m2, d12 = m2 - m1, s34 = m3 + m4, d34 = m3 - m4;
+  o[0] = 0.25f * m0 - (1.f / 6.f) * s12 + (1.f / 24.f) * s34;
+  o[SO] = (1.f / 6.f) * d12 + (1.f / 12.f) * d34;
+  o[2 * SO] = (1.f / 6.f) * (s34 - s12) + m5;
+}
+
+// ---- geometry of one transformed convolution -----------------------------------------------------
+// `H x W` is the tensor the 6x6 tiles are cut from (pad `pad` on every side), `OH x OW` the tensor
+// of 4x4 tiles (OH = H + 2*pad - 2).  Ctot = groups * Cg channels on the gathered side.
+struct WinoGeom {
+  int B, H, W, pad, OH, OW, th, tw, groups;
+  AX_HD int tiles() const { return B * th * tw; }
+};
+struct WinoTile {
+  int n, ty, tx;
+};
+AX_HD WinoTile wino_tile(const WinoGeom& g, int t) {
+  WinoTile r;
+  const int per = g.th * g.tw;
+  r.n = t / per;
+  const int rem = t - r.n * per;
+  r.ty = rem / g.tw;
+  r.tx = rem - r.ty * g.tw;
+  return r;
+}
+
+// V[t][(p*groups + g)*Cg + c] = (Bt d B)[p] of the 6x6 patch of x that tile t reads (zero outside x).
+// idx enumerates (tile, channel quad); x is [B][H][W][groups*Cg].
+AX_HD void wino_in_thread(const WinoGeom& g, int Cg, const float* x, float* V, long idx) {
+  const int Ctot = g.groups * Cg, quads = Ctot / 4;
+  const int t = (int)(idx / quads), c = 4 * (int)(idx - (long)t * quads);
+  const WinoTile tl = wino_tile(g, t);
+  const int y0 = 4 * tl.ty - g.pad, x0 = 4 * tl.tx - g.pad;
+  Vec4 d[36], u[36];
+#pragma unroll
+  for (int i = 0; i < 6; ++i)
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+      const int iy = y0 + i, ix = x0 + j;
+      const bool in = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
+      d[6 * i + j] = vzero();
+      if (in) d[6 * i + j] = vload(x + (((long)tl.n * g.H + iy) * g.W + ix) * Ctot + c);
+    }
+#pragma unroll
+  for (int j = 0; j < 6; ++j) wino_bt<6, 6>(d + j, u + j);  // columns
+  const int grp = c / Cg, cl = c - grp * Cg;
+  float* out = V + (long)t * 36 * Ctot + (long)grp * Cg + cl;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    Vec4 r[6];
+    wino_bt<1, 1>(u + 6 * i, r);  // row i
+#pragma unroll
+    for (int j = 0; j < 6; ++j) vstore(out + (long)(6 * i + j) * Ctot, r[j]);
+  }
+}
+
+// Y[t][(p*groups + g)*Og + o] = (A e At)[p] of the 4x4 block of dy that tile t owns (zero outside dy).
+// idx enumerates (tile, channel quad); dy is [B][OH][OW][groups*Og].
+AX_HD void wino_dy_thread(const WinoGeom& g, int Og, const float* dy, float* Y, long idx) {
+  const int Ctot = g.groups * Og, quads = Ctot / 4;
+  const int t = (int)(idx / quads), c = 4 * (int)(idx - (long)t * quads);
+  const WinoTile tl = wino_tile(g, t);
+  Vec4 e[16], u[24];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int oy = 4 * tl.ty + i, ox = 4 * tl.tx + j;
+      e[4 * i + j] = vzero();
+      if (oy < g.OH && ox < g.OW) e[4 * i + j] = vload(dy + (((long)tl.n * g.OH + oy) * g.OW + ox) * Ctot + c);
+    }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) wino_a<4, 4>(e + j, u + j);  // columns: 4 -> 6 rows of 4
+  const int grp = c / Og, cl = c - grp * Og;
+  float* out = Y + (long)t * 36 * Ctot + (long)grp * Og + cl;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    Vec4 r[6];
+    wino_a<1, 1>(u + 4 * i, r);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) vstore(out + (long)(6 * i + j) * Ctot, r[j]);
+  }
+}
+
+// y[n][4ty+i][4tx+j][c] = post((At m A)[i][j]) from M[t][(p*groups + g)*Ng + c'], inside OH x OW only.
+// post: + bias[c] and ReLU (relu != 0), or zero where gate[same index] <= 0; bias and gate may be null.
+AX_HD void wino_out_thread(const WinoGeom& g, int Ng, const float* M, const float* bias, int relu, const float* gate,
+                           float* y, long idx) {
+  const int Ctot = g.groups * Ng, quads = Ctot / 4;
+  const int t = (int)(idx / quads), c = 4 * (int)(idx - (long)t * quads);
+  const WinoTile tl = wino_tile(g, t);
+  const int grp = c / Ng, cl = c - grp * Ng;
+  const float* in = M + (long)t * 36 * Ctot + (long)grp * Ng + cl;
+  Vec4 u[24];
+#pragma unroll
+  for (int j = 0; j < 6; ++j) {
+    Vec4 col[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) col[i] = vload(in + (long)(6 * i + j) * Ctot);
+    wino_at<1, 6>(col, u + j);  // u[i][j], 4 rows of 6
+  }
+  Vec4 b = vzero();
+  if (bias) b = vload(bias + c);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    Vec4 r[4];
+    wino_at<1, 1>(u + 6 * i, r);
+    const int oy = 4 * tl.ty + i;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int ox = 4 * tl.tx + j;
+      if (oy < g.OH && ox < g.OW) {
+        const long o = (((long)tl.n * g.OH + oy) * g.OW + ox) * Ctot + c;
+        Vec4 v = r[j] + b;
+        if (relu) {
+          v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
+          v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
+        }
+        if (gate) {
+          const Vec4 q = vload(gate + o);
+          if (!(q.x > 0.f)) v.x = 0.f;
+          if (!(q.y > 0.f)) v.y = 0.f;
+          if (!(q.z > 0.f)) v.z = 0.f;
+          if (!(q.w > 0.f)) v.w = 0.f;
+        }
+        vstore(y + o, v);
+      }
+    }
+  }
+}
+
+// Taps to transformed taps and back.  `w` is [groups][(r, s, a)][b] (3x3 taps; a < Na rows, b < Nb
+// columns: the forward weights with a = input channel, b = output channel, or the backward-data
+// weights with the roles swapped), `U` is [(p*groups + g)][a][b].  flip reverses both tap axes
+// (the backward-data correlation).  idx enumerates (group, a, column quad).
+AX_HD void wino_filter_thread(int groups, int Na, int Nb, int flip, const float* w, float* U, long idx) {
+  const int quads = Nb / 4;
+  const long row = idx / quads;  // g*Na + a
+  const int b = 4 * (int)(idx - row * quads);
+  const int grp = (int)(row / Na), a = (int)(row - (long)grp * Na);
+  Vec4 k[9], u[18];
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      const int tap = flip ? (2 - r) * 3 + (2 - s) : r * 3 + s;
+      k[3 * r + s] = vload(w + (((long)grp * 9 + tap) * Na + a) * Nb + b);
+    }
+#pragma unroll
+  for (int s = 0; s < 3; ++s) wino_g<3, 3>(k + s, u + s);  // columns: 3 -> 6 rows of 3
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    Vec4 r[6];
+    wino_g<1, 1>(u + 3 * i, r);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) vstore(U + ((((long)(6 * i + j) * groups + grp) * Na + a) * Nb + b), r[j]);
+  }
+}
+// dw[groups][(r, s, a)][b] = (Gt m G)[r][s], m = sum over the ns partial products dU[(p*groups + g)*ns + s][a][b]
+// (the slices of a reduction that was split over workgroups, added here in a fixed order)
+AX_HD void wino_dw_thread(int groups, int Na, int Nb, int ns, const float* dU, float* dw, long idx) {
+  const int quads = Nb / 4;
+  const long row = idx / quads;
+  const int b = 4 * (int)(idx - row * quads);
+  const int grp = (int)(row / Na), a = (int)(row - (long)grp * Na);
+  Vec4 u[18];
+#pragma unroll
+  for (int j = 0; j < 6; ++j) {
+    Vec4 col[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      const float* src = dU + ((((long)(6 * i + j) * groups + grp) * ns * Na + a) * Nb + b);
+      col[i] = vload(src);
+      for (int sl = 1; sl < ns; ++sl) col[i] = col[i] + vload(src + (long)sl * Na * Nb);
+    }
+    wino_gt<1, 6>(col, u + j);  // u[r][j], 3 rows of 6
+  }
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    Vec4 o[3];
+    wino_gt<1, 1>(u + 6 * r, o);
+#pragma unroll
+    for (int s = 0; s < 3; ++s) vstore(dw + (((long)grp * 9 + r * 3 + s) * Na + a) * Nb + b, o[s]);
+  }
+}
+
+}  // namespace ax

@@ -1,0 +1,161 @@
+// Kernels and launchers of the F(4x4, 3x3) convolution path (see winograd.h): five bandwidth-bound
+// transforms; the 36 channel products between them are launched through the grouped implicit-GEMM
+// kernels as a 1x1 convolution with 36*groups groups.
+#include "winograd.h"
+
+#include "kernels.h"
+
+namespace ax {
+
+__global__ void __launch_bounds__(256) wino_in_kernel(WinoGeom g, int Cg, const float* __restrict__ x,
+                                                       float* __restrict__ V, long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < total) wino_in_thread(g, Cg, x, V, idx);
+}
+__global__ void __launch_bounds__(256) wino_dy_kernel(WinoGeom g, int Og, const float* __restrict__ dy,
+                                                       float* __restrict__ Y, long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < total) wino_dy_thread(g, Og, dy, Y, idx);
+}
+__global__ void __launch_bounds__(256) wino_out_kernel(WinoGeom g, int Ng, const float* __restrict__ M,
+                                                        const float* __restrict__ bias, int relu,
+                                                        const float* __restrict__ gate, float* __restrict__ y,
+                                                        long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < total) wino_out_thread(g, Ng, M, bias, relu, gate, y, idx);
+}
+__global__ void __launch_bounds__(256) wino_filter_kernel(int groups, int Na, int Nb, int flip,
+                                                           const float* __restrict__ w, float* __restrict__ U,
+                                                           long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < total) wino_filter_thread(groups, Na, Nb, flip, w, U, idx);
+}
+__global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb, int ns,
+                                                       const float* __restrict__ dU, float* __restrict__ dw,
+                                                       long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < total) wino_dw_thread(groups, Na, Nb, ns, dU, dw, idx);
+}
+
+// ---- geometry ----------------------------------------------------------------------------------
+bool wino_ok(const ConvGeom& c) {
+  if (c.k != 3 || c.stride != 1 || c.pad > 2 || c.cg() % 4 || c.og() % 4) return false;
+  // the transformed tensors are 36/16 (tiles cut exactly) to ~4x larger than the activations
+  const long th = (c.Ho + 3) / 4, tw = (c.Wo + 3) / 4, thb = (c.H + 3) / 4, twb = (c.W + 3) / 4;
+  const long T = std::max((long)c.B * th * tw, (long)c.B * thb * twb);
+  return T * 36 * std::max(c.Cin, c.Cout) <= 0x1ffffff0L;
+}
+static WinoGeom fwd_geom(const ConvGeom& c) {
+  return WinoGeom{c.B, c.H, c.W, c.pad, c.Ho, c.Wo, (c.Ho + 3) / 4, (c.Wo + 3) / 4, c.groups};
+}
+// backward-data: dx = correlation of dy (pad 2 - pad) with the reversed taps
+static WinoGeom bwd_geom(const ConvGeom& c) {
+  return WinoGeom{c.B, c.Ho, c.Wo, 2 - c.pad, c.H, c.W, (c.H + 3) / 4, (c.W + 3) / 4, c.groups};
+}
+// the 36*groups channel products as a 1x1 grouped convolution over one row of `tiles` pixels
+static ConvGeom product_geom(int tiles, int groups, int kin, int nout) {
+  ConvGeom p;
+  p.B = 1; p.H = 1; p.W = tiles; p.Cin = 36 * groups * kin; p.Cout = 36 * groups * nout;
+  p.k = 1; p.stride = 1; p.pad = 0; p.groups = 36 * groups; p.Ho = 1; p.Wo = tiles;
+  return p;
+}
+size_t wino_v_floats(const ConvGeom& c) { return (size_t)fwd_geom(c).tiles() * 36 * c.Cin; }
+size_t wino_u_floats(const ConvGeom& c) { return (size_t)36 * c.w_elems() / 9; }
+size_t wino_scratch_floats(const ConvGeom& c) {
+  const size_t tf = (size_t)fwd_geom(c).tiles(), tb = (size_t)bwd_geom(c).tiles();
+  return 36 * std::max(std::max(tf * c.Cout, tb * c.Cout), std::max(tb * c.Cin, tf * c.Cin));
+}
+size_t wino_gemm_ws_floats(const ConvGeom& c) {
+  const ConvGeom pf = product_geom(fwd_geom(c).tiles(), c.groups, c.cg(), c.og());
+  const ConvGeom pb = product_geom(bwd_geom(c).tiles(), c.groups, c.og(), c.cg());
+  return std::max(std::max(conv_fwd_ws_floats(pf), conv_fwd_ws_floats(pb)), conv_bwd_weight_ws_floats(pf));
+}
+
+// ---- launchers -----------------------------------------------------------------------------------
+static inline dim3 blocks_for(long total) { return dim3((unsigned)((total + 255) / 256)); }
+
+int launch_wino_filter(const ConvGeom& c, const float* wf, float* U, hipStream_t st) {
+  const long total = (long)c.groups * c.cg() * (c.og() / 4);
+  KernelScope ks("wino_filter", 0, (double)c.w_elems() * 4.0 * 5.0, st);
+  hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), 0, wf, U, total);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStream_t st) {
+  const long total = (long)c.groups * c.og() * (c.cg() / 4);
+  KernelScope ks("wino_filter", 0, (double)c.w_elems() * 4.0 * 5.0, st);
+  hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.og(), c.cg(), 1, wb, Ub, total);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+int launch_wino_input(const ConvGeom& c, const float* x, float* V, hipStream_t st) {
+  const WinoGeom g = fwd_geom(c);
+  const int T = g.tiles();
+  const long total = (long)T * (c.Cin / 4);
+  KernelScope ks("wino_in", 0, ((double)c.in_elems() + (double)T * 36 * c.Cin) * 4.0, st);
+  hipLaunchKernelGGL(wino_in_kernel, blocks_for(total), dim3(256), 0, st, g, c.cg(), x, V, total);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// x -> V (kept by the caller for the weight gradient), V x U -> m, m -> y = act(. + bias)
+int launch_wino_fwd(const ConvGeom& c, const float* x, const float* U, const float* bias, int relu, float* y, float* V,
+                    float* m, float* ws, hipStream_t st) {
+  const WinoGeom g = fwd_geom(c);
+  const int T = g.tiles();
+  AX_TRY(launch_wino_input(c, x, V, st));
+  const ConvGeom p = product_geom(T, c.groups, c.cg(), c.og());
+  AX_TRY(launch_conv_fwd(p, V, U, nullptr, nullptr, 0, m, ws, st));
+  const long total = (long)T * (c.Cout / 4);
+  KernelScope ks("wino_out", 0, ((double)c.out_elems() + (double)T * 36 * c.Cout) * 4.0, st);
+  hipLaunchKernelGGL(wino_out_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), m, bias, relu,
+                     (const float*)nullptr, y, total);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// dy -> v (transformed like an input), v x Ub -> m, m -> dx gated by gate > 0 (gate may be null)
+int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, const float* gate, float* dx, float* v,
+                         float* m, float* ws, hipStream_t st) {
+  const WinoGeom g = bwd_geom(c);
+  const int T = g.tiles();
+  {
+    const long total = (long)T * (c.Cout / 4);
+    KernelScope ks("wino_in", 0, ((double)c.out_elems() + (double)T * 36 * c.Cout) * 4.0, st);
+    hipLaunchKernelGGL(wino_in_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), dy, v, total);
+    AX_LAUNCH_CHECK();
+  }
+  const ConvGeom p = product_geom(T, c.groups, c.og(), c.cg());
+  AX_TRY(launch_conv_fwd(p, v, Ub, nullptr, nullptr, 0, m, ws, st));
+  const long total = (long)T * (c.Cin / 4);
+  KernelScope ks("wino_out", 0, ((double)c.in_elems() * (gate ? 2 : 1) + (double)T * 36 * c.Cin) * 4.0, st);
+  hipLaunchKernelGGL(wino_out_kernel, blocks_for(total), dim3(256), 0, st, g, c.cg(), m, (const float*)nullptr, 0, gate,
+                     dx, total);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// dy -> yt, V^T x yt -> dU (36 products over the tiles), dU -> dwf.  V is the forward pass's.
+int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
+                           float* ws, hipStream_t st) {
+  const WinoGeom g = fwd_geom(c);
+  const int T = g.tiles();
+  {
+    const long total = (long)T * (c.Cout / 4);
+    KernelScope ks("wino_dy", 0, ((double)c.out_elems() + (double)T * 36 * c.Cout) * 4.0, st);
+    hipLaunchKernelGGL(wino_dy_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), dy, yt, total);
+    AX_LAUNCH_CHECK();
+  }
+  const ConvGeom p = product_geom(T, c.groups, c.cg(), c.og());
+  int ns = 1;  // slices of the reduction over the tiles; their sum is taken by the transform below
+  AX_TRY(launch_conv_bwd_weight(p, V, yt, dU, nullptr, ws, st, &ns));
+  const long total = (long)c.groups * c.cg() * (c.og() / 4);
+  KernelScope ks("wino_dw", 0, (double)c.w_elems() * 4.0 * (4.0 * ns + 1.0), st);
+  hipLaunchKernelGGL(wino_dw_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), ns,
+                     ns > 1 ? ws : dU, dwf, total);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+}  // namespace ax

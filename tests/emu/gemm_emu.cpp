@@ -558,6 +558,14 @@ static ConvGeom geom(int B, int H, int Cin, int Cout, int k, int st, int pad, in
   return c;
 }
 
+static ConvGeom product_geom(int tiles, int groups, int kin, int nout) {
+  // the channel products of a transformed 3x3 convolution: a 1x1 convolution with many groups over one row of pixels
+  ConvGeom c;
+  c.B = 1; c.H = 1; c.W = tiles; c.Cin = groups * kin; c.Cout = groups * nout; c.k = 1; c.stride = 1; c.pad = 0;
+  c.groups = groups; c.Ho = 1; c.Wo = tiles;
+  return c;
+}
+
 template <int ROWS, int BK>
 static void dense_case() {
   // fully connected layer shapes with ragged and non-multiple-of-4 extents
@@ -698,6 +706,9 @@ int main() {
       {geom(3, 6, 32, 96, 5, 1, 2, 1), "k5p2c32"},       // 25 taps, ragged rows and columns
       {geom(4, 7, 8, 24, 3, 1, 1, 2), "k3p1g2px224"},    // 4*7*8 = 224 pixels: whole k-tiles for backward-weight
       {geom(4, 15, 3, 8, 5, 2, 0, 1), "k5s2c3px192"},    // run mode with 4*6*8 = 192 output pixels
+      {product_geom(48, 12, 16, 8), "1x1g12c16t48"},    // whole k-tiles in every product
+      {product_geom(40, 9, 20, 12), "1x1g9c20t40"},     // ragged k and pixel counts
+      {product_geom(160, 4, 32, 32), "1x1g4c32t160"},   // two row tiles
   };
   for (const Case& cs : cases) {
     run_case<Tile<128, 128, 32, 2, 2>>(cs);

@@ -1,0 +1,207 @@
+// CPU run of the per-thread programs in csrc/winograd.h (the F(4x4, 3x3) transforms), thread by thread,
+// with the channel products between them written as plain loops, checked against direct convolution
+// loops in double precision.  Buffers have exactly the sizes the library allocates and the test is built
+// with -fsanitize=address, so an out-of-range access of a transform aborts here, on the CPU.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <algorithm>
+#include <vector>
+
+struct float4 {
+  float x, y, z, w;
+};
+#define AX_HOST_EMU 1
+namespace ax {
+inline void emu_fail(const char* what) {
+  fprintf(stderr, "EMULATION FAULT: %s\n", what);
+  abort();
+}
+}  // namespace ax
+#include "../../paper_1412_2302_amd/csrc/winograd.h"
+
+using namespace ax;
+
+static int g_fail = 0;
+static unsigned g_seed = 12345;
+static float rnd() {
+  g_seed = g_seed * 1664525u + 1013904223u;
+  return ((g_seed >> 8) & 0xffff) / 32768.0f - 1.0f;
+}
+static void check(const char* what, const char* nm, const std::vector<float>& got, const std::vector<double>& ref,
+                  double tol = 2e-5) {
+  double num = 0, den = 0;
+  for (size_t i = 0; i < ref.size(); ++i) {
+    const double d = (double)got[i] - ref[i];
+    num += d * d;
+    den += ref[i] * ref[i];
+  }
+  const double rel = sqrt(num / (den > 0 ? den : 1));
+  const bool ok = rel <= tol && got.size() == ref.size();
+  printf("%-10s %-28s rel_l2=%.3e %s\n", what, nm, rel, ok ? "ok" : "FAIL");
+  if (!ok) ++g_fail;
+}
+
+// the 1-D identities behind everything else: y = At[(G g) .* (Bt d)] is the correlation, and the two adjoint forms
+static void check_1d() {
+  Vec4 d[6], g[3], e[4];
+  for (auto& v : d) v = {rnd(), rnd(), rnd(), rnd()};
+  for (auto& v : g) v = {rnd(), rnd(), rnd(), rnd()};
+  for (auto& v : e) v = {rnd(), rnd(), rnd(), rnd()};
+  Vec4 bd[6], gg[6], ae[6], prod[6], y[4], dg[3];
+  wino_bt<1, 1>(d, bd);
+  wino_g<1, 1>(g, gg);
+  wino_a<1, 1>(e, ae);
+  for (int p = 0; p < 6; ++p) prod[p] = {gg[p].x * bd[p].x, gg[p].y * bd[p].y, gg[p].z * bd[p].z, gg[p].w * bd[p].w};
+  wino_at<1, 1>(prod, y);
+  std::vector<float> got;
+  std::vector<double> ref;
+  for (int i = 0; i < 4; ++i) {
+    double r = 0;
+    for (int j = 0; j < 3; ++j) r += (double)g[j].x * d[i + j].x;
+    got.push_back(y[i].x);
+    ref.push_back(r);
+  }
+  check("1d", "y = sum_j g_j d_{i+j}", got, ref, 1e-5);
+  for (int p = 0; p < 6; ++p) prod[p] = {ae[p].x * bd[p].x, ae[p].y * bd[p].y, ae[p].z * bd[p].z, ae[p].w * bd[p].w};
+  wino_gt<1, 1>(prod, dg);
+  got.clear();
+  ref.clear();
+  for (int j = 0; j < 3; ++j) {
+    double r = 0;
+    for (int i = 0; i < 4; ++i) r += (double)e[i].y * d[i + j].y;
+    got.push_back(dg[j].y);
+    ref.push_back(r);
+  }
+  check("1d", "dg_j = sum_i e_i d_{i+j}", got, ref, 1e-5);
+}
+
+struct Case {
+  const char* name;
+  int B, H, W, pad, groups, cg, og;
+};
+
+// m[t][z*N + o] = sum_c a[t][z*K + c] * u[z][c][o]
+static void products(int T, int Z, int K, int N, const std::vector<float>& a, const std::vector<float>& u,
+                     std::vector<float>& m) {
+  for (int t = 0; t < T; ++t)
+    for (int z = 0; z < Z; ++z)
+      for (int o = 0; o < N; ++o) {
+        float s = 0.f;
+        for (int c = 0; c < K; ++c) s += a[((size_t)t * Z + z) * K + c] * u[((size_t)z * K + c) * N + o];
+        m[((size_t)t * Z + z) * N + o] = s;
+      }
+}
+
+static void run(const Case& k) {
+  const int Ho = k.H + 2 * k.pad - 2, Wo = k.W + 2 * k.pad - 2, G = k.groups, Cin = G * k.cg, Cout = G * k.og;
+  const WinoGeom gf{k.B, k.H, k.W, k.pad, Ho, Wo, (Ho + 3) / 4, (Wo + 3) / 4, G};
+  const WinoGeom gb{k.B, Ho, Wo, 2 - k.pad, k.H, k.W, (k.H + 3) / 4, (k.W + 3) / 4, G};
+  const int Tf = gf.tiles(), Tb = gb.tiles();
+  std::vector<float> x((size_t)k.B * k.H * k.W * Cin), dy((size_t)k.B * Ho * Wo * Cout), bias(Cout);
+  std::vector<float> wf((size_t)G * 9 * k.cg * k.og), wb(wf.size());
+  for (auto& v : x) v = rnd();
+  for (auto& v : dy) v = rnd();
+  for (auto& v : bias) v = 0.3f * rnd();
+  for (auto& v : wf) v = 0.2f * rnd();
+  for (int g = 0; g < G; ++g)
+    for (int t = 0; t < 9; ++t)
+      for (int c = 0; c < k.cg; ++c)
+        for (int o = 0; o < k.og; ++o)
+          wb[(((size_t)g * 9 + t) * k.og + o) * k.cg + c] = wf[(((size_t)g * 9 + t) * k.cg + c) * k.og + o];
+  auto X = [&](int n, int y, int xx, int c) -> double {
+    return (y < 0 || y >= k.H || xx < 0 || xx >= k.W) ? 0.0 : x[(((size_t)n * k.H + y) * k.W + xx) * Cin + c];
+  };
+  auto WF = [&](int g, int r, int s, int c, int o) -> double {
+    return wf[(((size_t)g * 9 + r * 3 + s) * k.cg + c) * k.og + o];
+  };
+  // ---- forward ----
+  std::vector<float> U(36 * wf.size() / 9), V((size_t)Tf * 36 * Cin), m((size_t)Tf * 36 * Cout), y(dy.size(), NAN);
+  for (long i = 0; i < (long)G * k.cg * (k.og / 4); ++i) wino_filter_thread(G, k.cg, k.og, 0, wf.data(), U.data(), i);
+  for (long i = 0; i < (long)Tf * (Cin / 4); ++i) wino_in_thread(gf, k.cg, x.data(), V.data(), i);
+  products(Tf, 36 * G, k.cg, k.og, V, U, m);
+  for (long i = 0; i < (long)Tf * (Cout / 4); ++i) wino_out_thread(gf, k.og, m.data(), bias.data(), 1, nullptr, y.data(), i);
+  std::vector<double> y_ref(y.size());
+  for (int n = 0; n < k.B; ++n)
+    for (int oy = 0; oy < Ho; ++oy)
+      for (int ox = 0; ox < Wo; ++ox)
+        for (int g = 0; g < G; ++g)
+          for (int o = 0; o < k.og; ++o) {
+            double s = bias[g * k.og + o];
+            for (int r = 0; r < 3; ++r)
+              for (int q = 0; q < 3; ++q)
+                for (int c = 0; c < k.cg; ++c) s += X(n, oy - k.pad + r, ox - k.pad + q, g * k.cg + c) * WF(g, r, q, c, o);
+            y_ref[(((size_t)n * Ho + oy) * Wo + ox) * Cout + g * k.og + o] = s > 0 ? s : 0;
+          }
+  check("fwd", k.name, y, y_ref);
+  // ---- backward data (gated by x > 0) ----
+  std::vector<float> Ub(U.size()), v((size_t)Tb * 36 * Cout), mb((size_t)Tb * 36 * Cin), dx(x.size(), NAN);
+  for (long i = 0; i < (long)G * k.og * (k.cg / 4); ++i) wino_filter_thread(G, k.og, k.cg, 1, wb.data(), Ub.data(), i);
+  for (long i = 0; i < (long)Tb * (Cout / 4); ++i) wino_in_thread(gb, k.og, dy.data(), v.data(), i);
+  products(Tb, 36 * G, k.og, k.cg, v, Ub, mb);
+  for (long i = 0; i < (long)Tb * (Cin / 4); ++i) wino_out_thread(gb, k.cg, mb.data(), nullptr, 0, x.data(), dx.data(), i);
+  std::vector<double> dx_ref(x.size(), 0.0);
+  for (int n = 0; n < k.B; ++n)
+    for (int oy = 0; oy < Ho; ++oy)
+      for (int ox = 0; ox < Wo; ++ox)
+        for (int g = 0; g < G; ++g)
+          for (int o = 0; o < k.og; ++o) {
+            const double e = dy[(((size_t)n * Ho + oy) * Wo + ox) * Cout + g * k.og + o];
+            for (int r = 0; r < 3; ++r)
+              for (int q = 0; q < 3; ++q) {
+                const int iy = oy - k.pad + r, ix = ox - k.pad + q;
+                if (iy < 0 || iy >= k.H || ix < 0 || ix >= k.W) continue;
+                for (int c = 0; c < k.cg; ++c)
+                  dx_ref[(((size_t)n * k.H + iy) * k.W + ix) * Cin + g * k.cg + c] += e * WF(g, r, q, c, o);
+              }
+          }
+  for (size_t i = 0; i < dx_ref.size(); ++i)
+    if (!(x[i] > 0.f)) dx_ref[i] = 0;
+  check("bwd_data", k.name, dx, dx_ref);
+  // ---- backward weight ----
+  // the reduction over the tiles in ns slices, as a split launch leaves them: [(z*ns + slice)][c][o]
+  const int ns = Tf >= 3 ? 3 : 1, per = (Tf + ns - 1) / ns;
+  std::vector<float> yt((size_t)Tf * 36 * Cout), dU(U.size() * ns), dw(wf.size(), NAN);
+  for (long i = 0; i < (long)Tf * (Cout / 4); ++i) wino_dy_thread(gf, k.og, dy.data(), yt.data(), i);
+  for (int z = 0; z < 36 * G; ++z)
+    for (int sl = 0; sl < ns; ++sl)
+      for (int c = 0; c < k.cg; ++c)
+        for (int o = 0; o < k.og; ++o) {
+          float s = 0.f;
+          for (int t = sl * per; t < std::min(Tf, (sl + 1) * per); ++t)
+            s += V[((size_t)t * 36 * G + z) * k.cg + c] * yt[((size_t)t * 36 * G + z) * k.og + o];
+          dU[(((size_t)z * ns + sl) * k.cg + c) * k.og + o] = s;
+        }
+  for (long i = 0; i < (long)G * k.cg * (k.og / 4); ++i) wino_dw_thread(G, k.cg, k.og, ns, dU.data(), dw.data(), i);
+  std::vector<double> dw_ref(wf.size(), 0.0);
+  for (int n = 0; n < k.B; ++n)
+    for (int oy = 0; oy < Ho; ++oy)
+      for (int ox = 0; ox < Wo; ++ox)
+        for (int g = 0; g < G; ++g)
+          for (int o = 0; o < k.og; ++o) {
+            const double e = dy[(((size_t)n * Ho + oy) * Wo + ox) * Cout + g * k.og + o];
+            for (int r = 0; r < 3; ++r)
+              for (int q = 0; q < 3; ++q)
+                for (int c = 0; c < k.cg; ++c)
+                  dw_ref[(((size_t)g * 9 + r * 3 + q) * k.cg + c) * k.og + o] +=
+                      e * X(n, oy - k.pad + r, ox - k.pad + q, g * k.cg + c);
+          }
+  check("bwd_weight", k.name, dw, dw_ref);
+}
+
+int main() {
+  check_1d();
+  const Case cases[] = {
+      {"13x13 pad1 g1", 2, 13, 13, 1, 1, 8, 12},  {"13x13 pad1 g2", 2, 13, 13, 1, 2, 4, 8},
+      {"6x6 pad1 g2", 3, 6, 6, 1, 2, 8, 4},        {"5x7 pad0 g1", 2, 5, 7, 0, 1, 4, 4},
+      {"4x9 pad2 g1", 1, 4, 9, 2, 1, 4, 8},        {"3x3 pad1 g1", 2, 3, 3, 1, 1, 4, 4},
+  };
+  for (const Case& c : cases) run(c);
+  if (g_fail) {
+    printf("%d FAILED\n", g_fail);
+    return 1;
+  }
+  printf("ALL OK\n");
+  return 0;
+}
