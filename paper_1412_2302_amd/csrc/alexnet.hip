@@ -273,10 +273,11 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     if (s.lrn && s.pool) cws = std::max(cws, lrn_part_floats(s.g.Cout));
   }
   {
-    // the dense-layer update shares the chip best with the largest direct convolution of the backward pass:
-    // the transformed 3x3 stages move several times their activations and compete with it for bandwidth
+    // the dense-layer update shares the chip best with the largest direct fp32 convolution of the backward pass:
+    // the transformed 3x3 stages move several times their activations and compete with it for bandwidth, and
+    // so do the bf16 products (those keep the fork behind the last stage, the earliest possible)
     double best = -1;
-    for (int i = 1; i < kStages; ++i) {
+    for (int i = 1; i < kStages && c.precision == ALEXNET_PRECISION_FP32; ++i) {
       const Stage& s = n->st[i];
       const double fl = (double)s.g.P() * s.g.Cout * s.g.cg() * s.g.k * s.g.k;
       if (!s.wino && fl > best) {

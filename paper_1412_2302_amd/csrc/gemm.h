@@ -73,7 +73,9 @@ struct Tile {
   static_assert(BK % (4 * G) == 0, "a lane's four consecutive k feed four MFMA steps");
   // k consumed by MFMA step u from lane group g (the same on both operands, so any order is a valid contraction)
   AX_HD static int step_k(int u, int g) { return 4 * G * (u >> 2) + 4 * g + (u & 3); }
-  // row of accumulator register r of a lane inside its block; the column is lane % RB
+  // The kernels feed the B fragment as the MFMA's first operand, so a block comes out transposed: register r
+  // of a lane holds C[lane % RB][acc_row(lane, r)], four consecutive columns per register quad -- one 16-byte
+  // store per quad in the epilogue.
   AX_HD static int acc_row(int lane, int r) {
     return RB == 32 ? 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) : 4 * (lane >> 4) + r;
   }
@@ -158,7 +160,7 @@ AX_HD uint32_t fdiv(uint32_t n, const FastDiv& f) {
 // MFMA step u = 4q + j of a k-tile consumes k = 8q + j (lanes 0..31) and
 // k = 8q + 4 + j (lanes 32..63).
 AX_HD int step_k(int u, int kh) { return 8 * (u >> 2) + 4 * kh + (u & 3); }
-// accumulator register r of a lane holds C[acc_row(lane,r)][lane%32] of the 32x32 block
+// accumulator register r of a lane holds D[acc_row(lane,r)][lane%32] of a 32x32 MFMA result D
 AX_HD int acc_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
 // =========================== operand loaders ================================
@@ -621,7 +623,10 @@ AX_HD int lds_index(int row, int k) {
 }
 
 // ================================ epilogues ==================================
-// apply(m, n, v) is called once per valid element of the tile.
+// apply4(m, n, v) is called for four consecutive valid columns n .. n+3 (n a multiple of 4) of row m,
+// apply(m, n, v) for single elements of a ragged last quad.  set_group() runs once per workgroup and also
+// decides whether the quads may be stored 16 bytes at a time.
+AX_HD bool epi_aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 // y[m][col_off + n] = act(v + bias[col_off + n]); col_off = group * cols_per_group
 struct EpiBiasAct {
@@ -629,11 +634,30 @@ struct EpiBiasAct {
   long ldc;
   const float* bias;  // may be null
   int relu, cols_per_group, col_off;
-  AX_HD void set_group(int g, int /*z*/) { col_off = g * cols_per_group; }
+  int vec;
+  AX_HD void set_group(int g, int /*z*/) {
+    col_off = g * cols_per_group;
+    vec = (ldc & 3) == 0 && (col_off & 3) == 0 && epi_aligned16(y) && epi_aligned16(bias);
+  }
   AX_HD void apply(int m, int n, float v) const {
     if (bias) v += bias[col_off + n];
     if (relu) v = v > 0.f ? v : 0.f;
     y[(long)m * ldc + col_off + n] = v;
+  }
+  AX_HD void apply4(int m, int n, float4 v) const {
+    if (!vec) {
+      apply(m, n, v.x); apply(m, n + 1, v.y); apply(m, n + 2, v.z); apply(m, n + 3, v.w);
+      return;
+    }
+    if (bias) {
+      const float4 b = *reinterpret_cast<const float4*>(bias + col_off + n);
+      v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+    }
+    if (relu) {
+      v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
+      v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
+    }
+    *reinterpret_cast<float4*>(y + (long)m * ldc + col_off + n) = v;
   }
 };
 
@@ -643,11 +667,30 @@ struct EpiGate {
   long ldc;
   const float* gate;  // forward activation with the layout of dx, or null
   int cols_per_group, col_off;
-  AX_HD void set_group(int g, int /*z*/) { col_off = g * cols_per_group; }
+  int vec;
+  AX_HD void set_group(int g, int /*z*/) {
+    col_off = g * cols_per_group;
+    vec = (ldc & 3) == 0 && (col_off & 3) == 0 && epi_aligned16(dx) && epi_aligned16(gate);
+  }
   AX_HD void apply(int m, int n, float v) const {
     const long o = (long)m * ldc + col_off + n;
     if (gate && !(gate[o] > 0.f)) v = 0.f;
     dx[o] = v;
+  }
+  AX_HD void apply4(int m, int n, float4 v) const {
+    if (!vec) {
+      apply(m, n, v.x); apply(m, n + 1, v.y); apply(m, n + 2, v.z); apply(m, n + 3, v.w);
+      return;
+    }
+    const long o = (long)m * ldc + col_off + n;
+    if (gate) {
+      const float4 q = *reinterpret_cast<const float4*>(gate + o);
+      if (!(q.x > 0.f)) v.x = 0.f;
+      if (!(q.y > 0.f)) v.y = 0.f;
+      if (!(q.z > 0.f)) v.z = 0.f;
+      if (!(q.w > 0.f)) v.w = 0.f;
+    }
+    *reinterpret_cast<float4*>(dx + o) = v;
   }
 };
 
@@ -659,6 +702,9 @@ struct EpiPhases {
   int H, W, C, st, pad, QW;
   FastDiv d_qhw, d_qw, d_stc, d_c;  // divisors QH*QW, QW, st*C, C
   AX_HD void set_group(int /*g*/, int /*z*/) {}
+  AX_HD void apply4(int m, int n, float4 v) const {  // neighbouring columns may land in different pixels
+    apply(m, n, v.x); apply(m, n + 1, v.y); apply(m, n + 2, v.z); apply(m, n + 3, v.w);
+  }
   AX_HD void apply(int m, int n, float v) const {
     const int img = (int)fdiv((uint32_t)m, d_qhw);
     const int rem = m - img * (int)d_qhw.d;
@@ -676,9 +722,39 @@ struct EpiSlab {
   long slab;  // M*N
   long ldc;   // N
   float* base;
-  AX_HD void set_group(int /*g*/, int z) { base = ws + (long)z * slab; }
+  int vec;
+  AX_HD void set_group(int /*g*/, int z) {
+    base = ws + (long)z * slab;
+    vec = (ldc & 3) == 0 && epi_aligned16(base);
+  }
   AX_HD void apply(int m, int n, float v) const { base[(long)m * ldc + n] = v; }
+  AX_HD void apply4(int m, int n, float4 v) const {
+    if (vec) {
+      *reinterpret_cast<float4*>(base + (long)m * ldc + n) = v;
+    } else {
+      apply(m, n, v.x); apply(m, n + 1, v.y); apply(m, n + 2, v.z); apply(m, n + 3, v.w);
+    }
+  }
 };
+
+// Hands one accumulator block of a lane to the epilogue: row m, register quads at columns nb + acc_row(lane, 4q).
+template <class T, class Epi, class Acc>
+AX_HD void store_block(const Epi& ep, const Acc& acc, int m, int nb, int lane, int M, int N) {
+  if (m >= M) return;
+#pragma unroll
+  for (int q = 0; q < T::NACC / 4; ++q) {
+    const int n = nb + T::acc_row(lane, 4 * q);
+    if (n + 3 < N) {
+      float4 v;
+      v.x = acc[4 * q]; v.y = acc[4 * q + 1]; v.z = acc[4 * q + 2]; v.w = acc[4 * q + 3];
+      ep.apply4(m, n, v);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e < N) ep.apply(m, n + e, acc[4 * q + e]);
+    }
+  }
+}
 
 // ================================= kernel ====================================
 #ifndef AX_HOST_EMU
@@ -805,7 +881,7 @@ __device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T>& fa, Frags<BL, T
     for (int i = 0; i < T::TM; ++i)
 #pragma unroll
       for (int j = 0; j < T::TN; ++j)
-        acc[i][j] = MfmaBlock<T::RB>::mma(fa.template get<U>(i), fb.template get<U>(j), acc[i][j]);
+        acc[i][j] = MfmaBlock<T::RB>::mma(fb.template get<U>(j), fa.template get<U>(i), acc[i][j]);
     if constexpr (U + 1 < KP) side_slot<T, AL, BL, U>(al, bl, as_next, bs_next, ra, rb, k_plan, kend);
     __builtin_amdgcn_sched_barrier(0);
     tile_stream<T, AL, BL, U + 1>(fa, fb, acc, al, bl, as_next, bs_next, ra, rb, k_plan, kend, a_row, b_row, kh);
@@ -900,15 +976,9 @@ gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N
 #pragma unroll
   for (int i = 0; i < T::TM; ++i)
 #pragma unroll
-    for (int j = 0; j < T::TN; ++j) {
-      const int n = n0 + wn * (T::TN * RB) + j * RB + lane % RB;
-      if (n >= N) continue;
-#pragma unroll
-      for (int r = 0; r < T::NACC; ++r) {
-        const int m = m0 + wm * (T::TM * RB) + i * RB + T::acc_row(lane, r);
-        if (m < M) ep.apply(m, n, acc[i][j][r]);
-      }
-    }
+    for (int j = 0; j < T::TN; ++j)
+      store_block<T>(ep, acc[i][j], m0 + wm * (T::TM * RB) + i * RB + lane % RB, n0 + wn * (T::TN * RB) + j * RB, lane,
+                     M, N);
 }
 #endif  // AX_HOST_EMU
 

@@ -351,6 +351,9 @@ gemm_bf16_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, 
   for (int i = 0; i < T::TM; ++i)
 #pragma unroll
     for (int j = 0; j < T::TN; ++j) {
+      // Blocks are not transposed here (A fragment first): register r of a lane is C[acc_row(lane, r)][lane % 32].
+      // These kernels wait on memory rather than on instruction issue, and 4-byte stores that fill whole
+      // 128-byte lines measured faster than the fp32 kernel's 16-byte stores, which touch 32 lines each.
       const int n = n0 + wn * (T::TN * 32) + j * 32 + (lane & 31);
       if (n >= N) continue;
 #pragma unroll
