@@ -888,20 +888,30 @@ __device__ __forceinline__ void tile_stream(Frags<AL, T::TM, T>& fa, Frags<BL, T
   }
 }
 
-// Workgroups the compiler must fit on a CU.  A forward pass over a short reduction (the first layer: 25
-// k-tiles per output tile) spends a good part of a tile's life in its prologue and epilogue, and co-resident
-// workgroups that started together stay in step; a third workgroup per CU fills those gaps.
-template <class T, class Epi>
+// Workgroups the compiler must fit on a CU.  Two co-resident workgroups that started together stay in
+// step, and a pass over a short reduction (the first layer's 25 k-tiles, the 12 to 16 of the transformed
+// 3x3 layers) spends a good part of a tile's life in its prologue and epilogue; a third workgroup per CU
+// fills those gaps (measured: 1-4 % per launch).  Three need at most 168 registers per lane, which every
+// variant reaches without spilling (the accumulators then live in ordinary registers) except the 128 x 128
+// tile with 4-byte loads, which keeps two.
+template <class L>
+struct loads_scalars : std::false_type {};
+template <int ROWS, int BK>
+struct loads_scalars<DenseKInner<ROWS, BK, false>> : std::true_type {};
+template <int ROWS, int BK>
+struct loads_scalars<DenseRowInner<ROWS, BK, false>> : std::true_type {};
+template <int ROWS, int BK, int MODE>
+struct loads_scalars<Im2colKInner<ROWS, BK, false, MODE>> : std::true_type {};
+template <int ROWS, int BK>
+struct loads_scalars<Im2colRowInner<ROWS, BK, false>> : std::true_type {};
+template <class T, class AL, class BL>
 struct MinBlocks {
-  static constexpr int value = 1;
-};
-template <int BK, int WM, int WN>
-struct MinBlocks<Tile<128, 96, BK, WM, WN, 32>, EpiBiasAct> {
-  static constexpr int value = 3;
+  static constexpr int value =
+      (T::BM * T::BN >= 128 * 128 && (loads_scalars<AL>::value || loads_scalars<BL>::value)) ? 2 : 3;
 };
 
 template <class T, class AL, class BL, class Epi>
-__global__ void __launch_bounds__(kThreads, (MinBlocks<T, Epi>::value))
+__global__ void __launch_bounds__(kThreads, (MinBlocks<T, AL, BL>::value))
 gemm_kernel(typename AL::Params ap, typename BL::Params bp, Epi ep, int M, int N, int K, int kchunk, int nsplit) {
   __shared__ __attribute__((aligned(16))) float As[2][AL::LDS_FLOATS];
   __shared__ __attribute__((aligned(16))) float Bs[2][BL::LDS_FLOATS];

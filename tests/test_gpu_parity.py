@@ -1,6 +1,8 @@
 """GPU parity: every call goes through the C ABI and is compared with the
 float64 oracle on the same seeded inputs."""
+import contextlib
 import math
+import os
 
 import numpy as np
 import pytest
@@ -37,9 +39,26 @@ def test_param_roundtrip_is_bit_exact(lib):
 
 
 # ---------------------------------------------------- single conv layers ----
+@contextlib.contextmanager
+def conv_path(direct):
+    """The library reads ALEXNET_DIRECT_CONV when a handle is created: "1" keeps the 3x3 unit-stride stages
+    on the direct implicit GEMM instead of the tile-transform path."""
+    old = os.environ.get("ALEXNET_DIRECT_CONV")
+    os.environ["ALEXNET_DIRECT_CONV"] = "1" if direct else "0"
+    try:
+        yield
+    finally:
+        if old is None:
+            del os.environ["ALEXNET_DIRECT_CONV"]
+        else:
+            os.environ["ALEXNET_DIRECT_CONV"] = old
+
+
+@pytest.mark.parametrize("direct", [False, True], ids=["transformed3x3", "direct3x3"])
 @pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5)])
-def test_conv_layers_alone(lib, wl, batch):
-    net = lib.AlexNet(wl, batch)
+def test_conv_layers_alone(lib, wl, batch, direct):
+    with conv_path(direct):
+        net = lib.AlexNet(wl, batch)
     spec = oracle_spec(wl, batch)
     for li, (cv, st) in enumerate(zip(spec.conv, stage_io_shapes(spec)), start=1):
         cin, h, w = st["in"]
@@ -61,6 +80,45 @@ def test_conv_layers_alone(lib, wl, batch):
         assert rel_l2(dw.cpu().numpy(), dw_ref) <= TENSOR_RTOL, (li, rel_l2(dw.cpu().numpy(), dw_ref))
         assert rel_l2(db.cpu().numpy(), db_ref) <= TENSOR_RTOL
     net.close()
+
+
+def test_3x3_stages_take_the_transform_path_by_default(lib):
+    """Same inputs through a default handle and through one created with ALEXNET_DIRECT_CONV=1: both
+    within the bar of the oracle, but not bit-identical on the 3x3 stages -- they are different
+    arithmetic -- and bit-identical on the others."""
+    wl, batch = S.MIDI, 5
+    with conv_path(False):
+        a = lib.AlexNet(wl, batch)
+    with conv_path(True):
+        b = lib.AlexNet(wl, batch)
+    spec = oracle_spec(wl, batch)
+    for li, (cv, st) in enumerate(zip(spec.conv, stage_io_shapes(spec)), start=1):
+        cin, h, w = st["in"]
+        cout, ho, wo = st["conv"]
+        x = S.make_normal((batch, cin, h, w), 110 + li)
+        wt = S.make_normal((cout, cin // cv.groups, cv.k, cv.k), 120 + li, std=0.05)
+        bias = S.make_normal((cout,), 130 + li)
+        dy = S.make_normal((batch, cout, ho, wo), 140 + li)
+        outs = []
+        for net in (a, b):
+            y = net.conv_forward(li, x, wt, bias, relu=False).cpu().numpy()
+            dx = net.conv_backward_data(li, dy, wt, x.shape).cpu().numpy()
+            dw, _ = net.conv_backward_weight(li, x, dy, wt.shape)
+            outs.append((y, dx, dw.cpu().numpy()))
+        same = [np.array_equal(p, q) for p, q in zip(*outs)]
+        if cv.k == 3 and cv.stride == 1:
+            assert not any(same), (li, same)
+            for p, q in zip(*outs):
+                assert rel_l2(p, q) <= 1e-5, li
+        else:
+            assert all(same), (li, same)
+    a.close()
+    b.close()
+
+
+def test_mini_three_steps_with_direct_3x3_stages(lib):
+    with conv_path(True):
+        run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01)
 
 
 # --------------------------------------------------------- preprocess -------
