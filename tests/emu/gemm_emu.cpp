@@ -81,15 +81,18 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
                 for (int j = 0; j < T::TN; ++j) b[lane][j] = Bs[lds_index<BL>(wn * (T::TN * RB) + lane % RB + j * RB, kr)];
               }
               // one MFMA: D[ii][jj] += sum over g < G of X[ii][g] * Y[g][jj]; lane g*RB+ii holds X[ii][g],
-              // lane g*RB+jj holds Y[g][jj]; register r of lane l is D[acc_row(l, r)][l % RB].  The kernel passes
-              // the B fragment as X and the A fragment as Y, so D is the block of C transposed.
+              // lane g*RB+jj holds Y[g][jj]; register r of lane l is D[acc_row(l, r)][l % RB].  For an epilogue
+              // with kTransposed the kernel passes the B fragment as X and the A fragment as Y, so D is the
+              // block of C transposed; otherwise X = A, Y = B.
               for (int i = 0; i < T::TM; ++i)
                 for (int j = 0; j < T::TN; ++j)
                   for (int lane = 0; lane < 64; ++lane)
                     for (int r = 0; r < T::NACC; ++r) {
                       const int ii = T::acc_row(lane, r), jj = lane % RB;
                       float s = 0.f;
-                      for (int k2 = 0; k2 < G; ++k2) s += b[k2 * RB + ii][j] * a[k2 * RB + jj][i];
+                      for (int k2 = 0; k2 < G; ++k2)
+                        s += Epi::kTransposed ? b[k2 * RB + ii][j] * a[k2 * RB + jj][i]
+                                              : a[k2 * RB + ii][i] * b[k2 * RB + jj][j];
                       ACC(wave, i, j, lane, r) += s;
                     }
             }
@@ -100,9 +103,19 @@ static void emu_gemm(typename AL::Params ap, typename BL::Params bp, Epi ep, int
           constexpr int RB = T::RB;
           for (int lane = 0; lane < 64; ++lane)
             for (int i = 0; i < T::TM; ++i)
-              for (int j = 0; j < T::TN; ++j)
-                store_block<T>(e, &ACC(wave, i, j, lane, 0), m0 + wm * (T::TM * RB) + i * RB + lane % RB,
-                               n0 + wn * (T::TN * RB) + j * RB, lane, M, N);
+              for (int j = 0; j < T::TN; ++j) {
+                if (Epi::kTransposed) {
+                  store_block<T>(e, &ACC(wave, i, j, lane, 0), m0 + wm * (T::TM * RB) + i * RB + lane % RB,
+                                 n0 + wn * (T::TN * RB) + j * RB, lane, M, N);
+                  continue;
+                }
+                const int n = n0 + wn * (T::TN * RB) + j * RB + lane % RB;
+                if (n >= N) continue;
+                for (int r = 0; r < T::NACC; ++r) {
+                  const int m = m0 + wm * (T::TM * RB) + i * RB + T::acc_row(lane, r);
+                  if (m < M) e.apply(m, n, ACC(wave, i, j, lane, r));
+                }
+              }
         }
       }
 }
