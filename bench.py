@@ -28,7 +28,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # Memory-side traffic of the GEMM launches of one fp32 batch-128 step, bytes per launch (23 launches):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB elementwise copy, from
 # profiles/train_step_alexnet_b128_fp32_counters.txt.  Not measured for other configurations.
-GEMM_TRAFFIC_FP32_B128 = 422544344
+GEMM_TRAFFIC_FP32_B128 = 343229955
 PEAK_HBM_GBS = 8000.0
 
 
@@ -166,7 +166,11 @@ def main():
         "frac": round(achieved / peak, 4),
         "traffic": GEMM_TRAFFIC_FP32_B128 if (not bf16 and batch == 128) else None,
         "launches_per_step": gemm_calls // prof_steps,
+        # flops the launches execute for the layers: 2 x multiply-adds of the operation for the direct
+        # convolutions and the dense layers, and the 36 channel products of the transformed 3x3 layers
+        # (2.6x fewer multiply-adds than their direct form, so this is below the step's 4.136 GFLOP/image)
         "flops_per_launch": gemm_flops / max(gemm_calls, 1),
+        "flops_by_definition_per_launch": 4.136e9 * batch / max(gemm_calls // prof_steps, 1),
         "avg_launch_ms": gemm_ms / max(gemm_calls, 1),
         "share_of_kernel_time": round(gemm_ms / all_ms, 4) if all_ms > 0 else None,
     }
