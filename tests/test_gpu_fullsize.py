@@ -135,3 +135,34 @@ def test_full_alexnet_bf16_step_batch256(lib):
                                 report=errs)
     print("bf16 batch 256: loss", loss, "worst gradient rel-L2", max(errs.values()), flush=True)
     assert abs(loss - np.log(1000)) < 0.05
+
+
+@pytest.mark.parametrize("batch", [128, 256])
+def test_train_step_equals_its_parts_bit_for_bit_at_full_size(lib, batch):
+    """`alexnet_train_step` runs the dense-layer update, the weight re-packing and the tap transforms of the
+    3x3 stages on the handle's own stream under the forward and backward passes; two steps that way must leave
+    exactly the parameters and momentum that forward_backward + apply_update leave (same kernels, same order
+    per tensor), at the sizes and in the launch configuration bench.py times (batch 256: `--batch 256`).
+    A missing wait between the streams would show here, where the kernels are long, not on the small nets."""
+    wl = S.ALEXNET
+    a, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3)
+    b, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3)
+    mean = cuda(S.make_mean_image(3, 256, 256, S.SEED_BASE + 7))
+    for step in range(2):
+        raw, labels = S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 30 + step)
+        raw, labels = cuda(raw), cuda(labels)
+        a.preprocess(raw, mean, step, step % 2)
+        b.preprocess(raw, mean, step, step % 2)
+        la = float(a.train_step(labels, step, slot=step % 2).cpu().item())
+        lb = float(b.forward_backward(labels, step, slot=step % 2).cpu().item())
+        b.apply_update()
+        assert la == lb, (step, la, lb)
+    a.check()
+    b.check()
+    pa, pb, ma, mb = a.get_params(), b.get_params(), a.get_momentum(), b.get_momentum()
+    for k in pa:
+        assert np.array_equal(pa[k], pb[k]), k
+        assert np.array_equal(ma[k], mb[k]), k
+    assert any(np.abs(v).max() > 0 for v in ma.values())
+    a.close()
+    b.close()
