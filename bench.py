@@ -223,7 +223,7 @@ def main():
                                                 for i in range(4)]))
         hlab = torch.from_numpy(np.concatenate([S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 3 + i)[1]
                                                 for i in range(4)]))
-        loader = B.Loader(net, himg, hlab, depth=3)
+        loader = B.Loader(net, himg, hlab, depth=3, copy_stream=side)
         torch.cuda.synchronize()
 
         lab = loader.stage(0, mean, side, compute)
@@ -242,7 +242,7 @@ def main():
         host_loader = {"value": round(batch * args.steps / dt_l, 1), "unit": "images/s",
                        "ms_per_step": round(dt_l / args.steps * 1e3, 4),
                        "note": f"{count} stored pictures in pageable host memory -> pinned staging (3 sets) -> "
-                               "host-to-device copies on the loader's stream -> on-device preprocessing; "
+                               "host-to-device copies on the side stream -> on-device preprocessing; "
                                "PCIe inclusive"}
         loader.close()
 

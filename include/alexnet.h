@@ -180,8 +180,14 @@ int alexnet_validate(alexnet_t* net, int32_t slot, const int32_t* d_labels, cons
  * bytes) and pinned_labels (depth*batch int32), and device memory d_raw /
  * d_labels of the same sizes; all must outlive the loader.  The thread copies
  * minibatch k into staging set k % depth and issues its host-to-device copies
- * on a stream of the loader's own, at most `depth` minibatches ahead of
- * alexnet_loader_done.
+ * on copy_stream, at most `depth` minibatches ahead of alexnet_loader_done.
+ * copy_stream is best the side stream later given to alexnet_loader_stage:
+ * a copy always precedes the preprocessing of the same minibatch there, and
+ * a process then needs only four streams (default, compute, side, the
+ * handle's own), which is the number of hardware queues HIP gives a process
+ * by default -- a fifth stream shares a queue with one of the others and its
+ * waits then hold that one up (measured: 4.6 -> 5.1 ms per step).  Null makes
+ * the loader create a stream of its own.
  *
  * alexnet_loader_stage(k): k must be the next minibatch in order and at most
  * two ahead of alexnet_loader_done (there are two input slots).  Blocks the
@@ -197,7 +203,8 @@ int alexnet_validate(alexnet_t* net, int32_t slot, const int32_t* d_labels, cons
 typedef struct alexnet_loader alexnet_loader_t;
 int alexnet_loader_create(alexnet_t* net, const alexnet_config_t* cfg, const uint8_t* host_images,
                           const int32_t* host_labels, int64_t count, int32_t depth, void* pinned_raw,
-                          void* pinned_labels, void* d_raw, void* d_labels, alexnet_loader_t** out);
+                          void* pinned_labels, void* d_raw, void* d_labels, void* copy_stream,
+                          alexnet_loader_t** out);
 int alexnet_loader_stage(alexnet_loader_t* loader, uint64_t k, const float* d_mean, void* side_stream,
                          void* compute_stream, const int32_t** d_labels_k);
 int alexnet_loader_done(alexnet_loader_t* loader, uint64_t k, void* compute_stream);

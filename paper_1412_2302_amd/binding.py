@@ -55,7 +55,7 @@ _SIGS = {
     "alexnet_average_replicas": [_vp, _vp, _vp],
     "alexnet_average_gradients_update": [_vp, _vp, _vp],
     "alexnet_preprocess_center": [_vp, _vp, _vp, _i32, _vp],
-    "alexnet_loader_create": [_vp, _vp, _vp, _vp, C.c_int64, _i32, _vp, _vp, _vp, _vp, C.POINTER(_vp)],
+    "alexnet_loader_create": [_vp, _vp, _vp, _vp, C.c_int64, _i32, _vp, _vp, _vp, _vp, _vp, C.POINTER(_vp)],
     "alexnet_loader_stage": [_vp, _u64, _vp, _vp, _vp, C.POINTER(_vp)],
     "alexnet_loader_done": [_vp, _u64, _vp],
     "alexnet_loader_destroy": [_vp],
@@ -405,7 +405,9 @@ class Loader:
     """Section 2.1's loading thread: `images` (uint8 [count][C][RH][RW]) and `labels` (int32 [count]) are CPU
     tensors standing for the disk; staging memory (pinned host + device) is allocated here with torch."""
 
-    def __init__(self, net: AlexNet, images: torch.Tensor, labels: torch.Tensor, depth: int = 2):
+    def __init__(self, net: AlexNet, images: torch.Tensor, labels: torch.Tensor, depth: int = 2, copy_stream=None):
+        """copy_stream: the stream of the host-to-device copies (best the side stream later given to stage());
+        None lets the library create one."""
         assert images.dtype == torch.uint8 and labels.dtype == torch.int32 and not images.is_cuda
         self.net, self.images, self.labels = net, images.contiguous(), labels.contiguous()
         per = net.batch * int(np.prod(images.shape[1:]))
@@ -417,8 +419,10 @@ class Loader:
         _check(_lib.alexnet_loader_create(net._h, C.byref(net.cfg), self.images.data_ptr(), self.labels.data_ptr(),
                                           self.images.shape[0], depth, self.pinned_raw.data_ptr(),
                                           self.pinned_labels.data_ptr(), self.d_raw.data_ptr(),
-                                          self.d_labels.data_ptr(), C.byref(h)))
+                                          self.d_labels.data_ptr(),
+                                          None if copy_stream is None else _stream(copy_stream), C.byref(h)))
         self._h = h
+        self._copy_stream = copy_stream  # keep the torch stream alive as long as the loader
 
     def stage(self, k: int, mean: torch.Tensor, side_stream, compute_stream) -> torch.Tensor:
         """Returns the labels of minibatch k (a view of the loader's device buffer)."""

@@ -1,7 +1,7 @@
 // Loading thread of Section 2.1 (Figure 1): while the GPU trains on minibatch k, a host thread copies
 // minibatch k+1 from the stored pictures ("disk", here an array in ordinary host memory) into pinned
-// staging memory and on to the GPU over a copy stream of its own; mean subtraction, crop and mirror then
-// run on the device (alexnet_preprocess) on the caller's side stream.  Uses only the public C ABI and the
+// staging memory and on to the GPU over the caller's side stream (or a stream of its own); mean subtraction,
+// crop and mirror then run on the device (alexnet_preprocess) on the caller's side stream.  Uses only the public C ABI and the
 // HIP runtime; all buffers are the caller's.
 #include <hip/hip_runtime.h>
 #include <string.h>
@@ -26,6 +26,7 @@ struct alexnet_loader {
   uint8_t *pinned_raw, *d_raw;
   int32_t *pinned_labels, *d_labels;
   hipStream_t copy_stream;
+  bool own_stream;  // copy_stream was created here (the caller gave none)
   std::vector<hipEvent_t> copy_done, pre_done, step_done;  // one of each per staging set
   std::thread worker;
   std::mutex mu;
@@ -111,7 +112,8 @@ extern "C" {
 
 int alexnet_loader_create(alexnet_t* net, const alexnet_config_t* cfg, const uint8_t* host_images,
                           const int32_t* host_labels, int64_t count, int32_t depth, void* pinned_raw,
-                          void* pinned_labels, void* d_raw, void* d_labels, alexnet_loader_t** out) {
+                          void* pinned_labels, void* d_raw, void* d_labels, void* copy_stream,
+                          alexnet_loader_t** out) {
   if (!net || !cfg || !host_images || !host_labels || !pinned_raw || !pinned_labels || !d_raw || !d_labels || !out) {
     set_error("alexnet_loader_create: null argument");
     return ALEXNET_EINVAL;
@@ -135,9 +137,10 @@ int alexnet_loader_create(alexnet_t* net, const alexnet_config_t* cfg, const uin
   L->produced = L->staged = L->released = 0;
   L->stop = false;
   L->worker_error = 0;
-  L->copy_stream = nullptr;
+  L->copy_stream = (hipStream_t)copy_stream;
+  L->own_stream = copy_stream == nullptr;
   hipError_t e = hipGetDevice(&L->device);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&L->copy_stream, hipStreamNonBlocking);
+  if (e == hipSuccess && L->own_stream) e = hipStreamCreateWithFlags(&L->copy_stream, hipStreamNonBlocking);
   for (int i = 0; e == hipSuccess && i < depth; ++i) {
     hipEvent_t a = nullptr, b = nullptr, c = nullptr;
     e = hipEventCreateWithFlags(&a, hipEventDisableTiming);
@@ -152,7 +155,7 @@ int alexnet_loader_create(alexnet_t* net, const alexnet_config_t* cfg, const uin
     destroy_events(L->copy_done);
     destroy_events(L->pre_done);
     destroy_events(L->step_done);
-    if (L->copy_stream) (void)hipStreamDestroy(L->copy_stream);
+    if (L->own_stream && L->copy_stream) (void)hipStreamDestroy(L->copy_stream);
     delete L;
     return ALEXNET_EHIP;
   }
@@ -231,7 +234,7 @@ int alexnet_loader_destroy(alexnet_loader_t* L) {
   destroy_events(L->copy_done);
   destroy_events(L->pre_done);
   destroy_events(L->step_done);
-  (void)hipStreamDestroy(L->copy_stream);
+  if (L->own_stream) (void)hipStreamDestroy(L->copy_stream);
   delete L;
   return ALEXNET_OK;
 }

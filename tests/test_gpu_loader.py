@@ -12,8 +12,10 @@ from oracle import alexnet_oracle as O
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("depth", [2, 3])
-def test_loader_matches_resident_training_bit_for_bit(lib, depth):
+@pytest.mark.parametrize("depth,shared_stream", [(2, True), (3, True), (3, False)])
+def test_loader_matches_resident_training_bit_for_bit(lib, depth, shared_stream):
+    """shared_stream: the loading thread issues its host-to-device copies on the caller's side stream
+    (the recommended set-up) instead of a stream of the loader's own."""
     wl, batch, steps, count = S.MIDI, 6, 7, 15   # 15 pictures: minibatches wrap around the data set
     raw, labels = S.make_raw_batch(count, 3, 80, 80, 37, 500)
     mean = cuda(S.make_mean_image(3, 80, 80, 501))
@@ -32,8 +34,9 @@ def test_loader_matches_resident_training_bit_for_bit(lib, depth):
 
     # (2) through the loader, preprocessing on a side stream
     net, _, _, _ = build_pair(lib, wl, batch, seed=31, bias=0.05, std=0.03, mom_std=0.01)
-    loader = lib.Loader(net, torch.from_numpy(raw), torch.from_numpy(labels), depth=depth)
     compute, side = torch.cuda.Stream(), torch.cuda.Stream()
+    loader = lib.Loader(net, torch.from_numpy(raw), torch.from_numpy(labels), depth=depth,
+                        copy_stream=side if shared_stream else None)
     torch.cuda.synchronize()
     losses = []
     lab = loader.stage(0, mean, side, compute)
