@@ -52,7 +52,7 @@ int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, co
 int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
                            float* ws, hipStream_t st);
 
-// ---- dense layers (fc_gemm.hip) ---------------------------------------------
+// ---- dense layers (conv_gemm.hip) -------------------------------------------
 struct FcAct {
   const float* bias;  // [out]
   int relu;

@@ -3,6 +3,8 @@
 // kernels as a 1x1 convolution with 36*groups groups.
 #include "winograd.h"
 
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace ax {
