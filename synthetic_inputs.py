@@ -65,7 +65,24 @@ MIDI = {
     "dropout_p": 0.5, "lr": 0.01, "momentum": 0.9, "weight_decay": 5e-4,
 }
 
-WORKLOADS = {"alexnet": ALEXNET, "mini": MINI, "midi": MIDI}
+# 3x3 unit-stride layers with every padding (0, 1, 2) over map sizes that are not multiples of the 4x4 tiles
+# of the transformed path: 31 -> 29 -> 31 -> 31 (pool 15) -> 13 -> 15 (pool 7); flatten 8*7*7 = 392.
+PADS = {
+    "name": "pads",
+    "in_c": 3, "crop": 31, "raw": 31,
+    "conv": [
+        (8, 3, 1, 0, 1, 0, 0),
+        (16, 3, 1, 2, 1, 0, 0),
+        (16, 3, 1, 1, 2, 0, 1),
+        (24, 3, 1, 0, 1, 0, 0),
+        (8, 3, 1, 2, 2, 0, 1),
+    ],
+    "fc": [32, 16, 5],
+    "lrn": (5, 2.0, 1e-4, 0.75),
+    "dropout_p": 0.5, "lr": 0.01, "momentum": 0.9, "weight_decay": 5e-4,
+}
+
+WORKLOADS = {"alexnet": ALEXNET, "mini": MINI, "midi": MIDI, "pads": PADS}
 
 
 def make_params(shapes, seed: int, bias_value: float = 0.0, std: float = 0.01):

@@ -55,7 +55,7 @@ def conv_path(direct):
 
 
 @pytest.mark.parametrize("direct", [False, True], ids=["transformed3x3", "direct3x3"])
-@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5)])
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5), (S.PADS, 3)])
 def test_conv_layers_alone(lib, wl, batch, direct):
     with conv_path(direct):
         net = lib.AlexNet(wl, batch)
@@ -114,6 +114,10 @@ def test_3x3_stages_take_the_transform_path_by_default(lib):
             assert all(same), (li, same)
     a.close()
     b.close()
+
+
+def test_whole_step_with_paddings_0_1_2_and_ragged_tiles(lib):
+    run_step_and_compare(lib, S.PADS, 3, seed=14, bias=0.05, std=0.08, use_raw=False, steps=2, mom_std=0.01)
 
 
 def test_mini_three_steps_with_direct_3x3_stages(lib):
