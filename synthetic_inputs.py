@@ -82,7 +82,23 @@ PADS = {
     "dropout_p": 0.5, "lr": 0.01, "momentum": 0.9, "weight_decay": 5e-4,
 }
 
-WORKLOADS = {"alexnet": ALEXNET, "mini": MINI, "midi": MIDI, "pads": PADS}
+# Degenerate sizes: 15 -> conv1(3,s2) 7 -> pool 3 -> conv2 3 -> pool 1 -> conv3/4/5 on 1x1 maps; flatten 8.
+TINY = {
+    "name": "tiny",
+    "in_c": 3, "crop": 15, "raw": 15,
+    "conv": [
+        (8, 3, 2, 0, 1, 1, 1),
+        (8, 3, 1, 1, 2, 1, 1),
+        (8, 3, 1, 1, 1, 0, 0),
+        (8, 3, 1, 1, 2, 0, 0),
+        (8, 3, 1, 1, 2, 0, 0),
+    ],
+    "fc": [12, 8, 3],
+    "lrn": (5, 2.0, 1e-4, 0.75),
+    "dropout_p": 0.5, "lr": 0.01, "momentum": 0.9, "weight_decay": 5e-4,
+}
+
+WORKLOADS = {"alexnet": ALEXNET, "mini": MINI, "midi": MIDI, "pads": PADS, "tiny": TINY}
 
 
 def make_params(shapes, seed: int, bias_value: float = 0.0, std: float = 0.01):

@@ -120,6 +120,13 @@ def test_whole_step_with_paddings_0_1_2_and_ragged_tiles(lib):
     run_step_and_compare(lib, S.PADS, 3, seed=14, bias=0.05, std=0.08, use_raw=False, steps=2, mom_std=0.01)
 
 
+@pytest.mark.parametrize("wl,batch", [(S.TINY, 1), (S.TINY, 2), (S.MINI, 1)])
+def test_whole_step_at_degenerate_sizes(lib, wl, batch):
+    """Batch 1 and 2, maps that shrink to 3x3 and 1x1 (one 4x4 tile per picture on the transformed path,
+    one pixel per picture on the direct one), dense layers narrower than a GEMM tile."""
+    run_step_and_compare(lib, wl, batch, seed=15, bias=0.1, std=0.3, use_raw=False, steps=2, mom_std=0.01)
+
+
 def test_mini_three_steps_with_direct_3x3_stages(lib):
     with conv_path(True):
         run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01)
