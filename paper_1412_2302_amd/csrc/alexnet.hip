@@ -81,7 +81,8 @@ struct Stage {
   float* wphase;        // weights regrouped by phase for a strided backward-data pass (null when not used)
   // 3x3 unit-stride stages run through the F(4x4, 3x3) transforms: the transformed input of the forward pass
   // (kept for the weight gradient) and the transformed taps of the forward and backward-data passes
-  bool wino;
+  bool wino;     // forward and weight gradient
+  bool wino_bx;  // data gradient too
   float *wino_v, *wino_u, *wino_ub;
   float *wrun, *dwrun;  // run-mode copies of the weights and their gradient (null when not used)
   uint8_t* slot;
@@ -136,14 +137,14 @@ struct alexnet {
   hipEvent_t ev_fc_done, ev_upd_done, ev_step_begin, ev_wb_done, ev_u_done;
 };
 
-// F(4x4, 3x3) pays when the 4x4 tiles cover the output without much waste (2.6x fewer multiplies at 13 x 13);
+// F(4x4, 3x3) pays when the 4x4 tiles cover the output without much waste (2.6x fewer multiplies for the 3x3
+// layers at 13 x 13 and for the 5x5 layer, as four 3x3 sub-kernels, at 27 x 27);
 // the environment variable ALEXNET_DIRECT_CONV=1 keeps every stage on the direct implicit GEMM.
 static bool use_winograd(const alexnet_config_t& c, const ConvGeom& g) {
   if (c.precision != ALEXNET_PRECISION_FP32 || !wino_ok(g)) return false;
   const char* e = getenv("ALEXNET_DIRECT_CONV");
   if (e && e[0] == '1') return false;
-  const double covered = (double)g.Ho * g.Wo / (16.0 * ((g.Ho + 3) / 4) * ((g.Wo + 3) / 4));
-  return 4.0 * covered >= 1.5;
+  return wino_gain(g) >= 1.5;
 }
 
 static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
@@ -255,9 +256,10 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.wrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     s.dwrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     s.wino = use_winograd(c, s.g) && s.w_off % 4 == 0 && s.b_off % 4 == 0;
+    s.wino_bx = s.wino && wino_bwd_data_ok(s.g);
     s.wino_v = s.wino ? a.take<float>(wino_v_floats(s.g)) : nullptr;
     s.wino_u = s.wino ? a.take<float>(wino_u_floats(s.g)) : nullptr;
-    s.wino_ub = s.wino ? a.take<float>(wino_u_floats(s.g)) : nullptr;
+    s.wino_ub = s.wino_bx ? a.take<float>(wino_u_floats(s.g)) : nullptr;
     if (s.wino) {
       wscr = std::max(wscr, wino_scratch_floats(s.g));
       wdu = std::max(wdu, wino_u_floats(s.g));
@@ -280,7 +282,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     for (int i = 1; i < kStages && c.precision == ALEXNET_PRECISION_FP32; ++i) {
       const Stage& s = n->st[i];
       const double fl = (double)s.g.P() * s.g.Cout * s.g.cg() * s.g.k * s.g.k;
-      if (!s.wino && fl > best) {
+      if (!s.wino_bx && fl > best) {  // a direct data gradient (its weight gradient may be transformed, see the fork)
         best = fl;
         n->upd_fork_stage = i;
       }
@@ -349,7 +351,7 @@ static int stage_bwd_weight(alexnet* n, Stage& s, const float* x, const float* d
 // taps_ready: s.wino_ub already holds the transform of wb
 static int stage_bwd_data(alexnet* n, Stage& s, const float* dy, const float* wf, const float* wb, float* wphase,
                           const float* gate, float* dx, bool taps_ready, hipStream_t st) {
-  if (wino_usable(s, dy, wb, dx, gate)) {
+  if (s.wino_bx && wino_usable(s, dy, wb, dx, gate)) {
     if (!taps_ready) AX_TRY(launch_wino_filter_bwd(s.g, wb, s.wino_ub, st));
     return launch_wino_bwd_data(s.g, dy, s.wino_ub, gate, dx, n->wino_a, n->wino_m, n->gemm_ws, st);
   }
@@ -461,20 +463,25 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     if (s.lrn && !s.fused())
       AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
                             c.lrn_alpha, c.lrn_beta, 1, st));
-    if (early_update && i == n->upd_fork_stage) {
-      // fork here, behind this stage's pooling adjoint: that kernel is bound by bandwidth like the update
-      // and would be starved by it, while the direct-convolution GEMMs that follow are not
+    // Fork of the dense-layer update, behind this stage's pooling adjoint: that kernel is bound by bandwidth
+    // like the update and would be starved by it, while the direct-convolution GEMMs that follow are not.  A
+    // transformed weight gradient is bandwidth-hungry too: then the fork waits until it has been enqueued.
+    auto fork_update = [&]() -> int {
       AX_HIP(hipEventRecord(n->ev_fc_done, st));
       AX_HIP(hipStreamWaitEvent(n->upd_stream, n->ev_fc_done, 0));
       AX_TRY(update_range(n, n->fc[0].w_off, n->n_weights, n->upd_stream));
       AX_HIP(hipEventRecord(n->ev_upd_done, n->upd_stream));
-    }
+      return ALEXNET_OK;
+    };
+    const bool fork_here = early_update && i == n->upd_fork_stage;
+    if (fork_here && !s.wino) AX_TRY(fork_update());
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
       AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st));
       if (!bias_done) AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
     }
+    if (fork_here && s.wino) AX_TRY(fork_update());
     if (i > 0) {
       ProfContext pc(s.lab[3]);
       Stage& prev = n->st[i - 1];
@@ -723,7 +730,7 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
       Stage& s = n->st[i];
       ProfContext pc(s.lab[3]);
       AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, n->upd_stream));
-      if (s.wino) AX_TRY(launch_wino_filter_bwd(s.g, s.wb, s.wino_ub, n->upd_stream));
+      if (s.wino_bx) AX_TRY(launch_wino_filter_bwd(s.g, s.wb, s.wino_ub, n->upd_stream));
     }
     AX_HIP(hipEventRecord(n->ev_wb_done, n->upd_stream));
   }

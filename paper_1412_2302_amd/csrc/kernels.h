@@ -34,10 +34,14 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
                            hipStream_t st, int* slices = nullptr);
 
-// ---- 3x3 unit-stride convolutions through F(4x4, 3x3) (winograd.hip) ------------
+// ---- 3x3 and 5x5 unit-stride convolutions through F(4x4, 3x3) (winograd.hip) ----
 // All tensors 16-byte aligned, channels per group multiples of 4.  V: wino_v_floats(), U / Ub / dU:
 // wino_u_floats(), every other transformed tensor (v, m, yt): wino_scratch_floats(); ws: wino_gemm_ws_floats().
+// wino_ok: forward and weight gradient can take this path; wino_bwd_data_ok: the data gradient too (3x3 only);
+// wino_gain: multiplies of the direct form per multiply of the transformed one at this layer's map size.
 bool wino_ok(const ConvGeom& c);
+bool wino_bwd_data_ok(const ConvGeom& c);
+double wino_gain(const ConvGeom& c);
 size_t wino_v_floats(const ConvGeom& c);
 size_t wino_u_floats(const ConvGeom& c);
 size_t wino_scratch_floats(const ConvGeom& c);

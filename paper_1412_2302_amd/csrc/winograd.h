@@ -16,6 +16,12 @@
 // exactly a channel-last activation tensor of a 1x1 convolution with 36*groups groups, so the 36 products
 // run as one launch of the grouped implicit-GEMM kernels (conv_gemm.hip) and need no kernel of their own.
 //
+// 5x5 kernels (the second layer) use the same transforms: a 5x5 correlation is the sum of four 3x3
+// correlations of the input shifted by 0 or 3 pixels in each direction, with the sub-kernels
+// w[3qy + i][3qx + j] (zero where that tap does not exist).  The four sub-kernels q are concatenated
+// along the reduction of the products, column (p*groups + g)*(4*Cg) + q*Cg + c, so the sum over them
+// happens inside the matrix product: 36 * 4 multiplies per tile and channel pair instead of 400.
+//
 // Everything here is per-thread code shared by the kernels (winograd.hip) and by the CPU emulation test,
 // which runs it thread by thread under an address sanitizer.
 #pragma once
@@ -103,9 +109,11 @@ AX_HD void wino_gt(const Vec4* m, Vec4* o) {
 // ---- geometry of one transformed convolution -----------------------------------------------------
 // `H x W` is the tensor the 6x6 tiles are cut from (pad `pad` on every side), `OH x OW` the tensor
 // of 4x4 tiles (OH = H + 2*pad - 2).  Ctot = groups * Cg channels on the gathered side.
+// k x k taps are handled as nsub x nsub sub-kernels of 3x3 (k = 3: one, k = 5: four).
 struct WinoGeom {
-  int B, H, W, pad, OH, OW, th, tw, groups;
+  int B, H, W, pad, OH, OW, th, tw, groups, k, nsub;
   AX_HD int tiles() const { return B * th * tw; }
+  AX_HD int nq() const { return nsub * nsub; }
 };
 struct WinoTile {
   int n, ty, tx;
@@ -120,13 +128,16 @@ AX_HD WinoTile wino_tile(const WinoGeom& g, int t) {
   return r;
 }
 
-// V[t][(p*groups + g)*Cg + c] = (Bt d B)[p] of the 6x6 patch of x that tile t reads (zero outside x).
-// idx enumerates (tile, channel quad); x is [B][H][W][groups*Cg].
+// V[t][(p*groups + g)*(nq*Cg) + q*Cg + c] = (Bt d B)[p] of the 6x6 patch of x that sub-kernel q of tile t
+// reads (zero outside x).  idx enumerates (tile, sub-kernel, channel quad); x is [B][H][W][groups*Cg].
 AX_HD void wino_in_thread(const WinoGeom& g, int Cg, const float* x, float* V, long idx) {
-  const int Ctot = g.groups * Cg, quads = Ctot / 4;
-  const int t = (int)(idx / quads), c = 4 * (int)(idx - (long)t * quads);
+  const int Ctot = g.groups * Cg, quads = Ctot / 4, nq = g.nq();
+  const int t = (int)(idx / ((long)nq * quads));
+  const int rem = (int)(idx - (long)t * nq * quads);
+  const int q = rem / quads, c = 4 * (rem - q * quads);
+  const int qy = q / g.nsub, qx = q - qy * g.nsub;
   const WinoTile tl = wino_tile(g, t);
-  const int y0 = 4 * tl.ty - g.pad, x0 = 4 * tl.tx - g.pad;
+  const int y0 = 4 * tl.ty - g.pad + 3 * qy, x0 = 4 * tl.tx - g.pad + 3 * qx;
   Vec4 d[36], u[36];
 #pragma unroll
   for (int i = 0; i < 6; ++i)
@@ -140,13 +151,14 @@ AX_HD void wino_in_thread(const WinoGeom& g, int Cg, const float* x, float* V, l
 #pragma unroll
   for (int j = 0; j < 6; ++j) wino_bt<6, 6>(d + j, u + j);  // columns
   const int grp = c / Cg, cl = c - grp * Cg;
-  float* out = V + (long)t * 36 * Ctot + (long)grp * Cg + cl;
+  const long pstride = (long)nq * Ctot;
+  float* out = V + (long)t * 36 * pstride + (long)grp * nq * Cg + (long)q * Cg + cl;
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
     Vec4 r[6];
     wino_bt<1, 1>(u + 6 * i, r);  // row i
 #pragma unroll
-    for (int j = 0; j < 6; ++j) vstore(out + (long)(6 * i + j) * Ctot, r[j]);
+    for (int j = 0; j < 6; ++j) vstore(out + (long)(6 * i + j) * pstride, r[j]);
   }
 }
 
@@ -225,58 +237,73 @@ AX_HD void wino_out_thread(const WinoGeom& g, int Ng, const float* M, const floa
   }
 }
 
-// Taps to transformed taps and back.  `w` is [groups][(r, s, a)][b] (3x3 taps; a < Na rows, b < Nb
+// Taps to transformed taps and back.  `w` is [groups][(r, s, a)][b] (k x k taps; a < Na rows, b < Nb
 // columns: the forward weights with a = input channel, b = output channel, or the backward-data
-// weights with the roles swapped), `U` is [(p*groups + g)][a][b].  flip reverses both tap axes
-// (the backward-data correlation).  idx enumerates (group, a, column quad).
-AX_HD void wino_filter_thread(int groups, int Na, int Nb, int flip, const float* w, float* U, long idx) {
-  const int quads = Nb / 4;
-  const long row = idx / quads;  // g*Na + a
+// weights with the roles swapped), `U` is [(p*groups + g)][q*Na + a][b] for sub-kernel q = (qy, qx) with the
+// taps (3qy + i, 3qx + j), zero where they do not exist.  flip reverses both tap axes (the backward-data
+// correlation).  idx enumerates (group, sub-kernel, a, column quad).
+AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int flip, const float* w, float* U,
+                              long idx) {
+  const int quads = Nb / 4, nq = nsub * nsub;
+  const long row = idx / quads;  // (g*nq + q)*Na + a
   const int b = 4 * (int)(idx - row * quads);
-  const int grp = (int)(row / Na), a = (int)(row - (long)grp * Na);
-  Vec4 k[9], u[18];
+  const int grp = (int)(row / ((long)nq * Na)), r2 = (int)(row - (long)grp * nq * Na);
+  const int q = r2 / Na, a = r2 - q * Na, qy = q / nsub, qx = q - qy * nsub;
+  Vec4 t[9], u[18];
 #pragma unroll
-  for (int r = 0; r < 3; ++r)
+  for (int i = 0; i < 3; ++i)
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
-      const int tap = flip ? (2 - r) * 3 + (2 - s) : r * 3 + s;
-      k[3 * r + s] = vload(w + (((long)grp * 9 + tap) * Na + a) * Nb + b);
+    for (int j = 0; j < 3; ++j) {
+      const int r = 3 * qy + i, s2 = 3 * qx + j;
+      t[3 * i + j] = vzero();
+      if (r < k && s2 < k) {
+        const int tap = flip ? (k - 1 - r) * k + (k - 1 - s2) : r * k + s2;
+        t[3 * i + j] = vload(w + (((long)grp * k * k + tap) * Na + a) * Nb + b);
+      }
     }
 #pragma unroll
-  for (int s = 0; s < 3; ++s) wino_g<3, 3>(k + s, u + s);  // columns: 3 -> 6 rows of 3
+  for (int j = 0; j < 3; ++j) wino_g<3, 3>(t + j, u + j);  // columns: 3 -> 6 rows of 3
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
     Vec4 r[6];
     wino_g<1, 1>(u + 3 * i, r);
 #pragma unroll
-    for (int j = 0; j < 6; ++j) vstore(U + ((((long)(6 * i + j) * groups + grp) * Na + a) * Nb + b), r[j]);
+    for (int j = 0; j < 6; ++j)
+      vstore(U + (((((long)(6 * i + j) * groups + grp) * nq + q) * Na + a) * Nb + b), r[j]);
   }
 }
-// dw[groups][(r, s, a)][b] = (Gt m G)[r][s], m = sum over the ns partial products dU[(p*groups + g)*ns + s][a][b]
-// (the slices of a reduction that was split over workgroups, added here in a fixed order)
-AX_HD void wino_dw_thread(int groups, int Na, int Nb, int ns, const float* dU, float* dw, long idx) {
-  const int quads = Nb / 4;
+// dw[groups][(r, s, a)][b] = (Gt m G)[i][j] at r = 3qy + i, s = 3qx + j (taps that exist only),
+// m = sum over the ns partial products dU[(p*groups + g)*ns + slice][q*Na + a][b] (the slices of a reduction
+// that was split over workgroups, added here in a fixed order).  idx as in wino_filter_thread.
+AX_HD void wino_dw_thread(int groups, int Na, int Nb, int k, int nsub, int ns, const float* dU, float* dw, long idx) {
+  const int quads = Nb / 4, nq = nsub * nsub;
   const long row = idx / quads;
   const int b = 4 * (int)(idx - row * quads);
-  const int grp = (int)(row / Na), a = (int)(row - (long)grp * Na);
+  const int grp = (int)(row / ((long)nq * Na)), r2 = (int)(row - (long)grp * nq * Na);
+  const int q = r2 / Na, a = r2 - q * Na, qy = q / nsub, qx = q - qy * nsub;
+  const long slice = (long)nq * Na * Nb;
   Vec4 u[18];
 #pragma unroll
   for (int j = 0; j < 6; ++j) {
     Vec4 col[6];
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
-      const float* src = dU + ((((long)(6 * i + j) * groups + grp) * ns * Na + a) * Nb + b);
+      const float* src = dU + ((long)(6 * i + j) * groups + grp) * ns * slice + ((long)q * Na + a) * Nb + b;
       col[i] = vload(src);
-      for (int sl = 1; sl < ns; ++sl) col[i] = col[i] + vload(src + (long)sl * Na * Nb);
+      for (int sl = 1; sl < ns; ++sl) col[i] = col[i] + vload(src + sl * slice);
     }
-    wino_gt<1, 6>(col, u + j);  // u[r][j], 3 rows of 6
+    wino_gt<1, 6>(col, u + j);  // u[i][j], 3 rows of 6
   }
 #pragma unroll
-  for (int r = 0; r < 3; ++r) {
+  for (int i = 0; i < 3; ++i) {
     Vec4 o[3];
-    wino_gt<1, 1>(u + 6 * r, o);
+    wino_gt<1, 1>(u + 6 * i, o);
+    const int r = 3 * qy + i;
 #pragma unroll
-    for (int s = 0; s < 3; ++s) vstore(dw + (((long)grp * 9 + r * 3 + s) * Na + a) * Nb + b, o[s]);
+    for (int j = 0; j < 3; ++j) {
+      const int s2 = 3 * qx + j;
+      if (r < k && s2 < k) vstore(dw + (((long)grp * k * k + r * k + s2) * Na + a) * Nb + b, o[j]);
+    }
   }
 }
 

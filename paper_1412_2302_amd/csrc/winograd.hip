@@ -26,33 +26,43 @@ __global__ void __launch_bounds__(256) wino_out_kernel(WinoGeom g, int Ng, const
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < total) wino_out_thread(g, Ng, M, bias, relu, gate, y, idx);
 }
-__global__ void __launch_bounds__(256) wino_filter_kernel(int groups, int Na, int Nb, int flip,
+__global__ void __launch_bounds__(256) wino_filter_kernel(int groups, int Na, int Nb, int k, int nsub, int flip,
                                                            const float* __restrict__ w, float* __restrict__ U,
                                                            long total) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < total) wino_filter_thread(groups, Na, Nb, flip, w, U, idx);
+  if (idx < total) wino_filter_thread(groups, Na, Nb, k, nsub, flip, w, U, idx);
 }
-__global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb, int ns,
+__global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb, int k, int nsub, int ns,
                                                        const float* __restrict__ dU, float* __restrict__ dw,
                                                        long total) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < total) wino_dw_thread(groups, Na, Nb, ns, dU, dw, idx);
+  if (idx < total) wino_dw_thread(groups, Na, Nb, k, nsub, ns, dU, dw, idx);
 }
 
 // ---- geometry ----------------------------------------------------------------------------------
-bool wino_ok(const ConvGeom& c) {
-  if (c.k != 3 || c.stride != 1 || c.pad > 2 || c.cg() % 4 || c.og() % 4) return false;
-  // the transformed tensors are 36/16 (tiles cut exactly) to ~4x larger than the activations
-  const long th = (c.Ho + 3) / 4, tw = (c.Wo + 3) / 4, thb = (c.H + 3) / 4, twb = (c.W + 3) / 4;
-  const long T = std::max((long)c.B * th * tw, (long)c.B * thb * twb);
-  return T * 36 * std::max(c.Cin, c.Cout) <= 0x1ffffff0L;
-}
+static inline int nsub_of(const ConvGeom& c) { return (c.k + 2) / 3; }
+static inline int nq_of(const ConvGeom& c) { return nsub_of(c) * nsub_of(c); }
 static WinoGeom fwd_geom(const ConvGeom& c) {
-  return WinoGeom{c.B, c.H, c.W, c.pad, c.Ho, c.Wo, (c.Ho + 3) / 4, (c.Wo + 3) / 4, c.groups};
+  return WinoGeom{c.B, c.H, c.W, c.pad, c.Ho, c.Wo, (c.Ho + 3) / 4, (c.Wo + 3) / 4, c.groups, c.k, nsub_of(c)};
 }
-// backward-data: dx = correlation of dy (pad 2 - pad) with the reversed taps
+// backward-data: dx = correlation of dy (pad k - 1 - pad) with the reversed taps
 static WinoGeom bwd_geom(const ConvGeom& c) {
-  return WinoGeom{c.B, c.Ho, c.Wo, 2 - c.pad, c.H, c.W, (c.H + 3) / 4, (c.W + 3) / 4, c.groups};
+  return WinoGeom{c.B, c.Ho, c.Wo, c.k - 1 - c.pad, c.H, c.W, (c.H + 3) / 4, (c.W + 3) / 4, c.groups, c.k, nsub_of(c)};
+}
+bool wino_ok(const ConvGeom& c) {
+  if ((c.k != 3 && c.k != 5) || c.stride != 1 || c.pad > c.k - 1 || c.cg() % 4 || c.og() % 4) return false;
+  // the transformed tensors are 36/16 (tiles cut exactly) to ~4x larger than the activations, times the
+  // number of sub-kernels on the gathered side
+  const long T = std::max((long)fwd_geom(c).tiles(), (long)bwd_geom(c).tiles());
+  return T * 36 * nq_of(c) * std::max(c.Cin, c.Cout) <= 0x1ffffff0L;
+}
+// the data gradient takes the transformed path for 3x3 kernels only (for 5x5 the four shifted transforms of
+// dy, with Cout channels each, cost what the 2.6x smaller products save)
+bool wino_bwd_data_ok(const ConvGeom& c) { return wino_ok(c) && c.k == 3; }
+// multiplies of the direct form per multiply of the products, at this map size
+double wino_gain(const ConvGeom& c) {
+  const double covered = (double)c.Ho * c.Wo / (16.0 * ((c.Ho + 3) / 4) * ((c.Wo + 3) / 4));
+  return covered * 16.0 * c.k * c.k / (36.0 * nq_of(c));
 }
 // the 36*groups channel products as a 1x1 grouped convolution over one row of `tiles` pixels
 static ConvGeom product_geom(int tiles, int groups, int kin, int nout) {
@@ -61,32 +71,38 @@ static ConvGeom product_geom(int tiles, int groups, int kin, int nout) {
   p.k = 1; p.stride = 1; p.pad = 0; p.groups = 36 * groups; p.Ho = 1; p.Wo = tiles;
   return p;
 }
-size_t wino_v_floats(const ConvGeom& c) { return (size_t)fwd_geom(c).tiles() * 36 * c.Cin; }
-size_t wino_u_floats(const ConvGeom& c) { return (size_t)36 * c.w_elems() / 9; }
+size_t wino_v_floats(const ConvGeom& c) { return (size_t)fwd_geom(c).tiles() * 36 * nq_of(c) * c.Cin; }
+size_t wino_u_floats(const ConvGeom& c) { return (size_t)36 * nq_of(c) * c.cg() * c.og() * c.groups; }
 size_t wino_scratch_floats(const ConvGeom& c) {
   const size_t tf = (size_t)fwd_geom(c).tiles(), tb = (size_t)bwd_geom(c).tiles();
-  return 36 * std::max(std::max(tf * c.Cout, tb * c.Cout), std::max(tb * c.Cin, tf * c.Cin));
+  size_t n = 36 * tf * c.Cout;  // forward products, transformed output gradient
+  if (wino_bwd_data_ok(c)) n = std::max(n, 36 * std::max(tb * c.Cout * nq_of(c), tb * c.Cin));
+  return n;
 }
 size_t wino_gemm_ws_floats(const ConvGeom& c) {
-  const ConvGeom pf = product_geom(fwd_geom(c).tiles(), c.groups, c.cg(), c.og());
-  const ConvGeom pb = product_geom(bwd_geom(c).tiles(), c.groups, c.og(), c.cg());
-  return std::max(std::max(conv_fwd_ws_floats(pf), conv_fwd_ws_floats(pb)), conv_bwd_weight_ws_floats(pf));
+  const ConvGeom pf = product_geom(fwd_geom(c).tiles(), c.groups, nq_of(c) * c.cg(), c.og());
+  size_t n = std::max(conv_fwd_ws_floats(pf), conv_bwd_weight_ws_floats(pf));
+  if (wino_bwd_data_ok(c))
+    n = std::max(n, conv_fwd_ws_floats(product_geom(bwd_geom(c).tiles(), c.groups, nq_of(c) * c.og(), c.cg())));
+  return n;
 }
 
 // ---- launchers -----------------------------------------------------------------------------------
 static inline dim3 blocks_for(long total) { return dim3((unsigned)((total + 255) / 256)); }
 
 int launch_wino_filter(const ConvGeom& c, const float* wf, float* U, hipStream_t st) {
-  const long total = (long)c.groups * c.cg() * (c.og() / 4);
-  KernelScope ks("wino_filter", 0, (double)c.w_elems() * 4.0 * 5.0, st);
-  hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), 0, wf, U, total);
+  const long total = (long)c.groups * nq_of(c) * c.cg() * (c.og() / 4);
+  KernelScope ks("wino_filter", 0, ((double)c.w_elems() + (double)wino_u_floats(c)) * 4.0, st);
+  hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), c.k, nsub_of(c),
+                     0, wf, U, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
 int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStream_t st) {
-  const long total = (long)c.groups * c.og() * (c.cg() / 4);
-  KernelScope ks("wino_filter", 0, (double)c.w_elems() * 4.0 * 5.0, st);
-  hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.og(), c.cg(), 1, wb, Ub, total);
+  const long total = (long)c.groups * nq_of(c) * c.og() * (c.cg() / 4);
+  KernelScope ks("wino_filter", 0, ((double)c.w_elems() + (double)wino_u_floats(c)) * 4.0, st);
+  hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.og(), c.cg(), c.k, nsub_of(c),
+                     1, wb, Ub, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -94,8 +110,8 @@ int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStr
 int launch_wino_input(const ConvGeom& c, const float* x, float* V, hipStream_t st) {
   const WinoGeom g = fwd_geom(c);
   const int T = g.tiles();
-  const long total = (long)T * (c.Cin / 4);
-  KernelScope ks("wino_in", 0, ((double)c.in_elems() + (double)T * 36 * c.Cin) * 4.0, st);
+  const long total = (long)T * nq_of(c) * (c.Cin / 4);
+  KernelScope ks("wino_in", 0, ((double)c.in_elems() + (double)T * 36 * nq_of(c) * c.Cin) * 4.0, st);
   hipLaunchKernelGGL(wino_in_kernel, blocks_for(total), dim3(256), 0, st, g, c.cg(), x, V, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
@@ -107,7 +123,7 @@ int launch_wino_fwd(const ConvGeom& c, const float* x, const float* U, const flo
   const WinoGeom g = fwd_geom(c);
   const int T = g.tiles();
   AX_TRY(launch_wino_input(c, x, V, st));
-  const ConvGeom p = product_geom(T, c.groups, c.cg(), c.og());
+  const ConvGeom p = product_geom(T, c.groups, nq_of(c) * c.cg(), c.og());
   AX_TRY(launch_conv_fwd(p, V, U, nullptr, nullptr, 0, m, ws, st));
   const long total = (long)T * (c.Cout / 4);
   KernelScope ks("wino_out", 0, ((double)c.out_elems() + (double)T * 36 * c.Cout) * 4.0, st);
@@ -123,12 +139,12 @@ int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, co
   const WinoGeom g = bwd_geom(c);
   const int T = g.tiles();
   {
-    const long total = (long)T * (c.Cout / 4);
-    KernelScope ks("wino_in", 0, ((double)c.out_elems() + (double)T * 36 * c.Cout) * 4.0, st);
+    const long total = (long)T * nq_of(c) * (c.Cout / 4);
+    KernelScope ks("wino_in", 0, ((double)c.out_elems() + (double)T * 36 * nq_of(c) * c.Cout) * 4.0, st);
     hipLaunchKernelGGL(wino_in_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), dy, v, total);
     AX_LAUNCH_CHECK();
   }
-  const ConvGeom p = product_geom(T, c.groups, c.og(), c.cg());
+  const ConvGeom p = product_geom(T, c.groups, nq_of(c) * c.og(), c.cg());
   AX_TRY(launch_conv_fwd(p, v, Ub, nullptr, nullptr, 0, m, ws, st));
   const long total = (long)T * (c.Cin / 4);
   KernelScope ks("wino_out", 0, ((double)c.in_elems() * (gate ? 2 : 1) + (double)T * 36 * c.Cin) * 4.0, st);
@@ -149,12 +165,19 @@ int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, f
     hipLaunchKernelGGL(wino_dy_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), dy, yt, total);
     AX_LAUNCH_CHECK();
   }
-  const ConvGeom p = product_geom(T, c.groups, c.cg(), c.og());
-  int ns = 1;  // slices of the reduction over the tiles; their sum is taken by the transform below
+  const ConvGeom p = product_geom(T, c.groups, nq_of(c) * c.cg(), c.og());
+  int ns = 1;  // slices of the reduction over the tiles
   AX_TRY(launch_conv_bwd_weight(p, V, yt, dU, nullptr, ws, st, &ns));
-  const long total = (long)c.groups * c.cg() * (c.og() / 4);
-  KernelScope ks("wino_dw", 0, (double)c.w_elems() * 4.0 * (4.0 * ns + 1.0), st);
-  hipLaunchKernelGGL(wino_dw_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), ns,
+  const long total = (long)c.groups * nq_of(c) * c.cg() * (c.og() / 4);
+  // The transform below can add the slices itself, which saves a pass over them, but it has one thread per four
+  // taps sets only: with many slices and few threads (the 5x5 layer: 12288 threads, 6 slices) a separate, wide
+  // reduction first is faster (85 -> 35 us).
+  if (ns > 2 && total < 16384) {
+    AX_TRY(launch_reduce_slabs(ws, ns, (long)nq_of(c) * c.cg() * c.og(), 36 * c.groups, dU, st));
+    ns = 1;
+  }
+  KernelScope ks("wino_dw", 0, ((double)wino_u_floats(c) * ns + (double)c.w_elems()) * 4.0, st);
+  hipLaunchKernelGGL(wino_dw_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), c.k, nsub_of(c), ns,
                      ns > 1 ? ws : dU, dwf, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;

@@ -79,7 +79,7 @@ static void check_1d() {
 
 struct Case {
   const char* name;
-  int B, H, W, pad, groups, cg, og;
+  int B, H, W, pad, groups, cg, og, k;  // k x k taps: 3, or 5 as four 3x3 sub-kernels
 };
 
 // m[t][z*N + o] = sum_c a[t][z*K + c] * u[z][c][o]
@@ -95,32 +95,35 @@ static void products(int T, int Z, int K, int N, const std::vector<float>& a, co
 }
 
 static void run(const Case& k) {
-  const int Ho = k.H + 2 * k.pad - 2, Wo = k.W + 2 * k.pad - 2, G = k.groups, Cin = G * k.cg, Cout = G * k.og;
-  const WinoGeom gf{k.B, k.H, k.W, k.pad, Ho, Wo, (Ho + 3) / 4, (Wo + 3) / 4, G};
-  const WinoGeom gb{k.B, Ho, Wo, 2 - k.pad, k.H, k.W, (k.H + 3) / 4, (k.W + 3) / 4, G};
+  const int K = k.k, KK = K * K, nsub = (K + 2) / 3, nq = nsub * nsub;
+  const int Ho = k.H + 2 * k.pad - (K - 1), Wo = k.W + 2 * k.pad - (K - 1), G = k.groups, Cin = G * k.cg, Cout = G * k.og;
+  const WinoGeom gf{k.B, k.H, k.W, k.pad, Ho, Wo, (Ho + 3) / 4, (Wo + 3) / 4, G, K, nsub};
+  const WinoGeom gb{k.B, Ho, Wo, K - 1 - k.pad, k.H, k.W, (k.H + 3) / 4, (k.W + 3) / 4, G, K, nsub};
   const int Tf = gf.tiles(), Tb = gb.tiles();
   std::vector<float> x((size_t)k.B * k.H * k.W * Cin), dy((size_t)k.B * Ho * Wo * Cout), bias(Cout);
-  std::vector<float> wf((size_t)G * 9 * k.cg * k.og), wb(wf.size());
+  std::vector<float> wf((size_t)G * KK * k.cg * k.og), wb(wf.size());
   for (auto& v : x) v = rnd();
   for (auto& v : dy) v = rnd();
   for (auto& v : bias) v = 0.3f * rnd();
   for (auto& v : wf) v = 0.2f * rnd();
   for (int g = 0; g < G; ++g)
-    for (int t = 0; t < 9; ++t)
+    for (int t = 0; t < KK; ++t)
       for (int c = 0; c < k.cg; ++c)
         for (int o = 0; o < k.og; ++o)
-          wb[(((size_t)g * 9 + t) * k.og + o) * k.cg + c] = wf[(((size_t)g * 9 + t) * k.cg + c) * k.og + o];
+          wb[(((size_t)g * KK + t) * k.og + o) * k.cg + c] = wf[(((size_t)g * KK + t) * k.cg + c) * k.og + o];
   auto X = [&](int n, int y, int xx, int c) -> double {
     return (y < 0 || y >= k.H || xx < 0 || xx >= k.W) ? 0.0 : x[(((size_t)n * k.H + y) * k.W + xx) * Cin + c];
   };
   auto WF = [&](int g, int r, int s, int c, int o) -> double {
-    return wf[(((size_t)g * 9 + r * 3 + s) * k.cg + c) * k.og + o];
+    return wf[(((size_t)g * KK + r * K + s) * k.cg + c) * k.og + o];
   };
   // ---- forward ----
-  std::vector<float> U(36 * wf.size() / 9), V((size_t)Tf * 36 * Cin), m((size_t)Tf * 36 * Cout), y(dy.size(), NAN);
-  for (long i = 0; i < (long)G * k.cg * (k.og / 4); ++i) wino_filter_thread(G, k.cg, k.og, 0, wf.data(), U.data(), i);
-  for (long i = 0; i < (long)Tf * (Cin / 4); ++i) wino_in_thread(gf, k.cg, x.data(), V.data(), i);
-  products(Tf, 36 * G, k.cg, k.og, V, U, m);
+  std::vector<float> U((size_t)36 * nq * G * k.cg * k.og, NAN), V((size_t)Tf * 36 * nq * Cin, NAN);
+  std::vector<float> m((size_t)Tf * 36 * Cout), y(dy.size(), NAN);
+  for (long i = 0; i < (long)G * nq * k.cg * (k.og / 4); ++i)
+    wino_filter_thread(G, k.cg, k.og, K, nsub, 0, wf.data(), U.data(), i);
+  for (long i = 0; i < (long)Tf * nq * (Cin / 4); ++i) wino_in_thread(gf, k.cg, x.data(), V.data(), i);
+  products(Tf, 36 * G, nq * k.cg, k.og, V, U, m);
   for (long i = 0; i < (long)Tf * (Cout / 4); ++i) wino_out_thread(gf, k.og, m.data(), bias.data(), 1, nullptr, y.data(), i);
   std::vector<double> y_ref(y.size());
   for (int n = 0; n < k.B; ++n)
@@ -129,17 +132,18 @@ static void run(const Case& k) {
         for (int g = 0; g < G; ++g)
           for (int o = 0; o < k.og; ++o) {
             double s = bias[g * k.og + o];
-            for (int r = 0; r < 3; ++r)
-              for (int q = 0; q < 3; ++q)
+            for (int r = 0; r < K; ++r)
+              for (int q = 0; q < K; ++q)
                 for (int c = 0; c < k.cg; ++c) s += X(n, oy - k.pad + r, ox - k.pad + q, g * k.cg + c) * WF(g, r, q, c, o);
             y_ref[(((size_t)n * Ho + oy) * Wo + ox) * Cout + g * k.og + o] = s > 0 ? s : 0;
           }
   check("fwd", k.name, y, y_ref);
-  // ---- backward data (gated by x > 0) ----
-  std::vector<float> Ub(U.size()), v((size_t)Tb * 36 * Cout), mb((size_t)Tb * 36 * Cin), dx(x.size(), NAN);
-  for (long i = 0; i < (long)G * k.og * (k.cg / 4); ++i) wino_filter_thread(G, k.og, k.cg, 1, wb.data(), Ub.data(), i);
-  for (long i = 0; i < (long)Tb * (Cout / 4); ++i) wino_in_thread(gb, k.og, dy.data(), v.data(), i);
-  products(Tb, 36 * G, k.og, k.cg, v, Ub, mb);
+  // ---- backward data (gated by x > 0): the forward form on dy with reversed taps ----
+  std::vector<float> Ub(U.size(), NAN), v((size_t)Tb * 36 * nq * Cout, NAN), mb((size_t)Tb * 36 * Cin), dx(x.size(), NAN);
+  for (long i = 0; i < (long)G * nq * k.og * (k.cg / 4); ++i)
+    wino_filter_thread(G, k.og, k.cg, K, nsub, 1, wb.data(), Ub.data(), i);
+  for (long i = 0; i < (long)Tb * nq * (Cout / 4); ++i) wino_in_thread(gb, k.og, dy.data(), v.data(), i);
+  products(Tb, 36 * G, nq * k.og, k.cg, v, Ub, mb);
   for (long i = 0; i < (long)Tb * (Cin / 4); ++i) wino_out_thread(gb, k.cg, mb.data(), nullptr, 0, x.data(), dx.data(), i);
   std::vector<double> dx_ref(x.size(), 0.0);
   for (int n = 0; n < k.B; ++n)
@@ -148,8 +152,8 @@ static void run(const Case& k) {
         for (int g = 0; g < G; ++g)
           for (int o = 0; o < k.og; ++o) {
             const double e = dy[(((size_t)n * Ho + oy) * Wo + ox) * Cout + g * k.og + o];
-            for (int r = 0; r < 3; ++r)
-              for (int q = 0; q < 3; ++q) {
+            for (int r = 0; r < K; ++r)
+              for (int q = 0; q < K; ++q) {
                 const int iy = oy - k.pad + r, ix = ox - k.pad + q;
                 if (iy < 0 || iy >= k.H || ix < 0 || ix >= k.W) continue;
                 for (int c = 0; c < k.cg; ++c)
@@ -162,18 +166,20 @@ static void run(const Case& k) {
   // ---- backward weight ----
   // the reduction over the tiles in ns slices, as a split launch leaves them: [(z*ns + slice)][c][o]
   const int ns = Tf >= 3 ? 3 : 1, per = (Tf + ns - 1) / ns;
+  const int kc = nq * k.cg;  // rows of one product's result: (sub-kernel, channel)
   std::vector<float> yt((size_t)Tf * 36 * Cout), dU(U.size() * ns), dw(wf.size(), NAN);
   for (long i = 0; i < (long)Tf * (Cout / 4); ++i) wino_dy_thread(gf, k.og, dy.data(), yt.data(), i);
   for (int z = 0; z < 36 * G; ++z)
     for (int sl = 0; sl < ns; ++sl)
-      for (int c = 0; c < k.cg; ++c)
+      for (int c = 0; c < kc; ++c)
         for (int o = 0; o < k.og; ++o) {
           float s = 0.f;
           for (int t = sl * per; t < std::min(Tf, (sl + 1) * per); ++t)
-            s += V[((size_t)t * 36 * G + z) * k.cg + c] * yt[((size_t)t * 36 * G + z) * k.og + o];
-          dU[(((size_t)z * ns + sl) * k.cg + c) * k.og + o] = s;
+            s += V[((size_t)t * 36 * G + z) * kc + c] * yt[((size_t)t * 36 * G + z) * k.og + o];
+          dU[(((size_t)z * ns + sl) * kc + c) * k.og + o] = s;
         }
-  for (long i = 0; i < (long)G * k.cg * (k.og / 4); ++i) wino_dw_thread(G, k.cg, k.og, ns, dU.data(), dw.data(), i);
+  for (long i = 0; i < (long)G * nq * k.cg * (k.og / 4); ++i)
+    wino_dw_thread(G, k.cg, k.og, K, nsub, ns, dU.data(), dw.data(), i);
   std::vector<double> dw_ref(wf.size(), 0.0);
   for (int n = 0; n < k.B; ++n)
     for (int oy = 0; oy < Ho; ++oy)
@@ -181,10 +187,10 @@ static void run(const Case& k) {
         for (int g = 0; g < G; ++g)
           for (int o = 0; o < k.og; ++o) {
             const double e = dy[(((size_t)n * Ho + oy) * Wo + ox) * Cout + g * k.og + o];
-            for (int r = 0; r < 3; ++r)
-              for (int q = 0; q < 3; ++q)
+            for (int r = 0; r < K; ++r)
+              for (int q = 0; q < K; ++q)
                 for (int c = 0; c < k.cg; ++c)
-                  dw_ref[(((size_t)g * 9 + r * 3 + q) * k.cg + c) * k.og + o] +=
+                  dw_ref[(((size_t)g * KK + r * K + q) * k.cg + c) * k.og + o] +=
                       e * X(n, oy - k.pad + r, ox - k.pad + q, g * k.cg + c);
           }
   check("bwd_weight", k.name, dw, dw_ref);
@@ -193,9 +199,11 @@ static void run(const Case& k) {
 int main() {
   check_1d();
   const Case cases[] = {
-      {"13x13 pad1 g1", 2, 13, 13, 1, 1, 8, 12},  {"13x13 pad1 g2", 2, 13, 13, 1, 2, 4, 8},
-      {"6x6 pad1 g2", 3, 6, 6, 1, 2, 8, 4},        {"5x7 pad0 g1", 2, 5, 7, 0, 1, 4, 4},
-      {"4x9 pad2 g1", 1, 4, 9, 2, 1, 4, 8},        {"3x3 pad1 g1", 2, 3, 3, 1, 1, 4, 4},
+      {"13x13 pad1 g1", 2, 13, 13, 1, 1, 8, 12, 3},  {"13x13 pad1 g2", 2, 13, 13, 1, 2, 4, 8, 3},
+      {"6x6 pad1 g2", 3, 6, 6, 1, 2, 8, 4, 3},        {"5x7 pad0 g1", 2, 5, 7, 0, 1, 4, 4, 3},
+      {"4x9 pad2 g1", 1, 4, 9, 2, 1, 4, 8, 3},        {"3x3 pad1 g1", 2, 3, 3, 1, 1, 4, 4, 3},
+      {"5x5: 27x27 pad2 g2", 2, 27, 27, 2, 2, 4, 8, 5}, {"5x5: 14x14 pad2 g1", 2, 14, 14, 2, 1, 8, 4, 5},
+      {"5x5: 7x9 pad0 g1", 1, 7, 9, 0, 1, 4, 4, 5},     {"5x5: 6x5 pad4 g2", 2, 6, 5, 4, 2, 4, 4, 5},
   };
   for (const Case& c : cases) run(c);
   if (g_fail) {
