@@ -130,7 +130,10 @@ struct alexnet {
   int32_t* err_flag;
   size_t gemm_ws_floats, colsum_ws_floats_;
   int flat;  // flatten size feeding fc6
-  int upd_fork_stage;  // the dense-layer update starts on the side stream behind this stage's pooling adjoint
+  // the dense-layer update starts on the side stream in this stage of the backward pass, just before its
+  // weight gradient (behind its pooling adjoint) or just before its data gradient
+  int upd_fork_stage;
+  bool upd_fork_before_bx;
   // The dense layers hold 96 % of the parameters and finish their backward pass first: their update, which is
   // bound by memory bandwidth, runs on this stream under the convolution backward pass, which is not.
   hipStream_t upd_stream;
@@ -275,16 +278,23 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     if (s.lrn && s.pool) cws = std::max(cws, lrn_part_floats(s.g.Cout));
   }
   {
-    // the dense-layer update shares the chip best with the largest direct fp32 convolution of the backward pass:
-    // the transformed 3x3 stages move several times their activations and compete with it for bandwidth, and
-    // so do the bf16 products (those keep the fork behind the last stage, the earliest possible)
+    // The dense-layer update shares the chip best with a direct fp32 convolution GEMM of the backward pass, the
+    // largest one: the transformed layers move several times their activations and compete with it for
+    // bandwidth, and so do the bf16 products (those keep the fork behind the last stage, the earliest possible).
     double best = -1;
-    for (int i = 1; i < kStages && c.precision == ALEXNET_PRECISION_FP32; ++i) {
+    n->upd_fork_before_bx = false;
+    for (int i = 0; i < kStages && c.precision == ALEXNET_PRECISION_FP32; ++i) {
       const Stage& s = n->st[i];
       const double fl = (double)s.g.P() * s.g.Cout * s.g.cg() * s.g.k * s.g.k;
-      if (!s.wino_bx && fl > best) {  // a direct data gradient (its weight gradient may be transformed, see the fork)
+      if (!s.wino && fl > best) {
         best = fl;
         n->upd_fork_stage = i;
+        n->upd_fork_before_bx = false;
+      }
+      if (i > 0 && !s.wino_bx && fl > best) {
+        best = fl;
+        n->upd_fork_stage = i;
+        n->upd_fork_before_bx = s.wino;  // behind a transformed weight gradient, else before both GEMMs
       }
     }
   }
@@ -348,11 +358,16 @@ static int stage_bwd_weight(alexnet* n, Stage& s, const float* x, const float* d
   }
   return launch_conv_bwd_weight(s.g, x, dy, dwf, s.dwrun, n->gemm_ws, st);
 }
-// taps_ready: s.wino_ub already holds the transform of wb
+// taps_ready: s.wino_ub already holds the transform of wb; yt_ready: n->wino_a already holds the transformed
+// output gradient (stage_bwd_weight of the same minibatch ran just before)
 static int stage_bwd_data(alexnet* n, Stage& s, const float* dy, const float* wf, const float* wb, float* wphase,
-                          const float* gate, float* dx, bool taps_ready, hipStream_t st) {
+                          const float* gate, float* dx, bool taps_ready, bool yt_ready, hipStream_t st) {
   if (s.wino_bx && wino_usable(s, dy, wb, dx, gate)) {
     if (!taps_ready) AX_TRY(launch_wino_filter_bwd(s.g, wb, s.wino_ub, st));
+    if (wino_bwd_data_shares_dy(s.g)) {
+      if (!yt_ready) AX_TRY(launch_wino_output_grad(s.g, dy, n->wino_a, st));
+      return launch_wino_bwd_data_adjoint(s.g, n->wino_a, s.wino_ub, gate, dx, n->wino_m, n->gemm_ws, st);
+    }
     return launch_wino_bwd_data(s.g, dy, s.wino_ub, gate, dx, n->wino_a, n->wino_m, n->gemm_ws, st);
   }
   return launch_conv_bwd_data(s.g, dy, wf, wb, wphase, gate, dx, n->gemm_ws, st);
@@ -463,9 +478,8 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     if (s.lrn && !s.fused())
       AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
                             c.lrn_alpha, c.lrn_beta, 1, st));
-    // Fork of the dense-layer update, behind this stage's pooling adjoint: that kernel is bound by bandwidth
-    // like the update and would be starved by it, while the direct-convolution GEMMs that follow are not.  A
-    // transformed weight gradient is bandwidth-hungry too: then the fork waits until it has been enqueued.
+    // Fork of the dense-layer update (see upd_fork_stage), never in front of this stage's pooling adjoint: that
+    // kernel is bound by bandwidth like the update and would be starved by it.
     auto fork_update = [&]() -> int {
       AX_HIP(hipEventRecord(n->ev_fc_done, st));
       AX_HIP(hipStreamWaitEvent(n->upd_stream, n->ev_fc_done, 0));
@@ -474,14 +488,14 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
       return ALEXNET_OK;
     };
     const bool fork_here = early_update && i == n->upd_fork_stage;
-    if (fork_here && !s.wino) AX_TRY(fork_update());
+    if (fork_here && !n->upd_fork_before_bx) AX_TRY(fork_update());
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
       AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st));
       if (!bias_done) AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
     }
-    if (fork_here && s.wino) AX_TRY(fork_update());
+    if (fork_here && n->upd_fork_before_bx) AX_TRY(fork_update());
     if (i > 0) {
       ProfContext pc(s.lab[3]);
       Stage& prev = n->st[i - 1];
@@ -491,7 +505,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
         AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
       }
       AX_TRY(stage_bwd_data(n, s, s.dact, n->params + s.w_off, s.wb, s.wphase, prev.plain() ? prev.act : nullptr,
-                            prev.d_out, early_update, st));
+                            prev.d_out, early_update, true, st));
     }
   }
   return ALEXNET_OK;
@@ -928,7 +942,7 @@ int alexnet_conv_backward_data_nhwc(alexnet_t* n, int32_t layer, const float* dy
   Stage* s;
   AX_TRY(stage_of(n, layer, &s));
   REQUIRE(dy && wb && dx, ALEXNET_EINVAL, "alexnet_conv_backward_data_nhwc: null argument");
-  return stage_bwd_data(n, *s, dy, wf, wb, wf ? s->wphase : nullptr, nullptr, dx, false, S(stream));
+  return stage_bwd_data(n, *s, dy, wf, wb, wf ? s->wphase : nullptr, nullptr, dx, false, false, S(stream));
 }
 int alexnet_conv_backward_weight_nhwc(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dwf,
                                       float* db, void* stream) {
@@ -960,7 +974,7 @@ int alexnet_conv_backward_data(alexnet_t* n, int32_t layer, const float* dy, con
   AX_TRY(launch_conv_weight_pack(w, n->scratch_w[0], g.Cout, g.cg(), g.k, g.groups, 0, S(stream)));
   AX_TRY(launch_conv_weight_wb(n->scratch_w[0], n->scratch_w[1], g.Cout, g.cg(), g.k, g.groups, S(stream)));
   AX_TRY(stage_bwd_data(n, *s, n->scratch_y, n->scratch_w[0], n->scratch_w[1], s->wphase, nullptr, n->scratch_x, false,
-                        S(stream)));
+                        false, S(stream)));
   return launch_nhwc_to_nchw(n->scratch_x, dx, g.B, g.Cin, g.H, g.W, S(stream));
 }
 int alexnet_conv_backward_weight(alexnet_t* n, int32_t layer, const float* x, const float* dy, float* dw, float* db,

@@ -41,6 +41,9 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
 // wino_gain: multiplies of the direct form per multiply of the transformed one at this layer's map size.
 bool wino_ok(const ConvGeom& c);
 bool wino_bwd_data_ok(const ConvGeom& c);
+// the data gradient starts from the transformed output gradient that launch_wino_bwd_weight leaves in `yt`
+// (5x5 layers: adjoint form) rather than from dy itself
+bool wino_bwd_data_shares_dy(const ConvGeom& c);
 double wino_gain(const ConvGeom& c);
 size_t wino_v_floats(const ConvGeom& c);
 size_t wino_u_floats(const ConvGeom& c);
@@ -55,6 +58,9 @@ int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, co
                          float* m, float* ws, hipStream_t st);
 int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
                            float* ws, hipStream_t st);
+int launch_wino_output_grad(const ConvGeom& c, const float* dy, float* yt, hipStream_t st);
+int launch_wino_bwd_data_adjoint(const ConvGeom& c, const float* yt, const float* Ut, const float* gate, float* dx,
+                                 float* m, float* ws, hipStream_t st);
 
 // ---- dense layers (conv_gemm.hip) -------------------------------------------
 struct FcAct {

@@ -61,6 +61,17 @@ AX_HD void wino_bt(const Vec4* d, Vec4* o) {
   o[4 * SO] = 2.f * (d1 - d3) - d2 + d4;
   o[5 * SO] = 4.f * d1 - 5.f * d3 + d5;
 }
+// B (6x6) = (Bt)^T: adjoint of the data transform
+template <int SI, int SO>
+AX_HD void wino_b(const Vec4* m, Vec4* o) {
+  const Vec4 m0 = m[0], m1 = m[SI], m2 = m[2 * SI], m3 = m[3 * SI], m4 = m[4 * SI], m5 = m[5 * SI];
+  o[0] = 4.f * m0;
+  o[SO] = 4.f * (m2 - m1 + m5) + 2.f * (m4 - m3);
+  o[2 * SO] = vzero() - 5.f * m0 - 4.f * (m1 + m2) - m3 - m4;
+  o[3 * SO] = m1 - m2 + 2.f * (m3 - m4) - 5.f * m5;
+  o[4 * SO] = m0 + m1 + m2 + m3 + m4;
+  o[5 * SO] = m5;
+}
 // At (4x6): output transform
 template <int SI, int SO>
 AX_HD void wino_at(const Vec4* m, Vec4* o) {
@@ -237,13 +248,96 @@ AX_HD void wino_out_thread(const WinoGeom& g, int Ng, const float* M, const floa
   }
 }
 
+// Data gradient as the adjoint of the input transform: dx += B m Bt of every 6x6 patch, where
+// m[p] = M[t][(p*groups + g)*(nq*Cg) + q*Cg + c] is the product of the transformed output gradient with the
+// transformed taps.  Patches overlap, so a workgroup owns one picture and CQ channel quads, keeps the picture
+// in LDS ([pixel][CQ] float4) and adds the patches in 4*nq phases -- tiles of one parity (ty % 2, tx % 2) and
+// one sub-kernel are 8 pixels apart and never touch the same pixel, so within a phase every LDS word has one
+// writer and the sum has a fixed order.  256 threads: tid % CQ is the quad, tid / CQ the worker that takes
+// every (256/CQ)-th tile of the phase.  Call order: wino_dx_zero, barrier, the phases with a barrier after
+// each, wino_dx_flush.
+struct WinoDx {
+  WinoGeom g;  // of the forward pass: H x W is the picture dx, th x tw the tiles of the output
+  int Cg, CQ;  // channels per group of dx; quads per workgroup (a power of two dividing 256)
+  AX_HD int Ctot() const { return g.groups * Cg; }
+  AX_HD int cblocks() const { return (Ctot() / 4 + CQ - 1) / CQ; }
+  AX_HD int phases() const { return 4 * g.nq(); }
+  AX_HD int lds_vec4() const { return g.H * g.W * CQ; }
+};
+AX_HD void wino_dx_zero(const WinoDx& d, Vec4* lds, int tid) {
+  for (int i = tid; i < d.lds_vec4(); i += kThreads) lds[i] = vzero();
+}
+AX_HD void wino_dx_phase(const WinoDx& d, const float* M, Vec4* lds, int block, int tid, int phase) {
+  const WinoGeom& g = d.g;
+  const int nq = g.nq(), Ctot = d.Ctot();
+  const int n = block / d.cblocks(), cblk = block - n * d.cblocks();
+  const int cq = tid % d.CQ, worker = tid / d.CQ, workers = kThreads / d.CQ;
+  const int c = 4 * (cblk * d.CQ + cq);
+  if (c >= Ctot) return;
+  const int q = phase % nq, par = phase / nq, py = par >> 1, px = par & 1;
+  const int qy = q / g.nsub, qx = q - qy * g.nsub;
+  const int ny = (g.th - py + 1) / 2, nx = (g.tw - px + 1) / 2;
+  const int grp = c / d.Cg, cl = c - grp * d.Cg;
+  const long pstride = (long)nq * Ctot;
+  for (int j = worker; j < ny * nx; j += workers) {
+    const int ty = py + 2 * (j / nx), tx = px + 2 * (j % nx);
+    const long t = ((long)n * g.th + ty) * g.tw + tx;
+    const float* in = M + t * 36 * pstride + (long)grp * nq * d.Cg + (long)q * d.Cg + cl;
+    Vec4 u[36];
+#pragma unroll
+    for (int jj = 0; jj < 6; ++jj) {
+      Vec4 col[6];
+#pragma unroll
+      for (int i = 0; i < 6; ++i) col[i] = vload(in + (long)(6 * i + jj) * pstride);
+      wino_b<1, 6>(col, u + jj);  // u[i][jj]
+    }
+    const int y0 = 4 * ty - g.pad + 3 * qy, x0 = 4 * tx - g.pad + 3 * qx;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      Vec4 r[6];
+      wino_b<1, 1>(u + 6 * i, r);
+      const int iy = y0 + i;
+#pragma unroll
+      for (int jj = 0; jj < 6; ++jj) {
+        const int ix = x0 + jj;
+        if ((uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W) {
+          Vec4* acc = lds + ((long)iy * g.W + ix) * d.CQ + cq;
+          *acc = *acc + r[jj];
+        }
+      }
+    }
+  }
+}
+// dx[n][pixel][c] = the picture in LDS, zero where gate <= 0 (gate may be null)
+AX_HD void wino_dx_flush(const WinoDx& d, const Vec4* lds, const float* gate, float* dx, int block, int tid) {
+  const int Ctot = d.Ctot();
+  const int n = block / d.cblocks(), cblk = block - n * d.cblocks();
+  for (int i = tid; i < d.lds_vec4(); i += kThreads) {
+    const int cq = i % d.CQ, pix = i / d.CQ;
+    const int c = 4 * (cblk * d.CQ + cq);
+    if (c >= Ctot) continue;
+    const long o = ((long)n * d.g.H * d.g.W + pix) * Ctot + c;
+    Vec4 v = lds[i];
+    if (gate) {
+      const Vec4 q = vload(gate + o);
+      if (!(q.x > 0.f)) v.x = 0.f;
+      if (!(q.y > 0.f)) v.y = 0.f;
+      if (!(q.z > 0.f)) v.z = 0.f;
+      if (!(q.w > 0.f)) v.w = 0.f;
+    }
+    vstore(dx + o, v);
+  }
+}
+
 // Taps to transformed taps and back.  `w` is [groups][(r, s, a)][b] (k x k taps; a < Na rows, b < Nb
 // columns: the forward weights with a = input channel, b = output channel, or the backward-data
 // weights with the roles swapped), `U` is [(p*groups + g)][q*Na + a][b] for sub-kernel q = (qy, qx) with the
 // taps (3qy + i, 3qx + j), zero where they do not exist.  flip reverses both tap axes (the backward-data
-// correlation).  idx enumerates (group, sub-kernel, a, column quad).
-AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int flip, const float* w, float* U,
-                              long idx) {
+// correlation).  q_in_cols stores U as [(p*groups + g)][a][q*Nb + b] instead (the operand of the adjoint
+// data-gradient product, whose columns are (sub-kernel, input channel)).  idx enumerates (group, sub-kernel,
+// a, column quad).
+AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int flip, int q_in_cols, const float* w,
+                              float* U, long idx) {
   const int quads = Nb / 4, nq = nsub * nsub;
   const long row = idx / quads;  // (g*nq + q)*Na + a
   const int b = 4 * (int)(idx - row * quads);
@@ -268,8 +362,10 @@ AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int f
     Vec4 r[6];
     wino_g<1, 1>(u + 3 * i, r);
 #pragma unroll
-    for (int j = 0; j < 6; ++j)
-      vstore(U + (((((long)(6 * i + j) * groups + grp) * nq + q) * Na + a) * Nb + b), r[j]);
+    for (int j = 0; j < 6; ++j) {
+      const long z = (long)(6 * i + j) * groups + grp;
+      vstore(U + (q_in_cols ? ((z * Na + a) * nq + q) * Nb + b : ((z * nq + q) * Na + a) * Nb + b), r[j]);
+    }
   }
 }
 // dw[groups][(r, s, a)][b] = (Gt m G)[i][j] at r = 3qy + i, s = 3qx + j (taps that exist only),

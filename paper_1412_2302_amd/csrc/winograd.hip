@@ -27,10 +27,24 @@ __global__ void __launch_bounds__(256) wino_out_kernel(WinoGeom g, int Ng, const
   if (idx < total) wino_out_thread(g, Ng, M, bias, relu, gate, y, idx);
 }
 __global__ void __launch_bounds__(256) wino_filter_kernel(int groups, int Na, int Nb, int k, int nsub, int flip,
-                                                           const float* __restrict__ w, float* __restrict__ U,
-                                                           long total) {
+                                                           int q_in_cols, const float* __restrict__ w,
+                                                           float* __restrict__ U, long total) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < total) wino_filter_thread(groups, Na, Nb, k, nsub, flip, w, U, idx);
+  if (idx < total) wino_filter_thread(groups, Na, Nb, k, nsub, flip, q_in_cols, w, U, idx);
+}
+// one workgroup per (picture, block of CQ channel quads); dynamic LDS: H*W*CQ float4
+__global__ void __launch_bounds__(256) wino_dx_kernel(WinoDx d, const float* __restrict__ M,
+                                                       const float* __restrict__ gate, float* __restrict__ dx) {
+  extern __shared__ __attribute__((aligned(16))) float4 wino_dx_lds[];
+  Vec4* lds = reinterpret_cast<Vec4*>(wino_dx_lds);
+  const int tid = threadIdx.x, block = blockIdx.x;
+  wino_dx_zero(d, lds, tid);
+  __syncthreads();
+  for (int ph = 0; ph < d.phases(); ++ph) {
+    wino_dx_phase(d, M, lds, block, tid, ph);
+    __syncthreads();
+  }
+  wino_dx_flush(d, lds, gate, dx, block, tid);
 }
 __global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb, int k, int nsub, int ns,
                                                        const float* __restrict__ dU, float* __restrict__ dw,
@@ -56,9 +70,17 @@ bool wino_ok(const ConvGeom& c) {
   const long T = std::max((long)fwd_geom(c).tiles(), (long)bwd_geom(c).tiles());
   return T * 36 * nq_of(c) * std::max(c.Cin, c.Cout) <= 0x1ffffff0L;
 }
-// the data gradient takes the transformed path for 3x3 kernels only (for 5x5 the four shifted transforms of
-// dy, with Cout channels each, cost what the 2.6x smaller products save)
-bool wino_bwd_data_ok(const ConvGeom& c) { return wino_ok(c) && c.k == 3; }
+// The data gradient of a 3x3 layer is the forward form applied to dy (reversed taps).  For 5x5 that would take
+// four shifted transforms of dy with Cout channels each, which cost what the smaller products save; there the
+// adjoint form is used: the products of the transformed output gradient (shared with the weight gradient) go
+// back through B . Bt, patches added up in LDS (wino_dx_kernel), which needs a picture of CQ >= 1 channel
+// quads to fit 48 KiB.
+static inline bool adjoint_form(const ConvGeom& c) { return c.k == 5; }
+constexpr size_t kDxLdsBytes = 48 * 1024;
+bool wino_bwd_data_ok(const ConvGeom& c) {
+  return wino_ok(c) && (!adjoint_form(c) || (size_t)c.H * c.W * 16 <= kDxLdsBytes);
+}
+bool wino_bwd_data_shares_dy(const ConvGeom& c) { return adjoint_form(c); }
 // multiplies of the direct form per multiply of the products, at this map size
 double wino_gain(const ConvGeom& c) {
   const double covered = (double)c.Ho * c.Wo / (16.0 * ((c.Ho + 3) / 4) * ((c.Wo + 3) / 4));
@@ -76,13 +98,16 @@ size_t wino_u_floats(const ConvGeom& c) { return (size_t)36 * nq_of(c) * c.cg() 
 size_t wino_scratch_floats(const ConvGeom& c) {
   const size_t tf = (size_t)fwd_geom(c).tiles(), tb = (size_t)bwd_geom(c).tiles();
   size_t n = 36 * tf * c.Cout;  // forward products, transformed output gradient
-  if (wino_bwd_data_ok(c)) n = std::max(n, 36 * std::max(tb * c.Cout * nq_of(c), tb * c.Cin));
+  if (wino_bwd_data_ok(c) && adjoint_form(c)) n = std::max(n, 36 * tf * nq_of(c) * c.Cin);
+  if (wino_bwd_data_ok(c) && !adjoint_form(c)) n = std::max(n, 36 * std::max(tb * c.Cout * nq_of(c), tb * c.Cin));
   return n;
 }
 size_t wino_gemm_ws_floats(const ConvGeom& c) {
   const ConvGeom pf = product_geom(fwd_geom(c).tiles(), c.groups, nq_of(c) * c.cg(), c.og());
   size_t n = std::max(conv_fwd_ws_floats(pf), conv_bwd_weight_ws_floats(pf));
-  if (wino_bwd_data_ok(c))
+  if (wino_bwd_data_ok(c) && adjoint_form(c))
+    n = std::max(n, conv_fwd_ws_floats(product_geom(fwd_geom(c).tiles(), c.groups, c.og(), nq_of(c) * c.cg())));
+  if (wino_bwd_data_ok(c) && !adjoint_form(c))
     n = std::max(n, conv_fwd_ws_floats(product_geom(bwd_geom(c).tiles(), c.groups, nq_of(c) * c.og(), c.cg())));
   return n;
 }
@@ -94,15 +119,17 @@ int launch_wino_filter(const ConvGeom& c, const float* wf, float* U, hipStream_t
   const long total = (long)c.groups * nq_of(c) * c.cg() * (c.og() / 4);
   KernelScope ks("wino_filter", 0, ((double)c.w_elems() + (double)wino_u_floats(c)) * 4.0, st);
   hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), c.k, nsub_of(c),
-                     0, wf, U, total);
+                     0, 0, wf, U, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
 int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStream_t st) {
   const long total = (long)c.groups * nq_of(c) * c.og() * (c.cg() / 4);
   KernelScope ks("wino_filter", 0, ((double)c.w_elems() + (double)wino_u_floats(c)) * 4.0, st);
+  // forward form: reversed taps, [z][(q, o)][c]; adjoint form: the taps as they are, [z][o][(q, c)]
+  const int adj = adjoint_form(c) ? 1 : 0;
   hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.og(), c.cg(), c.k, nsub_of(c),
-                     1, wb, Ub, total);
+                     1 - adj, adj, wb, Ub, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -154,17 +181,39 @@ int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, co
   return ALEXNET_OK;
 }
 
+int launch_wino_output_grad(const ConvGeom& c, const float* dy, float* yt, hipStream_t st) {
+  const WinoGeom g = fwd_geom(c);
+  const int T = g.tiles();
+  const long total = (long)T * (c.Cout / 4);
+  KernelScope ks("wino_dy", 0, ((double)c.out_elems() + (double)T * 36 * c.Cout) * 4.0, st);
+  hipLaunchKernelGGL(wino_dy_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), dy, yt, total);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// Adjoint form: yt x Ut -> m (36 products, columns (sub-kernel, input channel)), m -> dx gated by gate > 0.
+// yt is the transformed output gradient (launch_wino_output_grad, or what launch_wino_bwd_weight left there).
+int launch_wino_bwd_data_adjoint(const ConvGeom& c, const float* yt, const float* Ut, const float* gate, float* dx,
+                                 float* m, float* ws, hipStream_t st) {
+  const WinoGeom g = fwd_geom(c);
+  const int T = g.tiles();
+  const ConvGeom p = product_geom(T, c.groups, c.og(), nq_of(c) * c.cg());
+  AX_TRY(launch_conv_fwd(p, yt, Ut, nullptr, nullptr, 0, m, ws, st));
+  WinoDx d{g, c.cg(), 1};
+  while (d.CQ < 16 && d.CQ < c.Cin / 4 && (size_t)c.H * c.W * 16 * d.CQ * 2 <= kDxLdsBytes) d.CQ *= 2;
+  KernelScope ks("wino_dx", 0, ((double)c.in_elems() * (gate ? 2 : 1) + (double)T * 36 * nq_of(c) * c.Cin) * 4.0, st);
+  hipLaunchKernelGGL(wino_dx_kernel, dim3((unsigned)(c.B * d.cblocks())), dim3(256), (size_t)d.lds_vec4() * 16, st, d, m,
+                     gate, dx);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
 // dy -> yt, V^T x yt -> dU (36 products over the tiles), dU -> dwf.  V is the forward pass's.
 int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
                            float* ws, hipStream_t st) {
   const WinoGeom g = fwd_geom(c);
   const int T = g.tiles();
-  {
-    const long total = (long)T * (c.Cout / 4);
-    KernelScope ks("wino_dy", 0, ((double)c.out_elems() + (double)T * 36 * c.Cout) * 4.0, st);
-    hipLaunchKernelGGL(wino_dy_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), dy, yt, total);
-    AX_LAUNCH_CHECK();
-  }
+  AX_TRY(launch_wino_output_grad(c, dy, yt, st));
   const ConvGeom p = product_geom(T, c.groups, nq_of(c) * c.cg(), c.og());
   int ns = 1;  // slices of the reduction over the tiles
   AX_TRY(launch_conv_bwd_weight(p, V, yt, dU, nullptr, ws, st, &ns));

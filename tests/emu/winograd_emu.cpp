@@ -121,7 +121,7 @@ static void run(const Case& k) {
   std::vector<float> U((size_t)36 * nq * G * k.cg * k.og, NAN), V((size_t)Tf * 36 * nq * Cin, NAN);
   std::vector<float> m((size_t)Tf * 36 * Cout), y(dy.size(), NAN);
   for (long i = 0; i < (long)G * nq * k.cg * (k.og / 4); ++i)
-    wino_filter_thread(G, k.cg, k.og, K, nsub, 0, wf.data(), U.data(), i);
+    wino_filter_thread(G, k.cg, k.og, K, nsub, 0, 0, wf.data(), U.data(), i);
   for (long i = 0; i < (long)Tf * nq * (Cin / 4); ++i) wino_in_thread(gf, k.cg, x.data(), V.data(), i);
   products(Tf, 36 * G, nq * k.cg, k.og, V, U, m);
   for (long i = 0; i < (long)Tf * (Cout / 4); ++i) wino_out_thread(gf, k.og, m.data(), bias.data(), 1, nullptr, y.data(), i);
@@ -141,7 +141,7 @@ static void run(const Case& k) {
   // ---- backward data (gated by x > 0): the forward form on dy with reversed taps ----
   std::vector<float> Ub(U.size(), NAN), v((size_t)Tb * 36 * nq * Cout, NAN), mb((size_t)Tb * 36 * Cin), dx(x.size(), NAN);
   for (long i = 0; i < (long)G * nq * k.og * (k.cg / 4); ++i)
-    wino_filter_thread(G, k.og, k.cg, K, nsub, 1, wb.data(), Ub.data(), i);
+    wino_filter_thread(G, k.og, k.cg, K, nsub, 1, 0, wb.data(), Ub.data(), i);
   for (long i = 0; i < (long)Tb * nq * (Cout / 4); ++i) wino_in_thread(gb, k.og, dy.data(), v.data(), i);
   products(Tb, 36 * G, nq * k.og, k.cg, v, Ub, mb);
   for (long i = 0; i < (long)Tb * (Cin / 4); ++i) wino_out_thread(gb, k.cg, mb.data(), nullptr, 0, x.data(), dx.data(), i);
@@ -194,6 +194,26 @@ static void run(const Case& k) {
                       e * X(n, oy - k.pad + r, ox - k.pad + q, g * k.cg + c);
           }
   check("bwd_weight", k.name, dw, dw_ref);
+  // ---- backward data, adjoint form: dx = sum over patches of B [(A dy At) .* (G w Gt)] Bt, gated ----
+  for (int CQ : {1, 4, 16}) {
+    if (CQ > 1 && CQ > Cin / 4 * 2) continue;
+    WinoDx d{gf, k.cg, CQ};
+    std::vector<float> Ut(U.size(), NAN), ma((size_t)Tf * 36 * nq * Cin), dxa(x.size(), NAN);
+    for (long i = 0; i < (long)G * nq * k.og * (k.cg / 4); ++i)
+      wino_filter_thread(G, k.og, k.cg, K, nsub, 0, 1, wb.data(), Ut.data(), i);
+    products(Tf, 36 * G, k.og, nq * k.cg, yt, Ut, ma);
+    std::vector<Vec4> lds(d.lds_vec4());  // exactly what the kernel is given
+    for (int block = 0; block < k.B * d.cblocks(); ++block) {
+      for (auto& v : lds) v = {NAN, NAN, NAN, NAN};
+      for (int tid = 0; tid < kThreads; ++tid) wino_dx_zero(d, lds.data(), tid);
+      for (int ph = 0; ph < d.phases(); ++ph)
+        for (int tid = 0; tid < kThreads; ++tid) wino_dx_phase(d, ma.data(), lds.data(), block, tid, ph);
+      for (int tid = 0; tid < kThreads; ++tid) wino_dx_flush(d, lds.data(), x.data(), dxa.data(), block, tid);
+    }
+    char nm[64];
+    snprintf(nm, sizeof nm, "%s CQ%d", k.name, CQ);
+    check("bwd_d_adj", nm, dxa, dx_ref);
+  }
 }
 
 int main() {
