@@ -253,70 +253,188 @@ AX_HD void wino_out_thread(const WinoGeom& g, int Ng, const float* M, const floa
 // transformed taps.  Patches overlap, so a workgroup owns one picture and CQ channel quads, keeps the picture
 // in LDS ([pixel][CQ] float4) and adds the patches in 4*nq phases -- tiles of one parity (ty % 2, tx % 2) and
 // one sub-kernel are 8 pixels apart and never touch the same pixel, so within a phase every LDS word has one
-// writer and the sum has a fixed order.  256 threads: tid % CQ is the quad, tid / CQ the worker that takes
-// every (256/CQ)-th tile of the phase.  Call order: wino_dx_zero, barrier, the phases with a barrier after
-// each, wino_dx_flush.
+// writer and the sum has a fixed order.  256 threads: tid % CQ is the quad, tid / CQ the worker.  Work goes in
+// rounds: in a round every worker loads and transforms one patch (all of them at once, so that the memory
+// system sees 256 threads' loads, not one phase's), then the phases add them to the picture.  Eight quads are
+// one 128-byte line of M; where a whole picture of eight quads does not fit the LDS budget the picture is cut
+// into `bands` of rows, one workgroup each, and a patch that straddles two bands is transformed by both (each
+// keeps its own rows).  Call order: wino_dx_zero, barrier, per round: wino_dx_load, then wino_dx_add and a
+// barrier for each phase the round touches (wino_dx_round_phases); wino_dx_flush.
 struct WinoDx {
   WinoGeom g;  // of the forward pass: H x W is the picture dx, th x tw the tiles of the output
   int Cg, CQ;  // channels per group of dx; quads per workgroup (a power of two dividing 256)
+  int bands;   // row bands per picture
   AX_HD int Ctot() const { return g.groups * Cg; }
   AX_HD int cblocks() const { return (Ctot() / 4 + CQ - 1) / CQ; }
   AX_HD int phases() const { return 4 * g.nq(); }
-  AX_HD int lds_vec4() const { return g.H * g.W * CQ; }
+  AX_HD int band_rows() const { return (g.H + bands - 1) / bands; }
+  AX_HD int lds_vec4() const { return band_rows() * g.W * CQ; }
+  AX_HD int blocks() const { return g.B * bands * cblocks(); }
 };
+struct WinoDxBlock {
+  int n, cblk, h0, h1;  // picture, channel block, rows [h0, h1)
+};
+AX_HD WinoDxBlock wino_dx_block(const WinoDx& d, int block) {
+  WinoDxBlock b;
+  b.cblk = block % d.cblocks();
+  const int r = block / d.cblocks();
+  b.n = r / d.bands;
+  const int band = r - b.n * d.bands;
+  b.h0 = band * d.band_rows();
+  b.h1 = b.h0 + d.band_rows() < d.g.H ? b.h0 + d.band_rows() : d.g.H;
+  return b;
+}
 AX_HD void wino_dx_zero(const WinoDx& d, Vec4* lds, int tid) {
   for (int i = tid; i < d.lds_vec4(); i += kThreads) lds[i] = vzero();
 }
-AX_HD void wino_dx_phase(const WinoDx& d, const float* M, Vec4* lds, int block, int tid, int phase) {
+// The tiles whose patches can reach the rows of a block, listed phase by phase (phase = parity*nq + q with
+// parity = 2*(ty & 1) + (tx & 1)): all tasks of phase 0, then of phase 1, ...  Workers take consecutive tasks,
+// so the lanes of a wave mostly share a phase and a round spans few phases.
+struct WinoDxTasks {
+  int ty_lo, ty_hi;  // tile rows that can reach the block's rows (inclusive; hi < lo: none)
+  int count;         // tasks of the block
+};
+AX_HD int wino_dx_rows_of_parity(const WinoDxTasks& t, int py) {  // tile rows in [ty_lo, ty_hi] with ty % 2 == py
+  if (t.ty_hi < t.ty_lo) return 0;
+  const int first = t.ty_lo + ((t.ty_lo & 1) != py);
+  return first > t.ty_hi ? 0 : (t.ty_hi - first) / 2 + 1;
+}
+AX_HD int wino_dx_phase_count(const WinoDx& d, const WinoDxTasks& t, int phase) {
+  const int par = phase / d.g.nq(), py = par >> 1, px = par & 1;
+  return wino_dx_rows_of_parity(t, py) * ((d.g.tw - px + 1) / 2);
+}
+AX_HD WinoDxTasks wino_dx_tasks(const WinoDx& d, const WinoDxBlock& bk) {
+  const WinoGeom& g = d.g;
+  // patch rows of (ty, qy): 4ty - pad + 3qy + [0, 6)
+  int lo = bk.h0 - 5 + g.pad - 3 * (g.nsub - 1);
+  lo = lo <= 0 ? 0 : (lo + 3) / 4;
+  int hi = bk.h1 - 1 + g.pad;
+  hi = hi < 0 ? -1 : hi / 4;
+  if (hi > g.th - 1) hi = g.th - 1;
+  WinoDxTasks t;
+  t.ty_lo = lo;
+  t.ty_hi = hi;
+  t.count = 0;
+  for (int ph = 0; ph < d.phases(); ++ph) t.count += wino_dx_phase_count(d, t, ph);
+  return t;
+}
+// Everything about a block that does not change from round to round, worked out once per thread
+struct WinoDxPlan {
+  WinoDxBlock bk;
+  WinoDxTasks tk;
+  int prefix[17];  // tasks before phase ph; prefix[phases()] = count
+};
+AX_HD WinoDxPlan wino_dx_plan(const WinoDx& d, int block) {
+  WinoDxPlan p;
+  p.bk = wino_dx_block(d, block);
+  p.tk = wino_dx_tasks(d, p.bk);
+  p.prefix[0] = 0;
+  for (int ph = 0; ph < 16; ++ph)
+    p.prefix[ph + 1] = p.prefix[ph] + (ph < d.phases() ? wino_dx_phase_count(d, p.tk, ph) : 0);
+  return p;
+}
+// phase of task j (j < count)
+AX_HD int wino_dx_phase_of(const WinoDxPlan& p, int j) {
+  int ph = 0;
+#pragma unroll
+  for (int k = 1; k < 16; ++k) ph += j >= p.prefix[k] ? 1 : 0;
+  return ph;
+}
+AX_HD int wino_dx_rounds(const WinoDx& d) {  // the same for every block: the largest need of any band
+  int most = 0;
+  for (int b = 0; b < d.bands; ++b) {
+    WinoDxBlock bk;
+    bk.n = 0; bk.cblk = 0;
+    bk.h0 = b * d.band_rows();
+    bk.h1 = bk.h0 + d.band_rows() < d.g.H ? bk.h0 + d.band_rows() : d.g.H;
+    const int c = wino_dx_tasks(d, bk).count;
+    most = c > most ? c : most;
+  }
+  const int workers = kThreads / d.CQ;
+  return (most + workers - 1) / workers;
+}
+// phases that round `round` of a block touches: [*lo, *hi] (lo > hi: the round has no task)
+AX_HD void wino_dx_round_phases(const WinoDx& d, const WinoDxPlan& p, int round, int* lo, int* hi) {
+  const int workers = kThreads / d.CQ, first = round * workers;
+  int last = first + workers - 1;
+  if (last > p.tk.count - 1) last = p.tk.count - 1;
+  if (first > last) {
+    *lo = 1; *hi = 0;
+    return;
+  }
+  *lo = wino_dx_phase_of(p, first);
+  *hi = wino_dx_phase_of(p, last);
+}
+// One task of a thread: phase < 0 means none.  z = B m Bt of the patch, to be added at (y0 + i, x0 + j).
+struct WinoDxTask {
+  int phase, y0, x0;
+};
+// Round r of a block: every worker loads and transforms one patch (all threads at once: this is where the
+// memory traffic is), ...
+AX_HD WinoDxTask wino_dx_load(const WinoDx& d, const WinoDxPlan& p, const float* M, int tid, int round, Vec4* z) {
   const WinoGeom& g = d.g;
   const int nq = g.nq(), Ctot = d.Ctot();
-  const int n = block / d.cblocks(), cblk = block - n * d.cblocks();
+  const WinoDxBlock& bk = p.bk;
   const int cq = tid % d.CQ, worker = tid / d.CQ, workers = kThreads / d.CQ;
-  const int c = 4 * (cblk * d.CQ + cq);
-  if (c >= Ctot) return;
-  const int q = phase % nq, par = phase / nq, py = par >> 1, px = par & 1;
+  const int c = 4 * (bk.cblk * d.CQ + cq);
+  WinoDxTask task;
+  task.phase = -1; task.y0 = 0; task.x0 = 0;
+  const int j = round * workers + worker;
+  if (c >= Ctot || j >= p.tk.count) return task;
+  const int ph = wino_dx_phase_of(p, j), within = j - p.prefix[ph];
+  const int q = ph % nq, par = ph / nq, py = par >> 1, px = par & 1;
+  const int nx = (g.tw - px + 1) / 2;
+  const int ty = p.tk.ty_lo + ((p.tk.ty_lo & 1) != py) + 2 * (within / nx), tx = px + 2 * (within % nx);
   const int qy = q / g.nsub, qx = q - qy * g.nsub;
-  const int ny = (g.th - py + 1) / 2, nx = (g.tw - px + 1) / 2;
+  const int y0 = 4 * ty - g.pad + 3 * qy, x0 = 4 * tx - g.pad + 3 * qx;
+  if (y0 + 6 <= bk.h0 || y0 >= bk.h1) return task;  // the patch lies in another band
+  task.phase = ph;
+  task.y0 = y0; task.x0 = x0;
   const int grp = c / d.Cg, cl = c - grp * d.Cg;
   const long pstride = (long)nq * Ctot;
-  for (int j = worker; j < ny * nx; j += workers) {
-    const int ty = py + 2 * (j / nx), tx = px + 2 * (j % nx);
-    const long t = ((long)n * g.th + ty) * g.tw + tx;
-    const float* in = M + t * 36 * pstride + (long)grp * nq * d.Cg + (long)q * d.Cg + cl;
-    Vec4 u[36];
+  const long t = ((long)bk.n * g.th + ty) * g.tw + tx;
+  const float* in = M + t * 36 * pstride + (long)grp * nq * d.Cg + (long)q * d.Cg + cl;
+  Vec4 u[36];
+#pragma unroll
+  for (int jj = 0; jj < 6; ++jj) {
+    Vec4 col[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) col[i] = vload(in + (long)(6 * i + jj) * pstride);
+    wino_b<1, 6>(col, u + jj);  // u[i][jj]
+  }
+#pragma unroll
+  for (int i = 0; i < 6; ++i) wino_b<1, 1>(u + 6 * i, z + 6 * i);
+  return task;
+}
+// ... then the patches are added to the picture phase by phase (a barrier after each call).
+AX_HD void wino_dx_add(const WinoDx& d, const WinoDxPlan& p, Vec4* lds, int tid, const WinoDxTask& task, const Vec4* z,
+                       int phase) {
+  if (task.phase != phase) return;
+  const WinoDxBlock& bk = p.bk;
+  const int cq = tid % d.CQ;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    const int iy = task.y0 + i;
 #pragma unroll
     for (int jj = 0; jj < 6; ++jj) {
-      Vec4 col[6];
-#pragma unroll
-      for (int i = 0; i < 6; ++i) col[i] = vload(in + (long)(6 * i + jj) * pstride);
-      wino_b<1, 6>(col, u + jj);  // u[i][jj]
-    }
-    const int y0 = 4 * ty - g.pad + 3 * qy, x0 = 4 * tx - g.pad + 3 * qx;
-#pragma unroll
-    for (int i = 0; i < 6; ++i) {
-      Vec4 r[6];
-      wino_b<1, 1>(u + 6 * i, r);
-      const int iy = y0 + i;
-#pragma unroll
-      for (int jj = 0; jj < 6; ++jj) {
-        const int ix = x0 + jj;
-        if ((uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W) {
-          Vec4* acc = lds + ((long)iy * g.W + ix) * d.CQ + cq;
-          *acc = *acc + r[jj];
-        }
+      const int ix = task.x0 + jj;
+      if (iy >= bk.h0 && iy < bk.h1 && (uint32_t)ix < (uint32_t)d.g.W) {
+        Vec4* acc = lds + ((long)(iy - bk.h0) * d.g.W + ix) * d.CQ + cq;
+        *acc = *acc + z[6 * i + jj];
       }
     }
   }
 }
 // dx[n][pixel][c] = the picture in LDS, zero where gate <= 0 (gate may be null)
-AX_HD void wino_dx_flush(const WinoDx& d, const Vec4* lds, const float* gate, float* dx, int block, int tid) {
+AX_HD void wino_dx_flush(const WinoDx& d, const WinoDxPlan& p, const Vec4* lds, const float* gate, float* dx, int tid) {
   const int Ctot = d.Ctot();
-  const int n = block / d.cblocks(), cblk = block - n * d.cblocks();
-  for (int i = tid; i < d.lds_vec4(); i += kThreads) {
+  const WinoDxBlock& bk = p.bk;
+  const int count = (bk.h1 - bk.h0) * d.g.W * d.CQ;  // the last band may be shorter
+  for (int i = tid; i < count; i += kThreads) {
     const int cq = i % d.CQ, pix = i / d.CQ;
-    const int c = 4 * (cblk * d.CQ + cq);
+    const int c = 4 * (bk.cblk * d.CQ + cq);
     if (c >= Ctot) continue;
-    const long o = ((long)n * d.g.H * d.g.W + pix) * Ctot + c;
+    const long o = ((long)bk.n * d.g.H * d.g.W + (long)bk.h0 * d.g.W + pix) * Ctot + c;
     Vec4 v = lds[i];
     if (gate) {
       const Vec4 q = vload(gate + o);

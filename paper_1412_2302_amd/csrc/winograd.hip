@@ -33,18 +33,25 @@ __global__ void __launch_bounds__(256) wino_filter_kernel(int groups, int Na, in
   if (idx < total) wino_filter_thread(groups, Na, Nb, k, nsub, flip, q_in_cols, w, U, idx);
 }
 // one workgroup per (picture, block of CQ channel quads); dynamic LDS: H*W*CQ float4
-__global__ void __launch_bounds__(256) wino_dx_kernel(WinoDx d, const float* __restrict__ M,
+__global__ void __launch_bounds__(256) wino_dx_kernel(WinoDx d, int rounds, const float* __restrict__ M,
                                                        const float* __restrict__ gate, float* __restrict__ dx) {
   extern __shared__ __attribute__((aligned(16))) float4 wino_dx_lds[];
   Vec4* lds = reinterpret_cast<Vec4*>(wino_dx_lds);
-  const int tid = threadIdx.x, block = blockIdx.x;
+  const int tid = threadIdx.x;
+  const WinoDxPlan plan = wino_dx_plan(d, blockIdx.x);
   wino_dx_zero(d, lds, tid);
   __syncthreads();
-  for (int ph = 0; ph < d.phases(); ++ph) {
-    wino_dx_phase(d, M, lds, block, tid, ph);
-    __syncthreads();
+  for (int r = 0; r < rounds; ++r) {
+    Vec4 z[36];
+    const WinoDxTask task = wino_dx_load(d, plan, M, tid, r, z);
+    int lo, hi;  // the same for every thread of the block
+    wino_dx_round_phases(d, plan, r, &lo, &hi);
+    for (int ph = lo; ph <= hi; ++ph) {
+      wino_dx_add(d, plan, lds, tid, task, z, ph);
+      __syncthreads();
+    }
   }
-  wino_dx_flush(d, lds, gate, dx, block, tid);
+  wino_dx_flush(d, plan, lds, gate, dx, tid);
 }
 __global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb, int k, int nsub, int ns,
                                                        const float* __restrict__ dU, float* __restrict__ dw,
@@ -78,7 +85,7 @@ bool wino_ok(const ConvGeom& c) {
 static inline bool adjoint_form(const ConvGeom& c) { return c.k == 5; }
 constexpr size_t kDxLdsBytes = 48 * 1024;
 bool wino_bwd_data_ok(const ConvGeom& c) {
-  return wino_ok(c) && (!adjoint_form(c) || (size_t)c.H * c.W * 16 <= kDxLdsBytes);
+  return wino_ok(c) && (!adjoint_form(c) || (size_t)c.W * 16 <= kDxLdsBytes);  // one row of one quad at least
 }
 bool wino_bwd_data_shares_dy(const ConvGeom& c) { return adjoint_form(c); }
 // multiplies of the direct form per multiply of the products, at this map size
@@ -199,11 +206,16 @@ int launch_wino_bwd_data_adjoint(const ConvGeom& c, const float* yt, const float
   const int T = g.tiles();
   const ConvGeom p = product_geom(T, c.groups, c.og(), nq_of(c) * c.cg());
   AX_TRY(launch_conv_fwd(p, yt, Ut, nullptr, nullptr, 0, m, ws, st));
-  WinoDx d{g, c.cg(), 1};
-  while (d.CQ < 16 && d.CQ < c.Cin / 4 && (size_t)c.H * c.W * 16 * d.CQ * 2 <= kDxLdsBytes) d.CQ *= 2;
+  // eight channel quads (one 128-byte line of m) per workgroup where the channels allow, and as few row bands
+  // as make that fit; at most 16 quads when whole pictures fit
+  WinoDx d{g, c.cg(), 1, 1};
+  const int want = c.Cin / 4 >= 8 ? 8 : (c.Cin / 4 >= 4 ? 4 : (c.Cin / 4 >= 2 ? 2 : 1));
+  d.CQ = want;
+  while ((size_t)d.lds_vec4() * 16 > kDxLdsBytes && d.bands < c.H) ++d.bands;
+  while (d.bands == 1 && d.CQ < 16 && d.CQ * 2 <= c.Cin / 4 && (size_t)d.lds_vec4() * 32 <= kDxLdsBytes) d.CQ *= 2;
   KernelScope ks("wino_dx", 0, ((double)c.in_elems() * (gate ? 2 : 1) + (double)T * 36 * nq_of(c) * c.Cin) * 4.0, st);
-  hipLaunchKernelGGL(wino_dx_kernel, dim3((unsigned)(c.B * d.cblocks())), dim3(256), (size_t)d.lds_vec4() * 16, st, d, m,
-                     gate, dx);
+  hipLaunchKernelGGL(wino_dx_kernel, dim3((unsigned)d.blocks()), dim3(256), (size_t)d.lds_vec4() * 16, st, d,
+                     wino_dx_rounds(d), m, gate, dx);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }

@@ -195,23 +195,51 @@ static void run(const Case& k) {
           }
   check("bwd_weight", k.name, dw, dw_ref);
   // ---- backward data, adjoint form: dx = sum over patches of B [(A dy At) .* (G w Gt)] Bt, gated ----
-  for (int CQ : {1, 4, 16}) {
-    if (CQ > 1 && CQ > Cin / 4 * 2) continue;
-    WinoDx d{gf, k.cg, CQ};
+  for (int variant = 0; variant < 4; ++variant) {
+    const int CQ = variant == 0 ? 1 : 4, bands = variant < 2 ? 1 : (variant == 2 ? 2 : 3);
+    if (bands > k.H) continue;
+    WinoDx d{gf, k.cg, CQ, bands};
     std::vector<float> Ut(U.size(), NAN), ma((size_t)Tf * 36 * nq * Cin), dxa(x.size(), NAN);
     for (long i = 0; i < (long)G * nq * k.og * (k.cg / 4); ++i)
       wino_filter_thread(G, k.og, k.cg, K, nsub, 0, 1, wb.data(), Ut.data(), i);
     products(Tf, 36 * G, k.og, nq * k.cg, yt, Ut, ma);
     std::vector<Vec4> lds(d.lds_vec4());  // exactly what the kernel is given
-    for (int block = 0; block < k.B * d.cblocks(); ++block) {
+    for (int block = 0; block < d.blocks(); ++block) {
       for (auto& v : lds) v = {NAN, NAN, NAN, NAN};
       for (int tid = 0; tid < kThreads; ++tid) wino_dx_zero(d, lds.data(), tid);
-      for (int ph = 0; ph < d.phases(); ++ph)
-        for (int tid = 0; tid < kThreads; ++tid) wino_dx_phase(d, ma.data(), lds.data(), block, tid, ph);
-      for (int tid = 0; tid < kThreads; ++tid) wino_dx_flush(d, lds.data(), x.data(), dxa.data(), block, tid);
+      const WinoDxPlan plan = wino_dx_plan(d, block);
+      std::vector<Vec4> z((size_t)kThreads * 36);
+      std::vector<WinoDxTask> task(kThreads);
+      for (int r = 0; r < wino_dx_rounds(d); ++r) {
+        for (auto& v : z) v = {NAN, NAN, NAN, NAN};
+        for (int tid = 0; tid < kThreads; ++tid) task[tid] = wino_dx_load(d, plan, ma.data(), tid, r, &z[tid * 36]);
+        int ph_lo, ph_hi;
+        wino_dx_round_phases(d, plan, r, &ph_lo, &ph_hi);
+        for (int tid = 0; tid < kThreads; ++tid)
+          if (task[tid].phase >= 0 && (task[tid].phase < ph_lo || task[tid].phase > ph_hi))
+            emu_fail("a task's phase lies outside the phases its round runs");
+        for (int ph = ph_lo; ph <= ph_hi; ++ph) {
+          // within a phase no two threads may touch the same LDS word (on the GPU they run at once)
+          std::vector<int> writer(d.lds_vec4(), -1);
+          const WinoDxBlock bk = plan.bk;
+          for (int tid = 0; tid < kThreads; ++tid) {
+            if (task[tid].phase != ph) continue;
+            for (int i = 0; i < 6; ++i)
+              for (int jj = 0; jj < 6; ++jj) {
+                const int iy = task[tid].y0 + i, ix = task[tid].x0 + jj;
+                if (iy < bk.h0 || iy >= bk.h1 || ix < 0 || ix >= d.g.W) continue;
+                int& wtr = writer[((size_t)(iy - bk.h0) * d.g.W + ix) * d.CQ + tid % d.CQ];
+                if (wtr >= 0) emu_fail("two threads add to the same LDS word in one phase");
+                wtr = tid;
+              }
+          }
+          for (int tid = 0; tid < kThreads; ++tid) wino_dx_add(d, plan, lds.data(), tid, task[tid], &z[tid * 36], ph);
+        }
+      }
+      for (int tid = 0; tid < kThreads; ++tid) wino_dx_flush(d, plan, lds.data(), x.data(), dxa.data(), tid);
     }
     char nm[64];
-    snprintf(nm, sizeof nm, "%s CQ%d", k.name, CQ);
+    snprintf(nm, sizeof nm, "%s CQ%d b%d", k.name, CQ, bands);
     check("bwd_d_adj", nm, dxa, dx_ref);
   }
 }
