@@ -364,11 +364,8 @@ static int stage_bwd_data(alexnet* n, Stage& s, const float* dy, const float* wf
                           const float* gate, float* dx, bool taps_ready, bool yt_ready, hipStream_t st) {
   if (s.wino_bx && wino_usable(s, dy, wb, dx, gate)) {
     if (!taps_ready) AX_TRY(launch_wino_filter_bwd(s.g, wb, s.wino_ub, st));
-    if (wino_bwd_data_shares_dy(s.g)) {
-      if (!yt_ready) AX_TRY(launch_wino_output_grad(s.g, dy, n->wino_a, st));
-      return launch_wino_bwd_data_adjoint(s.g, n->wino_a, s.wino_ub, gate, dx, n->wino_m, n->gemm_ws, st);
-    }
-    return launch_wino_bwd_data(s.g, dy, s.wino_ub, gate, dx, n->wino_a, n->wino_m, n->gemm_ws, st);
+    if (!yt_ready) AX_TRY(launch_wino_output_grad(s.g, dy, n->wino_a, st));
+    return launch_wino_bwd_data(s.g, n->wino_a, s.wino_ub, gate, dx, n->wino_m, n->gemm_ws, st);
   }
   return launch_conv_bwd_data(s.g, dy, wf, wb, wphase, gate, dx, n->gemm_ws, st);
 }

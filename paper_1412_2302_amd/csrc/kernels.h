@@ -37,13 +37,10 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
 // ---- 3x3 and 5x5 unit-stride convolutions through F(4x4, 3x3) (winograd.hip) ----
 // All tensors 16-byte aligned, channels per group multiples of 4.  V: wino_v_floats(), U / Ub / dU:
 // wino_u_floats(), every other transformed tensor (v, m, yt): wino_scratch_floats(); ws: wino_gemm_ws_floats().
-// wino_ok: forward and weight gradient can take this path; wino_bwd_data_ok: the data gradient too (3x3 only);
+// wino_ok: forward and weight gradient can take this path; wino_bwd_data_ok: the data gradient too;
 // wino_gain: multiplies of the direct form per multiply of the transformed one at this layer's map size.
 bool wino_ok(const ConvGeom& c);
 bool wino_bwd_data_ok(const ConvGeom& c);
-// the data gradient starts from the transformed output gradient that launch_wino_bwd_weight leaves in `yt`
-// (5x5 layers: adjoint form) rather than from dy itself
-bool wino_bwd_data_shares_dy(const ConvGeom& c);
 double wino_gain(const ConvGeom& c);
 size_t wino_v_floats(const ConvGeom& c);
 size_t wino_u_floats(const ConvGeom& c);
@@ -54,13 +51,13 @@ int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStr
 int launch_wino_input(const ConvGeom& c, const float* x, float* V, hipStream_t st);
 int launch_wino_fwd(const ConvGeom& c, const float* x, const float* U, const float* bias, int relu, float* y, float* V,
                     float* m, float* ws, hipStream_t st);
-int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, const float* gate, float* dx, float* v,
-                         float* m, float* ws, hipStream_t st);
 int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
                            float* ws, hipStream_t st);
 int launch_wino_output_grad(const ConvGeom& c, const float* dy, float* yt, hipStream_t st);
-int launch_wino_bwd_data_adjoint(const ConvGeom& c, const float* yt, const float* Ut, const float* gate, float* dx,
-                                 float* m, float* ws, hipStream_t st);
+// the data gradient starts from the transformed output gradient yt (launch_wino_output_grad, or what
+// launch_wino_bwd_weight left in its `yt`), not from dy
+int launch_wino_bwd_data(const ConvGeom& c, const float* yt, const float* Ut, const float* gate, float* dx, float* m,
+                         float* ws, hipStream_t st);
 
 // ---- dense layers (conv_gemm.hip) -------------------------------------------
 struct FcAct {

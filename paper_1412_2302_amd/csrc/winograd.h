@@ -8,8 +8,7 @@
 // 36 multiplies per tile and channel pair instead of 144.  Writing the same trilinear form
 // T[i][j][k] = sum_p At[i][p] G[p][j] Bt[p][k] for the other two arguments gives the adjoints:
 //     dg = Gt [ (A dy) .* (Bt d) ]         (gradient of the taps: A = At^T applied to the 4 output gradients)
-// and the gradient of the input is again a 3x3 correlation (of dy, with the taps reversed and the channel
-// roles swapped), so it runs through the forward form.
+//     dd = B  [ (A dy) .* (G g)  ]         (gradient of the input patch: B = Bt^T; overlapping patches add up)
 //
 // Data layout of the transformed tensors: one row per tile t = (picture, tile row, tile column) and
 // 36 * groups * Cg columns, column (p*groups + g)*Cg + c for tile position p = 6*row + column.  That is
@@ -450,12 +449,11 @@ AX_HD void wino_dx_flush(const WinoDx& d, const WinoDxPlan& p, const Vec4* lds, 
 // Taps to transformed taps and back.  `w` is [groups][(r, s, a)][b] (k x k taps; a < Na rows, b < Nb
 // columns: the forward weights with a = input channel, b = output channel, or the backward-data
 // weights with the roles swapped), `U` is [(p*groups + g)][q*Na + a][b] for sub-kernel q = (qy, qx) with the
-// taps (3qy + i, 3qx + j), zero where they do not exist.  flip reverses both tap axes (the backward-data
-// correlation).  q_in_cols stores U as [(p*groups + g)][a][q*Nb + b] instead (the operand of the adjoint
-// data-gradient product, whose columns are (sub-kernel, input channel)).  idx enumerates (group, sub-kernel,
-// a, column quad).
-AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int flip, int q_in_cols, const float* w,
-                              float* U, long idx) {
+// taps (3qy + i, 3qx + j), zero where they do not exist.  q_in_cols stores U as [(p*groups + g)][a][q*Nb + b]
+// instead (the operand of the data-gradient products, whose columns are (sub-kernel, input channel)).
+// idx enumerates (group, sub-kernel, a, column quad).
+AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int q_in_cols, const float* w, float* U,
+                              long idx) {
   const int quads = Nb / 4, nq = nsub * nsub;
   const long row = idx / quads;  // (g*nq + q)*Na + a
   const int b = 4 * (int)(idx - row * quads);
@@ -468,10 +466,7 @@ AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int f
     for (int j = 0; j < 3; ++j) {
       const int r = 3 * qy + i, s2 = 3 * qx + j;
       t[3 * i + j] = vzero();
-      if (r < k && s2 < k) {
-        const int tap = flip ? (k - 1 - r) * k + (k - 1 - s2) : r * k + s2;
-        t[3 * i + j] = vload(w + (((long)grp * k * k + tap) * Na + a) * Nb + b);
-      }
+      if (r < k && s2 < k) t[3 * i + j] = vload(w + (((long)grp * k * k + r * k + s2) * Na + a) * Nb + b);
     }
 #pragma unroll
   for (int j = 0; j < 3; ++j) wino_g<3, 3>(t + j, u + j);  // columns: 3 -> 6 rows of 3

@@ -26,11 +26,11 @@ __global__ void __launch_bounds__(256) wino_out_kernel(WinoGeom g, int Ng, const
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < total) wino_out_thread(g, Ng, M, bias, relu, gate, y, idx);
 }
-__global__ void __launch_bounds__(256) wino_filter_kernel(int groups, int Na, int Nb, int k, int nsub, int flip,
-                                                           int q_in_cols, const float* __restrict__ w,
-                                                           float* __restrict__ U, long total) {
+__global__ void __launch_bounds__(256) wino_filter_kernel(int groups, int Na, int Nb, int k, int nsub, int q_in_cols,
+                                                           const float* __restrict__ w, float* __restrict__ U,
+                                                           long total) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < total) wino_filter_thread(groups, Na, Nb, k, nsub, flip, q_in_cols, w, U, idx);
+  if (idx < total) wino_filter_thread(groups, Na, Nb, k, nsub, q_in_cols, w, U, idx);
 }
 // one workgroup per (picture, block of CQ channel quads); dynamic LDS: H*W*CQ float4
 __global__ void __launch_bounds__(256) wino_dx_kernel(WinoDx d, int rounds, const float* __restrict__ M,
@@ -66,28 +66,19 @@ static inline int nq_of(const ConvGeom& c) { return nsub_of(c) * nsub_of(c); }
 static WinoGeom fwd_geom(const ConvGeom& c) {
   return WinoGeom{c.B, c.H, c.W, c.pad, c.Ho, c.Wo, (c.Ho + 3) / 4, (c.Wo + 3) / 4, c.groups, c.k, nsub_of(c)};
 }
-// backward-data: dx = correlation of dy (pad k - 1 - pad) with the reversed taps
-static WinoGeom bwd_geom(const ConvGeom& c) {
-  return WinoGeom{c.B, c.Ho, c.Wo, c.k - 1 - c.pad, c.H, c.W, (c.H + 3) / 4, (c.W + 3) / 4, c.groups, c.k, nsub_of(c)};
-}
 bool wino_ok(const ConvGeom& c) {
   if ((c.k != 3 && c.k != 5) || c.stride != 1 || c.pad > c.k - 1 || c.cg() % 4 || c.og() % 4) return false;
   // the transformed tensors are 36/16 (tiles cut exactly) to ~4x larger than the activations, times the
   // number of sub-kernels on the gathered side
-  const long T = std::max((long)fwd_geom(c).tiles(), (long)bwd_geom(c).tiles());
-  return T * 36 * nq_of(c) * std::max(c.Cin, c.Cout) <= 0x1ffffff0L;
+  return (long)fwd_geom(c).tiles() * 36 * std::max(nq_of(c) * c.Cin, c.Cout) <= 0x1ffffff0L;
 }
-// The data gradient of a 3x3 layer is the forward form applied to dy (reversed taps).  For 5x5 that would take
-// four shifted transforms of dy with Cout channels each, which cost what the smaller products save; there the
-// adjoint form is used: the products of the transformed output gradient (shared with the weight gradient) go
-// back through B . Bt, patches added up in LDS (wino_dx_kernel), which needs a picture of CQ >= 1 channel
-// quads to fit 48 KiB.
-static inline bool adjoint_form(const ConvGeom& c) { return c.k == 5; }
+// The data gradient is the adjoint of the forward form: the products of the transformed output gradient (the
+// one the weight gradient uses) with the transformed taps go back through B . Bt, overlapping patches added up
+// in LDS (wino_dx_kernel), which needs one picture row of one channel quad to fit the budget at the very least.
+// (The other way, the forward form applied to dy with reversed taps, needs a second transform of dy -- four of
+// them, with Cout channels each, for a 5x5 layer -- and measured 15-20 us slower per 3x3 layer.)
 constexpr size_t kDxLdsBytes = 48 * 1024;
-bool wino_bwd_data_ok(const ConvGeom& c) {
-  return wino_ok(c) && (!adjoint_form(c) || (size_t)c.W * 16 <= kDxLdsBytes);  // one row of one quad at least
-}
-bool wino_bwd_data_shares_dy(const ConvGeom& c) { return adjoint_form(c); }
+bool wino_bwd_data_ok(const ConvGeom& c) { return wino_ok(c) && (size_t)c.W * 16 <= kDxLdsBytes; }
 // multiplies of the direct form per multiply of the products, at this map size
 double wino_gain(const ConvGeom& c) {
   const double covered = (double)c.Ho * c.Wo / (16.0 * ((c.Ho + 3) / 4) * ((c.Wo + 3) / 4));
@@ -103,19 +94,16 @@ static ConvGeom product_geom(int tiles, int groups, int kin, int nout) {
 size_t wino_v_floats(const ConvGeom& c) { return (size_t)fwd_geom(c).tiles() * 36 * nq_of(c) * c.Cin; }
 size_t wino_u_floats(const ConvGeom& c) { return (size_t)36 * nq_of(c) * c.cg() * c.og() * c.groups; }
 size_t wino_scratch_floats(const ConvGeom& c) {
-  const size_t tf = (size_t)fwd_geom(c).tiles(), tb = (size_t)bwd_geom(c).tiles();
+  const size_t tf = (size_t)fwd_geom(c).tiles();
   size_t n = 36 * tf * c.Cout;  // forward products, transformed output gradient
-  if (wino_bwd_data_ok(c) && adjoint_form(c)) n = std::max(n, 36 * tf * nq_of(c) * c.Cin);
-  if (wino_bwd_data_ok(c) && !adjoint_form(c)) n = std::max(n, 36 * std::max(tb * c.Cout * nq_of(c), tb * c.Cin));
+  if (wino_bwd_data_ok(c)) n = std::max(n, 36 * tf * nq_of(c) * c.Cin);  // data-gradient products
   return n;
 }
 size_t wino_gemm_ws_floats(const ConvGeom& c) {
   const ConvGeom pf = product_geom(fwd_geom(c).tiles(), c.groups, nq_of(c) * c.cg(), c.og());
   size_t n = std::max(conv_fwd_ws_floats(pf), conv_bwd_weight_ws_floats(pf));
-  if (wino_bwd_data_ok(c) && adjoint_form(c))
+  if (wino_bwd_data_ok(c))
     n = std::max(n, conv_fwd_ws_floats(product_geom(fwd_geom(c).tiles(), c.groups, c.og(), nq_of(c) * c.cg())));
-  if (wino_bwd_data_ok(c) && !adjoint_form(c))
-    n = std::max(n, conv_fwd_ws_floats(product_geom(bwd_geom(c).tiles(), c.groups, nq_of(c) * c.og(), c.cg())));
   return n;
 }
 
@@ -126,17 +114,16 @@ int launch_wino_filter(const ConvGeom& c, const float* wf, float* U, hipStream_t
   const long total = (long)c.groups * nq_of(c) * c.cg() * (c.og() / 4);
   KernelScope ks("wino_filter", 0, ((double)c.w_elems() + (double)wino_u_floats(c)) * 4.0, st);
   hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), c.k, nsub_of(c),
-                     0, 0, wf, U, total);
+                     0, wf, U, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
 int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStream_t st) {
   const long total = (long)c.groups * nq_of(c) * c.og() * (c.cg() / 4);
   KernelScope ks("wino_filter", 0, ((double)c.w_elems() + (double)wino_u_floats(c)) * 4.0, st);
-  // forward form: reversed taps, [z][(q, o)][c]; adjoint form: the taps as they are, [z][o][(q, c)]
-  const int adj = adjoint_form(c) ? 1 : 0;
+  // the operand of the data-gradient products: [z][o][(q, c)]
   hipLaunchKernelGGL(wino_filter_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.og(), c.cg(), c.k, nsub_of(c),
-                     1 - adj, adj, wb, Ub, total);
+                     1, wb, Ub, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -167,27 +154,6 @@ int launch_wino_fwd(const ConvGeom& c, const float* x, const float* U, const flo
   return ALEXNET_OK;
 }
 
-// dy -> v (transformed like an input), v x Ub -> m, m -> dx gated by gate > 0 (gate may be null)
-int launch_wino_bwd_data(const ConvGeom& c, const float* dy, const float* Ub, const float* gate, float* dx, float* v,
-                         float* m, float* ws, hipStream_t st) {
-  const WinoGeom g = bwd_geom(c);
-  const int T = g.tiles();
-  {
-    const long total = (long)T * nq_of(c) * (c.Cout / 4);
-    KernelScope ks("wino_in", 0, ((double)c.out_elems() + (double)T * 36 * nq_of(c) * c.Cout) * 4.0, st);
-    hipLaunchKernelGGL(wino_in_kernel, blocks_for(total), dim3(256), 0, st, g, c.og(), dy, v, total);
-    AX_LAUNCH_CHECK();
-  }
-  const ConvGeom p = product_geom(T, c.groups, nq_of(c) * c.og(), c.cg());
-  AX_TRY(launch_conv_fwd(p, v, Ub, nullptr, nullptr, 0, m, ws, st));
-  const long total = (long)T * (c.Cin / 4);
-  KernelScope ks("wino_out", 0, ((double)c.in_elems() * (gate ? 2 : 1) + (double)T * 36 * c.Cin) * 4.0, st);
-  hipLaunchKernelGGL(wino_out_kernel, blocks_for(total), dim3(256), 0, st, g, c.cg(), m, (const float*)nullptr, 0, gate,
-                     dx, total);
-  AX_LAUNCH_CHECK();
-  return ALEXNET_OK;
-}
-
 int launch_wino_output_grad(const ConvGeom& c, const float* dy, float* yt, hipStream_t st) {
   const WinoGeom g = fwd_geom(c);
   const int T = g.tiles();
@@ -198,9 +164,9 @@ int launch_wino_output_grad(const ConvGeom& c, const float* dy, float* yt, hipSt
   return ALEXNET_OK;
 }
 
-// Adjoint form: yt x Ut -> m (36 products, columns (sub-kernel, input channel)), m -> dx gated by gate > 0.
+// yt x Ut -> m (36 products, columns (sub-kernel, input channel)), m -> dx gated by gate > 0 (gate may be null).
 // yt is the transformed output gradient (launch_wino_output_grad, or what launch_wino_bwd_weight left there).
-int launch_wino_bwd_data_adjoint(const ConvGeom& c, const float* yt, const float* Ut, const float* gate, float* dx,
+int launch_wino_bwd_data(const ConvGeom& c, const float* yt, const float* Ut, const float* gate, float* dx,
                                  float* m, float* ws, hipStream_t st) {
   const WinoGeom g = fwd_geom(c);
   const int T = g.tiles();
