@@ -441,7 +441,7 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
 }
 
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
-                           hipStream_t st, int* slices) {
+                           hipStream_t st) {
   const bool run = dwrun && run_mode(c) && bwdw_B_vec(c, dy);
   AlgoFlops af(conv_flops(c));
   GemmDims d = bwdw_dims(c);
@@ -466,11 +466,7 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
     AX_TRY((by_tile_tap<ConvWeightGradTable>(p, a, bwdw_B(c, dy), ep, d, st)));
   else
     AX_TRY((by_tile<ConvWeightGrad>(p, av, bv, a, bwdw_B(c, dy), ep, d, st)));
-  if (slices) *slices = 1;
-  if (p.ns > 1 && slices && !run)
-    *slices = p.ns;
-  else if (p.ns > 1)
-    AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, out, st));
+  if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, out, st));
   if (run) AX_TRY(launch_conv_run_unpack(c, dwrun, dwf, st));
   return ALEXNET_OK;
 }

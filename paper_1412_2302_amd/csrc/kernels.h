@@ -29,10 +29,8 @@ bool conv_phase_mode(const ConvGeom& c);
 size_t conv_phase_w_floats(const ConvGeom& c);
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, const float* wb, float* wphase,
                          const float* gate, float* dx, float* ws, hipStream_t st);
-// slices: when given and the reduction was split, the partial results stay in ws as [(group*n + slice)][rows][og]
-// and *slices = n (the caller adds them); otherwise they are added into dwf and *slices = 1
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
-                           hipStream_t st, int* slices = nullptr);
+                           hipStream_t st);
 
 // ---- 3x3 and 5x5 unit-stride convolutions through F(4x4, 3x3) (winograd.hip) ----
 // All tensors 16-byte aligned, channels per group multiples of 4.  V: wino_v_floats(), U / Ub / dU:

@@ -482,24 +482,21 @@ AX_HD void wino_filter_thread(int groups, int Na, int Nb, int k, int nsub, int q
   }
 }
 // dw[groups][(r, s, a)][b] = (Gt m G)[i][j] at r = 3qy + i, s = 3qx + j (taps that exist only),
-// m = sum over the ns partial products dU[(p*groups + g)*ns + slice][q*Na + a][b] (the slices of a reduction
-// that was split over workgroups, added here in a fixed order).  idx as in wino_filter_thread.
-AX_HD void wino_dw_thread(int groups, int Na, int Nb, int k, int nsub, int ns, const float* dU, float* dw, long idx) {
+// m[p] = dU[(p*groups + g)][q*Na + a][b].  idx as in wino_filter_thread.
+AX_HD void wino_dw_thread(int groups, int Na, int Nb, int k, int nsub, const float* dU, float* dw, long idx) {
   const int quads = Nb / 4, nq = nsub * nsub;
   const long row = idx / quads;
   const int b = 4 * (int)(idx - row * quads);
   const int grp = (int)(row / ((long)nq * Na)), r2 = (int)(row - (long)grp * nq * Na);
   const int q = r2 / Na, a = r2 - q * Na, qy = q / nsub, qx = q - qy * nsub;
-  const long slice = (long)nq * Na * Nb;
+  const long slab = (long)nq * Na * Nb;
   Vec4 u[18];
 #pragma unroll
   for (int j = 0; j < 6; ++j) {
     Vec4 col[6];
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
-      const float* src = dU + ((long)(6 * i + j) * groups + grp) * ns * slice + ((long)q * Na + a) * Nb + b;
-      col[i] = vload(src);
-      for (int sl = 1; sl < ns; ++sl) col[i] = col[i] + vload(src + sl * slice);
+      col[i] = vload(dU + ((long)(6 * i + j) * groups + grp) * slab + ((long)q * Na + a) * Nb + b);
     }
     wino_gt<1, 6>(col, u + j);  // u[i][j], 3 rows of 6
   }

@@ -53,11 +53,11 @@ __global__ void __launch_bounds__(256) wino_dx_kernel(WinoDx d, int rounds, cons
   }
   wino_dx_flush(d, plan, lds, gate, dx, tid);
 }
-__global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb, int k, int nsub, int ns,
+__global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb, int k, int nsub,
                                                        const float* __restrict__ dU, float* __restrict__ dw,
                                                        long total) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < total) wino_dw_thread(groups, Na, Nb, k, nsub, ns, dU, dw, idx);
+  if (idx < total) wino_dw_thread(groups, Na, Nb, k, nsub, dU, dw, idx);
 }
 
 // ---- geometry ----------------------------------------------------------------------------------
@@ -193,19 +193,13 @@ int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, f
   const int T = g.tiles();
   AX_TRY(launch_wino_output_grad(c, dy, yt, st));
   const ConvGeom p = product_geom(T, c.groups, nq_of(c) * c.cg(), c.og());
-  int ns = 1;  // slices of the reduction over the tiles
-  AX_TRY(launch_conv_bwd_weight(p, V, yt, dU, nullptr, ws, st, &ns));
+  // (split over the tiles where that fills the chip; the slices are added by the wide reduction kernel: letting
+  // the transform below add them, with its 12 to 25 thousand threads, measured 15-50 us slower)
+  AX_TRY(launch_conv_bwd_weight(p, V, yt, dU, nullptr, ws, st));
   const long total = (long)c.groups * nq_of(c) * c.cg() * (c.og() / 4);
-  // The transform below can add the slices itself, which saves a pass over them, but it has one thread per four
-  // taps sets only: with many slices and few threads (the 5x5 layer: 12288 threads, 6 slices) a separate, wide
-  // reduction first is faster (85 -> 35 us).
-  if (ns > 2 && total < 16384) {
-    AX_TRY(launch_reduce_slabs(ws, ns, (long)nq_of(c) * c.cg() * c.og(), 36 * c.groups, dU, st));
-    ns = 1;
-  }
-  KernelScope ks("wino_dw", 0, ((double)wino_u_floats(c) * ns + (double)c.w_elems()) * 4.0, st);
-  hipLaunchKernelGGL(wino_dw_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), c.k, nsub_of(c), ns,
-                     ns > 1 ? ws : dU, dwf, total);
+  KernelScope ks("wino_dw", 0, ((double)wino_u_floats(c) + (double)c.w_elems()) * 4.0, st);
+  hipLaunchKernelGGL(wino_dw_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), c.k, nsub_of(c), dU,
+                     dwf, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }

@@ -169,22 +169,18 @@ static void run(const Case& k) {
   for (size_t i = 0; i < dx_ref.size(); ++i)
     if (!(x[i] > 0.f)) dx_ref[i] = 0;
   // ---- backward weight ----
-  // the reduction over the tiles in ns slices, as a split launch leaves them: [(z*ns + slice)][c][o]
-  const int ns = Tf >= 3 ? 3 : 1, per = (Tf + ns - 1) / ns;
   const int kc = nq * k.cg;  // rows of one product's result: (sub-kernel, channel)
-  std::vector<float> yt((size_t)Tf * 36 * Cout), dU(U.size() * ns), dw(wf.size(), NAN);
+  std::vector<float> yt((size_t)Tf * 36 * Cout), dU(U.size()), dw(wf.size(), NAN);
   for (long i = 0; i < (long)Tf * (Cout / 4); ++i) wino_dy_thread(gf, k.og, dy.data(), yt.data(), i);
   for (int z = 0; z < 36 * G; ++z)
-    for (int sl = 0; sl < ns; ++sl)
-      for (int c = 0; c < kc; ++c)
-        for (int o = 0; o < k.og; ++o) {
-          float s = 0.f;
-          for (int t = sl * per; t < std::min(Tf, (sl + 1) * per); ++t)
-            s += V[((size_t)t * 36 * G + z) * kc + c] * yt[((size_t)t * 36 * G + z) * k.og + o];
-          dU[(((size_t)z * ns + sl) * kc + c) * k.og + o] = s;
-        }
+    for (int c = 0; c < kc; ++c)
+      for (int o = 0; o < k.og; ++o) {
+        float s = 0.f;
+        for (int t = 0; t < Tf; ++t) s += V[((size_t)t * 36 * G + z) * kc + c] * yt[((size_t)t * 36 * G + z) * k.og + o];
+        dU[((size_t)z * kc + c) * k.og + o] = s;
+      }
   for (long i = 0; i < (long)G * nq * k.cg * (k.og / 4); ++i)
-    wino_dw_thread(G, k.cg, k.og, K, nsub, ns, dU.data(), dw.data(), i);
+    wino_dw_thread(G, k.cg, k.og, K, nsub, dU.data(), dw.data(), i);
   std::vector<double> dw_ref(wf.size(), 0.0);
   for (int n = 0; n < k.B; ++n)
     for (int oy = 0; oy < Ho; ++oy)
