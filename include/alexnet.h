@@ -88,12 +88,13 @@ typedef struct {
 /* Sizes the caller must allocate: n_params floats each for parameters and
  * momentum, and workspace_bytes of scratch.  Host-only; no GPU work.
  *
- * In fp32, convolution stages with 3x3 kernels, unit stride and channel
- * counts per group that are multiples of 4 (conv3-5 of Section 2's network)
- * are computed through F(4x4, 3x3) tile transforms: the same result up to
- * rounding order with 2.6x fewer multiplications, at the price of more
- * workspace.  Setting the environment variable ALEXNET_DIRECT_CONV=1 before
- * alexnet_query and alexnet_create (both must see the same value) keeps those
+ * In fp32, convolution stages with 3x3 or 5x5 kernels, unit stride and
+ * channel counts per group that are multiples of 4 (conv2-5 of Section 2's
+ * network) are computed through F(4x4, 3x3) tile transforms (a 5x5 kernel as
+ * four 3x3 sub-kernels): the same result up to rounding order with 2.6x fewer
+ * multiplications, at the price of more workspace.  Setting the environment
+ * variable ALEXNET_DIRECT_CONV=1 before alexnet_query and alexnet_create
+ * (both must see the same value) keeps those
  * stages on the direct implicit GEMM. */
 int alexnet_query(const alexnet_config_t* cfg, size_t* n_params, size_t* workspace_bytes);
 
