@@ -328,15 +328,22 @@ AX_HD WinoDxPlan wino_dx_plan(const WinoDx& d, int block) {
   p.bk = wino_dx_block(d, block);
   p.tk = wino_dx_tasks(d, p.bk);
   p.prefix[0] = 0;
+#pragma unroll
   for (int ph = 0; ph < 16; ++ph)
     p.prefix[ph + 1] = p.prefix[ph] + (ph < d.phases() ? wino_dx_phase_count(d, p.tk, ph) : 0);
   return p;
 }
-// phase of task j (j < count)
-AX_HD int wino_dx_phase_of(const WinoDxPlan& p, int j) {
-  int ph = 0;
+// phase of task j (j < count) and the number of tasks before that phase; only constant indices into prefix[],
+// so that it stays in registers
+AX_HD int wino_dx_phase_of(const WinoDxPlan& p, int j, int* before) {
+  int ph = 0, b = 0;
 #pragma unroll
-  for (int k = 1; k < 16; ++k) ph += j >= p.prefix[k] ? 1 : 0;
+  for (int k = 1; k < 16; ++k)
+    if (j >= p.prefix[k]) {
+      ph = k;
+      b = p.prefix[k];
+    }
+  *before = b;
   return ph;
 }
 AX_HD int wino_dx_rounds(const WinoDx& d) {  // the same for every block: the largest need of any band
@@ -361,8 +368,9 @@ AX_HD void wino_dx_round_phases(const WinoDx& d, const WinoDxPlan& p, int round,
     *lo = 1; *hi = 0;
     return;
   }
-  *lo = wino_dx_phase_of(p, first);
-  *hi = wino_dx_phase_of(p, last);
+  int before;
+  *lo = wino_dx_phase_of(p, first, &before);
+  *hi = wino_dx_phase_of(p, last, &before);
 }
 // One task of a thread: phase < 0 means none.  z = B m Bt of the patch, to be added at (y0 + i, x0 + j).
 struct WinoDxTask {
@@ -380,7 +388,8 @@ AX_HD WinoDxTask wino_dx_load(const WinoDx& d, const WinoDxPlan& p, const float*
   task.phase = -1; task.y0 = 0; task.x0 = 0;
   const int j = round * workers + worker;
   if (c >= Ctot || j >= p.tk.count) return task;
-  const int ph = wino_dx_phase_of(p, j), within = j - p.prefix[ph];
+  int before;
+  const int ph = wino_dx_phase_of(p, j, &before), within = j - before;
   const int q = ph % nq, par = ph / nq, py = par >> 1, px = par & 1;
   const int nx = (g.tw - px + 1) / 2;
   const int ty = p.tk.ty_lo + ((p.tk.ty_lo & 1) != py) + 2 * (within / nx), tx = px + 2 * (within % nx);
