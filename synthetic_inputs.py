@@ -98,7 +98,25 @@ TINY = {
     "dropout_p": 0.5, "lr": 0.01, "momentum": 0.9, "weight_decay": 5e-4,
 }
 
-WORKLOADS = {"alexnet": ALEXNET, "mini": MINI, "midi": MIDI, "pads": PADS, "tiny": TINY}
+# Channel counts, group sizes and layer widths that are no multiples of four, a 1x1 kernel and three groups:
+# every kernel that has a 16-byte form falls back to its 4-byte form.
+# 33 -> conv1(5,s2,p1) 16 -> pool 7 -> conv2 7 -> pool 3 -> conv3/4 3 -> conv5(1x1) 3 -> pool 1; flatten 7.
+ODD = {
+    "name": "odd",
+    "in_c": 3, "crop": 33, "raw": 35,
+    "conv": [
+        (6, 5, 2, 1, 1, 1, 1),
+        (10, 3, 1, 1, 2, 1, 1),
+        (9, 3, 1, 1, 1, 0, 0),
+        (15, 3, 1, 1, 3, 0, 0),
+        (7, 1, 1, 0, 1, 0, 1),
+    ],
+    "fc": [13, 11, 3],
+    "lrn": (5, 2.0, 1e-4, 0.75),
+    "dropout_p": 0.5, "lr": 0.01, "momentum": 0.9, "weight_decay": 5e-4,
+}
+
+WORKLOADS = {"alexnet": ALEXNET, "mini": MINI, "midi": MIDI, "pads": PADS, "tiny": TINY, "odd": ODD}
 
 
 def make_params(shapes, seed: int, bias_value: float = 0.0, std: float = 0.01):

@@ -715,6 +715,11 @@ int main() {
       {geom(3, 6, 32, 96, 5, 1, 2, 1), "k5p2c32"},       // 25 taps, ragged rows and columns
       {geom(4, 7, 8, 24, 3, 1, 1, 2), "k3p1g2px224"},    // 4*7*8 = 224 pixels: whole k-tiles for backward-weight
       {geom(4, 15, 3, 8, 5, 2, 0, 1), "k5s2c3px192"},    // run mode with 4*6*8 = 192 output pixels
+      {geom(2, 9, 3, 6, 5, 2, 1, 1), "k5s2p1c3o6"},      // channel counts that are no multiples of four:
+      {geom(2, 7, 6, 10, 3, 1, 1, 2), "k3g2c3o5"},       // every operand falls back to 4-byte loads
+      {geom(2, 3, 10, 9, 3, 1, 1, 1), "k3c10o9"},
+      {geom(2, 3, 9, 15, 3, 1, 1, 3), "k3g3c3o5"},
+      {geom(2, 3, 15, 7, 1, 1, 0, 1), "k1c15o7"},
       {product_geom(48, 12, 16, 8), "1x1g12c16t48"},    // whole k-tiles in every product
       {product_geom(40, 9, 20, 12), "1x1g9c20t40"},     // ragged k and pixel counts
       {product_geom(160, 4, 32, 32), "1x1g4c32t160"},   // two row tiles

@@ -142,6 +142,12 @@ def test_bf16_midi_net_with_preprocess(lib):
     print(errs)
 
 
+def test_bf16_falls_back_to_fp32_products_where_sizes_are_no_multiples_of_four(lib):
+    """The bf16 kernels exist for 16-byte loads only; a net whose every operand is unaligned runs the fp32
+    kernels under precision = 1 and meets the fp32 bar."""
+    run_step_and_compare(lib, S.ODD, 5, seed=16, bias=0.1, std=0.2, use_raw=False, steps=2, mom_std=0.01, precision=1)
+
+
 def test_bf16_and_fp32_replicas_stay_close(lib):
     """Same data, same parameters: the bf16 step lands within the bf16 bar of the fp32 step."""
     batch, wl = 6, S.MIDI

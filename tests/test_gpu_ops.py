@@ -20,7 +20,7 @@ def _tie_heavy(shape, seed):
     return np.maximum(x, 0)
 
 
-@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 3), (S.ALEXNET, 128)])
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 3), (S.ODD, 3), (S.ALEXNET, 128)])
 def test_pool_forward_backward_bit_exact_decisions(lib, wl, batch):
     net = lib.AlexNet(wl, batch)
     spec = oracle_spec(wl, batch)
@@ -44,7 +44,7 @@ def test_pool_forward_backward_bit_exact_decisions(lib, wl, batch):
     net.close()
 
 
-@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 3), (S.ALEXNET, 16)])
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 3), (S.ODD, 3), (S.ALEXNET, 16)])
 def test_lrn_forward_backward(lib, wl, batch):
     net = lib.AlexNet(wl, batch)
     spec = oracle_spec(wl, batch)
@@ -68,7 +68,7 @@ def test_lrn_forward_backward(lib, wl, batch):
     net.close()
 
 
-@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 7), (S.ALEXNET, 128)])
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 7), (S.ODD, 3), (S.ALEXNET, 128)])
 def test_dense_layers_alone(lib, wl, batch):
     net = lib.AlexNet(wl, batch)
     spec = oracle_spec(wl, batch)

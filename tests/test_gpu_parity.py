@@ -55,7 +55,7 @@ def conv_path(direct):
 
 
 @pytest.mark.parametrize("direct", [False, True], ids=["transformed3x3", "direct3x3"])
-@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5), (S.PADS, 3)])
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5), (S.PADS, 3), (S.ODD, 3)])
 def test_conv_layers_alone(lib, wl, batch, direct):
     with conv_path(direct):
         net = lib.AlexNet(wl, batch)
@@ -126,6 +126,55 @@ def test_whole_step_at_degenerate_sizes(lib, wl, batch):
     """Batch 1 and 2, maps that shrink to 3x3 and 1x1 (one 4x4 tile per picture on the transformed path,
     one pixel per picture on the direct one), dense layers narrower than a GEMM tile."""
     run_step_and_compare(lib, wl, batch, seed=15, bias=0.1, std=0.3, use_raw=False, steps=2, mom_std=0.01)
+
+
+def test_whole_step_with_sizes_that_are_no_multiples_of_four(lib):
+    """Channel counts 6, 10, 9, 15, 7 (3 and 5 per group), dense widths 13, 11, 3: the 4-byte forms of the
+    GEMM loaders, normalisation, pooling and column sums, parameter blocks that start off 16-byte boundaries,
+    and one update at the end of the step instead of the early dense-layer update."""
+    run_step_and_compare(lib, S.ODD, 5, seed=16, bias=0.1, std=0.2, use_raw=False, steps=2, mom_std=0.01)
+
+
+def midi_with_odd_dense_widths():
+    return dict(S.MIDI, name="midi_odd_fc", fc=[201, 135, 37])
+
+
+def test_whole_step_with_transformed_stages_and_odd_dense_widths(lib):
+    """Aligned convolution stages (tile-transform path) over dense layers of odd width: the parameter count is
+    no multiple of four, so the step updates everything at its end and transforms the taps on the caller's
+    stream."""
+    wl = midi_with_odd_dense_widths()
+    probe = lib.AlexNet(wl, 4)
+    assert sum(int(np.prod(s)) for k, s in probe.shapes.items() if k.endswith(".w")) % 4 != 0
+    probe.close()
+    run_step_and_compare(lib, wl, 4, seed=17, bias=0.05, std=0.02, use_raw=True, steps=2, mom_std=0.01)
+
+
+@pytest.mark.parametrize("wl", [S.ODD, None], ids=["odd", "midi_odd_fc"])
+def test_train_step_equals_its_parts_without_the_early_update(lib, wl):
+    wl = wl or midi_with_odd_dense_widths()
+    batch, classes = 5, wl["fc"][-1]
+    a, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 4, pseed=4, std=0.1, bias=0.1)
+    b, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 4, pseed=4, std=0.1, bias=0.1)
+    mean = cuda(S.make_mean_image(3, wl["raw"], wl["raw"], S.SEED_BASE + 7))
+    for step in range(3):
+        raw, labels = S.make_raw_batch(batch, 3, wl["raw"], wl["raw"], classes, S.SEED_BASE + 40 + step)
+        raw, labels = cuda(raw), cuda(labels)
+        a.preprocess(raw, mean, step, step % 2)
+        b.preprocess(raw, mean, step, step % 2)
+        la = float(a.train_step(labels, step, slot=step % 2).cpu().item())
+        lb = float(b.forward_backward(labels, step, slot=step % 2).cpu().item())
+        b.apply_update()
+        assert la == lb, (step, la, lb)
+    a.check()
+    b.check()
+    pa, pb, ma, mb = a.get_params(), b.get_params(), a.get_momentum(), b.get_momentum()
+    for k in pa:
+        assert np.array_equal(pa[k], pb[k]), k
+        assert np.array_equal(ma[k], mb[k]), k
+    assert any(np.abs(v).max() > 0 for v in ma.values())
+    a.close()
+    b.close()
 
 
 def test_mini_three_steps_with_direct_3x3_stages(lib):
