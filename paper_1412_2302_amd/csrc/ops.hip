@@ -76,48 +76,44 @@ int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* o
   return ALEXNET_OK;
 }
 
-// out[n][y][x][c] = raw[n][c][oy+y][ox + (flip ? CW-1-x : x)] - mean[c][same place]; a lane makes four
-// consecutive floats of the flat output (16-byte stores), each from its own source byte.
-struct PreprocessDivs {
-  FastDiv c, chw, cw;  // channels, crop_h*crop_w, crop_w
-};
-__global__ void __launch_bounds__(256)
+// out[n][y][x][c] = raw[n][c][oy+y][ox + (flip ? CW-1-x : x)] - mean[c][same place].  A wave owns one output
+// row (n, y): picture, source row, crop offset and mirror flag are the same for all its lanes, a lane's work per
+// element is one division by C, and the wave's stores are consecutive floats of the flat output.
+constexpr int kPreRows = 4;  // rows (waves) per workgroup
+__global__ void __launch_bounds__(64 * kPreRows)
 preprocess_kernel(const uint8_t* __restrict__ raw, const float* __restrict__ mean, const int32_t* __restrict__ ox,
-                  const int32_t* __restrict__ oy, const int32_t* __restrict__ flip, uint32_t total, int C, int RH,
-                  int RW, int CH, int CW, PreprocessDivs d, float* __restrict__ out) {
-  const uint32_t e0 = (blockIdx.x * blockDim.x + threadIdx.x) * 4u;
-  if (e0 >= total) return;
+                  const int32_t* __restrict__ oy, const int32_t* __restrict__ flip, uint32_t rows, int C, int RH,
+                  int RW, int CH, int CW, FastDiv div_c, FastDiv div_ch, float* __restrict__ out) {
+  const uint32_t row = blockIdx.x * kPreRows + (threadIdx.x >> 6);  // n*CH + y, the same for the whole wave
+  if (row >= rows) return;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t n = fdiv(row, div_ch), y = row - n * (uint32_t)CH;
   const uint32_t plane = (uint32_t)(RH * RW);
-  float v[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t e = min(e0 + j, total - 1);  // a lane past the end repeats the last element and drops it below
-    const uint32_t p = fdiv(e, d.c), c = e - p * (uint32_t)C;
-    const uint32_t n = fdiv(p, d.chw), rem = p - n * (uint32_t)(CH * CW);
-    const uint32_t y = fdiv(rem, d.cw), x = rem - y * (uint32_t)CW;
-    const uint32_t sx = (uint32_t)ox[n] + (flip[n] ? (uint32_t)CW - 1u - x : x);
-    const uint32_t sy = (uint32_t)oy[n] + y;
-    const uint32_t src = sy * (uint32_t)RW + sx;
-    v[j] = (float)raw[((size_t)n * C + c) * plane + src] - mean[(size_t)c * plane + src];
-  }
-  if (e0 + 4 <= total) {
-    *reinterpret_cast<float4*>(out + e0) = make_float4(v[0], v[1], v[2], v[3]);
-  } else {
-    for (uint32_t j = 0; e0 + j < total; ++j) out[e0 + j] = v[j];
+  const int32_t x0 = ox[n], mirror = flip[n];
+  const uint32_t src_row = ((uint32_t)oy[n] + y) * (uint32_t)RW;
+  const uint8_t* rp = raw + (size_t)n * C * plane + src_row;
+  const float* mp = mean + src_row;
+  const uint32_t len = (uint32_t)(CW * C);
+  float* op = out + (size_t)row * len;
+#pragma unroll 4
+  for (uint32_t e = lane; e < len; e += 64) {
+    const uint32_t x = fdiv(e, div_c), c = e - x * (uint32_t)C;
+    const uint32_t src = c * plane + (uint32_t)x0 + (mirror ? (uint32_t)CW - 1u - x : x);
+    op[e] = (float)rp[src] - mp[src];
   }
 }
 int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, const int32_t* oy,
                       const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st) {
   const size_t total = (size_t)B * CH * CW * C;
   if (!total) return ALEXNET_OK;
-  if (total >= 0x7fffffffu) {
-    set_error("preprocess: more than 2^31 output elements");
+  if (total >= 0x7fffffffu || (size_t)C * RH * RW >= 0x7fffffffu) {
+    set_error("preprocess: more than 2^31 elements");
     return ALEXNET_ESHAPE;
   }
   KernelScope ks("preprocess", 0, (double)total * 5.0, st);
-  const PreprocessDivs d{make_fastdiv((uint32_t)C), make_fastdiv((uint32_t)(CH * CW)), make_fastdiv((uint32_t)CW)};
-  hipLaunchKernelGGL(preprocess_kernel, dim3(grid_for(ceil_div(total, 4), 256)), dim3(256), 0, st, raw, mean, ox, oy,
-                     flip, (uint32_t)total, C, RH, RW, CH, CW, d, out);
+  const uint32_t rows = (uint32_t)B * (uint32_t)CH;
+  hipLaunchKernelGGL(preprocess_kernel, dim3(ceil_div(rows, kPreRows)), dim3(64 * kPreRows), 0, st, raw, mean, ox, oy,
+                     flip, rows, C, RH, RW, CH, CW, make_fastdiv((uint32_t)C), make_fastdiv((uint32_t)CH), out);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
