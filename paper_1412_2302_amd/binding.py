@@ -168,6 +168,22 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else _vp(t.data_ptr())
 
 
+def _need(t, dtype, numel: int, what: str) -> torch.Tensor:
+    """The library takes bare device pointers: a tensor of the wrong kind, place or size would be read past its
+    end on the GPU, so it is refused here."""
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{what}: expected a torch.Tensor, got {type(t).__name__}")
+    if not t.is_cuda:
+        raise ValueError(f"{what}: expected a device tensor, got one on {t.device}")
+    if t.dtype != dtype:
+        raise ValueError(f"{what}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: expected a contiguous tensor")
+    if t.numel() < numel:
+        raise ValueError(f"{what}: expected at least {numel} elements, got {t.numel()}")
+    return t
+
+
 def _stream(stream: Optional[torch.cuda.Stream]):
     s = stream if stream is not None else torch.cuda.current_stream()
     return _vp(s.cuda_stream)
@@ -263,25 +279,40 @@ class AlexNet:
     def get_grads(self): return self._get(_lib.alexnet_get_grads)
 
     # ---- the hot path ----
+    def _raw_elems(self) -> int:
+        return self.workload["in_c"] * self.workload["raw"] * self.workload["raw"]
+
+    def _input_elems(self) -> int:
+        return self.batch * self.workload["in_c"] * self.workload["crop"] * self.workload["crop"]
+
     def preprocess(self, raw_u8: torch.Tensor, mean: torch.Tensor, step: int, slot: int, stream=None):
+        _need(raw_u8, torch.uint8, self.batch * self._raw_elems(), "preprocess: stored pictures")
+        _need(mean, torch.float32, self._raw_elems(), "preprocess: mean image")
         _check(_lib.alexnet_preprocess(self._h, _ptr(raw_u8), _ptr(mean), step, slot, _stream(stream)))
 
     def preprocess_center(self, raw_u8: torch.Tensor, mean: torch.Tensor, slot: int, stream=None):
+        _need(raw_u8, torch.uint8, self.batch * self._raw_elems(), "preprocess_center: stored pictures")
+        _need(mean, torch.float32, self._raw_elems(), "preprocess_center: mean image")
         _check(_lib.alexnet_preprocess_center(self._h, _ptr(raw_u8), _ptr(mean), slot, _stream(stream)))
 
     def validate(self, labels: torch.Tensor, ks, counts: torch.Tensor, slot: int = 0, stream=None):
         """counts (int32, device, one per k) += pictures of input slot `slot` whose label is in the top k."""
+        _need(labels, torch.int32, self.batch, "validate: labels")
+        _need(counts, torch.int32, len(ks), "validate: counts")
         arr = (_i32 * len(ks))(*ks)
         _check(_lib.alexnet_validate(self._h, slot, _ptr(labels), arr, len(ks), _ptr(counts), _stream(stream)))
 
     def set_input(self, x_nchw: torch.Tensor, slot: int = 0, stream=None):
+        _need(x_nchw, torch.float32, self._input_elems(), "set_input: input")
         _check(_lib.alexnet_set_input(self._h, _ptr(x_nchw), slot, _stream(stream)))
 
     def train_step(self, labels: torch.Tensor, step: int, slot: int = 0, stream=None) -> torch.Tensor:
+        _need(labels, torch.int32, self.batch, "train_step: labels")
         _check(_lib.alexnet_train_step(self._h, slot, _ptr(labels), step, _ptr(self.loss), _stream(stream)))
         return self.loss
 
     def forward_backward(self, labels: torch.Tensor, step: int, slot: int = 0, stream=None) -> torch.Tensor:
+        _need(labels, torch.int32, self.batch, "forward_backward: labels")
         _check(_lib.alexnet_forward_backward(self._h, slot, _ptr(labels), step, _ptr(self.loss), _stream(stream)))
         return self.loss
 
@@ -289,6 +320,7 @@ class AlexNet:
         _check(_lib.alexnet_apply_update(self._h, _stream(stream)))
 
     def forward(self, x_nchw: torch.Tensor, stream=None) -> torch.Tensor:
+        _need(x_nchw, torch.float32, self._input_elems(), "forward: input")
         probs = torch.empty(self.batch, self.workload["fc"][-1], dtype=torch.float32, device="cuda")
         _check(_lib.alexnet_forward(self._h, _ptr(x_nchw), _ptr(probs), _stream(stream)))
         return probs
@@ -337,13 +369,44 @@ class AlexNet:
         _check(_lib.alexnet_unpack_conv_weight(self._h, layer, _ptr(wf), _ptr(w), _stream(None)))
         return w.view(*w_shape)
 
+    def _conv_elems(self, layer: int) -> Tuple[int, int, int, int]:
+        """Elements of a convolution stage's input, output, weights and bias (the geometry rule of the library:
+        out = (in + 2 pad - k) / stride + 1, 3x3 stride-2 pooling behind the stages that pool)."""
+        if not 1 <= layer <= len(self.workload["conv"]):
+            raise ValueError(f"layer must be 1..{len(self.workload['conv'])}")
+        c, h = self.workload["in_c"], self.workload["crop"]
+        for i, (cout, k, stride, pad, groups, _lrn, pool) in enumerate(self.workload["conv"], start=1):
+            ho = (h + 2 * pad - k) // stride + 1
+            if i == layer:
+                return self.batch * h * h * c, self.batch * ho * ho * cout, cout * (c // groups) * k * k, cout
+            c, h = cout, ((ho - 3) // 2 + 1 if pool else ho)
+        raise AssertionError
+
     def conv_forward_nhwc(self, layer, x, wf, b, relu, y, stream=None):
+        nx, ny, nw, nb = self._conv_elems(layer)
+        _need(x, torch.float32, nx, "conv_forward_nhwc: x")
+        _need(wf, torch.float32, nw, "conv_forward_nhwc: wf")
+        _need(y, torch.float32, ny, "conv_forward_nhwc: y")
+        if b is not None:
+            _need(b, torch.float32, nb, "conv_forward_nhwc: bias")
         _check(_lib.alexnet_conv_forward_nhwc(self._h, layer, _ptr(x), _ptr(wf), _ptr(b), int(relu), _ptr(y), _stream(stream)))
 
     def conv_backward_data_nhwc(self, layer, dy, wb, dx, wf=None, stream=None):
+        nx, ny, nw, _ = self._conv_elems(layer)
+        _need(dy, torch.float32, ny, "conv_backward_data_nhwc: dy")
+        _need(wb, torch.float32, nw, "conv_backward_data_nhwc: wb")
+        _need(dx, torch.float32, nx, "conv_backward_data_nhwc: dx")
+        if wf is not None:
+            _need(wf, torch.float32, nw, "conv_backward_data_nhwc: wf")
         _check(_lib.alexnet_conv_backward_data_nhwc(self._h, layer, _ptr(dy), _ptr(wf), _ptr(wb), _ptr(dx), _stream(stream)))
 
     def conv_backward_weight_nhwc(self, layer, x, dy, dwf, db, stream=None):
+        nx, ny, nw, nb = self._conv_elems(layer)
+        _need(x, torch.float32, nx, "conv_backward_weight_nhwc: x")
+        _need(dy, torch.float32, ny, "conv_backward_weight_nhwc: dy")
+        _need(dwf, torch.float32, nw, "conv_backward_weight_nhwc: dwf")
+        if db is not None:
+            _need(db, torch.float32, nb, "conv_backward_weight_nhwc: db")
         _check(_lib.alexnet_conv_backward_weight_nhwc(self._h, layer, _ptr(x), _ptr(dy), _ptr(dwf), _ptr(db), _stream(stream)))
 
 
@@ -408,7 +471,14 @@ class Loader:
     def __init__(self, net: AlexNet, images: torch.Tensor, labels: torch.Tensor, depth: int = 2, copy_stream=None):
         """copy_stream: the stream of the host-to-device copies (best the side stream later given to stage());
         None lets the library create one."""
-        assert images.dtype == torch.uint8 and labels.dtype == torch.int32 and not images.is_cuda
+        want = (net.workload["in_c"], net.workload["raw"], net.workload["raw"])
+        if images.dtype != torch.uint8 or images.is_cuda or images.dim() != 4 or tuple(images.shape[1:]) != want:
+            raise ValueError(f"Loader: images must be a CPU uint8 tensor [count]{list(want)}, got "
+                             f"{images.dtype} {list(images.shape)} on {images.device}")
+        if labels.dtype != torch.int32 or labels.is_cuda or labels.numel() != images.shape[0]:
+            raise ValueError("Loader: labels must be a CPU int32 tensor with one entry per picture")
+        if depth < 1 or images.shape[0] < 1:
+            raise ValueError("Loader: need at least one staging set and one picture")
         self.net, self.images, self.labels = net, images.contiguous(), labels.contiguous()
         per = net.batch * int(np.prod(images.shape[1:]))
         self.pinned_raw = torch.empty(depth * per, dtype=torch.uint8, pin_memory=True)
@@ -426,6 +496,7 @@ class Loader:
 
     def stage(self, k: int, mean: torch.Tensor, side_stream, compute_stream) -> torch.Tensor:
         """Returns the labels of minibatch k (a view of the loader's device buffer)."""
+        _need(mean, torch.float32, self.net._raw_elems(), "Loader.stage: mean image")
         p = _vp()
         _check(_lib.alexnet_loader_stage(self._h, k, _ptr(mean), _stream(side_stream), _stream(compute_stream),
                                          C.byref(p)))

@@ -274,3 +274,24 @@ def test_out_of_range_label_is_reported(lib):
     assert e.value.code == lib.ELABEL
     net.check()  # flag is cleared once reported
     net.close()
+
+
+def test_binding_refuses_wrong_tensors_before_the_library_sees_them(lib):
+    net = lib.AlexNet(S.MIDI, 4)
+    good_raw = torch.zeros(4, 3, 80, 80, dtype=torch.uint8, device="cuda")
+    mean = torch.zeros(3, 80, 80, dtype=torch.float32, device="cuda")
+    net.preprocess(good_raw, mean, 0, 0)
+    with pytest.raises(ValueError, match="at least"):
+        net.preprocess(good_raw[:3], mean, 0, 0)                       # one picture short
+    with pytest.raises(ValueError, match="uint8"):
+        net.preprocess(good_raw.float(), mean, 0, 0)
+    with pytest.raises(ValueError, match="device"):
+        net.preprocess(good_raw.cpu(), mean, 0, 0)
+    with pytest.raises(ValueError, match="contiguous"):
+        net.preprocess(good_raw.permute(0, 1, 3, 2), mean, 0, 0)
+    with pytest.raises(ValueError, match="int32"):
+        net.train_step(torch.zeros(4, dtype=torch.int64, device="cuda"), 0)
+    with pytest.raises(ValueError, match="at least"):
+        net.set_input(torch.zeros(4, 3, 66, 67, device="cuda"))
+    net.check()
+    net.close()

@@ -83,3 +83,30 @@ def test_bad_arguments_are_reported_not_crashed(B):
     rc = B._lib.alexnet_create(C.byref(cfg), C.c_void_p(0x1001), C.c_void_p(0x2000), C.c_void_p(0x3000), 1 << 30,
                                None, C.byref(h))
     assert rc == B.EALIGN
+
+
+def test_binding_refuses_tensors_the_library_would_read_past(B):
+    """The binding hands bare pointers to the library, so it checks place, type, layout and size first.  The
+    checks run before any library call: a stand-in object with the fields they read is enough here."""
+    import torch
+
+    need = B._need
+    with pytest.raises(TypeError):
+        need([1, 2, 3], torch.int32, 3, "labels")
+    with pytest.raises(ValueError, match="device tensor"):
+        need(torch.zeros(4, dtype=torch.int32), torch.int32, 4, "labels")  # a host tensor
+
+    class Net:  # geometry helpers of AlexNet without creating a handle
+        workload, batch = S.MIDI, 5
+        _conv_elems = B.AlexNet._conv_elems
+        _raw_elems = B.AlexNet._raw_elems
+        _input_elems = B.AlexNet._input_elems
+
+    n = Net()
+    assert n._raw_elems() == 3 * 80 * 80 and n._input_elems() == 5 * 3 * 67 * 67
+    # midi: 67 -> conv1(11, s4) 15 -> pool 7 -> conv2(5, p2, g2) 7 -> pool 3 -> conv3 3
+    assert n._conv_elems(1) == (5 * 67 * 67 * 3, 5 * 15 * 15 * 24, 24 * 3 * 121, 24)
+    assert n._conv_elems(2) == (5 * 7 * 7 * 24, 5 * 7 * 7 * 40, 40 * 12 * 25, 40)
+    assert n._conv_elems(3) == (5 * 3 * 3 * 40, 5 * 3 * 3 * 72, 72 * 40 * 9, 72)
+    with pytest.raises(ValueError):
+        n._conv_elems(6)
