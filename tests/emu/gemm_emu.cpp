@@ -715,6 +715,7 @@ int main() {
       {geom(3, 6, 32, 96, 5, 1, 2, 1), "k5p2c32"},       // 25 taps, ragged rows and columns
       {geom(4, 7, 8, 24, 3, 1, 1, 2), "k3p1g2px224"},    // 4*7*8 = 224 pixels: whole k-tiles for backward-weight
       {geom(4, 15, 3, 8, 5, 2, 0, 1), "k5s2c3px192"},    // run mode with 4*6*8 = 192 output pixels
+      {geom(4, 10, 2, 8, 3, 1, 0, 1), "k3c2px256"},      // run mode with a run of 6 floats (padded to 8)
       {geom(2, 9, 3, 6, 5, 2, 1, 1), "k5s2p1c3o6"},      // channel counts that are no multiples of four:
       {geom(2, 7, 6, 10, 3, 1, 1, 2), "k3g2c3o5"},       // every operand falls back to 4-byte loads
       {geom(2, 3, 10, 9, 3, 1, 1, 1), "k3c10o9"},
