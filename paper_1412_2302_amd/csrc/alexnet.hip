@@ -241,7 +241,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     n->crop_y[s] = a.take<int32_t>(c.batch);
     n->flip[s] = a.take<int32_t>(c.batch);
   }
-  size_t max_in = in_elems, max_out = 0, max_w = 0, gws = 0, cws = 0, wscr = 0, wdu = 0;
+  size_t max_in = in_elems, max_out = 0, max_w = 0, gws = 0, cws = 0, cws_batch = 0, wscr = 0, wdu = 0;
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
     const size_t ae = s.act_elems(), oe = s.out_elems();
@@ -275,6 +275,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     gws = std::max(gws, conv_fwd_ws_floats(s.g));
     gws = std::max(gws, conv_bwd_data_ws_floats(s.g));
     cws = std::max(cws, colsum_ws_floats(s.g.P(), s.g.Cout));
+    cws_batch += colsum_batch_ws_floats(s.g.P(), s.g.Cout);
     if (s.lrn && s.pool) cws = std::max(cws, lrn_part_floats(s.g.Cout));
   }
   {
@@ -304,6 +305,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     f.dz = a.take<float>((size_t)c.batch * f.out);
     gws = std::max(gws, fc_ws_floats(c.batch, f.in, f.out));
     cws = std::max(cws, colsum_ws_floats(c.batch, f.out));
+    cws_batch += colsum_batch_ws_floats(c.batch, f.out);
   }
   n->grads = a.take<float>(n->n_params);
   n->wino_a = wscr ? a.take<float>(wscr) : nullptr;
@@ -311,6 +313,7 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
   n->wino_du = wdu ? a.take<float>(wdu) : nullptr;
   n->gemm_ws = a.take<float>(gws);
   n->gemm_ws_floats = gws;
+  cws = std::max(cws, cws_batch);  // the backward pass sums all its bias gradients in one batch
   n->colsum_ws = a.take<float>(cws);
   n->colsum_ws_floats_ = cws;
   n->row_loss = a.take<float>(c.batch);
@@ -438,6 +441,11 @@ static int update_range(alexnet* n, size_t begin, size_t end, hipStream_t st) {
 static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_update = false) {
   const alexnet_config_t& c = n->cfg;
   set_gemm_precision(c.precision);
+  // Bias gradients (column sums of every layer's output gradient) not made by a fused kernel on the way are
+  // collected and summed in two launches at the end: those tensors all outlive the pass, and eight small
+  // reductions of their own cost more in launches than in work.
+  ColsumBatch bias_sums;
+  size_t bias_ws_used = 0;
   // dense layers, last to first
   for (int j = kFc - 1; j >= 0; --j) {
     Dense& f = n->fc[j];
@@ -445,7 +453,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     {
       ProfContext pc(f.lab[2]);
       AX_TRY(launch_fc_bwd_weight(c.batch, f.in, f.out, x, f.dz, n->grads + f.w_off, st));
-      AX_TRY(launch_colsum(f.dz, c.batch, f.out, n->grads + f.b_off, n->colsum_ws, st));
+      AX_TRY(colsum_batch_add(bias_sums, f.dz, c.batch, f.out, n->grads + f.b_off, n->colsum_ws, &bias_ws_used));
     }
     ProfContext pc(f.lab[3]);
     if (j > 0) {
@@ -490,7 +498,8 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     {
       ProfContext pc(s.lab[2]);
       AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st));
-      if (!bias_done) AX_TRY(launch_colsum(s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, st));
+      if (!bias_done)
+        AX_TRY(colsum_batch_add(bias_sums, s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, &bias_ws_used));
     }
     if (fork_here && n->upd_fork_before_bx) AX_TRY(fork_update());
     if (i > 0) {
@@ -505,7 +514,12 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
                             prev.d_out, early_update, true, st));
     }
   }
-  return ALEXNET_OK;
+  if (bias_ws_used > n->colsum_ws_floats_) {
+    set_error("bias gradients: %zu floats of partial sums in a workspace of %zu", bias_ws_used, n->colsum_ws_floats_);
+    return ALEXNET_EINVAL;
+  }
+  ProfContext pcb("bias_grads");
+  return launch_colsum_batch(bias_sums, st);
 }
 
 static int fwd_bwd(alexnet* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss, hipStream_t st,

@@ -112,6 +112,23 @@ int launch_softmax_xent(const float* z, const int32_t* labels, int B, int classe
 int launch_mean_loss(const float* row_loss, int B, float* loss, hipStream_t st);
 int launch_colsum(const float* m, long rows, int cols, float* out, float* ws, hipStream_t st);
 size_t colsum_ws_floats(long rows, int cols);
+// Several column sums in two launches: add the jobs (each takes its partial sums from ws at *ws_used and moves
+// that on by colsum_batch_ws_floats(rows, cols)), then launch; every input must still hold its values then.
+constexpr int kMaxColsumJobs = 8;
+struct ColsumJob {
+  const float* m;
+  float *part, *out;
+  long rows;
+  int cols, rpb, nparts;
+};
+struct ColsumBatch {
+  ColsumJob job[kMaxColsumJobs];
+  int first1[kMaxColsumJobs], first2[kMaxColsumJobs];  // first workgroup of each job in the two launches
+  int n = 0, blocks1 = 0, blocks2 = 0;
+};
+int colsum_batch_add(ColsumBatch& b, const float* m, long rows, int cols, float* out, float* ws, size_t* ws_used);
+size_t colsum_batch_ws_floats(long rows, int cols);
+int launch_colsum_batch(const ColsumBatch& b, hipStream_t st);
 int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, float* out, hipStream_t st);
 int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
                       hipStream_t st);

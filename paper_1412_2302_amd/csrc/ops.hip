@@ -828,12 +828,12 @@ int launch_mean_loss(const float* row_loss, int B, float* loss, hipStream_t st) 
 // 16 column quads (16-byte loads when VEC), then a fixed-order LDS reduction.
 // rpb is chosen by the launcher so that the grid has about a thousand workgroups.
 template <bool VEC>
-__global__ void __launch_bounds__(256)
-colsum_stage1(const float* __restrict__ m, long rows, int cols, int rpb, float* __restrict__ part) {
+__device__ __forceinline__ void colsum_stage1_block(const float* __restrict__ m, long rows, int cols, int rpb,
+                                                    float* __restrict__ part, int stripe, int chunk) {
   __shared__ float sh[16][65];
   const int cq = threadIdx.x & 15, rl = threadIdx.x >> 4;
-  const int col = blockIdx.x * 64 + cq * 4;
-  const long r0 = (long)blockIdx.y * rpb;
+  const int col = stripe * 64 + cq * 4;
+  const long r0 = (long)chunk * rpb;
   const long r1 = min(rows, r0 + rpb);
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (VEC) {
@@ -861,24 +861,56 @@ colsum_stage1(const float* __restrict__ m, long rows, int cols, int rpb, float* 
   sh[rl][cq * 4 + 3] = s.w;
   __syncthreads();
   if (threadIdx.x < 64) {
-    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int c = stripe * 64 + threadIdx.x;
     float t = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) t += sh[r][threadIdx.x];
-    if (c < cols) part[(size_t)blockIdx.y * cols + c] = t;
+    if (c < cols) part[(size_t)chunk * cols + c] = t;
   }
 }
+template <bool VEC>
 __global__ void __launch_bounds__(256)
-colsum_stage2(const float* __restrict__ part, int nparts, int cols, float* __restrict__ out) {
+colsum_stage1(const float* __restrict__ m, long rows, int cols, int rpb, float* __restrict__ part) {
+  colsum_stage1_block<VEC>(m, rows, cols, rpb, part, blockIdx.x, blockIdx.y);
+}
+__device__ __forceinline__ void colsum_stage2_block(const float* __restrict__ part, int nparts, int cols,
+                                                    float* __restrict__ out, int stripe) {
   __shared__ float sh[4][64];
   const int cl = threadIdx.x & 63, pl = threadIdx.x >> 6;
-  const int col = blockIdx.x * 64 + cl;
+  const int col = stripe * 64 + cl;
   float s = 0.f;
   if (col < cols)
     for (int p = pl; p < nparts; p += 4) s += part[(size_t)p * cols + col];
   sh[pl][cl] = s;
   __syncthreads();
   if (pl == 0 && col < cols) out[col] = (sh[0][cl] + sh[1][cl]) + (sh[2][cl] + sh[3][cl]);
+}
+__global__ void __launch_bounds__(256)
+colsum_stage2(const float* __restrict__ part, int nparts, int cols, float* __restrict__ out) {
+  colsum_stage2_block(part, nparts, cols, out, blockIdx.x);
+}
+// Several column sums in two launches (the bias gradients of a backward pass, whose inputs all still exist at
+// its end).  The jobs' grids are laid end to end: a workgroup finds its job from the running totals (first1,
+// first2) and its place in that job's own grid.  Same arithmetic and order per job as colsum_stage1 +
+// colsum_stage2.
+__device__ __forceinline__ int colsum_job_of(const int* first, int n, int block) {
+  int j = 0;
+#pragma unroll
+  for (int k = 1; k < kMaxColsumJobs; ++k)
+    if (k < n && block >= first[k]) j = k;
+  return j;
+}
+template <bool VEC>
+__global__ void __launch_bounds__(256) colsum_batch_stage1(ColsumBatch b) {
+  const int ji = colsum_job_of(b.first1, b.n, blockIdx.x);
+  const ColsumJob& j = b.job[ji];
+  const int local = blockIdx.x - b.first1[ji], stripes = (j.cols + 63) / 64;
+  colsum_stage1_block<VEC>(j.m, j.rows, j.cols, j.rpb, j.part, local % stripes, local / stripes);
+}
+__global__ void __launch_bounds__(256) colsum_batch_stage2(ColsumBatch b) {
+  const int ji = colsum_job_of(b.first2, b.n, blockIdx.x);
+  const ColsumJob& j = b.job[ji];
+  colsum_stage2_block(j.part, j.nparts, j.cols, j.out, blockIdx.x - b.first2[ji]);
 }
 // rows per workgroup: enough row chunks for ~1024 workgroups, at least 64 rows each
 static int colsum_rows_per_block(long rows, int cols) {
@@ -906,6 +938,45 @@ int launch_colsum(const float* m, long rows, int cols, float* out, float* ws, hi
     hipLaunchKernelGGL(colsum_finish_kernel, dim3(cols / 4), dim3(256), 0, st, ws, nparts, cols, out);
   else
     hipLaunchKernelGGL(colsum_stage2, dim3(ceil_div(cols, 64)), dim3(256), 0, st, ws, nparts, cols, out);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+int colsum_batch_add(ColsumBatch& b, const float* m, long rows, int cols, float* out, float* ws, size_t* ws_used) {
+  if (b.n >= kMaxColsumJobs) {
+    set_error("colsum batch: more than %d jobs", kMaxColsumJobs);
+    return ALEXNET_EINVAL;
+  }
+  ColsumJob& j = b.job[b.n++];
+  j.m = m; j.rows = rows; j.cols = cols; j.out = out;
+  j.rpb = colsum_rows_per_block(rows, cols);
+  j.nparts = ceil_div(rows, j.rpb);
+  j.part = ws + *ws_used;
+  *ws_used += ((size_t)j.nparts * cols + 3) / 4 * 4;  // every job's partials start on a 16-byte boundary
+  const int stripes = ceil_div(cols, 64), k = b.n - 1;
+  b.first1[k] = k ? b.first1[k - 1] + ceil_div(b.job[k - 1].cols, 64) * b.job[k - 1].nparts : 0;
+  b.first2[k] = k ? b.first2[k - 1] + ceil_div(b.job[k - 1].cols, 64) : 0;
+  b.blocks1 = b.first1[k] + stripes * j.nparts;
+  b.blocks2 = b.first2[k] + stripes;
+  return ALEXNET_OK;
+}
+size_t colsum_batch_ws_floats(long rows, int cols) { return (colsum_ws_floats(rows, cols) + 3) / 4 * 4; }
+int launch_colsum_batch(const ColsumBatch& b, hipStream_t st) {
+  if (b.n == 0) return ALEXNET_OK;
+  bool vec = true;
+  double bytes = 0;
+  for (int i = 0; i < b.n; ++i) {
+    const ColsumJob& j = b.job[i];
+    vec = vec && j.cols % 4 == 0 && aligned16(j.m);
+    bytes += (double)j.rows * j.cols * 4.0;
+  }
+  KernelScope ks("colsum", 0, bytes, st);
+  if (vec)
+    hipLaunchKernelGGL((colsum_batch_stage1<true>), dim3(b.blocks1), dim3(256), 0, st, b);
+  else
+    hipLaunchKernelGGL((colsum_batch_stage1<false>), dim3(b.blocks1), dim3(256), 0, st, b);
+  AX_LAUNCH_CHECK();
+  hipLaunchKernelGGL(colsum_batch_stage2, dim3(b.blocks2), dim3(256), 0, st, b);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
