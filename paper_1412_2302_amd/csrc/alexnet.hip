@@ -78,6 +78,7 @@ struct Stage {
   int Hp, Wp;           // stage output size (after the pool when present)
   size_t w_off, b_off;  // offsets into the flat parameter vector
   float *act, *lrn_out, *pool_out, *dact, *d_lrn, *d_out, *wb;
+  float *wino_du, *wino_slices;  // weight-gradient products and their split-k slices (transformed stages)
   float* wphase;        // weights regrouped by phase for a strided backward-data pass (null when not used)
   // 3x3 unit-stride stages run through the F(4x4, 3x3) transforms: the transformed input of the forward pass
   // (kept for the weight gradient) and the transformed taps of the forward and backward-data passes
@@ -263,6 +264,9 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.wino_v = s.wino ? a.take<float>(wino_v_floats(s.g)) : nullptr;
     s.wino_u = s.wino ? a.take<float>(wino_u_floats(s.g)) : nullptr;
     s.wino_ub = s.wino_bx ? a.take<float>(wino_u_floats(s.g)) : nullptr;
+    // the products of the weight gradient and their split-k slices, kept until the end of the backward pass
+    s.wino_du = s.wino ? a.take<float>(wino_u_floats(s.g)) : nullptr;
+    s.wino_slices = s.wino && wino_wgrad_ws_floats(s.g) ? a.take<float>(wino_wgrad_ws_floats(s.g)) : nullptr;
     if (s.wino) {
       wscr = std::max(wscr, wino_scratch_floats(s.g));
       wdu = std::max(wdu, wino_u_floats(s.g));
@@ -353,10 +357,12 @@ static int stage_fwd(alexnet* n, Stage& s, const float* x, const float* wf, cons
   return launch_conv_fwd(s.g, x, wf, s.wrun, bias, relu, y, n->gemm_ws, st);
 }
 // have_v: s.wino_v already holds the transform of x (the forward pass of the same minibatch left it there)
+// tail: put the end of a transformed stage's weight gradient off to launch_wgrad_tail() (see WgradTail)
 static int stage_bwd_weight(alexnet* n, Stage& s, const float* x, const float* dy, float* dwf, bool have_v,
-                            hipStream_t st) {
+                            hipStream_t st, WgradTail* tail = nullptr) {
   if (wino_usable(s, x, dy, dwf)) {
     if (!have_v) AX_TRY(launch_wino_input(s.g, x, s.wino_v, st));
+    if (tail) return launch_wino_bwd_weight(s.g, s.wino_v, dy, dwf, n->wino_a, s.wino_du, s.wino_slices, st, tail);
     return launch_wino_bwd_weight(s.g, s.wino_v, dy, dwf, n->wino_a, n->wino_du, n->gemm_ws, st);
   }
   return launch_conv_bwd_weight(s.g, x, dy, dwf, s.dwrun, n->gemm_ws, st);
@@ -446,6 +452,8 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
   // reductions of their own cost more in launches than in work.
   ColsumBatch bias_sums;
   size_t bias_ws_used = 0;
+  // Likewise the end of every transformed stage's weight gradient (slices added up, products back to taps).
+  WgradTail wgrad_tail;
   // dense layers, last to first
   for (int j = kFc - 1; j >= 0; --j) {
     Dense& f = n->fc[j];
@@ -497,7 +505,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
-      AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st));
+      AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st, &wgrad_tail));
       if (!bias_done)
         AX_TRY(colsum_batch_add(bias_sums, s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, &bias_ws_used));
     }
@@ -517,6 +525,10 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
   if (bias_ws_used > n->colsum_ws_floats_) {
     set_error("bias gradients: %zu floats of partial sums in a workspace of %zu", bias_ws_used, n->colsum_ws_floats_);
     return ALEXNET_EINVAL;
+  }
+  {
+    ProfContext pct("wgrad_tail");
+    AX_TRY(launch_wgrad_tail(wgrad_tail, st));
   }
   ProfContext pcb("bias_grads");
   return launch_colsum_batch(bias_sums, st);

@@ -440,8 +440,10 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
   return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, nullptr, 0, gate, dx, st);
 }
 
+// defer_ns (generic layout only): the split-k slices are left in ws, [group][slice][slab], and their number is
+// returned there for the caller to add them up later (1: the result is in dwf already)
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
-                           hipStream_t st) {
+                           hipStream_t st, int* defer_ns) {
   const bool run = dwrun && run_mode(c) && bwdw_B_vec(c, dy);
   AlgoFlops af(conv_flops(c));
   GemmDims d = bwdw_dims(c);
@@ -466,6 +468,11 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
     AX_TRY((by_tile_tap<ConvWeightGradTable>(p, a, bwdw_B(c, dy), ep, d, st)));
   else
     AX_TRY((by_tile<ConvWeightGrad>(p, av, bv, a, bwdw_B(c, dy), ep, d, st)));
+  if (defer_ns && !run) {
+    *defer_ns = p.ns;
+    return ALEXNET_OK;
+  }
+  if (defer_ns) *defer_ns = 1;
   if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, out, st));
   if (run) AX_TRY(launch_conv_run_unpack(c, dwrun, dwf, st));
   return ALEXNET_OK;

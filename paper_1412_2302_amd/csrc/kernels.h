@@ -7,6 +7,29 @@
 
 namespace ax {
 
+// The tail of the weight gradient of a transformed stage -- adding up the split-k slices of the products, then
+// the transform back to taps -- can be put off to the end of a backward pass and run for all such stages in two
+// launches: each of those kernels is too short to fill the chip on its own.  The slices and the products then
+// need memory of their own until the tail runs.
+constexpr int kMaxWgradJobs = 5;
+struct WgradJob {
+  const float* slices;  // [groups36][nsplit][slab]; unused when nsplit == 1 (the products are in dU already)
+  float* dU;            // [groups36][slab]
+  float* dwf;
+  long slab, total;     // floats per product group; threads of the transform back
+  int nsplit, groups36, groups, Na, Nb, k, nsub;
+  int vec;              // set by wgrad_tail_add: the slices are added 16 bytes at a time
+};
+struct WgradTail {
+  WgradJob job[kMaxWgradJobs];
+  int first_r[kMaxWgradJobs], first_t[kMaxWgradJobs];  // first workgroup of each job in the two launches
+  int n = 0, blocks_r = 0, blocks_t = 0;
+};
+void wgrad_tail_add(WgradTail& t, const WgradJob& job);  // t.n < kMaxWgradJobs
+int launch_reduce_slabs_batch(const WgradTail& t, hipStream_t st);
+int launch_wino_dw_batch(const WgradTail& t, hipStream_t st);
+int launch_wgrad_tail(const WgradTail& t, hipStream_t st);
+
 // ---- convolution as implicit GEMM (conv_gemm.hip) ---------------------------
 // Arithmetic of the GEMMs the calling thread launches from now on: 0 = fp32 MFMA, 1 = operands rounded to
 // bf16 (nearest even) on their way into LDS, products accumulated in fp32.  Operands that cannot be read
@@ -30,7 +53,7 @@ size_t conv_phase_w_floats(const ConvGeom& c);
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, const float* wb, float* wphase,
                          const float* gate, float* dx, float* ws, hipStream_t st);
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
-                           hipStream_t st);
+                           hipStream_t st, int* defer_ns = nullptr);
 
 // ---- 3x3 and 5x5 unit-stride convolutions through F(4x4, 3x3) (winograd.hip) ----
 // All tensors 16-byte aligned, channels per group multiples of 4.  V: wino_v_floats(), U / Ub / dU:
@@ -44,13 +67,14 @@ size_t wino_v_floats(const ConvGeom& c);
 size_t wino_u_floats(const ConvGeom& c);
 size_t wino_scratch_floats(const ConvGeom& c);
 size_t wino_gemm_ws_floats(const ConvGeom& c);
+size_t wino_wgrad_ws_floats(const ConvGeom& c);
 int launch_wino_filter(const ConvGeom& c, const float* wf, float* U, hipStream_t st);
 int launch_wino_filter_bwd(const ConvGeom& c, const float* wb, float* Ub, hipStream_t st);
 int launch_wino_input(const ConvGeom& c, const float* x, float* V, hipStream_t st);
 int launch_wino_fwd(const ConvGeom& c, const float* x, const float* U, const float* bias, int relu, float* y, float* V,
                     float* m, float* ws, hipStream_t st);
 int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
-                           float* ws, hipStream_t st);
+                           float* ws, hipStream_t st, WgradTail* tail = nullptr);
 int launch_wino_output_grad(const ConvGeom& c, const float* dy, float* yt, hipStream_t st);
 // the data gradient starts from the transformed output gradient yt (launch_wino_output_grad, or what
 // launch_wino_bwd_weight left in its `yt`), not from dy

@@ -982,14 +982,14 @@ int launch_colsum_batch(const ColsumBatch& b, hipStream_t st) {
 }
 
 // out[g][i] = sum_s ws[g*nsplit + s][i]  (split-k partial slabs)
-__global__ void __launch_bounds__(256)
-reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int groups, float* __restrict__ out) {
+__device__ __forceinline__ void reduce_slabs_block(const float* __restrict__ ws, int nsplit, size_t slab, int groups,
+                                                   float* __restrict__ out, unsigned block) {
   // 64 consecutive elements per workgroup; four lanes per element take every fourth slab, then add up in a
   // fixed order
   __shared__ float sh[4][64];
   const size_t total = slab * groups;
   const int el = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const size_t i = (size_t)blockIdx.x * 64 + el;
+  const size_t i = (size_t)block * 64 + el;
   float s = 0.f;
   if (i < total) {
     const size_t g = i / slab, e = i - g * slab;
@@ -1001,12 +1001,82 @@ reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int g
   __syncthreads();
   if (part == 0 && i < total) out[i] = (sh[0][el] + sh[1][el]) + (sh[2][el] + sh[3][el]);
 }
+__global__ void __launch_bounds__(256)
+reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int groups, float* __restrict__ out) {
+  reduce_slabs_block(ws, nsplit, slab, groups, out, blockIdx.x);
+}
+// Few slices of a large result (slab a multiple of four floats, 16-byte aligned): a lane owns four consecutive
+// elements and adds its slices in order, 16 bytes per load.
+constexpr int kReduceVecMaxSlices = 16;
+__device__ __forceinline__ void reduce_slabs_vec_block(const float* __restrict__ ws, int nsplit, size_t slab,
+                                                       int groups, float* __restrict__ out, unsigned block) {
+  const size_t i = ((size_t)block * 256 + threadIdx.x) * 4;
+  if (i >= slab * groups) return;
+  const size_t g = i / slab, e = i - g * slab;
+  const float* p = ws + g * nsplit * slab + e;
+  float4 acc = *reinterpret_cast<const float4*>(p);
+#pragma unroll 4
+  for (int k = 1; k < nsplit; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(p + (size_t)k * slab);
+    acc.x += v.x;
+    acc.y += v.y;
+    acc.z += v.z;
+    acc.w += v.w;
+  }
+  *reinterpret_cast<float4*>(out + i) = acc;
+}
+static bool reduce_vec_ok(const float* ws, const float* out, int nsplit, long slab) {
+  return nsplit <= kReduceVecMaxSlices && slab % 4 == 0 && aligned16(ws) && aligned16(out);
+}
+static int reduce_blocks(bool vec, long slab, int groups) {
+  return vec ? ceil_div(slab * groups / 4, 256) : ceil_div(slab * groups, 64);
+}
+__global__ void __launch_bounds__(256)
+reduce_slabs_vec_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int groups, float* __restrict__ out) {
+  reduce_slabs_vec_block(ws, nsplit, slab, groups, out, blockIdx.x);
+}
+// the same for several results in one launch (see WgradTail): the jobs' grids laid end to end
+__global__ void __launch_bounds__(256) reduce_slabs_batch_kernel(WgradTail t) {
+  int ji = 0;
+#pragma unroll
+  for (int k = 1; k < kMaxWgradJobs; ++k)
+    if (k < t.n && (int)blockIdx.x >= t.first_r[k]) ji = k;
+  const WgradJob& j = t.job[ji];
+  if (j.vec)  // uniform over the workgroup
+    reduce_slabs_vec_block(j.slices, j.nsplit, (size_t)j.slab, j.groups36, j.dU, blockIdx.x - t.first_r[ji]);
+  else
+    reduce_slabs_block(j.slices, j.nsplit, (size_t)j.slab, j.groups36, j.dU, blockIdx.x - t.first_r[ji]);
+}
+void wgrad_tail_add(WgradTail& t, const WgradJob& job) {
+  const int k = t.n++;
+  WgradJob& j = t.job[k];
+  j = job;
+  j.vec = reduce_vec_ok(j.slices, j.dU, j.nsplit, j.slab) ? 1 : 0;
+  t.first_r[k] = t.blocks_r;
+  t.first_t[k] = t.blocks_t;
+  if (j.nsplit > 1) t.blocks_r += reduce_blocks(j.vec != 0, j.slab, j.groups36);
+  t.blocks_t += ceil_div(j.total, 256);
+}
+int launch_reduce_slabs_batch(const WgradTail& t, hipStream_t st) {
+  if (t.blocks_r == 0) return ALEXNET_OK;
+  double bytes = 0;
+  for (int i = 0; i < t.n; ++i)
+    if (t.job[i].nsplit > 1) bytes += (double)t.job[i].slab * t.job[i].groups36 * 4.0 * (t.job[i].nsplit + 1);
+  KernelScope ks("reduce_slabs", 0, bytes, st);
+  hipLaunchKernelGGL(reduce_slabs_batch_kernel, dim3(t.blocks_r), dim3(256), 0, st, t);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
 int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, float* out, hipStream_t st) {
   const size_t total = (size_t)slab * groups;
   if (!total) return ALEXNET_OK;
   KernelScope ks("reduce_slabs", 0, (double)total * 4.0 * (nsplit + 1), st);
-  hipLaunchKernelGGL(reduce_slabs_kernel, dim3(grid_for(total, 64)), dim3(256), 0, st, ws, nsplit, (size_t)slab, groups,
-                     out);
+  if (reduce_vec_ok(ws, out, nsplit, slab))
+    hipLaunchKernelGGL(reduce_slabs_vec_kernel, dim3(reduce_blocks(true, slab, groups)), dim3(256), 0, st, ws, nsplit,
+                       (size_t)slab, groups, out);
+  else
+    hipLaunchKernelGGL(reduce_slabs_kernel, dim3(grid_for(total, 64)), dim3(256), 0, st, ws, nsplit, (size_t)slab,
+                       groups, out);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }

@@ -59,6 +59,16 @@ __global__ void __launch_bounds__(256) wino_dw_kernel(int groups, int Na, int Nb
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < total) wino_dw_thread(groups, Na, Nb, k, nsub, dU, dw, idx);
 }
+// the same for several stages in one launch (see WgradTail): the jobs' grids laid end to end
+__global__ void __launch_bounds__(256) wino_dw_batch_kernel(WgradTail t) {
+  int ji = 0;
+#pragma unroll
+  for (int k = 1; k < kMaxWgradJobs; ++k)
+    if (k < t.n && (int)blockIdx.x >= t.first_t[k]) ji = k;
+  const WgradJob& j = t.job[ji];
+  const long idx = (long)(blockIdx.x - t.first_t[ji]) * blockDim.x + threadIdx.x;
+  if (idx < j.total) wino_dw_thread(j.groups, j.Na, j.Nb, j.k, j.nsub, j.dU, j.dwf, idx);
+}
 
 // ---- geometry ----------------------------------------------------------------------------------
 static inline int nsub_of(const ConvGeom& c) { return (c.k + 2) / 3; }
@@ -98,6 +108,11 @@ size_t wino_scratch_floats(const ConvGeom& c) {
   size_t n = 36 * tf * c.Cout;  // forward products, transformed output gradient
   if (wino_bwd_data_ok(c)) n = std::max(n, 36 * tf * nq_of(c) * c.Cin);  // data-gradient products
   return n;
+}
+// split-k slices of the weight-gradient products alone (the part of wino_gemm_ws_floats() that a deferred tail
+// keeps to itself)
+size_t wino_wgrad_ws_floats(const ConvGeom& c) {
+  return conv_bwd_weight_ws_floats(product_geom(fwd_geom(c).tiles(), c.groups, nq_of(c) * c.cg(), c.og()));
 }
 size_t wino_gemm_ws_floats(const ConvGeom& c) {
   const ConvGeom pf = product_geom(fwd_geom(c).tiles(), c.groups, nq_of(c) * c.cg(), c.og());
@@ -187,21 +202,52 @@ int launch_wino_bwd_data(const ConvGeom& c, const float* yt, const float* Ut, co
 }
 
 // dy -> yt, V^T x yt -> dU (36 products over the tiles), dU -> dwf.  V is the forward pass's.
+// With `tail`, the slices of the products stay in ws and their sum and the transform back are left to
+// launch_wgrad_tail(): ws and dU must then be this stage's own until that has run.
 int launch_wino_bwd_weight(const ConvGeom& c, const float* V, const float* dy, float* dwf, float* yt, float* dU,
-                           float* ws, hipStream_t st) {
+                           float* ws, hipStream_t st, WgradTail* tail) {
   const WinoGeom g = fwd_geom(c);
   const int T = g.tiles();
   AX_TRY(launch_wino_output_grad(c, dy, yt, st));
   const ConvGeom p = product_geom(T, c.groups, nq_of(c) * c.cg(), c.og());
+  const long total = (long)c.groups * nq_of(c) * c.cg() * (c.og() / 4);
+  if (tail) {
+    if (tail->n >= kMaxWgradJobs) {
+      set_error("weight-gradient tail: more than %d stages", kMaxWgradJobs);
+      return ALEXNET_EINVAL;
+    }
+    int ns = 1;
+    AX_TRY(launch_conv_bwd_weight(p, V, yt, dU, nullptr, ws, st, &ns));
+    WgradJob j;
+    j.slices = ws; j.dU = dU; j.dwf = dwf;
+    j.slab = (long)p.kf() * p.og(); j.total = total;
+    j.nsplit = ns; j.groups36 = p.groups; j.groups = c.groups; j.Na = c.cg(); j.Nb = c.og(); j.k = c.k;
+    j.nsub = nsub_of(c); j.vec = 0;
+    wgrad_tail_add(*tail, j);
+    return ALEXNET_OK;
+  }
   // (split over the tiles where that fills the chip; the slices are added by the wide reduction kernel: letting
   // the transform below add them, with its 12 to 25 thousand threads, measured 15-50 us slower)
   AX_TRY(launch_conv_bwd_weight(p, V, yt, dU, nullptr, ws, st));
-  const long total = (long)c.groups * nq_of(c) * c.cg() * (c.og() / 4);
   KernelScope ks("wino_dw", 0, ((double)wino_u_floats(c) + (double)c.w_elems()) * 4.0, st);
   hipLaunchKernelGGL(wino_dw_kernel, blocks_for(total), dim3(256), 0, st, c.groups, c.cg(), c.og(), c.k, nsub_of(c), dU,
                      dwf, total);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
+}
+int launch_wino_dw_batch(const WgradTail& t, hipStream_t st) {
+  if (t.blocks_t == 0) return ALEXNET_OK;
+  double bytes = 0;
+  for (int i = 0; i < t.n; ++i)
+    bytes += ((double)t.job[i].slab * t.job[i].groups36 + (double)t.job[i].groups * t.job[i].k * t.job[i].k * t.job[i].Na * t.job[i].Nb) * 4.0;
+  KernelScope ks("wino_dw", 0, bytes, st);
+  hipLaunchKernelGGL(wino_dw_batch_kernel, dim3(t.blocks_t), dim3(256), 0, st, t);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+int launch_wgrad_tail(const WgradTail& t, hipStream_t st) {
+  AX_TRY(launch_reduce_slabs_batch(t, st));
+  return launch_wino_dw_batch(t, st);
 }
 
 }  // namespace ax
