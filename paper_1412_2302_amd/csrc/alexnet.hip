@@ -280,7 +280,10 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     gws = std::max(gws, conv_bwd_data_ws_floats(s.g));
     cws = std::max(cws, colsum_ws_floats(s.g.P(), s.g.Cout));
     cws_batch += colsum_batch_ws_floats(s.g.P(), s.g.Cout);
-    if (s.lrn && s.pool) cws = std::max(cws, lrn_part_floats(s.g.Cout));
+    if (s.lrn && s.pool) {
+      cws = std::max(cws, lrn_part_floats(s.g.Cout));
+      cws_batch += lrn_part_floats(s.g.Cout);
+    }
   }
   {
     // The dense-layer update shares the chip best with a direct fp32 convolution GEMM of the backward pass, the
@@ -478,9 +481,19 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     Stage& s = n->st[i];
     ProfContext pc0(s.lab[0]);
     bool bias_done = false;
-    if (s.fused()) {  // pool adjoint, normalisation adjoint, ReLU gate and bias gradient in one pass
+    if (s.fused()) {  // pool adjoint, normalisation adjoint, ReLU gate and the bias gradient's partial sums in one pass
+      // the kernel leaves one row of sums per workgroup; those rows are one more matrix for the batch at the end
+      float* part = n->colsum_ws + bias_ws_used;
+      const size_t part_rows = lrn_part_rows(s.g.P(), s.g.Cout);
+      bias_ws_used += (part_rows * s.g.Cout + 3) / 4 * 4;
+      if (bias_ws_used > n->colsum_ws_floats_) {
+        set_error("bias gradients: partial sums do not fit their workspace");
+        return ALEXNET_EINVAL;
+      }
       AX_TRY(launch_pool_lrn_bwd(s.act, s.d_out, s.slot, s.dact, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, c.lrn_n,
-                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, 1, n->grads + s.b_off, n->colsum_ws, st));
+                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, 1, nullptr, part, st, true));
+      AX_TRY(colsum_batch_add(bias_sums, part, (long)part_rows, s.g.Cout, n->grads + s.b_off, n->colsum_ws,
+                              &bias_ws_used));
       bias_done = true;
     } else if (s.pool) {
       if (s.lrn)

@@ -122,7 +122,9 @@ int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, i
                         float k, float alpha, float beta, hipStream_t st);
 int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, float* da, int N, int H, int W, int C,
                         int Ho, int Wo, int n, float k, float alpha, float beta, int relu_gate, float* colsum_out,
-                        float* part, hipStream_t st);
+                        float* part, hipStream_t st, bool partials_only = false);
+// partials_only: leave the lrn_part_rows(pixels, C) rows of per-workgroup sums in `part` for the caller to add up
+size_t lrn_part_rows(long pixels, int C);
 int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo,
                     hipStream_t st);
 // dx[n][y][x][c] = sum of dy over the windows whose winning tap is (y,x); gated by gate > 0 when gate != null

@@ -578,22 +578,24 @@ int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, i
   return ALEXNET_OK;
 }
 
+size_t lrn_part_rows(long pixels, int C) { return (size_t)lrn_grid(pixels, 256 / (C / 4)); }
 int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, float* da, int N, int H, int W, int C,
                         int Ho, int Wo, int n, float k, float alpha, float beta, int relu_gate, float* colsum_out,
-                        float* part, hipStream_t st) {
+                        float* part, hipStream_t st, bool partials_only) {
   const long pixels = (long)N * H * W;
   if (!pixels) return ALEXNET_OK;
   const int PB = 256 / (C / 4);
   const int blocks = lrn_grid(pixels, PB);
+  const bool sums = colsum_out || partials_only;
   {
     KernelScope ks("pool_lrn_bwd", 0, (double)pixels * C * 8.0 + (double)N * Ho * Wo * C * 5.0, st);
     const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
     const PoolGather pg{dy, slot, H, W, Ho, Wo, make_fastdiv((uint32_t)W), make_fastdiv((uint32_t)H)};
     hipLaunchKernelGGL((lrn_vec_kernel<true, true>), dim3(blocks), dim3(256), lds, st, a, nullptr, da, pixels, C, n / 2,
-                       PB, k, alpha, beta, relu_gate, pg, colsum_out ? part : nullptr);
+                       PB, k, alpha, beta, relu_gate, pg, sums ? part : nullptr);
     AX_LAUNCH_CHECK();
   }
-  if (colsum_out) {
+  if (colsum_out && !partials_only) {
     KernelScope ks("colsum_finish", 0, (double)blocks * C * 4.0, st);
     hipLaunchKernelGGL(colsum_finish_kernel, dim3(C / 4), dim3(256), 0, st, part, blocks, C, colsum_out);
     AX_LAUNCH_CHECK();
@@ -954,10 +956,10 @@ int colsum_batch_add(ColsumBatch& b, const float* m, long rows, int cols, float*
   j.part = ws + *ws_used;
   *ws_used += ((size_t)j.nparts * cols + 3) / 4 * 4;  // every job's partials start on a 16-byte boundary
   const int stripes = ceil_div(cols, 64), k = b.n - 1;
-  b.first1[k] = k ? b.first1[k - 1] + ceil_div(b.job[k - 1].cols, 64) * b.job[k - 1].nparts : 0;
-  b.first2[k] = k ? b.first2[k - 1] + ceil_div(b.job[k - 1].cols, 64) : 0;
-  b.blocks1 = b.first1[k] + stripes * j.nparts;
-  b.blocks2 = b.first2[k] + stripes;
+  b.first1[k] = b.blocks1;
+  b.first2[k] = b.blocks2;
+  b.blocks1 += stripes * j.nparts;
+  b.blocks2 += stripes;
   return ALEXNET_OK;
 }
 size_t colsum_batch_ws_floats(long rows, int cols) { return (colsum_ws_floats(rows, cols) + 3) / 4 * 4; }
