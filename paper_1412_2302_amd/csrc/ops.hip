@@ -881,8 +881,10 @@ __device__ __forceinline__ void colsum_stage2_block(const float* __restrict__ pa
   const int cl = threadIdx.x & 63, pl = threadIdx.x >> 6;
   const int col = stripe * 64 + cl;
   float s = 0.f;
-  if (col < cols)
-    for (int p = pl; p < nparts; p += 4) s += part[(size_t)p * cols + col];
+  if (col < cols) {
+#pragma unroll 8
+    for (int p = pl; p < nparts; p += 4) s += part[(size_t)p * cols + col];  // eight loads in flight, added in order
+  }
   sh[pl][cl] = s;
   __syncthreads();
   if (pl == 0 && col < cols) out[col] = (sh[0][cl] + sh[1][cl]) + (sh[2][cl] + sh[3][cl]);
