@@ -240,7 +240,8 @@ __global__ void slab_finish_kernel(const float* __restrict__ ws, int ns, int gro
   const size_t slab = (size_t)M * N;
   const float* p = ws + (size_t)g * ns * slab + m * N + n;
   float v = 0.f;
-  for (int k = 0; k < ns; ++k) v += p[(size_t)k * slab];
+#pragma unroll 8
+  for (int k = 0; k < ns; ++k) v += p[(size_t)k * slab];  // loads in flight together, added in order
   if (bias) v += bias[col];
   if (relu) v = v > 0.f ? v : 0.f;
   if (gate && !(gate[i] > 0.f)) v = 0.f;
@@ -522,7 +523,8 @@ __global__ void fc_fwd_finish_kernel(const float* __restrict__ ws, int nsplit, i
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   float s = 0.f;
-  for (int k = 0; k < nsplit; ++k) s += ws[(size_t)k * total + i];
+#pragma unroll 8
+  for (int k = 0; k < nsplit; ++k) s += ws[(size_t)k * total + i];  // loads in flight together, added in order
   const int o = (int)(i % out);
   if (act.bias) s += act.bias[o];
   if (act.relu) s = s > 0.f ? s : 0.f;
@@ -534,7 +536,8 @@ __global__ void fc_bwd_finish_kernel(const float* __restrict__ ws, int nsplit, s
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   float s = 0.f;
-  for (int k = 0; k < nsplit; ++k) s += ws[(size_t)k * total + i];
+#pragma unroll 8
+  for (int k = 0; k < nsplit; ++k) s += ws[(size_t)k * total + i];  // loads in flight together, added in order
   if (gate && !(gate[i] > 0.f)) s = 0.f;
   dx[i] = s;
 }
