@@ -70,6 +70,8 @@ struct Profiler : ProfSink {
 static thread_local Profiler* g_profiler = nullptr;
 
 static const int kStages = 5, kFc = 3, kSlots = 3;  // slot 2 is the inference input
+static_assert(kMaxColsumJobs >= kStages + kFc, "one bias-gradient job per layer");
+static_assert(kMaxWgradJobs >= kStages, "one weight-gradient tail per stage");
 
 struct Stage {
   ConvGeom g;
