@@ -788,8 +788,9 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
   }
   AX_TRY(fwd_bwd(n, slot, d_labels, step, d_loss, S(stream), early));
   if (!early) return apply_update(n, S(stream));
-  AX_TRY(update_range(n, 0, fc_begin, S(stream)));              // convolution weights
-  AX_TRY(update_range(n, n->n_weights, n->n_params, S(stream)));  // all biases
+  // convolution weights and all biases, the two ends of the flat vector, in one launch
+  AX_TRY(launch_sgd_update_two(n->params, n->mom, n->grads, fc_begin, n->n_weights, n->n_params, n->n_weights,
+                               n->cfg.lr, n->cfg.momentum, n->cfg.weight_decay, S(stream)));
   AX_HIP(hipStreamWaitEvent(S(stream), n->ev_upd_done, 0));      // join the dense-layer update
   return ALEXNET_OK;
 }

@@ -474,6 +474,8 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
     return ALEXNET_OK;
   }
   if (defer_ns) *defer_ns = 1;
+  if (run && p.ns > 1)  // slices of the padded layout straight to the packed one
+    return launch_reduce_slabs_unpack(ws, p.ns, slab, run_len(c), c.k * c.Cin, c.Cout, dwf, st);
   if (p.ns > 1) AX_TRY(launch_reduce_slabs(ws, p.ns, slab, d.groups, out, st));
   if (run) AX_TRY(launch_conv_run_unpack(c, dwrun, dwf, st));
   return ALEXNET_OK;

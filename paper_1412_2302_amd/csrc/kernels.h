@@ -156,8 +156,15 @@ int colsum_batch_add(ColsumBatch& b, const float* m, long rows, int cols, float*
 size_t colsum_batch_ws_floats(long rows, int cols);
 int launch_colsum_batch(const ColsumBatch& b, hipStream_t st);
 int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, float* out, hipStream_t st);
+// one result of k*run rows by cout columns, rows (r, j >= kc) dropped and the rest packed to r*kc + j
+int launch_reduce_slabs_unpack(const float* ws, int nsplit, long slab, int run, int kc, int cout, float* out,
+                               hipStream_t st);
 int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
                       hipStream_t st);
+// the same for elements [0, n1) and [begin2, end2) of the vectors in one launch (n1 and begin2 multiples of four);
+// positions below n_decay are decayed
+int launch_sgd_update_two(float* w, float* v, const float* g, size_t n1, size_t begin2, size_t end2, size_t n_decay,
+                          float lr, float mu, float wd, hipStream_t st);
 int launch_average(float* a, float* b, size_t n, hipStream_t st);
 int launch_avg_grad_update(float* wa, float* va, const float* ga, float* wb, float* vb, const float* gb, size_t n,
                            size_t n_decay, float lr, float mu, float wd, hipStream_t st);

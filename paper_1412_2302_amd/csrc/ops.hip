@@ -1009,6 +1009,37 @@ __global__ void __launch_bounds__(256)
 reduce_slabs_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int groups, float* __restrict__ out) {
   reduce_slabs_block(ws, nsplit, slab, groups, out, blockIdx.x);
 }
+// The same for one result whose rows are runs padded to `run` entries (run mode of the first layer's weight
+// gradient): row (r, j) goes to row r*kc + j of the packed layout, the padding rows j >= kc nowhere.
+__global__ void __launch_bounds__(256)
+reduce_slabs_unpack_kernel(const float* __restrict__ ws, int nsplit, size_t slab, int run, int kc, int cout,
+                           float* __restrict__ out) {
+  __shared__ float sh[4][64];
+  const int el = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const size_t i = (size_t)blockIdx.x * 64 + el;
+  float s = 0.f;
+  if (i < slab) {
+    const float* p = ws + i;
+#pragma unroll 8
+    for (int k = part; k < nsplit; k += 4) s += p[(size_t)k * slab];
+  }
+  sh[part][el] = s;
+  __syncthreads();
+  if (part == 0 && i < slab) {
+    const size_t row = i / cout;
+    const int o = (int)(i - row * cout), r = (int)(row / run), j = (int)(row - (size_t)r * run);
+    if (j < kc) out[((size_t)r * kc + j) * cout + o] = (sh[0][el] + sh[1][el]) + (sh[2][el] + sh[3][el]);
+  }
+}
+int launch_reduce_slabs_unpack(const float* ws, int nsplit, long slab, int run, int kc, int cout, float* out,
+                               hipStream_t st) {
+  if (!slab) return ALEXNET_OK;
+  KernelScope ks("reduce_slabs", 0, (double)slab * 4.0 * (nsplit + 1), st);
+  hipLaunchKernelGGL(reduce_slabs_unpack_kernel, dim3(grid_for((size_t)slab, 64)), dim3(256), 0, st, ws, nsplit,
+                     (size_t)slab, run, kc, cout, out);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
 // Few slices of a large result (slab a multiple of four floats, 16-byte aligned): a lane owns four consecutive
 // elements and adds its slices in order, 16 bytes per load.
 constexpr int kReduceVecMaxSlices = 16;
@@ -1088,15 +1119,17 @@ int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, floa
 // ---------------------------------------------------------------- update ---
 // v <- mu v - lr (g + wd w);  w <- w + v.  Elements below n_decay are weights
 // (decayed), the rest are biases (not decayed).
+// Two pieces of the vectors in one launch: elements [0, n1) and [n1 + gap, n + gap) (n1 a multiple of four, or
+// gap = 0); n_decay counts positions in the vectors, not elements of the launch.
 __global__ void __launch_bounds__(256)
-sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g, size_t n, size_t n_decay,
-                  float lr, float mu, float wd) {
+sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g, size_t n, size_t n1,
+                  size_t gap, size_t n_decay, float lr, float mu, float wd) {
   // grid-stride over groups of four: a bounded number of workgroups, so that a GEMM running beside this
   // kernel on another stream still finds room on every CU
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q * 4 < n; q += stride) {
-    const size_t i = q * 4;
-    if (i + 3 < n) {
+    const size_t e = q * 4, i = e < n1 ? e : e + gap;
+    if (e + 3 < n) {
       float4 w4 = *reinterpret_cast<float4*>(w + i);
       float4 v4 = *reinterpret_cast<float4*>(v + i);
       const float4 g4 = *reinterpret_cast<const float4*>(g + i);
@@ -1113,7 +1146,7 @@ sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, const float* __r
       *reinterpret_cast<float4*>(v + i) = v4;
       *reinterpret_cast<float4*>(w + i) = w4;
     } else {
-      for (size_t j = i; j < n; ++j) {
+      for (size_t j = i; j < n + (e < n1 ? 0 : gap); ++j) {
         const float d = j < n_decay ? wd : 0.f;
         v[j] = mu * v[j] - lr * (g[j] + d * w[j]);
         w[j] += v[j];
@@ -1127,7 +1160,19 @@ int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_dec
   if (!n) return ALEXNET_OK;
   KernelScope ks("sgd_update", 0, (double)n * 20.0, st);
   const unsigned blocks = std::min<unsigned>(grid_for((n + 3) / 4, 256), kUpdateMaxBlocks);
-  hipLaunchKernelGGL(sgd_update_kernel, dim3(blocks), dim3(256), 0, st, w, v, g, n, n_decay, lr, mu, wd);
+  hipLaunchKernelGGL(sgd_update_kernel, dim3(blocks), dim3(256), 0, st, w, v, g, n, n, (size_t)0, n_decay, lr, mu, wd);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+// elements [0, n1) and [begin2, end2) of the vectors in one launch; n1 a multiple of four, begin2 >= n1
+int launch_sgd_update_two(float* w, float* v, const float* g, size_t n1, size_t begin2, size_t end2, size_t n_decay,
+                          float lr, float mu, float wd, hipStream_t st) {
+  const size_t n = n1 + (end2 - begin2);
+  if (!n) return ALEXNET_OK;
+  KernelScope ks("sgd_update", 0, (double)n * 20.0, st);
+  const unsigned blocks = std::min<unsigned>(grid_for((n + 3) / 4, 256), kUpdateMaxBlocks);
+  hipLaunchKernelGGL(sgd_update_kernel, dim3(blocks), dim3(256), 0, st, w, v, g, n, n1, begin2 - n1, n_decay, lr, mu,
+                     wd);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
