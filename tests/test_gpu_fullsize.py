@@ -166,3 +166,31 @@ def test_train_step_equals_its_parts_bit_for_bit_at_full_size(lib, batch):
     assert any(np.abs(v).max() > 0 for v in ma.values())
     a.close()
     b.close()
+
+
+def test_step_weight_gradients_equal_the_operator_alone_at_full_size(lib):
+    """Inside a step the split-k slices of conv2-5's weight-gradient products are added up, and the sums
+    transformed back to taps, in one batch for all four layers at the end of the backward pass, and the bias
+    gradients of all layers likewise; the single-operator entry point does each in launches of its own.  Same
+    inputs, same arithmetic per element: the weight gradients must agree bit for bit (the bias sums are
+    finished in another order: to rounding)."""
+    batch, wl = 128, S.ALEXNET
+    net, spec, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3, std=0.02, bias=0.1)
+    raw, labels = S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 5)
+    mean = S.make_mean_image(3, 256, 256, S.SEED_BASE + 7)
+    net.preprocess(cuda(raw), cuda(mean), 0, 0)
+    net.forward_backward(cuda(labels), 0, slot=0)
+    net.check()
+    g = net.get_grads()
+    stages, _ = O.layer_shapes(spec)
+    for li in range(2, 6):
+        prev = spec.conv[li - 2]
+        cin, h, w = stages[li - 1]["in"]
+        cout, ho, wo = stages[li - 1]["conv"]
+        x = net.tensor(lib.T_POOL if prev.pool else lib.T_CONV_ACT, li - 1).reshape(batch, cin, h, w)
+        dy = net.tensor(lib.T_CONV_DACT, li).reshape(batch, cout, ho, wo)
+        assert np.abs(dy).max() > 0
+        dw, db = net.conv_backward_weight(li, x, dy, g[f"conv{li}.w"].shape)
+        assert np.array_equal(dw.cpu().numpy(), g[f"conv{li}.w"]), li
+        assert rel_l2(db.cpu().numpy(), g[f"conv{li}.b"]) <= 1e-6, li
+    net.close()
