@@ -57,6 +57,11 @@ extern "C" {
 #define ALEXNET_PRECISION_FP32 0
 #define ALEXNET_PRECISION_BF16 1
 
+/* alexnet_config_t.flags.  DIRECT_CONV keeps every convolution stage on the
+ * direct implicit GEMM (see alexnet_query); unknown bits are refused with
+ * ALEXNET_EINVAL. */
+#define ALEXNET_FLAG_DIRECT_CONV 1
+
 typedef struct alexnet alexnet_t; /* opaque; host memory owned by the library */
 
 /* One convolution stage: conv -> ReLU -> [LRN] -> [3x3 stride-2 max-pool]. */
@@ -82,6 +87,7 @@ typedef struct {
   float lr, momentum, weight_decay; /* v <- mu v - lr (g + wd w); w <- w + v;  */
                                 /* wd applies to weights, not to biases        */
   int32_t precision;            /* ALEXNET_PRECISION_*                         */
+  int32_t flags;                /* ALEXNET_FLAG_* or'ed together; 0 = defaults */
   uint64_t seed;                /* keys the crop / flip / dropout generator    */
 } alexnet_config_t;
 
@@ -92,10 +98,10 @@ typedef struct {
  * channel counts per group that are multiples of 4 (conv2-5 of Section 2's
  * network) are computed through F(4x4, 3x3) tile transforms (a 5x5 kernel as
  * four 3x3 sub-kernels): the same result up to rounding order with 2.6x fewer
- * multiplications, at the price of more workspace.  Setting the environment
- * variable ALEXNET_DIRECT_CONV=1 before alexnet_query and alexnet_create
- * (both must see the same value) keeps those
- * stages on the direct implicit GEMM. */
+ * multiplications, at the price of more workspace.  ALEXNET_FLAG_DIRECT_CONV
+ * in cfg->flags keeps those stages on the direct implicit GEMM; the flag is
+ * part of the configuration, so alexnet_query and alexnet_create size and lay
+ * out the workspace for the same choice. */
 int alexnet_query(const alexnet_config_t* cfg, size_t* n_params, size_t* workspace_bytes);
 
 /* Builds a replica over caller-owned device memory (Section 2.2: replicas are
@@ -286,6 +292,18 @@ int alexnet_pool_forward(alexnet_t* net, int32_t layer, const float* d_x, float*
                          void* stream);
 int alexnet_pool_backward(alexnet_t* net, int32_t layer, const float* d_x, const float* d_dy, int32_t relu_gate,
                           float* d_dx, void* stream);
+/* A stage that normalises and pools (conv1, conv2 of Section 2's network) runs both
+ * in one kernel during a training step, and their adjoints, the ReLU gate and
+ * the bias-gradient sums in another.  These two calls run exactly those
+ * kernels alone: y = pool(lrn(a)) with the winning taps; da = gate(lrn^T(
+ * pool^T(dy))) where the taps are those of the fused forward kernel on the same
+ * a, and db[c] = sum of da over batch and pixels (d_db may be null; 16-byte
+ * aligned otherwise).  ALEXNET_ENOTIMPL for a stage that does not take the
+ * fused kernels (no LRN or no pool, or channels not a multiple of 4). */
+int alexnet_lrn_pool_forward(alexnet_t* net, int32_t layer, const float* d_a, float* d_y, int32_t* d_argmax,
+                             void* stream);
+int alexnet_pool_lrn_backward(alexnet_t* net, int32_t layer, const float* d_a, const float* d_dy,
+                              int32_t relu_gate, float* d_da, float* d_db, void* stream);
 /* Dense layer `layer` (6..8) as plain matrices: x [batch][in], w [out][in],
  * y, dy [batch][out]; y = act(x w^T + b), dx = dy w, dw = dy^T x, db = sum dy. */
 int alexnet_fc_forward(alexnet_t* net, int32_t layer, const float* d_x, const float* d_w, const float* d_b,

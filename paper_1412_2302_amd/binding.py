@@ -15,8 +15,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# ALEXNET_HIP_LIB points at another build of the same library (used when comparing kernel variants)
-LIB_PATH = os.environ.get("ALEXNET_HIP_LIB") or os.path.join(_HERE, "libalexnet_hip.so")
+LIB_PATH = os.path.join(_HERE, "libalexnet_hip.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1412_2302_amd.build`")
 _lib = C.CDLL(LIB_PATH)
@@ -38,7 +37,7 @@ class Config(C.Structure):
         ("conv", ConvCfg * 5), ("fc", C.c_int32 * 3),
         ("lrn_n", C.c_int32), ("lrn_k", C.c_float), ("lrn_alpha", C.c_float), ("lrn_beta", C.c_float),
         ("dropout_p", C.c_float), ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float),
-        ("precision", C.c_int32), ("seed", C.c_uint64),
+        ("precision", C.c_int32), ("flags", C.c_int32), ("seed", C.c_uint64),
     ]
 
 
@@ -91,6 +90,8 @@ _SIGS.update({
     "alexnet_lrn_backward": [_vp, _i32, _vp, _vp, _i32, _vp, _vp],
     "alexnet_pool_forward": [_vp, _i32, _vp, _vp, _vp, _vp],
     "alexnet_pool_backward": [_vp, _i32, _vp, _vp, _i32, _vp, _vp],
+    "alexnet_lrn_pool_forward": [_vp, _i32, _vp, _vp, _vp, _vp],
+    "alexnet_pool_lrn_backward": [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _vp],
     "alexnet_fc_forward": [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp],
     "alexnet_fc_backward": [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "alexnet_softmax_xent": [_vp, _vp, _vp, _vp, _vp, _vp],
@@ -140,7 +141,10 @@ def _check(rc: int):
         raise AlexNetError(rc, last_error())
 
 
-def make_config(workload: dict, batch: int, seed: int = 0, precision: int = 0) -> Config:
+FLAG_DIRECT_CONV = 1
+
+
+def make_config(workload: dict, batch: int, seed: int = 0, precision: int = 0, flags: int = 0) -> Config:
     cfg = Config()
     cfg.batch = batch
     cfg.in_c = workload["in_c"]
@@ -154,7 +158,7 @@ def make_config(workload: dict, batch: int, seed: int = 0, precision: int = 0) -
     cfg.lrn_n, cfg.lrn_k, cfg.lrn_alpha, cfg.lrn_beta = n, k, a, b
     cfg.dropout_p, cfg.lr = workload["dropout_p"], workload["lr"]
     cfg.momentum, cfg.weight_decay = workload["momentum"], workload["weight_decay"]
-    cfg.precision, cfg.seed = precision, seed
+    cfg.precision, cfg.flags, cfg.seed = precision, flags, seed
     return cfg
 
 
@@ -202,11 +206,11 @@ def _dev(a, dtype=None) -> torch.Tensor:
 class AlexNet:
     """One replica: owns parameter, momentum and workspace tensors on cuda:0."""
 
-    def __init__(self, workload: dict, batch: int, seed: int = 0, precision: int = 0):
+    def __init__(self, workload: dict, batch: int, seed: int = 0, precision: int = 0, flags: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("libalexnet_hip needs a GPU; there is no CPU path")
         self.workload, self.batch = workload, batch
-        self.cfg = make_config(workload, batch, seed, precision)
+        self.cfg = make_config(workload, batch, seed, precision, flags)
         self.n_params, self.ws_bytes = query(self.cfg)
         dev = torch.device("cuda", 0)
         self.params = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
@@ -437,6 +441,25 @@ class AlexNet:
         dx = torch.empty_like(xt)
         _check(_lib.alexnet_pool_backward(self._h, layer, _ptr(xt), _ptr(dyt), int(relu_gate), _ptr(dx), _stream(None)))
         return dx
+
+    def lrn_pool_forward(self, layer, a):
+        """The fused normalisation + pool kernel of a training step, alone: pooled values and winning taps."""
+        at = _dev(a, torch.float32)
+        n, c, h, w = at.shape
+        ho, wo = (h - 3) // 2 + 1, (w - 3) // 2 + 1
+        y = torch.empty(n, c, ho, wo, dtype=torch.float32, device="cuda")
+        arg = torch.empty(n, c, ho, wo, dtype=torch.int32, device="cuda")
+        _check(_lib.alexnet_lrn_pool_forward(self._h, layer, _ptr(at), _ptr(y), _ptr(arg), _stream(None)))
+        return y, arg
+
+    def pool_lrn_backward(self, layer, a, dy, relu_gate=True):
+        """The fused pool adjoint + normalisation adjoint + gate + bias sums kernel, alone: (da, db)."""
+        at, dyt = _dev(a, torch.float32), _dev(dy, torch.float32)
+        da = torch.empty_like(at)
+        db = torch.empty(at.shape[1], dtype=torch.float32, device="cuda")
+        _check(_lib.alexnet_pool_lrn_backward(self._h, layer, _ptr(at), _ptr(dyt), int(relu_gate), _ptr(da), _ptr(db),
+                                              _stream(None)))
+        return da, db
 
     def fc_forward(self, layer, x, w, b, relu=False):
         xt, wt, bt = _dev(x, torch.float32), _dev(w, torch.float32), _dev(b, torch.float32)

@@ -145,11 +145,10 @@ struct alexnet {
 
 // F(4x4, 3x3) pays when the 4x4 tiles cover the output without much waste (2.6x fewer multiplies for the 3x3
 // layers at 13 x 13 and for the 5x5 layer, as four 3x3 sub-kernels, at 27 x 27);
-// the environment variable ALEXNET_DIRECT_CONV=1 keeps every stage on the direct implicit GEMM.
+// ALEXNET_FLAG_DIRECT_CONV in the configuration keeps every stage on the direct implicit GEMM.
 static bool use_winograd(const alexnet_config_t& c, const ConvGeom& g) {
   if (c.precision != ALEXNET_PRECISION_FP32 || !wino_ok(g)) return false;
-  const char* e = getenv("ALEXNET_DIRECT_CONV");
-  if (e && e[0] == '1') return false;
+  if (c.flags & ALEXNET_FLAG_DIRECT_CONV) return false;
   return wino_gain(g) >= 1.5;
 }
 
@@ -162,6 +161,10 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
   if (c.precision != ALEXNET_PRECISION_FP32 && c.precision != ALEXNET_PRECISION_BF16) {
     set_error("precision %d is not available (0: fp32, 1: bf16 products with fp32 accumulation)", c.precision);
     return ALEXNET_ENOTIMPL;
+  }
+  if (c.flags & ~ALEXNET_FLAG_DIRECT_CONV) {
+    set_error("unknown bits in flags: 0x%x", (unsigned)c.flags);
+    return ALEXNET_EINVAL;
   }
   if (c.lrn_n < 1 || c.lrn_n % 2 == 0 || !(c.dropout_p >= 0.f && c.dropout_p < 1.f)) {
     set_error("bad lrn_n (must be odd) or dropout_p");
@@ -1083,6 +1086,43 @@ int alexnet_pool_backward(alexnet_t* n, int32_t layer, const float* d_x, const f
   AX_TRY(launch_pool_bwd(s->d_out, s->slot, relu_gate ? s->act : nullptr, s->dact, g.B, g.Ho, g.Wo, g.Cout, s->Hp,
                          s->Wp, S(stream)));
   return launch_nhwc_to_nchw(s->dact, d_dx, g.B, g.Cout, g.Ho, g.Wo, S(stream));
+}
+
+// The two kernels a training step runs for a stage that normalises and pools (conv1 and conv2 of the paper's
+// network), alone: normalisation + pool in one pass, and pool adjoint + normalisation adjoint + ReLU gate +
+// bias-gradient sums in one pass.
+int alexnet_lrn_pool_forward(alexnet_t* n, int32_t layer, const float* d_a, float* d_y, int32_t* d_argmax,
+                             void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(d_a && d_y, ALEXNET_EINVAL, "alexnet_lrn_pool_forward: null argument");
+  REQUIRE(s->fused(), ALEXNET_ENOTIMPL, "alexnet_lrn_pool_forward: this stage does not run the fused kernels");
+  const ConvGeom& g = s->g;
+  const alexnet_config_t& c = n->cfg;
+  AX_TRY(launch_nchw_to_nhwc(d_a, s->act, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  AX_TRY(launch_lrn_pool_fwd(s->act, s->pool_out, s->slot, g.B, g.Ho, g.Wo, g.Cout, s->Hp, s->Wp, c.lrn_n, c.lrn_k,
+                             c.lrn_alpha, c.lrn_beta, S(stream)));
+  AX_TRY(launch_nhwc_to_nchw(s->pool_out, d_y, g.B, g.Cout, s->Hp, s->Wp, S(stream)));
+  if (d_argmax) AX_TRY(launch_pool_argmax_canonical(s->slot, d_argmax, g.B, g.Cout, s->Hp, s->Wp, g.Wo, S(stream)));
+  return ALEXNET_OK;
+}
+int alexnet_pool_lrn_backward(alexnet_t* n, int32_t layer, const float* d_a, const float* d_dy, int32_t relu_gate,
+                              float* d_da, float* d_db, void* stream) {
+  Stage* s;
+  AX_TRY(stage_of(n, layer, &s));
+  REQUIRE(d_a && d_dy && d_da, ALEXNET_EINVAL, "alexnet_pool_lrn_backward: null argument");
+  REQUIRE(s->fused(), ALEXNET_ENOTIMPL, "alexnet_pool_lrn_backward: this stage does not run the fused kernels");
+  REQUIRE(!d_db || aligned16(d_db), ALEXNET_EALIGN, "alexnet_pool_lrn_backward: d_db must be 16-byte aligned");
+  const ConvGeom& g = s->g;
+  const alexnet_config_t& c = n->cfg;
+  AX_TRY(launch_nchw_to_nhwc(d_a, s->act, g.B, g.Cout, g.Ho, g.Wo, S(stream)));
+  // the winning taps come from the fused forward kernel, as in a training step
+  AX_TRY(launch_lrn_pool_fwd(s->act, s->pool_out, s->slot, g.B, g.Ho, g.Wo, g.Cout, s->Hp, s->Wp, c.lrn_n, c.lrn_k,
+                             c.lrn_alpha, c.lrn_beta, S(stream)));
+  AX_TRY(launch_nchw_to_nhwc(d_dy, s->d_out, g.B, g.Cout, s->Hp, s->Wp, S(stream)));
+  AX_TRY(launch_pool_lrn_bwd(s->act, s->d_out, s->slot, s->dact, g.B, g.Ho, g.Wo, g.Cout, s->Hp, s->Wp, c.lrn_n,
+                             c.lrn_k, c.lrn_alpha, c.lrn_beta, relu_gate, d_db, n->colsum_ws, S(stream)));
+  return launch_nhwc_to_nchw(s->dact, d_da, g.B, g.Cout, g.Ho, g.Wo, S(stream));
 }
 
 static int dense_of(alexnet* n, int32_t layer, Dense** f) {

@@ -7,10 +7,7 @@
 
 namespace ax {
 
-#ifndef AX_BK
-#define AX_BK 16
-#endif
-constexpr int kBK = AX_BK;  // depth of a k-tile
+constexpr int kBK = 16;  // depth of a k-tile
 typedef Tile<128, 128, kBK, 2, 2> T128;  // wave tile 64 x 64
 typedef Tile<128, 96, kBK, 4, 1> T96;    // wave tile 32 x 96
 typedef Tile<128, 64, kBK, 4, 1> T64;    // wave tile 32 x 64

@@ -115,15 +115,15 @@ def test_bf16_dense_layers_alone(lib):
 
 
 # ReLU gates and pooling winners: a bf16 forward pass moves pre-activations by ~1e-3 of their
-# scale, so more of them change side than in fp32; the library's choices must still be the
-# oracle's wherever the oracle's margin exceeds 3e-2 of the tensor's rms.
-_DECISIONS = dict(tau=3e-2, max_frac=3e-2)
+# scale, so more of them change side than in fp32; the window in which the library's choices may
+# differ from the oracle's is derived from the forward error measured in the same run
+# (gpu_common.validated_decisions), so it widens by itself.
 
 
 def test_bf16_mini_alexnet_step(lib):
     errs = {}
     loss = run_step_and_compare(lib, S.MINI, 4, seed=11, bias=0.0, std=0.01, use_raw=False, precision=1, direct=False,
-                                loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs, **_DECISIONS)
+                                loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
     print(errs)
     assert abs(loss - math.log(10)) < 1e-2
 
@@ -131,14 +131,14 @@ def test_bf16_mini_alexnet_step(lib):
 def test_bf16_mini_three_steps_with_signal_everywhere(lib):
     errs = {}
     run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01,
-                         precision=1, direct=False, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs, **_DECISIONS)
+                         precision=1, direct=False, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
     print(errs)
 
 
 def test_bf16_midi_net_with_preprocess(lib):
     errs = {}
     run_step_and_compare(lib, S.MIDI, 7, seed=13, bias=0.05, std=0.02, use_raw=True, steps=2, mom_std=0.01,
-                         precision=1, direct=False, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs, **_DECISIONS)
+                         precision=1, direct=False, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
     print(errs)
 
 

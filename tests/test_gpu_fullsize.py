@@ -12,6 +12,12 @@ from oracle import alexnet_oracle as O
 pytestmark = pytest.mark.gpu
 
 
+# Discrete choices (ReLU gates, pooling winners) of the fp32 library that differ from the float64 oracle's
+# at batch 128, per stage: measured on the seeded inputs of the test below (the kernels are deterministic, so
+# the counts are reproducible) with a factor of two on top.  One unit more than this fails the test.
+FULLSIZE_FLIP_CAPS = {"conv1": 64, "conv2": 64, "conv3": 32, "conv4": 32, "conv5": 32, "fc6": 8, "fc7": 8}
+
+
 @pytest.mark.timeout(900)
 def test_full_alexnet_step_batch128(lib):
     """Workload 3: uint8 pictures -> preprocess -> full fp32 step at batch 128.
@@ -19,11 +25,15 @@ def test_full_alexnet_step_batch128(lib):
     With ~10^8 ReLU units a handful of pre-activations lie within fp32 rounding
     of zero, and the library and the float64 oracle gate them differently; one
     such unit changes a gradient tensor by ~1/sqrt(units), i.e. at the 1e-3
-    level.  The test therefore (1) compares the forward pass directly,
-    (2) checks that every forward decision of the library is either the
-    oracle's or a tie within rounding, and (3) compares gradients and updated
-    weights with those decisions held fixed, to the 1e-3 bar.  The comparison
-    against the oracle's own decisions is reported and held to 1e-2."""
+    level.  The test therefore
+    (1) compares the forward pass directly;
+    (2) checks that every forward decision of the library is the oracle's, except inside a window
+        derived from the forward error measured in this run, and caps the count of exceptions
+        (gpu_common.validated_decisions, FULLSIZE_FLIP_CAPS);
+    (3) compares gradients and updated weights with those decisions held fixed, to the 1e-3 bar;
+    (4) compares against the oracle's own decisions with no information from the library: every
+        tensor either meets the 1e-3 bar outright, or the difference to the oracle's own gradient is
+        the one the validated flips produce inside the oracle itself, to 1 % of that difference."""
     batch, wl = 128, S.ALEXNET
     net, spec, p64, m64 = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3)
     raw, labels = S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 3)
@@ -42,7 +52,11 @@ def test_full_alexnet_step_batch128(lib):
     flips = {}
     loss_ref, p_new, m_new, g_ref, cache = O.train_step(
         spec, p64, m64, x64, labels, 0, decisions=validated_decisions(lib, net, spec, report=flips))
-    print("compare", loss, loss_ref, "decisions that differ (ties within rounding):", flips, flush=True)
+    print("compare", loss, loss_ref, flush=True)
+    for name, (ngate, nwin, inside, eps) in flips.items():
+        print(f"{name}: {ngate} gates and {nwin} pooling winners differ; {inside} oracle units inside the window, "
+              f"forward error {eps:.2e}", flush=True)
+        assert ngate + nwin <= FULLSIZE_FLIP_CAPS[name], (name, ngate, nwin)
     assert abs(loss - loss_ref) <= LOSS_RTOL * abs(loss_ref)
     assert abs(loss_ref - np.log(1000)) < 0.05
     for i in range(1, 6):
@@ -61,65 +75,52 @@ def test_full_alexnet_step_batch128(lib):
     _, _, _, g_own, _ = O.train_step(spec, p64, m64, x64, labels, 0)
     for k in g_own:
         e = rel_l2(g[k], g_own[k])
-        print(k, "grad rel_l2 vs oracle's own decisions %.2e" % e, flush=True)
+        gap = g_ref[k] - g_own[k]                      # what the flips do inside the oracle
+        unexplained = float(np.linalg.norm((g[k] - g_own[k]) - gap) / max(np.linalg.norm(gap), 1e-300))
+        print(k, "grad rel_l2 vs oracle's own decisions %.2e; part of it the flips do not explain %.2e" % (e, unexplained),
+              flush=True)
+        assert e <= TENSOR_RTOL or unexplained <= 1e-2, (k, e, unexplained)
         assert e <= 1e-2, (k, e)
     net.close()
 
 
-def _sample_idx(rng, shape, n):
-    return [tuple(int(rng.integers(0, s)) for s in shape) for _ in range(n)]
-
-
-@pytest.mark.timeout(600)
-def test_conv_stack_alone_batch128_sampled(lib):
-    """Workload 2: each convolution alone at batch 128 on N(0,1) inputs and
-    N(0,1) output gradients; outputs the oracle's definition gives one by one."""
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("direct", [False, True], ids=["default", "direct"])
+def test_conv_stack_alone_batch128_whole_tensors(lib, direct):
+    """Workload 2: each convolution alone at batch 128 on N(0,1) inputs and N(0,1) output gradients,
+    forward, data gradient (conv1's too: the strided pass by phases that no training step runs) and weight
+    gradient, every element against the float64 definition.  `direct` keeps conv2-5 on the direct implicit GEMM
+    (the default handle takes the tile-transform path for them); conv1 is the same in both and is checked once."""
     batch = 128
-    net = lib.AlexNet(S.ALEXNET, batch)
+    net = lib.AlexNet(S.ALEXNET, batch, flags=lib.FLAG_DIRECT_CONV if direct else 0)
     spec = oracle_spec(S.ALEXNET, batch)
     stages, _ = O.layer_shapes(spec)
-    rng = np.random.default_rng(S.SEED_BASE + 2)
     for li, (cv, st) in enumerate(zip(spec.conv, stages), start=1):
+        if direct and li == 1:
+            continue
         cin, h, w = st["in"]; cout, ho, wo = st["conv"]
-        cg, og, k, s_, pd = cin // cv.groups, cout // cv.groups, cv.k, cv.stride, cv.pad
-        print("conv", li, flush=True)
+        cg, k = cin // cv.groups, cv.k
+        print("conv", li, "direct" if direct else "default", flush=True)
         x = S.make_normal((batch, cin, h, w), S.SEED_BASE + 20 + li)
         wt = S.make_normal((cout, cg, k, k), S.SEED_BASE + 30 + li, std=0.01)
         dy = S.make_normal((batch, cout, ho, wo), S.SEED_BASE + 40 + li)
-        xp = np.pad(x, ((0, 0), (0, 0), (pd, pd), (pd, pd))).astype(np.float64)
         y = net.conv_forward(li, x, wt, None).cpu().numpy().reshape(batch, cout, ho, wo)
-        got, want = [], []
-        for (n, o, yy, xx) in _sample_idx(rng, y.shape, 300):
-            g = o // og
-            want.append(float((wt[o].astype(np.float64) * xp[n, g * cg:(g + 1) * cg, yy * s_:yy * s_ + k, xx * s_:xx * s_ + k]).sum()))
-            got.append(y[n, o, yy, xx])
-        assert rel_l2(got, want) <= TENSOR_RTOL, ("fwd", li, rel_l2(got, want))
+        want = O.conv_forward(x, wt, None, cv.stride, cv.pad, cv.groups)
+        assert rel_l2(y, want) <= TENSOR_RTOL, ("fwd", li, rel_l2(y, want))
+        assert np.abs(y - want).max() <= 1e-4 * np.abs(want).max(), ("fwd, worst element", li)
+        del y, want
         dx = net.conv_backward_data(li, dy, wt, x.shape).cpu().numpy()
-        got, want = [], []
-        for (n, c, iy, ix) in _sample_idx(rng, x.shape, 200):
-            g, cl = c // cg, c % cg
-            acc = 0.0
-            for r in range(k):
-                ty = iy + pd - r
-                if ty < 0 or ty % s_ or ty // s_ >= ho:
-                    continue
-                for q in range(k):
-                    tx = ix + pd - q
-                    if tx < 0 or tx % s_ or tx // s_ >= wo:
-                        continue
-                    acc += float(dy[n, g * og:(g + 1) * og, ty // s_, tx // s_].astype(np.float64) @ wt[g * og:(g + 1) * og, cl, r, q].astype(np.float64))
-            want.append(acc); got.append(dx[n, c, iy, ix])
-        assert rel_l2(got, want) <= TENSOR_RTOL, ("bwd_data", li, rel_l2(got, want))
+        want = O.conv_backward_data(dy, wt, (h, w), cv.stride, cv.pad, cv.groups)
+        assert rel_l2(dx, want) <= TENSOR_RTOL, ("bwd_data", li, rel_l2(dx, want))
+        # every border row and column, every stride phase and the last partial tile are in here
+        assert np.abs(dx - want).max() <= 1e-4 * np.abs(want).max(), ("bwd_data, worst element", li)
+        del dx, want
         dw, db = net.conv_backward_weight(li, x, dy, wt.shape)
-        dw = dw.cpu().numpy()
-        got, want = [], []
-        for (o, c, r, q) in _sample_idx(rng, wt.shape, 40):
-            g = o // og
-            patch = xp[:, g * cg + c, r:r + s_ * ho:s_, q:q + s_ * wo:s_]
-            want.append(float((patch * dy[:, o].astype(np.float64)).sum())); got.append(dw[o, c, r, q])
-        assert rel_l2(got, want) <= TENSOR_RTOL, ("bwd_weight", li, rel_l2(got, want))
-        assert rel_l2(db.cpu().numpy(), dy.astype(np.float64).sum((0, 2, 3))) <= TENSOR_RTOL
-        del x, dy, xp, y, dx
+        want_dw, want_db = O.conv_backward_weight(x, dy, k, cv.stride, cv.pad, cv.groups)
+        assert rel_l2(dw.cpu().numpy(), want_dw) <= TENSOR_RTOL, ("bwd_weight", li, rel_l2(dw.cpu().numpy(), want_dw))
+        assert np.abs(dw.cpu().numpy() - want_dw).max() <= 1e-4 * np.abs(want_dw).max(), ("bwd_weight, worst element", li)
+        assert rel_l2(db.cpu().numpy(), want_db) <= TENSOR_RTOL
+        del x, dy, want_dw
     net.close()
 
 
@@ -131,7 +132,7 @@ def test_full_alexnet_bf16_step_batch256(lib):
     margin a bf16 forward pass needs (3e-2 of the tensor's rms)."""
     errs = {}
     loss = run_step_and_compare(lib, S.ALEXNET, 256, seed=S.SEED_BASE + 4, bias=0.0, std=0.01, use_raw=True,
-                                precision=1, direct=False, loss_rtol=1e-2, tol=2e-2, tau=3e-2, max_frac=3e-2,
+                                precision=1, direct=False, loss_rtol=1e-2, tol=2e-2,
                                 report=errs)
     print("bf16 batch 256: loss", loss, "worst gradient rel-L2", max(errs.values()), flush=True)
     assert abs(loss - np.log(1000)) < 0.05

@@ -68,6 +68,76 @@ def test_lrn_forward_backward(lib, wl, batch):
     net.close()
 
 
+def _lrn_tie_heavy(shape, seed):
+    """Post-ReLU activations whose *normalised* values tie exactly inside pooling windows: zero blocks
+    (all-zero windows: the first tap must win), and whole pixels (all channels) copied onto their right
+    and lower neighbours, so that equal channel vectors give bit-equal normalised values in one window."""
+    rng = np.random.default_rng(seed)
+    a = np.maximum(rng.standard_normal(shape).astype(np.float32) * 40.0, 0)
+    n, c, h, w = shape
+    a[:, :, : h // 3, : w // 2] = 0.0
+    a[:, :, 1::4, :] = a[:, :, 0:h - 1:4, :][:, :, : a[:, :, 1::4, :].shape[2], :]   # row y+1 := row y
+    a[:, :, :, 2::5] = a[:, :, :, 1:w - 1:5][:, :, :, : a[:, :, :, 2::5].shape[3]]   # column x+1 := column x
+    return a
+
+
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 3), (S.TINY, 2), (S.ALEXNET, 128)])
+def test_fused_lrn_pool_kernels_of_the_training_step(lib, wl, batch):
+    """The kernels a training step runs for conv1 and conv2 -- normalisation + pool in one pass, and pool
+    adjoint + normalisation adjoint + ReLU gate + bias sums in one pass -- through entry points of their
+    own, at the layers' real shapes.
+    Forward: the pooled values and winning taps must be, bit for bit, the oracle's first-maximum pool of the
+    fp32 normalised tensor (which the separate normalisation kernel gives, itself within 2e-5 of the float64
+    normalisation); the inputs tie exactly in most windows.
+    Backward: against the float64 adjoints evaluated with those same winners."""
+    net = lib.AlexNet(wl, batch)
+    spec = oracle_spec(wl, batch)
+    stages, _ = O.layer_shapes(spec)
+    ran = 0
+    for li, (cv, st) in enumerate(zip(spec.conv, stages), start=1):
+        if not (cv.lrn and cv.pool):
+            continue
+        c, h, w = st["conv"]
+        for kind, a in (("ties", _lrn_tie_heavy((batch, c, h, w), 900 + li)),
+                        ("normal", np.maximum(S.make_normal((batch, c, h, w), 910 + li, std=60.0), 0))):
+            try:
+                y, arg = net.lrn_pool_forward(li, a)
+            except lib.AlexNetError as e:
+                assert e.code == lib.ENOTIMPL and c % 4, (li, str(e))  # only channel counts the kernel cannot take
+                continue
+            ran += 1
+            y, arg = y.cpu().numpy(), arg.cpu().numpy()
+            b32 = net.lrn_forward(li, a).cpu().numpy()
+            want_b, s = O.lrn_forward(a, spec.lrn_n, spec.lrn_k, spec.lrn_alpha, spec.lrn_beta)
+            assert rel_l2(b32, want_b) <= OP_RTOL, (li, kind)
+            want_y, want_arg = O.maxpool_forward(b32, 3, 2)
+            if kind == "ties":  # the input really ties: most windows hold their maximum more than once
+                taps = np.stack([b32[:, :, r:r + 2 * want_y.shape[2]:2, q:q + 2 * want_y.shape[3]:2]
+                                 for r in range(3) for q in range(3)])
+                assert ((taps == want_y[None]).sum(0) > 1).mean() > 0.3
+            assert np.array_equal(y, want_y), (li, kind, "pooled values")
+            assert np.array_equal(arg, want_arg), (li, kind, "winning taps")
+            assert rel_l2(y, O.maxpool_forward(want_b, 3, 2)[0]) <= OP_RTOL, (li, kind)
+            dy = S.make_normal(want_y.shape, 920 + li)
+            for gate in (True, False):
+                da, db = net.pool_lrn_backward(li, a, dy, relu_gate=gate)
+                da, db = da.cpu().numpy(), db.cpu().numpy()
+                d = O.maxpool_backward(dy, want_arg, (h, w))
+                want_da = O.lrn_backward(d, a, s, spec.lrn_n, spec.lrn_alpha, spec.lrn_beta)
+                if gate:
+                    want_da = want_da * (a > 0)
+                assert rel_l2(da, want_da) <= OP_RTOL, (li, kind, gate, rel_l2(da, want_da))
+                assert rel_l2(db, want_da.sum((0, 2, 3))) <= OP_RTOL, (li, kind, gate)
+                if gate:
+                    assert np.all(da[a <= 0] == 0)
+                # and the two-kernel route of the single operators gives the same numbers
+                d32 = net.pool_backward(li, b32, dy, relu_gate=False)
+                da2 = net.lrn_backward(li, a, d32, relu_gate=gate).cpu().numpy()
+                assert rel_l2(da, da2) <= 1e-6, (li, kind, gate)
+    assert ran >= 2 or wl is not S.ALEXNET
+    net.close()
+
+
 @pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 7), (S.ODD, 3), (S.ALEXNET, 128)])
 def test_dense_layers_alone(lib, wl, batch):
     net = lib.AlexNet(wl, batch)

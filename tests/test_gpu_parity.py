@@ -1,8 +1,6 @@
 """GPU parity: every call goes through the C ABI and is compared with the
 float64 oracle on the same seeded inputs."""
-import contextlib
 import math
-import os
 
 import numpy as np
 import pytest
@@ -39,26 +37,16 @@ def test_param_roundtrip_is_bit_exact(lib):
 
 
 # ---------------------------------------------------- single conv layers ----
-@contextlib.contextmanager
-def conv_path(direct):
-    """The library reads ALEXNET_DIRECT_CONV when a handle is created: "1" keeps the 3x3 unit-stride stages
-    on the direct implicit GEMM instead of the tile-transform path."""
-    old = os.environ.get("ALEXNET_DIRECT_CONV")
-    os.environ["ALEXNET_DIRECT_CONV"] = "1" if direct else "0"
-    try:
-        yield
-    finally:
-        if old is None:
-            del os.environ["ALEXNET_DIRECT_CONV"]
-        else:
-            os.environ["ALEXNET_DIRECT_CONV"] = old
+def conv_flags(lib, direct):
+    """ALEXNET_FLAG_DIRECT_CONV in the configuration keeps the 3x3 and 5x5 unit-stride stages on the direct
+    implicit GEMM instead of the tile-transform path."""
+    return lib.FLAG_DIRECT_CONV if direct else 0
 
 
 @pytest.mark.parametrize("direct", [False, True], ids=["transformed3x3", "direct3x3"])
 @pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5), (S.PADS, 3), (S.ODD, 3)])
 def test_conv_layers_alone(lib, wl, batch, direct):
-    with conv_path(direct):
-        net = lib.AlexNet(wl, batch)
+    net = lib.AlexNet(wl, batch, flags=conv_flags(lib, direct))
     spec = oracle_spec(wl, batch)
     for li, (cv, st) in enumerate(zip(spec.conv, stage_io_shapes(spec)), start=1):
         cin, h, w = st["in"]
@@ -83,14 +71,12 @@ def test_conv_layers_alone(lib, wl, batch, direct):
 
 
 def test_3x3_and_5x5_stages_take_the_transform_path_by_default(lib):
-    """Same inputs through a default handle and through one created with ALEXNET_DIRECT_CONV=1: both
+    """Same inputs through a default handle and through one created with ALEXNET_FLAG_DIRECT_CONV: both
     within the bar of the oracle, but not bit-identical where the default handle takes the transformed
     path -- different arithmetic -- and bit-identical elsewhere."""
     wl, batch = S.MIDI, 5
-    with conv_path(False):
-        a = lib.AlexNet(wl, batch)
-    with conv_path(True):
-        b = lib.AlexNet(wl, batch)
+    a = lib.AlexNet(wl, batch)
+    b = lib.AlexNet(wl, batch, flags=lib.FLAG_DIRECT_CONV)
     spec = oracle_spec(wl, batch)
     for li, (cv, st) in enumerate(zip(spec.conv, stage_io_shapes(spec)), start=1):
         cin, h, w = st["in"]
@@ -178,8 +164,8 @@ def test_train_step_equals_its_parts_without_the_early_update(lib, wl):
 
 
 def test_mini_three_steps_with_direct_3x3_stages(lib):
-    with conv_path(True):
-        run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01)
+    run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01,
+                         flags=lib.FLAG_DIRECT_CONV)
 
 
 # --------------------------------------------------------- preprocess -------

@@ -71,6 +71,13 @@ def test_bad_arguments_are_reported_not_crashed(B):
     with pytest.raises(B.AlexNetError) as e:
         B.query(cfg)
     assert e.value.code == B.EINVAL
+    # flags: the direct-convolution choice is part of the configuration (it changes the workspace), unknown bits are refused
+    _, ws_default = B.query(B.make_config(S.ALEXNET, 128))
+    _, ws_direct = B.query(B.make_config(S.ALEXNET, 128, flags=B.FLAG_DIRECT_CONV))
+    assert ws_direct < ws_default
+    with pytest.raises(B.AlexNetError) as e:
+        B.query(B.make_config(S.MINI, 4, flags=2))
+    assert e.value.code == B.EINVAL and "flags" in str(e.value)
     # null handles / pointers on calls that would otherwise enqueue work
     for fn, args in [("alexnet_train_step", (None, 0, None, 0, None, None)),
                      ("alexnet_average_replicas", (None, None, None)),
