@@ -78,11 +78,20 @@ static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int
 // Algorithmic flops of the launch being prepared (2 x multiply-adds of the
 // operation, not of the padded GEMM); 0 means "use 2*M*N*K".
 static thread_local double g_algo_flops = 0;
+// Algorithmic bytes of the same launch: every operand tensor read once and the result written once (for a
+// convolution the activation tensor itself, not its im2col expansion); 0 means "(M*K + K*N + M*N) floats".
+static thread_local double g_algo_bytes = 0;
 struct AlgoFlops {
-  explicit AlgoFlops(double f) { g_algo_flops = f; }
-  ~AlgoFlops() { g_algo_flops = 0; }
+  explicit AlgoFlops(double f, double b = 0) { g_algo_flops = f; g_algo_bytes = b; }
+  ~AlgoFlops() { g_algo_flops = 0; g_algo_bytes = 0; }
 };
 static inline double conv_flops(const ConvGeom& c) { return 2.0 * c.P() * c.Cout * c.cg() * c.k * c.k; }
+static inline double conv_bytes(const ConvGeom& c) {
+  return 4.0 * ((double)c.in_elems() + (double)c.w_elems() + (double)c.out_elems());
+}
+static inline double gemm_bytes(int M, int N, int K, int groups) {
+  return g_algo_bytes > 0 ? g_algo_bytes : 4.0 * groups * ((double)M * K + (double)K * N + (double)M * N);
+}
 
 template <class T, class AL, class BL, class Epi>
 static int launch_tile(const typename AL::Params& ap, const typename BL::Params& bp, const Epi& ep, int M, int N, int K,
@@ -93,7 +102,8 @@ static int launch_tile(const typename AL::Params& ap, const typename BL::Params&
     set_error("GEMM grid too large (%u,%u,%u)", grid.x, grid.y, grid.z);
     return ALEXNET_ESHAPE;
   }
-  KernelScope ks("gemm", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups, 0, st);
+  KernelScope ks("gemm", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups,
+                 gemm_bytes(M, N, K, groups), st);
   hipLaunchKernelGGL((gemm_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), dyn_lds, st, ap, bp, ep, M, N, K, kchunk,
                      nsplit);
   AX_LAUNCH_CHECK();
@@ -109,7 +119,8 @@ static int launch_tile_bf(const typename AL::Params& ap, const typename BL::Para
     set_error("GEMM grid too large (%u,%u,%u)", grid.x, grid.y, grid.z);
     return ALEXNET_ESHAPE;
   }
-  KernelScope ks("gemm_bf16", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups, 0, st);
+  KernelScope ks("gemm_bf16", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups,
+                 gemm_bytes(M, N, K, groups), st);
   hipLaunchKernelGGL((gemm_bf16_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), dyn_lds, st, ap, bp, ep, M, N, K,
                      kchunk, nsplit);
   AX_LAUNCH_CHECK();
@@ -339,7 +350,7 @@ static int launch_conv_run_unpack(const ConvGeom& c, const float* dwrun, float* 
 int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
                     int relu, float* y, float* ws, hipStream_t st) {
   const bool run = wrun && run_mode(c) && c.Cout % 4 == 0;
-  AlgoFlops af(conv_flops(c));
+  AlgoFlops af(conv_flops(c), conv_bytes(c));
   GemmDims d = fwd_dims(c);
   if (run) d.K = run_k(c);
   const bool av = run || fwd_A_vec(c, x), bv = run || fwd_B_vec(c, wf);
@@ -397,7 +408,7 @@ static int launch_conv_bwd_data_phases(const ConvGeom& c, const float* dy, const
     AX_LAUNCH_CHECK();
   }
   const GemmDims d = phase_dims(c);
-  AlgoFlops af(conv_flops(c));
+  AlgoFlops af(conv_flops(c), conv_bytes(c));
   GemmPlan p = plan_gemm(d.M, d.N, d.K, 1, 0, 1, false);  // never split: the epilogue scatters; fp32 only
   return by_tile<ConvGather<IM2COL_T1>>(p, true, true, phase_A(c, dy), phase_B(c, wphase), phase_epilogue(c, dx), d,
                                         st);
@@ -407,7 +418,7 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
                          const float* gate, float* dx, float* ws, hipStream_t st) {
   if (wphase && !gate && conv_phase_mode(c) && aligned16(dy)) return launch_conv_bwd_data_phases(c, dy, wf, wphase, dx, st);
   const GemmDims d = bwdd_dims(c);
-  AlgoFlops af(conv_flops(c));
+  AlgoFlops af(conv_flops(c), conv_bytes(c));
   const bool av = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb), bv = bwdd_B_vec(c, wb);
   const bool bf = g_bf16 && av && bv && c.stride == 1;
   const Im2colParams a = bwdd_A(c, dy);
@@ -443,7 +454,7 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
                            hipStream_t st, int* defer_ns) {
   const bool run = dwrun && run_mode(c) && bwdw_B_vec(c, dy);
-  AlgoFlops af(conv_flops(c));
+  AlgoFlops af(conv_flops(c), conv_bytes(c));
   GemmDims d = bwdw_dims(c);
   if (run) d.M = run_k(c);
   const bool av = run || bwdw_A_vec(c, x), bv = bwdw_B_vec(c, dy);

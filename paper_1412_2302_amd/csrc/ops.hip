@@ -218,6 +218,11 @@ __global__ void lrn_bwd_kernel(const float* __restrict__ a, const float* __restr
 // the per-channel terms dy*a*s^(-beta-1)) are staged in LDS rows that carry
 // `half` zeros on both sides, so the clipped window needs no branches and every
 // tensor is read from and written to HBM exactly once with 16-byte accesses.
+// x*x as a rounded product of its own: the pragma keeps the compiler from contracting it into a later sum
+__device__ __forceinline__ float sq_rounded(float x) {
+#pragma clang fp contract(off)
+  return x * x;
+}
 constexpr int kLrnMaxHalf = 4;
 constexpr int kLrnPad = 4;  // zeros on both sides of an LDS row; keeps 16-byte alignment
 // sums of v[4+j-half .. 4+j+half] for j = 0..3, each added up directly (v = values of channels c-4 .. c+7)
@@ -441,9 +446,12 @@ lrn_pool_fwd_kernel(const float* __restrict__ a, float* __restrict__ y, uint8_t*
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int pxl = pxl0 + u * PB;
-        const float v[12] = {l[u].x * l[u].x, l[u].y * l[u].y, l[u].z * l[u].z, l[u].w * l[u].w,
-                             m[u].x * m[u].x, m[u].y * m[u].y, m[u].z * m[u].z, m[u].w * m[u].w,
-                             h[u].x * h[u].x, h[u].y * h[u].y, h[u].z * h[u].z, h[u].w * h[u].w};
+        // rounded squares (no contraction into the window sums): the separate normalisation kernel adds
+        // squares that went through LDS, and the two must give the same bits for the same input
+        const float v[12] = {sq_rounded(l[u].x), sq_rounded(l[u].y), sq_rounded(l[u].z),
+                             sq_rounded(l[u].w), sq_rounded(m[u].x), sq_rounded(m[u].y),
+                             sq_rounded(m[u].z), sq_rounded(m[u].w), sq_rounded(h[u].x),
+                             sq_rounded(h[u].y), sq_rounded(h[u].z), sq_rounded(h[u].w)};
         const float4 w = lrn_window_sum_regs(v, half);
         if (pxl < np)
           *reinterpret_cast<float4*>(bbuf + (size_t)pxl * C + c) = make_float4(

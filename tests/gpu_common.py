@@ -12,6 +12,17 @@ LOSS_RTOL = 1e-4
 TENSOR_RTOL = 1e-3
 
 
+# ReLU gates and pooling winners: a bf16 forward pass moves pre-activations by ~1e-3 of their
+# scale, so more of them change side than in fp32; the window in which the library's choices may
+# differ from the oracle's is derived from the forward error measured in the same run
+# (gpu_common.validated_decisions), so it widens by itself.  With those validated choices held fixed the
+# gradients meet the 2e-2 bar; against the oracle's own choices (nothing of the library's enters the oracle)
+# about 0.1 % of the units gate differently and each such unit moves its gradient tensor and every one
+# below it: measured 3-16 % on these nets and 5-22 % at batch 256, so that comparison only guards against
+# gross errors.
+BF16_OWN_DECISIONS_RTOL = 0.5
+
+
 def build_pair(binding, wl, batch, seed, bias=0.0, std=0.01, pseed=1, mom_std=0.0, precision=0, flags=0):
     """Returns (net, spec, params64, mom64): a HIP replica and the oracle's
     view of the same float32 parameters."""
@@ -158,7 +169,7 @@ def check_forward(lib, net, spec, cache, batch, tol=TENSOR_RTOL):
 
 
 def run_step_and_compare(lib, wl, batch, seed, bias, std, use_raw, steps=1, mom_std=0.0, direct=True, precision=0,
-                         loss_rtol=LOSS_RTOL, tol=TENSOR_RTOL, direct_tol=None, report=None, flags=0):
+                         loss_rtol=LOSS_RTOL, tol=TENSOR_RTOL, direct_tol=None, report=None, flags=0, flip_report=None, direct_report=None):
     """Runs `steps` SGD steps in the library and in the oracle and compares loss,
     forward tensors, gradients, updated weights and momentum.
 
@@ -187,6 +198,8 @@ def run_step_and_compare(lib, wl, batch, seed, bias, std, use_raw, steps=1, mom_
         loss_ref, p_new, m_new, g_ref, cache = O.train_step(
             spec, p64, m64, x64, labels, step, decisions=validated_decisions(lib, net, spec, report=flips))
         assert abs(got_loss - loss_ref) <= loss_rtol * abs(loss_ref), (step, got_loss, loss_ref)
+        if flip_report is not None:
+            flip_report[step] = flips
         check_forward(lib, net, spec, cache, batch, tol)
         net.apply_update()
         pn, mn = net.get_params(), net.get_momentum()
@@ -195,13 +208,15 @@ def run_step_and_compare(lib, wl, batch, seed, bias, std, use_raw, steps=1, mom_
             assert rel_l2(g[k], g_ref[k]) <= tol, ("grad", k, rel_l2(g[k], g_ref[k]))
             if report is not None:
                 report[k] = max(report.get(k, 0.0), rel_l2(g[k], g_ref[k]))
-                report["flips"] = flips
             assert rel_l2(pn[k], p_new[k]) <= tol, ("param", k)
             assert rel_l2(mn[k], m_new[k]) <= tol, ("momentum", k, rel_l2(mn[k], m_new[k]))
         if direct:
             _, _, _, g_own, _ = O.train_step(spec, p64, m64, x64, labels, step)
             for k in g_own:
-                assert rel_l2(g[k], g_own[k]) <= direct_tol, ("grad vs oracle's own decisions", k, flips)
+                e_own = rel_l2(g[k], g_own[k])
+                if direct_report is not None:
+                    direct_report[k] = max(direct_report.get(k, 0.0), e_own)
+                assert e_own <= direct_tol, ("grad vs oracle's own decisions", k, e_own, flips)
         # continue from the library's own fp32 state so that errors do not pile up across steps
         p64, m64 = to64(pn), to64(mn)
     net.close()

@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 import synthetic_inputs as S
-from gpu_common import build_pair, cuda, run_step_and_compare
+from gpu_common import BF16_OWN_DECISIONS_RTOL, build_pair, cuda, run_step_and_compare
 from helpers import oracle_spec, rel_l2
 from oracle import alexnet_oracle as O
 
@@ -114,32 +114,28 @@ def test_bf16_dense_layers_alone(lib):
     net.close()
 
 
-# ReLU gates and pooling winners: a bf16 forward pass moves pre-activations by ~1e-3 of their
-# scale, so more of them change side than in fp32; the window in which the library's choices may
-# differ from the oracle's is derived from the forward error measured in the same run
-# (gpu_common.validated_decisions), so it widens by itself.
 
 
 def test_bf16_mini_alexnet_step(lib):
-    errs = {}
-    loss = run_step_and_compare(lib, S.MINI, 4, seed=11, bias=0.0, std=0.01, use_raw=False, precision=1, direct=False,
+    errs, own = {}, {}
+    loss = run_step_and_compare(lib, S.MINI, 4, seed=11, bias=0.0, std=0.01, use_raw=False, precision=1, direct=True, direct_tol=BF16_OWN_DECISIONS_RTOL, direct_report=own,
                                 loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
-    print(errs)
+    print(errs, 'decision-free:', own)
     assert abs(loss - math.log(10)) < 1e-2
 
 
 def test_bf16_mini_three_steps_with_signal_everywhere(lib):
-    errs = {}
+    errs, own = {}, {}
     run_step_and_compare(lib, S.MINI, 6, seed=12, bias=0.1, std=0.08, use_raw=False, steps=3, mom_std=0.01,
-                         precision=1, direct=False, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
-    print(errs)
+                         precision=1, direct=True, direct_tol=BF16_OWN_DECISIONS_RTOL, direct_report=own, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
+    print(errs, 'decision-free:', own)
 
 
 def test_bf16_midi_net_with_preprocess(lib):
-    errs = {}
+    errs, own = {}, {}
     run_step_and_compare(lib, S.MIDI, 7, seed=13, bias=0.05, std=0.02, use_raw=True, steps=2, mom_std=0.01,
-                         precision=1, direct=False, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
-    print(errs)
+                         precision=1, direct=True, direct_tol=BF16_OWN_DECISIONS_RTOL, direct_report=own, loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
+    print(errs, 'decision-free:', own)
 
 
 def test_bf16_falls_back_to_fp32_products_where_sizes_are_no_multiples_of_four(lib):

@@ -115,7 +115,8 @@ def test_fused_lrn_pool_kernels_of_the_training_step(lib, wl, batch):
                 taps = np.stack([b32[:, :, r:r + 2 * want_y.shape[2]:2, q:q + 2 * want_y.shape[3]:2]
                                  for r in range(3) for q in range(3)])
                 assert ((taps == want_y[None]).sum(0) > 1).mean() > 0.3
-            assert np.array_equal(y, want_y), (li, kind, "pooled values")
+            assert np.array_equal(y, want_y), (li, kind, "pooled values", int((y != want_y).sum()), y.size,
+                                               float(np.abs(y - want_y).max()), float(np.abs(want_y).max()))
             assert np.array_equal(arg, want_arg), (li, kind, "winning taps")
             assert rel_l2(y, O.maxpool_forward(want_b, 3, 2)[0]) <= OP_RTOL, (li, kind)
             dy = S.make_normal(want_y.shape, 920 + li)
