@@ -1,7 +1,10 @@
-"""Summarises rocprofv3 hardware-counter runs of bench.py into the text and JSON kept under profiles/.
+"""Summarises rocprofv3 runs of bench.py into the text and JSON kept under profiles/.
 
     python -m paper_1412_2302_amd.pmc_summary --key fp32_b128 --fetch F.csv --write W.csv [--mfma M.csv]
-        --command "<the rocprofv3 command line>" --txt profiles/<name>.txt [--json profiles/gemm_traffic.json]
+        --command "<the rocprofv3 command lines, ';;' between them>" --txt profiles/<name>.txt
+        [--json profiles/gemm_traffic.json]
+    python -m paper_1412_2302_amd.pmc_summary --key fp32_b128 --trace kt_kernel_stats.csv
+        --command "<the rocprofv3 --kernel-trace --stats command line>" --txt profiles/<name>.txt
 
 F.csv / W.csv / M.csv are the *_counter_collection.csv files of three `rocprofv3 --pmc` runs of
 `bench.py --only-step --traffic-calibration ...` collecting FETCH_SIZE, WRITE_SIZE and
@@ -43,16 +46,44 @@ def _scaled(path, counter):
     return cal, factor, agg
 
 
+def trace_summary(a):
+    rows = list(csv.DictReader(open(a.trace)))
+    tot = sum(float(r["TotalDurationNs"]) for r in rows)
+    lines = [f"rocprofv3 kernel trace, configuration {a.key}", "", "Command:", "  " + a.command.strip(), "",
+             f"{'kernel':102s} {'calls':>6s} {'total ms':>9s} {'avg us':>9s} {'min us':>8s} {'max us':>8s} {'%':>6s}"]
+    g_calls = g_ns = 0
+    for r in sorted(rows, key=lambda r: -float(r["TotalDurationNs"])):
+        k, c, t = _short(r["Name"]), int(r["Calls"]), float(r["TotalDurationNs"])
+        if t / tot < 0.001:
+            continue
+        lines.append(f"{k:102s} {c:6d} {t / 1e6:9.3f} {float(r['AverageNs']) / 1e3:9.2f} {float(r['MinNs']) / 1e3:8.2f} "
+                     f"{float(r['MaxNs']) / 1e3:8.2f} {100 * t / tot:6.2f}")
+        if k.startswith("gemm"):
+            g_calls += c
+            g_ns += t
+    lines += ["", f"total kernel time {tot / 1e6:.3f} ms",
+              f"all GEMM instantiations together: {g_calls} launches, {g_ns / 1e6:.3f} ms, average {g_ns / max(g_calls, 1) / 1e3:.2f} us per launch"]
+    os.makedirs(os.path.dirname(os.path.abspath(a.txt)), exist_ok=True)
+    with open(a.txt, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines[-2:]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--key", required=True)
-    ap.add_argument("--fetch", required=True)
-    ap.add_argument("--write", required=True)
+    ap.add_argument("--trace", help="the *_kernel_stats.csv of a `rocprofv3 --kernel-trace --stats` run")
+    ap.add_argument("--fetch")
+    ap.add_argument("--write")
     ap.add_argument("--mfma")
     ap.add_argument("--command", required=True)
     ap.add_argument("--txt", required=True)
     ap.add_argument("--json")
     a = ap.parse_args()
+    if a.trace:
+        return trace_summary(a)
+    if not (a.fetch and a.write):
+        raise SystemExit("--fetch and --write (or --trace) are required")
     cal_r, f_r, rd = _scaled(a.fetch, "FETCH_SIZE")
     cal_w, f_w, wr = _scaled(a.write, "WRITE_SIZE")
     util = {}
