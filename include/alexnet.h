@@ -314,6 +314,23 @@ int alexnet_fc_backward(alexnet_t* net, int32_t layer, const float* d_x, const f
 int alexnet_softmax_xent(alexnet_t* net, const float* d_logits, const int32_t* d_labels, float* d_dz,
                          float* d_loss, void* stream);
 
+/* alexnet_softmax_xent for callers that cannot allocate device memory or keep a
+ * handle's workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernels and same results as
+ * alexnet_softmax_xent, but no handle: the per-row losses and the label flag
+ * live in an array built into the library's device code (16.6 KB per GPU, held
+ * until the process ends), and the call allocates nothing.
+ *   d_logits [batch][classes], d_labels [batch] -> d_dz [batch][classes] =
+ *   (softmax - onehot)/batch, d_loss[0] = mean loss, and, when d_bad_label is
+ *   not null, d_bad_label[0] = 1 if a label was outside [0, classes) (such a
+ *   label is clamped for the arithmetic), else 0.  All device pointers.
+ * batch <= 4096, else ALEXNET_ENOMEM (use the handle-based call).  Every call
+ * on one GPU shares that GPU's array: calls that overlap in time on one GPU
+ * (different streams without ordering) race on it; calls on one stream, or
+ * ordered by events, are safe, and each clears what it needs first. */
+int alexnet_softmax_xent_static(const float* d_logits, const int32_t* d_labels, int32_t batch, int32_t classes,
+                                float* d_dz, float* d_loss, int32_t* d_bad_label, void* stream);
+
 /* --- per-kernel timing (measurement aid; not part of the training path) ---
  * Between alexnet_profile_begin and alexnet_profile_end every kernel the
  * calling thread launches through this library is bracketed by two HIP events

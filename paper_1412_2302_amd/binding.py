@@ -95,6 +95,7 @@ _SIGS.update({
     "alexnet_fc_forward": [_vp, _i32, _vp, _vp, _vp, _i32, _vp, _vp],
     "alexnet_fc_backward": [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "alexnet_softmax_xent": [_vp, _vp, _vp, _vp, _vp, _vp],
+    "alexnet_softmax_xent_static": [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp],
 })
 _SIGS["alexnet_profile_begin"] = []
 _SIGS["alexnet_profile_end"] = [C.POINTER(ProfEntry), _i32, C.POINTER(_i32)]
@@ -536,6 +537,20 @@ class Loader:
 
     def __del__(self):
         self.close()
+
+
+def softmax_xent_static(logits: torch.Tensor, labels: torch.Tensor, dz: torch.Tensor, loss: torch.Tensor,
+                        bad_label: Optional[torch.Tensor] = None, stream=None):
+    """alexnet_softmax_xent_static: no handle, no workspace; every tensor is the caller's."""
+    batch, classes = logits.shape
+    _need(logits, torch.float32, batch * classes, "softmax_xent_static: logits")
+    _need(labels, torch.int32, batch, "softmax_xent_static: labels")
+    _need(dz, torch.float32, batch * classes, "softmax_xent_static: dz")
+    _need(loss, torch.float32, 1, "softmax_xent_static: loss")
+    if bad_label is not None:
+        _need(bad_label, torch.int32, 1, "softmax_xent_static: bad_label")
+    _check(_lib.alexnet_softmax_xent_static(_ptr(logits), _ptr(labels), batch, classes, _ptr(dz), _ptr(loss),
+                                            _ptr(bad_label), _stream(stream)))
 
 
 def average_gradients_update(a: AlexNet, b: AlexNet, stream=None):

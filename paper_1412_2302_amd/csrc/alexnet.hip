@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <string>
 #include <utility>
@@ -1159,6 +1160,54 @@ int alexnet_softmax_xent(alexnet_t* n, const float* d_logits, const int32_t* d_l
   const int B = n->cfg.batch, classes = n->fc[kFc - 1].out;
   AX_TRY(launch_softmax_xent(d_logits, d_labels, B, classes, 0, d_dz, n->row_loss, n->err_flag, S(stream)));
   return launch_mean_loss(n->row_loss, B, d_loss, S(stream));
+}
+
+// ---- softmax cross-entropy for callers that cannot allocate ------------------
+// Scratch of alexnet_softmax_xent_static: the per-row losses of one call, then the label flag.  One copy per
+// GPU, held until the process ends; every call on a GPU shares it.
+constexpr int kStaticMaxRows = 4096;
+static __device__ __align__(256) float scratch[kStaticMaxRows + 64];
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, looked up once
+static std::mutex g_scratch_mu;
+
+static int static_scratch(float** out) {
+  int dev = -1;
+  AX_HIP(hipGetDevice(&dev));
+  REQUIRE(dev >= 0 && dev < kMaxDevices, ALEXNET_EINVAL, "alexnet_softmax_xent_static: device index out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    // in host code `scratch` is only a handle of the symbol: its address on the current device comes from the
+    // runtime, and each GPU has its own
+    float* p = nullptr;
+    AX_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    REQUIRE(p, ALEXNET_EHIP, "alexnet_softmax_xent_static: no device address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return ALEXNET_OK;
+}
+
+int alexnet_softmax_xent_static(const float* d_logits, const int32_t* d_labels, int32_t batch, int32_t classes,
+                                float* d_dz, float* d_loss, int32_t* d_bad_label, void* stream) {
+  REQUIRE(d_logits && d_labels && d_dz && d_loss, ALEXNET_EINVAL, "alexnet_softmax_xent_static: null argument");
+  REQUIRE(batch >= 1 && classes >= 1, ALEXNET_ESHAPE, "alexnet_softmax_xent_static: batch and classes must be positive");
+  if (batch > kStaticMaxRows) {
+    set_error("alexnet_softmax_xent_static: batch %d exceeds the %d rows of the built-in scratch; use "
+              "alexnet_softmax_xent with a handle's workspace", batch, kStaticMaxRows);
+    return ALEXNET_ENOMEM;
+  }
+  REQUIRE((long)batch * classes <= 0x1ffffff0L, ALEXNET_ESHAPE, "alexnet_softmax_xent_static: logits reach 2 GiB");
+  float* ws = nullptr;
+  AX_TRY(static_scratch(&ws));
+  float* row_loss = ws;
+  int32_t* flag = reinterpret_cast<int32_t*>(ws + kStaticMaxRows);
+  // the flag must start at zero; a fill kernel rather than a memset node, so that the call can be captured
+  AX_TRY(launch_fill_bytes(flag, 4, S(stream)));
+  AX_TRY(launch_softmax_xent(d_logits, d_labels, batch, classes, 0, d_dz, row_loss, flag, S(stream)));
+  AX_TRY(launch_mean_loss(row_loss, batch, d_loss, S(stream)));
+  if (d_bad_label) AX_TRY(launch_copy(reinterpret_cast<const float*>(flag), reinterpret_cast<float*>(d_bad_label), 1, S(stream)));
+  return ALEXNET_OK;
 }
 
 }  // extern "C"
