@@ -89,6 +89,11 @@ struct Stage {
   bool wino_bx;  // data gradient too
   float *wino_v, *wino_u, *wino_ub;
   float *wrun, *dwrun;  // run-mode copies of the weights and their gradient (null when not used)
+  // bf16 handles: copies in bf16 (nearest even) of the stage's GEMM operands -- input, output gradient, and the
+  // forward and backward-data weights with the reduction contiguous, wf16[g][o][(r,s,c)], wb16[g][c][(r,s,o)] --
+  // which the products then read instead of rounding fp32 values on the fly
+  bool b16;
+  uint16_t *x16, *dy16, *wf16, *wb16;
   uint8_t* slot;
   char lab[4][16];  // profiling labels: stage, .fwd, .bwd_w, .bwd_x
   long act_elems() const { return g.out_elems(); }
@@ -265,6 +270,11 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.wphase = conv_phase_mode(s.g) ? a.take<float>(conv_phase_w_floats(s.g)) : nullptr;
     s.wrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     s.dwrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
+    s.b16 = c.precision == ALEXNET_PRECISION_BF16 && conv_bf16_stored_ok(s.g) && s.w_off % 4 == 0;
+    s.x16 = s.b16 ? a.take<uint16_t>(s.g.in_elems()) : nullptr;
+    s.dy16 = s.b16 ? a.take<uint16_t>(ae) : nullptr;
+    s.wf16 = s.b16 ? a.take<uint16_t>(s.g.w_elems()) : nullptr;
+    s.wb16 = s.b16 ? a.take<uint16_t>(s.g.w_elems()) : nullptr;
     s.wino = use_winograd(c, s.g) && s.w_off % 4 == 0 && s.b_off % 4 == 0;
     s.wino_bx = s.wino && wino_bwd_data_ok(s.g);
     s.wino_v = s.wino ? a.take<float>(wino_v_floats(s.g)) : nullptr;
@@ -355,37 +365,64 @@ static uint32_t drop_thresh(float p) { return (uint32_t)floor((double)p * (doubl
 static bool wino_usable(const Stage& s, const void* a, const void* b, const void* c, const void* d = nullptr) {
   return s.wino && aligned16(a) && aligned16(b) && aligned16(c) && aligned16(d);
 }
-// taps_ready: s.wino_u already holds the transform of wf
+// bf16 handles, stages whose operands have bf16 copies: true when this call can use them
+static bool b16_usable(const Stage& s, const void* a, const void* b) { return s.b16 && aligned16(a) && aligned16(b); }
+
+// taps_ready: the forms of wf that the stage multiplies with are in place already (s.wino_u, the transform of wf;
+// s.wf16, its bf16 copy)
+// x16_ready: s.x16 already holds the bf16 copy of x (the kernel that made x wrote it);
+// y16 (may be null): where to leave a bf16 copy of y for the stage that reads y next
 static int stage_fwd(alexnet* n, Stage& s, const float* x, const float* wf, const float* bias, int relu, float* y,
-                     bool taps_ready, hipStream_t st) {
+                     bool taps_ready, hipStream_t st, bool x16_ready = false, uint16_t* y16 = nullptr) {
   if (wino_usable(s, x, wf, y, bias)) {
     if (!taps_ready) AX_TRY(launch_wino_filter(s.g, wf, s.wino_u, st));
-    return launch_wino_fwd(s.g, x, s.wino_u, bias, relu, y, s.wino_v, n->wino_m, n->gemm_ws, st);
+    AX_TRY(launch_wino_fwd(s.g, x, s.wino_u, bias, relu, y, s.wino_v, n->wino_m, n->gemm_ws, st));
+    return y16 ? launch_to_bf16(y, y16, (size_t)s.g.out_elems(), st) : ALEXNET_OK;
+  }
+  if (b16_usable(s, x, wf)) {
+    if (!x16_ready) AX_TRY(launch_to_bf16(x, s.x16, (size_t)s.g.in_elems(), st));
+    if (!taps_ready) AX_TRY(launch_to_bf16_transposed(wf, s.wf16, s.g.groups, s.g.kf(), s.g.og(), st));
+    return launch_conv_fwd(s.g, x, wf, nullptr, bias, relu, y, n->gemm_ws, st, s.x16, s.wf16, y16);
   }
   if (s.wrun) AX_TRY(launch_conv_run_pack(s.g, wf, s.wrun, st));
-  return launch_conv_fwd(s.g, x, wf, s.wrun, bias, relu, y, n->gemm_ws, st);
+  return launch_conv_fwd(s.g, x, wf, s.wrun, bias, relu, y, n->gemm_ws, st, nullptr, nullptr, y16);
 }
-// have_v: s.wino_v already holds the transform of x (the forward pass of the same minibatch left it there)
+// have_v: the forward pass of the same minibatch left its form of x in place (s.wino_v, the transform of x; s.x16,
+// its bf16 copy)
 // tail: put the end of a transformed stage's weight gradient off to launch_wgrad_tail() (see WgradTail)
+// dy16_ready: s.dy16 already holds the bf16 copy of dy (the kernel that made dy wrote it)
 static int stage_bwd_weight(alexnet* n, Stage& s, const float* x, const float* dy, float* dwf, bool have_v,
-                            hipStream_t st, WgradTail* tail = nullptr) {
+                            hipStream_t st, WgradTail* tail = nullptr, bool dy16_ready = false) {
   if (wino_usable(s, x, dy, dwf)) {
     if (!have_v) AX_TRY(launch_wino_input(s.g, x, s.wino_v, st));
     if (tail) return launch_wino_bwd_weight(s.g, s.wino_v, dy, dwf, n->wino_a, s.wino_du, s.wino_slices, st, tail);
     return launch_wino_bwd_weight(s.g, s.wino_v, dy, dwf, n->wino_a, n->wino_du, n->gemm_ws, st);
   }
+  if (b16_usable(s, x, dy)) {
+    if (!have_v) AX_TRY(launch_to_bf16(x, s.x16, (size_t)s.g.in_elems(), st));
+    if (!dy16_ready) AX_TRY(launch_to_bf16(dy, s.dy16, (size_t)s.g.out_elems(), st));
+    return launch_conv_bwd_weight(s.g, x, dy, dwf, nullptr, n->gemm_ws, st, nullptr, s.x16, s.dy16);
+  }
   return launch_conv_bwd_weight(s.g, x, dy, dwf, s.dwrun, n->gemm_ws, st);
 }
-// taps_ready: s.wino_ub already holds the transform of wb; yt_ready: n->wino_a already holds the transformed
-// output gradient (stage_bwd_weight of the same minibatch ran just before)
+// taps_ready: the forms of wb are in place (s.wino_ub; s.wb16); yt_ready: so is that of dy (n->wino_a, the
+// transformed output gradient; s.dy16): stage_bwd_weight of the same minibatch ran just before
+// dx16 (may be null): where to leave a bf16 copy of dx for the stage below
 static int stage_bwd_data(alexnet* n, Stage& s, const float* dy, const float* wf, const float* wb, float* wphase,
-                          const float* gate, float* dx, bool taps_ready, bool yt_ready, hipStream_t st) {
+                          const float* gate, float* dx, bool taps_ready, bool yt_ready, hipStream_t st,
+                          uint16_t* dx16 = nullptr) {
   if (s.wino_bx && wino_usable(s, dy, wb, dx, gate)) {
     if (!taps_ready) AX_TRY(launch_wino_filter_bwd(s.g, wb, s.wino_ub, st));
     if (!yt_ready) AX_TRY(launch_wino_output_grad(s.g, dy, n->wino_a, st));
-    return launch_wino_bwd_data(s.g, n->wino_a, s.wino_ub, gate, dx, n->wino_m, n->gemm_ws, st);
+    AX_TRY(launch_wino_bwd_data(s.g, n->wino_a, s.wino_ub, gate, dx, n->wino_m, n->gemm_ws, st));
+    return dx16 ? launch_to_bf16(dx, dx16, (size_t)s.g.in_elems(), st) : ALEXNET_OK;
   }
-  return launch_conv_bwd_data(s.g, dy, wf, wb, wphase, gate, dx, n->gemm_ws, st);
+  if (b16_usable(s, dy, wb)) {
+    if (!yt_ready) AX_TRY(launch_to_bf16(dy, s.dy16, (size_t)s.g.out_elems(), st));
+    if (!taps_ready) AX_TRY(launch_to_bf16_transposed(wb, s.wb16, s.g.groups, s.g.kb(), s.g.cg(), st));
+    return launch_conv_bwd_data(s.g, dy, wf, wb, nullptr, gate, dx, n->gemm_ws, st, s.dy16, s.wb16, dx16);
+  }
+  return launch_conv_bwd_data(s.g, dy, wf, wb, wphase, gate, dx, n->gemm_ws, st, nullptr, nullptr, dx16);
 }
 
 // --------------------------------------------------------------- passes ------
@@ -397,21 +434,27 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
   set_gemm_precision(c.precision);
   const float* h = in;
   bool waited = false;
+  bool x16_ready = false;  // the kernel that made h also left its bf16 copy in the next stage's x16
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
+    // bf16 handles: whoever writes this stage's output also writes the bf16 copy the next stage multiplies with
+    uint16_t* next16 = (i + 1 < kStages && n->st[i + 1].b16) ? n->st[i + 1].x16 : nullptr;
     {
       ProfContext pc(s.lab[1]);
-      if (s.wino && taps_ready && !waited) {
+      if ((s.wino || s.b16) && taps_ready && !waited) {
         AX_HIP(hipStreamWaitEvent(st, taps_ready, 0));
         waited = true;
       }
-      AX_TRY(stage_fwd(n, s, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, taps_ready != nullptr, st));
+      AX_TRY(stage_fwd(n, s, h, n->params + s.w_off, n->params + s.b_off, 1, s.act, taps_ready != nullptr, st,
+                       x16_ready, s.plain() ? next16 : nullptr));
     }
+    x16_ready = s.plain() && next16 != nullptr;
     ProfContext pc(s.lab[0]);
     h = s.act;
     if (s.fused()) {  // normalise and pool in one pass; the normalised tensor is only made on request
       AX_TRY(launch_lrn_pool_fwd(s.act, s.pool_out, s.slot, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, c.lrn_n,
-                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, st));
+                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, st, next16));
+      x16_ready = next16 != nullptr;
       h = s.pool_out;
       continue;
     }
@@ -483,10 +526,12 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
                                 last.d_out, n->gemm_ws, st));
     }
   }
+  bool dy16_ready = false;  // the kernel that made this stage's output gradient also left its bf16 copy in s.dy16
   for (int i = kStages - 1; i >= 0; --i) {
     Stage& s = n->st[i];
     ProfContext pc0(s.lab[0]);
     bool bias_done = false;
+    uint16_t* own16 = s.b16 ? s.dy16 : nullptr;
     if (s.fused()) {  // pool adjoint, normalisation adjoint, ReLU gate and the bias gradient's partial sums in one pass
       // the kernel leaves one row of sums per workgroup; those rows are one more matrix for the batch at the end
       float* part = n->colsum_ws + bias_ws_used;
@@ -497,7 +542,8 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
         return ALEXNET_EINVAL;
       }
       AX_TRY(launch_pool_lrn_bwd(s.act, s.d_out, s.slot, s.dact, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, c.lrn_n,
-                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, 1, nullptr, part, st, true));
+                                 c.lrn_k, c.lrn_alpha, c.lrn_beta, 1, nullptr, part, st, true, own16));
+      dy16_ready = own16 != nullptr;
       AX_TRY(colsum_batch_add(bias_sums, part, (long)part_rows, s.g.Cout, n->grads + s.b_off, n->colsum_ws,
                               &bias_ws_used));
       bias_done = true;
@@ -505,11 +551,16 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
       if (s.lrn)
         AX_TRY(launch_pool_bwd(s.d_out, s.slot, nullptr, s.d_lrn, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
       else
-        AX_TRY(launch_pool_bwd(s.d_out, s.slot, s.act, s.dact, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
+      {
+        AX_TRY(launch_pool_bwd(s.d_out, s.slot, s.act, s.dact, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st, own16));
+        dy16_ready = own16 != nullptr;
+      }
     }
-    if (s.lrn && !s.fused())
+    if (s.lrn && !s.fused()) {
       AX_TRY(launch_lrn_bwd(s.act, s.pool ? s.d_lrn : s.d_out, s.dact, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k,
                             c.lrn_alpha, c.lrn_beta, 1, st));
+      dy16_ready = false;
+    }
     // Fork of the dense-layer update (see upd_fork_stage), never in front of this stage's pooling adjoint: that
     // kernel is bound by bandwidth like the update and would be starved by it.
     auto fork_update = [&]() -> int {
@@ -524,7 +575,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
     const float* x = i == 0 ? in : n->st[i - 1].out();
     {
       ProfContext pc(s.lab[2]);
-      AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st, &wgrad_tail));
+      AX_TRY(stage_bwd_weight(n, s, x, s.dact, n->grads + s.w_off, true, st, &wgrad_tail, dy16_ready));
       if (!bias_done)
         AX_TRY(colsum_batch_add(bias_sums, s.dact, s.g.P(), s.g.Cout, n->grads + s.b_off, n->colsum_ws, &bias_ws_used));
     }
@@ -537,8 +588,13 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
       } else {
         AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, st));
       }
+      // a stage below without LRN or pool takes this data gradient as its output gradient as it is
+      uint16_t* below16 = (prev.plain() && prev.b16) ? prev.dy16 : nullptr;
       AX_TRY(stage_bwd_data(n, s, s.dact, n->params + s.w_off, s.wb, s.wphase, prev.plain() ? prev.act : nullptr,
-                            prev.d_out, early_update, true, st));
+                            prev.d_out, early_update, true, st, below16));
+      dy16_ready = below16 != nullptr;
+    } else {
+      dy16_ready = false;
     }
   }
   if (bias_ws_used > n->colsum_ws_floats_) {
@@ -780,6 +836,8 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
       Stage& s = n->st[i];
       ProfContext pc(s.lab[1]);
       if (s.wino) AX_TRY(launch_wino_filter(s.g, n->params + s.w_off, s.wino_u, n->upd_stream));
+      if (s.b16)
+        AX_TRY(launch_to_bf16_transposed(n->params + s.w_off, s.wf16, s.g.groups, s.g.kf(), s.g.og(), n->upd_stream));
     }
     AX_HIP(hipEventRecord(n->ev_u_done, n->upd_stream));
     for (int i = 1; i < kStages; ++i) {
@@ -787,6 +845,7 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
       ProfContext pc(s.lab[3]);
       AX_TRY(launch_conv_weight_wb(n->params + s.w_off, s.wb, s.g.Cout, s.g.cg(), s.g.k, s.g.groups, n->upd_stream));
       if (s.wino_bx) AX_TRY(launch_wino_filter_bwd(s.g, s.wb, s.wino_ub, n->upd_stream));
+      if (s.b16) AX_TRY(launch_to_bf16_transposed(s.wb, s.wb16, s.g.groups, s.g.kb(), s.g.cg(), n->upd_stream));
     }
     AX_HIP(hipEventRecord(n->ev_wb_done, n->upd_stream));
   }

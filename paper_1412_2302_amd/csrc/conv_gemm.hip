@@ -40,16 +40,19 @@ static const TileOption kTileOptions[] = {{128, 128, kBK, 0.80}, {128, 96, kBK, 
 constexpr int kBKbf = 32;
 typedef Tile<128, 128, kBKbf, 2, 2> B128;
 typedef Tile<128, 64, kBKbf, 4, 1> B64;
-static const TileOption kTileOptionsBf[] = {{128, 128, kBKbf, 3.2}, {128, 64, kBKbf, 2.2}};
+// 256 x 128 (wave tile 128 x 64): three fragment reads for every four MFMAs instead of four for four -- these
+// kernels are paced by LDS, not by the matrix cores; only with operands stored as bf16 (half the staging registers)
+typedef Tile<256, 128, kBKbf, 2, 2> B256;
+static const TileOption kTileOptionsBf[] = {{128, 128, kBKbf, 3.2}, {128, 64, kBKbf, 2.2}, {256, 128, kBKbf, 4.2}};
 
 // precision of the GEMMs launched by the calling thread: 0 fp32 MFMA, 1 bf16 MFMA with fp32 accumulation
 static thread_local int g_bf16 = 0;
 void set_gemm_precision(int bf16) { g_bf16 = bf16 ? 1 : 0; }
 
 static GemmPlan plan_gemm(int M, int N, int K, int groups, double out_bytes, int max_s, bool bf = false,
-                          bool allow48 = false, int max_chunk = 0) {
+                          bool allow48 = false, int max_chunk = 0, bool allow256 = false) {
   const TileOption* opts = bf ? kTileOptionsBf : kTileOptions;
-  const int nopts = bf ? 2 : (allow48 ? 4 : 3);
+  const int nopts = bf ? (allow256 ? 3 : 2) : (allow48 ? 4 : 3);
   GemmPlan best{128, 128, 1, ceil_div(K, opts[0].bk) * opts[0].bk};
   double best_t = 1e30;
   for (int o = 0; o < nopts; ++o) {
@@ -114,15 +117,17 @@ template <class T, class AL, class BL, class Epi>
 static int launch_tile_bf(const typename AL::Params& ap, const typename BL::Params& bp, const Epi& ep, int M, int N,
                           int K, int kchunk, int nsplit, int groups, hipStream_t st, size_t dyn_lds = 0) {
   if (M <= 0 || N <= 0) return ALEXNET_OK;
-  dim3 grid(ceil_div(M, T::BM), ceil_div(N, T::BN), groups * nsplit);
-  if (grid.y > 65535 || grid.z > 65535) {
-    set_error("GEMM grid too large (%u,%u,%u)", grid.x, grid.y, grid.z);
+  // one-dimensional launch: the kernel deals the tiles to the XCDs itself (xcd_tile)
+  const int gx = ceil_div(M, T::BM), gy = ceil_div(N, T::BN), gz = groups * nsplit;
+  const long total = (long)gx * gy * gz;
+  if (total > 0x7fffffffL) {
+    set_error("GEMM grid too large (%d,%d,%d)", gx, gy, gz);
     return ALEXNET_ESHAPE;
   }
   KernelScope ks("gemm_bf16", g_algo_flops > 0 ? g_algo_flops : 2.0 * M * N * (double)K * groups,
                  gemm_bytes(M, N, K, groups), st);
-  hipLaunchKernelGGL((gemm_bf16_kernel<T, AL, BL, Epi>), grid, dim3(kThreads), dyn_lds, st, ap, bp, ep, M, N, K,
-                     kchunk, nsplit);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, AL, BL, Epi>), dim3((unsigned)total), dim3(kThreads), dyn_lds, st, ap, bp, ep,
+                     M, N, K, kchunk, nsplit, gx, gy);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -212,6 +217,40 @@ struct ConvWeightGradTableBf {
         a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st, (size_t)std::min(kchunk, d.K) * sizeof(PixelEntry));
   }
 };
+// bf16 MFMA over operands that are stored as bf16 (gemm_bf16.h, "16" loaders)
+template <int MODE>
+struct ConvGather16 {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, Im2colKInner16<T::BM, T::BK, MODE>, DenseKInner16<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+template <int MODE>
+struct ConvGatherTap16 {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, Im2colKTap16<T::BM, T::BK, MODE>, DenseKInner16<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+struct ConvWeightGradTable16 {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, Im2colRowTable16<T::BM, T::BK>, DenseRowInner16<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st, (size_t)std::min(kchunk, d.K) * sizeof(PixelEntry));
+  }
+};
+template <class F, class Epi>
+static int by_tile_16(const GemmPlan& p, const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d,
+                      hipStream_t st) {
+  if (p.bm == 256) return F::template go<B256, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+  if (p.bn == 128) return F::template go<B128, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+  return F::template go<B64, Epi>(a, b, e, d, p.kchunk, p.ns, st);
+}
 template <class F, class Epi>
 static int by_tile_bf(const GemmPlan& p, const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d,
                       hipStream_t st) {
@@ -276,13 +315,14 @@ static int by_tile_tap(const GemmPlan& p, const Im2colParams& a, const DensePara
 }
 
 // t48: the 48-column tile may be used (its loaders need a k-tile of 32 inside one tap)
-static GemmPlan fwd_plan(const ConvGeom& c, bool run, bool bf, bool t48 = false) {
+// t256: the 256-row tile may be used (bf16-stored operands)
+static GemmPlan fwd_plan(const ConvGeom& c, bool run, bool bf, bool t48 = false, bool t256 = false) {
   const GemmDims d = fwd_dims(c);
-  return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8, bf, t48);
+  return plan_gemm(d.M, d.N, run ? run_k(c) : d.K, d.groups, (double)c.out_elems() * 4, 8, bf, t48, 0, t256);
 }
-static GemmPlan bwdd_plan(const ConvGeom& c, bool bf, bool t48 = false) {
+static GemmPlan bwdd_plan(const ConvGeom& c, bool bf, bool t48 = false, bool t256 = false) {
   const GemmDims d = bwdd_dims(c);
-  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8, bf, t48);
+  return plan_gemm(d.M, d.N, d.K, d.groups, (double)c.in_elems() * 4, 8, bf, t48, 0, t256);
 }
 static GemmPlan bwdw_plan(const ConvGeom& c, bool run, bool bf, bool table = false) {
   const GemmDims d = bwdw_dims(c);
@@ -295,10 +335,12 @@ size_t conv_fwd_ws_floats(const ConvGeom& c) {
   for (int run = 0; run < 2; ++run)
     for (int bf = 0; bf < 2; ++bf) ns = std::max(ns, fwd_plan(c, run && run_mode(c), bf).ns);
   ns = std::max(ns, fwd_plan(c, false, false, true).ns);
+  ns = std::max(ns, fwd_plan(c, false, true, false, true).ns);
   return ns > 1 ? (size_t)ns * c.out_elems() : 0;
 }
 size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
-  const int ns = std::max(std::max(bwdd_plan(c, false).ns, bwdd_plan(c, true).ns), bwdd_plan(c, false, true).ns);
+  const int ns = std::max(std::max(bwdd_plan(c, false).ns, bwdd_plan(c, true).ns),
+                          std::max(bwdd_plan(c, false, true).ns, bwdd_plan(c, true, false, true).ns));
   return ns > 1 ? (size_t)ns * c.in_elems() : 0;
 }
 size_t conv_bwd_weight_ws_floats(const ConvGeom& c) {
@@ -347,11 +389,37 @@ static int launch_conv_run_unpack(const ConvGeom& c, const float* dwrun, float* 
   return ALEXNET_OK;
 }
 
+bool conv_bf16_stored_ok(const ConvGeom& c) { return conv16_ok(c) && c.Cin % 8 == 0 && c.Cout % 8 == 0; }
+
 int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
-                    int relu, float* y, float* ws, hipStream_t st) {
+                    int relu, float* y, float* ws, hipStream_t st, const uint16_t* x16, const uint16_t* wf16,
+                    uint16_t* y16) {
+  // y16: also leave a bf16 copy of y there -- written by the epilogue of a single-pass product, else converted
+  struct Copy16 {
+    const float* y; uint16_t* y16; size_t n; hipStream_t st; bool pending;
+  } copy{y, y16, (size_t)c.out_elems(), st, false};
+  auto finish = [&copy](int rc) { return rc == ALEXNET_OK && copy.pending ? launch_to_bf16(copy.y, copy.y16, copy.n, copy.st) : rc; };
   const bool run = wrun && run_mode(c) && c.Cout % 4 == 0;
   AlgoFlops af(conv_flops(c), conv_bytes(c));
   GemmDims d = fwd_dims(c);
+  if (g_bf16 && x16 && wf16 && !run && conv_bf16_stored_ok(c) && aligned16(x16) && aligned16(wf16)) {
+    const Im2colParams a = im2col16(fwd_A(c, nullptr), x16);
+    const DenseParams b = fwd_B16k(c, wf16);
+    const GemmPlan p = fwd_plan(c, false, true, false, d.N % 128 == 0);  // 256-row tiles only without padded columns
+    const bool tap = tap_ok(a, d, kBKbf);
+    if (p.ns == 1) {
+      EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0, 0, y16};
+      if (tap) return by_tile_16<ConvGatherTap16<IM2COL_FWD>>(p, a, b, ep, d, st);
+      return by_tile_16<ConvGather16<IM2COL_FWD>>(p, a, b, ep, d, st);
+    }
+    copy.pending = y16 != nullptr;
+    EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
+    if (tap)
+      AX_TRY((by_tile_16<ConvGatherTap16<IM2COL_FWD>>(p, a, b, ep, d, st)));
+    else
+      AX_TRY((by_tile_16<ConvGather16<IM2COL_FWD>>(p, a, b, ep, d, st)));
+    return finish(launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st));
+  }
   if (run) d.K = run_k(c);
   const bool av = run || fwd_A_vec(c, x), bv = run || fwd_B_vec(c, wf);
   const bool bf = g_bf16 && av && bv;
@@ -362,7 +430,7 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
   const bool tap = !run && !bf && av && bv && tap_ok(a, d);
   const bool tapbf = bf && !run && tap_ok(a, d, kBKbf);
   if (p.ns == 1) {
-    EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0};
+    EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0, 0, y16};
     if (tapbf) return by_tile_bf<ConvGatherTapBf<IM2COL_FWD>>(p, a, b, ep, d, st);
     if (bf) return by_tile_bf<ConvGatherBf<IM2COL_FWD>>(p, a, b, ep, d, st);
     if (tap) return by_tile_tap<ConvGatherTap<IM2COL_FWD>>(p, a, b, ep, d, st);
@@ -377,7 +445,8 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
     AX_TRY((by_tile_tap<ConvGatherTap<IM2COL_FWD>>(p, a, b, ep, d, st)));
   else
     AX_TRY((by_tile<ConvGather<IM2COL_FWD>>(p, av, bv, a, b, ep, d, st)));
-  return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st);
+  copy.pending = y16 != nullptr;
+  return finish(launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st));
 }
 
 // ---- strided backward data by phases (conv_plan.h) ----
@@ -415,10 +484,37 @@ static int launch_conv_bwd_data_phases(const ConvGeom& c, const float* dy, const
 }
 
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, const float* wb, float* wphase,
-                         const float* gate, float* dx, float* ws, hipStream_t st) {
-  if (wphase && !gate && conv_phase_mode(c) && aligned16(dy)) return launch_conv_bwd_data_phases(c, dy, wf, wphase, dx, st);
+                         const float* gate, float* dx, float* ws, hipStream_t st, const uint16_t* dy16,
+                         const uint16_t* wb16, uint16_t* dx16) {
+  // dx16: also leave a bf16 copy of dx there (see launch_conv_fwd)
+  struct Copy16 {
+    const float* y; uint16_t* y16; size_t n; hipStream_t st; bool pending;
+  } copy{dx, dx16, (size_t)c.in_elems(), st, false};
+  auto finish = [&copy](int rc) { return rc == ALEXNET_OK && copy.pending ? launch_to_bf16(copy.y, copy.y16, copy.n, copy.st) : rc; };
+  if (wphase && !gate && conv_phase_mode(c) && aligned16(dy)) {
+    copy.pending = dx16 != nullptr;
+    return finish(launch_conv_bwd_data_phases(c, dy, wf, wphase, dx, st));
+  }
   const GemmDims d = bwdd_dims(c);
   AlgoFlops af(conv_flops(c), conv_bytes(c));
+  if (g_bf16 && dy16 && wb16 && conv_bf16_stored_ok(c) && aligned16(dy16) && aligned16(wb16)) {
+    const Im2colParams a = im2col16(bwdd_A(c, nullptr), dy16);
+    const DenseParams b = bwdd_B16k(c, wb16);
+    const GemmPlan p = bwdd_plan(c, true, false, d.N % 128 == 0);
+    const bool tap = tap_ok(a, d, kBKbf);
+    if (p.ns == 1) {
+      EpiGate ep{dx, c.Cin, gate, c.cg(), 0, 0, dx16};
+      if (tap) return by_tile_16<ConvGatherTap16<IM2COL_T1>>(p, a, b, ep, d, st);
+      return by_tile_16<ConvGather16<IM2COL_T1>>(p, a, b, ep, d, st);
+    }
+    copy.pending = dx16 != nullptr;
+    EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
+    if (tap)
+      AX_TRY((by_tile_16<ConvGatherTap16<IM2COL_T1>>(p, a, b, ep, d, st)));
+    else
+      AX_TRY((by_tile_16<ConvGather16<IM2COL_T1>>(p, a, b, ep, d, st)));
+    return finish(launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, nullptr, 0, gate, dx, st));
+  }
   const bool av = bwdd_A_vec(c, dy) && bwdd_B_vec(c, wb), bv = bwdd_B_vec(c, wb);
   const bool bf = g_bf16 && av && bv && c.stride == 1;
   const Im2colParams a = bwdd_A(c, dy);
@@ -428,7 +524,7 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
   const bool tap = !bf && c.stride == 1 && av && bv && tap_ok(a, d);
   const bool tapbf = bf && tap_ok(a, d, kBKbf);
   if (p.ns == 1) {
-    EpiGate ep{dx, c.Cin, gate, c.cg(), 0};
+    EpiGate ep{dx, c.Cin, gate, c.cg(), 0, 0, dx16};
     if (tapbf) return by_tile_bf<ConvGatherTapBf<IM2COL_T1>>(p, a, b, ep, d, st);
     if (bf) return by_tile_bf<ConvGatherBf<IM2COL_T1>>(p, a, b, ep, d, st);
     if (tap) return by_tile_tap<ConvGatherTap<IM2COL_T1>>(p, a, b, ep, d, st);
@@ -446,13 +542,14 @@ int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, co
     AX_TRY((by_tile<ConvGather<IM2COL_T1>>(p, av, bv, a, b, ep, d, st)));
   else
     AX_TRY((by_tile<ConvGather<IM2COL_TS>>(p, av, bv, a, b, ep, d, st)));
-  return launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, nullptr, 0, gate, dx, st);
+  copy.pending = dx16 != nullptr;
+  return finish(launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, nullptr, 0, gate, dx, st));
 }
 
 // defer_ns (generic layout only): the split-k slices are left in ws, [group][slice][slab], and their number is
 // returned there for the caller to add them up later (1: the result is in dwf already)
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
-                           hipStream_t st, int* defer_ns) {
+                           hipStream_t st, int* defer_ns, const uint16_t* x16, const uint16_t* dy16) {
   const bool run = dwrun && run_mode(c) && bwdw_B_vec(c, dy);
   AlgoFlops af(conv_flops(c), conv_bytes(c));
   GemmDims d = bwdw_dims(c);
@@ -469,7 +566,10 @@ int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, f
   const long slab = (long)d.M * d.N;
   float* out = run ? dwrun : dwf;
   EpiSlab ep{p.ns > 1 ? ws : out, slab, d.N, nullptr};
-  if (bf && table)
+  const bool s16 = bf && table && !run && x16 && dy16 && conv_bf16_stored_ok(c) && aligned16(x16) && aligned16(dy16);
+  if (s16)
+    AX_TRY((by_tile_bf<ConvWeightGradTable16>(p, im2col16(a, x16), dense16(bwdw_B(c, dy), dy16), ep, d, st)));
+  else if (bf && table)
     AX_TRY((by_tile_bf<ConvWeightGradTableBf>(p, a, bwdw_B(c, dy), ep, d, st)));
   else if (bf)
     AX_TRY((by_tile_bf<ConvWeightGradBf>(p, a, bwdw_B(c, dy), ep, d, st)));

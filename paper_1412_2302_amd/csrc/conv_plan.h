@@ -149,6 +149,36 @@ inline DenseParams bwdw_B(const ConvGeom& c, const float* dy) {
 }
 inline bool bwdw_B_vec(const ConvGeom& c, const float* dy) { return c.og() % 4 == 0 && c.Cout % 4 == 0 && aligned16(dy); }
 
+// The same operands over tensors that hold bf16: the pointer is carried in the same field, the extent counts
+// 2-byte elements (only the "16" loaders of gemm_bf16.h may be given these)
+inline Im2colParams im2col16(Im2colParams a, const uint16_t* p) {
+  a.x = reinterpret_cast<const float*>(p);
+  a.bytes /= 2;
+  return a;
+}
+inline DenseParams dense16(DenseParams b, const uint16_t* p) {
+  b.p = reinterpret_cast<const float*>(p);
+  b.bytes /= 2;
+  return b;
+}
+// Weights of the forward and backward-data products as bf16 with the reduction contiguous, wfk[g][o][(r,s,c)]
+// and wbk[g][c][(r,s,o)] (the transposes of wf and wb): both operands of those products are then read along k,
+// which is the cheap direction for the matrix cores' fragments (one 16-byte LDS read per fragment)
+inline DenseParams fwd_B16k(const ConvGeom& c, const uint16_t* wfk) {
+  DenseParams b;
+  b.p = reinterpret_cast<const float*>(wfk); b.ld = c.kf(); b.gstride = (long)c.og() * c.kf(); b.R = c.og();
+  b.bytes = (uint32_t)(c.w_elems() * 2);
+  return b;
+}
+inline DenseParams bwdd_B16k(const ConvGeom& c, const uint16_t* wbk) {
+  DenseParams b;
+  b.p = reinterpret_cast<const float*>(wbk); b.ld = c.kb(); b.gstride = (long)c.cg() * c.kb(); b.R = c.cg();
+  b.bytes = (uint32_t)(c.w_elems() * 2);
+  return b;
+}
+// every extent a 16-byte load of bf16 must not straddle is a multiple of 8
+inline bool conv16_ok(const ConvGeom& c) { return c.cg() % 8 == 0 && c.og() % 8 == 0 && c.stride == 1; }
+
 // Split of the reduction so that a launch has enough workgroups: returns the
 // number of splits and sets kchunk (a multiple of bk).
 inline int plan_split(long tiles, int K, int bk, int target_blocks, int max_split, int* kchunk) {

@@ -40,6 +40,7 @@
 #pragma once
 
 #include <stdint.h>
+#include <string.h>
 
 #include <type_traits>
 
@@ -344,8 +345,8 @@ AX_HD PixCoord decode_pixel(int p, const Im2colParams& g) {
 constexpr int kFar = 1 << 28;  // coordinate that puts every tap outside the tensor
 
 // Byte offset of tap (r,s,c) seen from a pixel whose origin is (y0, x0) and
-// whose origin offset is rowbase = ((n*H*W + y0*W + x0)*Ctot + c_off)*4 (mod 2^32).
-template <int MODE>
+// whose origin offset is rowbase = ((n*H*W + y0*W + x0)*Ctot + c_off)*ES (mod 2^32); ES = bytes per element.
+template <int MODE, int ES = 4>
 AX_HD uint32_t tap_address(const Im2colParams& g, uint32_t rowbase, int y0, int x0, const TapCoord& t) {
   if (MODE == IM2COL_TS) {
     const int ty = y0 - t.r, tx = x0 - t.s;
@@ -354,20 +355,20 @@ AX_HD uint32_t tap_address(const Im2colParams& g, uint32_t rowbase, int y0, int 
     const int ix = (int)fdiv((uint32_t)(pos ? tx : 0), g.d_stride);
     const bool ok = pos && iy * g.stride == ty && ix * g.stride == tx && iy < g.H && ix < g.W;
     // rowbase is the offset of (n, 0, 0, c_off) in this mode
-    return ok ? rowbase + ((uint32_t)(iy * g.W + ix) * (uint32_t)g.Ctot + (uint32_t)t.c) * 4u : kOob;
+    return ok ? rowbase + ((uint32_t)(iy * g.W + ix) * (uint32_t)g.Ctot + (uint32_t)t.c) * (uint32_t)ES : kOob;
   }
   const int iy = MODE == IM2COL_FWD ? y0 + t.r : y0 - t.r;
   const int ix = MODE == IM2COL_FWD ? x0 + t.s : x0 - t.s;
   const bool ok = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W;
-  const uint32_t tap = (((uint32_t)t.r * (uint32_t)g.W + (uint32_t)t.s) * (uint32_t)g.Ctot) * 4u;
-  const uint32_t o = (MODE == IM2COL_FWD ? rowbase + tap : rowbase - tap) + (uint32_t)t.c * 4u;
+  const uint32_t tap = (((uint32_t)t.r * (uint32_t)g.W + (uint32_t)t.s) * (uint32_t)g.Ctot) * (uint32_t)ES;
+  const uint32_t o = (MODE == IM2COL_FWD ? rowbase + tap : rowbase - tap) + (uint32_t)t.c * (uint32_t)ES;
   return ok ? o : kOob;
 }
-template <int MODE>
+template <int MODE, int ES = 4>
 AX_HD uint32_t row_base(const Im2colParams& g, int n, int y0, int x0, int c_off) {
   const uint32_t img = (uint32_t)n * (uint32_t)(g.H * g.W);
-  if (MODE == IM2COL_TS) return (img * (uint32_t)g.Ctot + (uint32_t)c_off) * 4u;
-  return ((img + (uint32_t)y0 * (uint32_t)g.W + (uint32_t)x0) * (uint32_t)g.Ctot + (uint32_t)c_off) * 4u;
+  if (MODE == IM2COL_TS) return (img * (uint32_t)g.Ctot + (uint32_t)c_off) * (uint32_t)ES;
+  return ((img + (uint32_t)y0 * (uint32_t)g.W + (uint32_t)x0) * (uint32_t)g.Ctot + (uint32_t)c_off) * (uint32_t)ES;
 }
 
 template <int ROWS, int BK, bool VEC, int MODE>
@@ -623,6 +624,40 @@ AX_HD int lds_index(int row, int k) {
   return L::kRowMajor ? row * L::LD + k : k * L::LD + row;
 }
 
+// ---- bf16 packing (round to nearest even) -----------------------------------------
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  bf2 v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+#else
+inline uint32_t bf16_bits(float f) {  // finite inputs
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+inline uint32_t pack_bf16(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+#endif
+// one bf16 / four consecutive bf16 (8-byte aligned) of a copy that shadows an fp32 tensor
+AX_HD void store_bf16(uint16_t* p, float v) { *p = (uint16_t)(pack_bf16(v, 0.f) & 0xffffu); }
+AX_HD void store_bf16x4(uint16_t* p, const float4& v) {
+  uint32_t* q = reinterpret_cast<uint32_t*>(p);
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+  v2u w;
+  w[0] = pack_bf16(v.x, v.y);
+  w[1] = pack_bf16(v.z, v.w);
+  *reinterpret_cast<v2u*>(q) = w;
+#else
+  q[0] = pack_bf16(v.x, v.y);
+  q[1] = pack_bf16(v.z, v.w);
+#endif
+}
+
 // ================================ epilogues ==================================
 // kTransposed selects how a lane's accumulators map to the tile (see Tile::acc_row):
 //  * true: apply4(m, n, v) is called for four consecutive valid columns n .. n+3 (n a multiple of 4) of row m
@@ -642,14 +677,17 @@ struct EpiBiasAct {
   const float* bias;  // may be null
   int relu, cols_per_group, col_off;
   int vec;
+  uint16_t* y16;  // may be null: a bf16 copy of y (same layout), for the product that reads y next
   AX_HD void set_group(int g, int /*z*/) {
     col_off = g * cols_per_group;
-    vec = (ldc & 3) == 0 && (col_off & 3) == 0 && epi_aligned16(y) && epi_aligned16(bias);
+    vec = (ldc & 3) == 0 && (col_off & 3) == 0 && epi_aligned16(y) && epi_aligned16(bias) &&
+          (((uintptr_t)y16 & 7) == 0);
   }
   AX_HD void apply(int m, int n, float v) const {
     if (bias) v += bias[col_off + n];
     if (relu) v = v > 0.f ? v : 0.f;
     y[(long)m * ldc + col_off + n] = v;
+    if (y16) store_bf16(y16 + (long)m * ldc + col_off + n, v);
   }
   AX_HD void apply4(int m, int n, float4 v) const {
     if (!vec) {
@@ -665,6 +703,7 @@ struct EpiBiasAct {
       v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
     }
     *reinterpret_cast<float4*>(y + (long)m * ldc + col_off + n) = v;
+    if (y16) store_bf16x4(y16 + (long)m * ldc + col_off + n, v);
   }
 };
 
@@ -676,14 +715,17 @@ struct EpiGate {
   const float* gate;  // forward activation with the layout of dx, or null
   int cols_per_group, col_off;
   int vec;
+  uint16_t* dx16;  // may be null: a bf16 copy of dx (same layout), for the products that read dx next
   AX_HD void set_group(int g, int /*z*/) {
     col_off = g * cols_per_group;
-    vec = (ldc & 3) == 0 && (col_off & 3) == 0 && epi_aligned16(dx) && epi_aligned16(gate);
+    vec = (ldc & 3) == 0 && (col_off & 3) == 0 && epi_aligned16(dx) && epi_aligned16(gate) &&
+          (((uintptr_t)dx16 & 7) == 0);
   }
   AX_HD void apply(int m, int n, float v) const {
     const long o = (long)m * ldc + col_off + n;
     if (gate && !(gate[o] > 0.f)) v = 0.f;
     dx[o] = v;
+    if (dx16) store_bf16(dx16 + o, v);
   }
   AX_HD void apply4(int m, int n, float4 v) const {
     if (!vec) {
@@ -699,6 +741,7 @@ struct EpiGate {
       if (!(q.w > 0.f)) v.w = 0.f;
     }
     *reinterpret_cast<float4*>(dx + o) = v;
+    if (dx16) store_bf16x4(dx16 + o, v);
   }
 };
 

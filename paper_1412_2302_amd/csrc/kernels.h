@@ -44,16 +44,25 @@ size_t conv_bwd_weight_ws_floats(const ConvGeom& c);
 bool conv_run_mode(const ConvGeom& c);
 size_t conv_run_w_floats(const ConvGeom& c);
 int launch_conv_run_pack(const ConvGeom& c, const float* wf, float* wrun, hipStream_t st);
+// x16 / dy16: copies of the activations in bf16, same layout; wf16 / wb16: bf16 copies of the packed weights with
+// the reduction contiguous, wf16[g][o][(r,s,c)] and wb16[g][c][(r,s,o)] (launch_to_bf16_transposed of wf / wb).
+// When both operands of a product are given, the handle's GEMMs are bf16 and conv_bf16_stored_ok(), the product
+// reads those instead of rounding fp32 on the fly.  y16 / dx16: where to leave a bf16 copy of the result for the
+// products that read it next (written by the epilogue, or converted after a split-k pass).
+bool conv_bf16_stored_ok(const ConvGeom& c);
 int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
-                    int relu, float* y, float* ws, hipStream_t st);
+                    int relu, float* y, float* ws, hipStream_t st, const uint16_t* x16 = nullptr,
+                    const uint16_t* wf16 = nullptr, uint16_t* y16 = nullptr);
 // Strided, ungrouped, ungated backward-data runs by phases when `wphase` (conv_phase_w_floats() floats of
 // scratch) is given; it then reads the forward weights wf instead of wb.
 bool conv_phase_mode(const ConvGeom& c);
 size_t conv_phase_w_floats(const ConvGeom& c);
 int launch_conv_bwd_data(const ConvGeom& c, const float* dy, const float* wf, const float* wb, float* wphase,
-                         const float* gate, float* dx, float* ws, hipStream_t st);
+                         const float* gate, float* dx, float* ws, hipStream_t st, const uint16_t* dy16 = nullptr,
+                         const uint16_t* wb16 = nullptr, uint16_t* dx16 = nullptr);
 int launch_conv_bwd_weight(const ConvGeom& c, const float* x, const float* dy, float* dwf, float* dwrun, float* ws,
-                           hipStream_t st, int* defer_ns = nullptr);
+                           hipStream_t st, int* defer_ns = nullptr, const uint16_t* x16 = nullptr,
+                           const uint16_t* dy16 = nullptr);
 
 // ---- 3x3 and 5x5 unit-stride convolutions through F(4x4, 3x3) (winograd.hip) ----
 // All tensors 16-byte aligned, channels per group multiples of 4.  V: wino_v_floats(), U / Ub / dU:
@@ -99,6 +108,10 @@ int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy
 
 // ---- bandwidth-bound kernels (ops.hip) --------------------------------------
 int launch_fill(float* p, size_t n, float v, hipStream_t st);
+// dst[i] = bf16(src[i]), round to nearest even
+int launch_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
+// dst[g][n][k] = bf16(src[g][k][n]) for G matrices of K x N
+int launch_to_bf16_transposed(const float* src, uint16_t* dst, int G, int K, int N, hipStream_t st);
 int launch_fill_bytes(void* p, size_t nbytes, hipStream_t st);  // zero fill, nbytes % 4 == 0
 int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* ox, int32_t* oy, int32_t* flip,
                        hipStream_t st);
@@ -118,18 +131,19 @@ int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int 
 bool lrn_pool_fused_ok(const float* a, const float* y, const float* dy, const float* da, const uint8_t* slot, int C,
                        int n);
 size_t lrn_part_floats(int C);
+// y16 / da16 / dx16 (may be null): where to leave a bf16 copy of the result
 int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo, int n,
-                        float k, float alpha, float beta, hipStream_t st);
+                        float k, float alpha, float beta, hipStream_t st, uint16_t* y16 = nullptr);
 int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, float* da, int N, int H, int W, int C,
                         int Ho, int Wo, int n, float k, float alpha, float beta, int relu_gate, float* colsum_out,
-                        float* part, hipStream_t st, bool partials_only = false);
+                        float* part, hipStream_t st, bool partials_only = false, uint16_t* da16 = nullptr);
 // partials_only: leave the lrn_part_rows(pixels, C) rows of per-workgroup sums in `part` for the caller to add up
 size_t lrn_part_rows(long pixels, int C);
 int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo,
                     hipStream_t st);
 // dx[n][y][x][c] = sum of dy over the windows whose winning tap is (y,x); gated by gate > 0 when gate != null
 int launch_pool_bwd(const float* dy, const uint8_t* slot, const float* gate, float* dx, int N, int H, int W, int C,
-                    int Ho, int Wo, hipStream_t st);
+                    int Ho, int Wo, hipStream_t st, uint16_t* dx16 = nullptr);
 int launch_pool_argmax_canonical(const uint8_t* slot, int32_t* out_nchw, int N, int C, int Ho, int Wo, int W,
                                  hipStream_t st);
 // mode 0: dz = (p - onehot)/B and per-row loss; mode 1: p only

@@ -29,6 +29,74 @@ int launch_fill(float* p, size_t n, float v, hipStream_t st) {
 }
 int launch_fill_bytes(void* p, size_t nbytes, hipStream_t st) { return launch_fill((float*)p, nbytes / 4, 0.f, st); }
 
+// fp32 -> bf16 (nearest even) copies of GEMM operands: eight values per lane and trip
+__global__ void __launch_bounds__(256) to_bf16_kernel(const float* __restrict__ s, uint16_t* __restrict__ d, size_t n8,
+                                                      size_t n) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
+    const float4 a = *reinterpret_cast<const float4*>(s + 8 * i);
+    const float4 b = *reinterpret_cast<const float4*>(s + 8 * i + 4);
+    v4u o;
+    bf2 t;
+    t[0] = (__bf16)a.x; t[1] = (__bf16)a.y; o[0] = __builtin_bit_cast(uint32_t, t);
+    t[0] = (__bf16)a.z; t[1] = (__bf16)a.w; o[1] = __builtin_bit_cast(uint32_t, t);
+    t[0] = (__bf16)b.x; t[1] = (__bf16)b.y; o[2] = __builtin_bit_cast(uint32_t, t);
+    t[0] = (__bf16)b.z; t[1] = (__bf16)b.w; o[3] = __builtin_bit_cast(uint32_t, t);
+    *reinterpret_cast<v4u*>(d + 8 * i) = o;
+  }
+  // tail (n % 8 values), by the first lanes of the grid
+  const size_t i = 8 * n8 + (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const __bf16 v = (__bf16)s[i];
+    d[i] = __builtin_bit_cast(uint16_t, v);
+  }
+}
+int launch_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st) {
+  if (n == 0) return ALEXNET_OK;
+  if ((((uintptr_t)src | (uintptr_t)dst) & 15) != 0) {
+    set_error("to_bf16: tensors must be 16-byte aligned");
+    return ALEXNET_EALIGN;
+  }
+  KernelScope ks("to_bf16", 0, (double)n * 6.0, st);
+  const size_t n8 = n / 8;
+  unsigned g = grid_for(std::max<size_t>(n8, 1), 256);
+  if (g > 4096) g = 4096;
+  hipLaunchKernelGGL(to_bf16_kernel, dim3(g), dim3(256), 0, st, src, dst, n8, n);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
+// dst[g][n][k] = bf16(src[g][k][n]): 32 x 32 tiles through LDS, reads and writes both along their rows
+__global__ void __launch_bounds__(256) to_bf16_transposed_kernel(const float* __restrict__ s, uint16_t* __restrict__ d,
+                                                                 int K, int N) {
+  __shared__ float tile[32][33];
+  const size_t g = blockIdx.z;
+  const int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int r = ty; r < 32; r += 8) {
+    const int k = k0 + r, n = n0 + tx;
+    tile[r][tx] = (k < K && n < N) ? s[(g * K + k) * N + n] : 0.f;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int n = n0 + r, k = k0 + tx;
+    if (n < N && k < K) {
+      const __bf16 v = (__bf16)tile[tx][r];
+      d[(g * N + n) * K + k] = __builtin_bit_cast(uint16_t, v);
+    }
+  }
+}
+int launch_to_bf16_transposed(const float* src, uint16_t* dst, int G, int K, int N, hipStream_t st) {
+  if (G <= 0 || K <= 0 || N <= 0) return ALEXNET_OK;
+  KernelScope ks("to_bf16", 0, (double)G * K * N * 6.0, st);
+  hipLaunchKernelGGL(to_bf16_transposed_kernel, dim3(ceil_div(N, 32), ceil_div(K, 32), G), dim3(256), 0, st, src, dst, K,
+                     N);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
 __global__ void copy_kernel(const float* __restrict__ s, float* __restrict__ d, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -298,7 +366,7 @@ template <bool BWD, bool GATHER>
 __global__ void __launch_bounds__(256)
 lrn_vec_kernel(const float* __restrict__ a, const float* __restrict__ db, float* __restrict__ out, long pixels, int C,
                int half, int PB, float k, float alpha, float beta, int relu_gate, PoolGather pg,
-               float* __restrict__ part) {
+               float* __restrict__ part, uint16_t* __restrict__ out16) {
   extern __shared__ __attribute__((aligned(16))) float sh[];  // [2][PB][kLrnPad + C + kLrnPad]
   const int q = C >> 2;                                        // lanes per pixel
   const int ld = C + 2 * kLrnPad;
@@ -371,6 +439,7 @@ lrn_vec_kernel(const float* __restrict__ a, const float* __restrict__ db, float*
         r.w = av.w > 0.f ? r.w : 0.f;
       }
       *reinterpret_cast<float4*>(out + pix * C + c) = r;
+      if (out16) store_bf16x4(out16 + pix * C + c, r);  // bf16 copy for the products that read the gradient next
       colsum.x += r.x;
       colsum.y += r.y;
       colsum.z += r.z;
@@ -405,7 +474,7 @@ lrn_vec_kernel(const float* __restrict__ a, const float* __restrict__ db, float*
 __global__ void __launch_bounds__(256)
 lrn_pool_fwd_kernel(const float* __restrict__ a, float* __restrict__ y, uint8_t* __restrict__ slot, int H, int W,
                     int C, int Ho, int Wo, int PH, int PW, int tiles_y, int tiles_x, int half, float k, float alpha,
-                    float beta) {
+                    float beta, uint16_t* __restrict__ y16) {
   extern __shared__ __attribute__((aligned(16))) float bbuf[];  // [(2PH+1)*(2PW+1)][C]
   const int q = C >> 2;
   int t = blockIdx.x;
@@ -485,6 +554,7 @@ lrn_pool_fwd_kernel(const float* __restrict__ a, float* __restrict__ y, uint8_t*
       }
     const size_t e = (((size_t)n * Ho + py0 + oy) * Wo + px0 + ox) * C + c;
     *reinterpret_cast<float4*>(y + e) = best;
+    if (y16) store_bf16x4(y16 + e, best);  // bf16 copy for the product that reads the pooled tensor next
     *reinterpret_cast<uint32_t*>(slot + e) = bs;
   }
 }
@@ -505,7 +575,7 @@ int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k,
     const int PB = 256 / (C / 4);
     const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
     hipLaunchKernelGGL((lrn_vec_kernel<false, false>), dim3(lrn_grid(pixels, PB)), dim3(256), lds, st, a, nullptr, b,
-                       pixels, C, half, PB, k, alpha, beta, 0, PoolGather{}, nullptr);
+                       pixels, C, half, PB, k, alpha, beta, 0, PoolGather{}, nullptr, nullptr);
   } else {
     hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, b, total, C, half, k, alpha,
                        beta);
@@ -523,7 +593,7 @@ int launch_lrn_bwd(const float* a, const float* db, float* da, long pixels, int 
     const int PB = 256 / (C / 4);
     const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
     hipLaunchKernelGGL((lrn_vec_kernel<true, false>), dim3(lrn_grid(pixels, PB)), dim3(256), lds, st, a, db, da,
-                       pixels, C, half, PB, k, alpha, beta, relu_gate, PoolGather{}, nullptr);
+                       pixels, C, half, PB, k, alpha, beta, relu_gate, PoolGather{}, nullptr, nullptr);
   } else {
     hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, a, db, da, total, C, half, k,
                        alpha, beta, relu_gate);
@@ -570,7 +640,7 @@ bool lrn_pool_fused_ok(const float* a, const float* y, const float* dy, const fl
 size_t lrn_part_floats(int C) { return (size_t)kLrnMaxBlocks * C; }
 
 int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo, int n,
-                        float k, float alpha, float beta, hipStream_t st) {
+                        float k, float alpha, float beta, hipStream_t st, uint16_t* y16) {
   const size_t total = (size_t)N * Ho * Wo * C;
   if (!total) return ALEXNET_OK;
   // pooled tile edge: the normalised input pixels under a tile fill at most 20 KiB of LDS (25 pixels at least)
@@ -581,7 +651,7 @@ int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, i
   const size_t lds = (size_t)(2 * PH + 1) * (2 * PW + 1) * C * sizeof(float);
   KernelScope ks("lrn_pool_fwd", 0, (double)N * H * W * C * 4.0 + (double)total * 5.0, st);
   hipLaunchKernelGGL(lrn_pool_fwd_kernel, dim3((unsigned)(N * tiles_y * tiles_x)), dim3(256), lds, st, a, y, slot, H, W,
-                     C, Ho, Wo, PH, PW, tiles_y, tiles_x, n / 2, k, alpha, beta);
+                     C, Ho, Wo, PH, PW, tiles_y, tiles_x, n / 2, k, alpha, beta, y16);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -589,7 +659,7 @@ int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, i
 size_t lrn_part_rows(long pixels, int C) { return (size_t)lrn_grid(pixels, 256 / (C / 4)); }
 int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, float* da, int N, int H, int W, int C,
                         int Ho, int Wo, int n, float k, float alpha, float beta, int relu_gate, float* colsum_out,
-                        float* part, hipStream_t st, bool partials_only) {
+                        float* part, hipStream_t st, bool partials_only, uint16_t* da16) {
   const long pixels = (long)N * H * W;
   if (!pixels) return ALEXNET_OK;
   const int PB = 256 / (C / 4);
@@ -600,7 +670,7 @@ int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, fl
     const size_t lds = (size_t)2 * PB * (C + 2 * kLrnPad) * sizeof(float);
     const PoolGather pg{dy, slot, H, W, Ho, Wo, make_fastdiv((uint32_t)W), make_fastdiv((uint32_t)H)};
     hipLaunchKernelGGL((lrn_vec_kernel<true, true>), dim3(blocks), dim3(256), lds, st, a, nullptr, da, pixels, C, n / 2,
-                       PB, k, alpha, beta, relu_gate, pg, sums ? part : nullptr);
+                       PB, k, alpha, beta, relu_gate, pg, sums ? part : nullptr, da16);
     AX_LAUNCH_CHECK();
   }
   if (colsum_out && !partials_only) {
@@ -683,7 +753,7 @@ __global__ void pool_bwd_kernel(const float* __restrict__ dy, const uint8_t* __r
 // Same gather with a lane owning four consecutive channels (C % 4 == 0).
 __global__ void pool_bwd_vec_kernel(const float* __restrict__ dy, const uint8_t* __restrict__ slot,
                                     const float* __restrict__ gate, float* __restrict__ dx, int N, int H, int W, int C,
-                                    int Ho, int Wo) {
+                                    int Ho, int Wo, uint16_t* __restrict__ dx16) {
   const int cq = C >> 2;
   const size_t total = (size_t)N * H * W * cq;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -717,20 +787,27 @@ __global__ void pool_bwd_vec_kernel(const float* __restrict__ dy, const uint8_t*
     acc.w = g.w > 0.f ? acc.w : 0.f;
   }
   *reinterpret_cast<float4*>(dx + e) = acc;
+  if (dx16) store_bf16x4(dx16 + e, acc);
 }
+// dx16 (may be null): where to leave a bf16 copy of dx
 int launch_pool_bwd(const float* dy, const uint8_t* slot, const float* gate, float* dx, int N, int H, int W, int C,
-                    int Ho, int Wo, hipStream_t st) {
+                    int Ho, int Wo, hipStream_t st, uint16_t* dx16) {
   const size_t total = (size_t)N * H * W * C;
   if (!total) return ALEXNET_OK;
-  KernelScope ks("pool_bwd", 0, (double)total * (gate ? 8.0 : 4.0) + (double)N * Ho * Wo * C * 5.0, st);
-  if (C % 4 == 0 && aligned16(dy) && aligned16(dx) && (!gate || aligned16(gate)) && ((uintptr_t)slot & 3) == 0)
-    hipLaunchKernelGGL(pool_bwd_vec_kernel, dim3(grid_for(total / 4, 256)), dim3(256), 0, st, dy, slot, gate, dx, N, H,
-                       W, C, Ho, Wo);
-  else
-  hipLaunchKernelGGL(pool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, slot, gate, dx, N, H, W, C,
-                     Ho, Wo);
-  AX_LAUNCH_CHECK();
-  return ALEXNET_OK;
+  {
+    KernelScope ks("pool_bwd", 0, (double)total * (gate ? 8.0 : 4.0) + (double)N * Ho * Wo * C * 5.0, st);
+    if (C % 4 == 0 && aligned16(dy) && aligned16(dx) && (!gate || aligned16(gate)) && ((uintptr_t)slot & 3) == 0 &&
+        ((uintptr_t)dx16 & 7) == 0) {
+      hipLaunchKernelGGL(pool_bwd_vec_kernel, dim3(grid_for(total / 4, 256)), dim3(256), 0, st, dy, slot, gate, dx, N,
+                         H, W, C, Ho, Wo, dx16);
+      AX_LAUNCH_CHECK();
+      return ALEXNET_OK;
+    }
+    hipLaunchKernelGGL(pool_bwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, dy, slot, gate, dx, N, H, W, C, Ho,
+                       Wo);
+    AX_LAUNCH_CHECK();
+  }
+  return dx16 ? launch_to_bf16(dx, dx16, total, st) : ALEXNET_OK;
 }
 
 // slot bytes (channel-last) -> canonical int32 NCHW index y_in*W + x_in

@@ -373,6 +373,125 @@ static void run_case(const Case& cs) {
         check("bwd_wgt_tbl", nm, dwf, dwf_ref);
       }
     }
+    // ---- operands stored as bf16 (values are exact in bf16 here, so the same references hold) ----
+    if (conv16_ok(c)) {
+      auto to16 = [](const float* src, long n) {
+        uint16_t* d = new uint16_t[n];  // exact size: the sanitizer sees any access past the end
+        for (long i = 0; i < n; ++i) d[i] = (uint16_t)bf16_bits(src[i]);
+        return d;
+      };
+      uint16_t* x16 = to16(x, c.in_elems());
+      uint16_t* dy16 = to16(dy, c.out_elems());
+      uint16_t* wf16 = to16(wf, c.w_elems());
+      uint16_t* wb16 = to16(wb, c.w_elems());
+      // the same weights with the reduction contiguous: wfk[g][o][(r,s,c)], wbk[g][c][(r,s,o)]
+      uint16_t* wfk = new uint16_t[c.w_elems()];
+      uint16_t* wbk = new uint16_t[c.w_elems()];
+      for (int g = 0; g < c.groups; ++g) {
+        for (int kk = 0; kk < c.kf(); ++kk)
+          for (int o = 0; o < og; ++o) wfk[((long)g * og + o) * c.kf() + kk] = wf16[((long)g * c.kf() + kk) * og + o];
+        for (int kk = 0; kk < c.kb(); ++kk)
+          for (int ci = 0; ci < cg; ++ci) wbk[((long)g * cg + ci) * c.kb() + kk] = wb16[((long)g * c.kb() + kk) * cg + ci];
+      }
+      {
+        std::vector<float> y(c.out_elems(), NAN);
+        const GemmDims d = fwd_dims(c);
+        const int kcf = ((d.K + T::BK - 1) / T::BK) * T::BK;
+        EpiBiasAct e{y.data(), c.Cout, bias, 1, og, 0};
+        const Im2colParams fa = im2col16(fwd_A(c, x), x16);
+        const DenseParams fb = dense16(fwd_B(c, wf), wf16);
+        emu_gemm_bf<T, Im2colKInner16<T::BM, T::BK, IM2COL_FWD>, DenseRowInner16<T::BN, T::BK>, EpiBiasAct>(
+            fa, fb, e, d.M, d.N, d.K, kcf, 1, d.groups);
+        check("fwd16", nm, y, y_ref);
+        if (fa.Cg % T::BK == 0 && c.k * c.k <= 32) {
+          std::fill(y.begin(), y.end(), NAN);
+          emu_gemm_bf<T, Im2colKTap16<T::BM, T::BK, IM2COL_FWD>, DenseRowInner16<T::BN, T::BK>, EpiBiasAct>(
+              fa, fb, e, d.M, d.N, d.K, kcf, 1, d.groups);
+          check("fwd_tap16", nm, y, y_ref);
+        }
+        {  // weights with the reduction contiguous
+          const DenseParams fk = fwd_B16k(c, wfk);
+          std::fill(y.begin(), y.end(), NAN);
+          emu_gemm_bf<T, Im2colKInner16<T::BM, T::BK, IM2COL_FWD>, DenseKInner16<T::BN, T::BK>, EpiBiasAct>(
+              fa, fk, e, d.M, d.N, d.K, kcf, 1, d.groups);
+          check("fwd16k", nm, y, y_ref);
+          if (fa.Cg % T::BK == 0 && c.k * c.k <= 32) {
+            std::fill(y.begin(), y.end(), NAN);
+            emu_gemm_bf<T, Im2colKTap16<T::BM, T::BK, IM2COL_FWD>, DenseKInner16<T::BN, T::BK>, EpiBiasAct>(
+                fa, fk, e, d.M, d.N, d.K, kcf, 1, d.groups);
+            check("fwd_tap16k", nm, y, y_ref);
+          }
+        }
+        if (d.K / T::BK >= 3) {  // split-k, chunks of whole k-tiles, the last one ragged
+          const int ns = 3, chunk = (((d.K + T::BK - 1) / T::BK + ns - 1) / ns) * T::BK;
+          std::vector<float> ws((size_t)d.groups * ns * d.M * d.N, NAN), ysum(c.out_elems(), 0.f);
+          EpiSlab es{ws.data(), (long)d.M * d.N, d.N, nullptr};
+          emu_gemm_bf<T, Im2colKInner16<T::BM, T::BK, IM2COL_FWD>, DenseRowInner16<T::BN, T::BK>, EpiSlab>(
+              fa, fb, es, d.M, d.N, d.K, chunk, ns, d.groups);
+          for (int g = 0; g < d.groups; ++g)
+            for (int sp = 0; sp < ns; ++sp)
+              for (int m = 0; m < d.M; ++m)
+                for (int n = 0; n < d.N; ++n) {
+                  const float v = ws[(((size_t)g * ns + sp) * d.M + m) * d.N + n];
+                  if (v == v) ysum[(size_t)m * c.Cout + g * og + n] += v;
+                }
+          for (long i = 0; i < c.out_elems(); ++i) {
+            const float v = ysum[i] + bias[i % c.Cout];
+            ysum[i] = v > 0 ? v : 0;
+          }
+          check("fwd16_s3", nm, ysum, y_ref);
+        }
+      }
+      {
+        std::vector<float> dx(c.in_elems(), NAN);
+        const GemmDims d = bwdd_dims(c);
+        EpiGate e{dx.data(), c.Cin, nullptr, cg, 0};
+        const Im2colParams ba = im2col16(bwdd_A(c, dy), dy16);
+        const DenseParams bb = dense16(bwdd_B(c, wb), wb16);
+        emu_gemm_bf<T, Im2colKInner16<T::BM, T::BK, IM2COL_T1>, DenseRowInner16<T::BN, T::BK>, EpiGate>(
+            ba, bb, e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
+        check("bwd_data16", nm, dx, dx_ref);
+        if (ba.Cg % T::BK == 0 && c.k * c.k <= 32) {
+          std::fill(dx.begin(), dx.end(), NAN);
+          emu_gemm_bf<T, Im2colKTap16<T::BM, T::BK, IM2COL_T1>, DenseRowInner16<T::BN, T::BK>, EpiGate>(
+              ba, bb, e, d.M, d.N, d.K, d.K, 1, d.groups);
+          check("bwdd_tap16", nm, dx, dx_ref);
+        }
+        const DenseParams bk = bwdd_B16k(c, wbk);
+        std::fill(dx.begin(), dx.end(), NAN);
+        emu_gemm_bf<T, Im2colKInner16<T::BM, T::BK, IM2COL_T1>, DenseKInner16<T::BN, T::BK>, EpiGate>(
+            ba, bk, e, d.M, d.N, d.K, ((d.K + T::BK - 1) / T::BK) * T::BK, 1, d.groups);
+        check("bwd_data16k", nm, dx, dx_ref);
+        if (ba.Cg % T::BK == 0 && c.k * c.k <= 32) {
+          std::fill(dx.begin(), dx.end(), NAN);
+          emu_gemm_bf<T, Im2colKTap16<T::BM, T::BK, IM2COL_T1>, DenseKInner16<T::BN, T::BK>, EpiGate>(
+              ba, bk, e, d.M, d.N, d.K, d.K, 1, d.groups);
+          check("bwdd_tap16k", nm, dx, dx_ref);
+        }
+      }
+      {
+        const GemmDims d = bwdw_dims(c);
+        int kchunk;
+        long tiles = (long)((d.M + T::BM - 1) / T::BM) * ((d.N + T::BN - 1) / T::BN) * d.groups;
+        int nsplit = plan_split(tiles, d.K, T::BK, 7, 5, &kchunk);
+        if (d.K % T::BK == 0 && c.k * c.k <= 31 && kchunk % T::BK == 0) {
+          std::vector<float> ws((size_t)d.groups * nsplit * d.M * d.N, NAN);
+          EpiSlab e{ws.data(), (long)d.M * d.N, d.N, nullptr};
+          emu_gemm_bf<T, Im2colRowTable16<T::BM, T::BK>, DenseRowInner16<T::BN, T::BK>, EpiSlab>(
+              im2col16(bwdw_A(c, x), x16), dense16(bwdw_B(c, dy), dy16), e, d.M, d.N, d.K, kchunk, nsplit, d.groups);
+          std::vector<float> dwf(c.w_elems(), 0.f);
+          for (int g = 0; g < d.groups; ++g)
+            for (int sp = 0; sp < nsplit; ++sp)
+              for (long i = 0; i < (long)d.M * d.N; ++i) {
+                const float v = ws[((long)g * nsplit + sp) * d.M * d.N + i];
+                if (v == v) dwf[(long)g * d.M * d.N + i] += v;
+              }
+          snprintf(nm, sizeof nm, "%s/%dx%d/s%d/bf16", cs.name, T::BM, T::BN, nsplit);
+          check("bwd_wgt_tbl16", nm, dwf, dwf_ref);
+        }
+      }
+      delete[] x16; delete[] dy16; delete[] wf16; delete[] wb16; delete[] wfk; delete[] wbk;
+    }
     delete[] x; delete[] dy; delete[] w; delete[] wf; delete[] wb; delete[] bias;
     g_round_bf = false;
     return;
@@ -661,6 +780,51 @@ static void dense_case_bf() {
     emu_gemm_bf<T, RIn, RIn, EpiSlab>(a, b, e, Out, In, Bn, 32, 1, 1);
     check("fc_bwd_w", "6x72->36 bf16", dw, ref);
   }
+  {  // the same three products over operands stored as bf16 (extents are multiples of 8: 72, 40)
+    const int Out8 = 40;
+    auto to16 = [](const float* src, long n) {
+      uint16_t* d = new uint16_t[n];
+      for (long i = 0; i < n; ++i) d[i] = (uint16_t)bf16_bits(src[i]);
+      return d;
+    };
+    float* w8 = new float[Out8 * In];
+    float* dy8 = new float[Bn * Out8];
+    for (int i = 0; i < Out8 * In; ++i) w8[i] = frand();
+    for (int i = 0; i < Bn * Out8; ++i) dy8[i] = frand();
+    uint16_t *x16 = to16(x, Bn * In), *w16 = to16(w8, Out8 * In), *dy16 = to16(dy8, Bn * Out8);
+    typedef DenseKInner16<128, 32> K16;
+    typedef DenseRowInner16<128, 32> R16;
+    {
+      const int ns = 2, kc = 64;
+      std::vector<float> ws(ns * Bn * Out8, NAN), y(Bn * Out8, 0.f);
+      std::vector<double> ref(Bn * Out8, 0.0);
+      for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out8; ++o) for (int i = 0; i < In; ++i) ref[n * Out8 + o] += (double)x[n * In + i] * w8[o * In + i];
+      DenseParams a{(const float*)x16, In, 0, Bn, Bn * In * 2}, b{(const float*)w16, In, 0, Out8, Out8 * In * 2};
+      EpiSlab e{ws.data(), (long)Bn * Out8, Out8, nullptr};
+      emu_gemm_bf<T, K16, K16, EpiSlab>(a, b, e, Bn, Out8, In, kc, ns, 1);
+      for (int sp = 0; sp < ns; ++sp) for (int i = 0; i < Bn * Out8; ++i) y[i] += ws[sp * Bn * Out8 + i];
+      check("fc_fwd16", "6x72->40 s2", y, ref);
+    }
+    {
+      std::vector<float> dx(Bn * In, NAN);
+      std::vector<double> ref(Bn * In, 0.0);
+      for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out8; ++o) for (int i = 0; i < In; ++i) ref[n * In + i] += (double)dy8[n * Out8 + o] * w8[o * In + i];
+      DenseParams a{(const float*)dy16, Out8, 0, Bn, Bn * Out8 * 2}, b{(const float*)w16, In, 0, In, Out8 * In * 2};
+      EpiSlab e{dx.data(), (long)Bn * In, In, nullptr};
+      emu_gemm_bf<T, K16, R16, EpiSlab>(a, b, e, Bn, In, Out8, 64, 1, 1);
+      check("fc_bwd_x16", "6x72->40", dx, ref);
+    }
+    {
+      std::vector<float> dw(Out8 * In, NAN);
+      std::vector<double> ref(Out8 * In, 0.0);
+      for (int n = 0; n < Bn; ++n) for (int o = 0; o < Out8; ++o) for (int i = 0; i < In; ++i) ref[o * In + i] += (double)dy8[n * Out8 + o] * x[n * In + i];
+      DenseParams a{(const float*)dy16, Out8, 0, Out8, Bn * Out8 * 2}, b{(const float*)x16, In, 0, In, Bn * In * 2};
+      EpiSlab e{dw.data(), (long)Out8 * In, In, nullptr};
+      emu_gemm_bf<T, R16, R16, EpiSlab>(a, b, e, Out8, In, Bn, 32, 1, 1);
+      check("fc_bwd_w16", "6x72->40", dw, ref);
+    }
+    delete[] w8; delete[] dy8; delete[] x16; delete[] w16; delete[] dy16;
+  }
   delete[] x; delete[] w; delete[] dy;
   g_round_bf = false;
 }
@@ -724,6 +888,9 @@ int main() {
       {product_geom(48, 12, 16, 8), "1x1g12c16t48"},    // whole k-tiles in every product
       {product_geom(40, 9, 20, 12), "1x1g9c20t40"},     // ragged k and pixel counts
       {product_geom(160, 4, 32, 32), "1x1g4c32t160"},   // two row tiles
+      {geom(4, 7, 48, 80, 3, 1, 1, 2), "k3p1g2c24o40"}, // multiples of 8 but not of 32: bf16-stored operands, general taps
+      {geom(4, 7, 16, 24, 5, 1, 2, 1), "k5p2c16o24"},   // 25 taps over bf16-stored operands, 24 columns in a 64-wide tile
+      {geom(2, 15, 64, 136, 3, 1, 1, 1), "k3c64o136"},  // bf16-stored operands: two column tiles, the second ragged
   };
   for (const Case& cs : cases) {
     run_case<Tile<128, 128, 32, 2, 2>>(cs);
@@ -733,6 +900,7 @@ int main() {
     run_case<Tile<128, 48, 32, 4, 1, 16>>(cs);
     run_case<Tile<128, 128, 32, 2, 2>, true>(cs);
     run_case<Tile<128, 64, 32, 4, 1>, true>(cs);
+    run_case<Tile<256, 128, 32, 2, 2>, true>(cs);
   }
   dense_case<128, 16>();
   dense_case_bf();
