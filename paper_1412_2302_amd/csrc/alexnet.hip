@@ -94,6 +94,11 @@ struct Stage {
   // which the products then read instead of rounding fp32 values on the fly
   bool b16;
   uint16_t *x16, *dy16, *wf16, *wb16;
+  // bf16 handles, first layer (three-channel pictures): the pictures as bf16 with four channels per pixel and the
+  // weights for that view (conv_plan.h, run16); x16 then holds the padded pictures, wf16 those weights
+  bool r16;
+  uint16_t* x16_own;  // the stage's own x16; in a training or inference pass the first layer's x16 points at the
+                      // padded copy that preprocessing left beside the input slot instead
   uint8_t* slot;
   char lab[4][16];  // profiling labels: stage, .fwd, .bwd_w, .bwd_x
   long act_elems() const { return g.out_elems(); }
@@ -133,6 +138,7 @@ struct alexnet {
   size_t n_params, n_weights, ws_bytes;
   float *params, *mom, *grads;
   float* input[kSlots];
+  uint16_t* input16[kSlots];  // bf16 handles whose first layer takes them: the inputs with four channels per pixel
   int32_t *crop_x[kSlots], *crop_y[kSlots], *flip[kSlots];
   float *gemm_ws, *colsum_ws, *row_loss, *scratch_x, *scratch_y, *scratch_w[3];
   float *wino_a, *wino_m, *wino_du;  // transformed operand / product / tap-gradient scratch shared by the stages
@@ -271,9 +277,11 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     s.wrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     s.dwrun = conv_run_mode(s.g) ? a.take<float>(conv_run_w_floats(s.g)) : nullptr;
     s.b16 = c.precision == ALEXNET_PRECISION_BF16 && conv_bf16_stored_ok(s.g) && s.w_off % 4 == 0;
-    s.x16 = s.b16 ? a.take<uint16_t>(s.g.in_elems()) : nullptr;
+    s.r16 = c.precision == ALEXNET_PRECISION_BF16 && !s.b16 && conv_run16_ok(s.g) && s.w_off % 4 == 0;
+    s.x16 = s.b16 ? a.take<uint16_t>(s.g.in_elems()) : s.r16 ? a.take<uint16_t>(conv_run16_x_elems(s.g)) : nullptr;
+    s.x16_own = s.x16;
     s.dy16 = s.b16 ? a.take<uint16_t>(ae) : nullptr;
-    s.wf16 = s.b16 ? a.take<uint16_t>(s.g.w_elems()) : nullptr;
+    s.wf16 = s.b16 ? a.take<uint16_t>(s.g.w_elems()) : s.r16 ? a.take<uint16_t>(conv_run16_w_elems(s.g)) : nullptr;
     s.wb16 = s.b16 ? a.take<uint16_t>(s.g.w_elems()) : nullptr;
     s.wino = use_winograd(c, s.g) && s.w_off % 4 == 0 && s.b_off % 4 == 0;
     s.wino_bx = s.wino && wino_bwd_data_ok(s.g);
@@ -330,6 +338,8 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
     cws = std::max(cws, colsum_ws_floats(c.batch, f.out));
     cws_batch += colsum_batch_ws_floats(c.batch, f.out);
   }
+  for (int sl = 0; sl < kSlots; ++sl)
+    n->input16[sl] = n->st[0].r16 ? a.take<uint16_t>(conv_run16_x_elems(n->st[0].g)) : nullptr;
   n->grads = a.take<float>(n->n_params);
   n->wino_a = wscr ? a.take<float>(wscr) : nullptr;
   n->wino_m = wscr ? a.take<float>(wscr) : nullptr;
@@ -384,6 +394,11 @@ static int stage_fwd(alexnet* n, Stage& s, const float* x, const float* wf, cons
     if (!taps_ready) AX_TRY(launch_to_bf16_transposed(wf, s.wf16, s.g.groups, s.g.kf(), s.g.og(), st));
     return launch_conv_fwd(s.g, x, wf, nullptr, bias, relu, y, n->gemm_ws, st, s.x16, s.wf16, y16);
   }
+  if (s.r16) {  // x16_ready: s.x16 holds the pictures padded to four channels
+    if (!x16_ready) AX_TRY(launch_pad4_bf16(x, s.x16, (size_t)s.g.Q(), s.g.Cin, st));
+    if (!taps_ready) AX_TRY(launch_run16_pack(wf, s.wf16, s.g.k, s.g.Cin, (int)(conv_run16_w_elems(s.g) / ((size_t)s.g.k * s.g.Cout)), s.g.Cout, st));
+    return launch_conv_fwd_run16(s.g, s.x16, s.wf16, bias, relu, y, n->gemm_ws, st, y16);
+  }
   if (s.wrun) AX_TRY(launch_conv_run_pack(s.g, wf, s.wrun, st));
   return launch_conv_fwd(s.g, x, wf, s.wrun, bias, relu, y, n->gemm_ws, st, nullptr, nullptr, y16);
 }
@@ -428,20 +443,26 @@ static int stage_bwd_data(alexnet* n, Stage& s, const float* dy, const float* wf
 // --------------------------------------------------------------- passes ------
 // taps_ready: recorded on another stream once every stage's transformed forward taps are in place (null: they
 // are made here)
+// in16: the padded bf16 copy of `in` that preprocessing left (bf16 handles; null: the first layer makes its own)
 static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, hipStream_t st,
-                       hipEvent_t taps_ready = nullptr) {
+                       hipEvent_t taps_ready = nullptr, uint16_t* in16 = nullptr) {
   const alexnet_config_t& c = n->cfg;
   set_gemm_precision(c.precision);
   const float* h = in;
   bool waited = false;
   bool x16_ready = false;  // the kernel that made h also left its bf16 copy in the next stage's x16
+  n->st[0].x16 = n->st[0].x16_own;
+  if (in16 && n->st[0].r16) {
+    n->st[0].x16 = in16;
+    x16_ready = true;
+  }
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
     // bf16 handles: whoever writes this stage's output also writes the bf16 copy the next stage multiplies with
     uint16_t* next16 = (i + 1 < kStages && n->st[i + 1].b16) ? n->st[i + 1].x16 : nullptr;
     {
       ProfContext pc(s.lab[1]);
-      if ((s.wino || s.b16) && taps_ready && !waited) {
+      if ((s.wino || s.b16 || s.r16) && taps_ready && !waited) {
         AX_HIP(hipStreamWaitEvent(st, taps_ready, 0));
         waited = true;
       }
@@ -612,7 +633,7 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
 static int fwd_bwd(alexnet* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss, hipStream_t st,
                    bool early_update = false) {
   const alexnet_config_t& c = n->cfg;
-  AX_TRY(run_forward(n, n->input[slot], true, step, st, early_update ? n->ev_u_done : nullptr));
+  AX_TRY(run_forward(n, n->input[slot], true, step, st, early_update ? n->ev_u_done : nullptr, n->input16[slot]));
   Dense& last = n->fc[kFc - 1];
   AX_TRY(launch_softmax_xent(last.act, d_labels, c.batch, last.out, 0, last.dz, n->row_loss, n->err_flag, st));
   AX_TRY(launch_mean_loss(n->row_loss, c.batch, d_loss, st));
@@ -651,6 +672,7 @@ static int stage_of(alexnet* n, int32_t layer, Stage** s) {
     return ALEXNET_EINVAL;
   }
   *s = &n->st[layer - 1];
+  (*s)->x16 = (*s)->x16_own;
   set_gemm_precision(n->cfg.precision);
   return ALEXNET_OK;
 }
@@ -787,7 +809,7 @@ int alexnet_preprocess(alexnet_t* n, const uint8_t* d_raw, const float* d_mean, 
   AX_TRY(launch_crop_params(key, c.batch, c.raw_w - c.crop_w + 1, c.raw_h - c.crop_h + 1, n->crop_x[slot],
                             n->crop_y[slot], n->flip[slot], S(stream)));
   return launch_preprocess(d_raw, d_mean, n->crop_x[slot], n->crop_y[slot], n->flip[slot], c.batch, c.in_c, c.raw_h,
-                           c.raw_w, c.crop_h, c.crop_w, n->input[slot], S(stream));
+                           c.raw_w, c.crop_h, c.crop_w, n->input[slot], S(stream), n->input16[slot]);
 }
 
 int alexnet_preprocess_center(alexnet_t* n, const uint8_t* d_raw, const float* d_mean, int32_t slot, void* stream) {
@@ -797,14 +819,17 @@ int alexnet_preprocess_center(alexnet_t* n, const uint8_t* d_raw, const float* d
   AX_TRY(launch_crop_center(c.batch, (c.raw_w - c.crop_w) / 2, (c.raw_h - c.crop_h) / 2, n->crop_x[slot],
                             n->crop_y[slot], n->flip[slot], S(stream)));
   return launch_preprocess(d_raw, d_mean, n->crop_x[slot], n->crop_y[slot], n->flip[slot], c.batch, c.in_c, c.raw_h,
-                           c.raw_w, c.crop_h, c.crop_w, n->input[slot], S(stream));
+                           c.raw_w, c.crop_h, c.crop_w, n->input[slot], S(stream), n->input16[slot]);
 }
 
 int alexnet_set_input(alexnet_t* n, const float* d_input_nchw, int32_t slot, void* stream) {
   REQUIRE(n && d_input_nchw, ALEXNET_EINVAL, "alexnet_set_input: null argument");
   REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_set_input: slot must be 0 or 1");
   const alexnet_config_t& c = n->cfg;
-  return launch_nchw_to_nhwc(d_input_nchw, n->input[slot], c.batch, c.in_c, c.crop_h, c.crop_w, S(stream));
+  AX_TRY(launch_nchw_to_nhwc(d_input_nchw, n->input[slot], c.batch, c.in_c, c.crop_h, c.crop_w, S(stream)));
+  if (n->input16[slot])
+    AX_TRY(launch_pad4_bf16(n->input[slot], n->input16[slot], (size_t)c.batch * c.crop_h * c.crop_w, c.in_c, S(stream)));
+  return ALEXNET_OK;
 }
 
 int alexnet_forward_backward(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss,
@@ -838,6 +863,9 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
       if (s.wino) AX_TRY(launch_wino_filter(s.g, n->params + s.w_off, s.wino_u, n->upd_stream));
       if (s.b16)
         AX_TRY(launch_to_bf16_transposed(n->params + s.w_off, s.wf16, s.g.groups, s.g.kf(), s.g.og(), n->upd_stream));
+      if (s.r16)
+        AX_TRY(launch_run16_pack(n->params + s.w_off, s.wf16, s.g.k, s.g.Cin,
+                                 (int)(conv_run16_w_elems(s.g) / ((size_t)s.g.k * s.g.Cout)), s.g.Cout, n->upd_stream));
     }
     AX_HIP(hipEventRecord(n->ev_u_done, n->upd_stream));
     for (int i = 1; i < kStages; ++i) {
@@ -862,7 +890,7 @@ int alexnet_forward(alexnet_t* n, const float* d_input_nchw, float* d_probs, voi
   REQUIRE(n && d_input_nchw && d_probs, ALEXNET_EINVAL, "alexnet_forward: null argument");
   const alexnet_config_t& c = n->cfg;
   AX_TRY(launch_nchw_to_nhwc(d_input_nchw, n->input[2], c.batch, c.in_c, c.crop_h, c.crop_w, S(stream)));
-  AX_TRY(run_forward(n, n->input[2], false, 0, S(stream)));
+  AX_TRY(run_forward(n, n->input[2], false, 0, S(stream)));  // the first layer pads its own bf16 copy
   Dense& last = n->fc[kFc - 1];
   return launch_softmax_xent(last.act, nullptr, c.batch, last.out, 1, d_probs, n->row_loss, n->err_flag, S(stream));
 }
@@ -873,7 +901,7 @@ int alexnet_validate(alexnet_t* n, int32_t slot, const int32_t* d_labels, const 
   REQUIRE(slot == 0 || slot == 1, ALEXNET_EINVAL, "alexnet_validate: slot must be 0 or 1");
   REQUIRE(nk >= 1 && nk <= 8, ALEXNET_EINVAL, "alexnet_validate: between 1 and 8 values of k");
   for (int j = 0; j < nk; ++j) REQUIRE(ks[j] >= 1, ALEXNET_EINVAL, "alexnet_validate: k must be positive");
-  AX_TRY(run_forward(n, n->input[slot], false, 0, S(stream)));
+  AX_TRY(run_forward(n, n->input[slot], false, 0, S(stream), nullptr, n->input16[slot]));
   Dense& last = n->fc[kFc - 1];
   // the order of the scores is the order of the probabilities, so the logits are counted directly
   return launch_topk_count(last.act, d_labels, n->cfg.batch, last.out, ks, nk, d_counts, n->err_flag, S(stream));

@@ -315,6 +315,7 @@ static int by_tile_tap(const GemmPlan& p, const Im2colParams& a, const DensePara
 }
 
 // t48: the 48-column tile may be used (its loaders need a k-tile of 32 inside one tap)
+static GemmPlan run16_fwd_plan(const ConvGeom& c);
 // t256: the 256-row tile may be used (bf16-stored operands)
 static GemmPlan fwd_plan(const ConvGeom& c, bool run, bool bf, bool t48 = false, bool t256 = false) {
   const GemmDims d = fwd_dims(c);
@@ -336,6 +337,7 @@ size_t conv_fwd_ws_floats(const ConvGeom& c) {
     for (int bf = 0; bf < 2; ++bf) ns = std::max(ns, fwd_plan(c, run && run_mode(c), bf).ns);
   ns = std::max(ns, fwd_plan(c, false, false, true).ns);
   ns = std::max(ns, fwd_plan(c, false, true, false, true).ns);
+  if (run16_mode(c)) ns = std::max(ns, run16_fwd_plan(c).ns);
   return ns > 1 ? (size_t)ns * c.out_elems() : 0;
 }
 size_t conv_bwd_data_ws_floats(const ConvGeom& c) {
@@ -449,6 +451,43 @@ int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const fl
   return finish(launch_slab_finish(ws, p.ns, d.groups, d.M, d.N, bias, relu, nullptr, y, st));
 }
 
+// ---- the first layer over bf16 pictures with four channels per pixel (conv_plan.h, run16) ----
+bool conv_run16_ok(const ConvGeom& c) { return run16_mode(c); }
+size_t conv_run16_x_elems(const ConvGeom& c) { return run16_mode(c) ? (size_t)run16_x_elems(c) : 0; }
+size_t conv_run16_w_elems(const ConvGeom& c) { return run16_mode(c) ? (size_t)run16_w_elems(c) : 0; }
+static GemmPlan run16_fwd_plan(const ConvGeom& c) {
+  const GemmDims d = fwd_dims(c);
+  return plan_gemm(d.M, d.N, run16_k(c), 1, (double)c.out_elems() * 4, 8, true, false, 0, true);
+}
+struct ConvRun16 {
+  template <class T, class Epi>
+  static int go(const Im2colParams& a, const DenseParams& b, const Epi& e, const GemmDims& d, int kchunk, int ns,
+                hipStream_t st) {
+    return launch_tile_bf<T, Im2colKInner16<T::BM, T::BK, IM2COL_FWD>, DenseKInner16<T::BN, T::BK>, Epi>(
+        a, b, e, d.M, d.N, d.K, kchunk, ns, d.groups, st);
+  }
+};
+int launch_conv_fwd_run16(const ConvGeom& c, const uint16_t* x4, const uint16_t* wk, const float* bias, int relu,
+                          float* y, float* ws, hipStream_t st, uint16_t* y16) {
+  if (!run16_mode(c) || !aligned16(x4) || !aligned16(wk)) {
+    set_error("conv run16: geometry or alignment does not allow it");
+    return ALEXNET_EINVAL;
+  }
+  AlgoFlops af(conv_flops(c), conv_bytes(c));
+  GemmDims d = fwd_dims(c);
+  d.K = run16_k(c);
+  const Im2colParams a = run16_A(c, x4);
+  const DenseParams b = run16_Bk(c, wk);
+  const GemmPlan p = run16_fwd_plan(c);
+  if (p.ns == 1) {
+    EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0, 0, y16};
+    return by_tile_16<ConvRun16>(p, a, b, ep, d, st);
+  }
+  EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};
+  AX_TRY((by_tile_16<ConvRun16>(p, a, b, ep, d, st)));
+  AX_TRY(launch_slab_finish(ws, p.ns, 1, d.M, d.N, bias, relu, nullptr, y, st));
+  return y16 ? launch_to_bf16(y, y16, (size_t)c.out_elems(), st) : ALEXNET_OK;
+}
 // ---- strided backward data by phases (conv_plan.h) ----
 bool conv_phase_mode(const ConvGeom& c) { return phase_mode(c) && c.Cout % 4 == 0 && phase_n(c) % 4 == 0; }
 size_t conv_phase_w_floats(const ConvGeom& c) { return conv_phase_mode(c) ? (size_t)phase_w_elems(c) : 0; }

@@ -176,6 +176,33 @@ inline DenseParams bwdd_B16k(const ConvGeom& c, const uint16_t* wbk) {
   b.bytes = (uint32_t)(c.w_elems() * 2);
   return b;
 }
+// ---- run mode over pictures stored as bf16 with their channels padded to four ----
+// The first layer's pictures have three channels.  Stored as bf16 x4[N][H][W][4] (fourth channel zero), viewed as
+// a one-channel tensor x'[N][H][W*4], all taps (s, c) of kernel row r are one contiguous run of k*4 values
+// starting at column x*stride*4, which is a multiple of 8 bytes: it is read in 16-byte pieces of eight values
+// and padded to a multiple of eight with weights that are zero.  The padding reads values of the next pixels (of
+// the next row at the right edge; nothing past the end of the tensor, where the loads return zero), which meet
+// zero weights.  Reduction length k * run16_len(); the weights are wk[o][(r, s*4 + c)], k-contiguous.
+inline bool run16_mode(const ConvGeom& c) { return run_mode(c) && c.Cin < 4 && c.Cout % 8 == 0; }
+inline int run16_len(const ConvGeom& c) { return (c.k * 4 + 7) / 8 * 8; }
+inline int run16_k(const ConvGeom& c) { return c.k * run16_len(c); }
+inline long run16_x_elems(const ConvGeom& c) { return (long)c.B * c.H * c.W * 4; }
+inline long run16_w_elems(const ConvGeom& c) { return (long)run16_k(c) * c.Cout; }
+inline Im2colParams run16_A(const ConvGeom& c, const uint16_t* x4) {
+  Im2colParams a;
+  a.x = reinterpret_cast<const float*>(x4); a.bytes = (uint32_t)(run16_x_elems(c) * 2);
+  a.H = c.H; a.W = c.W * 4; a.Ctot = 1; a.Cg = run16_len(c); a.c_stride_g = 0;
+  a.kh = c.k; a.kw = 1; a.stride = c.stride; a.pad = 0; a.stride_x = c.stride * 4; a.pad_x = 0;
+  a.OH = c.Ho; a.OW = c.Wo; a.P = (int)c.P();
+  fill_divs(a);
+  return a;
+}
+inline DenseParams run16_Bk(const ConvGeom& c, const uint16_t* wk) {
+  DenseParams b;
+  b.p = reinterpret_cast<const float*>(wk); b.ld = run16_k(c); b.gstride = 0; b.R = c.Cout;
+  b.bytes = (uint32_t)(run16_w_elems(c) * 2);
+  return b;
+}
 // every extent a 16-byte load of bf16 must not straddle is a multiple of 8
 inline bool conv16_ok(const ConvGeom& c) { return c.cg() % 8 == 0 && c.og() % 8 == 0 && c.stride == 1; }
 

@@ -53,6 +53,15 @@ bool conv_bf16_stored_ok(const ConvGeom& c);
 int launch_conv_fwd(const ConvGeom& c, const float* x, const float* wf, const float* wrun, const float* bias,
                     int relu, float* y, float* ws, hipStream_t st, const uint16_t* x16 = nullptr,
                     const uint16_t* wf16 = nullptr, uint16_t* y16 = nullptr);
+// The first layer with bf16 products over pictures stored as bf16, four channels per pixel (conv_plan.h, run16):
+// x4 from launch_pad4_bf16 (or the preprocessing kernel), wk from launch_run16_pack.  conv_run16_ok(): the
+// geometry allows it.  (The weight gradient keeps the fp32 pictures: over this view its reduction has 528 rows,
+// five 128-row tiles where the run mode of gemm.h has four, and measured slower.)
+bool conv_run16_ok(const ConvGeom& c);
+size_t conv_run16_x_elems(const ConvGeom& c);
+size_t conv_run16_w_elems(const ConvGeom& c);
+int launch_conv_fwd_run16(const ConvGeom& c, const uint16_t* x4, const uint16_t* wk, const float* bias, int relu,
+                          float* y, float* ws, hipStream_t st, uint16_t* y16 = nullptr);
 // Strided, ungrouped, ungated backward-data runs by phases when `wphase` (conv_phase_w_floats() floats of
 // scratch) is given; it then reads the forward weights wf instead of wb.
 bool conv_phase_mode(const ConvGeom& c);
@@ -112,11 +121,16 @@ int launch_fill(float* p, size_t n, float v, hipStream_t st);
 int launch_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
 // dst[g][n][k] = bf16(src[g][k][n]) for G matrices of K x N
 int launch_to_bf16_transposed(const float* src, uint16_t* dst, int G, int K, int N, hipStream_t st);
+// pictures with C < 4 channels as bf16 with four channels per pixel (the rest zero); the first layer's packed
+// weights as bf16 wk[o][(r, s*4 + c)] for that view
+int launch_pad4_bf16(const float* x, uint16_t* x4, size_t pixels, int C, hipStream_t st);
+int launch_run16_pack(const float* wf, uint16_t* wk, int k, int C, int run, int cout, hipStream_t st);
 int launch_fill_bytes(void* p, size_t nbytes, hipStream_t st);  // zero fill, nbytes % 4 == 0
 int launch_crop_params(uint64_t key, int B, int range_x, int range_y, int32_t* ox, int32_t* oy, int32_t* flip,
                        hipStream_t st);
 int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, const int32_t* oy,
-                      const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st);
+                      const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st,
+                      uint16_t* out4 = nullptr);  // out4: also the pictures as bf16, four channels per pixel (C <= 4)
 int launch_nchw_to_nhwc(const float* src, float* dst, int N, int C, int H, int W, hipStream_t st);
 int launch_nhwc_to_nchw(const float* src, float* dst, int N, int C, int H, int W, hipStream_t st);
 int launch_lrn_fwd(const float* a, float* b, long pixels, int C, int n, float k, float alpha, float beta,

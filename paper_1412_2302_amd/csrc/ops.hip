@@ -97,6 +97,46 @@ int launch_to_bf16_transposed(const float* src, uint16_t* dst, int G, int K, int
   return ALEXNET_OK;
 }
 
+// x4[p][0..3] = bf16(x[p][0..C-1]), 0 for the channels past C (C < 4): pictures for the first layer's bf16 products
+__global__ void __launch_bounds__(256) pad4_bf16_kernel(const float* __restrict__ x, uint16_t* __restrict__ x4,
+                                                        size_t pixels, int C) {
+  const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= pixels) return;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float* s = x + p * C;
+  v.x = s[0];
+  if (C > 1) v.y = s[1];
+  if (C > 2) v.z = s[2];
+  store_bf16x4(x4 + p * 4, v);
+}
+int launch_pad4_bf16(const float* x, uint16_t* x4, size_t pixels, int C, hipStream_t st) {
+  if (!pixels) return ALEXNET_OK;
+  KernelScope ks("to_bf16", 0, (double)pixels * (C * 4.0 + 8.0), st);
+  hipLaunchKernelGGL(pad4_bf16_kernel, dim3(grid_for(pixels, 256)), dim3(256), 0, st, x, x4, pixels, C);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+// wk[o][r*run + s*4 + c] = bf16(wf[(r, s, c)][o]) for s < k, c < C, else 0
+__global__ void __launch_bounds__(256) run16_pack_kernel(const float* __restrict__ wf, uint16_t* __restrict__ wk, int k,
+                                                         int C, int run, int cout) {
+  const size_t total = (size_t)cout * k * run;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into wk
+  if (i >= total) return;
+  const int j = (int)(i % run);
+  const size_t q = i / run;
+  const int r = (int)(q % k), o = (int)(q / k);
+  const int s2 = j >> 2, c = j & 3;
+  const float v = (s2 < k && c < C) ? wf[((size_t)(r * k + s2) * C + c) * cout + o] : 0.f;
+  store_bf16(wk + i, v);
+}
+int launch_run16_pack(const float* wf, uint16_t* wk, int k, int C, int run, int cout, hipStream_t st) {
+  const size_t total = (size_t)cout * k * run;
+  KernelScope ks("to_bf16", 0, (double)total * 6.0, st);
+  hipLaunchKernelGGL(run16_pack_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, wf, wk, k, C, run, cout);
+  AX_LAUNCH_CHECK();
+  return ALEXNET_OK;
+}
+
 __global__ void copy_kernel(const float* __restrict__ s, float* __restrict__ d, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -151,7 +191,8 @@ constexpr int kPreRows = 4;  // rows (waves) per workgroup
 __global__ void __launch_bounds__(64 * kPreRows)
 preprocess_kernel(const uint8_t* __restrict__ raw, const float* __restrict__ mean, const int32_t* __restrict__ ox,
                   const int32_t* __restrict__ oy, const int32_t* __restrict__ flip, uint32_t rows, int C, int RH,
-                  int RW, int CH, int CW, FastDiv div_c, FastDiv div_ch, float* __restrict__ out) {
+                  int RW, int CH, int CW, FastDiv div_c, FastDiv div_ch, float* __restrict__ out,
+                  uint16_t* __restrict__ out4) {
   const uint32_t row = blockIdx.x * kPreRows + (threadIdx.x >> 6);  // n*CH + y, the same for the whole wave
   if (row >= rows) return;
   const uint32_t lane = threadIdx.x & 63;
@@ -169,9 +210,27 @@ preprocess_kernel(const uint8_t* __restrict__ raw, const float* __restrict__ mea
     const uint32_t src = c * plane + (uint32_t)x0 + (mirror ? (uint32_t)CW - 1u - x : x);
     op[e] = (float)rp[src] - mp[src];
   }
+  if (out4) {  // the same row as bf16 with four channels per pixel (the rest zero), for bf16 first-layer products:
+               // a lane owns whole pixels, so that a wave stores 512 consecutive bytes
+    uint16_t* o4 = out4 + (size_t)row * CW * 4;
+    for (uint32_t x = lane; x < (uint32_t)CW; x += 64) {
+      const uint32_t sx = (uint32_t)x0 + (mirror ? (uint32_t)CW - 1u - x : x);
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      v.x = (float)rp[sx] - mp[sx];
+      if (C > 1) v.y = (float)rp[plane + sx] - mp[plane + sx];
+      if (C > 2) v.z = (float)rp[2 * plane + sx] - mp[2 * plane + sx];
+      if (C > 3) v.w = (float)rp[3 * plane + sx] - mp[3 * plane + sx];
+      store_bf16x4(o4 + (size_t)x * 4, v);
+    }
+  }
 }
 int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, const int32_t* oy,
-                      const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st) {
+                      const int32_t* flip, int B, int C, int RH, int RW, int CH, int CW, float* out, hipStream_t st,
+                      uint16_t* out4) {
+  if (out4 && C > 4) {
+    set_error("preprocess: the four-channel bf16 copy needs at most four channels");
+    return ALEXNET_EINVAL;
+  }
   const size_t total = (size_t)B * CH * CW * C;
   if (!total) return ALEXNET_OK;
   if (total >= 0x7fffffffu || (size_t)C * RH * RW >= 0x7fffffffu) {
@@ -181,7 +240,7 @@ int launch_preprocess(const uint8_t* raw, const float* mean, const int32_t* ox, 
   KernelScope ks("preprocess", 0, (double)total * 5.0, st);
   const uint32_t rows = (uint32_t)B * (uint32_t)CH;
   hipLaunchKernelGGL(preprocess_kernel, dim3(ceil_div(rows, kPreRows)), dim3(64 * kPreRows), 0, st, raw, mean, ox, oy,
-                     flip, rows, C, RH, RW, CH, CW, make_fastdiv((uint32_t)C), make_fastdiv((uint32_t)CH), out);
+                     flip, rows, C, RH, RW, CH, CW, make_fastdiv((uint32_t)C), make_fastdiv((uint32_t)CH), out, out4);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }

@@ -42,7 +42,7 @@ def _kind(got, exact, plain):
     return ("bf16", e_bf, e_fp) if e_bf < e_fp else ("fp32", e_fp, e_fp)
 
 
-@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5)])
+@pytest.mark.parametrize("wl,batch", [(S.MINI, 4), (S.MIDI, 5), (S.MINI, 32)])
 def test_bf16_conv_layers_alone(lib, wl, batch):
     net = lib.AlexNet(wl, batch, precision=1)
     spec = oracle_spec(wl, batch)
