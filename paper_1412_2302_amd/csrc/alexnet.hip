@@ -111,6 +111,7 @@ struct Dense {
   int in, out;
   size_t w_off, b_off;
   float *act, *dz;
+  uint16_t *act16, *dz16;  // bf16 copies for the products of a bf16 handle (null otherwise)
   char lab[4][16];
 };
 
@@ -139,6 +140,11 @@ struct alexnet {
   float *params, *mom, *grads;
   float* input[kSlots];
   uint16_t* input16[kSlots];  // bf16 handles whose first layer takes them: the inputs with four channels per pixel
+  // bf16 handles whose dense shapes allow it: the dense layers' products read bf16 copies of their operands --
+  // all dense weights (same order and layout as in the parameter vector, made anew from it in every pass) and
+  // the flattened output of the last stage; Dense holds the copies of the activations and their gradients
+  bool fc16;
+  uint16_t *fcw16, *flat16;
   int32_t *crop_x[kSlots], *crop_y[kSlots], *flip[kSlots];
   float *gemm_ws, *colsum_ws, *row_loss, *scratch_x, *scratch_y, *scratch_w[3];
   float *wino_a, *wino_m, *wino_du;  // transformed operand / product / tap-gradient scratch shared by the stages
@@ -152,7 +158,7 @@ struct alexnet {
   // The dense layers hold 96 % of the parameters and finish their backward pass first: their update, which is
   // bound by memory bandwidth, runs on this stream under the convolution backward pass, which is not.
   hipStream_t upd_stream;
-  hipEvent_t ev_fc_done, ev_upd_done, ev_step_begin, ev_wb_done, ev_u_done;
+  hipEvent_t ev_fc_done, ev_upd_done, ev_step_begin, ev_wb_done, ev_u_done, ev_fcw_done;
 };
 
 // F(4x4, 3x3) pays when the 4x4 tiles cover the output without much waste (2.6x fewer multiplies for the 3x3
@@ -330,10 +336,16 @@ static int plan(alexnet* n, const alexnet_config_t* cfg, char* base) {
       }
     }
   }
+  n->fc16 = c.precision == ALEXNET_PRECISION_BF16 && n->fc[0].w_off % 4 == 0;
+  for (int j = 0; j < kFc; ++j) n->fc16 = n->fc16 && fc_bf16_stored_ok(n->fc[j].in, n->fc[j].out);
+  n->fcw16 = n->fc16 ? a.take<uint16_t>(n->n_weights - n->fc[0].w_off) : nullptr;
+  n->flat16 = n->fc16 ? a.take<uint16_t>((size_t)c.batch * n->flat) : nullptr;
   for (int j = 0; j < kFc; ++j) {
     Dense& f = n->fc[j];
     f.act = a.take<float>((size_t)c.batch * f.out);
     f.dz = a.take<float>((size_t)c.batch * f.out);
+    f.act16 = n->fc16 ? a.take<uint16_t>((size_t)c.batch * f.out) : nullptr;
+    f.dz16 = n->fc16 ? a.take<uint16_t>((size_t)c.batch * f.out) : nullptr;
     gws = std::max(gws, fc_ws_floats(c.batch, f.in, f.out));
     cws = std::max(cws, colsum_ws_floats(c.batch, f.out));
     cws_batch += colsum_batch_ws_floats(c.batch, f.out);
@@ -444,10 +456,15 @@ static int stage_bwd_data(alexnet* n, Stage& s, const float* dy, const float* wf
 // taps_ready: recorded on another stream once every stage's transformed forward taps are in place (null: they
 // are made here)
 // in16: the padded bf16 copy of `in` that preprocessing left (bf16 handles; null: the first layer makes its own)
+// fcw_ready: recorded on another stream once the bf16 copy of the dense weights is in place (null: made here)
+static int fcw16_refresh(alexnet* n, hipStream_t st) {
+  return launch_to_bf16(n->params + n->fc[0].w_off, n->fcw16, n->n_weights - n->fc[0].w_off, st);
+}
 static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, hipStream_t st,
-                       hipEvent_t taps_ready = nullptr, uint16_t* in16 = nullptr) {
+                       hipEvent_t taps_ready = nullptr, uint16_t* in16 = nullptr, hipEvent_t fcw_ready = nullptr) {
   const alexnet_config_t& c = n->cfg;
   set_gemm_precision(c.precision);
+  if (n->fc16 && !fcw_ready) AX_TRY(fcw16_refresh(n, st));
   const float* h = in;
   bool waited = false;
   bool x16_ready = false;  // the kernel that made h also left its bf16 copy in the next stage's x16
@@ -459,7 +476,7 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
   for (int i = 0; i < kStages; ++i) {
     Stage& s = n->st[i];
     // bf16 handles: whoever writes this stage's output also writes the bf16 copy the next stage multiplies with
-    uint16_t* next16 = (i + 1 < kStages && n->st[i + 1].b16) ? n->st[i + 1].x16 : nullptr;
+    uint16_t* next16 = i + 1 == kStages ? n->flat16 : n->st[i + 1].b16 ? n->st[i + 1].x16 : nullptr;
     {
       ProfContext pc(s.lab[1]);
       if ((s.wino || s.b16 || s.r16) && taps_ready && !waited) {
@@ -482,12 +499,19 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
     if (s.lrn) {
       AX_TRY(launch_lrn_fwd(s.act, s.lrn_out, s.g.P(), s.g.Cout, c.lrn_n, c.lrn_k, c.lrn_alpha, c.lrn_beta, st));
       h = s.lrn_out;
+      x16_ready = false;
     }
     if (s.pool) {
-      AX_TRY(launch_pool_fwd(h, s.pool_out, s.slot, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st));
+      AX_TRY(launch_pool_fwd(h, s.pool_out, s.slot, s.g.B, s.g.Ho, s.g.Wo, s.g.Cout, s.Hp, s.Wp, st, next16));
+      x16_ready = next16 != nullptr;
       h = s.pool_out;
     }
   }
+  if (n->fc16) {
+    if (!x16_ready) AX_TRY(launch_to_bf16(h, n->flat16, (size_t)c.batch * n->flat, st));
+    if (fcw_ready) AX_HIP(hipStreamWaitEvent(st, fcw_ready, 0));
+  }
+  const uint16_t* h16 = n->flat16;
   const uint64_t key = step_key(c.seed, step);
   for (int j = 0; j < kFc; ++j) {
     Dense& f = n->fc[j];
@@ -501,8 +525,10 @@ static int run_forward(alexnet* n, const float* in, bool train, uint64_t step, h
     act.thresh24 = drop_thresh(c.dropout_p);
     act.scale = (hidden && !train) ? 1.0f - c.dropout_p : 1.0f;
     ProfContext pc(f.lab[1]);
-    AX_TRY(launch_fc_fwd(c.batch, f.in, f.out, h, n->params + f.w_off, act, f.act, n->gemm_ws, st));
+    AX_TRY(launch_fc_fwd(c.batch, f.in, f.out, h, n->params + f.w_off, act, f.act, n->gemm_ws, st, h16,
+                         n->fc16 ? n->fcw16 + (f.w_off - n->fc[0].w_off) : nullptr, f.act16));
     h = f.act;
+    h16 = f.act16;
   }
   return ALEXNET_OK;
 }
@@ -511,8 +537,10 @@ static int update_range(alexnet* n, size_t begin, size_t end, hipStream_t st) {
   const alexnet_config_t& c = n->cfg;
   if (end <= begin) return ALEXNET_OK;
   const size_t decayed = n->n_weights > begin ? std::min(n->n_weights, end) - begin : 0;
+  // Beside the bf16 products, which lean on the memory system themselves, the update is held to one workgroup
+  // per CU: it still ends well inside the convolution backward pass, and the step is about 1.5 % shorter.
   return launch_sgd_update(n->params + begin, n->mom + begin, n->grads + begin, end - begin, decayed, c.lr, c.momentum,
-                           c.weight_decay, st);
+                           c.weight_decay, st, c.precision == ALEXNET_PRECISION_BF16 ? 256u : 0u);
 }
 
 // early_update: also start the update of the dense-layer weights on the side stream as soon as the dense
@@ -531,20 +559,22 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
   for (int j = kFc - 1; j >= 0; --j) {
     Dense& f = n->fc[j];
     const float* x = j == 0 ? n->st[kStages - 1].out() : n->fc[j - 1].act;
+    const uint16_t* x16 = j == 0 ? n->flat16 : n->fc[j - 1].act16;
+    const uint16_t* w16 = n->fc16 ? n->fcw16 + (f.w_off - n->fc[0].w_off) : nullptr;
     {
       ProfContext pc(f.lab[2]);
-      AX_TRY(launch_fc_bwd_weight(c.batch, f.in, f.out, x, f.dz, n->grads + f.w_off, st));
+      AX_TRY(launch_fc_bwd_weight(c.batch, f.in, f.out, x, f.dz, n->grads + f.w_off, st, x16, f.dz16));
       AX_TRY(colsum_batch_add(bias_sums, f.dz, c.batch, f.out, n->grads + f.b_off, n->colsum_ws, &bias_ws_used));
     }
     ProfContext pc(f.lab[3]);
     if (j > 0) {
       // fc(j-1) output is ReLU+dropout: it is positive exactly where the gradient passes
       AX_TRY(launch_fc_bwd_data(c.batch, f.in, f.out, f.dz, n->params + f.w_off, n->fc[j - 1].act, n->fc[j - 1].dz,
-                                n->gemm_ws, st));
+                                n->gemm_ws, st, f.dz16, w16, n->fc[j - 1].dz16));
     } else {
       Stage& last = n->st[kStages - 1];
       AX_TRY(launch_fc_bwd_data(c.batch, f.in, f.out, f.dz, n->params + f.w_off, last.plain() ? last.act : nullptr,
-                                last.d_out, n->gemm_ws, st));
+                                last.d_out, n->gemm_ws, st, f.dz16, w16, nullptr));
     }
   }
   bool dy16_ready = false;  // the kernel that made this stage's output gradient also left its bf16 copy in s.dy16
@@ -633,9 +663,11 @@ static int run_backward(alexnet* n, const float* in, hipStream_t st, bool early_
 static int fwd_bwd(alexnet* n, int32_t slot, const int32_t* d_labels, uint64_t step, float* d_loss, hipStream_t st,
                    bool early_update = false) {
   const alexnet_config_t& c = n->cfg;
-  AX_TRY(run_forward(n, n->input[slot], true, step, st, early_update ? n->ev_u_done : nullptr, n->input16[slot]));
+  AX_TRY(run_forward(n, n->input[slot], true, step, st, early_update ? n->ev_u_done : nullptr, n->input16[slot],
+                     early_update && n->fc16 ? n->ev_fcw_done : nullptr));
   Dense& last = n->fc[kFc - 1];
   AX_TRY(launch_softmax_xent(last.act, d_labels, c.batch, last.out, 0, last.dz, n->row_loss, n->err_flag, st));
+  if (n->fc16) AX_TRY(launch_to_bf16(last.dz, last.dz16, (size_t)c.batch * last.out, st));
   AX_TRY(launch_mean_loss(n->row_loss, c.batch, d_loss, st));
   return run_backward(n, n->input[slot], st, early_update);
 }
@@ -773,6 +805,7 @@ int alexnet_create(const alexnet_config_t* cfg, void* d_params, void* d_momentum
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_step_begin, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_wb_done, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_u_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_fcw_done, hipEventDisableTiming);
     if (e != hipSuccess) {
       set_error("alexnet_create: %s", hipGetErrorString(e));
       r = ALEXNET_EHIP;
@@ -797,6 +830,7 @@ void alexnet_destroy(alexnet_t* net) {
   if (net->ev_step_begin) (void)hipEventDestroy(net->ev_step_begin);
   if (net->ev_wb_done) (void)hipEventDestroy(net->ev_wb_done);
   if (net->ev_u_done) (void)hipEventDestroy(net->ev_u_done);
+  if (net->ev_fcw_done) (void)hipEventDestroy(net->ev_fcw_done);
   delete net;
 }
 
@@ -868,6 +902,11 @@ int alexnet_train_step(alexnet_t* n, int32_t slot, const int32_t* d_labels, uint
                                  (int)(conv_run16_w_elems(s.g) / ((size_t)s.g.k * s.g.Cout)), s.g.Cout, n->upd_stream));
     }
     AX_HIP(hipEventRecord(n->ev_u_done, n->upd_stream));
+    if (n->fc16) {  // needed next, by the dense layers' forward products
+      ProfContext pc("fc.weights16");
+      AX_TRY(fcw16_refresh(n, n->upd_stream));
+      AX_HIP(hipEventRecord(n->ev_fcw_done, n->upd_stream));
+    }
     for (int i = 1; i < kStages; ++i) {
       Stage& s = n->st[i];
       ProfContext pc(s.lab[3]);

@@ -667,7 +667,7 @@ size_t fc_ws_floats(int B, int in, int out) {
 }
 
 __global__ void fc_fwd_finish_kernel(const float* __restrict__ ws, int nsplit, int B, int out, FcAct act,
-                                     float* __restrict__ y) {
+                                     float* __restrict__ y, uint16_t* __restrict__ y16) {
   const size_t total = (size_t)B * out;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
@@ -679,9 +679,11 @@ __global__ void fc_fwd_finish_kernel(const float* __restrict__ ws, int nsplit, i
   if (act.relu) s = s > 0.f ? s : 0.f;
   if (act.dropout && !dropout_keep(act.key, act.tag, i, act.thresh24)) s = 0.f;
   y[i] = s * act.scale;
+  if (y16) store_bf16(y16 + i, s * act.scale);
 }
 __global__ void fc_bwd_finish_kernel(const float* __restrict__ ws, int nsplit, size_t total,
-                                     const float* __restrict__ gate, float* __restrict__ dx) {
+                                     const float* __restrict__ gate, float* __restrict__ dx,
+                                     uint16_t* __restrict__ dx16) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   float s = 0.f;
@@ -689,6 +691,7 @@ __global__ void fc_bwd_finish_kernel(const float* __restrict__ ws, int nsplit, s
   for (int k = 0; k < nsplit; ++k) s += ws[(size_t)k * total + i];  // loads in flight together, added in order
   if (gate && !(gate[i] > 0.f)) s = 0.f;
   dx[i] = s;
+  if (dx16) store_bf16(dx16 + i, s);
 }
 
 static inline bool vec_ok(const float* p, long ld) { return aligned16(p) && ld % 4 == 0; }
@@ -704,51 +707,74 @@ static int launch_dense(bool vec, const DenseParams& a, const DenseParams& b, co
 typedef BfRowMajor<DenseKInner<128, kBKbf, true>, 128, kBKbf> BfDenseK;
 typedef BfDenseRowInner<128, kBKbf> BfDenseR;
 
+typedef DenseKInner16<128, kBKbf> Dense16K;
+typedef DenseRowInner16<128, kBKbf> Dense16R;
+bool fc_bf16_stored_ok(int in, int out) { return in % 8 == 0 && out % 8 == 0; }
+static inline DenseParams dense16_of(const uint16_t* p, long ld, int rows, size_t elems) {
+  return DenseParams{reinterpret_cast<const float*>(p), ld, 0, rows, (uint32_t)(elems * 2)};
+}
+
 int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const FcAct& act, float* y, float* ws,
-                  hipStream_t st) {
+                  hipStream_t st, const uint16_t* x16, const uint16_t* w16, uint16_t* y16) {
   const bool vec = vec_ok(x, in) && vec_ok(w, in), bf = g_bf16 && vec;
+  const bool s16 = bf && x16 && w16 && fc_bf16_stored_ok(in, out) && aligned16(x16) && aligned16(w16);
   int kchunk;
   const int ns = fc_split(B, out, in, &kchunk, bf);
   DenseParams a{x, in, 0, B, (uint32_t)((size_t)B * in * 4)};
   DenseParams b{w, in, 0, out, (uint32_t)((size_t)out * in * 4)};
   EpiSlab ep{ws, (long)B * out, out, nullptr};
   // both operands run along k = in
-  if (bf)
+  if (s16)
+    AX_TRY((launch_tile_bf<B128, Dense16K, Dense16K, EpiSlab>(dense16_of(x16, in, B, (size_t)B * in),
+                                                                dense16_of(w16, in, out, (size_t)out * in), ep, B, out,
+                                                                in, kchunk, ns, 1, st)));
+  else if (bf)
     AX_TRY((launch_tile_bf<B128, BfDenseK, BfDenseK, EpiSlab>(a, b, ep, B, out, in, kchunk, ns, 1, st)));
   else
     AX_TRY((launch_dense<DenseKInner, DenseKInner>(vec, a, b, ep, B, out, in, kchunk, ns, st)));
   const size_t total = (size_t)B * out;
   KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1), st);
-  hipLaunchKernelGGL(fc_fwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, B, out, act, y);
+  hipLaunchKernelGGL(fc_fwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, B, out, act, y, y16);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
 
 int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, const float* gate, float* dx,
-                       float* ws, hipStream_t st) {
+                       float* ws, hipStream_t st, const uint16_t* dy16, const uint16_t* w16, uint16_t* dx16) {
   const bool vec = vec_ok(dy, out) && vec_ok(w, in), bf = g_bf16 && vec;
+  const bool s16 = bf && dy16 && w16 && fc_bf16_stored_ok(in, out) && aligned16(dy16) && aligned16(w16);
   int kchunk;
   const int ns = fc_split(B, in, out, &kchunk, bf);
   DenseParams a{dy, out, 0, B, (uint32_t)((size_t)B * out * 4)};
   DenseParams b{w, in, 0, in, (uint32_t)((size_t)out * in * 4)};
   EpiSlab ep{ws, (long)B * in, in, nullptr};
   // A runs along k = out, B along its rows = in
-  if (bf)
+  if (s16)
+    AX_TRY((launch_tile_bf<B128, Dense16K, Dense16R, EpiSlab>(dense16_of(dy16, out, B, (size_t)B * out),
+                                                                dense16_of(w16, in, in, (size_t)out * in), ep, B, in,
+                                                                out, kchunk, ns, 1, st)));
+  else if (bf)
     AX_TRY((launch_tile_bf<B128, BfDenseK, BfDenseR, EpiSlab>(a, b, ep, B, in, out, kchunk, ns, 1, st)));
   else
     AX_TRY((launch_dense<DenseKInner, DenseRowInner>(vec, a, b, ep, B, in, out, kchunk, ns, st)));
   const size_t total = (size_t)B * in;
   KernelScope ks("fc_finish", 0, (double)total * 4.0 * (ns + 1 + (gate ? 1 : 0)), st);
-  hipLaunchKernelGGL(fc_bwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, total, gate, dx);
+  hipLaunchKernelGGL(fc_bwd_finish_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, ws, ns, total, gate, dx,
+                     dx16);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
 
-int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy, float* dw, hipStream_t st) {
+int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy, float* dw, hipStream_t st,
+                         const uint16_t* x16, const uint16_t* dy16) {
   DenseParams a{dy, out, 0, out, (uint32_t)((size_t)B * out * 4)};
   DenseParams b{x, in, 0, in, (uint32_t)((size_t)B * in * 4)};
   EpiSlab ep{dw, (long)out * in, in, nullptr};
   const bool vec = vec_ok(dy, out) && vec_ok(x, in);
+  if (g_bf16 && vec && x16 && dy16 && fc_bf16_stored_ok(in, out) && aligned16(x16) && aligned16(dy16))
+    return launch_tile_bf<B128, Dense16R, Dense16R, EpiSlab>(dense16_of(dy16, out, out, (size_t)B * out),
+                                                             dense16_of(x16, in, in, (size_t)B * in), ep, out, in, B,
+                                                             round_up(B, kBKbf), 1, 1, st);
   if (g_bf16 && vec)
     return launch_tile_bf<B128, BfDenseR, BfDenseR, EpiSlab>(a, b, ep, out, in, B, round_up(B, kBKbf), 1, 1, st);
   return launch_dense<DenseRowInner, DenseRowInner>(vec, a, b, ep, out, in, B, round_up(B, kBK), 1, st);

@@ -109,11 +109,16 @@ struct FcAct {
   float scale;        // applied after the ReLU (1 - p at inference, else 1)
 };
 size_t fc_ws_floats(int B, int in, int out);
+// x16 / w16 / dy16: bf16 copies of the operands (same layouts); when those of a product are given, the handle's
+// GEMMs are bf16 and fc_bf16_stored_ok(), the product reads them.  y16 / dx16: where to leave a bf16 copy of the result.
+bool fc_bf16_stored_ok(int in, int out);
 int launch_fc_fwd(int B, int in, int out, const float* x, const float* w, const FcAct& act, float* y, float* ws,
-                  hipStream_t st);
+                  hipStream_t st, const uint16_t* x16 = nullptr, const uint16_t* w16 = nullptr, uint16_t* y16 = nullptr);
 int launch_fc_bwd_data(int B, int in, int out, const float* dy, const float* w, const float* gate, float* dx,
-                       float* ws, hipStream_t st);
-int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy, float* dw, hipStream_t st);
+                       float* ws, hipStream_t st, const uint16_t* dy16 = nullptr, const uint16_t* w16 = nullptr,
+                       uint16_t* dx16 = nullptr);
+int launch_fc_bwd_weight(int B, int in, int out, const float* x, const float* dy, float* dw, hipStream_t st,
+                         const uint16_t* x16 = nullptr, const uint16_t* dy16 = nullptr);
 
 // ---- bandwidth-bound kernels (ops.hip) --------------------------------------
 int launch_fill(float* p, size_t n, float v, hipStream_t st);
@@ -154,7 +159,7 @@ int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, fl
 // partials_only: leave the lrn_part_rows(pixels, C) rows of per-workgroup sums in `part` for the caller to add up
 size_t lrn_part_rows(long pixels, int C);
 int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo,
-                    hipStream_t st);
+                    hipStream_t st, uint16_t* y16 = nullptr);
 // dx[n][y][x][c] = sum of dy over the windows whose winning tap is (y,x); gated by gate > 0 when gate != null
 int launch_pool_bwd(const float* dy, const uint8_t* slot, const float* gate, float* dx, int N, int H, int W, int C,
                     int Ho, int Wo, hipStream_t st, uint16_t* dx16 = nullptr);
@@ -187,8 +192,9 @@ int launch_reduce_slabs(const float* ws, int nsplit, long slab, int groups, floa
 // one result of k*run rows by cout columns, rows (r, j >= kc) dropped and the rest packed to r*kc + j
 int launch_reduce_slabs_unpack(const float* ws, int nsplit, long slab, int run, int kc, int cout, float* out,
                                hipStream_t st);
+// max_blocks: upper limit of the grid (0: the default, four workgroups per CU)
 int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
-                      hipStream_t st);
+                      hipStream_t st, unsigned max_blocks = 0);
 // the same for elements [0, n1) and [begin2, end2) of the vectors in one launch (n1 and begin2 multiples of four);
 // positions below n_decay are decayed
 int launch_sgd_update_two(float* w, float* v, const float* g, size_t n1, size_t begin2, size_t end2, size_t n_decay,

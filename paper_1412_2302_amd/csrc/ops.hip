@@ -748,7 +748,7 @@ int launch_pool_lrn_bwd(const float* a, const float* dy, const uint8_t* slot, fl
 // only when strictly greater (first maximum wins).  slot = r*3 + s of the
 // winner, one byte per output element.
 __global__ void pool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, uint8_t* __restrict__ slot,
-                                int N, int H, int W, int C, int Ho, int Wo) {
+                                int N, int H, int W, int C, int Ho, int Wo, uint16_t* __restrict__ y16) {
   const size_t total = (size_t)N * Ho * Wo * C;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
@@ -773,14 +773,16 @@ __global__ void pool_fwd_kernel(const float* __restrict__ x, float* __restrict__
       }
     }
   y[i] = best;
+  if (y16) store_bf16(y16 + i, best);
   slot[i] = (uint8_t)bs;
 }
 int launch_pool_fwd(const float* x, float* y, uint8_t* slot, int N, int H, int W, int C, int Ho, int Wo,
-                    hipStream_t st) {
+                    hipStream_t st, uint16_t* y16) {
   const size_t total = (size_t)N * Ho * Wo * C;
   if (!total) return ALEXNET_OK;
   KernelScope ks("pool_fwd", 0, (double)N * H * W * C * 4.0 + (double)total * 5.0, st);
-  hipLaunchKernelGGL(pool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, slot, N, H, W, C, Ho, Wo);
+  hipLaunchKernelGGL(pool_fwd_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, x, y, slot, N, H, W, C, Ho, Wo,
+                     y16);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
 }
@@ -1303,10 +1305,10 @@ sgd_update_kernel(float* __restrict__ w, float* __restrict__ v, const float* __r
 }
 constexpr unsigned kUpdateMaxBlocks = 1024;  // 4 per CU
 int launch_sgd_update(float* w, float* v, const float* g, size_t n, size_t n_decay, float lr, float mu, float wd,
-                      hipStream_t st) {
+                      hipStream_t st, unsigned max_blocks) {
   if (!n) return ALEXNET_OK;
   KernelScope ks("sgd_update", 0, (double)n * 20.0, st);
-  const unsigned blocks = std::min<unsigned>(grid_for((n + 3) / 4, 256), kUpdateMaxBlocks);
+  const unsigned blocks = std::min<unsigned>(grid_for((n + 3) / 4, 256), max_blocks ? max_blocks : kUpdateMaxBlocks);
   hipLaunchKernelGGL(sgd_update_kernel, dim3(blocks), dim3(256), 0, st, w, v, g, n, n, (size_t)0, n_decay, lr, mu, wd);
   AX_LAUNCH_CHECK();
   return ALEXNET_OK;
