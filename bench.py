@@ -295,6 +295,8 @@ def main():
                     help="skip the batch-256 fp32 / bf16 steps and the convolutions alone")
     ap.add_argument("--only-step", action="store_true",
                     help="the timed steps and their kernel profile only (what a rocprofv3 run should see)")
+    ap.add_argument("--only-conv-stack", action="store_true",
+                    help="only the convolutions alone (workload 2), for a rocprofv3 run of that workload")
     ap.add_argument("--kernel-table", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run three plain 1 GiB elementwise copies (under rocprofv3 --pmc they calibrate FETCH_SIZE / "
@@ -326,6 +328,10 @@ def main():
             torch.mul(src, 1.0, out=dst)  # an elementwise kernel (copy_ would go through the DMA engines)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.only_conv_stack:
+        print(json.dumps({"conv_stack": conv_stack(torch, B, S)}))
+        return
 
     rec, pipe = measure(torch, B, S, batch, bf16, args.steps, args.warmup, overlap=not args.no_overlap, keep=True)
     net, compute, side, mean = pipe.net, pipe.compute, pipe.side, pipe.mean
