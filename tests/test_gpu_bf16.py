@@ -162,3 +162,51 @@ def test_bf16_and_fp32_replicas_stay_close(lib):
     assert differ > 0, "the bf16 replica must actually compute in bf16"
     a.close()
     b.close()
+
+
+def mini_with_widths_of_eight():
+    """`mini` with 16 classes: every dense width is a multiple of eight, so a bf16 handle keeps bf16 copies of
+    the dense layers' operands too (with 10 classes only its convolutions do)."""
+    wl = dict(S.MINI)
+    wl["name"] = "mini16"
+    wl["fc"] = [256, 256, 16]
+    return wl
+
+
+def test_bf16_three_steps_with_every_operand_stored_as_bf16(lib):
+    errs, own = {}, {}
+    run_step_and_compare(lib, mini_with_widths_of_eight(), 6, seed=14, bias=0.1, std=0.08, use_raw=False, steps=3,
+                         mom_std=0.01, precision=1, direct=True, direct_tol=BF16_OWN_DECISIONS_RTOL, direct_report=own,
+                         loss_rtol=BF16_LOSS_RTOL, tol=BF16_RTOL, report=errs)
+    print(errs, 'decision-free:', own)
+
+
+@pytest.mark.parametrize("wl", [None, S.MIDI], ids=["mini16", "midi"])
+def test_bf16_train_step_equals_its_parts(lib, wl):
+    """alexnet_train_step makes the bf16 copies of the weights on the handle's own stream (events before the
+    first convolution that reads them, before fc6 and before the first data gradient) and forks the dense-layer
+    update; forward_backward + apply_update make them in line.  Same kernels on the same values: three steps
+    either way must leave the same bits."""
+    wl = wl or mini_with_widths_of_eight()
+    batch, classes = 6, wl["fc"][-1]
+    a, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 4, pseed=4, std=0.1, bias=0.1, precision=1)
+    b, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 4, pseed=4, std=0.1, bias=0.1, precision=1)
+    mean = cuda(S.make_mean_image(3, wl["raw"], wl["raw"], S.SEED_BASE + 7))
+    for step in range(3):
+        raw, labels = S.make_raw_batch(batch, 3, wl["raw"], wl["raw"], classes, S.SEED_BASE + 40 + step)
+        raw, labels = cuda(raw), cuda(labels)
+        a.preprocess(raw, mean, step, step % 2)
+        b.preprocess(raw, mean, step, step % 2)
+        la = float(a.train_step(labels, step, slot=step % 2).cpu().item())
+        lb = float(b.forward_backward(labels, step, slot=step % 2).cpu().item())
+        b.apply_update()
+        assert la == lb, (step, la, lb)
+    a.check()
+    b.check()
+    pa, pb, ma, mb = a.get_params(), b.get_params(), a.get_momentum(), b.get_momentum()
+    for k in pa:
+        assert np.array_equal(pa[k], pb[k]), k
+        assert np.array_equal(ma[k], mb[k]), k
+    assert any(np.abs(v).max() > 0 for v in ma.values())
+    a.close()
+    b.close()

@@ -143,16 +143,18 @@ def test_full_alexnet_bf16_step_batch256(lib):
     assert abs(loss - np.log(1000)) < 0.05
 
 
-@pytest.mark.parametrize("batch", [128, 256])
-def test_train_step_equals_its_parts_bit_for_bit_at_full_size(lib, batch):
+@pytest.mark.parametrize("batch,precision", [(128, 0), (256, 0), (256, 1)], ids=["fp32-128", "fp32-256", "bf16-256"])
+def test_train_step_equals_its_parts_bit_for_bit_at_full_size(lib, batch, precision):
     """`alexnet_train_step` runs the dense-layer update, the weight re-packing and the tap transforms of the
     3x3 stages on the handle's own stream under the forward and backward passes; two steps that way must leave
     exactly the parameters and momentum that forward_backward + apply_update leave (same kernels, same order
     per tensor), at the sizes and in the launch configuration bench.py times (batch 256: `--batch 256`).
-    A missing wait between the streams would show here, where the kernels are long, not on the small nets."""
+    A missing wait between the streams would show here, where the kernels are long, not on the small nets.
+    A bf16 handle also makes the bf16 copies of all weights on that stream (three events: convolution taps,
+    dense weights, data-gradient taps) where forward_backward makes them in line."""
     wl = S.ALEXNET
-    a, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3)
-    b, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3)
+    a, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3, precision=precision)
+    b, _, _, _ = build_pair(lib, wl, batch, seed=S.SEED_BASE + 3, pseed=3, precision=precision)
     mean = cuda(S.make_mean_image(3, 256, 256, S.SEED_BASE + 7))
     for step in range(2):
         raw, labels = S.make_raw_batch(batch, 3, 256, 256, 1000, S.SEED_BASE + 30 + step)
