@@ -48,6 +48,18 @@ AX_HD void vstore(float* p, Vec4 v) {
   *reinterpret_cast<float4*>(p) = o;
 }
 
+// two channels of a pixel (the overlap-add of the data gradient works on half quads, see WinoDx)
+struct Vec2 {
+  float x, y;
+};
+AX_HD Vec2 operator+(Vec2 a, Vec2 b) { return {a.x + b.x, a.y + b.y}; }
+AX_HD Vec2 operator-(Vec2 a, Vec2 b) { return {a.x - b.x, a.y - b.y}; }
+AX_HD Vec2 operator*(float s, Vec2 a) { return {s * a.x, s * a.y}; }
+AX_HD Vec2 vload2(const float* p) {
+  const float2 v = *reinterpret_cast<const float2*>(p);
+  return {v.x, v.y};
+}
+
 // ---- the five 1-D maps (strided in / out so that they serve rows and columns of a register tile) ----
 // Bt (6x6): data transform
 template <int SI, int SO>
@@ -61,12 +73,12 @@ AX_HD void wino_bt(const Vec4* d, Vec4* o) {
   o[5 * SO] = 4.f * d1 - 5.f * d3 + d5;
 }
 // B (6x6) = (Bt)^T: adjoint of the data transform
-template <int SI, int SO>
-AX_HD void wino_b(const Vec4* m, Vec4* o) {
-  const Vec4 m0 = m[0], m1 = m[SI], m2 = m[2 * SI], m3 = m[3 * SI], m4 = m[4 * SI], m5 = m[5 * SI];
+template <int SI, int SO, class V>
+AX_HD void wino_b(const V* m, V* o) {
+  const V m0 = m[0], m1 = m[SI], m2 = m[2 * SI], m3 = m[3 * SI], m4 = m[4 * SI], m5 = m[5 * SI];
   o[0] = 4.f * m0;
   o[SO] = 4.f * (m2 - m1 + m5) + 2.f * (m4 - m3);
-  o[2 * SO] = vzero() - 5.f * m0 - 4.f * (m1 + m2) - m3 - m4;
+  o[2 * SO] = (-5.f) * m0 - 4.f * (m1 + m2) - m3 - m4;
   o[3 * SO] = m1 - m2 + 2.f * (m3 - m4) - 5.f * m5;
   o[4 * SO] = m0 + m1 + m2 + m3 + m4;
   o[5 * SO] = m5;
@@ -252,9 +264,11 @@ AX_HD void wino_out_thread(const WinoGeom& g, int Ng, const float* M, const floa
 // transformed taps.  Patches overlap, so a workgroup owns one picture and CQ channel quads, keeps the picture
 // in LDS ([pixel][CQ] float4) and adds the patches in 4*nq phases -- tiles of one parity (ty % 2, tx % 2) and
 // one sub-kernel are 8 pixels apart and never touch the same pixel, so within a phase every LDS word has one
-// writer and the sum has a fixed order.  256 threads: tid % CQ is the quad, tid / CQ the worker.  Work goes in
-// rounds: in a round every worker loads and transforms one patch (all of them at once, so that the memory
-// system sees 256 threads' loads, not one phase's), then the phases add them to the picture.  Eight quads are
+// writer and the sum has a fixed order.  256 threads: a thread owns two channels (half a quad: 36 x float2 of
+// patch, so that four workgroups fit a CU and one's loads run under another's adds -- with whole quads, 227
+// registers, the two halves of a round took turns), tid % (2 CQ) is the channel pair, tid / (2 CQ) the worker.
+// Work goes in rounds: in a round every worker loads and transforms one patch (all of them at once, so that the
+// memory system sees 256 threads' loads, not one phase's), then the phases add them to the picture.  Eight quads are
 // one 128-byte line of M; where a whole picture of eight quads does not fit the LDS budget the picture is cut
 // into `bands` of rows, one workgroup each, and a patch that straddles two bands is transformed by both (each
 // keeps its own rows).  Call order: wino_dx_zero, barrier, per round: wino_dx_load, then wino_dx_add and a
@@ -268,6 +282,8 @@ struct WinoDx {
   AX_HD int phases() const { return 4 * g.nq(); }
   AX_HD int band_rows() const { return (g.H + bands - 1) / bands; }
   AX_HD int lds_vec4() const { return band_rows() * g.W * CQ; }
+  AX_HD int lanes() const { return 2 * CQ; }               // channel pairs, one thread each
+  AX_HD int workers() const { return kThreads / lanes(); }  // patches per round
   AX_HD int blocks() const { return g.B * bands * cblocks(); }
 };
 struct WinoDxBlock {
@@ -356,12 +372,12 @@ AX_HD int wino_dx_rounds(const WinoDx& d) {  // the same for every block: the la
     const int c = wino_dx_tasks(d, bk).count;
     most = c > most ? c : most;
   }
-  const int workers = kThreads / d.CQ;
+  const int workers = d.workers();
   return (most + workers - 1) / workers;
 }
 // phases that round `round` of a block touches: [*lo, *hi] (lo > hi: the round has no task)
 AX_HD void wino_dx_round_phases(const WinoDx& d, const WinoDxPlan& p, int round, int* lo, int* hi) {
-  const int workers = kThreads / d.CQ, first = round * workers;
+  const int workers = d.workers(), first = round * workers;
   int last = first + workers - 1;
   if (last > p.tk.count - 1) last = p.tk.count - 1;
   if (first > last) {
@@ -378,12 +394,12 @@ struct WinoDxTask {
 };
 // Round r of a block: every worker loads and transforms one patch (all threads at once: this is where the
 // memory traffic is), ...
-AX_HD WinoDxTask wino_dx_load(const WinoDx& d, const WinoDxPlan& p, const float* M, int tid, int round, Vec4* z) {
+AX_HD WinoDxTask wino_dx_load(const WinoDx& d, const WinoDxPlan& p, const float* M, int tid, int round, Vec2* z) {
   const WinoGeom& g = d.g;
   const int nq = g.nq(), Ctot = d.Ctot();
   const WinoDxBlock& bk = p.bk;
-  const int cq = tid % d.CQ, worker = tid / d.CQ, workers = kThreads / d.CQ;
-  const int c = 4 * (bk.cblk * d.CQ + cq);
+  const int cp = tid % d.lanes(), worker = tid / d.lanes(), workers = d.workers();
+  const int c = 4 * bk.cblk * d.CQ + 2 * cp;  // Ctot and Cg are multiples of four: the pair lies in one group
   WinoDxTask task;
   task.phase = -1; task.y0 = 0; task.x0 = 0;
   const int j = round * workers + worker;
@@ -402,12 +418,12 @@ AX_HD WinoDxTask wino_dx_load(const WinoDx& d, const WinoDxPlan& p, const float*
   const long pstride = (long)nq * Ctot;
   const long t = ((long)bk.n * g.th + ty) * g.tw + tx;
   const float* in = M + t * 36 * pstride + (long)grp * nq * d.Cg + (long)q * d.Cg + cl;
-  Vec4 u[36];
+  Vec2 u[36];
 #pragma unroll
   for (int jj = 0; jj < 6; ++jj) {
-    Vec4 col[6];
+    Vec2 col[6];
 #pragma unroll
-    for (int i = 0; i < 6; ++i) col[i] = vload(in + (long)(6 * i + jj) * pstride);
+    for (int i = 0; i < 6; ++i) col[i] = vload2(in + (long)(6 * i + jj) * pstride);
     wino_b<1, 6>(col, u + jj);  // u[i][jj]
   }
 #pragma unroll
@@ -415,11 +431,12 @@ AX_HD WinoDxTask wino_dx_load(const WinoDx& d, const WinoDxPlan& p, const float*
   return task;
 }
 // ... then the patches are added to the picture phase by phase (a barrier after each call).
-AX_HD void wino_dx_add(const WinoDx& d, const WinoDxPlan& p, Vec4* lds, int tid, const WinoDxTask& task, const Vec4* z,
+AX_HD void wino_dx_add(const WinoDx& d, const WinoDxPlan& p, Vec4* lds, int tid, const WinoDxTask& task, const Vec2* z,
                        int phase) {
   if (task.phase != phase) return;
   const WinoDxBlock& bk = p.bk;
-  const int cq = tid % d.CQ;
+  const int cp = tid % d.lanes();
+  Vec2* half = reinterpret_cast<Vec2*>(lds);  // [pixel][2 CQ] channel pairs over the same memory
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
     const int iy = task.y0 + i;
@@ -427,7 +444,7 @@ AX_HD void wino_dx_add(const WinoDx& d, const WinoDxPlan& p, Vec4* lds, int tid,
     for (int jj = 0; jj < 6; ++jj) {
       const int ix = task.x0 + jj;
       if (iy >= bk.h0 && iy < bk.h1 && (uint32_t)ix < (uint32_t)d.g.W) {
-        Vec4* acc = lds + ((long)(iy - bk.h0) * d.g.W + ix) * d.CQ + cq;
+        Vec2* acc = half + ((long)(iy - bk.h0) * d.g.W + ix) * d.lanes() + cp;
         *acc = *acc + z[6 * i + jj];
       }
     }

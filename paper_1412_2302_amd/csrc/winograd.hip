@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(256) wino_dx_kernel(WinoDx d, int rounds, cons
   wino_dx_zero(d, lds, tid);
   __syncthreads();
   for (int r = 0; r < rounds; ++r) {
-    Vec4 z[36];
+    Vec2 z[36];
     const WinoDxTask task = wino_dx_load(d, plan, M, tid, r, z);
     int lo, hi;  // the same for every thread of the block
     wino_dx_round_phases(d, plan, r, &lo, &hi);

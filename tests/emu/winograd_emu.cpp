@@ -12,6 +12,9 @@
 struct float4 {
   float x, y, z, w;
 };
+struct float2 {
+  float x, y;
+};
 #define AX_HOST_EMU 1
 namespace ax {
 inline void emu_fail(const char* what) {
@@ -209,10 +212,10 @@ static void run(const Case& k) {
       for (auto& v : lds) v = {NAN, NAN, NAN, NAN};
       for (int tid = 0; tid < kThreads; ++tid) wino_dx_zero(d, lds.data(), tid);
       const WinoDxPlan plan = wino_dx_plan(d, block);
-      std::vector<Vec4> z((size_t)kThreads * 36);
+      std::vector<Vec2> z((size_t)kThreads * 36);
       std::vector<WinoDxTask> task(kThreads);
       for (int r = 0; r < wino_dx_rounds(d); ++r) {
-        for (auto& v : z) v = {NAN, NAN, NAN, NAN};
+        for (auto& v : z) v = {NAN, NAN};
         for (int tid = 0; tid < kThreads; ++tid) task[tid] = wino_dx_load(d, plan, ma.data(), tid, r, &z[tid * 36]);
         int ph_lo, ph_hi;
         wino_dx_round_phases(d, plan, r, &ph_lo, &ph_hi);
@@ -221,7 +224,7 @@ static void run(const Case& k) {
             emu_fail("a task's phase lies outside the phases its round runs");
         for (int ph = ph_lo; ph <= ph_hi; ++ph) {
           // within a phase no two threads may touch the same LDS word (on the GPU they run at once)
-          std::vector<int> writer(d.lds_vec4(), -1);
+          std::vector<int> writer((size_t)d.lds_vec4() * 2, -1);  // one per channel pair
           const WinoDxBlock bk = plan.bk;
           for (int tid = 0; tid < kThreads; ++tid) {
             if (task[tid].phase != ph) continue;
@@ -229,7 +232,7 @@ static void run(const Case& k) {
               for (int jj = 0; jj < 6; ++jj) {
                 const int iy = task[tid].y0 + i, ix = task[tid].x0 + jj;
                 if (iy < bk.h0 || iy >= bk.h1 || ix < 0 || ix >= d.g.W) continue;
-                int& wtr = writer[((size_t)(iy - bk.h0) * d.g.W + ix) * d.CQ + tid % d.CQ];
+                int& wtr = writer[((size_t)(iy - bk.h0) * d.g.W + ix) * d.lanes() + tid % d.lanes()];
                 if (wtr >= 0) emu_fail("two threads add to the same LDS word in one phase");
                 wtr = tid;
               }
