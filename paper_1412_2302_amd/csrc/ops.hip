@@ -1191,7 +1191,7 @@ int launch_reduce_slabs_unpack(const float* ws, int nsplit, long slab, int run, 
 }
 // Few slices of a large result (slab a multiple of four floats, 16-byte aligned): a lane owns four consecutive
 // elements and adds its slices in order, 16 bytes per load.
-constexpr int kReduceVecMaxSlices = 16;
+constexpr int kReduceVecMaxSlices = 32;
 __device__ __forceinline__ void reduce_slabs_vec_block(const float* __restrict__ ws, int nsplit, size_t slab,
                                                        int groups, float* __restrict__ out, unsigned block) {
   const size_t i = ((size_t)block * 256 + threadIdx.x) * 4;
