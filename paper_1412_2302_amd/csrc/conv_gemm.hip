@@ -43,6 +43,8 @@ typedef Tile<128, 64, kBKbf, 4, 1> B64;
 // 256 x 128 (wave tile 128 x 64): three fragment reads for every four MFMAs instead of four for four -- these
 // kernels are paced by LDS, not by the matrix cores; only with operands stored as bf16 (half the staging registers)
 typedef Tile<256, 128, kBKbf, 2, 2> B256;
+// 256 x 96 (wave tile 64 x 96) for the first layer's 96 output channels, which the 128-wide tiles pad by a third
+typedef Tile<256, 96, kBKbf, 4, 1> B256n96;
 static const TileOption kTileOptionsBf[] = {{128, 128, kBKbf, 3.2}, {128, 64, kBKbf, 2.2}, {256, 128, kBKbf, 4.2}};
 
 // precision of the GEMMs launched by the calling thread: 0 fp32 MFMA, 1 bf16 MFMA with fp32 accumulation
@@ -481,6 +483,8 @@ int launch_conv_fwd_run16(const ConvGeom& c, const uint16_t* x4, const uint16_t*
   const GemmPlan p = run16_fwd_plan(c);
   if (p.ns == 1) {
     EpiBiasAct ep{y, c.Cout, bias, relu, c.og(), 0, 0, y16};
+    if (p.bm == 256 && d.N % 96 == 0 && d.N % 128 != 0)  // whole 96-column tiles instead of padded 128-column ones
+      return ConvRun16::go<B256n96, EpiBiasAct>(a, b, ep, d, round_up(d.K, kBKbf), 1, st);
     return by_tile_16<ConvRun16>(p, a, b, ep, d, st);
   }
   EpiSlab ep{ws, (long)d.M * d.N, d.N, nullptr};

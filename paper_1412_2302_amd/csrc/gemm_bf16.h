@@ -350,10 +350,11 @@ struct Im2colKTap16 {
 // k-contiguous dense operand elem(row, k) = p[row*ld + k] stored as bf16 (dense-layer activations and weights)
 template <int ROWS, int BK>
 struct DenseKInner16 {
-  static constexpr int QK = BK / 8, NQ = ROWS * QK, NL = NQ / kThreads, NA = NL, NS = NL;
+  static constexpr int QK = BK / 8, NQ = ROWS * QK, NL = (NQ + kThreads - 1) / kThreads, NA = NL, NS = NL;
+  static constexpr bool kWhole = NQ % kThreads == 0;  // else some threads own no load in the last round (96 rows)
   static constexpr bool kRowMajor = true;
   static constexpr int LDW = BK / 2 + 4, LDS_WORDS = ROWS * LDW;
-  static_assert(NQ % kThreads == 0 && NL >= 1, "tile must be a whole number of loads per thread");
+  static_assert(kThreads % QK == 0 && NL >= 1, "every load of a thread shares its k octet");
   typedef DenseParams Params;
   BufView v;
   int tid, kq;
@@ -366,8 +367,8 @@ struct DenseKInner16 {
     kq = tid % QK;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      const int row = row0 + (tid + i * kThreads) / QK;
-      base[i] = row < a.R ? ((uint32_t)row * (uint32_t)a.ld + 8u * kq) * 2u : kOob;
+      const int idx = tid + i * kThreads, row = row0 + idx / QK;
+      base[i] = (kWhole || idx < NQ) && row < a.R ? ((uint32_t)row * (uint32_t)a.ld + 8u * kq) * 2u : kOob;
     }
   }
   template <int S>
@@ -376,7 +377,8 @@ struct DenseKInner16 {
   }
   AX_HD void fetch(float4* r) const { pl.fetch(v, r); }
   AX_HD void store_step(int s, uint32_t* lds, const float4* r) const {
-    *reinterpret_cast<float4*>(lds + ((tid + s * kThreads) / QK) * LDW + 4 * kq) = r[s];
+    const int idx = tid + s * kThreads;
+    if (kWhole || idx < NQ) *reinterpret_cast<float4*>(lds + (idx / QK) * LDW + 4 * kq) = r[s];
   }
 };
 
